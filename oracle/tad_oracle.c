@@ -1,0 +1,364 @@
+/*
+ * CPU oracle (TEST INFRASTRUCTURE ONLY -- never part of the product path).
+ *
+ * A plain, slow, fp64 evaluation of an element-wise defined tensor and of its
+ * gradients, written straight from the definitions in the paper:
+ *
+ *   forward   Sec. 5.1 (definition of f_alpha through index maps A^p) and
+ *             Sec. 5.2 (a summation inside f: the summation index is appended
+ *             to alpha, giving the sum-extended index [alpha k]).
+ *   backward  the "elementary approach" of Sec. 5.1: visit every function
+ *             index (and, per Sec. 5.2, every summation index) and add
+ *             df_alpha * d fhat / d x^p  into  dx^p at position Ahat^p [alpha k].
+ *             This is the chain rule itself; it uses no index inversion, no
+ *             Smith normal form and no Fourier-Motzkin elimination.
+ *   gamma     the set  Gamma-hat(beta)  of Sec. 5.2 by exhaustive scan of the
+ *             index box (used to check index plans).
+ *
+ * Indices are zero based (Sec. 6).  Tensors are dense row-major doubles.
+ * Nothing here is shared with the GPU library: no headers, no tables.
+ *
+ * Scalar bodies  f = outer( sum_k inner(values) ):
+ *   "sq"       inner = x            outer = s^2
+ *   "cube"     inner = x            outer = s^3
+ *   "sin"      inner = x            outer = sin s
+ *   "exp"      inner = x            outer = exp s
+ *   "mul"      inner = x*y          outer = s
+ *   "worked"   inner = (a+b)^2 c + d^3   outer = exp(-s)      (Sec. 1, Sec. 6)
+ *   "tanh_dot" inner = x*w          outer = tanh s
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_MAX_EXT 8   /* function indices + summation indices */
+#define ORC_MAX_RANK 4
+#define ORC_MAX_ARGS 4
+
+typedef struct {
+    int rank;
+    int64_t shape[ORC_MAX_RANK];
+    int64_t A[ORC_MAX_RANK][ORC_MAX_EXT]; /* index matrix, columns: function then summation indices */
+} orc_arg;
+
+typedef struct {
+    char body[16];
+    int n_f;                       /* number of function indices */
+    int64_t f_shape[ORC_MAX_EXT];
+    int n_sum;                     /* number of summation indices */
+    int64_t sum_lo[ORC_MAX_EXT], sum_hi[ORC_MAX_EXT]; /* inclusive limits */
+    int n_args;
+    orc_arg args[ORC_MAX_ARGS];
+} orc_expr;
+
+enum { B_SQ, B_CUBE, B_SIN, B_EXP, B_MUL, B_WORKED, B_TANH_DOT, B_UNKNOWN };
+
+static int body_id(const char *s) {
+    if (!strcmp(s, "sq")) return B_SQ;
+    if (!strcmp(s, "cube")) return B_CUBE;
+    if (!strcmp(s, "sin")) return B_SIN;
+    if (!strcmp(s, "exp")) return B_EXP;
+    if (!strcmp(s, "mul")) return B_MUL;
+    if (!strcmp(s, "worked")) return B_WORKED;
+    if (!strcmp(s, "tanh_dot")) return B_TANH_DOT;
+    return B_UNKNOWN;
+}
+
+static int body_nargs(int b) {
+    switch (b) {
+    case B_SQ: case B_CUBE: case B_SIN: case B_EXP: return 1;
+    case B_MUL: case B_TANH_DOT: return 2;
+    case B_WORKED: return 4;
+    default: return -1;
+    }
+}
+
+/* summand s(v) of the inner sum */
+static double inner(int b, const double *v) {
+    switch (b) {
+    case B_MUL: case B_TANH_DOT: return v[0] * v[1];
+    case B_WORKED: { double t = v[0] + v[1]; return t * t * v[2] + v[3] * v[3] * v[3]; }
+    default: return v[0];
+    }
+}
+
+/* d s / d v[p] */
+static double dinner(int b, int p, const double *v) {
+    switch (b) {
+    case B_MUL: case B_TANH_DOT: return p == 0 ? v[1] : v[0];
+    case B_WORKED:
+        if (p == 0 || p == 1) return 2.0 * (v[0] + v[1]) * v[2];
+        if (p == 2) { double t = v[0] + v[1]; return t * t; }
+        return 3.0 * v[3] * v[3];
+    default: return 1.0;
+    }
+}
+
+static double outer(int b, double s) {
+    switch (b) {
+    case B_SQ: return s * s;
+    case B_CUBE: return s * s * s;
+    case B_SIN: return sin(s);
+    case B_EXP: return exp(s);
+    case B_MUL: return s;
+    case B_WORKED: return exp(-s);
+    case B_TANH_DOT: return tanh(s);
+    default: return 0.0;
+    }
+}
+
+/* d outer / d s */
+static double douter(int b, double s) {
+    switch (b) {
+    case B_SQ: return 2.0 * s;
+    case B_CUBE: return 3.0 * s * s;
+    case B_SIN: return cos(s);
+    case B_EXP: return exp(s);
+    case B_MUL: return 1.0;
+    case B_WORKED: return -exp(-s);
+    case B_TANH_DOT: { double t = tanh(s); return 1.0 - t * t; }
+    default: return 0.0;
+    }
+}
+
+/* flat row-major position of argument p at extended index ext; -1 if outside its shape */
+static int64_t arg_pos(const orc_arg *a, int n_ext, const int64_t *ext) {
+    int64_t pos = 0;
+    for (int r = 0; r < a->rank; ++r) {
+        int64_t idx = 0;
+        for (int d = 0; d < n_ext; ++d) idx += a->A[r][d] * ext[d];
+        if (idx < 0 || idx >= a->shape[r]) return -1;
+        pos = pos * a->shape[r] + idx;
+    }
+    return pos;
+}
+
+static int check_expr(const orc_expr *e, int *b) {
+    *b = body_id(e->body);
+    if (*b == B_UNKNOWN) return -1;
+    if (e->n_args != body_nargs(*b)) return -2;
+    if (e->n_f < 0 || e->n_sum < 0 || e->n_f + e->n_sum > ORC_MAX_EXT) return -3;
+    for (int p = 0; p < e->n_args; ++p)
+        if (e->args[p].rank < 1 || e->args[p].rank > ORC_MAX_RANK) return -4;
+    return 0;
+}
+
+static int64_t f_count(const orc_expr *e) {
+    int64_t n = 1;
+    for (int d = 0; d < e->n_f; ++d) n *= e->f_shape[d];
+    return n;
+}
+
+static void unflatten_f(const orc_expr *e, int64_t lin, int64_t *ext) {
+    for (int d = e->n_f - 1; d >= 0; --d) { ext[d] = lin % e->f_shape[d]; lin /= e->f_shape[d]; }
+}
+
+/* advance the summation part of ext (odometer, last index fastest); returns 0 when exhausted */
+static int next_sum(const orc_expr *e, int64_t *ext) {
+    for (int s = e->n_sum - 1; s >= 0; --s) {
+        int d = e->n_f + s;
+        if (ext[d] < e->sum_hi[s]) { ext[d]++; return 1; }
+        ext[d] = e->sum_lo[s];
+    }
+    return 0;
+}
+
+static int sums_empty(const orc_expr *e) {
+    for (int s = 0; s < e->n_sum; ++s) if (e->sum_lo[s] > e->sum_hi[s]) return 1;
+    return 0;
+}
+
+/* s_alpha = sum over the summation box of inner(values), ascending index order */
+static int eval_s(const orc_expr *e, int b, const double *const *args, int64_t *ext, double *s_out) {
+    int n_ext = e->n_f + e->n_sum;
+    double s = 0.0, v[ORC_MAX_ARGS];
+    if (!sums_empty(e)) {
+        for (int q = 0; q < e->n_sum; ++q) ext[e->n_f + q] = e->sum_lo[q];
+        do {
+            for (int p = 0; p < e->n_args; ++p) {
+                int64_t pos = arg_pos(&e->args[p], n_ext, ext);
+                if (pos < 0) return -10;
+                v[p] = args[p][pos];
+            }
+            s += inner(b, v);
+        } while (next_sum(e, ext));
+    }
+    *s_out = s;
+    return 0;
+}
+
+/* Forward: f_alpha for every alpha (Sec. 5.1, 5.2). */
+int orc_forward(const orc_expr *e, const double *const *args, double *f) {
+    int b, rc = check_expr(e, &b);
+    if (rc) return rc;
+    int64_t nf = f_count(e);
+    int err = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t lin = 0; lin < nf; ++lin) {
+        int64_t ext[ORC_MAX_EXT];
+        double s;
+        unflatten_f(e, lin, ext);
+        if (eval_s(e, b, args, ext, &s)) { err = -10; continue; }
+        f[lin] = outer(b, s);
+    }
+    return err;
+}
+
+/*
+ * Backward by brute-force scatter (Sec. 5.1 "elementary approach", with the
+ * sum-extended index set of Sec. 5.2):
+ *   for every alpha, every k:   dx^p[ Ahat^p [alpha k] ] += df_alpha * outer'(s_alpha) * d inner / d x^p
+ * dx[p] may be NULL (gradient not wanted).  dx[p] is overwritten.
+ * With nthreads > 1 the function indices are split in contiguous chunks, every
+ * thread scatters into private copies which are then added in thread order.
+ */
+int orc_backward(const orc_expr *e, const double *const *args, const double *df,
+                 double *const *dx, int nthreads) {
+    int b, rc = check_expr(e, &b);
+    if (rc) return rc;
+    int n_ext = e->n_f + e->n_sum;
+    int64_t nf = f_count(e);
+    int64_t asz[ORC_MAX_ARGS];
+    for (int p = 0; p < e->n_args; ++p) {
+        asz[p] = 1;
+        for (int r = 0; r < e->args[p].rank; ++r) asz[p] *= e->args[p].shape[r];
+        if (dx[p]) memset(dx[p], 0, (size_t)asz[p] * sizeof(double));
+    }
+    if (nthreads < 1) nthreads = 1;
+    if ((int64_t)nthreads > nf) nthreads = nf > 0 ? (int)nf : 1;
+    double **priv = (double **)calloc((size_t)nthreads * ORC_MAX_ARGS, sizeof(double *));
+    if (!priv) return -20;
+    int err = 0;
+    for (int t = 0; t < nthreads; ++t)
+        for (int p = 0; p < e->n_args; ++p) {
+            if (!dx[p]) continue;
+            if (t == 0) { priv[p] = dx[p]; continue; }
+            priv[t * ORC_MAX_ARGS + p] = (double *)calloc((size_t)asz[p], sizeof(double));
+            if (!priv[t * ORC_MAX_ARGS + p]) err = -20;
+        }
+    if (!err) {
+#pragma omp parallel for schedule(static, 1) num_threads(nthreads)
+        for (int t = 0; t < nthreads; ++t) {
+            int64_t lo = nf * t / nthreads, hi = nf * (t + 1) / nthreads;
+            double **my = priv + t * ORC_MAX_ARGS;
+            int64_t ext[ORC_MAX_EXT];
+            double v[ORC_MAX_ARGS];
+            int64_t pos[ORC_MAX_ARGS];
+            for (int64_t lin = lo; lin < hi; ++lin) {
+                double s;
+                unflatten_f(e, lin, ext);
+                if (eval_s(e, b, args, ext, &s)) { err = -10; break; }
+                double w = df[lin] * douter(b, s);
+                if (sums_empty(e)) continue;
+                for (int q = 0; q < e->n_sum; ++q) ext[e->n_f + q] = e->sum_lo[q];
+                do {
+                    for (int p = 0; p < e->n_args; ++p) {
+                        pos[p] = arg_pos(&e->args[p], n_ext, ext);
+                        v[p] = args[p][pos[p]];
+                    }
+                    for (int p = 0; p < e->n_args; ++p)
+                        if (my[p]) my[p][pos[p]] += w * dinner(b, p, v);
+                } while (next_sum(e, ext));
+            }
+        }
+        for (int t = 1; t < nthreads; ++t)
+            for (int p = 0; p < e->n_args; ++p) {
+                double *src = priv[t * ORC_MAX_ARGS + p];
+                if (!src) continue;
+                for (int64_t i = 0; i < asz[p]; ++i) dx[p][i] += src[i];
+            }
+    }
+    for (int t = 1; t < nthreads; ++t)
+        for (int p = 0; p < e->n_args; ++p) free(priv[t * ORC_MAX_ARGS + p]);
+    free(priv);
+    return err;
+}
+
+/* lexicographic scan of the whole extended index box; calls back with every point */
+static int box_first(const orc_expr *e, int64_t *ext) {
+    for (int d = 0; d < e->n_f; ++d) { if (e->f_shape[d] <= 0) return 0; ext[d] = 0; }
+    for (int s = 0; s < e->n_sum; ++s) {
+        if (e->sum_lo[s] > e->sum_hi[s]) return 0;
+        ext[e->n_f + s] = e->sum_lo[s];
+    }
+    return 1;
+}
+
+static int box_next(const orc_expr *e, int64_t *ext) {
+    for (int d = e->n_f + e->n_sum - 1; d >= 0; --d) {
+        int64_t lo = d < e->n_f ? 0 : e->sum_lo[d - e->n_f];
+        int64_t hi = d < e->n_f ? e->f_shape[d] - 1 : e->sum_hi[d - e->n_f];
+        if (ext[d] < hi) { ext[d]++; return 1; }
+        ext[d] = lo;
+    }
+    return 0;
+}
+
+/*
+ * Gamma-hat(beta) of Sec. 5.2 for argument `arg`: every extended index in the
+ * box whose image under Ahat equals beta, in lexicographic order.  Writes up to
+ * `cap` points (n_ext values each) into out and the total count into *n.
+ */
+int orc_gamma(const orc_expr *e, int arg, const int64_t *beta, int64_t *out, int64_t cap, int64_t *n) {
+    int b, rc = check_expr(e, &b);
+    if (rc) return rc;
+    if (arg < 0 || arg >= e->n_args) return -5;
+    const orc_arg *a = &e->args[arg];
+    int n_ext = e->n_f + e->n_sum;
+    int64_t ext[ORC_MAX_EXT], cnt = 0;
+    if (box_first(e, ext)) {
+        do {
+            int hit = 1;
+            for (int r = 0; r < a->rank && hit; ++r) {
+                int64_t idx = 0;
+                for (int d = 0; d < n_ext; ++d) idx += a->A[r][d] * ext[d];
+                hit = idx == beta[r];
+            }
+            if (hit) {
+                if (cnt < cap) memcpy(out + cnt * n_ext, ext, (size_t)n_ext * sizeof(int64_t));
+                cnt++;
+            }
+        } while (box_next(e, ext));
+    }
+    *n = cnt;
+    return 0;
+}
+
+/*
+ * |Gamma-hat(beta)| for every beta of argument `arg` in one scan of the box:
+ * counts[flat(beta)] = number of extended indices mapped onto beta.
+ * counts has one int64 per element of the argument and is overwritten.
+ */
+int orc_gamma_counts(const orc_expr *e, int arg, int64_t *counts) {
+    int b, rc = check_expr(e, &b);
+    if (rc) return rc;
+    if (arg < 0 || arg >= e->n_args) return -5;
+    const orc_arg *a = &e->args[arg];
+    int n_ext = e->n_f + e->n_sum;
+    int64_t sz = 1;
+    for (int r = 0; r < a->rank; ++r) sz *= a->shape[r];
+    memset(counts, 0, (size_t)sz * sizeof(int64_t));
+    int64_t ext[ORC_MAX_EXT];
+    if (box_first(e, ext)) {
+        do {
+            int64_t pos = arg_pos(a, n_ext, ext);
+            if (pos < 0) return -10;
+            counts[pos]++;
+        } while (box_next(e, ext));
+    }
+    return 0;
+}
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+int orc_sizeof_expr(void) { return (int)sizeof(orc_expr); }

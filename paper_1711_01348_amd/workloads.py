@@ -1,0 +1,211 @@
+"""Seeded synthetic workloads: expression descriptions and input tensors.
+
+This module only *describes* element-wise defined tensors (shapes, summation
+limits, integer index matrices, the name of the scalar body) and draws random
+input values.  It contains none of the method's arithmetic and imports neither
+the HIP binding nor the CPU oracle; both are driven from the data built here.
+
+An expression follows the problem statement of Sec. 5.1 / 5.2 of the paper:
+    f_alpha = fbar( sum_{k in Psi} s( y^p_{Ahat^p [alpha k]} ... ) )
+with every argument index an integer linear map of the function indices alpha
+followed by the summation indices k (the "sum-extended" multi-index).
+Indices are zero-based (Sec. 6) and tensors are dense, row-major.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+
+SEED_BASE = 171101348
+
+
+@dataclass
+class ArgSpec:
+    name: str
+    shape: Tuple[int, ...]
+    # index matrix, one row per argument axis, one column per function index
+    # followed by one column per summation index
+    A: List[List[int]]
+
+
+@dataclass
+class ExprSpec:
+    body: str                       # name of the scalar body
+    f_shape: Tuple[int, ...]
+    sums: List[Tuple[int, int]]     # inclusive (lo, hi) per summation index
+    args: List[ArgSpec]
+    dtype: str = "f64"              # "f64" or "f32"
+
+    @property
+    def n_ext(self) -> int:
+        return len(self.f_shape) + len(self.sums)
+
+
+@dataclass
+class Workload:
+    name: str
+    expr: ExprSpec
+    inputs: Dict[str, np.ndarray]   # argument tensors, in expr.args order
+    df: np.ndarray
+    notes: str = ""
+    arg_order: List[str] = field(default_factory=list)
+
+    def arg_list(self) -> List[np.ndarray]:
+        return [self.inputs[a.name] for a in self.expr.args]
+
+
+def _np_dtype(dtype: str):
+    return {"f64": np.float64, "f32": np.float32}[dtype]
+
+
+def _round(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Values are drawn in fp64 and rounded once to the working precision."""
+    return np.ascontiguousarray(x.astype(_np_dtype(dtype)))
+
+
+def _uniform(rng, lo, hi, shape):
+    return rng.uniform(lo, hi, size=shape)
+
+
+# --------------------------------------------------------------------------
+# expression builders
+# --------------------------------------------------------------------------
+
+def worked_expr(I: int, J: int, K: int, dtype: str, d_len: int | None = None,
+                c_shape: Tuple[int, int] | None = None) -> ExprSpec:
+    """f_ij = exp(-sum_k((a_ik + b_jk)^2 c_ii + d_{i+k}^3)), extended index (i, j, k)."""
+    d_len = I + K - 1 if d_len is None else d_len
+    c_shape = (I, I) if c_shape is None else c_shape
+    return ExprSpec(
+        body="worked", f_shape=(I, J), sums=[(0, K - 1)], dtype=dtype,
+        args=[
+            ArgSpec("a", (I, K), [[1, 0, 0], [0, 0, 1]]),
+            ArgSpec("b", (J, K), [[0, 1, 0], [0, 0, 1]]),
+            ArgSpec("c", c_shape, [[1, 0, 0], [1, 0, 0]]),
+            ArgSpec("d", (d_len,), [[1, 0, 1]]),
+        ])
+
+
+def broadcast_sq_expr(I: int, J: int, dtype: str) -> ExprSpec:
+    """f_ij = x_i^2."""
+    return ExprSpec("sq", (I, J), [], [ArgSpec("x", (I,), [[1, 0]])], dtype)
+
+
+def diagonal_sq_expr(I: int, dtype: str) -> ExprSpec:
+    """f_i = x_ii^2."""
+    return ExprSpec("sq", (I,), [], [ArgSpec("x", (I, I), [[1], [1]])], dtype)
+
+
+def index_sum_exp_expr(I: int, J: int, dtype: str) -> ExprSpec:
+    """f_ij = exp(x_{i+j})."""
+    return ExprSpec("exp", (I, J), [], [ArgSpec("x", (I + J - 1,), [[1, 1]])], dtype)
+
+
+def strided_tanh_expr(N: int, I: int, J: int, U: int, V: int, stride: int,
+                      dtype: str) -> ExprSpec:
+    """f_nij = tanh(sum_{u<U, v<V} x_{n, stride*i+u, stride*j+v} w_uv); extended index (n,i,j,u,v)."""
+    P = stride * (I - 1) + U
+    Q = stride * (J - 1) + V
+    return ExprSpec(
+        "tanh_dot", (N, I, J), [(0, U - 1), (0, V - 1)],
+        [ArgSpec("x", (N, P, Q), [[1, 0, 0, 0, 0],
+                                  [0, stride, 0, 1, 0],
+                                  [0, 0, stride, 0, 1]]),
+         ArgSpec("w", (U, V), [[0, 0, 0, 1, 0],
+                               [0, 0, 0, 0, 1]])],
+        dtype)
+
+
+# --------------------------------------------------------------------------
+# the five benchmark configurations
+# --------------------------------------------------------------------------
+
+def _worked_workload(name, seed, I, J, K, dtype, c_hi, d_half, d_len=None) -> Workload:
+    rng = np.random.Generator(np.random.PCG64(seed))
+    expr = worked_expr(I, J, K, dtype, d_len=d_len)
+    a = _uniform(rng, -1, 1, (I, K))
+    b = _uniform(rng, -1, 1, (J, K))
+    c = _uniform(rng, 0, c_hi, (I, I))
+    d = _uniform(rng, -d_half, d_half, expr.args[3].shape)
+    df = _uniform(rng, -1, 1, (I, J))
+    inputs = {"a": _round(a, dtype), "b": _round(b, dtype),
+              "c": _round(c, dtype), "d": _round(d, dtype)}
+    return Workload(name, expr, inputs, _round(df, dtype))
+
+
+def config1() -> Workload:
+    """Worked expression of the paper (Sec. 1 / Sec. 6) at I=8, J=6, K=5, fp64."""
+    return _worked_workload("cfg1_worked_8x6x5_f64", SEED_BASE + 1, 8, 6, 5, "f64", 1.0, 0.5)
+
+
+def config2(which: int, scale: str = "full") -> Workload:
+    """The three index patterns of the introduction, fp32."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 2 * 10 + which))
+    dtype = "f32"
+    if which == 1:
+        I, J = (4096, 4096) if scale == "full" else (203, 517)
+        expr = broadcast_sq_expr(I, J, dtype)
+        x = _uniform(rng, -1, 1, (I,))
+        df = _uniform(rng, -1, 1, (I, J))
+        name = f"cfg2_1_broadcast_sq_{I}x{J}"
+    elif which == 2:
+        I = 8192 if scale == "full" else 389
+        expr = diagonal_sq_expr(I, dtype)
+        x = _uniform(rng, -1, 1, (I, I))
+        df = _uniform(rng, -1, 1, (I,))
+        name = f"cfg2_2_diagonal_sq_{I}"
+    elif which == 3:
+        I, J = (4096, 4096) if scale == "full" else (301, 467)
+        expr = index_sum_exp_expr(I, J, dtype)
+        x = _uniform(rng, -1, 1, (I + J - 1,))
+        df = _uniform(rng, -1, 1, (I, J))
+        name = f"cfg2_3_index_sum_exp_{I}x{J}"
+    else:
+        raise ValueError(which)
+    return Workload(name, expr, {"x": _round(x, dtype)}, _round(df, dtype))
+
+
+def config3(scale: str = "full") -> Workload:
+    """Worked expression at scale, fp32, K=5 (memory bound)."""
+    I, J = (8192, 8192) if scale == "full" else (333, 1301)
+    return _worked_workload(f"cfg3_worked_{I}x{J}x5_f32", SEED_BASE + 3, I, J, 5, "f32", 0.2, 0.5)
+
+
+def config4(scale: str = "full") -> Workload:
+    """Worked expression with a long summed index, fp32, K=256 (compute heavy)."""
+    I, J, K = (4096, 4096, 256) if scale == "full" else (200, 328, 256)
+    return _worked_workload(f"cfg4_worked_{I}x{J}x{K}_f32", SEED_BASE + 4, I, J, K, "f32",
+                            1.0 / 256, 0.2)
+
+
+def config5(scale: str = "full") -> Workload:
+    """Strided (stride 2) 3x3 map, fp32."""
+    N, I, J = (32, 128, 128) if scale == "full" else (3, 21, 37)
+    dtype = "f32"
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 5))
+    expr = strided_tanh_expr(N, I, J, 3, 3, 2, dtype)
+    x = _uniform(rng, -1, 1, expr.args[0].shape)
+    w = _uniform(rng, -0.5, 0.5, (3, 3))
+    df = _uniform(rng, -1, 1, (N, I, J))
+    return Workload(f"cfg5_strided_tanh_{N}x{I}x{J}", expr,
+                    {"x": _round(x, dtype), "w": _round(w, dtype)}, _round(df, dtype))
+
+
+def all_configs(scale: str = "small") -> List[Workload]:
+    out = [config1()]
+    out += [config2(w, scale) for w in (1, 2, 3)]
+    out += [config3(scale), config4(scale), config5(scale)]
+    return out
+
+
+# --------------------------------------------------------------------------
+# generic random inputs for an arbitrary expression (used by property tests)
+# --------------------------------------------------------------------------
+
+def random_inputs(expr: ExprSpec, seed: int, lo: float = -1.0, hi: float = 1.0) -> Workload:
+    rng = np.random.Generator(np.random.PCG64(seed))
+    inputs = {a.name: _round(_uniform(rng, lo, hi, a.shape), expr.dtype) for a in expr.args}
+    df = _round(_uniform(rng, -1, 1, expr.f_shape), expr.dtype)
+    return Workload(f"random_{expr.body}_{seed}", expr, inputs, df)
