@@ -1,0 +1,213 @@
+/*
+ * tad.h -- C ABI of the tensor-algebra autodiff hot path (single GPU, gfx950).
+ *
+ * The library evaluates a tensor that is defined element-wise,
+ *
+ *     f_alpha = fbar( sum_{k in Psi} s( x^1_{A^1 [alpha k]}, ..., x^P_{A^P [alpha k]} ) ),
+ *
+ * (Sec. 5.1, and Sec. 5.2 for summations inside f), and the gradients
+ * dx^p_beta = dl/dx^p_beta of a scalar loss l(f) for every argument, in the
+ * gather form of Sec. 5.1 (final formula of that section):
+ *
+ *     dx^p_beta = delta(C beta) * sum_{z in Sigma(beta)} df_alpha * d fhat / d x^p  at  [alpha k] = I beta + K z,
+ *
+ * with I, K, C the pseudo-inverse, kernel and cokernel of the integer index
+ * matrix A^p (Sec. 4.1, Smith normal form) and the nested ranges Sigma(beta)
+ * obtained by Fourier-Motzkin elimination (Sec. 4.2).  One owner per gradient
+ * element: no scatter, no atomics, bit-identical results from run to run.
+ *
+ * Conventions (all entry points):
+ *   - indices are zero based (Sec. 6); summation limits are inclusive;
+ *   - every tensor is dense, row-major (last index fastest), of the plan's dtype;
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *     device memory of the current device, owned by the caller;
+ *   - every function returns 0 on success or a negative tad_status; nothing
+ *     throws, aborts or prints.
+ */
+#ifndef TAD_H
+#define TAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TAD_MAX_EXT 6    /* function indices + summation indices */
+#define TAD_MAX_RANK 4   /* rank of an argument tensor */
+#define TAD_MAX_ARGS 4
+#define TAD_MAX_KERNEL 4 /* dimension of the kernel of an index matrix */
+
+typedef enum {
+    TAD_OK = 0,
+    TAD_EINVAL = -1,       /* NULL pointer, rank/size out of the supported limits, zero index matrix */
+    TAD_ESHAPE = -2,       /* an index leaves its argument's shape; summation lo > hi; empty tensor */
+    TAD_EINFEASIBLE = -3,  /* constraint system without any solution (Sec. 4.2, feasibility rows) */
+    TAD_EOVERFLOW = -4,    /* integer overflow in Smith / Fourier-Motzkin, or index range beyond int32 */
+    TAD_EUNSUPPORTED = -5, /* body / pattern without a kernel, several occurrences of one argument */
+    TAD_EDEVICE = -6,      /* kernel launch failed */
+    TAD_ENOMEM = -7,       /* host allocation failed, or workspace too small */
+    TAD_ENOGPU = -8        /* library built without / cannot reach a HIP device */
+} tad_status;
+
+typedef enum { TAD_F32 = 0, TAD_F64 = 1 } tad_dtype;
+
+/*
+ * Built-in scalar bodies  f = outer( sum_k inner(values) ).
+ * Bodies SQ, CUBE and SIN take no summation index.
+ */
+typedef enum {
+    TAD_BODY_SQ = 0,       /* x^2                                   (Sec. 1)            1 argument  */
+    TAD_BODY_CUBE = 1,     /* x^3                                   (Sec. 5, f^3)       1 argument  */
+    TAD_BODY_SIN = 2,      /* sin x                                 (Sec. 5, f^1)       1 argument  */
+    TAD_BODY_EXP = 3,      /* exp(sum x)                            (Sec. 1, Sec. 5 f^5) 1 argument */
+    TAD_BODY_MUL = 4,      /* sum x*y                               (Sec. 5, f^2, f^4)  2 arguments */
+    TAD_BODY_WORKED = 5,   /* exp(-sum((a+b)^2 c + d^3))            (Sec. 1, Sec. 6)    4 arguments a,b,c,d */
+    TAD_BODY_TANH_DOT = 6  /* tanh(sum x*w)                                             2 arguments x,w */
+} tad_body;
+
+/* Element-wise definition of f (Sec. 5.1): shape of f and the summation ranges Psi (Sec. 5.2). */
+typedef struct {
+    int32_t body;                  /* tad_body */
+    int32_t n_f;                   /* number of function indices D_f (>= 1) */
+    int64_t f_shape[TAD_MAX_EXT];  /* N^f */
+    int32_t n_sum;                 /* number of summation indices; n_f + n_sum <= TAD_MAX_EXT */
+    int64_t sum_lo[TAD_MAX_EXT];   /* inclusive constant limits of every summation index */
+    int64_t sum_hi[TAD_MAX_EXT];
+} tad_expr;
+
+/* One tensor argument x^p and its index map (Sec. 5.1; Sec. 5.2 for the extended map). */
+typedef struct {
+    int32_t rank;                               /* D_p, 1..TAD_MAX_RANK */
+    int64_t shape[TAD_MAX_RANK];                /* N^p */
+    int32_t n_occ;                              /* occurrences of the argument; only 1 is supported */
+    int64_t index[TAD_MAX_RANK][TAD_MAX_EXT];   /* A^p, D_p x (n_f + n_sum): argument index = A^p [alpha k] */
+    int32_t needs_grad;                         /* derive a gather plan for this argument */
+} tad_arg;
+
+/* plan flags */
+#define TAD_PLAN_GENERIC_ONLY 1u /* never select a specialised kernel family; use the plan-driven generic kernels */
+
+typedef struct tad_plan tad_plan; /* opaque, immutable after derivation, may be shared between threads */
+
+/* What the derivation found for one argument (Sec. 4.1 quantities, host memory, row-major). */
+typedef struct {
+    int32_t rank;                                   /* R = rank of A^p */
+    int32_t kernel_dim;                             /* kappa = (n_f + n_sum) - R */
+    int32_t n_cokernel;                             /* D_p - R rows of C */
+    int64_t smith[TAD_MAX_RANK];                    /* alpha_1..alpha_R, positive, alpha_i | alpha_{i+1} */
+    int64_t U[TAD_MAX_RANK][TAD_MAX_RANK];          /* S = U A V, U is D_p x D_p */
+    int64_t V[TAD_MAX_EXT][TAD_MAX_EXT];            /* V is (n_f+n_sum) x (n_f+n_sum) */
+    int64_t K[TAD_MAX_EXT][TAD_MAX_KERNEL];         /* kernel basis, columns R.. of V */
+    int64_t C[TAD_MAX_RANK][TAD_MAX_RANK];          /* cokernel rows, rows R.. of U */
+    int32_t n_lower[TAD_MAX_KERNEL];                /* Fourier-Motzkin rows per kernel coordinate z_k */
+    int32_t n_upper[TAD_MAX_KERNEL];
+    int32_t n_feasibility;
+    int32_t family;                                 /* kernel family chosen for this gradient (tad_family) */
+} tad_plan_info;
+
+typedef enum {
+    TAD_FAMILY_GENERIC = 0,      /* one thread per gradient element, nested z loops (Sec. 5.1) */
+    TAD_FAMILY_ROW_REDUCE = 1,   /* broadcast index: the whole last function dimension collapses */
+    TAD_FAMILY_DIAGONAL = 2,     /* cokernel mask only, no summation */
+    TAD_FAMILY_ANTIDIAGONAL = 3, /* one clipped window over x_{i+j} */
+    TAD_FAMILY_WORKED = 4,       /* fused kernels for the worked expression */
+    TAD_FAMILY_WORKED_MFMA = 5,  /* worked expression, long summed index: expanded cross term on MFMA */
+    TAD_FAMILY_STRIDED = 6       /* strided stencil */
+} tad_family;
+
+/* which set of Fourier-Motzkin rows tad_plan_bound_row reads */
+typedef enum { TAD_ROWS_LOWER = 0, TAD_ROWS_UPPER = 1, TAD_ROWS_FEASIBILITY = 2 } tad_row_kind;
+
+/*
+ * Derive the index plan of an expression (Sec. 5.3, the element-wise derivation
+ * algorithm; index half only: the scalar partial derivatives of the built-in
+ * bodies are fixed in the kernels).  Host only: touches no GPU.
+ *   expr, args[n_args]  host, read; n_args must equal the body's argument count
+ *   dt                  element type of every tensor
+ *   flags               TAD_PLAN_* bits
+ *   out                 receives a heap-allocated plan owned by the caller (tad_plan_free)
+ * Errors: EINVAL, ESHAPE (some in-range [alpha k] maps outside an argument),
+ * EOVERFLOW, EUNSUPPORTED, ENOMEM.
+ */
+int tad_plan_derive(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt,
+                    uint32_t flags, tad_plan **out);
+
+void tad_plan_free(tad_plan *plan);
+
+/* Bytes of device workspace tad_eval_forward / tad_eval_backward need (two-pass reductions). */
+size_t tad_plan_workspace_bytes(const tad_plan *plan);
+
+/* Smith normal form parts and row counts for argument `arg` (host, written to *out). */
+int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out);
+
+/*
+ * One Fourier-Motzkin row (Sec. 4.2) for kernel coordinate `level` (0 = innermost z_1):
+ *   lower:        scale * z_level >= coef_b . b(beta) + coef_z . z      (coef_z[m] = 0 for m <= level)
+ *   upper:        scale * z_level <= coef_b . b(beta) + coef_z . z
+ *   feasibility:  coef_b . b(beta) <= 0                                  (level ignored)
+ * with b(beta) = [lo - I beta ; I beta - hi] (2 (n_f+n_sum) entries, Sec. 5.1 with zero-based box lo..hi).
+ * coef_b has 2*TAD_MAX_EXT entries (entry j and TAD_MAX_EXT + j for index j), coef_z TAD_MAX_KERNEL. Host memory.
+ */
+int tad_plan_bound_row(const tad_plan *plan, int arg, int kind, int level, int row,
+                       int64_t *scale, int64_t *coef_b, int64_t *coef_z);
+
+/*
+ * The extended indices the plan visits for gradient element beta (host): writes up to `cap`
+ * points ((n_f+n_sum) int64 each) in lexicographic order to alpha_out and the total count to *n.
+ * Uses exactly the masks, bound rows and index maps the kernels use.
+ */
+int tad_plan_enumerate(const tad_plan *plan, int arg, int occ, const int64_t *beta,
+                       int64_t *alpha_out, size_t cap, size_t *n);
+
+/* Number of visited extended indices for every beta of argument `arg` (host; counts has one int64 per element). */
+int tad_plan_count_all(const tad_plan *plan, int arg, int64_t *counts);
+
+/*
+ * Forward evaluation of f (Sec. 5.1 / 5.2).  Enqueues kernels on `stream` (a hipStream_t, NULL = default
+ * stream), never synchronises, never allocates.
+ *   args_dev[n_args]  device, read
+ *   f_dev             device, overwritten (all of f)
+ *   ws_dev, ws_bytes  device scratch of at least tad_plan_workspace_bytes (may be NULL if that is 0)
+ */
+int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_dev,
+                     void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
+ * Gather-form gradients (final formula of Sec. 5.1).
+ *   f_dev     device, read: the forward result for the same args_dev
+ *   df_dev    device, read: dl/df, shape of f
+ *   dx_dev[p] device, overwritten with the full gradient in argument p's shape (zeros where the
+ *             cokernel / divisibility / range conditions fail); NULL skips that gradient
+ * Same stream / workspace rules as tad_eval_forward.  Deterministic.
+ */
+int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const void *f_dev,
+                      const void *df_dev, void *const *dx_dev, void *ws_dev, size_t ws_bytes,
+                      void *stream);
+
+/* Name of the device kernel family used for the forward pass (tad_family). */
+int tad_plan_forward_family(const tad_plan *plan);
+
+/*
+ * Host utilities of the integer machinery (Sec. 4), independent of any expression.
+ *
+ * tad_extended_gcd:       g = gcd(a, b) = a x + b y, g >= 0            (extended Euclidean algorithm)
+ * tad_smith_normal_form:  S = U A V for the non-zero n x m matrix A (row-major, n, m <= 16); S is n x m,
+ *                         U n x n, V m x m, all row-major host arrays owned by the caller; *rank = R.
+ * tad_lattice_enumerate:  all integer x with A x = beta and lo <= x <= hi (inclusive), found through
+ *                         Smith normal form and Fourier-Motzkin ranges (never by scanning the box), in
+ *                         lexicographic order; n <= TAD_MAX_RANK, m <= TAD_MAX_EXT, kernel dimension
+ *                         <= TAD_MAX_KERNEL.  Writes up to cap points (m int64 each), total to *count.
+ */
+int tad_extended_gcd(int64_t a, int64_t b, int64_t *g, int64_t *x, int64_t *y);
+int tad_smith_normal_form(const int64_t *A, int n, int m, int64_t *S, int64_t *U, int64_t *V, int *rank);
+int tad_lattice_enumerate(const int64_t *A, int n, int m, const int64_t *lo, const int64_t *hi,
+                          const int64_t *beta, int64_t *x_out, size_t cap, size_t *count);
+
+const char *tad_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAD_H */

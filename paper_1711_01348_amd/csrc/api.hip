@@ -1,0 +1,36 @@
+// Device entry points of the C ABI: dispatch on the kernel family chosen at plan time.
+#include <hip/hip_runtime.h>
+
+#include "launch.h"
+
+using namespace tad;
+
+extern "C" {
+
+int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_dev, void *ws_dev,
+                     size_t ws_bytes, void *stream) {
+    if (!plan || !args_dev || !f_dev) return TAD_EINVAL;
+    for (size_t p = 0; p < plan->args.size(); ++p)
+        if (!args_dev[p]) return TAD_EINVAL;
+    if (plan->ws_bytes && (!ws_dev || ws_bytes < plan->ws_bytes)) return TAD_ENOMEM;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (plan->fwd_family) {
+    case TAD_FAMILY_GENERIC: return generic_forward(*plan, args_dev, f_dev, s);
+    default: return TAD_EUNSUPPORTED;
+    }
+}
+
+int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const void *f_dev,
+                      const void *df_dev, void *const *dx_dev, void *ws_dev, size_t ws_bytes, void *stream) {
+    if (!plan || !args_dev || !f_dev || !df_dev || !dx_dev) return TAD_EINVAL;
+    for (size_t p = 0; p < plan->args.size(); ++p) {
+        if (!args_dev[p]) return TAD_EINVAL;
+        if (dx_dev[p] && !plan->ap[p].derived) return TAD_EINVAL;  // gradient was not planned
+    }
+    if (plan->ws_bytes && (!ws_dev || ws_bytes < plan->ws_bytes)) return TAD_ENOMEM;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = generic_backward(*plan, args_dev, f_dev, df_dev, dx_dev, s);
+    return rc;
+}
+
+}  // extern "C"

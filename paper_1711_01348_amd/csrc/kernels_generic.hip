@@ -1,0 +1,158 @@
+// Plan-driven generic kernels: the method exactly as stated.
+//   forward: one thread per function index alpha, loop over the summation box (Sec. 5.1, 5.2)
+//   gather:  one thread per gradient element beta: cokernel / divisibility / feasibility masks,
+//            nested z loops with Fourier-Motzkin ranges, single store (final formula of Sec. 5.1)
+// Works for every supported body and index matrix; the specialised families exist for speed only.
+#include <hip/hip_runtime.h>
+
+#include "bodies.h"
+#include "launch.h"
+#include "plan_dev.h"
+
+namespace tad {
+
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, const ArgPtrs A,
+                                                         T *__restrict__ f, int nf) {
+    constexpr int NA = BodyTraits<BODY>::NA;
+    int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= nf) return;
+    int32_t ext[kMaxExt];
+    {
+        int t = lin;
+        for (int d = P.n_f - 1; d >= 0; --d) { ext[d] = t % P.f_shape[d]; t /= P.f_shape[d]; }
+    }
+    int64_t base[NA];
+    for (int p = 0; p < NA; ++p) {
+        int64_t o = 0;
+        for (int d = 0; d < P.n_f; ++d) o += P.off[p][d] * (int64_t)ext[d];
+        for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)P.sum_lo[s];
+        base[p] = o;
+    }
+    int32_t k[kMaxExt] = {0};
+    double acc = 0.0;
+    for (;;) {
+        T v[NA];
+        for (int p = 0; p < NA; ++p) {
+            int64_t o = base[p];
+            for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)k[s];
+            v[p] = static_cast<const T *>(A.p[p])[o];
+        }
+        acc += (double)body_inner<BODY, T>(v);
+        int s = P.n_sum - 1;
+        for (; s >= 0; --s) {
+            if (++k[s] < P.sum_n[s]) break;
+            k[s] = 0;
+        }
+        if (s < 0) break;
+    }
+    f[lin] = body_outer<BODY, T>((T)acc);
+}
+
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int p, const ArgPtrs A,
+                                                        const T *__restrict__ f, const T *__restrict__ df,
+                                                        T *__restrict__ dx, int n) {
+    constexpr int NA = BodyTraits<BODY>::NA;
+    int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= n) return;
+    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
+    {
+        int t = lin;
+        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+    }
+    if (!gather_prepare(P, beta, y)) { dx[lin] = T(0); return; }
+
+    double acc = 0.0;
+    auto term = [&](const int64_t *off) {
+        T v[NA];
+        for (int q = 0; q < NA; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
+        T fv = f[off[NA]], dfv = df[off[NA]];
+        acc += (double)(dfv * body_douter<BODY, T>(fv, v) * body_dinner<BODY, T>(p, v));
+    };
+    int32_t z[kMaxKernel] = {0, 0, 0, 0}, hi[kMaxKernel] = {0, 0, 0, 0};
+    int64_t off[NA + 1];
+    if (P.kappa == 0) {
+        for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
+        off[NA] = gather_offset(P, kSlotF, y, z);
+        term(off);
+        dx[lin] = (T)acc;
+        return;
+    }
+    int lvl = P.kappa - 1;
+    gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
+    for (;;) {
+        if (z[lvl] > hi[lvl]) {
+            if (++lvl == P.kappa) break;
+            ++z[lvl];
+            continue;
+        }
+        if (lvl == 0) {
+            // innermost loop: offsets advance by a constant per step
+            for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
+            off[NA] = gather_offset(P, kSlotF, y, z);
+            for (int32_t z0 = z[0]; z0 <= hi[0]; ++z0) {
+                term(off);
+                for (int q = 0; q < NA; ++q) off[q] += P.offZ[q][0];
+                off[NA] += P.offZ[kSlotF][0];
+            }
+            z[0] = hi[0] + 1;
+        } else {
+            --lvl;
+            gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
+        }
+    }
+    dx[lin] = (T)acc;
+}
+
+template <int BODY, typename T>
+static int launch_body(const tad_plan &pl, const void *const *args, const void *f, const void *df,
+                       void *const *dx, void *fout, hipStream_t s) {
+    ArgPtrs A{};
+    for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[q];
+    if (fout) {
+        int nf = (int)pl.f_count;
+        hipLaunchKernelGGL((k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd, A,
+                           static_cast<T *>(fout), nf);
+        return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+    }
+    for (size_t p = 0; p < pl.args.size(); ++p) {
+        if (!dx[p] || pl.ap[p].family != TAD_FAMILY_GENERIC) continue;
+        if (!pl.ap[p].derived) return TAD_EINVAL;
+        int n = (int)pl.arg_count[p];
+        hipLaunchKernelGGL((k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[p].dev,
+                           (int)p, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                           static_cast<T *>(dx[p]), n);
+        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    }
+    return TAD_OK;
+}
+
+template <typename T>
+static int launch_dtype(const tad_plan &pl, const void *const *args, const void *f, const void *df,
+                        void *const *dx, void *fout, hipStream_t s) {
+    switch (pl.expr.body) {
+    case TAD_BODY_SQ: return launch_body<TAD_BODY_SQ, T>(pl, args, f, df, dx, fout, s);
+    case TAD_BODY_CUBE: return launch_body<TAD_BODY_CUBE, T>(pl, args, f, df, dx, fout, s);
+    case TAD_BODY_SIN: return launch_body<TAD_BODY_SIN, T>(pl, args, f, df, dx, fout, s);
+    case TAD_BODY_EXP: return launch_body<TAD_BODY_EXP, T>(pl, args, f, df, dx, fout, s);
+    case TAD_BODY_MUL: return launch_body<TAD_BODY_MUL, T>(pl, args, f, df, dx, fout, s);
+    case TAD_BODY_WORKED: return launch_body<TAD_BODY_WORKED, T>(pl, args, f, df, dx, fout, s);
+    case TAD_BODY_TANH_DOT: return launch_body<TAD_BODY_TANH_DOT, T>(pl, args, f, df, dx, fout, s);
+    default: return TAD_EUNSUPPORTED;
+    }
+}
+
+int generic_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s) {
+    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, nullptr, nullptr, nullptr, f, s)
+                               : launch_dtype<float>(pl, args, nullptr, nullptr, nullptr, f, s);
+}
+
+// Launches the generic gather kernel for every wanted gradient whose family is GENERIC.
+int generic_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
+                     void *const *dx, hipStream_t s) {
+    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, f, df, dx, nullptr, s)
+                               : launch_dtype<float>(pl, args, f, df, dx, nullptr, s);
+}
+
+}  // namespace tad

@@ -1,0 +1,17 @@
+// Declarations shared by the kernel translation units and the C ABI front end.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "plan.hpp"
+
+namespace tad {
+
+struct ArgPtrs {
+    const void *p[kMaxArgs];
+};
+
+int generic_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
+int generic_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
+                     void *const *dx, hipStream_t s);
+
+}  // namespace tad

@@ -1,0 +1,562 @@
+// Index-plan derivation on the host (Sec. 5.3, index half of the element-wise
+// derivation algorithm) and the host-only entry points of the C ABI.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+namespace tad {
+
+int body_arg_count(int body) {
+    switch (body) {
+    case TAD_BODY_SQ: case TAD_BODY_CUBE: case TAD_BODY_SIN: case TAD_BODY_EXP: return 1;
+    case TAD_BODY_MUL: case TAD_BODY_TANH_DOT: return 2;
+    case TAD_BODY_WORKED: return 4;
+    default: return -1;
+    }
+}
+
+static const int64_t kInt32Safe = (int64_t)1 << 30;
+
+static int32_t fit32(int64_t v) {
+    if (v >= kInt32Safe || v <= -kInt32Safe) throw overflow_error();
+    return (int32_t)v;
+}
+
+// Solve  A x = beta,  lo <= x <= hi  once for all beta with |beta_r| < extent[r]: Smith parts, constraints
+// Omega', Fourier-Motzkin rows and the folded device form (masks, transformed index, ranges).
+static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, const int64_t *extent,
+                          ArgPlan &ap) {
+    const int D = A.cols, N = A.rows;
+    bool nonzero = false;
+    for (int64_t v : A.a) nonzero |= v != 0;
+    if (!nonzero) return TAD_EINVAL;  // the Smith algorithm is defined for non-zero matrices only
+
+    ap.smith = smith_normal_form(A);
+    const int R = ap.smith.R, kappa = D - R;
+    if (kappa > TAD_MAX_KERNEL) return TAD_EUNSUPPORTED;
+    ap.diag.resize(R);
+    for (int r = 0; r < R; ++r) ap.diag[r] = ap.smith.S(r, r);
+    ap.UR = IMat(R, N);
+    ap.C = IMat(N - R, N);
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < N; ++j) {
+            if (i < R) ap.UR(i, j) = ap.smith.U(i, j);
+            else ap.C(i - R, j) = ap.smith.U(i, j);
+        }
+    ap.VR = IMat(D, R);
+    ap.K = IMat(D, kappa);
+    for (int i = 0; i < D; ++i)
+        for (int j = 0; j < D; ++j) {
+            if (j < R) ap.VR(i, j) = ap.smith.V(i, j);
+            else ap.K(i, j - R) = ap.smith.V(i, j);
+        }
+
+    // Omega': [K ; -K] z >= b(beta),  b = [lo - I beta ; I beta - hi]  (Sec. 5.1, zero-based box)
+    IMat cons(2 * D, kappa), B = IMat::identity(2 * D);
+    for (int d = 0; d < D; ++d)
+        for (int m = 0; m < kappa; ++m) {
+            cons(d, m) = ap.K(d, m);
+            cons(D + d, m) = cneg(ap.K(d, m));
+        }
+    ap.fm = fourier_motzkin(cons, 2 * D, B);
+    if (!ap.fm.bounded) return TAD_EINVAL;  // a kernel direction that is bounded from one side only
+
+    // ---- fold into the device form -------------------------------------------------------------
+    GatherPlan &g = ap.dev;
+    std::memset(&g, 0, sizeof g);
+    g.rank = N;
+    for (int r = 0; r < N; ++r) g.shape[r] = fit32(extent[r]);
+    g.R = R; g.kappa = kappa; g.nC = N - R;
+    for (int r = 0; r < R; ++r) {
+        g.diag[r] = fit32(ap.diag[r]);
+        for (int d = 0; d < N; ++d) g.U[r][d] = fit32(ap.UR(r, d));
+    }
+    for (int c = 0; c < N - R; ++c)
+        for (int d = 0; d < N; ++d) g.C[c][d] = fit32(ap.C(c, d));
+
+    // Magnitude bounds of y and z over all beta, to prove that int32 arithmetic on the device cannot
+    // overflow.  |y_r| <= |U beta|_r.  [y z] = V^{-1} [alpha k] with V unimodular, so |z_m| is bounded by
+    // row R+m of V^{-1} applied to the box extents.
+    int64_t ymax[kMaxRank] = {0}, zmax = 0;
+    for (int r = 0; r < R; ++r) {
+        int64_t s = 0;
+        for (int d = 0; d < N; ++d) s = cadd(s, cmul(cabs(ap.UR(r, d)), extent[d]));
+        ymax[r] = s;
+        fit32(s);
+    }
+    for (int c = 0; c < N - R; ++c) {
+        int64_t s = 0;
+        for (int d = 0; d < N; ++d) s = cadd(s, cmul(cabs(ap.C(c, d)), extent[d]));
+        fit32(s);
+    }
+    {
+        // integer Gauss-Jordan on [V | 1] with row operations (V is unimodular, pivots end as +-1)
+        IMat W = ap.smith.V, Inv = IMat::identity(D);
+        for (int c = 0; c < D; ++c) {
+            for (;;) {
+                int piv = -1;
+                int64_t best = 0;
+                for (int i = c; i < D; ++i) {
+                    int64_t v = cabs(W(i, c));
+                    if (v != 0 && (piv < 0 || v < best)) { best = v; piv = i; }
+                }
+                if (piv < 0) return TAD_EINVAL;
+                detail::swap_rows(W, c, piv); detail::swap_rows(Inv, c, piv);
+                bool clean = true;
+                for (int i = c + 1; i < D; ++i) {
+                    if (W(i, c) == 0) continue;
+                    int64_t f = W(i, c) / W(c, c);
+                    detail::sub_row(W, i, c, f); detail::sub_row(Inv, i, c, f);
+                    if (W(i, c) != 0) clean = false;
+                }
+                if (clean) break;
+            }
+            if (W(c, c) < 0)
+                for (int j = 0; j < D; ++j) { W(c, j) = cneg(W(c, j)); Inv(c, j) = cneg(Inv(c, j)); }
+            if (W(c, c) != 1) return TAD_EINVAL;
+        }
+        for (int c = D - 1; c >= 0; --c)   // back substitution: clear the entries above each pivot
+            for (int i = 0; i < c; ++i) {
+                int64_t f = W(i, c);
+                if (f == 0) continue;
+                detail::sub_row(W, i, c, f); detail::sub_row(Inv, i, c, f);
+            }
+        for (int m = 0; m < kappa; ++m) {
+            int64_t s = 0;
+            for (int d = 0; d < D; ++d)
+                s = cadd(s, cmul(cabs(Inv(R + m, d)), std::max(cabs(lo[d]), cabs(hi[d]))));
+            zmax = std::max(zmax, s);
+        }
+        fit32(zmax);
+    }
+
+    auto fold = [&](int64_t scale, const std::vector<int64_t> &cb, const std::vector<int64_t> *cz) {
+        GRow row;
+        std::memset(&row, 0, sizeof row);
+        row.scale = fit32(scale);
+        int64_t k0 = 0;
+        for (int d = 0; d < D; ++d)
+            k0 = cadd(k0, csub(cmul(cb[d], lo[d]), cmul(cb[D + d], hi[d])));
+        row.k0 = fit32(k0);
+        int64_t mag = cabs(k0);
+        for (int r = 0; r < R; ++r) {
+            int64_t s = 0;
+            for (int d = 0; d < D; ++d) s = cadd(s, cmul(csub(cb[D + d], cb[d]), ap.VR(d, r)));
+            row.ky[r] = fit32(s);
+            mag = cadd(mag, cmul(cabs(s), ymax[r]));
+        }
+        if (cz)
+            for (int m = 0; m < kappa; ++m) {
+                row.kz[m] = fit32((*cz)[m]);
+                mag = cadd(mag, cmul(cabs((*cz)[m]), zmax));
+            }
+        fit32(mag);
+        return row;
+    };
+
+    int nrows = 0;
+    for (int k = 0; k < kappa; ++k) {
+        const auto &lo = ap.fm.lower[k];
+        const auto &hi = ap.fm.upper[k];
+        if (nrows + (int)lo.size() + (int)hi.size() > kMaxRows) return TAD_EUNSUPPORTED;
+        g.lo_begin[k] = (uint8_t)nrows;
+        for (const FMRow &r : lo) g.rows[nrows++] = fold(r.scale, r.coef_b, &r.coef_z);
+        g.lo_end[k] = (uint8_t)nrows;
+        g.hi_begin[k] = (uint8_t)nrows;
+        for (const FMRow &r : hi) g.rows[nrows++] = fold(r.scale, r.coef_b, &r.coef_z);
+        g.hi_end[k] = (uint8_t)nrows;
+    }
+    // only the original variable-free constraints need an explicit test; derived rows of F are implied
+    // by the loop ranges being empty
+    g.nF = 0;
+    for (size_t f = 0; f < ap.fm.feasibility.size(); ++f) {
+        if (!ap.fm.feasibility_original[f]) continue;
+        if (g.nF == kMaxFeas) return TAD_EUNSUPPORTED;
+        g.feas[g.nF++] = fold(1, ap.fm.feasibility[f], nullptr);
+    }
+    ap.derived = true;
+    return TAD_OK;
+}
+
+// Index plan of one argument of an expression (one pass of the loop body of the derivation algorithm).
+static int derive_arg(const tad_plan &pl, int p, ArgPlan &ap) {
+    const tad_arg &arg = pl.args[p];
+    const int D = pl.n_ext, N = arg.rank;
+    IMat A(N, D);
+    for (int r = 0; r < N; ++r)
+        for (int d = 0; d < D; ++d) A(r, d) = arg.index[r][d];
+    int rc = derive_lattice(A, pl.lo, pl.hi, arg.shape, ap);
+    if (rc) return rc;
+    GatherPlan &g = ap.dev;
+    const int R = ap.smith.R, kappa = D - R;
+
+    // memory offsets, linear in the extended index, re-expressed in (y, z)
+    for (int s = 0; s < kSlots; ++s) {
+        int64_t lin[TAD_MAX_EXT] = {0};
+        if (s < (int)pl.args.size()) {
+            const tad_arg &q = pl.args[s];
+            int64_t stride = 1;
+            for (int r = q.rank - 1; r >= 0; --r) {
+                for (int d = 0; d < D; ++d) lin[d] = cadd(lin[d], cmul(stride, q.index[r][d]));
+                stride = cmul(stride, q.shape[r]);
+            }
+        } else if (s == kSlotF) {
+            int64_t stride = 1;
+            for (int d = pl.expr.n_f - 1; d >= 0; --d) {
+                lin[d] = stride;
+                stride = cmul(stride, pl.expr.f_shape[d]);
+            }
+        } else {
+            continue;
+        }
+        for (int r = 0; r < R; ++r) {
+            int64_t v = 0;
+            for (int d = 0; d < D; ++d) v = cadd(v, cmul(lin[d], ap.VR(d, r)));
+            g.offY[s][r] = v;
+        }
+        for (int m = 0; m < kappa; ++m) {
+            int64_t v = 0;
+            for (int d = 0; d < D; ++d) v = cadd(v, cmul(lin[d], ap.K(d, m)));
+            g.offZ[s][m] = v;
+        }
+    }
+    ap.derived = true;
+    return TAD_OK;
+}
+
+int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt, uint32_t flags,
+                tad_plan **out) {
+    if (!expr || !args || !out) return TAD_EINVAL;
+    *out = nullptr;
+    if (dt != TAD_F32 && dt != TAD_F64) return TAD_EINVAL;
+    const int want = body_arg_count(expr->body);
+    if (want < 0) return TAD_EUNSUPPORTED;
+    if (n_args != want) return TAD_EINVAL;
+    if (expr->n_f < 1 || expr->n_sum < 0 || expr->n_f + expr->n_sum > TAD_MAX_EXT) return TAD_EINVAL;
+    if (expr->n_sum > 0 &&
+        (expr->body == TAD_BODY_SQ || expr->body == TAD_BODY_CUBE || expr->body == TAD_BODY_SIN))
+        return TAD_EUNSUPPORTED;
+
+    tad_plan *pl = new (std::nothrow) tad_plan();
+    if (!pl) return TAD_ENOMEM;
+    struct Guard {
+        tad_plan *p;
+        ~Guard() { delete p; }
+    } guard{pl};
+
+    pl->expr = *expr;
+    pl->args.assign(args, args + n_args);
+    pl->dtype = dt;
+    pl->flags = flags;
+    pl->n_ext = expr->n_f + expr->n_sum;
+    const int D = pl->n_ext;
+    pl->f_count = 1;
+    for (int d = 0; d < expr->n_f; ++d) {
+        if (expr->f_shape[d] < 1) return TAD_ESHAPE;
+        pl->lo[d] = 0;
+        pl->hi[d] = expr->f_shape[d] - 1;
+        pl->f_count = cmul(pl->f_count, expr->f_shape[d]);
+    }
+    for (int s = 0; s < expr->n_sum; ++s) {
+        if (expr->sum_lo[s] > expr->sum_hi[s]) return TAD_ESHAPE;
+        pl->lo[expr->n_f + s] = expr->sum_lo[s];
+        pl->hi[expr->n_f + s] = expr->sum_hi[s];
+    }
+    if (pl->f_count >= ((int64_t)1 << 31)) return TAD_EOVERFLOW;
+
+    pl->arg_count.resize(n_args);
+    for (int p = 0; p < n_args; ++p) {
+        const tad_arg &a = args[p];
+        if (a.rank < 1 || a.rank > TAD_MAX_RANK) return TAD_EINVAL;
+        if (a.n_occ != 1) return TAD_EUNSUPPORTED;
+        int64_t cnt = 1;
+        for (int r = 0; r < a.rank; ++r) {
+            if (a.shape[r] < 1) return TAD_ESHAPE;
+            cnt = cmul(cnt, a.shape[r]);
+            // extremes of the linear map over the box: every reachable index must lie in the shape
+            int64_t mn = 0, mx = 0;
+            for (int d = 0; d < D; ++d) {
+                int64_t u = cmul(a.index[r][d], pl->lo[d]), v = cmul(a.index[r][d], pl->hi[d]);
+                mn = cadd(mn, std::min(u, v));
+                mx = cadd(mx, std::max(u, v));
+            }
+            if (mn < 0 || mx >= a.shape[r]) return TAD_ESHAPE;
+        }
+        if (cnt >= ((int64_t)1 << 31)) return TAD_EOVERFLOW;
+        pl->arg_count[p] = cnt;
+    }
+
+    // forward plan: linear element offsets of every argument in the extended index
+    ForwardPlan &fw = pl->fwd;
+    std::memset(&fw, 0, sizeof fw);
+    fw.n_f = expr->n_f;
+    fw.n_sum = expr->n_sum;
+    for (int d = 0; d < expr->n_f; ++d) fw.f_shape[d] = fit32(expr->f_shape[d]);
+    for (int s = 0; s < expr->n_sum; ++s) {
+        fw.sum_lo[s] = fit32(expr->sum_lo[s]);
+        fw.sum_n[s] = fit32(csub(expr->sum_hi[s], expr->sum_lo[s]) + 1);
+    }
+    for (int p = 0; p < n_args; ++p) {
+        int64_t stride = 1;
+        for (int r = args[p].rank - 1; r >= 0; --r) {
+            for (int d = 0; d < D; ++d)
+                fw.off[p][d] = cadd(fw.off[p][d], cmul(stride, args[p].index[r][d]));
+            stride = cmul(stride, args[p].shape[r]);
+        }
+    }
+
+    pl->ap.resize(n_args);
+    for (int p = 0; p < n_args; ++p) {
+        if (!args[p].needs_grad) continue;
+        int rc = derive_arg(*pl, p, pl->ap[p]);
+        if (rc) return rc;
+    }
+    select_families(*pl);
+    guard.p = nullptr;
+    *out = pl;
+    return TAD_OK;
+}
+
+// Visit every extended index of beta through masks, ranges and the maps V_R y + K z.
+template <class Fn>
+static void visit_beta(int n_ext, const ArgPlan &ap, const int32_t *beta, Fn &&fn) {
+    const GatherPlan &g = ap.dev;
+    int32_t y[kMaxRank] = {0}, z[kMaxKernel] = {0}, hi[kMaxKernel] = {0};
+    if (!gather_prepare(g, beta, y)) return;
+    auto emit = [&]() {
+        int64_t ext[TAD_MAX_EXT];
+        for (int d = 0; d < n_ext; ++d) {
+            int64_t v = 0;
+            for (int r = 0; r < g.R; ++r) v += ap.VR(d, r) * (int64_t)y[r];
+            for (int m = 0; m < g.kappa; ++m) v += ap.K(d, m) * (int64_t)z[m];
+            ext[d] = v;
+        }
+        fn(ext);
+    };
+    if (g.kappa == 0) { emit(); return; }
+    int lvl = g.kappa - 1;
+    gather_bounds(g, lvl, y, z, z[lvl], hi[lvl]);
+    for (;;) {
+        if (z[lvl] > hi[lvl]) {
+            if (++lvl == g.kappa) break;
+            ++z[lvl];
+            continue;
+        }
+        if (lvl == 0) { emit(); ++z[0]; }
+        else { --lvl; gather_bounds(g, lvl, y, z, z[lvl], hi[lvl]); }
+    }
+}
+
+}  // namespace tad
+
+using namespace tad;
+
+extern "C" {
+
+int tad_plan_derive(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt, uint32_t flags,
+                    tad_plan **out) {
+    try {
+        return derive_plan(expr, args, n_args, dt, flags, out);
+    } catch (const overflow_error &) {
+        return TAD_EOVERFLOW;
+    } catch (const std::bad_alloc &) {
+        return TAD_ENOMEM;
+    } catch (...) {
+        return TAD_EINVAL;
+    }
+}
+
+void tad_plan_free(tad_plan *plan) { delete plan; }
+
+size_t tad_plan_workspace_bytes(const tad_plan *plan) { return plan ? plan->ws_bytes : 0; }
+
+int tad_plan_forward_family(const tad_plan *plan) { return plan ? plan->fwd_family : TAD_EINVAL; }
+
+static const ArgPlan *get_arg(const tad_plan *plan, int arg, int occ) {
+    if (!plan || arg < 0 || arg >= (int)plan->ap.size() || occ != 0) return nullptr;
+    return plan->ap[arg].derived ? &plan->ap[arg] : nullptr;
+}
+
+int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out) {
+    const ArgPlan *ap = get_arg(plan, arg, occ);
+    if (!ap || !out) return TAD_EINVAL;
+    std::memset(out, 0, sizeof *out);
+    const int N = plan->args[arg].rank, D = plan->n_ext, R = ap->smith.R;
+    out->rank = R;
+    out->kernel_dim = D - R;
+    out->n_cokernel = N - R;
+    for (int r = 0; r < R; ++r) out->smith[r] = ap->diag[r];
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < N; ++j) out->U[i][j] = ap->smith.U(i, j);
+    for (int i = 0; i < D; ++i)
+        for (int j = 0; j < D; ++j) out->V[i][j] = ap->smith.V(i, j);
+    for (int i = 0; i < D; ++i)
+        for (int m = 0; m < D - R; ++m) out->K[i][m] = ap->K(i, m);
+    for (int c = 0; c < N - R; ++c)
+        for (int j = 0; j < N; ++j) out->C[c][j] = ap->C(c, j);
+    for (int k = 0; k < D - R; ++k) {
+        out->n_lower[k] = (int32_t)ap->fm.lower[k].size();
+        out->n_upper[k] = (int32_t)ap->fm.upper[k].size();
+    }
+    out->n_feasibility = (int32_t)ap->fm.feasibility.size();
+    out->family = ap->family;
+    return TAD_OK;
+}
+
+int tad_plan_bound_row(const tad_plan *plan, int arg, int kind, int level, int row, int64_t *scale,
+                       int64_t *coef_b, int64_t *coef_z) {
+    const ArgPlan *ap = get_arg(plan, arg, 0);
+    if (!ap || !scale || !coef_b || !coef_z) return TAD_EINVAL;
+    const int D = plan->n_ext, kappa = D - ap->smith.R;
+    std::fill(coef_b, coef_b + 2 * TAD_MAX_EXT, 0);
+    std::fill(coef_z, coef_z + TAD_MAX_KERNEL, 0);
+    auto put_b = [&](const std::vector<int64_t> &cb) {
+        for (int d = 0; d < D; ++d) {
+            coef_b[d] = cb[d];
+            coef_b[TAD_MAX_EXT + d] = cb[D + d];
+        }
+    };
+    if (kind == TAD_ROWS_FEASIBILITY) {
+        if (row < 0 || row >= (int)ap->fm.feasibility.size()) return TAD_EINVAL;
+        *scale = 1;
+        put_b(ap->fm.feasibility[row]);
+        return TAD_OK;
+    }
+    if (level < 0 || level >= kappa) return TAD_EINVAL;
+    const std::vector<FMRow> &rows = kind == TAD_ROWS_LOWER ? ap->fm.lower[level] : ap->fm.upper[level];
+    if (kind != TAD_ROWS_LOWER && kind != TAD_ROWS_UPPER) return TAD_EINVAL;
+    if (row < 0 || row >= (int)rows.size()) return TAD_EINVAL;
+    *scale = rows[row].scale;
+    put_b(rows[row].coef_b);
+    for (int m = 0; m < kappa; ++m) coef_z[m] = rows[row].coef_z[m];
+    return TAD_OK;
+}
+
+int tad_plan_enumerate(const tad_plan *plan, int arg, int occ, const int64_t *beta, int64_t *alpha_out,
+                       size_t cap, size_t *n) {
+    const ArgPlan *ap = get_arg(plan, arg, occ);
+    if (!ap || !beta || !n) return TAD_EINVAL;
+    const int N = plan->args[arg].rank, D = plan->n_ext;
+    int32_t b32[kMaxRank];
+    *n = 0;
+    for (int r = 0; r < N; ++r) {
+        if (beta[r] < 0 || beta[r] >= plan->args[arg].shape[r]) return TAD_ESHAPE;
+        b32[r] = (int32_t)beta[r];
+    }
+    std::vector<std::vector<int64_t>> pts;
+    try {
+        visit_beta(D, *ap, b32, [&](const int64_t *ext) { pts.emplace_back(ext, ext + D); });
+        std::sort(pts.begin(), pts.end());
+    } catch (const std::bad_alloc &) {
+        return TAD_ENOMEM;
+    }
+    *n = pts.size();
+    if (alpha_out)
+        for (size_t i = 0; i < pts.size() && i < cap; ++i)
+            std::copy(pts[i].begin(), pts[i].end(), alpha_out + i * D);
+    return TAD_OK;
+}
+
+int tad_plan_count_all(const tad_plan *plan, int arg, int64_t *counts) {
+    const ArgPlan *ap = get_arg(plan, arg, 0);
+    if (!ap || !counts) return TAD_EINVAL;
+    const tad_arg &a = plan->args[arg];
+    int32_t beta[kMaxRank] = {0};
+    const int64_t total = plan->arg_count[arg];
+    for (int64_t lin = 0; lin < total; ++lin) {
+        int64_t t = lin;
+        for (int r = a.rank - 1; r >= 0; --r) { beta[r] = (int32_t)(t % a.shape[r]); t /= a.shape[r]; }
+        int64_t c = 0;
+        visit_beta(plan->n_ext, *ap, beta, [&](const int64_t *) { ++c; });
+        counts[lin] = c;
+    }
+    return TAD_OK;
+}
+
+int tad_extended_gcd(int64_t a, int64_t b, int64_t *g, int64_t *x, int64_t *y) {
+    if (!g || !x || !y) return TAD_EINVAL;
+    try {
+        Bezout bz = egcd(a, b);
+        *g = bz.g; *x = bz.x; *y = bz.y;
+        return TAD_OK;
+    } catch (const overflow_error &) {
+        return TAD_EOVERFLOW;
+    }
+}
+
+int tad_smith_normal_form(const int64_t *A, int n, int m, int64_t *S, int64_t *U, int64_t *V, int *rank) {
+    if (!A || !S || !U || !V || !rank || n < 1 || m < 1 || n > 16 || m > 16) return TAD_EINVAL;
+    try {
+        IMat a(n, m);
+        bool nonzero = false;
+        for (int i = 0; i < n * m; ++i) { a.a[i] = A[i]; nonzero |= A[i] != 0; }
+        if (!nonzero) return TAD_EINVAL;
+        Smith w = smith_normal_form(a);
+        std::copy(w.S.a.begin(), w.S.a.end(), S);
+        std::copy(w.U.a.begin(), w.U.a.end(), U);
+        std::copy(w.V.a.begin(), w.V.a.end(), V);
+        *rank = w.R;
+        return TAD_OK;
+    } catch (const overflow_error &) {
+        return TAD_EOVERFLOW;
+    } catch (...) {
+        return TAD_ENOMEM;
+    }
+}
+
+int tad_lattice_enumerate(const int64_t *A, int n, int m, const int64_t *lo, const int64_t *hi,
+                          const int64_t *beta, int64_t *x_out, size_t cap, size_t *count) {
+    if (!A || !lo || !hi || !beta || !count || n < 1 || n > TAD_MAX_RANK || m < 1 || m > TAD_MAX_EXT)
+        return TAD_EINVAL;
+    *count = 0;
+    try {
+        IMat a(n, m);
+        for (int i = 0; i < n * m; ++i) a.a[i] = A[i];
+        int64_t extent[TAD_MAX_RANK];
+        int32_t b32[kMaxRank] = {0};
+        for (int r = 0; r < n; ++r) {
+            int64_t s = 1;
+            for (int d = 0; d < m; ++d) {
+                if (lo[d] > hi[d]) return TAD_ESHAPE;
+                s = cadd(s, cmul(cabs(a(r, d)), std::max(cabs(lo[d]), cabs(hi[d]))));
+            }
+            extent[r] = s;
+            if (cabs(beta[r]) >= s) return TAD_OK;   // beyond every reachable value: no solution
+            b32[r] = (int32_t)beta[r];
+        }
+        ArgPlan ap;
+        int rc = derive_lattice(a, lo, hi, extent, ap);
+        if (rc) return rc;
+        std::vector<std::vector<int64_t>> pts;
+        visit_beta(m, ap, b32, [&](const int64_t *x) { pts.emplace_back(x, x + m); });
+        std::sort(pts.begin(), pts.end());
+        *count = pts.size();
+        if (x_out)
+            for (size_t i = 0; i < pts.size() && i < cap; ++i)
+                std::copy(pts[i].begin(), pts[i].end(), x_out + i * m);
+        return TAD_OK;
+    } catch (const overflow_error &) {
+        return TAD_EOVERFLOW;
+    } catch (...) {
+        return TAD_ENOMEM;
+    }
+}
+
+const char *tad_strerror(int status) {
+    switch (status) {
+    case TAD_OK: return "ok";
+    case TAD_EINVAL: return "invalid argument";
+    case TAD_ESHAPE: return "index leaves a tensor's shape, or empty range";
+    case TAD_EINFEASIBLE: return "constraint system has no solution";
+    case TAD_EOVERFLOW: return "integer overflow";
+    case TAD_EUNSUPPORTED: return "unsupported body or index pattern";
+    case TAD_EDEVICE: return "device error";
+    case TAD_ENOMEM: return "out of memory or workspace too small";
+    case TAD_ENOGPU: return "no HIP device";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

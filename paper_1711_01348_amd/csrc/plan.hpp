@@ -1,0 +1,56 @@
+// Host-side index plan: result of the element-wise derivation (Sec. 5.3) for
+// every argument of one expression.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "../../include/tad.h"
+#include "fm.hpp"
+#include "plan_dev.h"
+#include "snf.hpp"
+
+namespace tad {
+
+struct ArgPlan {
+    bool derived = false;
+    Smith smith;                 // S = U A V
+    IMat UR, VR, K, C;           // first R rows of U, first R columns of V, kernel, cokernel
+    std::vector<int64_t> diag;   // alpha_1..alpha_R
+    FMResult fm;                 // rows over b(beta) in the paper's form
+    GatherPlan dev;              // folded form used by kernels and by enumeration
+    int family = TAD_FAMILY_GENERIC;
+};
+
+// Parameters of the specialised kernel families (filled by pattern recognition).
+struct FastParams {
+    int64_t I = 0, J = 0, K = 0;     // worked expression / 2-D patterns
+    int64_t N = 0, U = 0, V = 0, stride = 0, P = 0, Q = 0;  // strided stencil
+    int64_t c_ld = 0;                // row length of c (diagonal gather stride is c_ld + 1)
+};
+
+}  // namespace tad
+
+struct tad_plan {
+    tad_expr expr;
+    std::vector<tad_arg> args;
+    tad_dtype dtype;
+    uint32_t flags;
+    int n_ext;
+    int64_t lo[TAD_MAX_EXT], hi[TAD_MAX_EXT];  // inclusive box of the extended index
+    int64_t f_count;
+    std::vector<int64_t> arg_count;
+    tad::ForwardPlan fwd;
+    std::vector<tad::ArgPlan> ap;
+    int fwd_family = TAD_FAMILY_GENERIC;
+    tad::FastParams fast;
+    size_t ws_bytes = 0;
+};
+
+namespace tad {
+// Derivation proper; throws tad::overflow_error on int64 overflow.
+int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt, uint32_t flags,
+                tad_plan **out);
+int body_arg_count(int body);
+// Pattern recognition of the specialised kernel families (device-independent; defined in families.cpp).
+void select_families(tad_plan &plan);
+}  // namespace tad

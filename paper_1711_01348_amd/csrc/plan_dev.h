@@ -1,0 +1,123 @@
+// Compact, trivially copyable form of an index plan as the kernels receive it
+// (by value, as a kernel argument), and the mask / range evaluation shared by
+// the device kernels and the host-side enumeration (tad_plan_enumerate).
+//
+// For gradient element beta of one argument (Sec. 4.1 / 5.1):
+//   cokernel mask      C beta = 0
+//   transformed index  y_r = (U beta)_r / alpha_r  (r < R), zero gradient unless every division is exact
+//   function index     [alpha k] = V_R y + K z
+//   ranges             scale * z_k >= (<=) k0 + ky . y + kz . z_{>k}      (Fourier-Motzkin rows with
+//                      b(beta) = [lo - V_R y ; V_R y - hi] already substituted)
+// Memory offsets of every tensor are linear in (y, z) because the index maps are linear.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define TAD_HD __host__ __device__ __forceinline__
+#else
+#define TAD_HD inline
+#endif
+
+namespace tad {
+
+constexpr int kMaxExt = 6;
+constexpr int kMaxRank = 4;
+constexpr int kMaxArgs = 4;
+constexpr int kMaxKernel = 4;
+constexpr int kMaxRows = 32;   // lower + upper rows over all levels
+constexpr int kMaxFeas = 12;
+constexpr int kSlotF = kMaxArgs;        // offset slot of f / df
+constexpr int kSlots = kMaxArgs + 1;
+
+struct GRow {
+    int32_t scale;
+    int32_t k0;
+    int32_t ky[kMaxRank];
+    int32_t kz[kMaxKernel];
+};
+
+struct GatherPlan {
+    int32_t rank;                 // D_p
+    int32_t shape[kMaxRank];      // N^p
+    int32_t R, kappa, nC, nF;
+    int32_t U[kMaxRank][kMaxRank];   // first R rows of U
+    int32_t diag[kMaxRank];          // alpha_1..alpha_R
+    int32_t C[kMaxRank][kMaxRank];   // cokernel rows
+    GRow feas[kMaxFeas];             // k0 + ky . y <= 0
+    uint8_t lo_begin[kMaxKernel], lo_end[kMaxKernel];
+    uint8_t hi_begin[kMaxKernel], hi_end[kMaxKernel];
+    GRow rows[kMaxRows];
+    int64_t offY[kSlots][kMaxRank];    // element offset of tensor slot s = offY[s] . y + offZ[s] . z
+    int64_t offZ[kSlots][kMaxKernel];
+};
+
+struct ForwardPlan {
+    int32_t n_f, n_sum;
+    int32_t f_shape[kMaxExt];
+    int32_t sum_lo[kMaxExt];
+    int32_t sum_n[kMaxExt];            // number of values of each summation index
+    int64_t off[kMaxArgs][kMaxExt];    // element offset of argument p = off[p] . [alpha k]
+};
+
+TAD_HD int32_t floor_div_i(int32_t a, int32_t b) {  // b > 0
+    int32_t q = a / b, r = a % b;
+    return (r < 0) ? q - 1 : q;
+}
+TAD_HD int32_t ceil_div_i(int32_t a, int32_t b) {  // b > 0
+    int32_t q = a / b, r = a % b;
+    return (r > 0) ? q + 1 : q;
+}
+
+// Masks and transformed index for one beta.  Returns false when the gradient element is zero
+// because of the cokernel condition, the divisibility condition or an infeasible range system.
+TAD_HD bool gather_prepare(const GatherPlan &P, const int32_t *beta, int32_t *y) {
+    for (int c = 0; c < P.nC; ++c) {
+        int32_t s = 0;
+        for (int d = 0; d < P.rank; ++d) s += P.C[c][d] * beta[d];
+        if (s != 0) return false;
+    }
+    for (int r = 0; r < P.R; ++r) {
+        int32_t s = 0;
+        for (int d = 0; d < P.rank; ++d) s += P.U[r][d] * beta[d];
+        if (s % P.diag[r] != 0) return false;
+        y[r] = s / P.diag[r];
+    }
+    for (int f = 0; f < P.nF; ++f) {
+        int32_t s = P.feas[f].k0;
+        for (int r = 0; r < P.R; ++r) s += P.feas[f].ky[r] * y[r];
+        if (s > 0) return false;
+    }
+    return true;
+}
+
+TAD_HD int32_t row_rhs(const GatherPlan &P, const GRow &g, int level, const int32_t *y, const int32_t *z) {
+    int32_t s = g.k0;
+    for (int r = 0; r < P.R; ++r) s += g.ky[r] * y[r];
+    for (int m = level + 1; m < P.kappa; ++m) s += g.kz[m] * z[m];
+    return s;
+}
+
+// Inclusive range of z_level given y and the outer coordinates z_{>level} (may be empty: lo > hi).
+TAD_HD void gather_bounds(const GatherPlan &P, int level, const int32_t *y, const int32_t *z,
+                          int32_t &lo, int32_t &hi) {
+    int32_t l = INT32_MIN, h = INT32_MAX;
+    for (int i = P.lo_begin[level]; i < P.lo_end[level]; ++i) {
+        int32_t v = ceil_div_i(row_rhs(P, P.rows[i], level, y, z), P.rows[i].scale);
+        l = v > l ? v : l;
+    }
+    for (int i = P.hi_begin[level]; i < P.hi_end[level]; ++i) {
+        int32_t v = floor_div_i(row_rhs(P, P.rows[i], level, y, z), P.rows[i].scale);
+        h = v < h ? v : h;
+    }
+    lo = l;
+    hi = h;
+}
+
+TAD_HD int64_t gather_offset(const GatherPlan &P, int slot, const int32_t *y, const int32_t *z) {
+    int64_t o = 0;
+    for (int r = 0; r < P.R; ++r) o += P.offY[slot][r] * (int64_t)y[r];
+    for (int m = 0; m < P.kappa; ++m) o += P.offZ[slot][m] * (int64_t)z[m];
+    return o;
+}
+
+}  // namespace tad

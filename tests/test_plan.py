@@ -1,0 +1,365 @@
+"""Host-side index plans: integer machinery invariants, paper pins, brute-force parity (no GPU)."""
+import itertools
+import os
+import re
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1711_01348_amd import binding as B
+from paper_1711_01348_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+HEADER = os.path.join(os.path.dirname(os.path.dirname(__file__)), "include", "tad.h")
+
+
+def _expr(body, f_shape, sums, args, dtype="f64"):
+    return wl.ExprSpec(body, tuple(f_shape), list(sums),
+                       [wl.ArgSpec(n, tuple(s), A) for n, s, A in args], dtype)
+
+
+# ---------------------------------------------------------------- ABI surface
+
+def test_library_exports_every_declared_symbol():
+    text = open(HEADER).read()
+    declared = set(re.findall(r"\b(tad_[a-z_0-9]+)\s*\(", text))
+    assert declared, "no declarations found"
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+
+
+# ---------------------------------------------------------------- Sec. 4.1: Euclid and Smith
+
+def test_extended_gcd_bezout_identity():
+    rng = np.random.default_rng(1)
+    pairs = [(0, 0), (0, 7), (-7, 0), (12, 18), (-12, 18), (12, -18), (-12, -18), (1, 1), (2**40, 2**20 * 3)]
+    pairs += [tuple(int(v) for v in rng.integers(-10**6, 10**6, 2)) for _ in range(300)]
+    for a, b in pairs:
+        g, x, y = B.extended_gcd(a, b)
+        assert g == int(np.gcd(a, b)) and g >= 0
+        assert a * x + b * y == g
+
+
+def _det(M):
+    M = [[Fraction(int(v)) for v in row] for row in M]
+    n, d = len(M), Fraction(1)
+    for c in range(n):
+        piv = next((r for r in range(c, n) if M[r][c] != 0), None)
+        if piv is None:
+            return Fraction(0)
+        if piv != c:
+            M[c], M[piv] = M[piv], M[c]
+            d = -d
+        d *= M[c][c]
+        for r in range(c + 1, n):
+            f = M[r][c] / M[c][c]
+            M[r] = [a - f * b for a, b in zip(M[r], M[c])]
+    return d
+
+
+def _check_smith(A):
+    A = np.asarray(A, dtype=np.int64)
+    S, U, V, R = B.smith_normal_form(A)
+    assert np.array_equal(U.astype(object) @ A.astype(object) @ V.astype(object), S.astype(object))
+    assert abs(_det(U)) == 1 and abs(_det(V)) == 1
+    off = S.copy()
+    for i in range(min(S.shape)):
+        off[i, i] = 0
+    assert not off.any()
+    diag = [int(S[i, i]) for i in range(min(S.shape))]
+    assert all(d > 0 for d in diag[:R]) and all(d == 0 for d in diag[R:])
+    assert all(diag[i + 1] % diag[i] == 0 for i in range(R - 1))
+    assert R == np.linalg.matrix_rank(A.astype(float))
+    # pseudo-inverse, kernel, cokernel (Sec. 4.1)
+    n, m = A.shape
+    Sd = [[Fraction(0)] * n for _ in range(m)]
+    for r in range(R):
+        Sd[r][r] = Fraction(1, diag[r])
+    fr = lambda M: [[Fraction(int(v)) for v in row] for row in M]
+    mul = lambda X, Y: [[sum(X[i][k] * Y[k][j] for k in range(len(Y))) for j in range(len(Y[0]))] for i in range(len(X))]
+    I = mul(mul(fr(V), Sd), fr(U))
+    assert mul(mul(fr(A), I), fr(A)) == fr(A)            # A I A = A
+    assert not (A.astype(object) @ V[:, R:].astype(object)).any()   # A K = 0
+    assert not (U[R:, :].astype(object) @ A.astype(object)).any()   # C A = 0
+    return diag[:R]
+
+
+def test_smith_known_and_edge_cases():
+    assert _check_smith([[2, 4, 4], [-6, 6, 12], [10, -4, -16]]) == [2, 6, 12]
+    assert _check_smith([[6, 0], [0, 4]]) == [2, 12]       # needs the divisibility repair
+    assert _check_smith([[4, 0, 0], [0, 6, 0], [0, 0, 10]]) == [2, 2, 60]
+    assert _check_smith([[1, -2]]) == [1]
+    assert _check_smith([[2, 4]]) == [2]
+    assert _check_smith([[2], [4], [6]]) == [2]
+    assert _check_smith([[0, 0], [0, -3]]) == [3]
+    assert _check_smith([[1, 0, 0], [1, 0, 0]]) == [1]
+    assert _check_smith([[1, 0, 0, 0, 0], [0, 2, 0, 1, 0], [0, 0, 2, 0, 1]]) == [1, 1, 1]
+
+
+def test_smith_random_matrices():
+    rng = np.random.default_rng(2)
+    for _ in range(300):
+        n, m = rng.integers(1, 5), rng.integers(1, 6)
+        A = rng.integers(-6, 7, (n, m))
+        if rng.random() < 0.3 and n > 1:       # force rank deficiency
+            A[-1] = A[0] * rng.integers(-2, 3)
+        if not A.any():
+            continue
+        _check_smith(A)
+
+
+def test_smith_rejects_zero_matrix_and_overflow():
+    with pytest.raises(B.TadError) as e:
+        B.smith_normal_form([[0, 0], [0, 0]])
+    assert e.value.status == -1
+    big = 2**62
+    with pytest.raises(B.TadError) as e:
+        B.smith_normal_form([[big, big - 1], [big - 3, big - 7]])
+    assert e.value.status == -4
+
+
+# ---------------------------------------------------------------- Sec. 4.2 / 5.1: ranges
+
+def _brute(A, lo, hi, beta):
+    A = np.asarray(A)
+    pts = [x for x in itertools.product(*[range(l, h + 1) for l, h in zip(lo, hi)])
+           if np.array_equal(A @ np.array(x), np.asarray(beta))]
+    return sorted(pts)
+
+
+def _fig(name):
+    out = {}
+    for line in open(os.path.join(GOLDEN, "lattice_figures.txt")):
+        if line.startswith(name + " "):
+            _, key, *vals = line.split()
+            out[key] = [int(v) for v in vals]
+    return out
+
+
+def test_fig1_line_in_a_box():
+    g = _fig("fig1")
+    lo, hi = [g["box"][0], g["box"][2]], [g["box"][1], g["box"][3]]
+    pts = B.lattice_enumerate([g["A"]], lo, hi, g["beta"])
+    zlo, zhi = g["z"]
+    assert [tuple(p) for p in pts] == [(-1 + 2 * z, z) for z in range(zlo, zhi + 1)]
+    # neighbours of the end points l = (0, 0.5), h = (6, 3.5): ceil(0.5) = 1, floor(3.5) = 3
+    assert (-1 + 2 * 0, 0) not in map(tuple, pts) and (-1 + 2 * 4, 4) not in map(tuple, pts)
+
+
+def test_fig2_plane_in_a_box():
+    g = _fig("fig2")
+    lo, hi = [g["box"][0], g["box"][2], -30], [g["box"][1], g["box"][3], 30]
+    pts = {tuple(p) for p in B.lattice_enumerate([g["A"]], lo, hi, g["beta"])}
+    K = np.array(g["K"]).reshape(2, 3).T
+    expect = {tuple(np.array([3, 0, 0]) + K @ np.array([z1, z2]))
+              for z2 in range(-1, 6) for z1 in range(max(-1, -z2), min(1, 4 - z2) + 1)}
+    assert len(expect) == g["count"][0]
+    assert pts == expect
+
+
+def test_lattice_enumeration_matches_brute_force_on_random_systems():
+    rng = np.random.default_rng(3)
+    done = 0
+    while done < 150:
+        n, m = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        A = rng.integers(-3, 4, (n, m))
+        if not A.any():
+            continue
+        lo = rng.integers(-3, 2, m)
+        hi = lo + rng.integers(0, 5, m)
+        # a few reachable and a few arbitrary right-hand sides
+        betas = [A @ rng.integers(lo, hi + 1) for _ in range(3)] + [rng.integers(-6, 7, n) for _ in range(3)]
+        for beta in betas:
+            got = [tuple(p) for p in B.lattice_enumerate(A, lo, hi, beta)]
+            assert got == _brute(A, lo, hi, beta), (A, lo, hi, beta)
+        done += 1
+
+
+def test_divisibility_condition_is_not_redundant():
+    """f_ij = x_{2i}: for odd beta the z range is the full j range, yet there is no integer solution."""
+    assert len(B.lattice_enumerate([[2, 0]], [0, 0], [4, 3], [3])) == 0
+    assert len(B.lattice_enumerate([[2, 0]], [0, 0], [4, 3], [4])) == 4
+    assert len(B.lattice_enumerate([[2]], [0], [4], [3])) == 0
+    assert [tuple(p) for p in B.lattice_enumerate([[2, 4]], [0, 0], [5, 5], [10])] == [(1, 2), (3, 1), (5, 0)]
+    assert len(B.lattice_enumerate([[2, 4]], [0, 0], [5, 5], [7])) == 0
+
+
+# ---------------------------------------------------------------- Sec. 6: printed plan of the worked expression
+
+def _read_limits():
+    lim = {}
+    for line in open(os.path.join(GOLDEN, "worked_expression_limits.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        g, kind, *rest = line.split()
+        if kind not in ("condition", "index"):
+            lim.setdefault(g, {})[kind] = (rest[0], rest[1])
+    return lim
+
+
+def _lim(txt, m=0):
+    mm = re.fullmatch(r"(max|min)\((-?\d+),m(-\d+)?\)", txt)
+    if mm:
+        return (max if mm.group(1) == "max" else min)(int(mm.group(2)), m + int(mm.group(3) or 0))
+    return int(txt)
+
+
+def test_plan_reproduces_printed_limits():
+    lim = _read_limits()
+    e = wl.worked_expr(3, 4, 5, "f64", d_len=8)
+    plan = B.Plan(e)
+    rng = lambda g, z, m=0: range(_lim(lim[g][z][0], m), _lim(lim[g][z][1], m) + 1)
+    for i in range(3):
+        for k in range(5):
+            assert [tuple(p) for p in plan.enumerate(0, [i, k])] == [(i, z, k) for z in rng("da", "z0")]
+    for j in range(4):
+        for k in range(5):
+            assert [tuple(p) for p in plan.enumerate(1, [j, k])] == [(z, j, k) for z in rng("db", "z0")]
+    for b0 in range(3):
+        for b1 in range(3):
+            got = [tuple(p) for p in plan.enumerate(2, [b0, b1])]
+            want = sorted((b1, z0, z1) for z1 in rng("dc", "z1") for z0 in rng("dc", "z0")) if b0 == b1 else []
+            assert got == want
+    for m in range(8):
+        got = [tuple(p) for p in plan.enumerate(3, [m])]
+        want = sorted((m - z1, z0, z1) for z1 in rng("dd", "z1", m) for z0 in rng("dd", "z0"))
+        assert got == want
+    assert len(plan.enumerate(3, [7])) == 0
+    # the parameterisation itself: one cokernel row +-(1, -1) for c; kernel of d spans j and (i down, k up)
+    qc, qd = plan.query(2), plan.query(3)
+    assert qc["rank"] == 1 and qc["C"].tolist() in ([[1, -1]], [[-1, 1]])
+    assert qd["rank"] == 1 and qd["kernel_dim"] == 2
+    assert not (np.array([[1, 0, 1]]) @ qd["K"]).any()
+
+
+def _ranges_from_rows(plan, arg, beta):
+    """Evaluate the Fourier-Motzkin rows in the paper's form (over b(beta)) with exact fractions."""
+    q = plan.query(arg)
+    e = plan.expr
+    D, R, kap = plan.n_ext, q["rank"], q["kernel_dim"]
+    lo = [0] * len(e.f_shape) + [s[0] for s in e.sums]
+    hi = [n - 1 for n in e.f_shape] + [s[1] for s in e.sums]
+    U, V = q["U"], q["V"]
+    y = [Fraction(int((U[r] * np.array(beta)).sum()), q["smith"][r]) for r in range(R)]
+    base = [sum(Fraction(int(V[d, r])) * y[r] for r in range(R)) for d in range(D)]     # I beta
+    b = [Fraction(lo[d]) - base[d] for d in range(D)] + [base[d] - Fraction(hi[d]) for d in range(D)]
+    for row in plan.bound_rows(arg, B.ROWS_FEASIBILITY):
+        if sum(int(c) * v for c, v in zip(row["coef_b"], b)) > 0:
+            return None
+    return q, b
+
+
+def test_bound_rows_in_paper_form_give_the_printed_dd_range():
+    e = wl.worked_expr(3, 4, 5, "f64", d_len=8)
+    plan = B.Plan(e)
+    import math
+    for m in range(7):
+        q, b = _ranges_from_rows(plan, 3, [m])
+        outer = q["kernel_dim"] - 1
+        lo = max(math.ceil(sum(int(c) * v for c, v in zip(r["coef_b"], b)) / r["scale"])
+                 for r in plan.bound_rows(3, B.ROWS_LOWER, outer))
+        hi = min(math.floor(sum(int(c) * v for c, v in zip(r["coef_b"], b)) / r["scale"])
+                 for r in plan.bound_rows(3, B.ROWS_UPPER, outer))
+        # outermost kernel coordinate of d moves k up and i down: printed range max(0, m-2) .. min(4, m)
+        col = q["K"][:, outer]
+        assert col.tolist() in ([-1, 0, 1], [1, 0, -1])
+        if col.tolist() == [-1, 0, 1]:
+            assert (lo, hi) == (max(0, m - 2), min(4, m))
+        else:
+            assert (-hi, -lo) == (max(0, m - 2), min(4, m))
+
+
+# ---------------------------------------------------------------- plans of the benchmark configurations
+
+def _check_plan_against_scan(expr, sample=40, seed=0):
+    plan = B.Plan(expr)
+    rng = np.random.default_rng(seed)
+    for p, a in enumerate(expr.args):
+        counts = oracle.gamma_counts(expr, p)
+        assert np.array_equal(plan.count_all(p), counts), (expr.body, p)
+        total = int(np.prod(a.shape))
+        picks = range(total) if total <= sample else rng.choice(total, sample, replace=False)
+        for lin in picks:
+            beta = np.unravel_index(int(lin), a.shape)
+            assert np.array_equal(plan.enumerate(p, beta), oracle.gamma(expr, p, beta)), (expr.body, p, beta)
+
+
+@pytest.mark.parametrize("w", wl.all_configs("small")[:5] + [wl.config5("small")], ids=lambda w: w.name)
+def test_config_plans_match_exhaustive_scan_small(w):
+    _check_plan_against_scan(w.expr)
+
+
+def test_config4_plan_matches_scan_reduced_rows():
+    _check_plan_against_scan(wl.worked_expr(9, 7, 256, "f32"), sample=25)
+
+
+@pytest.mark.parametrize("make", [
+    lambda: _expr("exp", (5,), [], [("x", (9,), [[2]])]),
+    lambda: _expr("exp", (5, 4), [], [("x", (9,), [[2, 0]])]),
+    lambda: _expr("exp", (4, 3), [], [("x", (20,), [[2, 4]])]),
+    lambda: _expr("exp", (4, 3), [], [("x", (12,), [[3, 1]])]),
+    lambda: _expr("exp", (3, 4), [(0, 2)], [("x", (7, 9), [[2, 0, 1], [0, 2, 1]])]),
+    lambda: _expr("mul", (5, 4), [(1, 6)], [("x", (5, 7), [[1, 0, 0], [0, 0, 1]]), ("y", (7, 4), [[0, 0, 1], [0, 1, 0]])]),
+    lambda: _expr("exp", (3, 3, 3), [], [("x", (5, 5), [[1, 1, 0], [0, 1, 1]])]),
+    lambda: _expr("exp", (6,), [(0, 3), (0, 2)], [("x", (30,), [[3, 2, 4]])]),
+    lambda: wl.worked_expr(4, 3, 5, "f64", d_len=11, c_shape=(6, 5)),     # arguments larger than the referenced range
+])
+def test_assorted_index_maps_match_scan(make):
+    _check_plan_against_scan(make(), sample=1000)
+
+
+def test_counts_at_full_size():
+    """Bit-exact counts for every gradient element at the full benchmark sizes (cfg 2, 3, 5)."""
+    for w in [wl.config2(1), wl.config2(2), wl.config2(3), wl.config3(), wl.config5()]:
+        plan = B.Plan(w.expr)
+        for p in range(len(w.expr.args)):
+            assert np.array_equal(plan.count_all(p), oracle.gamma_counts(w.expr, p)), (w.name, p)
+
+
+# ---------------------------------------------------------------- error paths (host only)
+
+def _status(fn):
+    with pytest.raises(B.TadError) as e:
+        fn()
+    return e.value.status
+
+
+def test_error_paths():
+    ok = _expr("exp", (4, 4), [], [("x", (7,), [[1, 1]])])
+    B.Plan(ok)
+    assert _status(lambda: B.Plan(_expr("exp", (4, 4), [], [("x", (7,), [[0, 0]])]))) == -1       # zero matrix
+    assert _status(lambda: B.Plan(_expr("exp", (4, 4), [], [("x", (6,), [[1, 1]])]))) == -2       # leaves shape
+    assert _status(lambda: B.Plan(_expr("exp", (4, 4), [], [("x", (7,), [[1, -1]])]))) == -2      # negative index
+    assert _status(lambda: B.Plan(_expr("exp", (4, 4), [(3, 2)], [("x", (9,), [[1, 1, 1]])]))) == -2   # lo > hi
+    assert _status(lambda: B.Plan(_expr("sq", (4,), [(0, 1)], [("x", (9,), [[1, 1]])]))) == -5     # sq takes no sum
+    assert _status(lambda: B.Plan(_expr("mul", (4,), [], [("x", (4,), [[1]])]))) == -1             # argument count
+    assert _status(lambda: B.Plan(_expr("exp", (4, 0), [], [("x", (7,), [[1, 1]])]))) == -2        # empty f
+    big = 2**40
+    assert _status(lambda: B.Plan(_expr("exp", (4,), [], [("x", (3 * big + 1,), [[big]])]))) == -4  # int32 range
+
+
+def test_null_and_misuse_at_the_abi():
+    import ctypes
+    e = _expr("exp", (4, 4), [], [("x", (7,), [[1, 1]])])
+    ce, ca = B.pack_expr(e), B.pack_args(e)
+    h = ctypes.c_void_p()
+    assert B.lib.tad_plan_derive(None, ca, 1, 1, 0, ctypes.byref(h)) == -1
+    assert B.lib.tad_plan_derive(ctypes.byref(ce), None, 1, 1, 0, ctypes.byref(h)) == -1
+    assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, None) == -1
+    assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 7, 0, ctypes.byref(h)) == -1
+    ca[0].n_occ = 2
+    assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, ctypes.byref(h)) == -5
+    ca[0].n_occ = 1
+    ca[0].needs_grad = 0
+    assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, ctypes.byref(h)) == 0
+    info = B.TadPlanInfo()
+    assert B.lib.tad_plan_query(h, 0, 0, ctypes.byref(info)) == -1      # gradient was not planned
+    assert B.lib.tad_plan_query(h, 5, 0, ctypes.byref(info)) == -1
+    assert B.lib.tad_eval_forward(h, None, None, None, 0, None) == -1
+    assert B.lib.tad_eval_backward(h, None, None, None, None, None, 0, None) == -1
+    B.lib.tad_plan_free(h)
+    B.lib.tad_plan_free(None)
+    assert B.strerror(-4) == "integer overflow"
