@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: forward + gather-form backward of an element-wise
+defined tensor, reported as tensor elements per second and as a fraction of the HBM roofline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--others] [--no-cpu]
+
+One "step" is one pass of the whole path (tad_eval_forward + tad_eval_backward, every gradient)
+over one batch of seeded synthetic inputs that already live in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VALU_TFLOPS = 157.3       # published vector fp32 peak (packed); 256 CUs x 2.4 GHz x 256 flop/clk
+FP32_MFMA_TFLOPS = 157.3
+
+
+def workload(name):
+    from paper_1711_01348_amd import workloads as wl
+    table = {
+        "cfg1": wl.config1, "cfg2_1": lambda: wl.config2(1), "cfg2_2": lambda: wl.config2(2),
+        "cfg2_3": lambda: wl.config2(3), "cfg3": wl.config3, "cfg4": wl.config4, "cfg5": wl.config5,
+    }
+    return table[name]()
+
+
+def accounting(name, w):
+    """Compulsory traffic of one forward+backward step: (tensor elements, bytes), and the dominant kernel
+    with its algorithmic bytes per launch."""
+    import numpy as np
+    e = w.expr
+    nf = int(np.prod(e.f_shape))
+    small = sum(int(np.prod(a.shape)) for a in e.args)
+    es = 4 if e.dtype == "f32" else 8
+    if name in ("cfg3", "cfg4", "cfg1"):
+        I = e.f_shape[0]
+        cdense = int(np.prod(e.args[2].shape))
+        small_rw = 2 * (small - cdense) + I          # a, b, d read; da, db, dd written; diagonal of c read
+        elems = nf + nf + nf + cdense + small_rw      # write f; read df; read f; write dense dc
+        dom = ("k_worked_backward", (2 * nf + cdense) * es)
+    elif name == "cfg2_1":
+        elems = nf + nf + 2 * small                   # write f; read df; x read, dx written
+        dom = ("k_rowreduce_backward", nf * es)
+    elif name == "cfg2_2":
+        elems = small + 3 * nf                        # write dense dx; diagonal read, f written, df read
+        dom = ("k_diagonal_backward", small * es)
+    elif name == "cfg2_3":
+        elems = nf + nf + 2 * small
+        dom = ("k_antidiag_backward", nf * es)
+    elif name == "cfg5":
+        nx = int(np.prod(e.args[0].shape))
+        elems = nx + nf + 2 * nf + nx + nx + 18       # fwd: read x, write f; bwd: read df, f; write dx; read x (dw)
+        dom = ("k_strided_backward", (2 * nf + 2 * nx) * es)
+    else:
+        raise ValueError(name)
+    return elems, elems * es, dom
+
+
+def run_gpu(name, steps, warmup, profile_kernel=True):
+    import torch
+    from paper_1711_01348_amd import binding as B
+    import ctypes
+    w = workload(name)
+    plan = B.Plan(w.expr)
+    dev = torch.device("cuda:0")
+    args = [torch.from_numpy(a).to(dev) for a in w.arg_list()]
+    df = torch.from_numpy(w.df).to(dev)
+    f = torch.empty(tuple(w.expr.f_shape), dtype=df.dtype, device=dev)
+    grads = [torch.empty_like(a) for a in args]
+    ws = plan.workspace(dev)
+    elems, nbytes, (dom_kernel, dom_bytes) = accounting(name, w)
+
+    def step():
+        plan.forward(args, out=f, ws=ws)
+        plan.backward(args, f, df, out=grads, ws=ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    families = {"forward": plan.forward_family, "backward": [plan.query(p)["family"] for p in range(len(args))]}
+    if profile_kernel:
+        B._check(B.lib.tad_profile_begin(dom_kernel.encode()), "tad_profile_begin")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_n = None, 0
+    if profile_kernel:
+        ms, n = ctypes.c_double(0), ctypes.c_int(0)
+        B._check(B.lib.tad_profile_end(ctypes.byref(ms), ctypes.byref(n)), "tad_profile_end")
+        dom_ms, dom_n = (ms.value / n.value if n.value else None), n.value
+    # separate forward / backward split (outside the timed region) with stream events
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record()
+    plan.forward(args, out=f, ws=ws)
+    ev[1].record()
+    plan.backward(args, f, df, out=grads, ws=ws)
+    ev[2].record()
+    torch.cuda.synchronize()
+    ms_step = (t1 - t0) * 1e3 / steps
+    return dict(workload=w.name, ms_per_step=ms_step, elements=elems, bytes=nbytes,
+                elements_per_s=elems / (ms_step * 1e-3), algorithmic_gbs=nbytes / (ms_step * 1e-3) / 1e9,
+                ms_forward=ev[0].elapsed_time(ev[1]), ms_backward=ev[1].elapsed_time(ev[2]),
+                dominant_kernel=dom_kernel, dominant_ms=dom_ms, dominant_launches=dom_n,
+                dominant_bytes=dom_bytes, families=families, dtype=w.expr.dtype)
+
+
+def run_cpu_oracle(name):
+    """The fp64 oracle as it stands, on the host cores, on the same workload (whole cfg3 fits in ~10-30 s)."""
+    import oracle
+    w = workload(name)
+    nthreads = min(oracle.max_threads(), 16)
+    t0 = time.perf_counter()
+    oracle.forward(w.expr, w.arg_list())
+    oracle.backward(w.expr, w.arg_list(), w.df, nthreads=nthreads)
+    t = time.perf_counter() - t0
+    elems, _, _ = accounting(name, w)
+    return dict(value=elems / t, unit="elements/s", cores=nthreads, kind="oracle",
+                sample=f"whole workload {w.name}: forward + brute-force scatter backward, fp64, {t:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--others", action="store_true", help="also time the other configurations (extra keys)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    r = run_gpu(a.workload, a.steps, a.warmup)
+    dom_s = (r["dominant_ms"] or float("nan")) * 1e-3
+    achieved = r["dominant_bytes"] / dom_s / 1e9 if r["dominant_ms"] else None
+    out = {
+        "metric": "fwd+bwd tensor elements/s; achieved HBM GB/s or FLOP/s vs MI355X peak",
+        "value": r["elements_per_s"], "unit": "elements/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": r["dtype"], "data": "synthetic",
+        "config": {"workload": r["workload"], "families": r["families"],
+                   "elements_per_step": r["elements"], "algorithmic_bytes_per_step": r["bytes"],
+                   "ms_forward": r["ms_forward"], "ms_backward": r["ms_backward"],
+                   "step_algorithmic_GBs": r["algorithmic_gbs"],
+                   "step_frac_of_hbm_peak": r["algorithmic_gbs"] / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": r["dominant_kernel"], "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
+                     "avg_kernel_ms": r["dominant_ms"], "launches": r["dominant_launches"],
+                     "algorithmic_bytes_per_launch": r["dominant_bytes"]},
+    }
+    if a.others:
+        per = {}
+        for name in ("cfg2_1", "cfg2_2", "cfg2_3", "cfg4", "cfg5"):
+            try:
+                q = run_gpu(name, a.steps, a.warmup, profile_kernel=False)
+                per[name] = {k: q[k] for k in ("workload", "ms_per_step", "ms_forward", "ms_backward",
+                                               "elements_per_s", "algorithmic_gbs", "families")}
+                per[name]["frac_of_hbm_peak"] = q["algorithmic_gbs"] / HBM_PEAK_GBS
+            except Exception as ex:  # report, never hide
+                per[name] = {"error": repr(ex)}
+        out["per_config"] = per
+    if not a.no_cpu:
+        out["cpu_baseline"] = run_cpu_oracle(a.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -205,6 +205,16 @@ int tad_smith_normal_form(const int64_t *A, int n, int m, int64_t *S, int64_t *U
 int tad_lattice_enumerate(const int64_t *A, int n, int m, const int64_t *lo, const int64_t *hi,
                           const int64_t *beta, int64_t *x_out, size_t cap, size_t *count);
 
+/*
+ * Instrumentation: time one kernel of the library with HIP events.  After tad_profile_begin(name) every
+ * launch of the kernel called `name` (up to 4096 launches) is bracketed by two events recorded on the
+ * stream it is launched on; tad_profile_end waits for them, returns the summed duration in milliseconds
+ * and the number of launches, and switches the instrumentation off.  Not thread safe against concurrent
+ * evaluation calls from other threads while armed.
+ */
+int tad_profile_begin(const char *kernel_name);
+int tad_profile_end(double *total_ms, int *launches);
+
 const char *tad_strerror(int status);
 
 #ifdef __cplusplus

@@ -304,3 +304,8 @@ def lattice_enumerate(A, lo, hi, beta) -> np.ndarray:
                                          beta.ctypes.data, out.ctypes.data, cnt.value, ctypes.byref(cnt)),
                "tad_lattice_enumerate")
     return out
+
+
+lib.tad_profile_begin.argtypes = [ctypes.c_char_p]
+lib.tad_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+EXPORTS += ["tad_profile_begin", "tad_profile_end"]

@@ -16,6 +16,7 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (plan->fwd_family) {
     case TAD_FAMILY_GENERIC: return generic_forward(*plan, args_dev, f_dev, s);
+    case TAD_FAMILY_WORKED: return worked_forward(*plan, args_dev, f_dev, s);
     default: return TAD_EUNSUPPORTED;
     }
 }
@@ -29,8 +30,18 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
     }
     if (plan->ws_bytes && (!ws_dev || ws_bytes < plan->ws_bytes)) return TAD_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc = generic_backward(*plan, args_dev, f_dev, df_dev, dx_dev, s);
-    return rc;
+    bool any_wanted = false;
+    for (size_t p = 0; p < plan->args.size(); ++p) any_wanted |= dx_dev[p] != nullptr;
+    if (!any_wanted) return TAD_OK;
+    // a specialised family owns all gradients of its expression; anything left is generic
+    int fam = TAD_FAMILY_GENERIC;
+    for (size_t p = 0; p < plan->args.size(); ++p)
+        if (plan->ap[p].derived && plan->ap[p].family != TAD_FAMILY_GENERIC) fam = plan->ap[p].family;
+    switch (fam) {
+    case TAD_FAMILY_GENERIC: return generic_backward(*plan, args_dev, f_dev, df_dev, dx_dev, s);
+    case TAD_FAMILY_WORKED: return worked_backward(*plan, args_dev, f_dev, df_dev, dx_dev, ws_dev, s);
+    default: return TAD_EUNSUPPORTED;
+    }
 }
 
 }  // extern "C"

@@ -1,15 +1,72 @@
 // Pattern recognition: which kernel family evaluates the forward pass and each gradient.
 // Every plan can run on the plan-driven generic kernels; a specialised family is chosen only
-// when body, index matrices and dtype match its template exactly.
+// when body, index matrices, shapes and dtype match its template exactly, and the derived plan
+// has the structure the family's kernels assume (which kernel coordinate collapses, which is a window).
 #include "plan.hpp"
+#include "worked_geom.h"
 
 namespace tad {
+
+static bool index_is(const tad_arg &a, int n_ext, std::initializer_list<std::initializer_list<int64_t>> m) {
+    if ((size_t)a.rank != m.size()) return false;
+    int r = 0;
+    for (const auto &row : m) {
+        if ((int)row.size() != n_ext) return false;
+        int d = 0;
+        for (int64_t v : row)
+            if (a.index[r][d++] != v) return false;
+        ++r;
+    }
+    return true;
+}
+
+static bool all_derived(const tad_plan &pl) {
+    for (const auto &ap : pl.ap)
+        if (!ap.derived) return false;
+    return true;
+}
+
+// f_ij = exp(-sum_k((a_ik + b_jk)^2 c_ii + d_{i+k}^3)), extended index (i, j, k)
+static bool match_worked(tad_plan &pl) {
+    const tad_expr &e = pl.expr;
+    if (e.body != TAD_BODY_WORKED || pl.dtype != TAD_F32 || e.n_f != 2 || e.n_sum != 1) return false;
+    if (e.sum_lo[0] != 0 || !all_derived(pl)) return false;
+    const int64_t I = e.f_shape[0], J = e.f_shape[1], K = e.sum_hi[0] + 1;
+    const tad_arg &a = pl.args[0], &b = pl.args[1], &c = pl.args[2], &d = pl.args[3];
+    if (!index_is(a, 3, {{1, 0, 0}, {0, 0, 1}}) || a.shape[0] != I || a.shape[1] != K) return false;
+    if (!index_is(b, 3, {{0, 1, 0}, {0, 0, 1}}) || b.shape[0] != J || b.shape[1] != K) return false;
+    if (!index_is(c, 3, {{1, 0, 0}, {1, 0, 0}})) return false;
+    if (!index_is(d, 3, {{1, 0, 1}})) return false;
+    if (J % 4 != 0) return false;   // rows of f must start 16-byte aligned for the vector loads and stores
+    // plan of d: one kernel coordinate must be the collapsed j, the other the clipped window moving i
+    const ArgPlan &pd = pl.ap[3];
+    if (pd.smith.R != 1 || pd.K.cols != 2 || pd.VR(1, 0) != 0) return false;
+    int lvl_j = -1, lvl_w = -1;
+    for (int m = 0; m < 2; ++m) {
+        if (pd.K(0, m) == 0 && pd.K(1, m) == 1 && pd.K(2, m) == 0) lvl_j = m;
+        else if (pd.K(1, m) == 0 && pd.K(0, m) != 0) lvl_w = m;
+    }
+    if (lvl_j < 0 || lvl_w < 0) return false;
+    pl.fast.I = I; pl.fast.J = J; pl.fast.K = K;
+    pl.fast.c_ld = c.shape[1];
+    pl.fast.dd_level = lvl_w;
+    pl.fast.dd_iy = (int)pd.VR(0, 0);
+    pl.fast.dd_iz = (int)pd.K(0, lvl_w);
+    if (K <= kWorkedMaxK) {
+        pl.fwd_family = TAD_FAMILY_WORKED;
+        for (auto &ap : pl.ap) ap.family = TAD_FAMILY_WORKED;
+        pl.ws_bytes = worked_workspace_bytes(I, J, K);
+        return true;
+    }
+    return false;
+}
 
 void select_families(tad_plan &plan) {
     plan.fwd_family = TAD_FAMILY_GENERIC;
     for (auto &ap : plan.ap) ap.family = TAD_FAMILY_GENERIC;
     plan.ws_bytes = 0;
     if (plan.flags & TAD_PLAN_GENERIC_ONLY) return;
+    if (match_worked(plan)) return;
 }
 
 }  // namespace tad

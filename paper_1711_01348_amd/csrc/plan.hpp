@@ -26,6 +26,8 @@ struct FastParams {
     int64_t I = 0, J = 0, K = 0;     // worked expression / 2-D patterns
     int64_t N = 0, U = 0, V = 0, stride = 0, P = 0, Q = 0;  // strided stencil
     int64_t c_ld = 0;                // row length of c (diagonal gather stride is c_ld + 1)
+    // gradient of d: which kernel coordinate is the clipped window, and i = dd_iy * y_0 + dd_iz * z_window
+    int dd_level = 0, dd_iy = 0, dd_iz = 0;
 };
 
 }  // namespace tad

@@ -169,7 +169,7 @@ def config2(which: int, scale: str = "full") -> Workload:
 
 def config3(scale: str = "full") -> Workload:
     """Worked expression at scale, fp32, K=5 (memory bound)."""
-    I, J = (8192, 8192) if scale == "full" else (333, 1301)
+    I, J = (8192, 8192) if scale == "full" else (333, 1300)
     return _worked_workload(f"cfg3_worked_{I}x{J}x5_f32", SEED_BASE + 3, I, J, 5, "f32", 0.2, 0.5)
 
 

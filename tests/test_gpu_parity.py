@@ -81,6 +81,8 @@ ASSORTED = [
     lambda: _expr("exp", (6,), [(0, 3), (0, 2)], [("x", (30,), [[3, 2, 4]])]),
     lambda: wl.worked_expr(4, 3, 5, "f64", d_len=11, c_shape=(6, 5)),
     lambda: wl.worked_expr(3, 4, 5, "f64", d_len=8),
+    lambda: wl.worked_expr(70, 1301, 5, "f32"),          # row length not a multiple of 4: generic kernels
+    lambda: wl.worked_expr(130, 520, 3, "f32", d_len=140, c_shape=(133, 131)),
     lambda: wl.strided_tanh_expr(2, 5, 4, 2, 3, 3, "f64"),
 ]
 
