@@ -46,7 +46,7 @@ def accounting(name, w):
         cdense = int(np.prod(e.args[2].shape))
         small_rw = 2 * (small - cdense) + I          # a, b, d read; da, db, dd written; diagonal of c read
         elems = nf + nf + nf + cdense + small_rw      # write f; read df; read f; write dense dc
-        dom = ("k_worked_backward", (2 * nf + cdense) * es)
+        dom = ("k_worked_backward", 2 * nf * es)
     elif name == "cfg2_1":
         elems = nf + nf + 2 * small                   # write f; read df; x read, dx written
         dom = ("k_rowreduce_backward", nf * es)

@@ -14,6 +14,8 @@
 // order, so results are deterministic and need no atomics.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "launch.h"
 #include "plan_dev.h"
 #include "profile.h"
@@ -89,187 +91,273 @@ __global__ __launch_bounds__(256) void k_worked_forward(const float *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// backward main pass: block = 4 waves over the same 256 columns, BWD_TI rows (each wave a quarter)
+// backward main pass.  Block = 4 waves over the same BWD_TJ = 512 columns (lane owns columns
+// 4*lane..4*lane+3 and 256+4*lane..+3), each wave a quarter of the block's BWD_TI rows, four rows per
+// step.  Column sums stay in registers for the whole tile; row sums are reduced across the wave with
+// DPP adds and written once per (row, column tile).
 // ---------------------------------------------------------------------------------------------
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, ROW_MASK == 0xf);
+    return v + __int_as_float(t);
+}
+
+// sum over the 64 lanes; the total is valid in lane 63
+__device__ __forceinline__ float wave_sum_lane63(float v) {
+    v = dpp_add<0x111, 0xf>(v);   // row_shr:1
+    v = dpp_add<0x112, 0xf>(v);   // row_shr:2
+    v = dpp_add<0x114, 0xf>(v);   // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);   // row_shr:8  -> lane 15 of every row of 16 holds the row total
+    v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+constexpr int BWD_RB = 4;   // rows per step
 
 template <int K>
 __global__ __launch_bounds__(256) void k_worked_backward(const float *__restrict__ a, const float *__restrict__ b,
                                                          const float *__restrict__ c, const float *__restrict__ f,
-                                                         const float *__restrict__ df, float *__restrict__ dc,
-                                                         long long dc_count, float *__restrict__ rowp,
+                                                         const float *__restrict__ df, float *__restrict__ rowp,
                                                          float *__restrict__ colp, int I, int J, int c_ld) {
-    constexpr int RW = K + 1;      // a_i0..a_i{K-1}, c_ii
+    constexpr int RW = K + 1;      // c_ii a_i0..c_ii a_i{K-1}, c_ii
     constexpr int RP = K + 2;      // row partials: r, P_0..P_{K-1}, Q
     constexpr int CP = K + 1;      // column partials: t, T_0..T_{K-1}
+    constexpr int WR = BWD_TI / 4; // rows per wave
     __shared__ float rd[BWD_TI][RW];
+    __shared__ float rows_out[RP][BWD_TI];
     __shared__ float cred[4][CP][BWD_TJ];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i0 = blockIdx.y * BWD_TI;
-    const int j0 = blockIdx.x * BWD_TJ + lane * 4;
-    const int nblk = gridDim.x * gridDim.y, blk = blockIdx.y * gridDim.x + blockIdx.x;
-
-    // this block's share of the dense zero fill of dc (its diagonal is written by the finishing kernel)
-    if (dc) {
-        long long n4 = dc_count >> 2;
-        long long per = (n4 + nblk - 1) / nblk;
-        long long lo = (long long)blk * per, hi = lo + per < n4 ? lo + per : n4;
-        float4v z = {0.f, 0.f, 0.f, 0.f};
-        for (long long q = lo + tid; q < hi; q += 256) reinterpret_cast<float4v *>(dc)[q] = z;
-        if (blk == 0 && tid < (int)(dc_count & 3)) dc[(n4 << 2) + tid] = 0.f;
-    }
+    const int jb = blockIdx.x * BWD_TJ;
 
     for (int t = tid; t < BWD_TI; t += 256) {
-        int i = i0 + t;
-        if (i < I) {
+        const int i = i0 + t;
+        float ci = 0.f;
+        if (i < I) ci = c[(size_t)i * c_ld + i];
 #pragma unroll
-            for (int k = 0; k < K; ++k) rd[t][k] = a[(size_t)i * K + k];
-            rd[t][K] = c[(size_t)i * c_ld + i];
-        }
+        for (int k = 0; k < K; ++k) rd[t][k] = i < I ? ci * a[(size_t)i * K + k] : 0.f;
+        rd[t][K] = ci;
     }
     __syncthreads();
 
-    const bool live = j0 < J;
-    float bj[4][K], nb[4];
+    int jc[2];
+    bool live[2];
+    float bj[2][4][K], nb[2][4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        nb[v] = 0.f;
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            bj[v][k] = live ? b[(size_t)(j0 + v) * K + k] : 0.f;
-            nb[v] = fmaf(bj[v][k], bj[v][k], nb[v]);
-        }
-    }
-    float tc[4] = {0.f, 0.f, 0.f, 0.f}, Tc[4][K];
-#pragma unroll
-    for (int v = 0; v < 4; ++v)
-#pragma unroll
-        for (int k = 0; k < K; ++k) Tc[v][k] = 0.f;
-
-    constexpr int WR = BWD_TI / 4;
-    const int r0 = wave * WR;
-    const int rows = max(0, min(WR, I - (i0 + r0)));
-    const float *fp = f + (size_t)(i0 + r0) * J + j0;
-    const float *gp = df + (size_t)(i0 + r0) * J + j0;
-    float *rp = rowp + ((size_t)blockIdx.x * I + (i0 + r0)) * RP;
-    for (int r = 0; r < rows; ++r) {
-        float4v fv = {0.f, 0.f, 0.f, 0.f}, dv = fv;
-        if (live) {
-            fv = *reinterpret_cast<const float4v *>(fp);
-            dv = *reinterpret_cast<const float4v *>(gp);
-        }
-        fp += J;
-        gp += J;
-        float ai[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) ai[k] = rd[r0 + r][k];
-        const float ci = rd[r0 + r][K];
-        float part[RP];
-#pragma unroll
-        for (int q = 0; q < RP; ++q) part[q] = 0.f;
+    for (int h = 0; h < 2; ++h) {
+        jc[h] = jb + h * 256 + lane * 4;
+        live[h] = jc[h] < J;
+        const float *bp = b + (size_t)(live[h] ? jc[h] : 0) * K;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float g = dv[v] * fv[v];
-            part[0] += g;
+            nb[h][v] = 0.f;
 #pragma unroll
-            for (int k = 0; k < K; ++k) part[1 + k] = fmaf(g, bj[v][k], part[1 + k]);
-            part[K + 1] = fmaf(g, nb[v], part[K + 1]);
-            float h = ci * g;
-            tc[v] += h;
-#pragma unroll
-            for (int k = 0; k < K; ++k) Tc[v][k] = fmaf(h, ai[k], Tc[v][k]);
+            for (int k = 0; k < K; ++k) {
+                const float bv = bp[v * K + k];     // J % 4 == 0: a live lane owns four existing columns
+                bj[h][v][k] = live[h] ? bv : 0.f;
+                nb[h][v] = fmaf(bj[h][v][k], bj[h][v][k], nb[h][v]);
+            }
         }
+    }
+    float tc[2][4], Tc[2][4][K];
 #pragma unroll
-        for (int q = 0; q < RP; ++q) part[q] = wave_sum(part[q]);
-        if (lane == 0) {
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int q = 0; q < RP; ++q) rp[q] = part[q];
+        for (int v = 0; v < 4; ++v) {
+            tc[h][v] = 0.f;
+#pragma unroll
+            for (int k = 0; k < K; ++k) Tc[h][v][k] = 0.f;
         }
-        rp += RP;
+
+    const int r0 = wave * WR;
+    const int rows = max(0, min(WR, I - (i0 + r0)));
+    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < WR; rb += BWD_RB) {
+        float part[BWD_RB][RP];
+#pragma unroll
+        for (int r = 0; r < BWD_RB; ++r)
+#pragma unroll
+            for (int q = 0; q < RP; ++q) part[r][q] = 0.f;
+        if (rb < rows) {
+            float4v fv[BWD_RB][2], dv[BWD_RB][2];
+#pragma unroll
+            for (int r = 0; r < BWD_RB; ++r)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const bool ok = live[h] && (rb + r) < rows;
+                    const size_t off = (size_t)(i0 + r0 + rb + r) * J + jc[h];
+                    fv[r][h] = ok ? *reinterpret_cast<const float4v *>(f + off) : zero4;
+                    dv[r][h] = ok ? *reinterpret_cast<const float4v *>(df + off) : zero4;
+                }
+#pragma unroll
+            for (int r = 0; r < BWD_RB; ++r) {
+                float ai[K];
+#pragma unroll
+                for (int k = 0; k < K; ++k) ai[k] = rd[r0 + rb + r][k];
+                const float ci = rd[r0 + rb + r][K];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float g = dv[r][h][v] * fv[r][h][v];
+                        part[r][0] += g;
+#pragma unroll
+                        for (int k = 0; k < K; ++k) part[r][1 + k] = fmaf(g, bj[h][v][k], part[r][1 + k]);
+                        part[r][K + 1] = fmaf(g, nb[h][v], part[r][K + 1]);
+                        tc[h][v] = fmaf(g, ci, tc[h][v]);
+#pragma unroll
+                        for (int k = 0; k < K; ++k) Tc[h][v][k] = fmaf(g, ai[k], Tc[h][v][k]);
+                    }
+            }
+#pragma unroll
+            for (int r = 0; r < BWD_RB; ++r)
+#pragma unroll
+                for (int q = 0; q < RP; ++q) part[r][q] = wave_sum_lane63(part[r][q]);
+        }
+        if (lane == 63) {
+#pragma unroll
+            for (int r = 0; r < BWD_RB; ++r)
+#pragma unroll
+                for (int q = 0; q < RP; ++q) rows_out[q][r0 + rb + r] = part[r][q];
+        }
     }
 
-    // column partials: add the four waves in fixed order, one thread per column
+    // column partials: add the four waves in fixed order, one thread per column (two columns per thread)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        cred[wave][0][lane * 4 + v] = tc[v];
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int k = 0; k < K; ++k) cred[wave][1 + k][lane * 4 + v] = Tc[v][k];
-    }
+        for (int v = 0; v < 4; ++v) {
+            cred[wave][0][h * 256 + lane * 4 + v] = tc[h][v];
+#pragma unroll
+            for (int k = 0; k < K; ++k) cred[wave][1 + k][h * 256 + lane * 4 + v] = Tc[h][v][k];
+        }
     __syncthreads();
-    const int j = blockIdx.x * BWD_TJ + tid;
-    if (j < J) {
 #pragma unroll
-        for (int q = 0; q < CP; ++q) {
-            float s = (cred[0][q][tid] + cred[1][q][tid]) + (cred[2][q][tid] + cred[3][q][tid]);
-            colp[((size_t)blockIdx.y * CP + q) * J + j] = s;
+    for (int h = 0; h < 2; ++h) {
+        const int col = h * 256 + tid, j = jb + col;
+        if (j < J) {
+#pragma unroll
+            for (int q = 0; q < CP; ++q) {
+                float s = (cred[0][q][col] + cred[1][q][col]) + (cred[2][q][col] + cred[3][q][col]);
+                colp[((size_t)blockIdx.y * CP + q) * J + j] = s;
+            }
+        }
+    }
+    // row partials of the tile, rowp[jt][q][i], contiguous in i
+    for (int t = tid; t < BWD_TI; t += 256) {
+        const int i = i0 + t;
+        if (i < I) {
+#pragma unroll
+            for (int q = 0; q < RP; ++q) rowp[((size_t)blockIdx.x * RP + q) * I + i] = rows_out[q][t];
         }
     }
 }
 
-// rows: da, dc diagonal, r_i
-template <int K>
-__global__ __launch_bounds__(256) void k_worked_finish_rows(const float *__restrict__ a, const float *__restrict__ c,
-                                                            const float *__restrict__ rowp, int n_jt,
-                                                            float *__restrict__ da, float *__restrict__ dc,
-                                                            float *__restrict__ rsum, int I, int c_ld) {
-    constexpr int RP = K + 2;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= I) return;
-    double acc[RP];
-#pragma unroll
-    for (int q = 0; q < RP; ++q) acc[q] = 0.0;
-    for (int jt = 0; jt < n_jt; ++jt) {
-        const float *p = rowp + ((size_t)jt * I + i) * RP;
-#pragma unroll
-        for (int q = 0; q < RP; ++q) acc[q] += (double)p[q];
-    }
-    const double ci = (double)c[(size_t)i * c_ld + i];
-    double na = 0.0, cross = 0.0;
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        double ak = (double)a[(size_t)i * K + k];
-        na += ak * ak;
-        cross += ak * acc[1 + k];
-        if (da) da[(size_t)i * K + k] = (float)(-2.0 * ci * (ak * acc[0] + acc[1 + k]));
-    }
-    if (dc) dc[(size_t)i * c_ld + i] = (float)(-(na * acc[0] + 2.0 * cross + acc[K + 1]));
-    rsum[i] = (float)acc[0];
+// Dense zero fill of a gradient whose non-zero elements are written afterwards (cokernel mask: only the
+// diagonal of dc is non-zero).  A pure write stream runs faster than the same stores mixed into a read pass.
+__global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, long long n) {
+    const long long n4 = n >> 2;
+    const float4v z = {0.f, 0.f, 0.f, 0.f};
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < n4; q += stride)
+        reinterpret_cast<float4v *>(p)[q] = z;
+    if (blockIdx.x == 0 && threadIdx.x < (int)(n & 3)) p[(n4 << 2) + threadIdx.x] = 0.f;
 }
 
-// columns: db
+// Finishing pass, one launch with three block roles, 64 outputs per block; the four waves of a block split
+// the tile partials (wave w takes tiles w, w+4, ...) and are combined in fixed order through LDS.
+//   rows:  da, diagonal of dc               (sum of the row partials over the column tiles)
+//   cols:  db                               (sum of the column partials over the row tiles)
+//   dd:    dd_m = -3 d_m^2 * sum over the window coordinate of r_i; masks and the window come from the
+//          plan of d: kernel coordinate `lvl_win` is the window, the other one (j) is already summed.
 template <int K>
-__global__ __launch_bounds__(256) void k_worked_finish_cols(const float *__restrict__ b,
-                                                            const float *__restrict__ colp, int n_it,
-                                                            float *__restrict__ db, int J) {
-    constexpr int CP = K + 1;
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= J) return;
-    double acc[CP];
+__global__ __launch_bounds__(256) void k_worked_finish(const GatherPlan Pd, int lvl_win, int iy, int iz,
+                                                       const float *__restrict__ a, const float *__restrict__ b,
+                                                       const float *__restrict__ c, const float *__restrict__ d,
+                                                       const float *__restrict__ rowp, int n_jt,
+                                                       const float *__restrict__ colp, int n_it,
+                                                       float *__restrict__ da, float *__restrict__ db,
+                                                       float *__restrict__ dc, float *__restrict__ dd, int I,
+                                                       int J, int c_ld, int n_d, int blocks_rows, int blocks_cols) {
+    constexpr int RP = K + 2, CP = K + 1;
+    __shared__ double red[4][RP][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int blk = blockIdx.x;
+    if (blk < blocks_rows) {
+        const int i = blk * 64 + lane;
+        double acc[RP];
 #pragma unroll
-    for (int q = 0; q < CP; ++q) acc[q] = 0.0;
-    for (int it = 0; it < n_it; ++it)
+        for (int q = 0; q < RP; ++q) acc[q] = 0.0;
+        if (i < I)
+            for (int jt = wave; jt < n_jt; jt += 4)
 #pragma unroll
-        for (int q = 0; q < CP; ++q) acc[q] += (double)colp[((size_t)it * CP + q) * J + j];
+                for (int q = 0; q < RP; ++q) acc[q] += (double)rowp[((size_t)jt * RP + q) * I + i];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        double bk = (double)b[(size_t)j * K + k];
-        db[(size_t)j * K + k] = (float)(-2.0 * (acc[1 + k] + bk * acc[0]));
+        for (int q = 0; q < RP; ++q) red[wave][q][lane] = acc[q];
+        __syncthreads();
+        if (wave != 0 || i >= I) return;
+#pragma unroll
+        for (int q = 0; q < RP; ++q) acc[q] = (red[0][q][lane] + red[1][q][lane]) + (red[2][q][lane] + red[3][q][lane]);
+        const double ci = (double)c[(size_t)i * c_ld + i];
+        double na = 0.0, cross = 0.0;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            double ak = (double)a[(size_t)i * K + k];
+            na += ak * ak;
+            cross += ak * acc[1 + k];
+            if (da) da[(size_t)i * K + k] = (float)(-2.0 * ci * (ak * acc[0] + acc[1 + k]));
+        }
+        if (dc) dc[(size_t)i * c_ld + i] = (float)(-(na * acc[0] + 2.0 * cross + acc[K + 1]));
+        return;
     }
-}
-
-// dd_m = -3 d_m^2 * sum over the window coordinate of r_i.  Masks and the window come from the plan of d:
-// kernel coordinate `lvl_win` is the window, the other coordinate (the collapsed j) is already summed in r.
-__global__ __launch_bounds__(256) void k_worked_dd(const GatherPlan P, int lvl_win, int iy, int iz,
-                                                   const float *__restrict__ d, const float *__restrict__ rsum,
-                                                   float *__restrict__ dd, int n) {
-    const int m = blockIdx.x * blockDim.x + threadIdx.x;
-    if (m >= n) return;
-    int32_t beta[kMaxRank] = {m, 0, 0, 0}, y[kMaxRank] = {0, 0, 0, 0}, z[kMaxKernel] = {0, 0, 0, 0};
+    blk -= blocks_rows;
+    if (blk < blocks_cols) {
+        const int j = blk * 64 + lane;
+        double acc[CP];
+#pragma unroll
+        for (int q = 0; q < CP; ++q) acc[q] = 0.0;
+        if (j < J && db)
+            for (int it = wave; it < n_it; it += 4)
+#pragma unroll
+                for (int q = 0; q < CP; ++q) acc[q] += (double)colp[((size_t)it * CP + q) * J + j];
+#pragma unroll
+        for (int q = 0; q < CP; ++q) red[wave][q][lane] = acc[q];
+        __syncthreads();
+        if (wave != 0 || j >= J || !db) return;
+#pragma unroll
+        for (int q = 0; q < CP; ++q) acc[q] = (red[0][q][lane] + red[1][q][lane]) + (red[2][q][lane] + red[3][q][lane]);
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            // the column partials carry c_ii a_ik and c_ii already:  db_jk = -2 (T_jk + b_jk t_j)
+            double bk = (double)b[(size_t)j * K + k];
+            db[(size_t)j * K + k] = (float)(-2.0 * (acc[1 + k] + bk * acc[0]));
+        }
+        return;
+    }
+    blk -= blocks_cols;
+    const int m = blk * 64 + lane;
+    double s = 0.0;
+    bool nonzero = false;
+    if (m < n_d && dd) {
+        int32_t beta[kMaxRank] = {m, 0, 0, 0}, y[kMaxRank] = {0, 0, 0, 0}, z[kMaxKernel] = {0, 0, 0, 0};
+        if (gather_prepare(Pd, beta, y)) {
+            nonzero = true;
+            int32_t lo, hi;
+            gather_bounds(Pd, lvl_win, y, z, lo, hi);
+            for (int32_t w = lo; w <= hi; ++w) {
+                const int i = iy * y[0] + iz * w;
+                for (int jt = wave; jt < n_jt; jt += 4) s += (double)rowp[((size_t)jt * RP) * I + i];
+            }
+        }
+    }
+    red[wave][0][lane] = s;
+    __syncthreads();
+    if (wave != 0 || m >= n_d || !dd) return;
     float out = 0.f;
-    if (gather_prepare(P, beta, y)) {
-        int32_t lo, hi;
-        gather_bounds(P, lvl_win, y, z, lo, hi);
-        double s = 0.0;
-        for (int32_t w = lo; w <= hi; ++w) s += (double)rsum[iy * y[0] + iz * w];
+    if (nonzero) {
+        s = (red[0][0][lane] + red[1][0][lane]) + (red[2][0][lane] + red[3][0][lane]);
         const double dm = (double)d[m];
         out = (float)(-3.0 * dm * dm * s);
     }
@@ -280,7 +368,7 @@ __global__ __launch_bounds__(256) void k_worked_dd(const GatherPlan P, int lvl_w
 // host side
 // ---------------------------------------------------------------------------------------------
 struct WorkedWs {
-    float *rowp, *colp, *rsum;
+    float *rowp, *colp;
     int n_jt, n_it;
 };
 
@@ -292,8 +380,6 @@ static WorkedWs carve(void *ws, int64_t I, int64_t J, int64_t K) {
     w.rowp = reinterpret_cast<float *>(p);
     p += align256((size_t)w.n_jt * I * (K + 2) * 4);
     w.colp = reinterpret_cast<float *>(p);
-    p += align256((size_t)w.n_it * (K + 1) * J * 4);
-    w.rsum = reinterpret_cast<float *>(p);
     return w;
 }
 
@@ -317,22 +403,21 @@ static int bwd_k(const tad_plan &pl, const void *const *args, const void *f, con
     float *dc = (float *)dx[2];
     dim3 grid(w.n_jt, w.n_it);
     TAD_LAUNCH("k_worked_backward", (k_worked_backward<K>), grid, dim3(256), 0, s, a, b, c, (const float *)f,
-               (const float *)df, dc, (long long)pl.arg_count[2], w.rowp, w.colp, I, J, c_ld);
+               (const float *)df, w.rowp, w.colp, I, J, c_ld);
     if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
-    if (dx[0] || dx[2] || dx[3]) {
-        TAD_LAUNCH("k_worked_finish_rows", (k_worked_finish_rows<K>), dim3((I + 255) / 256), dim3(256), 0, s, a, c,
-                   w.rowp, w.n_jt, (float *)dx[0], dc, w.rsum, I, c_ld);
+    if (dc) {
+        // after the read pass: a write burst right before it slows the reads down
+        const long long n = pl.arg_count[2];
+        const int g = (int)std::min<long long>(16384, (n / 4 + 255) / 256 + 1);
+        TAD_LAUNCH("k_fill_zero", k_fill_zero, dim3(g), dim3(256), 0, s, dc, n);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
-    if (dx[1]) {
-        TAD_LAUNCH("k_worked_finish_cols", (k_worked_finish_cols<K>), dim3((J + 255) / 256), dim3(256), 0, s, b,
-                   w.colp, w.n_it, (float *)dx[1], J);
-        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
-    }
-    if (dx[3]) {
-        const int n = (int)pl.arg_count[3];
-        TAD_LAUNCH("k_worked_dd", k_worked_dd, dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[3].dev,
-                   pl.fast.dd_level, pl.fast.dd_iy, pl.fast.dd_iz, d, w.rsum, (float *)dx[3], n);
+    {
+        const int n_d = (int)pl.arg_count[3];
+        const int br = (I + 63) / 64, bc = (J + 63) / 64, bd = (n_d + 63) / 64;
+        TAD_LAUNCH("k_worked_finish", (k_worked_finish<K>), dim3(br + bc + bd), dim3(256), 0, s, pl.ap[3].dev,
+                   pl.fast.dd_level, pl.fast.dd_iy, pl.fast.dd_iz, a, b, c, d, w.rowp, w.n_jt, w.colp, w.n_it,
+                   (float *)dx[0], (float *)dx[1], dc, (float *)dx[3], I, J, c_ld, n_d, br, bc);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

@@ -6,16 +6,16 @@
 namespace tad {
 
 constexpr int FWD_TI = 32;      // rows per forward block (1024 columns)
-constexpr int BWD_TI = 128;     // rows per backward block
-constexpr int BWD_TJ = 256;     // columns per backward block
+constexpr int BWD_TI = 256;     // rows per backward block
+constexpr int BWD_TJ = 512;     // columns per backward block
 constexpr int kWorkedMaxK = 8;  // longest summed index the direct (VALU) kernels are instantiated for
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// row partials [n_jt][I][K+2], column partials [n_it][K+1][J], row sums r[I]
+// row partials [n_jt][K+2][I], column partials [n_it][K+1][J]
 inline size_t worked_workspace_bytes(int64_t I, int64_t J, int64_t K) {
     size_t n_jt = (size_t)((J + BWD_TJ - 1) / BWD_TJ), n_it = (size_t)((I + BWD_TI - 1) / BWD_TI);
-    return align256(n_jt * I * (K + 2) * 4) + align256(n_it * (K + 1) * J * 4) + align256((size_t)I * 4);
+    return align256(n_jt * I * (K + 2) * 4) + align256(n_it * (K + 1) * J * 4);
 }
 
 }  // namespace tad
