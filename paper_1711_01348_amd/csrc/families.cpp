@@ -61,12 +61,50 @@ static bool match_worked(tad_plan &pl) {
     return false;
 }
 
+static bool unary_body(int body) {
+    return body == TAD_BODY_SQ || body == TAD_BODY_CUBE || body == TAD_BODY_SIN || body == TAD_BODY_EXP;
+}
+
+// the three one-argument patterns of the introduction: f_ij = phi(x_i), f_i = phi(x_ii), f_ij = phi(x_{i+j})
+static bool match_patterns(tad_plan &pl) {
+    const tad_expr &e = pl.expr;
+    if (!unary_body(e.body) || pl.dtype != TAD_F32 || e.n_sum != 0 || !all_derived(pl)) return false;
+    const tad_arg &x = pl.args[0];
+    const ArgPlan &px = pl.ap[0];
+    int fam = TAD_FAMILY_GENERIC;
+    if (e.n_f == 2 && index_is(x, 2, {{1, 0}})) {
+        // kernel coordinate = j over its whole range, i = y_0
+        if (e.f_shape[1] % 4 != 0 || px.smith.R != 1 || px.K.cols != 1) return false;
+        if (px.VR(0, 0) != 1 || px.VR(1, 0) != 0 || px.K(0, 0) != 0 || px.K(1, 0) * px.K(1, 0) != 1) return false;
+        fam = TAD_FAMILY_ROW_REDUCE;
+    } else if (e.n_f == 1 && index_is(x, 1, {{1}, {1}})) {
+        if (x.shape[1] % 4 != 0 || px.smith.R != 1 || px.K.cols != 0 || px.VR(0, 0) != 1) return false;
+        pl.fast.c_ld = x.shape[1];
+        fam = TAD_FAMILY_DIAGONAL;
+    } else if (e.n_f == 2 && index_is(x, 2, {{1, 1}})) {
+        if (e.f_shape[1] % 4 != 0 || px.smith.R != 1 || px.K.cols != 1) return false;
+        if (px.K(0, 0) * px.K(0, 0) != 1 || px.K(1, 0) * px.K(1, 0) != 1) return false;
+        pl.fast.dd_iy = (int)px.VR(0, 0); pl.fast.dd_iz = (int)px.K(0, 0);
+        pl.fast.jy = (int)px.VR(1, 0); pl.fast.jz = (int)px.K(1, 0);
+        pl.ws_bytes = antidiag_workspace_bytes(e.f_shape[0], x.shape[0]);
+        fam = TAD_FAMILY_ANTIDIAGONAL;
+    } else {
+        return false;
+    }
+    pl.fast.I = e.f_shape[0];
+    pl.fast.J = e.n_f == 2 ? e.f_shape[1] : 1;
+    pl.fwd_family = fam;
+    pl.ap[0].family = fam;
+    return true;
+}
+
 void select_families(tad_plan &plan) {
     plan.fwd_family = TAD_FAMILY_GENERIC;
     for (auto &ap : plan.ap) ap.family = TAD_FAMILY_GENERIC;
     plan.ws_bytes = 0;
     if (plan.flags & TAD_PLAN_GENERIC_ONLY) return;
     if (match_worked(plan)) return;
+    if (match_patterns(plan)) return;
 }
 
 }  // namespace tad

@@ -18,4 +18,8 @@ int worked_forward(const tad_plan &pl, const void *const *args, void *f, hipStre
 int worked_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
                     void *const *dx, void *ws, hipStream_t s);
 
+int pattern_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
+int pattern_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
+                     hipStream_t s);
+
 }  // namespace tad

@@ -28,6 +28,7 @@ struct FastParams {
     int64_t c_ld = 0;                // row length of c (diagonal gather stride is c_ld + 1)
     // gradient of d: which kernel coordinate is the clipped window, and i = dd_iy * y_0 + dd_iz * z_window
     int dd_level = 0, dd_iy = 0, dd_iz = 0;
+    int jy = 0, jz = 0;              // antidiagonal pattern: j = jy * y_0 + jz * z
 };
 
 }  // namespace tad

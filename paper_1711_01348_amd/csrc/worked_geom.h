@@ -18,4 +18,9 @@ inline size_t worked_workspace_bytes(int64_t I, int64_t J, int64_t K) {
     return align256(n_jt * I * (K + 2) * 4) + align256(n_it * (K + 1) * J * 4);
 }
 
+constexpr int AD_BTI_ROWS = 64;   // rows per backward tile of the antidiagonal pattern
+inline size_t antidiag_workspace_bytes(int64_t I, int64_t n_x) {
+    return align256((size_t)((I + AD_BTI_ROWS - 1) / AD_BTI_ROWS) * (size_t)n_x * 4);
+}
+
 }  // namespace tad

@@ -145,19 +145,19 @@ def config2(which: int, scale: str = "full") -> Workload:
     rng = np.random.Generator(np.random.PCG64(SEED_BASE + 2 * 10 + which))
     dtype = "f32"
     if which == 1:
-        I, J = (4096, 4096) if scale == "full" else (203, 517)
+        I, J = (4096, 4096) if scale == "full" else (203, 516)
         expr = broadcast_sq_expr(I, J, dtype)
         x = _uniform(rng, -1, 1, (I,))
         df = _uniform(rng, -1, 1, (I, J))
         name = f"cfg2_1_broadcast_sq_{I}x{J}"
     elif which == 2:
-        I = 8192 if scale == "full" else 389
+        I = 8192 if scale == "full" else 388
         expr = diagonal_sq_expr(I, dtype)
         x = _uniform(rng, -1, 1, (I, I))
         df = _uniform(rng, -1, 1, (I,))
         name = f"cfg2_2_diagonal_sq_{I}"
     elif which == 3:
-        I, J = (4096, 4096) if scale == "full" else (301, 467)
+        I, J = (4096, 4096) if scale == "full" else (301, 468)
         expr = index_sum_exp_expr(I, J, dtype)
         x = _uniform(rng, -1, 1, (I + J - 1,))
         df = _uniform(rng, -1, 1, (I, J))

@@ -83,6 +83,12 @@ ASSORTED = [
     lambda: wl.worked_expr(3, 4, 5, "f64", d_len=8),
     lambda: wl.worked_expr(70, 1301, 5, "f32"),          # row length not a multiple of 4: generic kernels
     lambda: wl.worked_expr(130, 520, 3, "f32", d_len=140, c_shape=(133, 131)),
+    # pattern families with other bodies, arguments longer than the referenced range, ragged tiles
+    lambda: _expr("sin", (70, 1028), [], [("x", (75,), [[1, 0]])], "f32"),
+    lambda: _expr("cube", (259,), [], [("x", (263, 264), [[1], [1]])], "f32"),
+    lambda: _expr("sq", (130, 260), [], [("x", (400,), [[1, 1]])], "f32"),
+    lambda: _expr("exp", (65, 1032), [], [("x", (1096,), [[1, 1]])], "f32"),
+    lambda: _expr("exp", (33, 517), [], [("x", (33,), [[1, 0]])], "f32"),        # not a multiple of 4: generic
     lambda: wl.strided_tanh_expr(2, 5, 4, 2, 3, 3, "f64"),
 ]
 
