@@ -142,7 +142,7 @@ class Plan:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and lib is not None:   # lib is None while the interpreter shuts down
             lib.tad_plan_free(h)
 
     # ---- host introspection -------------------------------------------------------------------

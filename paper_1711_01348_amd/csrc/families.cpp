@@ -7,6 +7,53 @@
 
 namespace tad {
 
+bool flatten_level(const GatherPlan &g, int level, FlatLevel &out) {
+    if (level < 0 || level >= g.kappa || g.R > kFlatY) return false;
+    const int nl = g.lo_end[level] - g.lo_begin[level], nh = g.hi_end[level] - g.hi_begin[level];
+    if (nl > kFlatRows || nh > kFlatRows) return false;
+    for (int r = 0; r < kFlatRows; ++r) {
+        out.ls[r] = 1; out.lk0[r] = -(1 << 30);      // neutral lower row
+        out.hs[r] = 1; out.hk0[r] = (1 << 30) - 1;   // neutral upper row
+        for (int c = 0; c < kFlatY; ++c) out.lky[r][c] = out.hky[r][c] = 0;
+    }
+    for (int r = 0; r < nl + nh; ++r) {
+        const GRow &row = g.rows[(r < nl ? g.lo_begin[level] : g.hi_begin[level] - nl) + r];
+        for (int m = 0; m < kMaxKernel; ++m)
+            if (row.kz[m] != 0) return false;
+        if (r < nl) {
+            out.ls[r] = row.scale; out.lk0[r] = row.k0;
+            for (int c = 0; c < g.R; ++c) out.lky[r][c] = row.ky[c];
+        } else {
+            out.hs[r - nl] = row.scale; out.hk0[r - nl] = row.k0;
+            for (int c = 0; c < g.R; ++c) out.hky[r - nl][c] = row.ky[c];
+        }
+    }
+    return true;
+}
+
+bool flatten_feas(const GatherPlan &g, FlatFeas &out) {
+    if (g.nF > kFlatFeas || g.R > kFlatY) return false;
+    for (int r = 0; r < kFlatFeas; ++r) {
+        out.k0[r] = -1;                               // neutral: always satisfied
+        for (int c = 0; c < kFlatY; ++c) out.ky[r][c] = 0;
+    }
+    for (int r = 0; r < g.nF; ++r) {
+        out.k0[r] = g.feas[r].k0;
+        for (int c = 0; c < g.R; ++c) out.ky[r][c] = g.feas[r].ky[c];
+    }
+    return true;
+}
+
+bool y_is_beta(const GatherPlan &g) {
+    if (g.nC != 0 || g.R != g.rank) return false;
+    for (int r = 0; r < g.R; ++r) {
+        if (g.diag[r] != 1) return false;
+        for (int c = 0; c < g.rank; ++c)
+            if (g.U[r][c] != (r == c ? 1 : 0)) return false;
+    }
+    return true;
+}
+
 static bool index_is(const tad_arg &a, int n_ext, std::initializer_list<std::initializer_list<int64_t>> m) {
     if ((size_t)a.rank != m.size()) return false;
     int r = 0;
@@ -47,6 +94,8 @@ static bool match_worked(tad_plan &pl) {
         else if (pd.K(1, m) == 0 && pd.K(0, m) != 0) lvl_w = m;
     }
     if (lvl_j < 0 || lvl_w < 0) return false;
+    if (!y_is_beta(pd.dev) || !flatten_feas(pd.dev, pl.fast.feas) || !flatten_level(pd.dev, lvl_w, pl.fast.flat[0]))
+        return false;
     pl.fast.I = I; pl.fast.J = J; pl.fast.K = K;
     pl.fast.c_ld = c.shape[1];
     pl.fast.dd_level = lvl_w;
@@ -84,6 +133,8 @@ static bool match_patterns(tad_plan &pl) {
     } else if (e.n_f == 2 && index_is(x, 2, {{1, 1}})) {
         if (e.f_shape[1] % 4 != 0 || px.smith.R != 1 || px.K.cols != 1) return false;
         if (px.K(0, 0) * px.K(0, 0) != 1 || px.K(1, 0) * px.K(1, 0) != 1) return false;
+        if (!y_is_beta(px.dev) || !flatten_feas(px.dev, pl.fast.feas) || !flatten_level(px.dev, 0, pl.fast.flat[0]))
+            return false;
         pl.fast.dd_iy = (int)px.VR(0, 0); pl.fast.dd_iz = (int)px.K(0, 0);
         pl.fast.jy = (int)px.VR(1, 0); pl.fast.jz = (int)px.K(1, 0);
         pl.ws_bytes = antidiag_workspace_bytes(e.f_shape[0], x.shape[0]);
@@ -98,6 +149,34 @@ static bool match_patterns(tad_plan &pl) {
     return true;
 }
 
+// f_nij = tanh(sum_{u,v} x_{n, s i + u, s j + v} w_uv), extended index (n, i, j, u, v)
+static bool match_strided(tad_plan &pl) {
+    const tad_expr &e = pl.expr;
+    if (e.body != TAD_BODY_TANH_DOT || pl.dtype != TAD_F32 || e.n_f != 3 || e.n_sum != 2) return false;
+    if (e.sum_lo[0] != 0 || e.sum_lo[1] != 0 || !all_derived(pl)) return false;
+    const tad_arg &x = pl.args[0], &w = pl.args[1];
+    if (x.rank != 3 || w.rank != 2) return false;
+    const int64_t s = x.index[1][1];
+    if (s < 1) return false;
+    if (!index_is(x, 5, {{1, 0, 0, 0, 0}, {0, s, 0, 1, 0}, {0, 0, s, 0, 1}})) return false;
+    if (!index_is(w, 5, {{0, 0, 0, 1, 0}, {0, 0, 0, 0, 1}})) return false;
+    const int64_t U = e.sum_hi[0] + 1, V = e.sum_hi[1] + 1;
+    if (w.shape[0] != U || w.shape[1] != V || U * V > 49) return false;
+    // x: two kernel coordinates with plan-driven ranges; w: the three function indices collapse completely
+    const ArgPlan &px = pl.ap[0], &pw = pl.ap[1];
+    if (px.K.cols != 2 || pw.K.cols != 3 || px.smith.R != 3) return false;
+    // x: y = beta, and both ranges in the loop-free form (neither depends on the other kernel coordinate)
+    if (!y_is_beta(px.dev) || !flatten_feas(px.dev, pl.fast.feas)) return false;
+    if (!flatten_level(px.dev, 0, pl.fast.flat[0]) || !flatten_level(px.dev, 1, pl.fast.flat[1])) return false;
+    pl.fast.N = e.f_shape[0]; pl.fast.I = e.f_shape[1]; pl.fast.J = e.f_shape[2];
+    pl.fast.U = U; pl.fast.V = V; pl.fast.stride = s;
+    pl.fast.P = x.shape[1]; pl.fast.Q = x.shape[2];
+    pl.fwd_family = TAD_FAMILY_STRIDED;
+    pl.ap[0].family = pl.ap[1].family = TAD_FAMILY_STRIDED;
+    pl.ws_bytes = align256((size_t)((pl.f_count + 1023) / 1024) * (size_t)(U * V) * 4);
+    return true;
+}
+
 void select_families(tad_plan &plan) {
     plan.fwd_family = TAD_FAMILY_GENERIC;
     for (auto &ap : plan.ap) ap.family = TAD_FAMILY_GENERIC;
@@ -105,6 +184,7 @@ void select_families(tad_plan &plan) {
     if (plan.flags & TAD_PLAN_GENERIC_ONLY) return;
     if (match_worked(plan)) return;
     if (match_patterns(plan)) return;
+    if (match_strided(plan)) return;
 }
 
 }  // namespace tad

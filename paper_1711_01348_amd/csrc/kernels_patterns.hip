@@ -157,17 +157,17 @@ __global__ __launch_bounds__(256) void k_antidiag_forward(const float *__restric
 // partial[tile][m] = sum over the rows i of the tile that lie in window(m) of df[i][m - i].
 // Thread owns m: for a fixed row consecutive m are consecutive addresses.  z is the plan's kernel coordinate,
 // i = iy*y + iz*z (iz = +-1), j = jy*y + jz*z.
-__global__ __launch_bounds__(256) void k_antidiag_backward(const GatherPlan P, int iy, int iz, int jy, int jz,
-                                                           const float *__restrict__ df, float *__restrict__ part,
-                                                           int n_x, int J) {
+__global__ __launch_bounds__(256) void k_antidiag_backward(const FlatFeas feas, const FlatLevel win, int iy, int iz,
+                                                           int jy, int jz, const float *__restrict__ df,
+                                                           float *__restrict__ part, int n_x, int J) {
     const int m = blockIdx.x * 256 + threadIdx.x;
     if (m >= n_x) return;
     const int t = blockIdx.y;
-    int32_t beta[kMaxRank] = {m, 0, 0, 0}, y[kMaxRank] = {0, 0, 0, 0}, z[kMaxKernel] = {0, 0, 0, 0};
+    const int32_t y[3] = {m, 0, 0};   // the transformed index is the gradient index (checked on the host)
     float s = 0.f;
-    if (gather_prepare(P, beta, y)) {
+    if (flat_feasible(feas, y)) {
         int32_t lo, hi;
-        gather_bounds(P, 0, y, z, lo, hi);
+        flat_bounds(win, y, lo, hi);
         // rows of this tile: i0 <= iy*y + iz*z < i0 + AD_BTI
         const int base = iy * y[0], i0 = t * AD_BTI;
         int zlo, zhi;
@@ -261,8 +261,9 @@ int pattern_backward(const tad_plan &pl, const void *const *args, const void *df
     case TAD_FAMILY_ANTIDIAGONAL: {
         const int n_tiles = (I + AD_BTI - 1) / AD_BTI;
         float *part = (float *)ws;
-        TAD_LAUNCH("k_antidiag_backward", k_antidiag_backward, dim3((n_x + 255) / 256, n_tiles), dim3(256), 0, s, P,
-                   pl.fast.dd_iy, pl.fast.dd_iz, pl.fast.jy, pl.fast.jz, df, part, n_x, J);
+        TAD_LAUNCH("k_antidiag_backward", k_antidiag_backward, dim3((n_x + 255) / 256, n_tiles), dim3(256), 0, s,
+                   pl.fast.feas, pl.fast.flat[0], pl.fast.dd_iy, pl.fast.dd_iz, pl.fast.jy, pl.fast.jz, df, part, n_x,
+                   J);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_antidiag_finish", (k_antidiag_finish<B_>),
                                                   dim3((n_x + 255) / 256), dim3(256), 0, s, x, part, n_tiles, dx, n_x));

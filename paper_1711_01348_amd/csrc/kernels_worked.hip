@@ -271,9 +271,10 @@ __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, long l
 //   rows:  da, diagonal of dc               (sum of the row partials over the column tiles)
 //   cols:  db                               (sum of the column partials over the row tiles)
 //   dd:    dd_m = -3 d_m^2 * sum over the window coordinate of r_i; masks and the window come from the
-//          plan of d: kernel coordinate `lvl_win` is the window, the other one (j) is already summed.
+//          plan of d (loop-free copy of its rows): one kernel coordinate is the window, the other one (j)
+//          is already summed in the row partials.
 template <int K>
-__global__ __launch_bounds__(256) void k_worked_finish(const GatherPlan Pd, int lvl_win, int iy, int iz,
+__global__ __launch_bounds__(256) void k_worked_finish(const FlatFeas feas, const FlatLevel win, int iy, int iz,
                                                        const float *__restrict__ a, const float *__restrict__ b,
                                                        const float *__restrict__ c, const float *__restrict__ d,
                                                        const float *__restrict__ rowp, int n_jt,
@@ -341,11 +342,11 @@ __global__ __launch_bounds__(256) void k_worked_finish(const GatherPlan Pd, int 
     double s = 0.0;
     bool nonzero = false;
     if (m < n_d && dd) {
-        int32_t beta[kMaxRank] = {m, 0, 0, 0}, y[kMaxRank] = {0, 0, 0, 0}, z[kMaxKernel] = {0, 0, 0, 0};
-        if (gather_prepare(Pd, beta, y)) {
+        const int32_t y[3] = {m, 0, 0};   // the transformed index is the gradient index (checked on the host)
+        if (flat_feasible(feas, y)) {
             nonzero = true;
             int32_t lo, hi;
-            gather_bounds(Pd, lvl_win, y, z, lo, hi);
+            flat_bounds(win, y, lo, hi);
             for (int32_t w = lo; w <= hi; ++w) {
                 const int i = iy * y[0] + iz * w;
                 for (int jt = wave; jt < n_jt; jt += 4) s += (double)rowp[((size_t)jt * RP) * I + i];
@@ -415,8 +416,8 @@ static int bwd_k(const tad_plan &pl, const void *const *args, const void *f, con
     {
         const int n_d = (int)pl.arg_count[3];
         const int br = (I + 63) / 64, bc = (J + 63) / 64, bd = (n_d + 63) / 64;
-        TAD_LAUNCH("k_worked_finish", (k_worked_finish<K>), dim3(br + bc + bd), dim3(256), 0, s, pl.ap[3].dev,
-                   pl.fast.dd_level, pl.fast.dd_iy, pl.fast.dd_iz, a, b, c, d, w.rowp, w.n_jt, w.colp, w.n_it,
+        TAD_LAUNCH("k_worked_finish", (k_worked_finish<K>), dim3(br + bc + bd), dim3(256), 0, s, pl.fast.feas,
+                   pl.fast.flat[0], pl.fast.dd_iy, pl.fast.dd_iz, a, b, c, d, w.rowp, w.n_jt, w.colp, w.n_it,
                    (float *)dx[0], (float *)dx[1], dc, (float *)dx[3], I, J, c_ld, n_d, br, bc);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }

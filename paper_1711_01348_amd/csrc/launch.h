@@ -22,4 +22,8 @@ int pattern_forward(const tad_plan &pl, const void *const *args, void *f, hipStr
 int pattern_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
                      hipStream_t s);
 
+int strided_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
+int strided_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
+                     void *const *dx, void *ws, hipStream_t s);
+
 }  // namespace tad

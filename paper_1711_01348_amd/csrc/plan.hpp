@@ -29,6 +29,8 @@ struct FastParams {
     // gradient of d: which kernel coordinate is the clipped window, and i = dd_iy * y_0 + dd_iz * z_window
     int dd_level = 0, dd_iy = 0, dd_iz = 0;
     int jy = 0, jz = 0;              // antidiagonal pattern: j = jy * y_0 + jz * z
+    FlatLevel flat[2];               // loop-free range rows of the family's plan-driven coordinates
+    FlatFeas feas;
 };
 
 }  // namespace tad
@@ -50,6 +52,13 @@ struct tad_plan {
 };
 
 namespace tad {
+// Loop-free copies of one level's range rows / of the feasibility rows; false if the plan does not fit
+// (more rows than the fixed form holds, dependence on an outer kernel coordinate, more than kFlatY y's).
+bool flatten_level(const GatherPlan &g, int level, FlatLevel &out);
+bool flatten_feas(const GatherPlan &g, FlatFeas &out);
+// true if the transformed index is the gradient index itself (U = 1, unit Smith diagonal, no cokernel)
+bool y_is_beta(const GatherPlan &g);
+
 // Derivation proper; throws tad::overflow_error on int64 overflow.
 int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt, uint32_t flags,
                 tad_plan **out);

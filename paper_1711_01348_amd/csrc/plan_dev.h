@@ -14,8 +14,10 @@
 
 #if defined(__HIPCC__)
 #define TAD_HD __host__ __device__ __forceinline__
+#define TAD_UNROLL _Pragma("unroll")
 #else
 #define TAD_HD inline
+#define TAD_UNROLL
 #endif
 
 namespace tad {
@@ -59,11 +61,17 @@ struct ForwardPlan {
     int64_t off[kMaxArgs][kMaxExt];    // element offset of argument p = off[p] . [alpha k]
 };
 
-TAD_HD int32_t floor_div_i(int32_t a, int32_t b) {  // b > 0
+// floor(a / b) and ceil(a / b) for b > 0, exact for negative a.  Divisors 1 and 2 (unit and stride-2
+// index maps) avoid the integer division, which costs tens of instructions on the GPU.
+TAD_HD int32_t floor_div_i(int32_t a, int32_t b) {
+    if (b == 1) return a;
+    if (b == 2) return a >> 1;
     int32_t q = a / b, r = a % b;
     return (r < 0) ? q - 1 : q;
 }
-TAD_HD int32_t ceil_div_i(int32_t a, int32_t b) {  // b > 0
+TAD_HD int32_t ceil_div_i(int32_t a, int32_t b) {
+    if (b == 1) return a;
+    if (b == 2) return -((-a) >> 1);
     int32_t q = a / b, r = a % b;
     return (r > 0) ? q + 1 : q;
 }
@@ -79,8 +87,11 @@ TAD_HD bool gather_prepare(const GatherPlan &P, const int32_t *beta, int32_t *y)
     for (int r = 0; r < P.R; ++r) {
         int32_t s = 0;
         for (int d = 0; d < P.rank; ++d) s += P.U[r][d] * beta[d];
-        if (s % P.diag[r] != 0) return false;
-        y[r] = s / P.diag[r];
+        if (P.diag[r] != 1) {
+            if (s % P.diag[r] != 0) return false;
+            s /= P.diag[r];
+        }
+        y[r] = s;
     }
     for (int f = 0; f < P.nF; ++f) {
         int32_t s = P.feas[f].k0;
@@ -111,6 +122,54 @@ TAD_HD void gather_bounds(const GatherPlan &P, int level, const int32_t *y, cons
     }
     lo = l;
     hi = h;
+}
+
+// Fixed-size, loop-free form of the mask and range rows for plans whose ranges do not depend on outer
+// kernel coordinates.  Evaluating the general form costs one dependent scalar load per row entry; this
+// form is fetched with a few wide scalar loads and evaluated as straight-line code.  Unused rows hold
+// neutral values, so no row counts are needed.
+constexpr int kFlatRows = 3;
+constexpr int kFlatFeas = 6;
+constexpr int kFlatY = 3;
+
+struct FlatLevel {
+    int32_t ls[kFlatRows], lk0[kFlatRows], lky[kFlatRows][kFlatY];   // ls * z >= lk0 + lky . y
+    int32_t hs[kFlatRows], hk0[kFlatRows], hky[kFlatRows][kFlatY];   // hs * z <= hk0 + hky . y
+};
+
+struct FlatFeas {
+    int32_t k0[kFlatFeas], ky[kFlatFeas][kFlatY];                    // k0 + ky . y <= 0
+};
+
+TAD_HD void flat_bounds(const FlatLevel &L, const int32_t *y, int32_t &lo, int32_t &hi) {
+    int32_t l = INT32_MIN, h = INT32_MAX;
+TAD_UNROLL
+    for (int r = 0; r < kFlatRows; ++r) {
+        int32_t a = L.lk0[r], b = L.hk0[r];
+TAD_UNROLL
+        for (int c = 0; c < kFlatY; ++c) {
+            a += L.lky[r][c] * y[c];
+            b += L.hky[r][c] * y[c];
+        }
+        a = ceil_div_i(a, L.ls[r]);
+        b = floor_div_i(b, L.hs[r]);
+        l = a > l ? a : l;
+        h = b < h ? b : h;
+    }
+    lo = l;
+    hi = h;
+}
+
+TAD_HD bool flat_feasible(const FlatFeas &F, const int32_t *y) {
+    bool ok = true;
+TAD_UNROLL
+    for (int r = 0; r < kFlatFeas; ++r) {
+        int32_t s = F.k0[r];
+TAD_UNROLL
+        for (int c = 0; c < kFlatY; ++c) s += F.ky[r][c] * y[c];
+        ok = ok && s <= 0;
+    }
+    return ok;
 }
 
 TAD_HD int64_t gather_offset(const GatherPlan &P, int slot, const int32_t *y, const int32_t *z) {

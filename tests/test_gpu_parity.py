@@ -89,6 +89,8 @@ ASSORTED = [
     lambda: _expr("sq", (130, 260), [], [("x", (400,), [[1, 1]])], "f32"),
     lambda: _expr("exp", (65, 1032), [], [("x", (1096,), [[1, 1]])], "f32"),
     lambda: _expr("exp", (33, 517), [], [("x", (33,), [[1, 0]])], "f32"),        # not a multiple of 4: generic
+    lambda: wl.strided_tanh_expr(3, 19, 23, 5, 4, 3, "f32"),
+    lambda: wl.strided_tanh_expr(2, 30, 41, 2, 2, 1, "f32"),
     lambda: wl.strided_tanh_expr(2, 5, 4, 2, 3, 3, "f64"),
 ]
 
