@@ -17,6 +17,7 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
     switch (plan->fwd_family) {
     case TAD_FAMILY_GENERIC: return generic_forward(*plan, args_dev, f_dev, s);
     case TAD_FAMILY_WORKED: return worked_forward(*plan, args_dev, f_dev, s);
+    case TAD_FAMILY_WORKED_MFMA: return mfma_forward(*plan, args_dev, f_dev, ws_dev, s);
     case TAD_FAMILY_ROW_REDUCE:
     case TAD_FAMILY_DIAGONAL:
     case TAD_FAMILY_ANTIDIAGONAL: return pattern_forward(*plan, args_dev, f_dev, s);
@@ -44,6 +45,7 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
     switch (fam) {
     case TAD_FAMILY_GENERIC: return generic_backward(*plan, args_dev, f_dev, df_dev, dx_dev, s);
     case TAD_FAMILY_WORKED: return worked_backward(*plan, args_dev, f_dev, df_dev, dx_dev, ws_dev, s);
+    case TAD_FAMILY_WORKED_MFMA: return mfma_backward(*plan, args_dev, f_dev, df_dev, dx_dev, ws_dev, s);
     case TAD_FAMILY_ROW_REDUCE:
     case TAD_FAMILY_DIAGONAL:
     case TAD_FAMILY_ANTIDIAGONAL: return pattern_backward(*plan, args_dev, df_dev, dx_dev, ws_dev, s);

@@ -107,6 +107,14 @@ static bool match_worked(tad_plan &pl) {
         pl.ws_bytes = worked_workspace_bytes(I, J, K);
         return true;
     }
+    if (K % 32 == 0) {
+        // long summed index: the contraction over k (and the collapsed j / i contractions of the gradients)
+        // are dense matrix products and run on the matrix cores
+        pl.fwd_family = TAD_FAMILY_WORKED_MFMA;
+        for (auto &ap : pl.ap) ap.family = TAD_FAMILY_WORKED_MFMA;
+        pl.ws_bytes = mfma_workspace_bytes(I, J, K);
+        return true;
+    }
     return false;
 }
 

@@ -1,0 +1,529 @@
+// Worked expression with a long summed index (K a multiple of 32, fp32): the contraction over k is a
+// genuine dense matrix product, so it runs on the matrix cores (v_mfma_f32_32x32x2f32).
+//
+//   forward   s_ij = |a_i|^2 + |b_j|^2 + 2 a_i . b_j        (expanded square; a . b^T on MFMA)
+//             f_ij = exp(-(c_ii s_ij + D_i)),  D_i = sum_k d_{i+k}^3
+//   backward  G_ij = df_ij f_ij
+//             P = G b        (I x K, contraction over the collapsed kernel coordinate j, split in chunks)
+//             T = (c G)^T a  (J x K, contraction over the collapsed kernel coordinate i, split in chunks)
+//             r_i = sum_j G_ij, Q_i = sum_j G_ij |b_j|^2, t_j = sum_i c_ii G_ij   (streaming pass)
+//             da_ik = -2 c_ii (a_ik r_i + P_ik)      db_jk = -2 (T_jk + b_jk t_j)
+//             dc_ii = -(|a_i|^2 r_i + 2 sum_k a_ik P_ik + Q_i)      dd_m = -3 d_m^2 sum_{i in window(m)} r_i
+// All partial results are combined in a fixed order (no atomics).
+//
+// MFMA operand layout used below (wave64): A operand lane l = A[m = l % 32][k = l / 32],
+// B operand lane l = B[k = l / 32][n = l % 32], result register r of lane l = D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32].
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "launch.h"
+#include "plan_dev.h"
+#include "profile.h"
+#include "worked_geom.h"
+
+namespace tad {
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+constexpr float kLog2eM = 1.4426950408889634f;
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add_m(float v) {
+    int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, ROW_MASK == 0xf);
+    return v + __int_as_float(t);
+}
+__device__ __forceinline__ float wave_sum63m(float v) {   // total valid in lane 63
+    v = dpp_add_m<0x111, 0xf>(v);
+    v = dpp_add_m<0x112, 0xf>(v);
+    v = dpp_add_m<0x114, 0xf>(v);
+    v = dpp_add_m<0x118, 0xf>(v);
+    v = dpp_add_m<0x142, 0xa>(v);
+    v = dpp_add_m<0x143, 0xc>(v);
+    return v;
+}
+
+__device__ __forceinline__ void zero_acc(float16v (&acc)[2][2]) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+}
+
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// ---------------------------------------------------------------------------------------------
+// per-row and per-column quantities: rowv[i] = {|a_i|^2, -log2e c_ii, -log2e D_i, c_ii}, nb[j] = |b_j|^2
+// one wave per row
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_mfma_prep(const float *__restrict__ a, const float *__restrict__ b,
+                                                   const float *__restrict__ c, const float *__restrict__ d,
+                                                   float *__restrict__ rowv, float *__restrict__ nb, int I, int J,
+                                                   int K, int c_ld) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row < I) {
+        float na = 0.f, D = 0.f;
+        for (int k = lane; k < K; k += 64) {
+            const float av = a[(size_t)row * K + k], dv = d[row + k];
+            na = fmaf(av, av, na);
+            D = fmaf(dv * dv, dv, D);
+        }
+        na = wave_sum63m(na);
+        D = wave_sum63m(D);
+        if (lane == 63) {
+            const float cv = c[(size_t)row * c_ld + row];
+            rowv[row * 4 + 0] = na;
+            rowv[row * 4 + 1] = -kLog2eM * cv;
+            rowv[row * 4 + 2] = -kLog2eM * D;
+            rowv[row * 4 + 3] = cv;
+        }
+    } else if (row - I < J) {
+        const int j = row - I;
+        float s = 0.f;
+        for (int k = lane; k < K; k += 64) {
+            const float bv = b[(size_t)j * K + k];
+            s = fmaf(bv, bv, s);
+        }
+        s = wave_sum63m(s);
+        if (lane == 63) nb[j] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward: block tile 128 x 128, 2 x 2 waves of 64 x 64, k tile 32, global -> register -> LDS staging
+// ---------------------------------------------------------------------------------------------
+constexpr int MF_KT = 32;
+constexpr int MF_LD = 33;   // odd row stride: conflict-free ds_read_b32 of [row][k] tiles
+
+__global__ __launch_bounds__(256) void k_mfma_forward(const float *__restrict__ a, const float *__restrict__ b,
+                                                      const float *__restrict__ rowv, const float *__restrict__ nb,
+                                                      float *__restrict__ f, int I, int J, int K) {
+    __shared__ float As[128][MF_LD];
+    __shared__ float Bs[128][MF_LD];
+    __shared__ float rv[128][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int i0 = blockIdx.y * 128, j0 = blockIdx.x * 128;
+    if (tid < 128) {
+        const int i = i0 + tid;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rv[tid][q] = i < I ? rowv[i * 4 + q] : 0.f;
+    }
+    float16v acc[2][2];
+    zero_acc(acc);
+    float4v ra[4], rb[4];
+    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int idx = tid + 256 * p, row = idx >> 3, kq = idx & 7;
+            ra[p] = (i0 + row < I) ? *reinterpret_cast<const float4v *>(a + (size_t)(i0 + row) * K + k0 + 4 * kq) : zero4;
+            rb[p] = (j0 + row < J) ? *reinterpret_cast<const float4v *>(b + (size_t)(j0 + row) * K + k0 + 4 * kq) : zero4;
+        }
+    };
+    gload(0);
+    const int mrow = lane & 31, kof = lane >> 5;
+    for (int k0 = 0; k0 < K; k0 += MF_KT) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int idx = tid + 256 * p, row = idx >> 3, kq = idx & 7;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                As[row][4 * kq + q] = ra[p][q];
+                Bs[row][4 * kq + q] = rb[p][q];
+            }
+        }
+        __syncthreads();
+        if (k0 + MF_KT < K) gload(k0 + MF_KT);
+#pragma unroll
+        for (int ks = 0; ks < MF_KT / 2; ++ks) {
+            const float a0 = As[wm * 64 + mrow][2 * ks + kof], a1 = As[wm * 64 + 32 + mrow][2 * ks + kof];
+            const float b0 = Bs[wn * 64 + mrow][2 * ks + kof], b1 = Bs[wn * 64 + 32 + mrow][2 * ks + kof];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // epilogue: f = exp2(c' (|a|^2 + |b|^2 + 2 a.b) + D')
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+        const int j = j0 + wn * 64 + tn * 32 + mrow;
+        const float nbj = j < J ? nb[j] : 0.f;
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = wm * 64 + tm * 32 + acc_row(r, lane);
+                const int i = i0 + m;
+                const float s = rv[m][0] + nbj + 2.f * acc[tm][tn][r];
+                const float val = __builtin_amdgcn_exp2f(fmaf(rv[m][1], s, rv[m][2]));
+                if (i < I && j < J) f[(size_t)i * J + j] = val;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward contractions.  Block tile 64 (M) x 256 (N = k), 1 x 4 waves of 64 x 64, contraction tile 32.
+//   TRANS_A = false:  M = i, contraction over j in [cs, ce):  A[m][kk] = df f            B[kk][n] = b[j][k]
+//   TRANS_A = true:   M = j, contraction over i in [cs, ce):  A[m][kk] = c_ii df f (read transposed), B[kk][n] = a[i][k]
+// out[(split * Mtot + m) * K + n]
+// ---------------------------------------------------------------------------------------------
+template <bool TRANS_A>
+__global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__ f, const float *__restrict__ df,
+                                                       const float *__restrict__ bmat, const float *__restrict__ rowv,
+                                                       float *__restrict__ out, int I, int J, int K, int chunk) {
+    __shared__ float As[TRANS_A ? 32 : 64][TRANS_A ? 64 : MF_LD];
+    __shared__ float Bs[32][256];
+    const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
+    const int Mtot = TRANS_A ? J : I, Ctot = TRANS_A ? I : J;
+    const int m0 = blockIdx.x * 64, split = blockIdx.y, n0 = blockIdx.z * 256;
+    const int cs = split * chunk, ce = min(Ctot, cs + chunk);
+    float16v acc[2][2];
+    zero_acc(acc);
+    float4v ga[2], gb[8];
+    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    auto gload = [&](int c0) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int idx = tid + 256 * p;
+            if (!TRANS_A) {
+                const int row = idx >> 3, q = idx & 7;            // i = m0 + row, j = c0 + 4 q
+                const int i = m0 + row, j = c0 + 4 * q;
+                if (i < I && j < ce) {
+                    const size_t off = (size_t)i * J + j;
+                    ga[p] = *reinterpret_cast<const float4v *>(df + off) * *reinterpret_cast<const float4v *>(f + off);
+                } else ga[p] = zero4;
+            } else {
+                const int kk = idx >> 4, q = idx & 15;            // i = c0 + kk, j = m0 + 4 q
+                const int i = c0 + kk, j = m0 + 4 * q;
+                if (i < ce && j < J) {
+                    const size_t off = (size_t)i * J + j;
+                    ga[p] = *reinterpret_cast<const float4v *>(df + off) * *reinterpret_cast<const float4v *>(f + off) *
+                            rowv[i * 4 + 3];
+                } else ga[p] = zero4;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int idx = tid + 256 * p, kk = idx >> 6, q = idx & 63;
+            const int cc = c0 + kk, n = n0 + 4 * q;
+            gb[p] = (cc < ce && n < K) ? *reinterpret_cast<const float4v *>(bmat + (size_t)cc * K + n) : zero4;
+        }
+    };
+    gload(cs);
+    const int mrow = lane & 31, kof = lane >> 5;
+    for (int c0 = cs; c0 < ce; c0 += MF_KT) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int idx = tid + 256 * p;
+            if (!TRANS_A) {
+                const int row = idx >> 3, q = idx & 7;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) As[row][4 * q + e] = ga[p][e];
+            } else {
+                const int kk = idx >> 4, q = idx & 15;
+                *reinterpret_cast<float4v *>(&As[kk][4 * q]) = ga[p];
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int idx = tid + 256 * p, kk = idx >> 6, q = idx & 63;
+            *reinterpret_cast<float4v *>(&Bs[kk][4 * q]) = gb[p];
+        }
+        __syncthreads();
+        if (c0 + MF_KT < ce) gload(c0 + MF_KT);
+#pragma unroll
+        for (int ks = 0; ks < MF_KT / 2; ++ks) {
+            float a0, a1;
+            if (!TRANS_A) {
+                a0 = As[mrow][2 * ks + kof];
+                a1 = As[32 + mrow][2 * ks + kof];
+            } else {
+                a0 = As[2 * ks + kof][mrow];
+                a1 = As[2 * ks + kof][32 + mrow];
+            }
+            const float b0 = Bs[2 * ks + kof][wn * 64 + mrow], b1 = Bs[2 * ks + kof][wn * 64 + 32 + mrow];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+        const int n = n0 + wn * 64 + tn * 32 + mrow;
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + tm * 32 + acc_row(r, lane);
+                if (m < Mtot && n < K) out[((size_t)split * Mtot + m) * K + n] = acc[tm][tn][r];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// streaming sums r_i, Q_i (row partials per column tile) and t_j (column partials per row tile)
+// block: 4 waves over the same 512 columns, 256 rows (a quarter per wave), 4 rows per step
+// ---------------------------------------------------------------------------------------------
+constexpr int MS_RB = 4;
+
+__global__ __launch_bounds__(256) void k_mfma_sums(const float *__restrict__ f, const float *__restrict__ df,
+                                                   const float *__restrict__ rowv, const float *__restrict__ nb,
+                                                   float *__restrict__ rowp, float *__restrict__ colp, int I, int J) {
+    constexpr int WR = MS_TI / 4;
+    __shared__ float rows_out[2][MS_TI];
+    __shared__ float cred[4][MS_TJ];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i0 = blockIdx.y * MS_TI, jb = blockIdx.x * MS_TJ;
+    int jc[2];
+    bool live[2];
+    float nbv[2][4], tc[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        jc[h] = jb + h * 256 + lane * 4;
+        live[h] = jc[h] < J;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            nbv[h][v] = live[h] ? nb[jc[h] + v] : 0.f;
+            tc[h][v] = 0.f;
+        }
+    }
+    const int r0 = wave * WR;
+    const int rows = max(0, min(WR, I - (i0 + r0)));
+    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < WR; rb += MS_RB) {
+        float pr[MS_RB], pq[MS_RB];
+#pragma unroll
+        for (int r = 0; r < MS_RB; ++r) pr[r] = pq[r] = 0.f;
+        if (rb < rows) {
+            float4v fv[MS_RB][2], dv[MS_RB][2];
+#pragma unroll
+            for (int r = 0; r < MS_RB; ++r)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const bool ok = live[h] && (rb + r) < rows;
+                    const size_t off = (size_t)(i0 + r0 + rb + r) * J + jc[h];
+                    fv[r][h] = ok ? *reinterpret_cast<const float4v *>(f + off) : zero4;
+                    dv[r][h] = ok ? *reinterpret_cast<const float4v *>(df + off) : zero4;
+                }
+#pragma unroll
+            for (int r = 0; r < MS_RB; ++r) {
+                const int i = i0 + r0 + rb + r;
+                const float ci = i < I ? rowv[i * 4 + 3] : 0.f;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float g = dv[r][h][v] * fv[r][h][v];
+                        pr[r] += g;
+                        pq[r] = fmaf(g, nbv[h][v], pq[r]);
+                        tc[h][v] = fmaf(g, ci, tc[h][v]);
+                    }
+            }
+#pragma unroll
+            for (int r = 0; r < MS_RB; ++r) {
+                pr[r] = wave_sum63m(pr[r]);
+                pq[r] = wave_sum63m(pq[r]);
+            }
+        }
+        if (lane == 63) {
+#pragma unroll
+            for (int r = 0; r < MS_RB; ++r) {
+                rows_out[0][r0 + rb + r] = pr[r];
+                rows_out[1][r0 + rb + r] = pq[r];
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) cred[wave][h * 256 + lane * 4 + v] = tc[h][v];
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int col = h * 256 + tid, j = jb + col;
+        if (j < J) colp[(size_t)blockIdx.y * J + j] = (cred[0][col] + cred[1][col]) + (cred[2][col] + cred[3][col]);
+    }
+    for (int t = tid; t < MS_TI; t += 256) {
+        const int i = i0 + t;
+        if (i < I) {
+            rowp[((size_t)blockIdx.x * 2 + 0) * I + i] = rows_out[0][t];
+            rowp[((size_t)blockIdx.x * 2 + 1) * I + i] = rows_out[1][t];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_mfma_fill_zero(float *__restrict__ p, long long n) {
+    const long long n4 = n >> 2;
+    const float4v z = {0.f, 0.f, 0.f, 0.f};
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < n4; q += stride)
+        reinterpret_cast<float4v *>(p)[q] = z;
+    if (blockIdx.x == 0 && threadIdx.x < (int)(n & 3)) p[(n4 << 2) + threadIdx.x] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// finishing: one wave per output row.  Blocks [0, blocks_rows) : rows i (da, dc_ii, r_i); the rest: rows j (db)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_mfma_finish(const float *__restrict__ a, const float *__restrict__ b,
+                                                     const float *__restrict__ rowv, const float *__restrict__ Ppart,
+                                                     const float *__restrict__ Tpart, int n_split,
+                                                     const float *__restrict__ rowp, int n_jt,
+                                                     const float *__restrict__ colp, int n_it, float *__restrict__ da,
+                                                     float *__restrict__ db, float *__restrict__ dc,
+                                                     float *__restrict__ rsum, int I, int J, int K, int c_ld,
+                                                     int blocks_rows) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if ((int)blockIdx.x < blocks_rows) {
+        const int i = blockIdx.x * 4 + wv;
+        if (i >= I) return;
+        double r = 0.0, Q = 0.0;
+        for (int jt = 0; jt < n_jt; ++jt) {
+            r += (double)rowp[((size_t)jt * 2 + 0) * I + i];
+            Q += (double)rowp[((size_t)jt * 2 + 1) * I + i];
+        }
+        const double ci = (double)rowv[i * 4 + 3], na = (double)rowv[i * 4 + 0];
+        float cross = 0.f;
+        for (int k = lane; k < K; k += 64) {
+            double P = 0.0;
+            for (int s = 0; s < n_split; ++s) P += (double)Ppart[((size_t)s * I + i) * K + k];
+            const double ak = (double)a[(size_t)i * K + k];
+            if (da) da[(size_t)i * K + k] = (float)(-2.0 * ci * (ak * r + P));
+            cross += (float)(ak * P);
+        }
+        cross = wave_sum63m(cross);
+        if (lane == 63) {
+            if (dc) dc[(size_t)i * c_ld + i] = (float)(-(na * r + 2.0 * (double)cross + Q));
+            rsum[i] = (float)r;
+        }
+        return;
+    }
+    const int j = ((int)blockIdx.x - blocks_rows) * 4 + wv;
+    if (j >= J || !db) return;
+    double t = 0.0;
+    for (int it = 0; it < n_it; ++it) t += (double)colp[(size_t)it * J + j];
+    for (int k = lane; k < K; k += 64) {
+        double T = 0.0;
+        for (int s = 0; s < n_split; ++s) T += (double)Tpart[((size_t)s * J + j) * K + k];
+        db[(size_t)j * K + k] = (float)(-2.0 * (T + (double)b[(size_t)j * K + k] * t));
+    }
+}
+
+// dd_m = -3 d_m^2 sum_{i in window(m)} r_i, one wave per m; window and masks from the plan of d
+__global__ __launch_bounds__(256) void k_mfma_dd(const FlatFeas feas, const FlatLevel win, int iy, int iz,
+                                                 const float *__restrict__ d, const float *__restrict__ rsum,
+                                                 float *__restrict__ dd, int n_d) {
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= n_d) return;
+    const int32_t y[3] = {m, 0, 0};
+    float s = 0.f;
+    const bool ok = flat_feasible(feas, y);
+    if (ok) {
+        int32_t lo, hi;
+        flat_bounds(win, y, lo, hi);
+        for (int32_t w = lo + lane; w <= hi; w += 64) s += rsum[iy * y[0] + iz * w];
+    }
+    s = wave_sum63m(s);
+    if (lane == 63) {
+        const float dm = d[m];
+        dd[m] = ok ? -3.f * dm * dm * s : 0.f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct MfmaWs {
+    float *rowv, *nb, *Ppart, *Tpart, *rowp, *colp, *rsum;
+    int n_split, chunk_j, chunk_i, n_jt, n_it;
+};
+
+static MfmaWs carve_mfma(void *ws, int64_t I, int64_t J, int64_t K) {
+    MfmaWs w;
+    w.n_split = kMfmaSplit;
+    w.chunk_j = (int)(((J + kMfmaSplit - 1) / kMfmaSplit + 31) / 32 * 32);
+    w.chunk_i = (int)(((I + kMfmaSplit - 1) / kMfmaSplit + 31) / 32 * 32);
+    w.n_jt = (int)((J + MS_TJ - 1) / MS_TJ);
+    w.n_it = (int)((I + MS_TI - 1) / MS_TI);
+    char *p = static_cast<char *>(ws);
+    auto take = [&](size_t bytes) { float *r = reinterpret_cast<float *>(p); p += align256(bytes); return r; };
+    w.rowv = take((size_t)I * 16);
+    w.nb = take((size_t)J * 4);
+    w.Ppart = take((size_t)kMfmaSplit * I * K * 4);
+    w.Tpart = take((size_t)kMfmaSplit * J * K * 4);
+    w.rowp = take((size_t)w.n_jt * 2 * I * 4);
+    w.colp = take((size_t)w.n_it * J * 4);
+    w.rsum = take((size_t)I * 4);
+    return w;
+}
+
+static int prep(const tad_plan &pl, const void *const *args, const MfmaWs &w, hipStream_t s) {
+    const int I = (int)pl.fast.I, J = (int)pl.fast.J, K = (int)pl.fast.K;
+    TAD_LAUNCH("k_mfma_prep", k_mfma_prep, dim3((I + J + 3) / 4), dim3(256), 0, s, (const float *)args[0],
+               (const float *)args[1], (const float *)args[2], (const float *)args[3], w.rowv, w.nb, I, J, K,
+               (int)pl.fast.c_ld);
+    return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+}
+
+int mfma_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s) {
+    const int I = (int)pl.fast.I, J = (int)pl.fast.J, K = (int)pl.fast.K;
+    MfmaWs w = carve_mfma(ws, I, J, K);
+    int rc = prep(pl, args, w, s);
+    if (rc) return rc;
+    TAD_LAUNCH("k_mfma_forward", k_mfma_forward, dim3((J + 127) / 128, (I + 127) / 128), dim3(256), 0, s,
+               (const float *)args[0], (const float *)args[1], w.rowv, w.nb, (float *)f, I, J, K);
+    return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+}
+
+int mfma_backward(const tad_plan &pl, const void *const *args, const void *f_, const void *df_, void *const *dx,
+                  void *ws, hipStream_t s) {
+    const int I = (int)pl.fast.I, J = (int)pl.fast.J, K = (int)pl.fast.K, c_ld = (int)pl.fast.c_ld;
+    MfmaWs w = carve_mfma(ws, I, J, K);
+    const float *a = (const float *)args[0], *b = (const float *)args[1], *d = (const float *)args[3];
+    const float *f = (const float *)f_, *df = (const float *)df_;
+    int rc = prep(pl, args, w, s);
+    if (rc) return rc;
+    TAD_LAUNCH("k_mfma_sums", k_mfma_sums, dim3(w.n_jt, w.n_it), dim3(256), 0, s, f, df, w.rowv, w.nb, w.rowp, w.colp,
+               I, J);
+    if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    const int nz = (K + 255) / 256;
+    if (dx[0] || dx[2]) {
+        TAD_LAUNCH("k_mfma_backward", (k_mfma_backward<false>), dim3((I + 63) / 64, w.n_split, nz), dim3(256), 0, s, f,
+                   df, b, w.rowv, w.Ppart, I, J, K, w.chunk_j);
+        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    }
+    if (dx[1]) {
+        TAD_LAUNCH("k_mfma_backward", (k_mfma_backward<true>), dim3((J + 63) / 64, w.n_split, nz), dim3(256), 0, s, f,
+                   df, a, w.rowv, w.Tpart, I, J, K, w.chunk_i);
+        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    }
+    if (dx[2]) {
+        const long long n = pl.arg_count[2];
+        const int g = (int)std::min<long long>(16384, (n / 4 + 255) / 256 + 1);
+        TAD_LAUNCH("k_fill_zero", k_mfma_fill_zero, dim3(g), dim3(256), 0, s, (float *)dx[2], n);
+        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    }
+    const int br = (I + 3) / 4, bc = dx[1] ? (J + 3) / 4 : 0;
+    TAD_LAUNCH("k_mfma_finish", k_mfma_finish, dim3(br + bc), dim3(256), 0, s, a, b, w.rowv, w.Ppart, w.Tpart,
+               (dx[0] || dx[2]) ? w.n_split : 0, w.rowp, w.n_jt, w.colp, w.n_it, (float *)dx[0], (float *)dx[1],
+               (float *)dx[2], w.rsum, I, J, K, c_ld, br);
+    if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    if (dx[3]) {
+        const int n_d = (int)pl.arg_count[3];
+        TAD_LAUNCH("k_mfma_dd", k_mfma_dd, dim3((n_d + 3) / 4), dim3(256), 0, s, pl.fast.feas, pl.fast.flat[0],
+                   pl.fast.dd_iy, pl.fast.dd_iz, d, w.rsum, (float *)dx[3], n_d);
+        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    }
+    return TAD_OK;
+}
+
+}  // namespace tad

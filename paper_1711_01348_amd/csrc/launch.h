@@ -18,6 +18,9 @@ int worked_forward(const tad_plan &pl, const void *const *args, void *f, hipStre
 int worked_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
                     void *const *dx, void *ws, hipStream_t s);
 
+int mfma_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s);
+int mfma_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df, void *const *dx,
+                  void *ws, hipStream_t s);
 int pattern_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
 int pattern_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
                      hipStream_t s);

@@ -56,6 +56,23 @@ def test_configs_small(w, generic_only):
     assert_parity(w, f, grads, f_ref, g_ref, "generic" if generic_only else "selected")
 
 
+EXPECTED_FAMILY = {"cfg1": "generic", "cfg2_1": "row_reduce", "cfg2_2": "diagonal", "cfg2_3": "antidiagonal",
+                   "cfg3": "worked", "cfg4": "worked_mfma", "cfg5": "strided"}
+
+
+@pytest.mark.parametrize("w", wl.all_configs("small") + [wl.config3(), wl.config4(), wl.config5()],
+                         ids=lambda w: w.name)
+def test_selected_kernel_family(w):
+    """The benchmark configurations must run on their specialised kernels, not on the generic fallback."""
+    from paper_1711_01348_amd import binding as B
+    plan = B.Plan(w.expr)
+    key = next(k for k in sorted(EXPECTED_FAMILY, key=len, reverse=True) if w.name.startswith(k))
+    assert plan.forward_family == EXPECTED_FAMILY[key], w.name
+    for p in range(len(w.expr.args)):
+        assert plan.query(p)["family"] == EXPECTED_FAMILY[key], (w.name, p)
+    assert B.Plan(w.expr, generic_only=True).forward_family == "generic"
+
+
 def test_config1_fp64_tight():
     w = wl.config1()
     f_ref, g_ref = oracle_all(w, 1)
