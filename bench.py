@@ -2,7 +2,7 @@
 """Benchmark of the hot path on one MI355X: forward + gather-form backward of an element-wise
 defined tensor, reported as tensor elements per second and as a fraction of the HBM roofline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--others] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-others] [--no-cpu]
 
 One "step" is one pass of the whole path (tad_eval_forward + tad_eval_backward, every gradient)
 over one batch of seeded synthetic inputs that already live in HBM.  Prints ONE JSON line.
@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VALU_TFLOPS = 157.3       # published vector fp32 peak (packed); 256 CUs x 2.4 GHz x 256 flop/clk
 FP32_MFMA_TFLOPS = 157.3
+ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 2x the 256 MB last-level cache)
 
 
 def workload(name):
@@ -34,74 +35,94 @@ def workload(name):
 
 
 def accounting(name, w):
-    """Compulsory traffic of one forward+backward step: (tensor elements, bytes), and the dominant kernel
-    with its algorithmic bytes per launch."""
+    """Compulsory work of one forward+backward step.
+
+    Returns (tensor elements, bytes, dominant) where dominant describes the kernel the roofline entry is
+    computed for: name, bound ("hbm" or "mfma"), algorithmic bytes or flops per launch, launches per step.
+    """
     import numpy as np
     e = w.expr
     nf = int(np.prod(e.f_shape))
     small = sum(int(np.prod(a.shape)) for a in e.args)
     es = 4 if e.dtype == "f32" else 8
     if name in ("cfg3", "cfg4", "cfg1"):
-        I = e.f_shape[0]
+        I, J = e.f_shape
+        K = e.sums[0][1] + 1
         cdense = int(np.prod(e.args[2].shape))
         small_rw = 2 * (small - cdense) + I          # a, b, d read; da, db, dd written; diagonal of c read
         elems = nf + nf + nf + cdense + small_rw      # write f; read df; read f; write dense dc
-        dom = ("k_worked_backward", 2 * nf * es)
+        if name == "cfg4":
+            # expanded form on the matrix cores: a.b^T, G b and (cG)^T a, 2 I J K flops each
+            dom = dict(kernel="k_mfma_backward", bound="mfma", per_launch=2.0 * I * J * K, launches=2,
+                       step_flops=6.0 * I * J * K)
+        elif name == "cfg3":
+            dom = dict(kernel="k_worked_backward", bound="hbm", per_launch=2 * nf * es, launches=1)
+        else:
+            dom = dict(kernel="k_generic_gather", bound="hbm", per_launch=0, launches=4)
     elif name == "cfg2_1":
         elems = nf + nf + 2 * small                   # write f; read df; x read, dx written
-        dom = ("k_rowreduce_backward", nf * es)
+        dom = dict(kernel="k_rowreduce_backward", bound="hbm", per_launch=nf * es, launches=1)
     elif name == "cfg2_2":
         elems = small + 3 * nf                        # write dense dx; diagonal read, f written, df read
-        dom = ("k_diagonal_backward", small * es)
+        dom = dict(kernel="k_diagonal_backward", bound="hbm", per_launch=small * es, launches=1)
     elif name == "cfg2_3":
         elems = nf + nf + 2 * small
-        dom = ("k_antidiag_backward", nf * es)
+        dom = dict(kernel="k_antidiag_backward", bound="hbm", per_launch=nf * es, launches=1)
     elif name == "cfg5":
         nx = int(np.prod(e.args[0].shape))
         elems = nx + nf + 2 * nf + nx + nx + 18       # fwd: read x, write f; bwd: read df, f; write dx; read x (dw)
-        dom = ("k_strided_backward", (2 * nf + 2 * nx) * es)
+        dom = dict(kernel="k_strided_backward", bound="hbm", per_launch=(2 * nf + 2 * nx) * es, launches=1)
     else:
         raise ValueError(name)
     return elems, elems * es, dom
 
 
-def run_gpu(name, steps, warmup, profile_kernel=True):
+def run_gpu(name, steps, warmup, rotate_bytes=0):
+    """Time `steps` forward+backward passes.  With rotate_bytes > 0 the step cycles over enough independent
+    buffer sets to exceed that footprint, so that a workload smaller than the last-level cache still streams
+    from HBM."""
+    import ctypes
     import torch
     from paper_1711_01348_amd import binding as B
-    import ctypes
     w = workload(name)
     plan = B.Plan(w.expr)
     dev = torch.device("cuda:0")
-    args = [torch.from_numpy(a).to(dev) for a in w.arg_list()]
-    df = torch.from_numpy(w.df).to(dev)
-    f = torch.empty(tuple(w.expr.f_shape), dtype=df.dtype, device=dev)
-    grads = [torch.empty_like(a) for a in args]
-    ws = plan.workspace(dev)
-    elems, nbytes, (dom_kernel, dom_bytes) = accounting(name, w)
+    elems, nbytes, dom = accounting(name, w)
 
-    def step():
+    def make_set():
+        args = [torch.from_numpy(a).to(dev) for a in w.arg_list()]
+        df = torch.from_numpy(w.df).to(dev)
+        f = torch.empty(tuple(w.expr.f_shape), dtype=df.dtype, device=dev)
+        grads = [torch.empty_like(a) for a in args]
+        return args, df, f, grads, plan.workspace(dev)
+
+    sets = [make_set()]
+    foot = sum(t.numel() * t.element_size() for t in sets[0][0] + [sets[0][1], sets[0][2]] + sets[0][3])
+    while rotate_bytes and foot * len(sets) < rotate_bytes and len(sets) < 64:
+        sets.append(make_set())
+
+    def step(i):
+        args, df, f, grads, ws = sets[i % len(sets)]
         plan.forward(args, out=f, ws=ws)
         plan.backward(args, f, df, out=grads, ws=ws)
 
-    for _ in range(warmup):
-        step()
+    for i in range(warmup):
+        step(i)
     torch.cuda.synchronize()
-    families = {"forward": plan.forward_family, "backward": [plan.query(p)["family"] for p in range(len(args))]}
-    if profile_kernel:
-        B._check(B.lib.tad_profile_begin(dom_kernel.encode()), "tad_profile_begin")
+    families = {"forward": plan.forward_family, "backward": [plan.query(p)["family"] for p in range(len(w.expr.args))]}
+    B._check(B.lib.tad_profile_begin(dom["kernel"].encode()), "tad_profile_begin")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
+    for i in range(steps):
+        step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    dom_ms, dom_n = None, 0
-    if profile_kernel:
-        ms, n = ctypes.c_double(0), ctypes.c_int(0)
-        B._check(B.lib.tad_profile_end(ctypes.byref(ms), ctypes.byref(n)), "tad_profile_end")
-        dom_ms, dom_n = (ms.value / n.value if n.value else None), n.value
-    # separate forward / backward split (outside the timed region) with stream events
+    ms, n = ctypes.c_double(0), ctypes.c_int(0)
+    B._check(B.lib.tad_profile_end(ctypes.byref(ms), ctypes.byref(n)), "tad_profile_end")
+    dom_ms = ms.value / n.value if n.value else None
+    # forward / backward split (outside the timed region) with events on the stream the kernels run on
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    args, df, f, grads, ws = sets[0]
     ev[0].record()
     plan.forward(args, out=f, ws=ws)
     ev[1].record()
@@ -112,8 +133,22 @@ def run_gpu(name, steps, warmup, profile_kernel=True):
     return dict(workload=w.name, ms_per_step=ms_step, elements=elems, bytes=nbytes,
                 elements_per_s=elems / (ms_step * 1e-3), algorithmic_gbs=nbytes / (ms_step * 1e-3) / 1e9,
                 ms_forward=ev[0].elapsed_time(ev[1]), ms_backward=ev[1].elapsed_time(ev[2]),
-                dominant_kernel=dom_kernel, dominant_ms=dom_ms, dominant_launches=dom_n,
-                dominant_bytes=dom_bytes, families=families, dtype=w.expr.dtype)
+                dominant=dom, dominant_ms=dom_ms, dominant_launches=n.value, families=families,
+                dtype=w.expr.dtype, buffer_sets=len(sets), footprint_bytes_per_set=foot)
+
+
+def roofline(r):
+    dom, ms = r["dominant"], r["dominant_ms"]
+    if not ms or not dom["per_launch"]:
+        return {"bound": dom["bound"], "kernel": dom["kernel"], "achieved": None, "peak": None, "unit": None,
+                "frac": None, "traffic": None}
+    if dom["bound"] == "mfma":
+        achieved, peak, unit = dom["per_launch"] / (ms * 1e-3) / 1e12, FP32_MFMA_TFLOPS, "TFLOP/s"
+    else:
+        achieved, peak, unit = dom["per_launch"] / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+    return {"bound": dom["bound"], "kernel": dom["kernel"], "achieved": achieved, "peak": peak, "unit": unit,
+            "frac": achieved / peak, "traffic": None, "avg_kernel_ms": ms, "launches": r["dominant_launches"],
+            "algorithmic_per_launch": dom["per_launch"]}
 
 
 def run_cpu_oracle(name):
@@ -136,8 +171,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3")
-    ap.add_argument("--others", action="store_true", help="also time the other configurations (extra keys)")
+    ap.add_argument("--no-others", action="store_true", help="skip the other configurations (extra keys)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy 5 times (reference point for HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -148,9 +185,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
 
-    r = run_gpu(a.workload, a.steps, a.warmup)
-    dom_s = (r["dominant_ms"] or float("nan")) * 1e-3
-    achieved = r["dominant_bytes"] / dom_s / 1e9 if r["dominant_ms"] else None
+    if a.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    rot = 0 if a.workload == "cfg3" else ROTATE_BYTES
+    r = run_gpu(a.workload, a.steps, a.warmup, rotate_bytes=rot)
     out = {
         "metric": "fwd+bwd tensor elements/s; achieved HBM GB/s or FLOP/s vs MI355X peak",
         "value": r["elements_per_s"], "unit": "elements/s", "n_gpus": 1, "steps": a.steps,
@@ -160,21 +203,26 @@ def main():
                    "elements_per_step": r["elements"], "algorithmic_bytes_per_step": r["bytes"],
                    "ms_forward": r["ms_forward"], "ms_backward": r["ms_backward"],
                    "step_algorithmic_GBs": r["algorithmic_gbs"],
-                   "step_frac_of_hbm_peak": r["algorithmic_gbs"] / HBM_PEAK_GBS},
-        "roofline": {"bound": "hbm", "kernel": r["dominant_kernel"], "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
-                     "avg_kernel_ms": r["dominant_ms"], "launches": r["dominant_launches"],
-                     "algorithmic_bytes_per_launch": r["dominant_bytes"]},
+                   "step_frac_of_hbm_peak": r["algorithmic_gbs"] / HBM_PEAK_GBS,
+                   "buffer_sets": r["buffer_sets"]},
+        "roofline": roofline(r),
     }
-    if a.others:
+    if not a.no_others:
         per = {}
-        for name in ("cfg2_1", "cfg2_2", "cfg2_3", "cfg4", "cfg5"):
+        for name in ("cfg1", "cfg2_1", "cfg2_2", "cfg2_3", "cfg4", "cfg5"):
+            if name == a.workload:
+                continue
             try:
-                q = run_gpu(name, a.steps, a.warmup, profile_kernel=False)
-                per[name] = {k: q[k] for k in ("workload", "ms_per_step", "ms_forward", "ms_backward",
-                                               "elements_per_s", "algorithmic_gbs", "families")}
-                per[name]["frac_of_hbm_peak"] = q["algorithmic_gbs"] / HBM_PEAK_GBS
+                q = run_gpu(name, a.steps, a.warmup, rotate_bytes=ROTATE_BYTES)
+                e = {k: q[k] for k in ("workload", "ms_per_step", "ms_forward", "ms_backward", "elements_per_s",
+                                       "algorithmic_gbs", "families", "buffer_sets")}
+                e["frac_of_hbm_peak"] = q["algorithmic_gbs"] / HBM_PEAK_GBS
+                if q["dominant"]["bound"] == "mfma":
+                    tf = q["dominant"]["step_flops"] / (q["ms_per_step"] * 1e-3) / 1e12
+                    e["step_TFLOPs"] = tf
+                    e["step_frac_of_fp32_mfma_peak"] = tf / FP32_MFMA_TFLOPS
+                e["roofline"] = roofline(q)
+                per[name] = e
             except Exception as ex:  # report, never hide
                 per[name] = {"error": repr(ex)}
         out["per_config"] = per

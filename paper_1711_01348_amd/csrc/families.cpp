@@ -133,9 +133,14 @@ static bool match_patterns(tad_plan &pl) {
         // kernel coordinate = j over its whole range, i = y_0
         if (e.f_shape[1] % 4 != 0 || px.smith.R != 1 || px.K.cols != 1) return false;
         if (px.VR(0, 0) != 1 || px.VR(1, 0) != 0 || px.K(0, 0) != 0 || px.K(1, 0) * px.K(1, 0) != 1) return false;
+        if (!y_is_beta(px.dev) || !flatten_feas(px.dev, pl.fast.feas)) return false;
         fam = TAD_FAMILY_ROW_REDUCE;
     } else if (e.n_f == 1 && index_is(x, 1, {{1}, {1}})) {
         if (x.shape[1] % 4 != 0 || px.smith.R != 1 || px.K.cols != 0 || px.VR(0, 0) != 1) return false;
+        // transformed index y = first gradient index; one cokernel row +-(1, -1)
+        const GatherPlan &g = px.dev;
+        if (g.nC != 1 || g.C[0][0] + g.C[0][1] != 0 || g.C[0][0] * g.C[0][0] != 1) return false;
+        if (g.diag[0] != 1 || g.U[0][0] != 1 || g.U[0][1] != 0 || !flatten_feas(g, pl.fast.feas)) return false;
         pl.fast.c_ld = x.shape[1];
         fam = TAD_FAMILY_DIAGONAL;
     } else if (e.n_f == 2 && index_is(x, 2, {{1, 1}})) {

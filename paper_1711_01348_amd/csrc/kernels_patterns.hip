@@ -64,31 +64,35 @@ __global__ __launch_bounds__(256) void k_rowreduce_forward(const float *__restri
     }
 }
 
-// one wave per row of df; the j range of the plan is the whole row (collapsed kernel coordinate)
+// one wave per row of df; the j range of the plan is the whole row (collapsed kernel coordinate);
+// y = beta for this family (checked on the host), the feasibility rows zero the elements of a longer x
 template <int BODY>
-__global__ __launch_bounds__(256) void k_rowreduce_backward(const GatherPlan P, const float *__restrict__ x,
+__global__ __launch_bounds__(256) void k_rowreduce_backward(const FlatFeas feas, const float *__restrict__ x,
                                                             const float *__restrict__ df, float *__restrict__ dx,
                                                             int n_x, int J) {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (i >= n_x) return;
-    int32_t beta[kMaxRank] = {i, 0, 0, 0}, y[kMaxRank] = {0, 0, 0, 0};
-    if (!gather_prepare(P, beta, y)) {   // x longer than the referenced range: zero gradient
+    const int32_t y[3] = {i, 0, 0};
+    if (!flat_feasible(feas, y)) {
         if (lane == 63) dx[i] = 0.f;
         return;
     }
-    const float *row = df + (size_t)y[0] * J;
-    float4v acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0, acc2 = acc0, acc3 = acc0;
+    const float *row = df + (size_t)i * J;
+    float4v acc[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
     int j = lane * 4;
-    for (; j + 768 < J; j += 1024) {
-        acc0 += *reinterpret_cast<const float4v *>(row + j);
-        acc1 += *reinterpret_cast<const float4v *>(row + j + 256);
-        acc2 += *reinterpret_cast<const float4v *>(row + j + 512);
-        acc3 += *reinterpret_cast<const float4v *>(row + j + 768);
+    for (; j + 7 * 256 < J; j += 8 * 256) {
+        float4v v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const float4v *>(row + j + u * 256));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[u] += v[u];
     }
-    for (; j < J; j += 256) acc0 += *reinterpret_cast<const float4v *>(row + j);
-    acc0 = (acc0 + acc1) + (acc2 + acc3);
-    const float s = wave_sum63((acc0[0] + acc0[1]) + (acc0[2] + acc0[3]));
+    for (; j < J; j += 256) acc[0] += *reinterpret_cast<const float4v *>(row + j);
+    const float4v t = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    const float s = wave_sum63((t[0] + t[1]) + (t[2] + t[3]));
     if (lane == 63) dx[i] = dphi<BODY>(x[i]) * s;
 }
 
@@ -104,23 +108,25 @@ __global__ __launch_bounds__(256) void k_diagonal_forward(const float *__restric
 }
 
 // dense write of dx (rows x ld): zeros, except where the plan's masks pass (the diagonal inside the range)
-// block: 1024 columns x 8 rows
+// block: 1024 columns x 16 rows
 template <int BODY>
-__global__ __launch_bounds__(256) void k_diagonal_backward(const GatherPlan P, const float *__restrict__ x,
+__global__ __launch_bounds__(256) void k_diagonal_backward(const FlatFeas feas, const float *__restrict__ x,
                                                            const float *__restrict__ df, float *__restrict__ dx,
                                                            int rows, int ld) {
     const int c0 = blockIdx.x * 1024 + threadIdx.x * 4;
-    const int r0 = blockIdx.y * 8;
+    const int r0 = blockIdx.y * 16;
     if (c0 >= ld) return;
-    const int nr = min(8, rows - r0);
+    const int nr = min(16, rows - r0);
     for (int r = 0; r < nr; ++r) {
         const int row = r0 + r;
         float4v o = {0.f, 0.f, 0.f, 0.f};
         if (row >= c0 && row < c0 + 4) {
-            int32_t beta[kMaxRank] = {row, row, 0, 0}, y[kMaxRank] = {0, 0, 0, 0};
-            if (gather_prepare(P, beta, y)) {
+            // on the diagonal the cokernel condition holds; the transformed index is y = row (checked on the
+            // host); the feasibility rows remove rows beyond the range of f
+            const int32_t y[3] = {row, 0, 0};
+            if (flat_feasible(feas, y)) {
                 const float xv = x[(size_t)row * ld + row];
-                o[row - c0] = df[y[0]] * dphi<BODY>(xv);
+                o[row - c0] = df[row] * dphi<BODY>(xv);
             }
         }
         *reinterpret_cast<float4v *>(dx + (size_t)row * ld + c0) = o;
@@ -177,29 +183,40 @@ __global__ __launch_bounds__(256) void k_antidiag_backward(const FlatFeas feas, 
         hi = min(hi, zhi);
         const long long step = (long long)iz * J + jz;
         const float *p = df + ((long long)(base + iz * lo) * J + (jy * y[0] + jz * lo));
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        float acc[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[u] = 0.f;
         int w = lo;
-        for (; w + 3 <= hi; w += 4) {
-            s0 += p[0];
-            s1 += p[step];
-            s2 += p[2 * step];
-            s3 += p[3 * step];
-            p += 4 * step;
+        for (; w + 7 <= hi; w += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + u * step);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc[u] += v[u];
+            p += 8 * step;
         }
-        for (; w <= hi; ++w) { s0 += *p; p += step; }
-        s = (s0 + s1) + (s2 + s3);
+        for (; w <= hi; ++w) { acc[0] += *p; p += step; }
+        s = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
     }
     part[(size_t)t * n_x + m] = s;
 }
 
+// 64 outputs per block; the four waves split the tiles and are combined in fixed order
 template <int BODY>
 __global__ __launch_bounds__(256) void k_antidiag_finish(const float *__restrict__ x, const float *__restrict__ part,
                                                          int n_tiles, float *__restrict__ dx, int n_x) {
-    const int m = blockIdx.x * 256 + threadIdx.x;
-    if (m >= n_x) return;
+    __shared__ double red[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = blockIdx.x * 64 + lane;
     double s = 0.0;
-    for (int t = 0; t < n_tiles; ++t) s += (double)part[(size_t)t * n_x + m];
-    dx[m] = (float)((double)dphi<BODY>(x[m]) * s);
+    if (m < n_x)
+        for (int t = wave; t < n_tiles; t += 4) s += (double)part[(size_t)t * n_x + m];
+    red[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && m < n_x) {
+        s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+        dx[m] = (float)((double)dphi<BODY>(x[m]) * s);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -245,17 +262,17 @@ int pattern_backward(const tad_plan &pl, const void *const *args, const void *df
     float *dx = (float *)dx_[0];
     const int I = (int)pl.fast.I, J = (int)pl.fast.J;
     const int n_x = (int)pl.arg_count[0];
-    const GatherPlan &P = pl.ap[0].dev;
     switch (pl.ap[0].family) {
     case TAD_FAMILY_ROW_REDUCE:
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_rowreduce_backward", (k_rowreduce_backward<B_>),
-                                                  dim3((n_x + 3) / 4), dim3(256), 0, s, P, x, df, dx, n_x, J));
+                                                  dim3((n_x + 3) / 4), dim3(256), 0, s, pl.fast.feas, x, df, dx,
+                                                  n_x, J));
         break;
     case TAD_FAMILY_DIAGONAL: {
         const int rows = (int)pl.args[0].shape[0], ld = (int)pl.args[0].shape[1];
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_diagonal_backward", (k_diagonal_backward<B_>),
-                                                  dim3((ld + 1023) / 1024, (rows + 7) / 8), dim3(256), 0, s, P, x, df,
-                                                  dx, rows, ld));
+                                                  dim3((ld + 1023) / 1024, (rows + 15) / 16), dim3(256), 0, s,
+                                                  pl.fast.feas, x, df, dx, rows, ld));
         break;
     }
     case TAD_FAMILY_ANTIDIAGONAL: {
@@ -266,7 +283,7 @@ int pattern_backward(const tad_plan &pl, const void *const *args, const void *df
                    J);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_antidiag_finish", (k_antidiag_finish<B_>),
-                                                  dim3((n_x + 255) / 256), dim3(256), 0, s, x, part, n_tiles, dx, n_x));
+                                                  dim3((n_x + 63) / 64), dim3(256), 0, s, x, part, n_tiles, dx, n_x));
         break;
     }
     default: return TAD_EUNSUPPORTED;
