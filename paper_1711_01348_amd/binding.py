@@ -59,6 +59,10 @@ class TadError(RuntimeError):
 
 
 def _load():
+    # PyTorch carries its own copy of the HIP runtime.  It must be loaded first so that libtad.so binds to
+    # the same runtime instance as the streams and allocations it is handed; two runtimes in one process
+    # make every launch fail.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
     lib = ctypes.CDLL(LIB_PATH)

@@ -8,6 +8,7 @@
 #include "bodies.h"
 #include "launch.h"
 #include "plan_dev.h"
+#include "profile.h"
 
 namespace tad {
 
@@ -112,17 +113,16 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[q];
     if (fout) {
         int nf = (int)pl.f_count;
-        hipLaunchKernelGGL((k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd, A,
-                           static_cast<T *>(fout), nf);
+        TAD_LAUNCH("k_generic_forward", (k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd, A,
+                   static_cast<T *>(fout), nf);
         return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
     }
     for (size_t p = 0; p < pl.args.size(); ++p) {
         if (!dx[p] || pl.ap[p].family != TAD_FAMILY_GENERIC) continue;
         if (!pl.ap[p].derived) return TAD_EINVAL;
         int n = (int)pl.arg_count[p];
-        hipLaunchKernelGGL((k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[p].dev,
-                           (int)p, A, static_cast<const T *>(f), static_cast<const T *>(df),
-                           static_cast<T *>(dx[p]), n);
+        TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[p].dev,
+                   (int)p, A, static_cast<const T *>(f), static_cast<const T *>(df), static_cast<T *>(dx[p]), n);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

@@ -15,8 +15,11 @@ struct ProfileScope {
 
 }  // namespace tad
 
+// A launch is checked with hipGetLastError() right after it; an error left behind by an earlier, unrelated
+// runtime call of this thread is discarded first so that it is not mistaken for a launch failure.
 #define TAD_LAUNCH(name, kernel, grid, block, shmem, stream, ...)              \
     do {                                                                       \
+        (void)hipGetLastError();                                               \
         tad::ProfileScope _ps(name, stream);                                   \
         hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);   \
     } while (0)
