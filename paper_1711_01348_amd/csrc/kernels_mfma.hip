@@ -6,7 +6,7 @@
 //   backward  G_ij = df_ij f_ij
 //             P = G b        (I x K, contraction over the collapsed kernel coordinate j, split in chunks)
 //             T = (c G)^T a  (J x K, contraction over the collapsed kernel coordinate i, split in chunks)
-//             r_i = sum_j G_ij, Q_i = sum_j G_ij |b_j|^2, t_j = sum_i c_ii G_ij   (streaming pass)
+//             r_i = sum_j G_ij, Q_i = sum_j G_ij |b_j|^2, t_j = sum_i c_ii G_ij   (accumulated while G is staged)
 //             da_ik = -2 c_ii (a_ik r_i + P_ik)      db_jk = -2 (T_jk + b_jk t_j)
 //             dc_ii = -(|a_i|^2 r_i + 2 sum_k a_ik P_ik + Q_i)      dd_m = -3 d_m^2 sum_{i in window(m)} r_i
 // All partial results are combined in a fixed order (no atomics).
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void k_mfma_prep(const float *__restrict__ a, 
 constexpr int MF_KT = 32;
 constexpr int MF_LD = 33;   // odd row stride: conflict-free ds_read_b32 of [row][k] tiles
 
-__global__ __launch_bounds__(256) void k_mfma_forward(const float *__restrict__ a, const float *__restrict__ b,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_mfma_forward(const float *__restrict__ a, const float *__restrict__ b,
                                                       const float *__restrict__ rowv, const float *__restrict__ nb,
                                                       float *__restrict__ f, int I, int J, int K) {
     __shared__ float As[128][MF_LD];
@@ -174,12 +174,18 @@ __global__ __launch_bounds__(256) void k_mfma_forward(const float *__restrict__ 
 //   TRANS_A = true:   M = j, contraction over i in [cs, ce):  A[m][kk] = c_ii df f (read transposed), B[kk][n] = a[i][k]
 // out[(split * Mtot + m) * K + n]
 // ---------------------------------------------------------------------------------------------
+// While G is staged, the same thread keeps meeting the same rows (TRANS_A = false) or the same columns
+// (TRANS_A = true), so the plain sums over the collapsed index are accumulated on the side:
+//   TRANS_A = false:  sums[(split * 2 + 0) * I + i] = sum_j G_ij,  sums[(split * 2 + 1) * I + i] = sum_j G_ij |b_j|^2
+//   TRANS_A = true:   sums[split * J + j] = sum_i c_ii G_ij
 template <bool TRANS_A>
 __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__ f, const float *__restrict__ df,
                                                        const float *__restrict__ bmat, const float *__restrict__ rowv,
-                                                       float *__restrict__ out, int I, int J, int K, int chunk) {
+                                                       const float *__restrict__ nb, float *__restrict__ out,
+                                                       float *__restrict__ sums, int I, int J, int K, int chunk) {
     __shared__ float As[TRANS_A ? 32 : 64][TRANS_A ? 64 : MF_LD];
     __shared__ float Bs[32][256];
+    __shared__ float tred[4][64];
     const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
     const int Mtot = TRANS_A ? J : I, Ctot = TRANS_A ? I : J;
     const int m0 = blockIdx.x * 64, split = blockIdx.y, n0 = blockIdx.z * 256;
@@ -188,6 +194,8 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
     zero_acc(acc);
     float4v ga[2], gb[8];
     const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    float sr[2] = {0.f, 0.f}, sq[2] = {0.f, 0.f};   // TRANS_A = false: row sums of the thread's two rows
+    float4v st = zero4;                               // TRANS_A = true: column sums of the thread's four columns
     auto gload = [&](int c0) {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
@@ -198,6 +206,9 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
                 if (i < I && j < ce) {
                     const size_t off = (size_t)i * J + j;
                     ga[p] = *reinterpret_cast<const float4v *>(df + off) * *reinterpret_cast<const float4v *>(f + off);
+                    const float4v nv = *reinterpret_cast<const float4v *>(nb + j);
+                    sr[p] += (ga[p][0] + ga[p][1]) + (ga[p][2] + ga[p][3]);
+                    sq[p] += (ga[p][0] * nv[0] + ga[p][1] * nv[1]) + (ga[p][2] * nv[2] + ga[p][3] * nv[3]);
                 } else ga[p] = zero4;
             } else {
                 const int kk = idx >> 4, q = idx & 15;            // i = c0 + kk, j = m0 + 4 q
@@ -206,6 +217,7 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
                     const size_t off = (size_t)i * J + j;
                     ga[p] = *reinterpret_cast<const float4v *>(df + off) * *reinterpret_cast<const float4v *>(f + off) *
                             rowv[i * 4 + 3];
+                    st += ga[p];
                 } else ga[p] = zero4;
             }
         }
@@ -267,96 +279,36 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
                 if (m < Mtot && n < K) out[((size_t)split * Mtot + m) * K + n] = acc[tm][tn][r];
             }
     }
-}
-
-// ---------------------------------------------------------------------------------------------
-// streaming sums r_i, Q_i (row partials per column tile) and t_j (column partials per row tile)
-// block: 4 waves over the same 512 columns, 256 rows (a quarter per wave), 4 rows per step
-// ---------------------------------------------------------------------------------------------
-constexpr int MS_RB = 4;
-
-__global__ __launch_bounds__(256) void k_mfma_sums(const float *__restrict__ f, const float *__restrict__ df,
-                                                   const float *__restrict__ rowv, const float *__restrict__ nb,
-                                                   float *__restrict__ rowp, float *__restrict__ colp, int I, int J) {
-    constexpr int WR = MS_TI / 4;
-    __shared__ float rows_out[2][MS_TI];
-    __shared__ float cred[4][MS_TJ];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i0 = blockIdx.y * MS_TI, jb = blockIdx.x * MS_TJ;
-    int jc[2];
-    bool live[2];
-    float nbv[2][4], tc[2][4];
+    if (blockIdx.z != 0) return;
+    if (!TRANS_A) {
+        // eight consecutive lanes share a row: add them in a fixed order
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        jc[h] = jb + h * 256 + lane * 4;
-        live[h] = jc[h] < J;
+        for (int p = 0; p < 2; ++p) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            nbv[h][v] = live[h] ? nb[jc[h] + v] : 0.f;
-            tc[h][v] = 0.f;
-        }
-    }
-    const int r0 = wave * WR;
-    const int rows = max(0, min(WR, I - (i0 + r0)));
-    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
-    for (int rb = 0; rb < WR; rb += MS_RB) {
-        float pr[MS_RB], pq[MS_RB];
-#pragma unroll
-        for (int r = 0; r < MS_RB; ++r) pr[r] = pq[r] = 0.f;
-        if (rb < rows) {
-            float4v fv[MS_RB][2], dv[MS_RB][2];
-#pragma unroll
-            for (int r = 0; r < MS_RB; ++r)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const bool ok = live[h] && (rb + r) < rows;
-                    const size_t off = (size_t)(i0 + r0 + rb + r) * J + jc[h];
-                    fv[r][h] = ok ? *reinterpret_cast<const float4v *>(f + off) : zero4;
-                    dv[r][h] = ok ? *reinterpret_cast<const float4v *>(df + off) : zero4;
-                }
-#pragma unroll
-            for (int r = 0; r < MS_RB; ++r) {
-                const int i = i0 + r0 + rb + r;
-                const float ci = i < I ? rowv[i * 4 + 3] : 0.f;
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float g = dv[r][h][v] * fv[r][h][v];
-                        pr[r] += g;
-                        pq[r] = fmaf(g, nbv[h][v], pq[r]);
-                        tc[h][v] = fmaf(g, ci, tc[h][v]);
-                    }
+            for (int m = 1; m <= 4; m <<= 1) {
+                sr[p] += __shfl_xor(sr[p], m, 64);
+                sq[p] += __shfl_xor(sq[p], m, 64);
             }
-#pragma unroll
-            for (int r = 0; r < MS_RB; ++r) {
-                pr[r] = wave_sum63m(pr[r]);
-                pq[r] = wave_sum63m(pq[r]);
+            const int i = m0 + (tid >> 3) + 32 * p;
+            if ((tid & 7) == 0 && i < I) {
+                sums[((size_t)split * 2 + 0) * I + i] = sr[p];
+                sums[((size_t)split * 2 + 1) * I + i] = sq[p];
             }
         }
-        if (lane == 63) {
+    } else {
+        // lanes q, q+16, q+32, q+48 of every wave hold the same four columns: add within the wave, then the waves
 #pragma unroll
-            for (int r = 0; r < MS_RB; ++r) {
-                rows_out[0][r0 + rb + r] = pr[r];
-                rows_out[1][r0 + rb + r] = pq[r];
-            }
+        for (int e = 0; e < 4; ++e) {
+            st[e] += __shfl_xor(st[e], 16, 64);
+            st[e] += __shfl_xor(st[e], 32, 64);
         }
-    }
+        if (lane < 16)
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) cred[wave][h * 256 + lane * 4 + v] = tc[h][v];
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int col = h * 256 + tid, j = jb + col;
-        if (j < J) colp[(size_t)blockIdx.y * J + j] = (cred[0][col] + cred[1][col]) + (cred[2][col] + cred[3][col]);
-    }
-    for (int t = tid; t < MS_TI; t += 256) {
-        const int i = i0 + t;
-        if (i < I) {
-            rowp[((size_t)blockIdx.x * 2 + 0) * I + i] = rows_out[0][t];
-            rowp[((size_t)blockIdx.x * 2 + 1) * I + i] = rows_out[1][t];
+            for (int e = 0; e < 4; ++e) tred[wn][lane * 4 + e] = st[e];
+        __syncthreads();
+        if (tid < 64) {
+            const int j = m0 + tid;
+            if (j < J) sums[(size_t)split * J + j] = (tred[0][tid] + tred[1][tid]) + (tred[2][tid] + tred[3][tid]);
         }
     }
 }
@@ -371,34 +323,41 @@ __global__ __launch_bounds__(256) void k_mfma_fill_zero(float *__restrict__ p, l
 }
 
 // ---------------------------------------------------------------------------------------------
-// finishing: one wave per output row.  Blocks [0, blocks_rows) : rows i (da, dc_ii, r_i); the rest: rows j (db)
+// finishing: one wave per output row, lane owns four consecutive k.
+// Blocks [0, blocks_rows): rows i (da, dc_ii, r_i); the rest: rows j (db).  Fixed summation order.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_mfma_finish(const float *__restrict__ a, const float *__restrict__ b,
                                                      const float *__restrict__ rowv, const float *__restrict__ Ppart,
                                                      const float *__restrict__ Tpart, int n_split,
-                                                     const float *__restrict__ rowp, int n_jt,
-                                                     const float *__restrict__ colp, int n_it, float *__restrict__ da,
-                                                     float *__restrict__ db, float *__restrict__ dc,
-                                                     float *__restrict__ rsum, int I, int J, int K, int c_ld,
-                                                     int blocks_rows) {
+                                                     const float *__restrict__ rowp, const float *__restrict__ colp,
+                                                     float *__restrict__ da, float *__restrict__ db,
+                                                     float *__restrict__ dc, float *__restrict__ rsum, int I, int J,
+                                                     int K, int c_ld, int blocks_rows) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if ((int)blockIdx.x < blocks_rows) {
         const int i = blockIdx.x * 4 + wv;
         if (i >= I) return;
         double r = 0.0, Q = 0.0;
-        for (int jt = 0; jt < n_jt; ++jt) {
-            r += (double)rowp[((size_t)jt * 2 + 0) * I + i];
-            Q += (double)rowp[((size_t)jt * 2 + 1) * I + i];
+        for (int s = 0; s < n_split; ++s) {
+            r += (double)rowp[((size_t)s * 2 + 0) * I + i];
+            Q += (double)rowp[((size_t)s * 2 + 1) * I + i];
         }
         const double ci = (double)rowv[i * 4 + 3], na = (double)rowv[i * 4 + 0];
         float cross = 0.f;
-        for (int k = lane; k < K; k += 64) {
-            double P = 0.0;
-            for (int s = 0; s < n_split; ++s) P += (double)Ppart[((size_t)s * I + i) * K + k];
-            const double ak = (double)a[(size_t)i * K + k];
-            if (da) da[(size_t)i * K + k] = (float)(-2.0 * ci * (ak * r + P));
-            cross += (float)(ak * P);
-        }
+        if (da || dc)
+            for (int k = lane * 4; k < K; k += 256) {
+                float4v P = {0.f, 0.f, 0.f, 0.f};
+                for (int s = 0; s < n_split; ++s)
+                    P += *reinterpret_cast<const float4v *>(Ppart + ((size_t)s * I + i) * K + k);
+                const float4v av = *reinterpret_cast<const float4v *>(a + (size_t)i * K + k);
+                if (da) {
+                    float4v o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (float)(-2.0 * ci * ((double)av[e] * r + (double)P[e]));
+                    *reinterpret_cast<float4v *>(da + (size_t)i * K + k) = o;
+                }
+                cross += (av[0] * P[0] + av[1] * P[1]) + (av[2] * P[2] + av[3] * P[3]);
+            }
         cross = wave_sum63m(cross);
         if (lane == 63) {
             if (dc) dc[(size_t)i * c_ld + i] = (float)(-(na * r + 2.0 * (double)cross + Q));
@@ -409,11 +368,15 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const float *__restrict__ a
     const int j = ((int)blockIdx.x - blocks_rows) * 4 + wv;
     if (j >= J || !db) return;
     double t = 0.0;
-    for (int it = 0; it < n_it; ++it) t += (double)colp[(size_t)it * J + j];
-    for (int k = lane; k < K; k += 64) {
-        double T = 0.0;
-        for (int s = 0; s < n_split; ++s) T += (double)Tpart[((size_t)s * J + j) * K + k];
-        db[(size_t)j * K + k] = (float)(-2.0 * (T + (double)b[(size_t)j * K + k] * t));
+    for (int s = 0; s < n_split; ++s) t += (double)colp[(size_t)s * J + j];
+    for (int k = lane * 4; k < K; k += 256) {
+        float4v T = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < n_split; ++s) T += *reinterpret_cast<const float4v *>(Tpart + ((size_t)s * J + j) * K + k);
+        const float4v bv = *reinterpret_cast<const float4v *>(b + (size_t)j * K + k);
+        float4v o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (float)(-2.0 * ((double)T[e] + (double)bv[e] * t));
+        *reinterpret_cast<float4v *>(db + (size_t)j * K + k) = o;
     }
 }
 
@@ -444,7 +407,7 @@ __global__ __launch_bounds__(256) void k_mfma_dd(const FlatFeas feas, const Flat
 // ---------------------------------------------------------------------------------------------
 struct MfmaWs {
     float *rowv, *nb, *Ppart, *Tpart, *rowp, *colp, *rsum;
-    int n_split, chunk_j, chunk_i, n_jt, n_it;
+    int n_split, chunk_j, chunk_i;
 };
 
 static MfmaWs carve_mfma(void *ws, int64_t I, int64_t J, int64_t K) {
@@ -452,16 +415,14 @@ static MfmaWs carve_mfma(void *ws, int64_t I, int64_t J, int64_t K) {
     w.n_split = kMfmaSplit;
     w.chunk_j = (int)(((J + kMfmaSplit - 1) / kMfmaSplit + 31) / 32 * 32);
     w.chunk_i = (int)(((I + kMfmaSplit - 1) / kMfmaSplit + 31) / 32 * 32);
-    w.n_jt = (int)((J + MS_TJ - 1) / MS_TJ);
-    w.n_it = (int)((I + MS_TI - 1) / MS_TI);
     char *p = static_cast<char *>(ws);
     auto take = [&](size_t bytes) { float *r = reinterpret_cast<float *>(p); p += align256(bytes); return r; };
     w.rowv = take((size_t)I * 16);
     w.nb = take((size_t)J * 4);
     w.Ppart = take((size_t)kMfmaSplit * I * K * 4);
     w.Tpart = take((size_t)kMfmaSplit * J * K * 4);
-    w.rowp = take((size_t)w.n_jt * 2 * I * 4);
-    w.colp = take((size_t)w.n_it * J * 4);
+    w.rowp = take((size_t)kMfmaSplit * 2 * I * 4);
+    w.colp = take((size_t)kMfmaSplit * J * 4);
     w.rsum = take((size_t)I * 4);
     return w;
 }
@@ -492,18 +453,14 @@ int mfma_backward(const tad_plan &pl, const void *const *args, const void *f_, c
     const float *f = (const float *)f_, *df = (const float *)df_;
     int rc = prep(pl, args, w, s);
     if (rc) return rc;
-    TAD_LAUNCH("k_mfma_sums", k_mfma_sums, dim3(w.n_jt, w.n_it), dim3(256), 0, s, f, df, w.rowv, w.nb, w.rowp, w.colp,
-               I, J);
-    if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     const int nz = (K + 255) / 256;
-    if (dx[0] || dx[2]) {
-        TAD_LAUNCH("k_mfma_backward", (k_mfma_backward<false>), dim3((I + 63) / 64, w.n_split, nz), dim3(256), 0, s, f,
-                   df, b, w.rowv, w.Ppart, I, J, K, w.chunk_j);
-        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
-    }
+    // the row pass always runs: r_i feeds da, dc and dd; the column pass only for db
+    TAD_LAUNCH("k_mfma_backward", (k_mfma_backward<false>), dim3((I + 63) / 64, w.n_split, nz), dim3(256), 0, s, f, df,
+               b, w.rowv, w.nb, w.Ppart, w.rowp, I, J, K, w.chunk_j);
+    if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     if (dx[1]) {
         TAD_LAUNCH("k_mfma_backward", (k_mfma_backward<true>), dim3((J + 63) / 64, w.n_split, nz), dim3(256), 0, s, f,
-                   df, a, w.rowv, w.Tpart, I, J, K, w.chunk_i);
+                   df, a, w.rowv, w.nb, w.Tpart, w.colp, I, J, K, w.chunk_i);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     if (dx[2]) {
@@ -514,8 +471,7 @@ int mfma_backward(const tad_plan &pl, const void *const *args, const void *f_, c
     }
     const int br = (I + 3) / 4, bc = dx[1] ? (J + 3) / 4 : 0;
     TAD_LAUNCH("k_mfma_finish", k_mfma_finish, dim3(br + bc), dim3(256), 0, s, a, b, w.rowv, w.Ppart, w.Tpart,
-               (dx[0] || dx[2]) ? w.n_split : 0, w.rowp, w.n_jt, w.colp, w.n_it, (float *)dx[0], (float *)dx[1],
-               (float *)dx[2], w.rsum, I, J, K, c_ld, br);
+               w.n_split, w.rowp, w.colp, (float *)dx[0], (float *)dx[1], (float *)dx[2], w.rsum, I, J, K, c_ld, br);
     if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     if (dx[3]) {
         const int n_d = (int)pl.arg_count[3];

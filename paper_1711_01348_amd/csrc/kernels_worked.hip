@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void k_worked_forward(const float *__restrict_
             }
             e[v] = __builtin_amdgcn_exp2f(fmaf(cs, s, Ds));
         }
-        *reinterpret_cast<float4v *>(fp) = e;
+        __builtin_nontemporal_store(e, reinterpret_cast<float4v *>(fp));
         fp += J;
     }
 }
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, long l
     const float4v z = {0.f, 0.f, 0.f, 0.f};
     const long long stride = (long long)gridDim.x * 256;
     for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < n4; q += stride)
-        reinterpret_cast<float4v *>(p)[q] = z;
+        __builtin_nontemporal_store(z, reinterpret_cast<float4v *>(p) + q);
     if (blockIdx.x == 0 && threadIdx.x < (int)(n & 3)) p[(n4 << 2) + threadIdx.x] = 0.f;
 }
 

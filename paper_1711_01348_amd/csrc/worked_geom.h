@@ -20,12 +20,10 @@ inline size_t worked_workspace_bytes(int64_t I, int64_t J, int64_t K) {
 
 // long summed index (MFMA family): split of the collapsed contraction, tiles of the streaming sums pass
 constexpr int kMfmaSplit = 8;
-constexpr int MS_TI = 256, MS_TJ = 512;
 inline size_t mfma_workspace_bytes(int64_t I, int64_t J, int64_t K) {
-    size_t n_jt = (size_t)((J + MS_TJ - 1) / MS_TJ), n_it = (size_t)((I + MS_TI - 1) / MS_TI);
     return align256((size_t)I * 16) + align256((size_t)J * 4) + align256((size_t)kMfmaSplit * I * K * 4) +
-           align256((size_t)kMfmaSplit * J * K * 4) + align256(n_jt * 2 * I * 4) + align256(n_it * J * 4) +
-           align256((size_t)I * 4);
+           align256((size_t)kMfmaSplit * J * K * 4) + align256((size_t)kMfmaSplit * 2 * I * 4) +
+           align256((size_t)kMfmaSplit * J * 4) + align256((size_t)I * 4);
 }
 
 constexpr int AD_BTI_ROWS = 128;   // rows per backward tile of the antidiagonal pattern
