@@ -102,9 +102,10 @@ constexpr int MF_LD = 33;   // odd row stride: conflict-free ds_read_b32 of [row
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_mfma_forward(const float *__restrict__ a, const float *__restrict__ b,
                                                       const float *__restrict__ rowv, const float *__restrict__ nb,
                                                       float *__restrict__ f, int I, int J, int K) {
-    __shared__ float As[128][MF_LD];
-    __shared__ float Bs[128][MF_LD];
+    __shared__ float smem[2 * 128 * MF_LD];   // A tile then B tile; reused as the output stage in the epilogue
     __shared__ float rv[128][4];
+    float (*As)[MF_LD] = reinterpret_cast<float (*)[MF_LD]>(smem);
+    float (*Bs)[MF_LD] = reinterpret_cast<float (*)[MF_LD]>(smem + 128 * MF_LD);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int i0 = blockIdx.y * 128, j0 = blockIdx.x * 128;
@@ -150,21 +151,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         }
         __syncthreads();
     }
-    // epilogue: f = exp2(c' (|a|^2 + |b|^2 + 2 a.b) + D')
+    // epilogue: f = exp2(c' (|a|^2 + |b|^2 + 2 a.b) + D').  Each wave stages 32 x 64 results at a time in its own
+    // quarter of the tile memory (32 rows of 66 floats) and writes them as 16-byte stores, 256 bytes per row.
+    // (the last barrier of the loop guarantees that nobody still reads the tiles)
+    float *stage = smem + wave * (32 * 66);
+    constexpr int kStageOk = (4 * 32 * 66 <= 2 * 128 * MF_LD) ? 1 : -1;
+    static_assert(kStageOk == 1, "output stage does not fit in the tile memory");
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-        const int j = j0 + wn * 64 + tn * 32 + mrow;
-        const float nbj = j < J ? nb[j] : 0.f;
+    for (int tm = 0; tm < 2; ++tm) {
 #pragma unroll
-        for (int tm = 0; tm < 2; ++tm)
+        for (int tn = 0; tn < 2; ++tn) {
+            const int j = j0 + wn * 64 + tn * 32 + mrow;
+            const float nbj = j < J ? nb[j] : 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = wm * 64 + tm * 32 + acc_row(r, lane);
-                const int i = i0 + m;
+                const int mloc = acc_row(r, lane), m = wm * 64 + tm * 32 + mloc;
                 const float s = rv[m][0] + nbj + 2.f * acc[tm][tn][r];
-                const float val = __builtin_amdgcn_exp2f(fmaf(rv[m][1], s, rv[m][2]));
-                if (i < I && j < J) f[(size_t)i * J + j] = val;
+                stage[mloc * 66 + tn * 32 + mrow] = __builtin_amdgcn_exp2f(fmaf(rv[m][1], s, rv[m][2]));
             }
+        }
+        // the wave reads back only what it wrote itself: no barrier needed, LDS operations of a wave are ordered
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int rl = it * 4 + (lane >> 4), c = (lane & 15) * 4;
+            const int i = i0 + wm * 64 + tm * 32 + rl, j = j0 + wn * 64 + c;
+            if (i < I && j < J) {   // J % 4 == 0: the four columns exist together
+                const float4v v = {stage[rl * 66 + c], stage[rl * 66 + c + 1], stage[rl * 66 + c + 2],
+                                   stage[rl * 66 + c + 3]};
+                *reinterpret_cast<float4v *>(f + (size_t)i * J + j) = v;
+            }
+        }
     }
 }
 
