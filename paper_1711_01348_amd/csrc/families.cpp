@@ -7,8 +7,16 @@
 
 namespace tad {
 
+// 24-bit safety of the loop-free form: every coefficient and every index extent below 2^23
+static bool fits24(int64_t v) { return v > -(1 << 23) && v < (1 << 23); }
+static bool extents_fit24(const GatherPlan &g) {
+    for (int r = 0; r < g.rank; ++r)
+        if (!fits24(g.shape[r])) return false;
+    return true;
+}
+
 bool flatten_level(const GatherPlan &g, int level, FlatLevel &out) {
-    if (level < 0 || level >= g.kappa || g.R > kFlatY) return false;
+    if (level < 0 || level >= g.kappa || g.R > kFlatY || !extents_fit24(g)) return false;
     const int nl = g.lo_end[level] - g.lo_begin[level], nh = g.hi_end[level] - g.hi_begin[level];
     if (nl > kFlatRows || nh > kFlatRows) return false;
     for (int r = 0; r < kFlatRows; ++r) {
@@ -20,6 +28,8 @@ bool flatten_level(const GatherPlan &g, int level, FlatLevel &out) {
         const GRow &row = g.rows[(r < nl ? g.lo_begin[level] : g.hi_begin[level] - nl) + r];
         for (int m = 0; m < kMaxKernel; ++m)
             if (row.kz[m] != 0) return false;
+        for (int c = 0; c < g.R; ++c)
+            if (!fits24(row.ky[c])) return false;
         if (r < nl) {
             out.ls[r] = row.scale; out.lk0[r] = row.k0;
             for (int c = 0; c < g.R; ++c) out.lky[r][c] = row.ky[c];
@@ -32,7 +42,10 @@ bool flatten_level(const GatherPlan &g, int level, FlatLevel &out) {
 }
 
 bool flatten_feas(const GatherPlan &g, FlatFeas &out) {
-    if (g.nF > kFlatFeas || g.R > kFlatY) return false;
+    if (g.nF > kFlatFeas || g.R > kFlatY || !extents_fit24(g)) return false;
+    for (int r = 0; r < g.nF; ++r)
+        for (int c = 0; c < g.R; ++c)
+            if (!fits24(g.feas[r].ky[c])) return false;
     for (int r = 0; r < kFlatFeas; ++r) {
         out.k0[r] = -1;                               // neutral: always satisfied
         for (int c = 0; c < kFlatY; ++c) out.ky[r][c] = 0;

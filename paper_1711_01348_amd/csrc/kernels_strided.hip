@@ -61,23 +61,24 @@ struct StridedDx {
 };
 
 // Block roles in one launch.
-//  * blocks [0, blocks_dx): one thread per gradient element (n, p, q) of x.  Masks and both ranges come from
+//  * blocks [blocks_dw, ...): one thread per gradient element (n, p, q) of x.  Masks and both ranges come from
 //    the plan (feasibility rows, rational range rows rounded exactly); the two ranges do not depend on each other.
-//  * the remaining blocks reduce dw over 1024 function elements each into part[block][taps].
+//  * blocks [0, blocks_dw) reduce dw over 1024 function elements each into part[block][taps].
 template <int TAPS>
 __global__ __launch_bounds__(256) void k_strided_backward(const StridedGeom g, const StridedDx D,
                                                           const float *__restrict__ x, const float *__restrict__ w,
                                                           const float *__restrict__ f, const float *__restrict__ df,
                                                           float *__restrict__ dx, float *__restrict__ part, int n_x,
-                                                          int nf, int blocks_dx) {
+                                                          int nf, int blocks_dw) {
     __shared__ float ws[kMaxTaps];
     __shared__ float red[4][TAPS];
     __shared__ int tapoff[TAPS];
     const int taps = g.U * g.V;
-    if (blockIdx.x < blocks_dx) {
+    // the few long-running dw blocks come first in launch order so that they overlap the dx stream
+    if ((int)blockIdx.x >= blocks_dw) {
         if (threadIdx.x < taps) ws[threadIdx.x] = w[threadIdx.x];
         __syncthreads();
-        const int lin = blockIdx.x * 256 + threadIdx.x;
+        const int lin = ((int)blockIdx.x - blocks_dw) * 256 + threadIdx.x;
         if (lin >= n_x) return;
         const int q = lin % g.Q, t = lin / g.Q;
         const int32_t y[3] = {t / g.P, t % g.P, q};
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(256) void k_strided_backward(const StridedGeom g, c
     }
     if (threadIdx.x < taps) tapoff[threadIdx.x] = (threadIdx.x / g.V) * g.Q + (threadIdx.x % g.V);
     __syncthreads();
-    const int blk = blockIdx.x - blocks_dx;
+    const int blk = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float acc[TAPS];
 #pragma unroll
@@ -168,7 +169,7 @@ static void launch_bwd(const tad_plan &pl, const void *const *args, const void *
     for (int m = 0; m < 2; ++m) { D.fZ[m] = (int32_t)gp.offZ[kSlotF][m]; D.wZ[m] = (int32_t)gp.offZ[1][m]; }
     TAD_LAUNCH("k_strided_backward", (k_strided_backward<TAPS>), dim3(blocks_dx + blocks_dw), dim3(256), 0, s,
                geom(pl), D, (const float *)args[0], (const float *)args[1], (const float *)f, (const float *)df,
-               (float *)dx[0], (float *)ws, (int)pl.arg_count[0], (int)pl.f_count, blocks_dx);
+               (float *)dx[0], (float *)ws, (int)pl.arg_count[0], (int)pl.f_count, blocks_dw);
 }
 
 int strided_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,

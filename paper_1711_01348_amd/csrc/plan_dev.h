@@ -141,6 +141,16 @@ struct FlatFeas {
     int32_t k0[kFlatFeas], ky[kFlatFeas][kFlatY];                    // k0 + ky . y <= 0
 };
 
+// 24-bit multiply (full rate on the GPU, a 32-bit integer multiply is quarter rate); flatten_level /
+// flatten_feas only accept plans whose coefficients and index extents stay below 2^23.
+TAD_HD int32_t mul24(int32_t a, int32_t b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __mul24(a, b);
+#else
+    return a * b;
+#endif
+}
+
 TAD_HD void flat_bounds(const FlatLevel &L, const int32_t *y, int32_t &lo, int32_t &hi) {
     int32_t l = INT32_MIN, h = INT32_MAX;
 TAD_UNROLL
@@ -148,8 +158,8 @@ TAD_UNROLL
         int32_t a = L.lk0[r], b = L.hk0[r];
 TAD_UNROLL
         for (int c = 0; c < kFlatY; ++c) {
-            a += L.lky[r][c] * y[c];
-            b += L.hky[r][c] * y[c];
+            a += mul24(L.lky[r][c], y[c]);
+            b += mul24(L.hky[r][c], y[c]);
         }
         a = ceil_div_i(a, L.ls[r]);
         b = floor_div_i(b, L.hs[r]);
@@ -166,7 +176,7 @@ TAD_UNROLL
     for (int r = 0; r < kFlatFeas; ++r) {
         int32_t s = F.k0[r];
 TAD_UNROLL
-        for (int c = 0; c < kFlatY; ++c) s += F.ky[r][c] * y[c];
+        for (int c = 0; c < kFlatY; ++c) s += mul24(F.ky[r][c], y[c]);
         ok = ok && s <= 0;
     }
     return ok;
