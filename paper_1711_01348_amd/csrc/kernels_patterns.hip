@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void k_rowreduce_forward(const float *__restri
     for (int r = 0; r < rows; ++r) {
         const float v = phi<BODY>(x[i0 + r]);
         float4v o = {v, v, v, v};
-        *reinterpret_cast<float4v *>(fp) = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<float4v *>(fp));
         fp += J;
     }
 }
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void k_diagonal_backward(const FlatFeas feas, 
                 o[row - c0] = df[row] * dphi<BODY>(xv);
             }
         }
-        *reinterpret_cast<float4v *>(dx + (size_t)row * ld + c0) = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<float4v *>(dx + (size_t)row * ld + c0));
     }
 }
 
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void k_antidiag_forward(const float *__restric
     float4v e = {phi<BODY>(xp[0]), phi<BODY>(xp[1]), phi<BODY>(xp[2]), phi<BODY>(xp[3])};
     float *fp = f + (size_t)i0 * J + j0;
     for (int r = 0; r < rows; ++r) {
-        *reinterpret_cast<float4v *>(fp) = e;
+        __builtin_nontemporal_store(e, reinterpret_cast<float4v *>(fp));
         fp += J;
         if (r + 1 < rows) {
             const float nx = phi<BODY>(xp[r + 4]);   // i0 + r + 1 + j0 + 3 <= I + J - 2: inside x

@@ -5,7 +5,7 @@
 
 namespace tad {
 
-constexpr int FWD_TI = 32;      // rows per forward block (1024 columns)
+constexpr int FWD_TI = 8;       // rows per forward block (1024 columns); small tiles measured best for write streams
 constexpr int BWD_TI = 256;     // rows per backward block
 constexpr int BWD_TJ = 512;     // columns per backward block
 constexpr int kWorkedMaxK = 8;  // longest summed index the direct (VALU) kernels are instantiated for
