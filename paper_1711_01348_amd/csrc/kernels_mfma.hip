@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void k_mfma_prep(const float *__restrict__ a, 
 constexpr int MF_KT = 32;
 constexpr int MF_LD = 33;   // odd row stride: conflict-free ds_read_b32 of [row][k] tiles
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_mfma_forward(const float *__restrict__ a, const float *__restrict__ b,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_mfma_forward(const float *__restrict__ a, const float *__restrict__ b,
                                                       const float *__restrict__ rowv, const float *__restrict__ nb,
                                                       float *__restrict__ f, int I, int J, int K) {
     __shared__ float smem[2 * 128 * MF_LD];   // A tile then B tile; reused as the output stage in the epilogue
@@ -140,14 +140,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         }
         __syncthreads();
         if (k0 + MF_KT < K) gload(k0 + MF_KT);
+        // the operands of step ks + 1 are read from LDS before the MFMAs of step ks are issued
+        float a0 = As[wm * 64 + mrow][kof], a1 = As[wm * 64 + 32 + mrow][kof];
+        float b0 = Bs[wn * 64 + mrow][kof], b1 = Bs[wn * 64 + 32 + mrow][kof];
 #pragma unroll
         for (int ks = 0; ks < MF_KT / 2; ++ks) {
-            const float a0 = As[wm * 64 + mrow][2 * ks + kof], a1 = As[wm * 64 + 32 + mrow][2 * ks + kof];
-            const float b0 = Bs[wn * 64 + mrow][2 * ks + kof], b1 = Bs[wn * 64 + 32 + mrow][2 * ks + kof];
+            float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+            if (ks + 1 < MF_KT / 2) {
+                na0 = As[wm * 64 + mrow][2 * ks + 2 + kof];
+                na1 = As[wm * 64 + 32 + mrow][2 * ks + 2 + kof];
+                nb0 = Bs[wn * 64 + mrow][2 * ks + 2 + kof];
+                nb1 = Bs[wn * 64 + 32 + mrow][2 * ks + 2 + kof];
+            }
+            __builtin_amdgcn_sched_barrier(0);
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
         }
         __syncthreads();
     }
@@ -266,21 +277,28 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
         }
         __syncthreads();
         if (c0 + MF_KT < ce) gload(c0 + MF_KT);
+        auto afrag = [&](int kk, int half) -> float {
+            return TRANS_A ? As[kk + kof][32 * half + mrow] : As[32 * half + mrow][kk + kof];
+        };
+        // the operands of step ks + 1 are read from LDS before the MFMAs of step ks are issued
+        float a0 = afrag(0, 0), a1 = afrag(0, 1);
+        float b0 = Bs[kof][wn * 64 + mrow], b1 = Bs[kof][wn * 64 + 32 + mrow];
 #pragma unroll
         for (int ks = 0; ks < MF_KT / 2; ++ks) {
-            float a0, a1;
-            if (!TRANS_A) {
-                a0 = As[mrow][2 * ks + kof];
-                a1 = As[32 + mrow][2 * ks + kof];
-            } else {
-                a0 = As[2 * ks + kof][mrow];
-                a1 = As[2 * ks + kof][32 + mrow];
+            float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+            if (ks + 1 < MF_KT / 2) {
+                na0 = afrag(2 * ks + 2, 0);
+                na1 = afrag(2 * ks + 2, 1);
+                nb0 = Bs[2 * ks + 2 + kof][wn * 64 + mrow];
+                nb1 = Bs[2 * ks + 2 + kof][wn * 64 + 32 + mrow];
             }
-            const float b0 = Bs[2 * ks + kof][wn * 64 + mrow], b1 = Bs[2 * ks + kof][wn * 64 + 32 + mrow];
+            __builtin_amdgcn_sched_barrier(0);
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
         }
         __syncthreads();
     }
