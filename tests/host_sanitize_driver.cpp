@@ -1,0 +1,84 @@
+// Host-only driver for the address / undefined-behaviour sanitizer run of the index planner
+// (tests/test_host_sanitizers.py builds it together with plan.cpp and families.cpp; no GPU code).
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "../include/tad.h"
+
+static int derive_worked(int64_t I, int64_t J, int64_t K, tad_dtype dt, uint32_t flags) {
+    tad_expr e;
+    std::memset(&e, 0, sizeof e);
+    e.body = TAD_BODY_WORKED; e.n_f = 2; e.f_shape[0] = I; e.f_shape[1] = J; e.n_sum = 1; e.sum_lo[0] = 0; e.sum_hi[0] = K - 1;
+    tad_arg a[4];
+    std::memset(a, 0, sizeof a);
+    const int64_t idx[4][2][3] = {{{1, 0, 0}, {0, 0, 1}}, {{0, 1, 0}, {0, 0, 1}}, {{1, 0, 0}, {1, 0, 0}}, {{1, 0, 1}, {0, 0, 0}}};
+    const int64_t shp[4][2] = {{I, K}, {J, K}, {I, I}, {I + K - 1, 0}};
+    for (int p = 0; p < 4; ++p) {
+        a[p].rank = p == 3 ? 1 : 2; a[p].n_occ = 1; a[p].needs_grad = 1;
+        for (int r = 0; r < a[p].rank; ++r) {
+            a[p].shape[r] = shp[p][r];
+            for (int d = 0; d < 3; ++d) a[p].index[r][d] = idx[p][r][d];
+        }
+    }
+    tad_plan *pl = nullptr;
+    int rc = tad_plan_derive(&e, a, 4, dt, flags, &pl);
+    if (rc) return rc;
+    // walk the plan: query, rows, enumeration of every gradient element of d and a few of c
+    for (int p = 0; p < 4; ++p) {
+        tad_plan_info info;
+        if (tad_plan_query(pl, p, 0, &info)) return -100;
+        int64_t scale, cb[2 * TAD_MAX_EXT], cz[TAD_MAX_KERNEL];
+        for (int lvl = 0; lvl < info.kernel_dim; ++lvl)
+            for (int r = 0; r < info.n_lower[lvl]; ++r)
+                if (tad_plan_bound_row(pl, p, TAD_ROWS_LOWER, lvl, r, &scale, cb, cz)) return -101;
+    }
+    std::vector<int64_t> buf((size_t)J * K * 3 + 3);
+    for (int64_t m = 0; m < I + K - 1; ++m) {
+        size_t n = 0;
+        if (tad_plan_enumerate(pl, 3, 0, &m, buf.data(), (size_t)J * K, &n)) return -102;
+    }
+    const int64_t beta[2] = {I - 1, I - 1};
+    size_t n = 0;
+    if (tad_plan_enumerate(pl, 2, 0, beta, buf.data(), (size_t)J * K, &n) || n != (size_t)(J * K)) return -103;
+    std::vector<int64_t> counts((size_t)I * I);
+    if (tad_plan_count_all(pl, 2, counts.data())) return -104;
+    (void)tad_plan_workspace_bytes(pl);
+    tad_plan_free(pl);
+    return 0;
+}
+
+int main() {
+    if (derive_worked(8, 6, 5, TAD_F64, 0)) return 1;
+    if (derive_worked(333, 1300, 5, TAD_F32, 0)) return 2;
+    if (derive_worked(64, 128, 256, TAD_F32, 0)) return 3;
+    if (derive_worked(40, 44, 7, TAD_F32, TAD_PLAN_GENERIC_ONLY)) return 4;
+    // integer machinery on awkward inputs
+    unsigned seed = 12345;
+    auto rnd = [&]() { seed = seed * 1664525u + 1013904223u; return (int)((seed >> 16) % 9) - 4; };
+    for (int t = 0; t < 400; ++t) {
+        const int n = 1 + (t % 3), m = 1 + (t % 4);
+        int64_t A[12], lo[4], hi[4], beta[3];
+        bool nz = false;
+        for (int i = 0; i < n * m; ++i) { A[i] = rnd(); nz |= A[i] != 0; }
+        if (!nz) continue;
+        for (int d = 0; d < m; ++d) { lo[d] = rnd() / 2; hi[d] = lo[d] + (rnd() + 4) / 2; }
+        for (int r = 0; r < n; ++r) beta[r] = rnd();
+        int64_t S[12], U[9], V[16], out[4 * 4096];
+        int R = 0;
+        if (tad_smith_normal_form(A, n, m, S, U, V, &R)) return 5;
+        size_t cnt = 0;
+        const int rc = tad_lattice_enumerate(A, n, m, lo, hi, beta, out, 4096, &cnt);
+        if (rc != 0 && rc != TAD_EUNSUPPORTED) return 6;
+    }
+    // overflow paths must report, not trap
+    const int64_t big = (int64_t)1 << 62;
+    int64_t Ab[4] = {big, big - 1, big - 3, big - 7}, S[4], U[4], V[4];
+    int R = 0;
+    if (tad_smith_normal_form(Ab, 2, 2, S, U, V, &R) != TAD_EOVERFLOW) return 7;
+    int64_t g, x, y;
+    if (tad_extended_gcd(INT64_MIN, 3, &g, &x, &y) != TAD_EOVERFLOW) return 8;
+    std::puts("sanitizer driver ok");
+    return 0;
+}

@@ -198,3 +198,54 @@ def test_determinism_full_config3():
     assert np.array_equal(f1, f2)
     for x, y in zip(g1, g2):
         assert np.array_equal(x, y)
+
+
+def test_device_entry_points_reject_misuse():
+    """Host-side checks of the device entry points: no kernel is launched on any of these paths."""
+    import ctypes
+    import torch
+    from paper_1711_01348_amd import binding as B
+    w = wl.config3("small")
+    plan = B.Plan(w.expr)
+    args = [_to_dev(a) for a in w.arg_list()]
+    f = torch.empty(tuple(w.expr.f_shape), dtype=torch.float32, device="cuda")
+    ptrs = (ctypes.c_void_p * 4)(*[t.data_ptr() for t in args])
+    assert plan.workspace_bytes > 0
+    # workspace missing / too small
+    assert B.lib.tad_eval_forward(plan._h, ptrs, f.data_ptr(), None, 0, None) in (0, -7)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    dptr = (ctypes.c_void_p * 4)(*[t.data_ptr() for t in args])
+    assert B.lib.tad_eval_backward(plan._h, ptrs, f.data_ptr(), f.data_ptr(), dptr, small.data_ptr(), 16, None) == -7
+    # NULL argument pointer
+    bad = (ctypes.c_void_p * 4)(args[0].data_ptr(), None, args[2].data_ptr(), args[3].data_ptr())
+    assert B.lib.tad_eval_forward(plan._h, bad, f.data_ptr(), small.data_ptr(), 16, None) == -1
+    # a gradient that was not planned
+    plan2 = B.Plan(w.expr, needs_grad=[True, True, False, True])
+    ws = plan2.workspace()
+    assert B.lib.tad_eval_backward(plan2._h, ptrs, f.data_ptr(), f.data_ptr(), dptr, ws.data_ptr(), ws.numel(), None) == -1
+    # the binding refuses wrong dtypes, shapes and host tensors before calling the library
+    with pytest.raises(ValueError):
+        plan.forward([a.double() for a in args])
+    with pytest.raises(ValueError):
+        plan.forward([a.cpu() for a in args])
+    with pytest.raises(ValueError):
+        plan.forward([args[0][:-1].contiguous()] + args[1:])
+    torch.cuda.synchronize()
+
+
+def test_runs_on_a_side_stream():
+    """Kernels are enqueued on the caller's stream."""
+    import torch
+    from paper_1711_01348_amd import binding as B
+    w = wl.config5("small")
+    plan = B.Plan(w.expr)
+    f_ref, g_ref = oracle_all(w, 1)
+    s = torch.cuda.Stream()
+    args = [_to_dev(a) for a in w.arg_list()]
+    df = _to_dev(w.df)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        f = plan.forward(args)
+        grads = plan.backward(args, f, df)
+    s.synchronize()
+    assert_parity(w, f.cpu().numpy(), [g.cpu().numpy() for g in grads], f_ref, g_ref, "side stream")

@@ -363,3 +363,22 @@ def test_null_and_misuse_at_the_abi():
     B.lib.tad_plan_free(h)
     B.lib.tad_plan_free(None)
     assert B.strerror(-4) == "integer overflow"
+
+
+def test_size_limits():
+    # 2^32 function elements: beyond the int32 element index of the kernels
+    assert _status(lambda: B.Plan(wl.broadcast_sq_expr(65536, 65536, "f32"))) == -4
+    # too many indices / too high rank are rejected before the library is called or by it
+    with pytest.raises(B.TadError):
+        B.Plan(_expr("exp", (2, 2, 2, 2, 2, 2, 2), [], [("x", (2,), [[1, 0, 0, 0, 0, 0, 0]])]))
+    # kernel dimension 5 > TAD_MAX_KERNEL
+    assert _status(lambda: B.Plan(_expr("exp", (2, 2, 2, 2, 2, 2), [], [("x", (2,), [[1, 0, 0, 0, 0, 0]])]))) == -5
+    # the largest benchmark shapes derive fine
+    for w in (wl.config3(), wl.config4(), wl.config2(2)):
+        assert B.Plan(w.expr).workspace_bytes >= 0
+
+
+def test_workspace_sizes_are_reported():
+    assert B.Plan(wl.config1().expr).workspace_bytes == 0          # generic kernels need none
+    assert B.Plan(wl.config3().expr).workspace_bytes > 0
+    assert B.Plan(wl.config3().expr, generic_only=True).workspace_bytes == 0
