@@ -206,13 +206,16 @@ int tad_lattice_enumerate(const int64_t *A, int n, int m, const int64_t *lo, con
                           const int64_t *beta, int64_t *x_out, size_t cap, size_t *count);
 
 /*
- * Instrumentation: time one kernel of the library with HIP events.  After tad_profile_begin(name) every
- * launch of the kernel called `name` (up to 4096 launches) is bracketed by two events recorded on the
- * stream it is launched on; tad_profile_end waits for them, returns the summed duration in milliseconds
- * and the number of launches, and switches the instrumentation off.  Not thread safe against concurrent
- * evaluation calls from other threads while armed.
+ * Instrumentation: time one kernel of the library with HIP events.  After tad_profile_begin(name, every)
+ * each `every`-th launch of the kernel called `name` (the first one included, up to 4096 timed launches)
+ * carries a start and a stop event attached to its own dispatch on the stream it is launched on, so the
+ * pair reads that kernel's begin and end timestamps.  A timed launch delays the launch that follows it by
+ * several microseconds; every > 1 spreads the samples over a run while keeping that cost small.
+ * tad_profile_end waits for the events, returns the summed duration in milliseconds and the number of
+ * timed launches, and switches the instrumentation off.  every < 1 is TAD_EINVAL.  Not thread safe against
+ * concurrent evaluation calls from other threads while armed.
  */
-int tad_profile_begin(const char *kernel_name);
+int tad_profile_begin(const char *kernel_name, int every);
 int tad_profile_end(double *total_ms, int *launches);
 
 const char *tad_strerror(int status);

@@ -310,6 +310,6 @@ def lattice_enumerate(A, lo, hi, beta) -> np.ndarray:
     return out
 
 
-lib.tad_profile_begin.argtypes = [ctypes.c_char_p]
+lib.tad_profile_begin.argtypes = [ctypes.c_char_p, ctypes.c_int]
 lib.tad_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 EXPORTS += ["tad_profile_begin", "tad_profile_end"]

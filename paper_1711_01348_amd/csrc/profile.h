@@ -1,16 +1,16 @@
 // Optional per-kernel timing with HIP events (tad_profile_begin / tad_profile_end).
-// When a kernel name is armed, every launch of that kernel is bracketed by a pair of events recorded
-// on the stream the kernel is launched on.
+// When a kernel name is armed, every launch of that kernel carries a pair of events that the runtime
+// attaches to the dispatch itself (hipExtLaunchKernelGGL): they take the kernel's own begin and end
+// timestamps on the stream it runs on and put no extra packet into the queue.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 namespace tad {
 
 struct ProfileScope {
-    ProfileScope(const char *name, hipStream_t s);
-    ~ProfileScope();
-    int slot;
-    hipStream_t stream;
+    explicit ProfileScope(const char *name);
+    hipEvent_t start, stop;   // null unless this launch is being timed
 };
 
 }  // namespace tad
@@ -20,6 +20,6 @@ struct ProfileScope {
 #define TAD_LAUNCH(name, kernel, grid, block, shmem, stream, ...)              \
     do {                                                                       \
         (void)hipGetLastError();                                               \
-        tad::ProfileScope _ps(name, stream);                                   \
-        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);   \
+        tad::ProfileScope _ps(name);                                           \
+        hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, _ps.start, _ps.stop, 0, __VA_ARGS__); \
     } while (0)

@@ -1,5 +1,6 @@
 #include "profile.h"
 
+#include <atomic>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -10,21 +11,19 @@ namespace tad {
 
 static std::mutex g_mu;
 static char g_name[64] = {0};
-static bool g_armed = false;
+static std::atomic<bool> g_armed{false};
 static std::vector<hipEvent_t> g_start, g_stop;
-static int g_used = 0;
+static int g_used = 0, g_seen = 0, g_every = 1;
 static const int kMaxLaunches = 4096;
 
-ProfileScope::ProfileScope(const char *name, hipStream_t s) : slot(-1), stream(s) {
+ProfileScope::ProfileScope(const char *name) : start(nullptr), stop(nullptr) {
     if (!g_armed) return;
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_armed || std::strcmp(name, g_name) != 0 || g_used >= kMaxLaunches) return;
-    slot = g_used++;
-    (void)hipEventRecord(g_start[slot], stream);
-}
-
-ProfileScope::~ProfileScope() {
-    if (slot >= 0) (void)hipEventRecord(g_stop[slot], stream);
+    if (g_seen++ % g_every != 0) return;
+    start = g_start[g_used];
+    stop = g_stop[g_used];
+    ++g_used;
 }
 
 }  // namespace tad
@@ -33,8 +32,8 @@ using namespace tad;
 
 extern "C" {
 
-int tad_profile_begin(const char *kernel_name) {
-    if (!kernel_name || std::strlen(kernel_name) >= sizeof g_name) return TAD_EINVAL;
+int tad_profile_begin(const char *kernel_name, int every) {
+    if (!kernel_name || std::strlen(kernel_name) >= sizeof g_name || every < 1) return TAD_EINVAL;
     std::lock_guard<std::mutex> lk(g_mu);
     if (g_start.empty()) {
         g_start.resize(kMaxLaunches);
@@ -49,6 +48,8 @@ int tad_profile_begin(const char *kernel_name) {
     }
     std::strcpy(g_name, kernel_name);
     g_used = 0;
+    g_seen = 0;
+    g_every = every;
     g_armed = true;
     return TAD_OK;
 }
