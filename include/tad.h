@@ -45,7 +45,7 @@ typedef enum {
     TAD_ESHAPE = -2,       /* an index leaves its argument's shape; summation lo > hi; empty tensor */
     TAD_EINFEASIBLE = -3,  /* constraint system without any solution (Sec. 4.2, feasibility rows) */
     TAD_EOVERFLOW = -4,    /* integer overflow in Smith / Fourier-Motzkin, or index range beyond int32 */
-    TAD_EUNSUPPORTED = -5, /* body / pattern without a kernel, several occurrences of one argument */
+    TAD_EUNSUPPORTED = -5, /* body / pattern without a kernel, plan beyond the fixed device limits */
     TAD_EDEVICE = -6,      /* kernel launch failed */
     TAD_ENOMEM = -7,       /* host allocation failed, or workspace too small */
     TAD_ENOGPU = -8        /* library built without / cannot reach a HIP device */
@@ -77,13 +77,20 @@ typedef struct {
     int64_t sum_hi[TAD_MAX_EXT];
 } tad_expr;
 
-/* One tensor argument x^p and its index map (Sec. 5.1; Sec. 5.2 for the extended map). */
+/*
+ * One operand of the scalar body: a tensor x^p and its index map (Sec. 5.1; Sec. 5.2 for the extended map).
+ * A tensor that occurs several times in the expression (Sec. 5.3: its gradient is the sum of the
+ * contributions of all its occurrences) is given once as an operand of its own and then again, with
+ * another index map, as operands whose `alias` names the first one.
+ */
 typedef struct {
     int32_t rank;                               /* D_p, 1..TAD_MAX_RANK */
     int64_t shape[TAD_MAX_RANK];                /* N^p */
-    int32_t n_occ;                              /* occurrences of the argument; only 1 is supported */
+    int32_t alias;                              /* 0: a tensor of its own; q + 1: a further occurrence of operand
+                                                   q < p (itself not an alias; same rank and shape) */
     int64_t index[TAD_MAX_RANK][TAD_MAX_EXT];   /* A^p, D_p x (n_f + n_sum): argument index = A^p [alpha k] */
-    int32_t needs_grad;                         /* derive a gather plan for this argument */
+    int32_t needs_grad;                         /* derive a gather plan for this operand; for an alias the
+                                                   flag of the operand it names is used */
 } tad_arg;
 
 /* plan flags */
@@ -124,12 +131,13 @@ typedef enum { TAD_ROWS_LOWER = 0, TAD_ROWS_UPPER = 1, TAD_ROWS_FEASIBILITY = 2 
  * Derive the index plan of an expression (Sec. 5.3, the element-wise derivation
  * algorithm; index half only: the scalar partial derivatives of the built-in
  * bodies are fixed in the kernels).  Host only: touches no GPU.
- *   expr, args[n_args]  host, read; n_args must equal the body's argument count
+ *   expr, args[n_args]  host, read; n_args must equal the body's operand count (aliases included)
  *   dt                  element type of every tensor
  *   flags               TAD_PLAN_* bits
  *   out                 receives a heap-allocated plan owned by the caller (tad_plan_free)
- * Errors: EINVAL, ESHAPE (some in-range [alpha k] maps outside an argument),
- * EOVERFLOW, EUNSUPPORTED, ENOMEM.
+ * Errors: EINVAL (also: alias of a later operand or of another alias), ESHAPE (some in-range [alpha k]
+ * maps outside an argument; alias with another rank or shape), EOVERFLOW, EUNSUPPORTED, ENOMEM.
+ * An expression with aliases always runs on the plan-driven generic kernels.
  */
 int tad_plan_derive(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt,
                     uint32_t flags, tad_plan **out);
@@ -139,7 +147,11 @@ void tad_plan_free(tad_plan *plan);
 /* Bytes of device workspace tad_eval_forward / tad_eval_backward need (two-pass reductions). */
 size_t tad_plan_workspace_bytes(const tad_plan *plan);
 
-/* Smith normal form parts and row counts for argument `arg` (host, written to *out). */
+/*
+ * Smith normal form parts and row counts for occurrence `occ` of the tensor given as operand `arg` (host,
+ * written to *out): occ = 0 is operand `arg` itself, occ = k its k-th alias in operand order.
+ * EINVAL if `arg` is an alias, has no plan, or has fewer occurrences.
+ */
 int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out);
 
 /*
@@ -161,13 +173,14 @@ int tad_plan_bound_row(const tad_plan *plan, int arg, int kind, int level, int r
 int tad_plan_enumerate(const tad_plan *plan, int arg, int occ, const int64_t *beta,
                        int64_t *alpha_out, size_t cap, size_t *n);
 
-/* Number of visited extended indices for every beta of argument `arg` (host; counts has one int64 per element). */
+/* Number of visited extended indices for every beta of operand `arg`, first occurrence only (host; counts has
+ * one int64 per element). */
 int tad_plan_count_all(const tad_plan *plan, int arg, int64_t *counts);
 
 /*
  * Forward evaluation of f (Sec. 5.1 / 5.2).  Enqueues kernels on `stream` (a hipStream_t, NULL = default
  * stream), never synchronises, never allocates.
- *   args_dev[n_args]  device, read
+ *   args_dev[n_args]  device, read; the entry of an alias operand is ignored (its tensor is the one it names)
  *   f_dev             device, overwritten (all of f)
  *   ws_dev, ws_bytes  device scratch of at least tad_plan_workspace_bytes (may be NULL if that is 0)
  */
@@ -179,7 +192,8 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
  *   f_dev     device, read: the forward result for the same args_dev
  *   df_dev    device, read: dl/df, shape of f
  *   dx_dev[p] device, overwritten with the full gradient in argument p's shape (zeros where the
- *             cokernel / divisibility / range conditions fail); NULL skips that gradient
+ *             cokernel / divisibility / range conditions fail), summed over all occurrences of the tensor;
+ *             NULL skips that gradient; must be NULL for an alias operand (EINVAL otherwise)
  * Same stream / workspace rules as tad_eval_forward.  Deterministic.
  */
 int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const void *f_dev,

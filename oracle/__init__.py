@@ -139,6 +139,22 @@ def backward(expr, args, df, wanted: Optional[Sequence[bool]] = None,
     return dx
 
 
+def backward_by_tensor(expr, args, df, nthreads: int = 1) -> List[Optional[np.ndarray]]:
+    """Gradients per tensor when a tensor occurs as several operands (an operand whose ``same_as`` names an
+    earlier operand is a further occurrence of that tensor and must be given the same array).  The
+    derivative with respect to the tensor is the sum of the per-operand derivatives (Sec. 5.3: the
+    gradient is accumulated over all occurrences).  Entries of alias operands are None."""
+    per_operand = backward(expr, args, df, nthreads=nthreads)
+    out: List[Optional[np.ndarray]] = list(per_operand)
+    for p, a in enumerate(expr.args):
+        q = getattr(a, "same_as", None)
+        if q is not None:
+            assert args[p] is args[q] or np.array_equal(args[p], args[q]), "alias operands share their tensor"
+            out[q] = out[q] + per_operand[p]
+            out[p] = None
+    return out
+
+
 def gamma(expr, arg: int, beta: Sequence[int]) -> np.ndarray:
     """All extended indices in the box mapped onto ``beta`` (lexicographic), shape (n, n_ext)."""
     lib = _load()

@@ -37,7 +37,7 @@ class TadExpr(ctypes.Structure):
 
 class TadArg(ctypes.Structure):
     _fields_ = [("rank", ctypes.c_int32), ("shape", ctypes.c_int64 * MAX_RANK),
-                ("n_occ", ctypes.c_int32), ("index", (ctypes.c_int64 * MAX_EXT) * MAX_RANK),
+                ("alias", ctypes.c_int32), ("index", (ctypes.c_int64 * MAX_EXT) * MAX_RANK),
                 ("needs_grad", ctypes.c_int32)]
 
 
@@ -118,7 +118,7 @@ def pack_args(expr, needs_grad: Optional[Sequence[bool]] = None):
     n_ext = len(expr.f_shape) + len(expr.sums)
     for p, a in enumerate(expr.args):
         arr[p].rank = len(a.shape)
-        arr[p].n_occ = 1
+        arr[p].alias = 0 if getattr(a, "same_as", None) is None else int(a.same_as) + 1
         arr[p].needs_grad = 1 if needs_grad is None else int(bool(needs_grad[p]))
         for r, s in enumerate(a.shape):
             arr[p].shape[r] = int(s)
@@ -158,9 +158,9 @@ class Plan:
     def forward_family(self) -> str:
         return FAMILY[lib.tad_plan_forward_family(self._h)]
 
-    def query(self, arg: int) -> dict:
+    def query(self, arg: int, occ: int = 0) -> dict:
         info = TadPlanInfo()
-        _check(lib.tad_plan_query(self._h, arg, 0, ctypes.byref(info)), "tad_plan_query")
+        _check(lib.tad_plan_query(self._h, arg, occ, ctypes.byref(info)), "tad_plan_query")
         N, D, R, kap = len(self.expr.args[arg].shape), self.n_ext, info.rank, info.kernel_dim
         mat = lambda m, r, c: np.array([[m[i][j] for j in range(c)] for i in range(r)], dtype=np.int64).reshape(r, c)
         return dict(rank=R, kernel_dim=kap, smith=[info.smith[i] for i in range(R)],
@@ -187,14 +187,14 @@ class Plan:
                             coef_z=np.array([cz[m] for m in range(q["kernel_dim"])], dtype=np.int64)))
         return out
 
-    def enumerate(self, arg: int, beta: Sequence[int]) -> np.ndarray:
+    def enumerate(self, arg: int, beta: Sequence[int], occ: int = 0) -> np.ndarray:
         b = np.asarray(beta, dtype=np.int64)
         n = ctypes.c_size_t(0)
-        _check(lib.tad_plan_enumerate(self._h, arg, 0, b.ctypes.data, None, 0, ctypes.byref(n)),
+        _check(lib.tad_plan_enumerate(self._h, arg, occ, b.ctypes.data, None, 0, ctypes.byref(n)),
                "tad_plan_enumerate")
         out = np.empty((n.value, self.n_ext), dtype=np.int64)
         if n.value:
-            _check(lib.tad_plan_enumerate(self._h, arg, 0, b.ctypes.data, out.ctypes.data, n.value,
+            _check(lib.tad_plan_enumerate(self._h, arg, occ, b.ctypes.data, out.ctypes.data, n.value,
                                           ctypes.byref(n)), "tad_plan_enumerate")
         return out
 
@@ -214,10 +214,19 @@ class Plan:
             raise ValueError(f"{what}: need a contiguous {self._torch_dtype()} cuda tensor of shape {tuple(shape)}, "
                              f"got {t.dtype} {tuple(t.shape)} on {t.device}")
 
+    def _is_alias(self, p: int) -> bool:
+        return getattr(self.expr.args[p], "same_as", None) is not None
+
     def _arg_ptrs(self, args):
-        for t, a in zip(args, self.expr.args):
+        """One entry per operand; the entry of an alias operand is not used (it may be None)."""
+        ptrs = []
+        for p, (t, a) in enumerate(zip(args, self.expr.args)):
+            if self._is_alias(p):
+                ptrs.append(None)
+                continue
             self._check_tensor(t, a.shape, a.name)
-        return (ctypes.c_void_p * len(args))(*[t.data_ptr() for t in args])
+            ptrs.append(t.data_ptr())
+        return (ctypes.c_void_p * len(args))(*ptrs)
 
     def workspace(self, device="cuda"):
         import torch
@@ -242,6 +251,7 @@ class Plan:
         self._check_tensor(f, self.expr.f_shape, "f")
         self._check_tensor(df, self.expr.f_shape, "df")
         wanted = [True] * len(args) if wanted is None else list(wanted)
+        wanted = [w and not self._is_alias(p) for p, w in enumerate(wanted)]   # an alias has no gradient of its own
         if out is None:
             out = [torch.empty_like(t) if w else None for t, w in zip(args, wanted)]
         for t, a in zip(out, self.expr.args):

@@ -11,7 +11,7 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
                      size_t ws_bytes, void *stream) {
     if (!plan || !args_dev || !f_dev) return TAD_EINVAL;
     for (size_t p = 0; p < plan->args.size(); ++p)
-        if (!args_dev[p]) return TAD_EINVAL;
+        if (!args_dev[plan->root[p]]) return TAD_EINVAL;
     if (plan->ws_bytes && (!ws_dev || ws_bytes < plan->ws_bytes)) return TAD_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (plan->fwd_family) {
@@ -30,8 +30,8 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
                       const void *df_dev, void *const *dx_dev, void *ws_dev, size_t ws_bytes, void *stream) {
     if (!plan || !args_dev || !f_dev || !df_dev || !dx_dev) return TAD_EINVAL;
     for (size_t p = 0; p < plan->args.size(); ++p) {
-        if (!args_dev[p]) return TAD_EINVAL;
-        if (dx_dev[p] && !plan->ap[p].derived) return TAD_EINVAL;  // gradient was not planned
+        if (!args_dev[plan->root[p]]) return TAD_EINVAL;
+        if (dx_dev[p] && (!plan->ap[p].derived || plan->root[p] != (int)p)) return TAD_EINVAL;  // not planned / alias
     }
     if (plan->ws_bytes && (!ws_dev || ws_bytes < plan->ws_bytes)) return TAD_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -207,7 +207,7 @@ void select_families(tad_plan &plan) {
     plan.fwd_family = TAD_FAMILY_GENERIC;
     for (auto &ap : plan.ap) ap.family = TAD_FAMILY_GENERIC;
     plan.ws_bytes = 0;
-    if (plan.flags & TAD_PLAN_GENERIC_ONLY) return;
+    if ((plan.flags & TAD_PLAN_GENERIC_ONLY) || plan.has_alias) return;
     if (match_worked(plan)) return;
     if (match_patterns(plan)) return;
     if (match_strided(plan)) return;

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, co
 template <int BODY, typename T>
 __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int p, const ArgPtrs A,
                                                         const T *__restrict__ f, const T *__restrict__ df,
-                                                        T *__restrict__ dx, int n) {
+                                                        T *__restrict__ dx, int n, int accumulate) {
     constexpr int NA = BodyTraits<BODY>::NA;
     int lin = blockIdx.x * blockDim.x + threadIdx.x;
     if (lin >= n) return;
@@ -62,7 +62,13 @@ __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int 
         int t = lin;
         for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
     }
-    if (!gather_prepare(P, beta, y)) { dx[lin] = T(0); return; }
+    // accumulate != 0: a further occurrence of the same tensor adds to what the earlier launches stored
+    // (same owner thread, launches ordered on the stream: still no atomics)
+    if (!gather_prepare(P, beta, y)) {
+        if (!accumulate) dx[lin] = T(0);
+        return;
+    }
+    const T prev = accumulate ? dx[lin] : T(0);
 
     double acc = 0.0;
     auto term = [&](const int64_t *off) {
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int 
         for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
         off[NA] = gather_offset(P, kSlotF, y, z);
         term(off);
-        dx[lin] = (T)acc;
+        dx[lin] = prev + (T)acc;
         return;
     }
     int lvl = P.kappa - 1;
@@ -103,26 +109,30 @@ __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int 
             gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
         }
     }
-    dx[lin] = (T)acc;
+    dx[lin] = prev + (T)acc;
 }
 
 template <int BODY, typename T>
 static int launch_body(const tad_plan &pl, const void *const *args, const void *f, const void *df,
                        void *const *dx, void *fout, hipStream_t s) {
     ArgPtrs A{};
-    for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[q];
+    for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     if (fout) {
         int nf = (int)pl.f_count;
         TAD_LAUNCH("k_generic_forward", (k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd, A,
                    static_cast<T *>(fout), nf);
         return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
     }
-    for (size_t p = 0; p < pl.args.size(); ++p) {
-        if (!dx[p] || pl.ap[p].family != TAD_FAMILY_GENERIC) continue;
-        if (!pl.ap[p].derived) return TAD_EINVAL;
+    // the gradient of a tensor is the sum over its occurrences (Sec. 5.3): the first occurrence stores,
+    // every alias operand adds in a launch of its own
+    for (size_t q = 0; q < pl.args.size(); ++q) {
+        const size_t p = (size_t)pl.root[q];
+        if (!dx[p] || pl.ap[q].family != TAD_FAMILY_GENERIC) continue;
+        if (!pl.ap[q].derived) return TAD_EINVAL;
         int n = (int)pl.arg_count[p];
-        TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[p].dev,
-                   (int)p, A, static_cast<const T *>(f), static_cast<const T *>(df), static_cast<T *>(dx[p]), n);
+        TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
+                   (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df), static_cast<T *>(dx[p]), n,
+                   q != p ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

@@ -267,10 +267,21 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     if (pl->f_count >= ((int64_t)1 << 31)) return TAD_EOVERFLOW;
 
     pl->arg_count.resize(n_args);
+    pl->root.resize(n_args);
     for (int p = 0; p < n_args; ++p) {
         const tad_arg &a = args[p];
         if (a.rank < 1 || a.rank > TAD_MAX_RANK) return TAD_EINVAL;
-        if (a.n_occ != 1) return TAD_EUNSUPPORTED;
+        if (a.alias < 0 || a.alias > p) return TAD_EINVAL;
+        pl->root[p] = a.alias ? a.alias - 1 : p;
+        if (a.alias) {
+            const tad_arg &r = args[a.alias - 1];
+            if (r.alias) return TAD_EINVAL;
+            if (r.rank != a.rank) return TAD_ESHAPE;
+            for (int d = 0; d < a.rank; ++d)
+                if (r.shape[d] != a.shape[d]) return TAD_ESHAPE;
+            pl->args[p].needs_grad = r.needs_grad;
+            pl->has_alias = true;
+        }
         int64_t cnt = 1;
         for (int r = 0; r < a.rank; ++r) {
             if (a.shape[r] < 1) return TAD_ESHAPE;
@@ -309,7 +320,7 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
 
     pl->ap.resize(n_args);
     for (int p = 0; p < n_args; ++p) {
-        if (!args[p].needs_grad) continue;
+        if (!pl->args[p].needs_grad) continue;
         int rc = derive_arg(*pl, p, pl->ap[p]);
         if (rc) return rc;
     }
@@ -374,9 +385,14 @@ size_t tad_plan_workspace_bytes(const tad_plan *plan) { return plan ? plan->ws_b
 
 int tad_plan_forward_family(const tad_plan *plan) { return plan ? plan->fwd_family : TAD_EINVAL; }
 
+// plan of occurrence `occ` of the tensor given as operand `arg` (0: the operand itself, k: its k-th alias)
 static const ArgPlan *get_arg(const tad_plan *plan, int arg, int occ) {
-    if (!plan || arg < 0 || arg >= (int)plan->ap.size() || occ != 0) return nullptr;
-    return plan->ap[arg].derived ? &plan->ap[arg] : nullptr;
+    if (!plan || arg < 0 || arg >= (int)plan->ap.size() || occ < 0 || plan->root[arg] != arg) return nullptr;
+    int slot = -1;
+    for (int p = arg, k = 0; p < (int)plan->ap.size(); ++p)
+        if (plan->root[p] == arg && k++ == occ) { slot = p; break; }
+    if (slot < 0) return nullptr;
+    return plan->ap[slot].derived ? &plan->ap[slot] : nullptr;
 }
 
 int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out) {

@@ -44,6 +44,8 @@ struct tad_plan {
     int64_t lo[TAD_MAX_EXT], hi[TAD_MAX_EXT];  // inclusive box of the extended index
     int64_t f_count;
     std::vector<int64_t> arg_count;
+    std::vector<int> root;                     // operand that holds the tensor of operand p (p itself unless alias)
+    bool has_alias = false;
     tad::ForwardPlan fwd;
     std::vector<tad::ArgPlan> ap;
     int fwd_family = TAD_FAMILY_GENERIC;

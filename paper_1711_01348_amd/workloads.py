@@ -28,6 +28,8 @@ class ArgSpec:
     # index matrix, one row per argument axis, one column per function index
     # followed by one column per summation index
     A: List[List[int]]
+    # a further occurrence of the tensor given as operand `same_as` (an earlier operand), else None
+    same_as: int | None = None
 
 
 @dataclass
@@ -53,7 +55,9 @@ class Workload:
     arg_order: List[str] = field(default_factory=list)
 
     def arg_list(self) -> List[np.ndarray]:
-        return [self.inputs[a.name] for a in self.expr.args]
+        """One array per operand; an alias operand gets the array of the operand it names."""
+        args = self.expr.args
+        return [self.inputs[(a if a.same_as is None else args[a.same_as]).name] for a in args]
 
 
 def _np_dtype(dtype: str):
@@ -121,6 +125,37 @@ def strided_tanh_expr(N: int, I: int, J: int, U: int, V: int, stride: int,
 # --------------------------------------------------------------------------
 # the five benchmark configurations
 # --------------------------------------------------------------------------
+
+# A tensor that occurs more than once in an expression (Sec. 5.3: its gradient is the sum over the
+# occurrences): the later occurrences are alias operands.
+
+def matrix_square_expr(N: int, dtype: str) -> ExprSpec:
+    """f_ij = sum_k x_ik x_kj, extended index (i, j, k)."""
+    return ExprSpec("mul", (N, N), [(0, N - 1)],
+                    [ArgSpec("x", (N, N), [[1, 0, 0], [0, 0, 1]]),
+                     ArgSpec("x_again", (N, N), [[0, 0, 1], [0, 1, 0]], same_as=0)], dtype)
+
+
+def symmetric_product_expr(N: int, M: int, dtype: str) -> ExprSpec:
+    """f_ij = x_ij x_ji for i, j < N with x of shape M x M (M >= N), no summation."""
+    return ExprSpec("mul", (N, N), [],
+                    [ArgSpec("x", (M, M), [[1, 0], [0, 1]]),
+                     ArgSpec("x_again", (M, M), [[0, 1], [1, 0]], same_as=0)], dtype)
+
+
+def autocorrelation_expr(N: int, K: int, dtype: str) -> ExprSpec:
+    """f_i = sum_{k<K} x_k x_{i+k}, i < N, x of length N + K - 1."""
+    L = N + K - 1
+    return ExprSpec("mul", (N,), [(0, K - 1)],
+                    [ArgSpec("x", (L,), [[0, 1]]), ArgSpec("x_again", (L,), [[1, 1]], same_as=0)], dtype)
+
+
+def worked_shared_expr(I: int, K: int, dtype: str) -> ExprSpec:
+    """The worked expression with b = a:  f_ij = exp(-sum_k((a_ik + a_jk)^2 c_ii + d_{i+k}^3))."""
+    e = worked_expr(I, I, K, dtype)
+    e.args[1] = ArgSpec("a_again", e.args[1].shape, e.args[1].A, same_as=0)
+    return e
+
 
 def _worked_workload(name, seed, I, J, K, dtype, c_hi, d_half, d_len=None) -> Workload:
     rng = np.random.Generator(np.random.PCG64(seed))
@@ -206,6 +241,7 @@ def all_configs(scale: str = "small") -> List[Workload]:
 
 def random_inputs(expr: ExprSpec, seed: int, lo: float = -1.0, hi: float = 1.0) -> Workload:
     rng = np.random.Generator(np.random.PCG64(seed))
-    inputs = {a.name: _round(_uniform(rng, lo, hi, a.shape), expr.dtype) for a in expr.args}
+    inputs = {a.name: _round(_uniform(rng, lo, hi, a.shape), expr.dtype) for a in expr.args
+              if a.same_as is None}
     df = _round(_uniform(rng, -1, 1, expr.f_shape), expr.dtype)
     return Workload(f"random_{expr.body}_{seed}", expr, inputs, df)

@@ -16,7 +16,7 @@ static int derive_worked(int64_t I, int64_t J, int64_t K, tad_dtype dt, uint32_t
     const int64_t idx[4][2][3] = {{{1, 0, 0}, {0, 0, 1}}, {{0, 1, 0}, {0, 0, 1}}, {{1, 0, 0}, {1, 0, 0}}, {{1, 0, 1}, {0, 0, 0}}};
     const int64_t shp[4][2] = {{I, K}, {J, K}, {I, I}, {I + K - 1, 0}};
     for (int p = 0; p < 4; ++p) {
-        a[p].rank = p == 3 ? 1 : 2; a[p].n_occ = 1; a[p].needs_grad = 1;
+        a[p].rank = p == 3 ? 1 : 2; a[p].needs_grad = 1;
         for (int r = 0; r < a[p].rank; ++r) {
             a[p].shape[r] = shp[p][r];
             for (int d = 0; d < 3; ++d) a[p].index[r][d] = idx[p][r][d];

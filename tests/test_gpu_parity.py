@@ -45,7 +45,7 @@ def assert_parity(w, f, grads, f_ref, g_ref, tag=""):
 
 def oracle_all(w, nthreads=8):
     args = w.arg_list()
-    return oracle.forward(w.expr, args), oracle.backward(w.expr, args, w.df, nthreads=nthreads)
+    return oracle.forward(w.expr, args), oracle.backward_by_tensor(w.expr, args, w.df, nthreads=nthreads)
 
 
 @pytest.mark.parametrize("generic_only", [True, False], ids=["generic", "selected"])
@@ -109,6 +109,13 @@ ASSORTED = [
     lambda: wl.strided_tanh_expr(3, 19, 23, 5, 4, 3, "f32"),
     lambda: wl.strided_tanh_expr(2, 30, 41, 2, 2, 1, "f32"),
     lambda: wl.strided_tanh_expr(2, 5, 4, 2, 3, 3, "f64"),
+    # a tensor that occurs twice: the gradient is the sum over both occurrences
+    lambda: wl.matrix_square_expr(23, "f64"),
+    lambda: wl.matrix_square_expr(67, "f32"),
+    lambda: wl.symmetric_product_expr(19, 21, "f64"),
+    lambda: wl.autocorrelation_expr(300, 17, "f32"),
+    lambda: wl.worked_shared_expr(41, 5, "f32"),
+    lambda: wl.worked_shared_expr(9, 3, "f64"),
 ]
 
 

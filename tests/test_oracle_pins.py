@@ -216,6 +216,51 @@ def test_central_finite_differences(make):
         assert np.allclose(g, fd, rtol=2e-7, atol=2e-8), (e.body, p)
 
 
+def _fd_grad_tensor(expr, args, df, p, h=1e-6):
+    """Central differences with respect to the tensor of operand p: all its occurrences move together."""
+    same = [q for q, a in enumerate(expr.args) if q == p or a.same_as == p]
+    out = np.zeros_like(args[p])
+    it = np.nditer(args[p], flags=["multi_index"])
+    for _ in it:
+        idx = it.multi_index
+        xp = [a.copy() for a in args]
+        xm = [a.copy() for a in args]
+        for q in same:
+            xp[q][idx] += h
+            xm[q][idx] -= h
+        out[idx] = (_loss(expr, xp, df) - _loss(expr, xm, df)) / (2 * h)
+    return out
+
+
+@pytest.mark.parametrize("make", [
+    lambda: wl.matrix_square_expr(4, "f64"),
+    lambda: wl.symmetric_product_expr(3, 4, "f64"),
+    lambda: wl.autocorrelation_expr(5, 3, "f64"),
+    lambda: wl.worked_shared_expr(3, 2, "f64"),
+])
+def test_repeated_tensor_matches_finite_differences(make):
+    e = make()
+    w = wl.random_inputs(e, 5)
+    args = [np.asarray(a, dtype=np.float64) for a in w.arg_list()]
+    grads = oracle.backward_by_tensor(e, args, w.df)
+    for p, g in enumerate(grads):
+        if e.args[p].same_as is not None:
+            assert g is None
+            continue
+        fd = _fd_grad_tensor(e, args, w.df, p)
+        assert np.allclose(g, fd, rtol=2e-7, atol=2e-8), (e.body, p)
+
+
+def test_matrix_square_closed_form():
+    """f = X X: dl/dX = df X^T + X^T df (textbook)."""
+    e = wl.matrix_square_expr(6, "f64")
+    w = wl.random_inputs(e, 9)
+    X = np.asarray(w.arg_list()[0], dtype=np.float64)
+    assert np.allclose(oracle.forward(e, [X, X]), X @ X, rtol=1e-13, atol=1e-14)
+    g = oracle.backward_by_tensor(e, [X, X], w.df)[0]
+    assert np.allclose(g, w.df @ X.T + X.T @ w.df, rtol=1e-12, atol=1e-13)
+
+
 def test_jacobian_rows_by_one_hot_df():
     """One-hot df picks one row of the Jacobian (Sec. 5.3); compare with central differences of f."""
     e = wl.worked_expr(2, 3, 2, "f64")

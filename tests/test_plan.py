@@ -350,9 +350,11 @@ def test_null_and_misuse_at_the_abi():
     assert B.lib.tad_plan_derive(ctypes.byref(ce), None, 1, 1, 0, ctypes.byref(h)) == -1
     assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, None) == -1
     assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 7, 0, ctypes.byref(h)) == -1
-    ca[0].n_occ = 2
-    assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, ctypes.byref(h)) == -5
-    ca[0].n_occ = 1
+    ca[0].alias = 1        # an operand cannot be an alias of itself or of a later operand
+    assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, ctypes.byref(h)) == -1
+    ca[0].alias = -1
+    assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, ctypes.byref(h)) == -1
+    ca[0].alias = 0
     ca[0].needs_grad = 0
     assert B.lib.tad_plan_derive(ctypes.byref(ce), ca, 1, 1, 0, ctypes.byref(h)) == 0
     info = B.TadPlanInfo()
@@ -382,3 +384,46 @@ def test_workspace_sizes_are_reported():
     assert B.Plan(wl.config1().expr).workspace_bytes == 0          # generic kernels need none
     assert B.Plan(wl.config3().expr).workspace_bytes > 0
     assert B.Plan(wl.config3().expr, generic_only=True).workspace_bytes == 0
+
+
+# ---- a tensor that occurs several times (Sec. 5.3: one plan per occurrence) ---------------------
+
+REPEATED = [
+    ("matrix_square", lambda: wl.matrix_square_expr(5, "f64")),
+    ("symmetric_product", lambda: wl.symmetric_product_expr(4, 6, "f64")),
+    ("autocorrelation", lambda: wl.autocorrelation_expr(7, 4, "f64")),
+    ("worked_shared", lambda: wl.worked_shared_expr(5, 3, "f64")),
+]
+
+
+@pytest.mark.parametrize("name,make", REPEATED, ids=[r[0] for r in REPEATED])
+def test_each_occurrence_has_its_own_exact_plan(name, make):
+    """Every occurrence's plan visits exactly the extended indices that the brute-force scan of the box
+    finds for that occurrence's index map."""
+    import itertools
+    e = make()
+    plan = B.Plan(e)
+    assert plan.forward_family == "generic"
+    root = 0
+    alias = [p for p, a in enumerate(e.args) if a.same_as == root]
+    assert len(alias) == 1
+    for occ, slot in enumerate([root] + alias):
+        for beta in itertools.product(*[range(n) for n in e.args[root].shape]):
+            got = plan.enumerate(root, beta, occ=occ)
+            want = oracle.gamma(e, slot, beta)
+            assert got.shape == want.shape and (got == want).all(), (name, occ, beta)
+
+
+def test_alias_rules():
+    e = wl.matrix_square_expr(4, "f64")
+    e.args[1].shape = (4, 5)
+    assert _status(lambda: B.Plan(e)) == -2          # alias with another shape
+    e = wl.worked_shared_expr(4, 2, "f64")
+    e.args[2].same_as = 1                            # alias of an alias
+    assert _status(lambda: B.Plan(e)) in (-1, -2)
+    e = wl.matrix_square_expr(4, "f64")
+    plan = B.Plan(e)
+    assert _status(lambda: plan.query(1)) == -1      # an alias operand is reached through its tensor
+    q0, q1 = plan.query(0), plan.query(0, occ=1)
+    assert q0["kernel_dim"] == 1 and q1["kernel_dim"] == 1
+    assert _status(lambda: plan.query(0, occ=2)) == -1
