@@ -31,6 +31,7 @@ def workload(name):
     table = {
         "cfg1": wl.config1, "cfg2_1": lambda: wl.config2(1), "cfg2_2": lambda: wl.config2(2),
         "cfg2_3": lambda: wl.config2(3), "cfg3": wl.config3, "cfg4": wl.config4, "cfg5": wl.config5,
+        "matmul": wl.matmul_workload,
     }
     return table[name]()
 
@@ -69,6 +70,12 @@ def accounting(name, w):
     elif name == "cfg2_3":
         elems = nf + nf + 2 * small
         dom = dict(kernel="k_antidiag_backward", bound="hbm", per_launch=nf * es, launches=1)
+    elif name == "matmul":
+        I, J = e.f_shape
+        K = e.sums[0][1] + 1
+        elems = 2 * small + nf + nf + small           # fwd: read x, y, write f; bwd: read df, x, y, write dx, dy
+        dom = dict(kernel="k_contract", bound="mfma", per_launch=2.0 * I * J * K, launches=3,
+                   step_flops=6.0 * I * J * K)
     elif name == "cfg5":
         nx = int(np.prod(e.args[0].shape))
         elems = nx + nf + 2 * nf + nx + nx + 18       # fwd: read x, write f; bwd: read df, f; write dx; read x (dw)
@@ -210,7 +217,7 @@ def main():
     }
     if not a.no_others:
         per = {}
-        for name in ("cfg1", "cfg2_1", "cfg2_2", "cfg2_3", "cfg4", "cfg5"):
+        for name in ("cfg1", "cfg2_1", "cfg2_2", "cfg2_3", "cfg4", "cfg5", "matmul"):
             if name == a.workload:
                 continue
             try:

@@ -121,7 +121,8 @@ typedef enum {
     TAD_FAMILY_ANTIDIAGONAL = 3, /* one clipped window over x_{i+j} */
     TAD_FAMILY_WORKED = 4,       /* fused kernels for the worked expression */
     TAD_FAMILY_WORKED_MFMA = 5,  /* worked expression, long summed index: expanded cross term on MFMA */
-    TAD_FAMILY_STRIDED = 6       /* strided stencil */
+    TAD_FAMILY_STRIDED = 6,      /* strided stencil */
+    TAD_FAMILY_CONTRACTION = 7   /* product of two matrices over one summation index: dense products on MFMA */
 } tad_family;
 
 /* which set of Fourier-Motzkin rows tad_plan_bound_row reads */

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libtad.so")
 F32, F64 = 0, 1
 BODY = {"sq": 0, "cube": 1, "sin": 2, "exp": 3, "mul": 4, "worked": 5, "tanh_dot": 6}
 FAMILY = {0: "generic", 1: "row_reduce", 2: "diagonal", 3: "antidiagonal", 4: "worked",
-          5: "worked_mfma", 6: "strided"}
+          5: "worked_mfma", 6: "strided", 7: "contraction"}
 PLAN_GENERIC_ONLY = 1
 ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 

@@ -2,6 +2,8 @@
 // Every plan can run on the plan-driven generic kernels; a specialised family is chosen only
 // when body, index matrices, shapes and dtype match its template exactly, and the derived plan
 // has the structure the family's kernels assume (which kernel coordinate collapses, which is a window).
+#include <algorithm>
+
 #include "plan.hpp"
 #include "worked_geom.h"
 
@@ -203,6 +205,78 @@ static bool match_strided(tad_plan &pl) {
     return true;
 }
 
+// f_ij = sum_k P(i, k) Q(k, j): both operands are matrices indexed by one function index and the summation index,
+// their axes in either order, shapes exactly the index ranges.  Extended index (i, j, k).
+static bool match_contraction(tad_plan &pl) {
+    const tad_expr &e = pl.expr;
+    if (e.body != TAD_BODY_MUL || pl.dtype != TAD_F32 || e.n_f != 2 || e.n_sum != 1 || e.sum_lo[0] != 0) return false;
+    if (!all_derived(pl)) return false;
+    const int64_t ext[3] = {e.f_shape[0], e.f_shape[1], e.sum_hi[0] + 1};
+    for (int d = 0; d < 3; ++d)
+        if (ext[d] % 4 != 0 || ext[d] > (1 << 20)) return false;   // 16-byte rows; int32 addressing inside the kernel
+    // axis_dim[p][r]: which extended index axis r of operand p follows (rows of the index matrix are unit vectors)
+    int axis_dim[2][2];
+    for (int p = 0; p < 2; ++p) {
+        const tad_arg &a = pl.args[p];
+        if (a.rank != 2) return false;
+        for (int r = 0; r < 2; ++r) {
+            int dim = -1;
+            for (int d = 0; d < 3; ++d) {
+                if (a.index[r][d] == 1 && dim < 0) dim = d;
+                else if (a.index[r][d] != 0) return false;
+            }
+            if (dim < 0 || a.shape[r] != ext[dim]) return false;
+            axis_dim[p][r] = dim;
+        }
+        if (axis_dim[p][0] == axis_dim[p][1]) return false;
+    }
+    auto has = [&](int p, int dim) { return axis_dim[p][0] == dim || axis_dim[p][1] == dim; };
+    int P = -1, Q = -1;
+    if (has(0, 0) && has(0, 2) && has(1, 1) && has(1, 2)) { P = 0; Q = 1; }
+    else if (has(1, 0) && has(1, 2) && has(0, 1) && has(0, 2)) { P = 1; Q = 0; }
+    else return false;
+    // the derived plans must say what the kernels assume: y = beta, one kernel coordinate, and its range is the
+    // whole collapsed dimension whatever beta is
+    for (int p = 0; p < 2; ++p) {
+        const ArgPlan &ap = pl.ap[p];
+        const int gone = p == P ? 1 : 0;   // function index missing from the operand
+        if (ap.smith.R != 2 || ap.K.cols != 1 || !y_is_beta(ap.dev)) return false;
+        // no feasibility row may fail anywhere inside the operand's shape (no element is masked out)
+        for (int r = 0; r < ap.dev.nF; ++r) {
+            int64_t worst = ap.dev.feas[r].k0;
+            for (int c = 0; c < 2; ++c) worst += std::max<int64_t>(0, (int64_t)ap.dev.feas[r].ky[c] * (ap.dev.shape[c] - 1));
+            if (worst > 0) return false;
+        }
+        for (int d = 0; d < 3; ++d)
+            if (ap.K(d, 0) * ap.K(d, 0) != (d == gone ? 1 : 0)) return false;
+        FlatLevel fl;
+        if (!flatten_level(ap.dev, 0, fl)) return false;
+        for (int r = 0; r < kFlatRows; ++r)
+            for (int c = 0; c < kFlatY; ++c)
+                if (fl.lky[r][c] != 0 || fl.hky[r][c] != 0) return false;
+        const int32_t y0[3] = {0, 0, 0};
+        int32_t lo, hi;
+        flat_bounds(fl, y0, lo, hi);
+        if ((int64_t)hi - lo + 1 != ext[gone]) return false;
+    }
+    const int I = (int)ext[0], J = (int)ext[1], Kc = (int)ext[2];
+    const bool p_ik = axis_dim[P][0] == 0;   // P stored [i][k]
+    const bool q_kj = axis_dim[Q][0] == 2;   // Q stored [k][j]
+    const int ldp = (int)pl.args[P].shape[1], ldq = (int)pl.args[Q].shape[1];
+    GemmDesc *g = pl.fast.gemm;
+    // f[i][j] = sum_k P(i,k) Q(k,j)
+    g[0] = GemmDesc{I, J, Kc, P, Q, -1, ldp, ldq, !p_ik, !q_kj};
+    // gradient of P in its own memory order
+    if (p_ik) g[1] = GemmDesc{I, Kc, J, -1, Q, P, J, ldq, 0, q_kj};       // dP[i][k] = sum_j df[i][j] Q(k,j)
+    else      g[1] = GemmDesc{Kc, I, J, Q, -1, P, ldq, J, !q_kj, 1};      // dP[k][i] = sum_j Q(k,j) df[i][j]
+    // gradient of Q in its own memory order
+    if (q_kj) g[2] = GemmDesc{Kc, J, I, P, -1, Q, ldp, J, p_ik, 0};       // dQ[k][j] = sum_i P(i,k) df[i][j]
+    else      g[2] = GemmDesc{J, Kc, I, -1, P, Q, J, ldp, 1, !p_ik};      // dQ[j][k] = sum_i df[i][j] P(i,k)
+    pl.fwd_family = TAD_FAMILY_CONTRACTION;
+    pl.ap[0].family = pl.ap[1].family = TAD_FAMILY_CONTRACTION;
+    return true;
+}
+
 void select_families(tad_plan &plan) {
     plan.fwd_family = TAD_FAMILY_GENERIC;
     for (auto &ap : plan.ap) ap.family = TAD_FAMILY_GENERIC;
@@ -211,6 +285,7 @@ void select_families(tad_plan &plan) {
     if (match_worked(plan)) return;
     if (match_patterns(plan)) return;
     if (match_strided(plan)) return;
+    if (match_contraction(plan)) return;
 }
 
 }  // namespace tad

@@ -1,0 +1,209 @@
+// Contraction of two matrices over one summation index (Sec. 5, example f^4_ij = sum_k x_ik y_kj, and Sec. 5.2):
+// body "mul" with two function indices and one summation index, fp32.  In the gather form every gradient
+// element owns one kernel coordinate that runs over a whole dimension with constant limits (the collapsed
+// function index), so forward pass and both gradients are dense matrix products,
+//
+//     f  = P Q          dP = df Q^T          dQ = P^T df
+//
+// (P: the operand indexed by the first function index and the summation index, Q: the other one; either may be
+// stored with its two axes in either order).  They run on the matrix cores (v_mfma_f32_32x32x2f32).
+//
+// One kernel, C[m][n] = sum_k A(m, k) B(k, n), with the memory order of each operand a template parameter:
+//   AT = false: A(m, k) = a[m * lda + k]      AT = true: A(m, k) = a[k * lda + m]
+//   BT = false: B(k, n) = b[k * ldb + n]      BT = true: B(k, n) = b[n * ldb + k]
+// Block tile 128 x 128, four waves of 64 x 64 (2 x 2 MFMA tiles), contraction tile 32, global -> register -> LDS
+// staging with the loads of the next tile in flight during the MFMAs of the current one.
+//
+// MFMA operand layout (wave64): A operand lane l = A[m = l % 32][k = l / 32], B operand lane l = B[k = l / 32][n = l % 32],
+// result register r of lane l = D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32].
+#include <hip/hip_runtime.h>
+
+#include "launch.h"
+#include "profile.h"
+
+namespace tad {
+
+typedef float float4c __attribute__((ext_vector_type(4)));
+typedef float float16c __attribute__((ext_vector_type(16)));
+
+constexpr int CT_KT = 32;        // contraction tile
+constexpr int CT_LDK = 33;       // row stride of a [row][k] tile: odd, conflict-free 4-byte reads down a column of rows
+constexpr int CT_LDM = 132;      // row stride of a [k][row] tile: 16-byte aligned rows
+constexpr int CT_TILE = 128 * CT_LDK;   // floats per operand tile; 32 * CT_LDM is the same size
+static_assert(32 * CT_LDM == CT_TILE, "both tile layouts use the same amount of LDS");
+
+// The 8 accelerator dies take workgroups round robin; give each die a contiguous range of logical tiles and walk
+// the tiles in groups of 8 tile rows so that concurrently running workgroups share operand tiles in their L2.
+__device__ __forceinline__ void tile_of_block(int gm, int gn, int &tm, int &tn) {
+    const int total = gm * gn;
+    int lid = blockIdx.x;
+    if (total % 8 == 0) lid = (lid % 8) * (total / 8) + lid / 8;
+    const int group = 8 * gn;
+    const int g0 = (lid / group) * 8;
+    const int rows = min(8, gm - g0);
+    const int in = lid - (lid / group) * group;
+    tm = g0 + in % rows;
+    tn = in / rows;
+}
+
+template <bool AT, bool BT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_contract(const float *__restrict__ a, const float *__restrict__ b, float *__restrict__ c, int M, int N, int Kc,
+                int lda, int ldb, int gm, int gn) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * CT_TILE];   // A tile, B tile; reused as the output stage in the epilogue
+    float *As = smem, *Bs = smem + CT_TILE;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    int tm, tn;
+    tile_of_block(gm, gn, tm, tn);
+    const int m0 = tm * 128, n0 = tn * 128;
+    float16c acc[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
+    float4c ra[4], rb[4];
+    const float4c zero4 = {0.f, 0.f, 0.f, 0.f};
+    // every dimension is a multiple of 4 (checked on the host): a 16-byte load is inside or outside as a whole
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int idx = tid + 256 * p;
+            if (!AT) {
+                const int row = idx >> 3, kq = idx & 7;
+                const int m = m0 + row, k = k0 + 4 * kq;
+                ra[p] = (m < M && k < Kc) ? *reinterpret_cast<const float4c *>(a + (size_t)m * lda + k) : zero4;
+            } else {
+                const int kk = idx >> 5, mq = idx & 31;
+                const int m = m0 + 4 * mq, k = k0 + kk;
+                ra[p] = (m < M && k < Kc) ? *reinterpret_cast<const float4c *>(a + (size_t)k * lda + m) : zero4;
+            }
+            if (BT) {
+                const int row = idx >> 3, kq = idx & 7;
+                const int n = n0 + row, k = k0 + 4 * kq;
+                rb[p] = (n < N && k < Kc) ? *reinterpret_cast<const float4c *>(b + (size_t)n * ldb + k) : zero4;
+            } else {
+                const int kk = idx >> 5, nq = idx & 31;
+                const int n = n0 + 4 * nq, k = k0 + kk;
+                rb[p] = (n < N && k < Kc) ? *reinterpret_cast<const float4c *>(b + (size_t)k * ldb + n) : zero4;
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int idx = tid + 256 * p;
+            if (!AT) {
+                const int row = idx >> 3, kq = idx & 7;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) As[row * CT_LDK + 4 * kq + q] = ra[p][q];
+            } else {
+                const int kk = idx >> 5, mq = idx & 31;
+                *reinterpret_cast<float4c *>(&As[kk * CT_LDM + 4 * mq]) = ra[p];
+            }
+            if (BT) {
+                const int row = idx >> 3, kq = idx & 7;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) Bs[row * CT_LDK + 4 * kq + q] = rb[p][q];
+            } else {
+                const int kk = idx >> 5, nq = idx & 31;
+                *reinterpret_cast<float4c *>(&Bs[kk * CT_LDM + 4 * nq]) = rb[p];
+            }
+        }
+    };
+    const int mrow = lane & 31, kof = lane >> 5;
+    auto afrag = [&](int kk, int half) -> float {
+        const int m = wm * 64 + 32 * half + mrow;
+        return AT ? As[(kk + kof) * CT_LDM + m] : As[m * CT_LDK + kk + kof];
+    };
+    auto bfrag = [&](int kk, int half) -> float {
+        const int n = wn * 64 + 32 * half + mrow;
+        return BT ? Bs[n * CT_LDK + kk + kof] : Bs[(kk + kof) * CT_LDM + n];
+    };
+    gload(0);
+    for (int k0 = 0; k0 < Kc; k0 += CT_KT) {
+        stage();
+        __syncthreads();
+        if (k0 + CT_KT < Kc) gload(k0 + CT_KT);
+        // the operands of step ks + 1 are read from LDS before the MFMAs of step ks are issued
+        float a0 = afrag(0, 0), a1 = afrag(0, 1), b0 = bfrag(0, 0), b1 = bfrag(0, 1);
+#pragma unroll
+        for (int ks = 0; ks < CT_KT / 2; ++ks) {
+            float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+            if (ks + 1 < CT_KT / 2) {
+                na0 = afrag(2 * ks + 2, 0);
+                na1 = afrag(2 * ks + 2, 1);
+                nb0 = bfrag(2 * ks + 2, 0);
+                nb1 = bfrag(2 * ks + 2, 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+        }
+        __syncthreads();
+    }
+    // epilogue: each wave stages 32 x 64 results at a time in its own quarter of the tile memory (32 rows of 66
+    // floats) and writes them as 16-byte stores, 256 bytes per row.  The last barrier of the loop guarantees that
+    // nobody still reads the tiles; a wave reads back only what it wrote itself.
+    static_assert(4 * 32 * 66 <= 2 * CT_TILE, "output stage does not fit in the tile memory");
+    float *out = smem + wave * (32 * 66);
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+#pragma unroll
+        for (int y = 0; y < 2; ++y)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int mloc = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                out[mloc * 66 + y * 32 + mrow] = acc[x][y][r];
+            }
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int rl = it * 4 + (lane >> 4), cl = (lane & 15) * 4;
+            const int m = m0 + wm * 64 + x * 32 + rl, n = n0 + wn * 64 + cl;
+            if (m < M && n < N) {
+                const float4c v = {out[rl * 66 + cl], out[rl * 66 + cl + 1], out[rl * 66 + cl + 2], out[rl * 66 + cl + 3]};
+                *reinterpret_cast<float4c *>(c + (size_t)m * N + n) = v;
+            }
+        }
+    }
+}
+
+static int launch_gemm(const GemmDesc &g, const float *a, const float *b, float *c, hipStream_t s) {
+    const int gm = (g.M + 127) / 128, gn = (g.N + 127) / 128;
+    const dim3 grid(gm * gn), block(256);
+    if (!g.at && !g.bt)
+        TAD_LAUNCH("k_contract", (k_contract<false, false>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
+    else if (!g.at && g.bt)
+        TAD_LAUNCH("k_contract", (k_contract<false, true>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
+    else if (g.at && !g.bt)
+        TAD_LAUNCH("k_contract", (k_contract<true, false>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
+    else
+        TAD_LAUNCH("k_contract", (k_contract<true, true>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
+    return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+}
+
+// source -1 of a product is df, destination -1 is f
+int contract_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s) {
+    const GemmDesc &g = pl.fast.gemm[0];
+    return launch_gemm(g, (const float *)args[g.a_src], (const float *)args[g.b_src], (float *)f, s);
+}
+
+int contract_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, hipStream_t s) {
+    for (int q = 1; q <= 2; ++q) {
+        const GemmDesc &g = pl.fast.gemm[q];
+        if (!dx[g.out]) continue;
+        const float *a = g.a_src < 0 ? (const float *)df : (const float *)args[g.a_src];
+        const float *b = g.b_src < 0 ? (const float *)df : (const float *)args[g.b_src];
+        const int rc = launch_gemm(g, a, b, (float *)dx[g.out], s);
+        if (rc) return rc;
+    }
+    return TAD_OK;
+}
+
+}  // namespace tad

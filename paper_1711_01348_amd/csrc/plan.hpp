@@ -21,6 +21,16 @@ struct ArgPlan {
     int family = TAD_FAMILY_GENERIC;
 };
 
+// One dense product C[m][n] = sum_k A(m, k) B(k, n) of the contraction family.  a_src / b_src: operand index,
+// or -1 for df; out: operand index of the gradient written, or -1 for f.  at: A is stored [k][m]; bt: B is
+// stored [n][k]; lda / ldb: row length of the stored matrix.
+struct GemmDesc {
+    int M = 0, N = 0, Kc = 0;
+    int a_src = 0, b_src = 0, out = 0;
+    int lda = 0, ldb = 0;
+    int at = 0, bt = 0;
+};
+
 // Parameters of the specialised kernel families (filled by pattern recognition).
 struct FastParams {
     int64_t I = 0, J = 0, K = 0;     // worked expression / 2-D patterns
@@ -31,6 +41,7 @@ struct FastParams {
     int jy = 0, jz = 0;              // antidiagonal pattern: j = jy * y_0 + jz * z
     FlatLevel flat[2];               // loop-free range rows of the family's plan-driven coordinates
     FlatFeas feas;
+    GemmDesc gemm[3];                // contraction family: forward, gradient of the i-operand, of the j-operand
 };
 
 }  // namespace tad

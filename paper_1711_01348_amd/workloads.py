@@ -126,6 +126,27 @@ def strided_tanh_expr(N: int, I: int, J: int, U: int, V: int, stride: int,
 # the five benchmark configurations
 # --------------------------------------------------------------------------
 
+def matmul_expr(I: int, J: int, K: int, dtype: str, x_transposed: bool = False,
+                y_transposed: bool = False, swap: bool = False) -> ExprSpec:
+    """f_ij = sum_k x_ik y_kj (Sec. 5, f^4), extended index (i, j, k).  x is stored I x K (K x I if
+    x_transposed), y is stored K x J (J x K if y_transposed); swap lists y before x."""
+    ri, rj, rk = [1, 0, 0], [0, 1, 0], [0, 0, 1]
+    x = ArgSpec("x", (K, I), [rk, ri]) if x_transposed else ArgSpec("x", (I, K), [ri, rk])
+    y = ArgSpec("y", (J, K), [rj, rk]) if y_transposed else ArgSpec("y", (K, J), [rk, rj])
+    return ExprSpec("mul", (I, J), [(0, K - 1)], [y, x] if swap else [x, y], dtype)
+
+
+def matmul_workload(n: int = 4096) -> Workload:
+    """Square fp32 matrix product and its two derived products, uniform[-1,1] inputs."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 6))
+    expr = matmul_expr(n, n, n, "f32")
+    x = _uniform(rng, -1, 1, (n, n))
+    y = _uniform(rng, -1, 1, (n, n))
+    df = _uniform(rng, -1, 1, (n, n))
+    return Workload(f"matmul_{n}x{n}x{n}_f32", expr, {"x": _round(x, "f32"), "y": _round(y, "f32")},
+                    _round(df, "f32"))
+
+
 # A tensor that occurs more than once in an expression (Sec. 5.3: its gradient is the sum over the
 # occurrences): the later occurrences are alias operands.
 

@@ -256,3 +256,45 @@ def test_runs_on_a_side_stream():
         grads = plan.backward(args, f, df)
     s.synchronize()
     assert_parity(w, f.cpu().numpy(), [g.cpu().numpy() for g in grads], f_ref, g_ref, "side stream")
+
+
+CONTRACTIONS = [(xt, yt, sw) for xt in (False, True) for yt in (False, True) for sw in (False, True)]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("xt,yt,sw", CONTRACTIONS)
+def test_contraction_family_all_memory_orders(xt, yt, sw):
+    """Matrix product and its two derived products on the matrix cores, every storage order of the operands,
+    sizes that are not multiples of the tile."""
+    e = wl.matmul_expr(132, 260, 72, "f32", xt, yt, sw)
+    w = wl.random_inputs(e, 21)
+    f_ref, g_ref = oracle_all(w, 4)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "contraction"
+    assert [plan.query(p)["family"] for p in range(2)] == ["contraction", "contraction"]
+    assert_parity(w, f, grads, f_ref, g_ref)
+    _, f2, grads2 = run_gpu(w, generic_only=True)
+    assert_parity(w, f2, grads2, f_ref, g_ref, "generic")
+
+
+@pytest.mark.gpu
+def test_contraction_full_size_against_sampled_rows():
+    """4096^3 product: the oracle computes sampled rows of f, dx and dy one by one (fp64 dot products)."""
+    w = wl.matmul_workload(4096)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "contraction"
+    x, y = [np.asarray(a, dtype=np.float64) for a in w.arg_list()]
+    df = np.asarray(w.df, dtype=np.float64)
+    rng = np.random.default_rng(5)
+    rows = sorted(set(rng.integers(0, 4096, size=6).tolist() + [0, 127, 128, 4095]))
+    for r in rows:
+        # restrict the expression to one row of f / dx (a 1 x J x K problem) and one row of dy
+        e1 = wl.matmul_expr(1, 4096, 4096, "f32")
+        f_row = oracle.forward(e1, [x[r:r + 1], y])[0]
+        assert check.within(f[r], f_row, "f32"), ("f", r, check.errors(f[r], f_row))
+        dx_row = oracle.backward(e1, [x[r:r + 1], y], df[r:r + 1], wanted=[True, False])[0][0]
+        assert check.within(grads[0][r], dx_row, "f32"), ("dx", r, check.errors(grads[0][r], dx_row))
+        # dy[r, :] = sum_i x[i, r] df[i, :]: the expression with K restricted to index r
+        e2 = wl.matmul_expr(4096, 4096, 1, "f32")
+        dy_row = oracle.backward(e2, [x[:, r:r + 1], y[r:r + 1]], df, wanted=[False, True], nthreads=8)[1][0]
+        assert check.within(grads[1][r], dy_row, "f32"), ("dy", r, check.errors(grads[1][r], dy_row))

@@ -427,3 +427,14 @@ def test_alias_rules():
     q0, q1 = plan.query(0), plan.query(0, occ=1)
     assert q0["kernel_dim"] == 1 and q1["kernel_dim"] == 1
     assert _status(lambda: plan.query(0, occ=2)) == -1
+
+
+def test_contraction_family_is_selected_only_for_exact_matrix_products():
+    assert B.Plan(wl.matmul_expr(8, 12, 16, "f32")).forward_family == "contraction"
+    assert B.Plan(wl.matmul_expr(8, 12, 16, "f32", True, True, True)).forward_family == "contraction"
+    assert B.Plan(wl.matmul_expr(8, 12, 16, "f64")).forward_family == "generic"        # fp32 only
+    assert B.Plan(wl.matmul_expr(8, 12, 18, "f32")).forward_family == "generic"        # rows not 16-byte multiples
+    assert B.Plan(wl.matrix_square_expr(8, "f32")).forward_family == "generic"         # repeated tensor
+    e = wl.matmul_expr(8, 12, 16, "f32")
+    e.args[0].shape = (9, 16)                                                           # longer than the range
+    assert B.Plan(e).forward_family == "generic"
