@@ -17,13 +17,21 @@ static bool extents_fit24(const GatherPlan &g) {
     return true;
 }
 
+// Largest |y_c| a kernel can meet for gradient elements inside the shape: y = (U beta) / alpha.
+static int64_t y_extent(const GatherPlan &g, int c) {
+    int64_t v = 0;
+    for (int d = 0; d < g.rank; ++d) v += (g.U[c][d] < 0 ? -(int64_t)g.U[c][d] : g.U[c][d]) * (g.shape[d] - 1);
+    return v;   // dividing by alpha_c >= 1 only makes it smaller
+}
+
 bool flatten_level(const GatherPlan &g, int level, FlatLevel &out) {
     if (level < 0 || level >= g.kappa || g.R > kFlatY || !extents_fit24(g)) return false;
     const int nl = g.lo_end[level] - g.lo_begin[level], nh = g.hi_end[level] - g.hi_begin[level];
     if (nl > kFlatRows || nh > kFlatRows) return false;
     for (int r = 0; r < kFlatRows; ++r) {
-        out.ls[r] = 1; out.lk0[r] = -(1 << 30);      // neutral lower row
-        out.hs[r] = 1; out.hk0[r] = (1 << 30) - 1;   // neutral upper row
+        out.ls[r] = 1; out.lk0[r] = kFlatNeutralLo;   // neutral lower row
+        out.hs[r] = 1; out.hk0[r] = kFlatNeutralHi;   // neutral upper row
+        out.lrs[r] = out.hrs[r] = 1.f;
         for (int c = 0; c < kFlatY; ++c) out.lky[r][c] = out.hky[r][c] = 0;
     }
     for (int r = 0; r < nl + nh; ++r) {
@@ -32,11 +40,15 @@ bool flatten_level(const GatherPlan &g, int level, FlatLevel &out) {
             if (row.kz[m] != 0) return false;
         for (int c = 0; c < g.R; ++c)
             if (!fits24(row.ky[c])) return false;
+        // the loop-free division needs |k0 + ky . y| < 2^23 for every y the kernels can meet
+        int64_t worst = row.k0 < 0 ? -(int64_t)row.k0 : row.k0;
+        for (int c = 0; c < g.R; ++c) worst += (row.ky[c] < 0 ? -(int64_t)row.ky[c] : row.ky[c]) * y_extent(g, c);
+        if (worst >= kFlatNeutralHi || !fits24(row.scale)) return false;
         if (r < nl) {
-            out.ls[r] = row.scale; out.lk0[r] = row.k0;
+            out.ls[r] = row.scale; out.lk0[r] = row.k0; out.lrs[r] = 1.f / (float)row.scale;
             for (int c = 0; c < g.R; ++c) out.lky[r][c] = row.ky[c];
         } else {
-            out.hs[r - nl] = row.scale; out.hk0[r - nl] = row.k0;
+            out.hs[r - nl] = row.scale; out.hk0[r - nl] = row.k0; out.hrs[r - nl] = 1.f / (float)row.scale;
             for (int c = 0; c < g.R; ++c) out.hky[r - nl][c] = row.ky[c];
         }
     }

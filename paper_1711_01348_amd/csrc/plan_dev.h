@@ -10,6 +10,7 @@
 //                      b(beta) = [lo - V_R y ; V_R y - hi] already substituted)
 // Memory offsets of every tensor are linear in (y, z) because the index maps are linear.
 #pragma once
+#include <math.h>
 #include <stdint.h>
 
 #if defined(__HIPCC__)
@@ -135,7 +136,9 @@ constexpr int kFlatY = 3;
 struct FlatLevel {
     int32_t ls[kFlatRows], lk0[kFlatRows], lky[kFlatRows][kFlatY];   // ls * z >= lk0 + lky . y
     int32_t hs[kFlatRows], hk0[kFlatRows], hky[kFlatRows][kFlatY];   // hs * z <= hk0 + hky . y
+    float lrs[kFlatRows], hrs[kFlatRows];                            // 1 / ls, 1 / hs
 };
+constexpr int32_t kFlatNeutralLo = -(1 << 23) + 1, kFlatNeutralHi = (1 << 23) - 1;
 
 struct FlatFeas {
     int32_t k0[kFlatFeas], ky[kFlatFeas][kFlatY];                    // k0 + ky . y <= 0
@@ -151,6 +154,20 @@ TAD_HD int32_t mul24(int32_t a, int32_t b) {
 #endif
 }
 
+// floor(a / s) for s > 0 and |a| < 2^23 (guaranteed by flatten_level) without an integer division:
+// a converts exactly, the float quotient a * (1 / s) is within 1/2 of a / s, so its floor is off by at most one
+// and one correction in each direction makes it exact.
+TAD_HD int32_t floor_div_flat(int32_t a, int32_t s, float rs) {
+    // unit and stride-2 index maps: the branch is uniform over the wave and far cheaper than the arithmetic below
+    if (s == 1) return a;
+    if (s == 2) return a >> 1;
+    int32_t q = (int32_t)floorf((float)a * rs);
+    const int32_t r = a - mul24(q, s);
+    q += (r >= s) ? 1 : 0;
+    q -= (r < 0) ? 1 : 0;
+    return q;
+}
+
 TAD_HD void flat_bounds(const FlatLevel &L, const int32_t *y, int32_t &lo, int32_t &hi) {
     int32_t l = INT32_MIN, h = INT32_MAX;
 TAD_UNROLL
@@ -161,8 +178,8 @@ TAD_UNROLL
             a += mul24(L.lky[r][c], y[c]);
             b += mul24(L.hky[r][c], y[c]);
         }
-        a = ceil_div_i(a, L.ls[r]);
-        b = floor_div_i(b, L.hs[r]);
+        a = -floor_div_flat(-a, L.ls[r], L.lrs[r]);   // ceil
+        b = floor_div_flat(b, L.hs[r], L.hrs[r]);
         l = a > l ? a : l;
         h = b < h ? b : h;
     }

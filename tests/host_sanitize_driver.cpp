@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "../include/tad.h"
+#include "../paper_1711_01348_amd/csrc/plan_dev.h"
 
 static int derive_worked(int64_t I, int64_t J, int64_t K, tad_dtype dt, uint32_t flags) {
     tad_expr e;
@@ -79,6 +80,29 @@ int main() {
     if (tad_smith_normal_form(Ab, 2, 2, S, U, V, &R) != TAD_EOVERFLOW) return 7;
     int64_t g, x, y;
     if (tad_extended_gcd(INT64_MIN, 3, &g, &x, &y) != TAD_EOVERFLOW) return 8;
+    // the loop-free floor division is exact on its whole domain (|a| < 2^23, 0 < s < 2^23)
+    {
+        const int32_t lim = (1 << 23) - 1;
+        unsigned st = 99;
+        auto next = [&]() { st = st * 1664525u + 1013904223u; return st; };
+        auto exact = [](int64_t a, int64_t s) { int64_t q = a / s; if (a % s != 0 && a < 0) --q; return (int32_t)q; };
+        for (int32_t s = 1; s <= 64; ++s) {
+            const float rs = 1.f / (float)s;
+            for (int32_t a = -lim; a <= lim; a += (s <= 8 ? 1 : 97))
+                if (tad::floor_div_flat(a, s, rs) != exact(a, s)) return 9;
+            for (int32_t a : {-lim, -lim + 1, -s, -s - 1, -s + 1, -1, 0, 1, s - 1, s, s + 1, lim - 1, lim})
+                if (tad::floor_div_flat(a, s, rs) != exact(a, s)) return 10;
+        }
+        for (int t = 0; t < 2000000; ++t) {
+            const int32_t s = 1 + (int32_t)(next() % (unsigned)lim);
+            const int32_t a = (int32_t)(next() % (2u * lim + 1)) - lim;
+            if (tad::floor_div_flat(a, s, 1.f / (float)s) != exact(a, s)) return 11;
+            // multiples of s and their neighbours are the hard cases
+            const int32_t m = (int32_t)((int64_t)(a / s) * s);
+            for (int32_t d = -1; d <= 1; ++d)
+                if (m + d >= -lim && m + d <= lim && tad::floor_div_flat(m + d, s, 1.f / (float)s) != exact(m + d, s)) return 12;
+        }
+    }
     std::puts("sanitizer driver ok");
     return 0;
 }

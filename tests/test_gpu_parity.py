@@ -109,6 +109,9 @@ ASSORTED = [
     lambda: wl.strided_tanh_expr(3, 19, 23, 5, 4, 3, "f32"),
     lambda: wl.strided_tanh_expr(2, 30, 41, 2, 2, 1, "f32"),
     lambda: wl.strided_tanh_expr(2, 5, 4, 2, 3, 3, "f64"),
+    lambda: wl.strided_tanh_expr(2, 5, 130, 7, 7, 8, "f32"),     # 49 taps, stride 8: general range divisors
+    lambda: wl.strided_tanh_expr(2, 9, 200, 3, 3, 2, "f32"),
+    lambda: wl.strided_tanh_expr(1, 6, 70, 4, 5, 1, "f32"),      # stride 1: up to 20 terms per gradient element
     # a tensor that occurs twice: the gradient is the sum over both occurrences
     lambda: wl.matrix_square_expr(23, "f64"),
     lambda: wl.matrix_square_expr(67, "f32"),
