@@ -26,6 +26,27 @@ PROFILE_EVERY = 7               # every 7th launch of the dominant kernel carrie
 ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 2x the 256 MB last-level cache)
 
 
+# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a plain
+# 256 MiB copy in the same run (summaries under profiles/).  Each entry carries the SHA-256 prefix of the kernel source
+# the counters were taken with; once that file changes the entry is stale and the bench line reports traffic = null.
+MEASURED_TRAFFIC = {
+    "cfg3": dict(source="kernels_worked.hip", sha256="5f117112224f3767", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
+            summary="profiles/worked_8192x8192x5_f32.md"),
+    "cfg4": dict(source="kernels_mfma.hip", sha256="38ef1379bb0b16f5", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
+            summary="profiles/worked_mfma_4096x4096x256_f32.md"),
+    "matmul": dict(source="kernels_contract.hip", sha256="766cfe452e2e41d9", fetch_bytes=512.1 * 2**20, write_bytes=64.0 * 2**20,
+            summary="profiles/contraction_4096x4096x4096_f32.md"),
+    "cfg2_1": dict(source="kernels_patterns.hip", sha256="4032b4c2ce4eaabb", fetch_bytes=64.1 * 2**20, write_bytes=0.0 * 2**20,
+            summary="profiles/row_reduce_4096x4096_f32.md"),
+    "cfg2_2": dict(source="kernels_patterns.hip", sha256="4032b4c2ce4eaabb", fetch_bytes=1.1 * 2**20, write_bytes=256.3 * 2**20,
+            summary="profiles/diagonal_8192_f32.md"),
+    "cfg2_3": dict(source="kernels_patterns.hip", sha256="4032b4c2ce4eaabb", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
+            summary="profiles/antidiagonal_4096x4096_f32.md"),
+    "cfg5": dict(source="kernels_strided.hip", sha256="ed800e41532ec145", fetch_bytes=24.1 * 2**20, write_bytes=8.1 * 2**20,
+            summary="profiles/strided_32x128x128_f32.md"),
+}
+
+
 def workload(name):
     from paper_1711_01348_amd import workloads as wl
     table = {
@@ -138,11 +159,28 @@ def run_gpu(name, steps, warmup, rotate_bytes=0):
     ev[2].record()
     torch.cuda.synchronize()
     ms_step = (t1 - t0) * 1e3 / steps
-    return dict(workload=w.name, ms_per_step=ms_step, elements=elems, bytes=nbytes,
+    return dict(name=name, workload=w.name, ms_per_step=ms_step, elements=elems, bytes=nbytes,
                 elements_per_s=elems / (ms_step * 1e-3), algorithmic_gbs=nbytes / (ms_step * 1e-3) / 1e9,
                 ms_forward=ev[0].elapsed_time(ev[1]), ms_backward=ev[1].elapsed_time(ev[2]),
                 dominant=dom, dominant_ms=dom_ms, dominant_launches=n.value, families=families,
                 dtype=w.expr.dtype, buffer_sets=len(sets), footprint_bytes_per_set=foot)
+
+
+def measured_traffic(name):
+    """Per-launch HBM bytes of the dominant kernel from the committed counter runs, or None if the kernel source
+    has changed since."""
+    import hashlib
+    t = MEASURED_TRAFFIC.get(name)
+    if not t:
+        return None
+    src = os.path.join(ROOT, "paper_1711_01348_amd", "csrc", t["source"])
+    try:
+        with open(src, "rb") as fh:
+            if hashlib.sha256(fh.read()).hexdigest()[:16] != t["sha256"]:
+                return None
+    except OSError:
+        return None
+    return t["fetch_bytes"] + t["write_bytes"]
 
 
 def roofline(r):
@@ -155,7 +193,7 @@ def roofline(r):
     else:
         achieved, peak, unit = dom["per_launch"] / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
     return {"bound": dom["bound"], "kernel": dom["kernel"], "achieved": achieved, "peak": peak, "unit": unit,
-            "frac": achieved / peak, "traffic": None, "avg_kernel_ms": ms, "launches": r["dominant_launches"], "timed_every": PROFILE_EVERY,
+            "frac": achieved / peak, "traffic": measured_traffic(r["name"]), "avg_kernel_ms": ms, "launches": r["dominant_launches"], "timed_every": PROFILE_EVERY,
             "algorithmic_per_launch": dom["per_launch"]}
 
 
