@@ -64,8 +64,33 @@ typedef enum {
     TAD_BODY_EXP = 3,      /* exp(sum x)                            (Sec. 1, Sec. 5 f^5) 1 argument */
     TAD_BODY_MUL = 4,      /* sum x*y                               (Sec. 5, f^2, f^4)  2 arguments */
     TAD_BODY_WORKED = 5,   /* exp(-sum((a+b)^2 c + d^3))            (Sec. 1, Sec. 6)    4 arguments a,b,c,d */
-    TAD_BODY_TANH_DOT = 6  /* tanh(sum x*w)                                             2 arguments x,w */
+    TAD_BODY_TANH_DOT = 6, /* tanh(sum x*w)                                             2 arguments x,w */
+    TAD_BODY_PROGRAM = 7   /* inner and outer function given as postfix programs (tad_op), 1..4 operands;
+                              their derivatives are derived by reverse accumulation (Sec. 2) at plan time */
 } tad_body;
+
+/*
+ * Scalar functions given as postfix (reverse Polish) programs.  The inner program combines the operand values
+ * of one extended index (TAD_OP_ARG p pushes the value of operand p), the outer program maps the summed inner
+ * values to f (TAD_OP_SUM pushes that sum); each must leave exactly one value on the stack.
+ */
+typedef enum {
+    TAD_OP_CONST = 0, /* push `value` */
+    TAD_OP_ARG = 1,   /* inner program only: push the value of operand `iarg` */
+    TAD_OP_SUM = 2,   /* outer program only: push the summed inner value */
+    TAD_OP_ADD = 3, TAD_OP_SUB = 4, TAD_OP_MUL = 5, TAD_OP_DIV = 6,   /* pop b, pop a, push a op b */
+    TAD_OP_NEG = 7, TAD_OP_EXP = 8, TAD_OP_LOG = 9, TAD_OP_SIN = 10, TAD_OP_COS = 11, TAD_OP_TANH = 12,
+    TAD_OP_SQRT = 13, /* pop a, push op(a) */
+    TAD_OP_POWI = 14  /* pop a, push a^iarg for an integer exponent 1 <= iarg <= 16 */
+} tad_opcode;
+
+typedef struct {
+    int32_t op;    /* tad_opcode */
+    int32_t iarg;  /* operand index (ARG) or exponent (POWI) */
+    double value;  /* CONST */
+} tad_op;
+
+#define TAD_MAX_PROGRAM 24 /* operations per program */
 
 /* Element-wise definition of f (Sec. 5.1): shape of f and the summation ranges Psi (Sec. 5.2). */
 typedef struct {
@@ -75,6 +100,11 @@ typedef struct {
     int32_t n_sum;                 /* number of summation indices; n_f + n_sum <= TAD_MAX_EXT */
     int64_t sum_lo[TAD_MAX_EXT];   /* inclusive constant limits of every summation index */
     int64_t sum_hi[TAD_MAX_EXT];
+    /* TAD_BODY_PROGRAM only (ignored otherwise) */
+    int32_t n_operands;            /* operands of the inner program, 1..TAD_MAX_ARGS */
+    int32_t n_inner, n_outer;      /* program lengths, 1..TAD_MAX_PROGRAM */
+    tad_op inner[TAD_MAX_PROGRAM];
+    tad_op outer[TAD_MAX_PROGRAM];
 } tad_expr;
 
 /*
@@ -122,7 +152,8 @@ typedef enum {
     TAD_FAMILY_WORKED = 4,       /* fused kernels for the worked expression */
     TAD_FAMILY_WORKED_MFMA = 5,  /* worked expression, long summed index: expanded cross term on MFMA */
     TAD_FAMILY_STRIDED = 6,      /* strided stencil */
-    TAD_FAMILY_CONTRACTION = 7   /* product of two matrices over one summation index: dense products on MFMA */
+    TAD_FAMILY_CONTRACTION = 7,  /* product of two matrices over one summation index: dense products on MFMA */
+    TAD_FAMILY_PROGRAM = 8       /* program body: generic plan-driven kernels with an interpreter for the scalar part */
 } tad_family;
 
 /* which set of Fourier-Motzkin rows tad_plan_bound_row reads */
@@ -215,6 +246,15 @@ int tad_plan_forward_family(const tad_plan *plan);
  *                         lexicographic order; n <= TAD_MAX_RANK, m <= TAD_MAX_EXT, kernel dimension
  *                         <= TAD_MAX_KERNEL.  Writes up to cap points (m int64 each), total to *count.
  */
+/*
+ * Host evaluation of the scalar functions of a TAD_BODY_PROGRAM plan in fp64, exactly the derived programs the
+ * kernels interpret (for checking the symbolic differentiation without a GPU):
+ *   which = -1: inner value            which = p >= 0: d inner / d operand p     (values[n_operands], host, read)
+ *   which = -2: outer(sum)             which = -3: d outer / d sum               (sum is used, values may be NULL)
+ * Errors: EINVAL (not a program plan, bad `which`, NULL).
+ */
+int tad_plan_program_eval(const tad_plan *plan, int which, const double *values, double sum, double *out);
+
 int tad_extended_gcd(int64_t a, int64_t b, int64_t *g, int64_t *x, int64_t *y);
 int tad_smith_normal_form(const int64_t *A, int n, int m, int64_t *S, int64_t *U, int64_t *V, int *rank);
 int tad_lattice_enumerate(const int64_t *A, int n, int m, const int64_t *lo, const int64_t *hi,

@@ -31,6 +31,16 @@ class _Arg(ctypes.Structure):
                 ("A", (ctypes.c_int64 * MAX_EXT) * MAX_RANK)]
 
 
+MAX_PROGRAM = 24
+# postfix operation names of a program body -> the oracle's own codes (enum O_* in tad_oracle.c)
+_OPS = {"const": 0, "arg": 1, "sum": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "exp": 8, "log": 9,
+        "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14}
+
+
+class _Op(ctypes.Structure):
+    _fields_ = [("op", ctypes.c_int), ("iarg", ctypes.c_int), ("value", ctypes.c_double)]
+
+
 class _Expr(ctypes.Structure):
     _fields_ = [("body", ctypes.c_char * 16),
                 ("n_f", ctypes.c_int),
@@ -39,7 +49,9 @@ class _Expr(ctypes.Structure):
                 ("sum_lo", ctypes.c_int64 * MAX_EXT),
                 ("sum_hi", ctypes.c_int64 * MAX_EXT),
                 ("n_args", ctypes.c_int),
-                ("args", _Arg * MAX_ARGS)]
+                ("args", _Arg * MAX_ARGS),
+                ("n_inner", ctypes.c_int), ("n_outer", ctypes.c_int),
+                ("inner", _Op * MAX_PROGRAM), ("outer", _Op * MAX_PROGRAM)]
 
 
 def build(force: bool = False) -> str:
@@ -90,6 +102,15 @@ def _pack(expr) -> _Expr:
             assert len(a.A[r]) == n_ext
             for d in range(n_ext):
                 e.args[p].A[r][d] = int(a.A[r][d])
+    if expr.body == "program":
+        for name, dst in (("inner", e.inner), ("outer", e.outer)):
+            prog = list(getattr(expr, name))
+            assert 1 <= len(prog) <= MAX_PROGRAM
+            for i, t in enumerate(prog):
+                dst[i].op = _OPS[t[0]]
+                dst[i].iarg = int(t[1]) if t[0] in ("arg", "powi") else 0
+                dst[i].value = float(t[1]) if t[0] == "const" else 0.0
+        e.n_inner, e.n_outer = len(expr.inner), len(expr.outer)
     return e
 
 

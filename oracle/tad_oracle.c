@@ -26,6 +26,10 @@
  *   "mul"      inner = x*y          outer = s
  *   "worked"   inner = (a+b)^2 c + d^3   outer = exp(-s)      (Sec. 1, Sec. 6)
  *   "tanh_dot" inner = x*w          outer = tanh s
+ *   "program"  inner and outer given as postfix programs over the operand values / the sum; their
+ *              derivatives are taken by forward-mode differentiation with dual numbers (value and
+ *              derivative carried together through every operation), the textbook rules of Sec. 2's
+ *              elementary functions -- deliberately not the reverse accumulation the GPU library uses.
  */
 #include <math.h>
 #include <stdint.h>
@@ -45,6 +49,15 @@ typedef struct {
     int64_t A[ORC_MAX_RANK][ORC_MAX_EXT]; /* index matrix, columns: function then summation indices */
 } orc_arg;
 
+#define ORC_MAX_PROGRAM 24
+/* postfix operation codes of a program body */
+enum { O_CONST, O_ARG, O_SUM, O_ADD, O_SUB, O_MUL, O_DIV, O_NEG, O_EXP, O_LOG, O_SIN, O_COS, O_TANH, O_SQRT, O_POWI };
+typedef struct {
+    int op;        /* O_* */
+    int iarg;      /* operand index (O_ARG) or integer exponent (O_POWI) */
+    double value;  /* O_CONST */
+} orc_op;
+
 typedef struct {
     char body[16];
     int n_f;                       /* number of function indices */
@@ -53,9 +66,11 @@ typedef struct {
     int64_t sum_lo[ORC_MAX_EXT], sum_hi[ORC_MAX_EXT]; /* inclusive limits */
     int n_args;
     orc_arg args[ORC_MAX_ARGS];
+    int n_inner, n_outer;          /* body "program" only */
+    orc_op inner[ORC_MAX_PROGRAM], outer[ORC_MAX_PROGRAM];
 } orc_expr;
 
-enum { B_SQ, B_CUBE, B_SIN, B_EXP, B_MUL, B_WORKED, B_TANH_DOT, B_UNKNOWN };
+enum { B_SQ, B_CUBE, B_SIN, B_EXP, B_MUL, B_WORKED, B_TANH_DOT, B_PROGRAM, B_UNKNOWN };
 
 static int body_id(const char *s) {
     if (!strcmp(s, "sq")) return B_SQ;
@@ -65,6 +80,7 @@ static int body_id(const char *s) {
     if (!strcmp(s, "mul")) return B_MUL;
     if (!strcmp(s, "worked")) return B_WORKED;
     if (!strcmp(s, "tanh_dot")) return B_TANH_DOT;
+    if (!strcmp(s, "program")) return B_PROGRAM;
     return B_UNKNOWN;
 }
 
@@ -77,8 +93,55 @@ static int body_nargs(int b) {
     }
 }
 
+/* A value together with its derivative with respect to one chosen input. */
+typedef struct { double v, d; } dual;
+
+/*
+ * Run a postfix program on dual numbers.  `args` are the operand values (inner program), `sum` the summed
+ * inner value (outer program).  The input `seed` (operand index; 0 for the sum) has derivative one, every
+ * other input and every constant derivative zero; seed < 0 gives the plain value.  A malformed program
+ * yields NaN.
+ */
+static dual run_program(const orc_op *ops, int n, const double *args, double sum, int seed) {
+    dual st[ORC_MAX_PROGRAM + 1];
+    int top = 0;
+    const dual bad = {NAN, NAN};
+    for (int i = 0; i < n; ++i) {
+        const orc_op *o = &ops[i];
+        dual r;
+        if (o->op == O_CONST) { r.v = o->value; r.d = 0.0; }
+        else if (o->op == O_ARG) { r.v = args[o->iarg]; r.d = (o->iarg == seed) ? 1.0 : 0.0; }
+        else if (o->op == O_SUM) { r.v = sum; r.d = (seed == 0) ? 1.0 : 0.0; }
+        else if (o->op >= O_ADD && o->op <= O_DIV) {
+            if (top < 2) return bad;
+            dual y = st[--top], x = st[--top];
+            if (o->op == O_ADD) { r.v = x.v + y.v; r.d = x.d + y.d; }
+            else if (o->op == O_SUB) { r.v = x.v - y.v; r.d = x.d - y.d; }
+            else if (o->op == O_MUL) { r.v = x.v * y.v; r.d = x.d * y.v + x.v * y.d; }
+            else { r.v = x.v / y.v; r.d = (x.d - r.v * y.d) / y.v; }
+        } else {
+            if (top < 1) return bad;
+            dual x = st[--top];
+            switch (o->op) {
+            case O_NEG: r.v = -x.v; r.d = -x.d; break;
+            case O_EXP: r.v = exp(x.v); r.d = x.d * r.v; break;
+            case O_LOG: r.v = log(x.v); r.d = x.d / x.v; break;
+            case O_SIN: r.v = sin(x.v); r.d = x.d * cos(x.v); break;
+            case O_COS: r.v = cos(x.v); r.d = -x.d * sin(x.v); break;
+            case O_TANH: r.v = tanh(x.v); r.d = x.d * (1.0 - r.v * r.v); break;
+            case O_SQRT: r.v = sqrt(x.v); r.d = x.d / (2.0 * r.v); break;
+            case O_POWI: r.v = pow(x.v, (double)o->iarg); r.d = x.d * (double)o->iarg * pow(x.v, (double)(o->iarg - 1)); break;
+            default: return bad;
+            }
+        }
+        st[top++] = r;
+    }
+    return top == 1 ? st[0] : bad;
+}
+
 /* summand s(v) of the inner sum */
-static double inner(int b, const double *v) {
+static double inner(const orc_expr *e, int b, const double *v) {
+    if (b == B_PROGRAM) return run_program(e->inner, e->n_inner, v, 0.0, -1).v;
     switch (b) {
     case B_MUL: case B_TANH_DOT: return v[0] * v[1];
     case B_WORKED: { double t = v[0] + v[1]; return t * t * v[2] + v[3] * v[3] * v[3]; }
@@ -87,7 +150,8 @@ static double inner(int b, const double *v) {
 }
 
 /* d s / d v[p] */
-static double dinner(int b, int p, const double *v) {
+static double dinner(const orc_expr *e, int b, int p, const double *v) {
+    if (b == B_PROGRAM) return run_program(e->inner, e->n_inner, v, 0.0, p).d;
     switch (b) {
     case B_MUL: case B_TANH_DOT: return p == 0 ? v[1] : v[0];
     case B_WORKED:
@@ -98,7 +162,8 @@ static double dinner(int b, int p, const double *v) {
     }
 }
 
-static double outer(int b, double s) {
+static double outer(const orc_expr *e, int b, double s) {
+    if (b == B_PROGRAM) return run_program(e->outer, e->n_outer, NULL, s, -1).v;
     switch (b) {
     case B_SQ: return s * s;
     case B_CUBE: return s * s * s;
@@ -112,7 +177,8 @@ static double outer(int b, double s) {
 }
 
 /* d outer / d s */
-static double douter(int b, double s) {
+static double douter(const orc_expr *e, int b, double s) {
+    if (b == B_PROGRAM) return run_program(e->outer, e->n_outer, NULL, s, 0).d;
     switch (b) {
     case B_SQ: return 2.0 * s;
     case B_CUBE: return 3.0 * s * s;
@@ -140,7 +206,15 @@ static int64_t arg_pos(const orc_arg *a, int n_ext, const int64_t *ext) {
 static int check_expr(const orc_expr *e, int *b) {
     *b = body_id(e->body);
     if (*b == B_UNKNOWN) return -1;
-    if (e->n_args != body_nargs(*b)) return -2;
+    if (*b == B_PROGRAM) {
+        if (e->n_args < 1 || e->n_args > ORC_MAX_ARGS) return -2;
+        if (e->n_inner < 1 || e->n_inner > ORC_MAX_PROGRAM || e->n_outer < 1 || e->n_outer > ORC_MAX_PROGRAM) return -5;
+        for (int i = 0; i < e->n_inner; ++i)
+            if (e->inner[i].op == O_SUM || (e->inner[i].op == O_ARG && (e->inner[i].iarg < 0 || e->inner[i].iarg >= e->n_args)))
+                return -5;
+        for (int i = 0; i < e->n_outer; ++i)
+            if (e->outer[i].op == O_ARG) return -5;
+    } else if (e->n_args != body_nargs(*b)) return -2;
     if (e->n_f < 0 || e->n_sum < 0 || e->n_f + e->n_sum > ORC_MAX_EXT) return -3;
     for (int p = 0; p < e->n_args; ++p)
         if (e->args[p].rank < 1 || e->args[p].rank > ORC_MAX_RANK) return -4;
@@ -184,7 +258,7 @@ static int eval_s(const orc_expr *e, int b, const double *const *args, int64_t *
                 if (pos < 0) return -10;
                 v[p] = args[p][pos];
             }
-            s += inner(b, v);
+            s += inner(e, b, v);
         } while (next_sum(e, ext));
     }
     *s_out = s;
@@ -203,7 +277,7 @@ int orc_forward(const orc_expr *e, const double *const *args, double *f) {
         double s;
         unflatten_f(e, lin, ext);
         if (eval_s(e, b, args, ext, &s)) { err = -10; continue; }
-        f[lin] = outer(b, s);
+        f[lin] = outer(e, b, s);
     }
     return err;
 }
@@ -252,7 +326,7 @@ int orc_backward(const orc_expr *e, const double *const *args, const double *df,
                 double s;
                 unflatten_f(e, lin, ext);
                 if (eval_s(e, b, args, ext, &s)) { err = -10; break; }
-                double w = df[lin] * douter(b, s);
+                double w = df[lin] * douter(e, b, s);
                 if (sums_empty(e)) continue;
                 for (int q = 0; q < e->n_sum; ++q) ext[e->n_f + q] = e->sum_lo[q];
                 do {
@@ -261,7 +335,7 @@ int orc_backward(const orc_expr *e, const double *const *args, const double *df,
                         v[p] = args[p][pos[p]];
                     }
                     for (int p = 0; p < e->n_args; ++p)
-                        if (my[p]) my[p][pos[p]] += w * dinner(b, p, v);
+                        if (my[p]) my[p][pos[p]] += w * dinner(e, b, p, v);
                 } while (next_sum(e, ext));
             }
         }

@@ -18,21 +18,30 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtad.so")
 
 F32, F64 = 0, 1
-BODY = {"sq": 0, "cube": 1, "sin": 2, "exp": 3, "mul": 4, "worked": 5, "tanh_dot": 6}
+BODY = {"sq": 0, "cube": 1, "sin": 2, "exp": 3, "mul": 4, "worked": 5, "tanh_dot": 6, "program": 7}
+MAX_PROGRAM = 24
+OPCODE = {"const": 0, "arg": 1, "sum": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "exp": 8, "log": 9,
+          "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14}
 FAMILY = {0: "generic", 1: "row_reduce", 2: "diagonal", 3: "antidiagonal", 4: "worked",
-          5: "worked_mfma", 6: "strided", 7: "contraction"}
+          5: "worked_mfma", 6: "strided", 7: "contraction", 8: "program"}
 PLAN_GENERIC_ONLY = 1
 ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
            "tad_plan_bound_row", "tad_plan_enumerate", "tad_plan_count_all", "tad_eval_forward",
-           "tad_eval_backward", "tad_plan_forward_family", "tad_strerror"]
+           "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval"]
+
+
+class TadOp(ctypes.Structure):
+    _fields_ = [("op", ctypes.c_int32), ("iarg", ctypes.c_int32), ("value", ctypes.c_double)]
 
 
 class TadExpr(ctypes.Structure):
     _fields_ = [("body", ctypes.c_int32), ("n_f", ctypes.c_int32),
                 ("f_shape", ctypes.c_int64 * MAX_EXT), ("n_sum", ctypes.c_int32),
-                ("sum_lo", ctypes.c_int64 * MAX_EXT), ("sum_hi", ctypes.c_int64 * MAX_EXT)]
+                ("sum_lo", ctypes.c_int64 * MAX_EXT), ("sum_hi", ctypes.c_int64 * MAX_EXT),
+                ("n_operands", ctypes.c_int32), ("n_inner", ctypes.c_int32), ("n_outer", ctypes.c_int32),
+                ("inner", TadOp * MAX_PROGRAM), ("outer", TadOp * MAX_PROGRAM)]
 
 
 class TadArg(ctypes.Structure):
@@ -83,6 +92,7 @@ def _load():
     lib.tad_eval_backward.argtypes = [vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp,
                                       ctypes.c_size_t, vp]
     lib.tad_plan_forward_family.argtypes = [vp]
+    lib.tad_plan_program_eval.argtypes = [vp, ctypes.c_int, vp, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
     lib.tad_strerror.argtypes = [ctypes.c_int]
     lib.tad_strerror.restype = ctypes.c_char_p
     return lib
@@ -109,6 +119,20 @@ def pack_expr(expr) -> TadExpr:
     e.n_sum = len(expr.sums)
     for s, (lo, hi) in enumerate(expr.sums):
         e.sum_lo[s], e.sum_hi[s] = int(lo), int(hi)
+    if expr.body == "program":
+        # postfix programs as lists of tuples: ("arg", p), ("const", c), ("sum",), ("powi", n), ("add",), ...
+        e.n_operands = len(expr.args)
+        for name, dst in (("inner", e.inner), ("outer", e.outer)):
+            prog = list(getattr(expr, name))
+            if len(prog) > MAX_PROGRAM:
+                raise TadError(-1, "tad_plan_derive")
+            for i, t in enumerate(prog):
+                dst[i].op = OPCODE[t[0]]
+                if t[0] in ("arg", "powi"):
+                    dst[i].iarg = int(t[1])
+                elif t[0] == "const":
+                    dst[i].value = float(t[1])
+        e.n_inner, e.n_outer = len(expr.inner), len(expr.outer)
     return e
 
 
@@ -197,6 +221,15 @@ class Plan:
             _check(lib.tad_plan_enumerate(self._h, arg, occ, b.ctypes.data, out.ctypes.data, n.value,
                                           ctypes.byref(n)), "tad_plan_enumerate")
         return out
+
+    def program_eval(self, which: int, values=None, total: float = 0.0) -> float:
+        """Host evaluation of the derived scalar programs: which = -1 inner, p >= 0 d inner / d operand p,
+        -2 outer(total), -3 d outer / d total."""
+        out = ctypes.c_double(0.0)
+        v = None if values is None else np.ascontiguousarray(values, dtype=np.float64)
+        _check(lib.tad_plan_program_eval(self._h, which, None if v is None else v.ctypes.data, float(total),
+                                         ctypes.byref(out)), "tad_plan_program_eval")
+        return out.value
 
     def count_all(self, arg: int) -> np.ndarray:
         counts = np.empty(tuple(self.expr.args[arg].shape), dtype=np.int64)

@@ -293,6 +293,13 @@ void select_families(tad_plan &plan) {
     plan.fwd_family = TAD_FAMILY_GENERIC;
     for (auto &ap : plan.ap) ap.family = TAD_FAMILY_GENERIC;
     plan.ws_bytes = 0;
+    if (plan.expr.body == TAD_BODY_PROGRAM) {
+        // interpreter kernels; the backward pass keeps g = df * outer'(sum) for every function element
+        plan.fwd_family = TAD_FAMILY_PROGRAM;
+        for (auto &ap : plan.ap) ap.family = TAD_FAMILY_PROGRAM;
+        plan.ws_bytes = align256((size_t)plan.f_count * (plan.dtype == TAD_F64 ? 8 : 4));
+        return;
+    }
     if ((plan.flags & TAD_PLAN_GENERIC_ONLY) || plan.has_alias) return;
     if (match_worked(plan)) return;
     if (match_patterns(plan)) return;

@@ -1,0 +1,207 @@
+// Plan-driven kernels for scalar bodies given as programs.  Index handling is that of the generic kernels (one
+// thread per function index / per gradient element, masks and nested ranges from the plan); the scalar part is a
+// small interpreter of the three-address programs derived on the host: the inner and outer function for the
+// forward pass, and for the backward pass their derivatives obtained by reverse accumulation (Sec. 2).
+//
+//   forward   f_alpha = outer( sum_k inner(values at [alpha k]) )
+//   prepare   g_alpha = df_alpha * outer'( sum_k inner(...) )         (shared by all gradients, Sec. 5.3: the
+//             derivative graph reuses common sub-expressions; stored in the workspace)
+//   gather    dx^p_beta = sum_{z in Sigma(beta)} g_alpha * (d inner / d x^p)(values at [alpha k]),  [alpha k] = I beta + K z
+#include <hip/hip_runtime.h>
+
+#include "launch.h"
+#include "plan_dev.h"
+#include "profile.h"
+
+namespace tad {
+
+template <typename T> struct Fn;
+template <> struct Fn<float> {
+    static __device__ __forceinline__ float exp_(float x) { return expf(x); }
+    static __device__ __forceinline__ float log_(float x) { return logf(x); }
+    static __device__ __forceinline__ float sin_(float x) { return sinf(x); }
+    static __device__ __forceinline__ float cos_(float x) { return cosf(x); }
+    static __device__ __forceinline__ float tanh_(float x) { return tanhf(x); }
+    static __device__ __forceinline__ float sqrt_(float x) { return sqrtf(x); }
+};
+template <> struct Fn<double> {
+    static __device__ __forceinline__ double exp_(double x) { return exp(x); }
+    static __device__ __forceinline__ double log_(double x) { return log(x); }
+    static __device__ __forceinline__ double sin_(double x) { return sin(x); }
+    static __device__ __forceinline__ double cos_(double x) { return cos(x); }
+    static __device__ __forceinline__ double tanh_(double x) { return tanh(x); }
+    static __device__ __forceinline__ double sqrt_(double x) { return sqrt(x); }
+};
+
+// One pass over the operations; temporaries live in the thread's private memory.
+template <typename T>
+__device__ T prog_eval(const DevProg &P, const T *v, T s) {
+    if (P.result < 0) return T(0);
+    T t[kMaxProgOps];
+    for (int i = 0; i < P.n; ++i) {
+        const int a = P.a[i], b = P.b[i];
+        T r;
+        switch (P.op[i]) {
+        case P_CONST: r = (T)P.cst[a]; break;
+        case P_ARG: r = v[a]; break;
+        case P_SUM: r = s; break;
+        case P_ADD: r = t[a] + t[b]; break;
+        case P_SUB: r = t[a] - t[b]; break;
+        case P_MUL: r = t[a] * t[b]; break;
+        case P_DIV: r = t[a] / t[b]; break;
+        case P_NEG: r = -t[a]; break;
+        case P_EXP: r = Fn<T>::exp_(t[a]); break;
+        case P_LOG: r = Fn<T>::log_(t[a]); break;
+        case P_SIN: r = Fn<T>::sin_(t[a]); break;
+        case P_COS: r = Fn<T>::cos_(t[a]); break;
+        case P_TANH: r = Fn<T>::tanh_(t[a]); break;
+        case P_SQRT: r = Fn<T>::sqrt_(t[a]); break;
+        case P_POWI: {
+            const T x = t[a];
+            r = x;
+            for (int e = 1; e < P.k[i]; ++e) r *= x;
+            break;
+        }
+        default: r = T(0);
+        }
+        t[i] = r;
+    }
+    return t[P.result];
+}
+
+// sum over the summation box of inner(values) for one function index, fp64 accumulation
+template <typename T>
+__device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_ops, const ArgPtrs &A, int lin) {
+    int32_t ext[kMaxExt];
+    {
+        int t = lin;
+        for (int d = P.n_f - 1; d >= 0; --d) { ext[d] = t % P.f_shape[d]; t /= P.f_shape[d]; }
+    }
+    int64_t base[kMaxArgs];
+    for (int p = 0; p < n_ops; ++p) {
+        int64_t o = 0;
+        for (int d = 0; d < P.n_f; ++d) o += P.off[p][d] * (int64_t)ext[d];
+        for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)P.sum_lo[s];
+        base[p] = o;
+    }
+    int32_t k[kMaxExt] = {0};
+    double acc = 0.0;
+    for (;;) {
+        T v[kMaxArgs];
+        for (int p = 0; p < n_ops; ++p) {
+            int64_t o = base[p];
+            for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)k[s];
+            v[p] = static_cast<const T *>(A.p[p])[o];
+        }
+        acc += (double)prog_eval<T>(inner, v, T(0));
+        int s = P.n_sum - 1;
+        for (; s >= 0; --s) {
+            if (++k[s] < P.sum_n[s]) break;
+            k[s] = 0;
+        }
+        if (s < 0) break;
+    }
+    return acc;
+}
+
+// df == nullptr: out = outer(sum) (forward);  otherwise out = df * outer'(sum) (backward preparation)
+template <typename T>
+__global__ __launch_bounds__(256) void k_program_forward(const ForwardPlan P, const DevProg inner, const DevProg outer,
+                                                         int n_ops, const ArgPtrs A, const T *__restrict__ df,
+                                                         T *__restrict__ out, int nf) {
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= nf) return;
+    const T s = (T)inner_sum<T>(P, inner, n_ops, A, lin);
+    const T o = prog_eval<T>(outer, nullptr, s);
+    out[lin] = df ? df[lin] * o : o;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, const DevProg dinner, int n_ops,
+                                                        const ArgPtrs A, const T *__restrict__ g,
+                                                        T *__restrict__ dx, int n, int accumulate) {
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= n) return;
+    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
+    {
+        int t = lin;
+        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+    }
+    if (!gather_prepare(P, beta, y)) {
+        if (!accumulate) dx[lin] = T(0);
+        return;
+    }
+    const T prev = accumulate ? dx[lin] : T(0);
+    double acc = 0.0;
+    int32_t z[kMaxKernel] = {0, 0, 0, 0}, hi[kMaxKernel] = {0, 0, 0, 0};
+    auto term = [&]() {
+        T v[kMaxArgs];
+        for (int q = 0; q < n_ops; ++q) v[q] = static_cast<const T *>(A.p[q])[gather_offset(P, q, y, z)];
+        acc += (double)(g[gather_offset(P, kSlotF, y, z)] * prog_eval<T>(dinner, v, T(0)));
+    };
+    if (P.kappa == 0) {
+        term();
+        dx[lin] = prev + (T)acc;
+        return;
+    }
+    int lvl = P.kappa - 1;
+    gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
+    for (;;) {
+        if (z[lvl] > hi[lvl]) {
+            if (++lvl == P.kappa) break;
+            ++z[lvl];
+            continue;
+        }
+        if (lvl == 0) {
+            term();
+            ++z[0];
+        } else {
+            --lvl;
+            gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
+        }
+    }
+    dx[lin] = prev + (T)acc;
+}
+
+template <typename T>
+static int fwd_t(const tad_plan &pl, const void *const *args, const void *df, void *out, hipStream_t s) {
+    ArgPtrs A{};
+    for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
+    const int nf = (int)pl.f_count;
+    TAD_LAUNCH("k_program_forward", (k_program_forward<T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
+               pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), A, static_cast<const T *>(df),
+               static_cast<T *>(out), nf);
+    return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+}
+
+int program_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s) {
+    return pl.dtype == TAD_F64 ? fwd_t<double>(pl, args, nullptr, f, s) : fwd_t<float>(pl, args, nullptr, f, s);
+}
+
+template <typename T>
+static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
+                 hipStream_t s) {
+    int rc = fwd_t<T>(pl, args, df, ws, s);   // g = df * outer'(sum) into the workspace
+    if (rc) return rc;
+    ArgPtrs A{};
+    for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
+    // the gradient of a tensor is the sum over its occurrences: the first occurrence stores, aliases add
+    for (size_t q = 0; q < pl.args.size(); ++q) {
+        const size_t p = (size_t)pl.root[q];
+        if (!dx[p]) continue;
+        if (!pl.ap[q].derived) return TAD_EINVAL;
+        const int n = (int)pl.arg_count[p];
+        TAD_LAUNCH("k_program_gather", (k_program_gather<T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
+                   pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
+                   q != p ? 1 : 0);
+        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    }
+    return TAD_OK;
+}
+
+int program_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
+                     hipStream_t s) {
+    return pl.dtype == TAD_F64 ? bwd_t<double>(pl, args, df, dx, ws, s) : bwd_t<float>(pl, args, df, dx, ws, s);
+}
+
+}  // namespace tad

@@ -231,8 +231,9 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     if (!expr || !args || !out) return TAD_EINVAL;
     *out = nullptr;
     if (dt != TAD_F32 && dt != TAD_F64) return TAD_EINVAL;
-    const int want = body_arg_count(expr->body);
+    const int want = expr->body == TAD_BODY_PROGRAM ? expr->n_operands : body_arg_count(expr->body);
     if (want < 0) return TAD_EUNSUPPORTED;
+    if (expr->body == TAD_BODY_PROGRAM && (want < 1 || want > TAD_MAX_ARGS)) return TAD_EINVAL;
     if (n_args != want) return TAD_EINVAL;
     if (expr->n_f < 1 || expr->n_sum < 0 || expr->n_f + expr->n_sum > TAD_MAX_EXT) return TAD_EINVAL;
     if (expr->n_sum > 0 &&
@@ -247,6 +248,10 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     } guard{pl};
 
     pl->expr = *expr;
+    if (expr->body == TAD_BODY_PROGRAM) {
+        const int rc = build_program_body(*expr, pl->prog);
+        if (rc) return rc;
+    }
     pl->args.assign(args, args + n_args);
     pl->dtype = dt;
     pl->flags = flags;
@@ -488,6 +493,16 @@ int tad_plan_count_all(const tad_plan *plan, int arg, int64_t *counts) {
         visit_beta(plan->n_ext, *ap, beta, [&](const int64_t *) { ++c; });
         counts[lin] = c;
     }
+    return TAD_OK;
+}
+
+int tad_plan_program_eval(const tad_plan *plan, int which, const double *values, double sum, double *out) {
+    if (!plan || !out || plan->expr.body != TAD_BODY_PROGRAM) return TAD_EINVAL;
+    const ProgramBody &pb = plan->prog;
+    if (which == -2) { *out = eval_host(pb.outer, nullptr, sum); return TAD_OK; }
+    if (which == -3) { *out = eval_host(pb.douter, nullptr, sum); return TAD_OK; }
+    if (!values || which < -1 || which >= pb.n_operands) return TAD_EINVAL;
+    *out = eval_host(which < 0 ? pb.inner : pb.dinner[which], values, 0.0);
     return TAD_OK;
 }
 

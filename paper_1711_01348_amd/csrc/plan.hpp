@@ -7,6 +7,7 @@
 #include "../../include/tad.h"
 #include "fm.hpp"
 #include "plan_dev.h"
+#include "program.hpp"
 #include "snf.hpp"
 
 namespace tad {
@@ -61,6 +62,7 @@ struct tad_plan {
     std::vector<tad::ArgPlan> ap;
     int fwd_family = TAD_FAMILY_GENERIC;
     tad::FastParams fast;
+    tad::ProgramBody prog;                     // TAD_BODY_PROGRAM only
     size_t ws_bytes = 0;
 };
 

@@ -62,6 +62,22 @@ struct ForwardPlan {
     int64_t off[kMaxArgs][kMaxExt];    // element offset of argument p = off[p] . [alpha k]
 };
 
+// Scalar function in three-address form, as the kernels interpret it: operation i computes temporary i from
+// earlier temporaries a[i], b[i] (or an operand / the sum / a constant).  Produced on the host from the user's
+// postfix program or from its symbolic derivative (program.hpp).
+constexpr int kMaxProgOps = 48;
+constexpr int kMaxProgConst = 8;
+enum ProgOp : uint8_t {
+    P_CONST, P_ARG, P_SUM, P_ADD, P_SUB, P_MUL, P_DIV, P_NEG, P_EXP, P_LOG, P_SIN, P_COS, P_TANH, P_SQRT, P_POWI
+};
+struct DevProg {
+    int32_t n;        // operations
+    int32_t result;   // temporary holding the result; -1: the function is identically zero
+    uint8_t op[kMaxProgOps], a[kMaxProgOps], b[kMaxProgOps];   // a: first input / operand index / constant index / exponent base
+    int8_t k[kMaxProgOps];                                     // exponent of P_POWI
+    double cst[kMaxProgConst];
+};
+
 // floor(a / b) and ceil(a / b) for b > 0, exact for negative a.  Divisors 1 and 2 (unit and stride-2
 // index maps) avoid the integer division, which costs tens of instructions on the GPU.
 TAD_HD int32_t floor_div_i(int32_t a, int32_t b) {

@@ -1,0 +1,240 @@
+// Scalar bodies given as programs: parsing of the postfix form, symbolic differentiation by reverse
+// accumulation on the expression graph (Sec. 2: the derivative of the output with respect to a node is the sum,
+// over the nodes consuming it, of their derivative times the local partial derivative; one backward sweep yields
+// the derivatives with respect to all inputs), and lowering to the three-address form the kernels interpret.
+// Host only.
+#pragma once
+#include <cmath>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/tad.h"
+#include "plan_dev.h"
+
+namespace tad {
+
+// expression graph in three-address form; node i only refers to nodes < i
+struct Node {
+    uint8_t op;     // ProgOp
+    int a = -1, b = -1;   // input nodes
+    int k = 0;      // operand index (P_ARG) or exponent (P_POWI)
+    double c = 0;   // P_CONST
+};
+
+struct Graph {
+    std::vector<Node> nodes;
+    int add(uint8_t op, int a = -1, int b = -1, int k = 0, double c = 0) {
+        nodes.push_back(Node{op, a, b, k, c});
+        return (int)nodes.size() - 1;
+    }
+    int constant(double c) { return add(P_CONST, -1, -1, 0, c); }
+};
+
+// Postfix program -> graph.  `outer`: TAD_OP_SUM allowed and TAD_OP_ARG not, and vice versa.
+// Returns the result node or a negative tad_status.
+inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, Graph &g) {
+    if (!ops || n < 1 || n > TAD_MAX_PROGRAM) return TAD_EINVAL;
+    std::vector<int> st;
+    for (int i = 0; i < n; ++i) {
+        const tad_op &o = ops[i];
+        auto pop = [&]() { int v = st.back(); st.pop_back(); return v; };
+        switch (o.op) {
+        case TAD_OP_CONST:
+            if (!std::isfinite(o.value)) return TAD_EINVAL;
+            st.push_back(g.constant(o.value));
+            break;
+        case TAD_OP_ARG:
+            if (outer || o.iarg < 0 || o.iarg >= n_operands) return TAD_EINVAL;
+            st.push_back(g.add(P_ARG, -1, -1, o.iarg));
+            break;
+        case TAD_OP_SUM:
+            if (!outer) return TAD_EINVAL;
+            st.push_back(g.add(P_SUM));
+            break;
+        case TAD_OP_ADD: case TAD_OP_SUB: case TAD_OP_MUL: case TAD_OP_DIV: {
+            if (st.size() < 2) return TAD_EINVAL;
+            const int b = pop(), a = pop();
+            const uint8_t op = o.op == TAD_OP_ADD ? P_ADD : o.op == TAD_OP_SUB ? P_SUB : o.op == TAD_OP_MUL ? P_MUL : P_DIV;
+            st.push_back(g.add(op, a, b));
+            break;
+        }
+        case TAD_OP_NEG: case TAD_OP_EXP: case TAD_OP_LOG: case TAD_OP_SIN: case TAD_OP_COS: case TAD_OP_TANH:
+        case TAD_OP_SQRT: {
+            if (st.empty()) return TAD_EINVAL;
+            const int a = pop();
+            const uint8_t op = o.op == TAD_OP_NEG ? P_NEG : o.op == TAD_OP_EXP ? P_EXP : o.op == TAD_OP_LOG ? P_LOG
+                             : o.op == TAD_OP_SIN ? P_SIN : o.op == TAD_OP_COS ? P_COS : o.op == TAD_OP_TANH ? P_TANH : P_SQRT;
+            st.push_back(g.add(op, a));
+            break;
+        }
+        case TAD_OP_POWI: {
+            if (st.empty() || o.iarg < 1 || o.iarg > 16) return TAD_EINVAL;
+            const int a = pop();
+            st.push_back(g.add(P_POWI, a, -1, o.iarg));
+            break;
+        }
+        default: return TAD_EINVAL;
+        }
+    }
+    if (st.size() != 1) return TAD_EINVAL;
+    return st[0];
+}
+
+// Reverse accumulation from `result` back to the inputs.  The derivative expressions are appended to the same
+// graph, so they share the forward nodes (Sec. 2: the derivative graph reuses the values of the function graph).
+// input_grad[p] receives the node of d result / d input p (inputs: operands 0..n_inputs-1 for an inner program,
+// the sum as input 0 for an outer program), or -1 where the derivative is identically zero.
+inline void reverse_accumulate(Graph &g, int result, int n_inputs, std::vector<int> &input_grad) {
+    const int n_fwd = (int)g.nodes.size();
+    std::vector<int> adj(n_fwd, -1);   // node holding d result / d node, -1 = zero
+    auto accumulate = [&](int node, int term) { adj[node] = adj[node] < 0 ? term : g.add(P_ADD, adj[node], term); };
+    input_grad.assign(n_inputs, -1);
+    adj[result] = g.constant(1.0);
+    for (int i = n_fwd - 1; i >= 0; --i) {
+        const int d = adj[i];
+        if (d < 0) continue;
+        const Node nd = g.nodes[i];   // copy: g.nodes grows below
+        switch (nd.op) {
+        case P_CONST: break;
+        case P_ARG: input_grad[nd.k] = input_grad[nd.k] < 0 ? d : g.add(P_ADD, input_grad[nd.k], d); break;
+        case P_SUM: input_grad[0] = input_grad[0] < 0 ? d : g.add(P_ADD, input_grad[0], d); break;
+        case P_ADD: accumulate(nd.a, d); accumulate(nd.b, d); break;
+        case P_SUB: accumulate(nd.a, d); accumulate(nd.b, g.add(P_NEG, d)); break;
+        case P_MUL: accumulate(nd.a, g.add(P_MUL, d, nd.b)); accumulate(nd.b, g.add(P_MUL, d, nd.a)); break;
+        case P_DIV: {   // a / b: d/da = 1 / b, d/db = -(a / b) / b
+            accumulate(nd.a, g.add(P_DIV, d, nd.b));
+            accumulate(nd.b, g.add(P_NEG, g.add(P_DIV, g.add(P_MUL, d, i), nd.b)));
+            break;
+        }
+        case P_NEG: accumulate(nd.a, g.add(P_NEG, d)); break;
+        case P_EXP: accumulate(nd.a, g.add(P_MUL, d, i)); break;
+        case P_LOG: accumulate(nd.a, g.add(P_DIV, d, nd.a)); break;
+        case P_SIN: accumulate(nd.a, g.add(P_MUL, d, g.add(P_COS, nd.a))); break;
+        case P_COS: accumulate(nd.a, g.add(P_NEG, g.add(P_MUL, d, g.add(P_SIN, nd.a)))); break;
+        case P_TANH: accumulate(nd.a, g.add(P_MUL, d, g.add(P_SUB, g.constant(1.0), g.add(P_MUL, i, i)))); break;
+        case P_SQRT: accumulate(nd.a, g.add(P_DIV, d, g.add(P_MUL, g.constant(2.0), i))); break;
+        case P_POWI: {
+            int pw = nd.k == 1 ? -1 : nd.k == 2 ? nd.a : g.add(P_POWI, nd.a, -1, nd.k - 1);
+            int t = nd.k == 1 ? d : g.add(P_MUL, d, g.add(P_MUL, g.constant((double)nd.k), pw));
+            accumulate(nd.a, t);
+            break;
+        }
+        }
+    }
+}
+
+// Lower the part of the graph that `result` depends on: products with the constant 1 and double negations are
+// dropped, equal constants share a slot, the nodes are renumbered densely.  False if it does not fit.
+inline bool lower(const Graph &g, int result, DevProg &out) {
+    out = DevProg{};
+    if (result < 0) { out.n = 0; out.result = -1; return true; }
+    const int N = (int)g.nodes.size();
+    // peephole: alias[i] = node that computes the same value
+    std::vector<int> alias(N);
+    auto is_one = [&](int i) { return g.nodes[i].op == P_CONST && g.nodes[i].c == 1.0; };
+    for (int i = 0; i < N; ++i) {
+        const Node &nd = g.nodes[i];
+        alias[i] = i;
+        const int a = nd.a >= 0 ? alias[nd.a] : -1, b = nd.b >= 0 ? alias[nd.b] : -1;
+        if (nd.op == P_MUL && is_one(a)) alias[i] = b;
+        else if (nd.op == P_MUL && is_one(b)) alias[i] = a;
+        else if (nd.op == P_DIV && is_one(b)) alias[i] = a;
+        else if (nd.op == P_NEG && g.nodes[a].op == P_NEG) alias[i] = alias[g.nodes[a].a];
+    }
+    result = alias[result];
+    std::vector<char> live(N, 0);
+    live[result] = 1;
+    for (int i = N - 1; i >= 0; --i) {
+        if (!live[i]) continue;
+        if (g.nodes[i].a >= 0) live[alias[g.nodes[i].a]] = 1;
+        if (g.nodes[i].b >= 0) live[alias[g.nodes[i].b]] = 1;
+    }
+    std::vector<int> slot(N, -1);
+    int n = 0, nc = 0;
+    for (int i = 0; i < N; ++i) {
+        if (!live[i]) continue;
+        if (n >= kMaxProgOps) return false;
+        const Node &nd = g.nodes[i];
+        out.op[n] = nd.op;
+        out.k[n] = 0;
+        out.a[n] = out.b[n] = 0;
+        if (nd.op == P_CONST) {
+            int c = 0;
+            while (c < nc && out.cst[c] != nd.c) ++c;
+            if (c == nc) {
+                if (nc >= kMaxProgConst) return false;
+                out.cst[nc++] = nd.c;
+            }
+            out.a[n] = (uint8_t)c;
+        } else if (nd.op == P_ARG) {
+            out.a[n] = (uint8_t)nd.k;
+        } else if (nd.op != P_SUM) {
+            out.a[n] = (uint8_t)slot[alias[nd.a]];
+            if (nd.b >= 0) out.b[n] = (uint8_t)slot[alias[nd.b]];
+            if (nd.op == P_POWI) out.k[n] = (int8_t)nd.k;
+        }
+        slot[i] = n++;
+    }
+    out.n = n;
+    out.result = slot[result];
+    return true;
+}
+
+// Evaluation of a lowered program (the host twin of the kernels' interpreter), fp64.
+inline double eval_host(const DevProg &P, const double *v, double s) {
+    if (P.result < 0) return 0.0;
+    double t[kMaxProgOps] = {0};
+    for (int i = 0; i < P.n; ++i) {
+        const double x = t[P.a[i]], y = t[P.b[i]];
+        switch (P.op[i]) {
+        case P_CONST: t[i] = P.cst[P.a[i]]; break;
+        case P_ARG: t[i] = v[P.a[i]]; break;
+        case P_SUM: t[i] = s; break;
+        case P_ADD: t[i] = x + y; break;
+        case P_SUB: t[i] = x - y; break;
+        case P_MUL: t[i] = x * y; break;
+        case P_DIV: t[i] = x / y; break;
+        case P_NEG: t[i] = -x; break;
+        case P_EXP: t[i] = std::exp(x); break;
+        case P_LOG: t[i] = std::log(x); break;
+        case P_SIN: t[i] = std::sin(x); break;
+        case P_COS: t[i] = std::cos(x); break;
+        case P_TANH: t[i] = std::tanh(x); break;
+        case P_SQRT: t[i] = std::sqrt(x); break;
+        case P_POWI: { double r = x; for (int e = 1; e < P.k[i]; ++e) r *= x; t[i] = r; break; }
+        default: t[i] = 0.0;
+        }
+    }
+    return t[P.result];
+}
+
+// Everything a program-body plan carries.
+struct ProgramBody {
+    int n_operands = 0;
+    DevProg inner, outer;            // values
+    DevProg dinner[TAD_MAX_ARGS];    // d inner / d operand p
+    DevProg douter;                  // d outer / d sum
+};
+
+// Parse, differentiate and lower both programs of an expression.  Returns a tad_status.
+inline int build_program_body(const tad_expr &e, ProgramBody &pb) {
+    if (e.n_operands < 1 || e.n_operands > TAD_MAX_ARGS) return TAD_EINVAL;
+    pb.n_operands = e.n_operands;
+    Graph gi;
+    const int ri = parse_postfix(e.inner, e.n_inner, false, e.n_operands, gi);
+    if (ri < 0) return ri;
+    if (!lower(gi, ri, pb.inner)) return TAD_EUNSUPPORTED;
+    std::vector<int> grads;
+    reverse_accumulate(gi, ri, e.n_operands, grads);
+    for (int p = 0; p < e.n_operands; ++p)
+        if (!lower(gi, grads[p], pb.dinner[p])) return TAD_EUNSUPPORTED;
+    Graph go;
+    const int ro = parse_postfix(e.outer, e.n_outer, true, 0, go);
+    if (ro < 0) return ro;
+    if (!lower(go, ro, pb.outer)) return TAD_EUNSUPPORTED;
+    reverse_accumulate(go, ro, 1, grads);
+    if (!lower(go, grads[0], pb.douter)) return TAD_EUNSUPPORTED;
+    return TAD_OK;
+}
+
+}  // namespace tad

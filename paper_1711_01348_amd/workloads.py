@@ -39,6 +39,11 @@ class ExprSpec:
     sums: List[Tuple[int, int]]     # inclusive (lo, hi) per summation index
     args: List[ArgSpec]
     dtype: str = "f64"              # "f64" or "f32"
+    # body "program": the scalar functions as postfix programs, f = outer(sum_k inner(operand values)).
+    # Entries: ("arg", p), ("const", c), ("sum",), ("add",), ("sub",), ("mul",), ("div",), ("neg",), ("exp",),
+    # ("log",), ("sin",), ("cos",), ("tanh",), ("sqrt",), ("powi", n)
+    inner: List[tuple] = field(default_factory=list)
+    outer: List[tuple] = field(default_factory=list)
 
     @property
     def n_ext(self) -> int:
@@ -145,6 +150,36 @@ def matmul_workload(n: int = 4096) -> Workload:
     df = _uniform(rng, -1, 1, (n, n))
     return Workload(f"matmul_{n}x{n}x{n}_f32", expr, {"x": _round(x, "f32"), "y": _round(y, "f32")},
                     _round(df, "f32"))
+
+
+# The built-in bodies written as programs (same index maps, scalar part given in postfix form)
+PROGRAM_OF_BODY = {
+    "sq": ([("arg", 0)], [("sum",), ("powi", 2)]),
+    "cube": ([("arg", 0)], [("sum",), ("powi", 3)]),
+    "sin": ([("arg", 0)], [("sum",), ("sin",)]),
+    "exp": ([("arg", 0)], [("sum",), ("exp",)]),
+    "mul": ([("arg", 0), ("arg", 1), ("mul",)], [("sum",)]),
+    "tanh_dot": ([("arg", 0), ("arg", 1), ("mul",)], [("sum",), ("tanh",)]),
+    # (a + b)^2 c + d^3, exp(-s)
+    "worked": ([("arg", 0), ("arg", 1), ("add",), ("powi", 2), ("arg", 2), ("mul",), ("arg", 3), ("powi", 3), ("add",)],
+               [("sum",), ("neg",), ("exp",)]),
+}
+
+
+def as_program(expr: ExprSpec) -> ExprSpec:
+    """The same expression with its built-in body replaced by the equivalent postfix programs."""
+    inner, outer = PROGRAM_OF_BODY[expr.body]
+    return ExprSpec("program", expr.f_shape, list(expr.sums), list(expr.args), expr.dtype, list(inner), list(outer))
+
+
+def softplus_ratio_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
+    """f_ij = log(1 + sum_k exp(x_ik) * sqrt(y_kj^2 + 1) / (2 + cos(z_{i+k})))  -- a body with no built-in twin."""
+    inner = [("arg", 0), ("exp",), ("arg", 1), ("powi", 2), ("const", 1.0), ("add",), ("sqrt",), ("mul",),
+             ("const", 2.0), ("arg", 2), ("cos",), ("add",), ("div",)]
+    outer = [("const", 1.0), ("sum",), ("add",), ("log",)]
+    return ExprSpec("program", (I, J), [(0, K - 1)],
+                    [ArgSpec("x", (I, K), [[1, 0, 0], [0, 0, 1]]), ArgSpec("y", (K, J), [[0, 0, 1], [0, 1, 0]]),
+                     ArgSpec("z", (I + K - 1,), [[1, 0, 1]])], dtype, inner, outer)
 
 
 # A tensor that occurs more than once in an expression (Sec. 5.3: its gradient is the sum over the

@@ -80,6 +80,35 @@ int main() {
     if (tad_smith_normal_form(Ab, 2, 2, S, U, V, &R) != TAD_EOVERFLOW) return 7;
     int64_t g, x, y;
     if (tad_extended_gcd(INT64_MIN, 3, &g, &x, &y) != TAD_EOVERFLOW) return 8;
+    // scalar bodies as programs: parsing, reverse accumulation, lowering, host evaluation
+    {
+        tad_expr e;
+        std::memset(&e, 0, sizeof e);
+        e.body = TAD_BODY_PROGRAM; e.n_f = 1; e.f_shape[0] = 5; e.n_operands = 2;
+        const tad_op inner[] = {{TAD_OP_ARG, 0, 0}, {TAD_OP_ARG, 1, 0}, {TAD_OP_ARG, 0, 0}, {TAD_OP_SUB, 0, 0}, {TAD_OP_DIV, 0, 0},
+                                {TAD_OP_ARG, 1, 0}, {TAD_OP_SQRT, 0, 0}, {TAD_OP_ARG, 0, 0}, {TAD_OP_POWI, 5, 0}, {TAD_OP_MUL, 0, 0},
+                                {TAD_OP_SUB, 0, 0}, {TAD_OP_TANH, 0, 0}, {TAD_OP_CONST, 0, 1.5}, {TAD_OP_MUL, 0, 0}};
+        const tad_op outer[] = {{TAD_OP_SUM, 0, 0}, {TAD_OP_COS, 0, 0}, {TAD_OP_NEG, 0, 0}, {TAD_OP_EXP, 0, 0}, {TAD_OP_LOG, 0, 0}};
+        e.n_inner = (int)(sizeof inner / sizeof inner[0]); e.n_outer = (int)(sizeof outer / sizeof outer[0]);
+        std::memcpy(e.inner, inner, sizeof inner);
+        std::memcpy(e.outer, outer, sizeof outer);
+        tad_arg a[2];
+        std::memset(a, 0, sizeof a);
+        for (int p = 0; p < 2; ++p) { a[p].rank = 1; a[p].shape[0] = 5; a[p].index[0][0] = 1; a[p].needs_grad = 1; }
+        tad_plan *pl = nullptr;
+        if (tad_plan_derive(&e, a, 2, TAD_F64, 0, &pl)) return 13;
+        const double v[2] = {0.4, 1.3};
+        double o = 0;
+        for (int which = -3; which < 2; ++which)
+            if (tad_plan_program_eval(pl, which, v, 0.7, &o) || o != o) return 14;
+        if (tad_plan_program_eval(pl, 2, v, 0.7, &o) != TAD_EINVAL) return 15;
+        tad_plan_free(pl);
+        // malformed programs are refused
+        e.n_inner = 2;   // ARG ARG: two values left
+        if (tad_plan_derive(&e, a, 2, TAD_F64, 0, &pl) != TAD_EINVAL) return 16;
+        e.n_inner = TAD_MAX_PROGRAM + 1;
+        if (tad_plan_derive(&e, a, 2, TAD_F64, 0, &pl) != TAD_EINVAL) return 17;
+    }
     // the loop-free floor division is exact on its whole domain (|a| < 2^23, 0 < s < 2^23)
     {
         const int32_t lim = (1 << 23) - 1;

@@ -301,3 +301,34 @@ def test_contraction_full_size_against_sampled_rows():
         e2 = wl.matmul_expr(4096, 4096, 1, "f32")
         dy_row = oracle.backward(e2, [x[:, r:r + 1], y[r:r + 1]], df, wanted=[False, True], nthreads=8)[1][0]
         assert check.within(grads[1][r], dy_row, "f32"), ("dy", r, check.errors(grads[1][r], dy_row))
+
+
+def _alias_program():
+    e = wl.matrix_square_expr(31, "f64")
+    return wl.as_program(e)
+
+
+PROGRAM_CASES = [
+    ("worked_f64", lambda: wl.Workload("p", wl.as_program(wl.config1().expr), wl.config1().inputs, wl.config1().df)),
+    ("worked_f32", lambda: wl.random_inputs(wl.as_program(wl.worked_expr(37, 52, 5, "f32")), 2, -0.9, 0.9)),
+    ("sq_f32", lambda: wl.random_inputs(wl.as_program(wl.broadcast_sq_expr(50, 72, "f32")), 3)),
+    ("diag_f32", lambda: wl.random_inputs(wl.as_program(wl.diagonal_sq_expr(77, "f32")), 4)),
+    ("exp_f32", lambda: wl.random_inputs(wl.as_program(wl.index_sum_exp_expr(40, 33, "f32")), 5)),
+    ("strided_f32", lambda: wl.random_inputs(wl.as_program(wl.strided_tanh_expr(2, 9, 11, 3, 3, 2, "f32")), 6)),
+    ("matmul_f64", lambda: wl.random_inputs(wl.as_program(wl.matmul_expr(12, 9, 14, "f64")), 7)),
+    ("softplus_f64", lambda: wl.random_inputs(wl.softplus_ratio_expr(9, 13, 6, "f64"), 8)),
+    ("softplus_f32", lambda: wl.random_inputs(wl.softplus_ratio_expr(33, 21, 17, "f32"), 9)),
+    ("alias_f64", lambda: wl.random_inputs(_alias_program(), 10)),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,make", PROGRAM_CASES, ids=[c[0] for c in PROGRAM_CASES])
+def test_program_bodies(name, make):
+    """Scalar part given as postfix programs: derivatives derived by reverse accumulation at plan time and
+    interpreted by the kernels, against the oracle's own interpreter with forward-mode derivatives."""
+    w = make()
+    f_ref, g_ref = oracle_all(w, 2)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "program"
+    assert_parity(w, f, grads, f_ref, g_ref, name)

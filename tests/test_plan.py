@@ -438,3 +438,65 @@ def test_contraction_family_is_selected_only_for_exact_matrix_products():
     e = wl.matmul_expr(8, 12, 16, "f32")
     e.args[0].shape = (9, 16)                                                           # longer than the range
     assert B.Plan(e).forward_family == "generic"
+
+
+# ---- scalar bodies given as programs: symbolic reverse accumulation on the host (Sec. 2) ---------
+
+def _scalar_expr(inner, outer, n_operands):
+    """f_0 = outer(inner(v_0..)) on one-element tensors: the gradient is outer' * d inner / d v_p."""
+    args = [wl.ArgSpec("v%d" % p, (1,), [[1]]) for p in range(n_operands)]
+    return wl.ExprSpec("program", (1,), [], args, "f64", list(inner), list(outer))
+
+
+PROGRAMS = [
+    (wl.PROGRAM_OF_BODY["worked"][0], wl.PROGRAM_OF_BODY["worked"][1], 4),
+    (wl.PROGRAM_OF_BODY["tanh_dot"][0], wl.PROGRAM_OF_BODY["tanh_dot"][1], 2),
+    (wl.softplus_ratio_expr(2, 2, 2, "f64").inner, wl.softplus_ratio_expr(2, 2, 2, "f64").outer, 3),
+    # x / (y - x) + sin(x y) - sqrt(y) * x^5, repeated operands and every derivative rule with two inputs
+    ([("arg", 0), ("arg", 1), ("arg", 0), ("sub",), ("div",), ("arg", 0), ("arg", 1), ("mul",), ("sin",), ("add",),
+      ("arg", 1), ("sqrt",), ("arg", 0), ("powi", 5), ("mul",), ("sub",)], [("sum",), ("cos",), ("neg",), ("exp",)], 2),
+    # an operand the function does not depend on, and a constant function of the sum
+    ([("arg", 0), ("const", 3.0), ("mul",)], [("const", 2.5)], 2),
+    ([("arg", 1), ("powi", 1)], [("sum",), ("powi", 1)], 2),
+]
+
+
+@pytest.mark.parametrize("inner,outer,nop", PROGRAMS, ids=["worked", "tanh_dot", "softplus", "mixed", "unused", "powi1"])
+def test_symbolic_derivatives_match_forward_mode_oracle(inner, outer, nop):
+    """The programs derived by reverse accumulation, evaluated on the host, against the oracle's dual numbers."""
+    e = _scalar_expr(inner, outer, nop)
+    plan = B.Plan(e)
+    rng = np.random.default_rng(8)
+    for _ in range(20):
+        v = rng.uniform(0.2, 1.4, size=nop)      # positive: sqrt and log stay real, y - x may be either sign
+        if abs(v[-1] - v[0]) < 0.05:
+            continue
+        args = [np.array([x]) for x in v]
+        total = plan.program_eval(-1, v)
+        f_ref = oracle.forward(e, args)[0]
+        assert abs(plan.program_eval(-2, None, total) - f_ref) <= 1e-13 * max(1.0, abs(f_ref))
+        g_ref = oracle.backward(e, args, np.array([1.0]))
+        for p in range(nop):
+            got = plan.program_eval(-3, None, total) * plan.program_eval(p, v)
+            assert abs(got - g_ref[p][0]) <= 1e-12 * max(1.0, abs(g_ref[p][0])), (p, got, g_ref[p][0])
+
+
+def test_program_rules():
+    ok_in, ok_out = [("arg", 0)], [("sum",)]
+    mk = lambda i, o, n=1: B.Plan(_scalar_expr(i, o, n))
+    mk(ok_in, ok_out)
+    assert _status(lambda: mk([("arg", 1)], ok_out)) == -1                      # operand index out of range
+    assert _status(lambda: mk([("sum",)], ok_out)) == -1                        # the sum is not an inner input
+    assert _status(lambda: mk(ok_in, [("arg", 0)])) == -1                       # operands are not outer inputs
+    assert _status(lambda: mk([("arg", 0), ("add",)], ok_out)) == -1            # stack underflow
+    assert _status(lambda: mk([("arg", 0), ("arg", 0)], ok_out)) == -1          # two values left
+    assert _status(lambda: mk([("arg", 0), ("powi", 0)], ok_out)) == -1
+    assert _status(lambda: mk([("const", float("inf"))], ok_out)) == -1
+    assert _status(lambda: mk(ok_in, [])) == -1
+    assert _status(lambda: mk([("arg", 0)] + [("neg",)] * 24, ok_out)) == -1    # longer than TAD_MAX_PROGRAM
+    # a derivative too long for the device form is refused, not truncated
+    long_inner = [("arg", 0)] + [("arg", 0), ("div",), ("sin",)] * 7
+    assert _status(lambda: mk(long_inner, ok_out)) in (0, -5)
+    plan = B.Plan(wl.as_program(wl.config1().expr))
+    assert plan.forward_family == "program" and plan.workspace_bytes >= 8 * 6 * 8
+    assert _status(lambda: B.Plan(wl.config1().expr).program_eval(-1, np.zeros(4))) == -1   # not a program plan
