@@ -36,11 +36,11 @@ MEASURED_TRAFFIC = {
             summary="profiles/worked_mfma_4096x4096x256_f32.md"),
     "matmul": dict(source="kernels_contract.hip", sha256="766cfe452e2e41d9", fetch_bytes=512.1 * 2**20, write_bytes=64.0 * 2**20,
             summary="profiles/contraction_4096x4096x4096_f32.md"),
-    "cfg2_1": dict(source="kernels_patterns.hip", sha256="4032b4c2ce4eaabb", fetch_bytes=64.1 * 2**20, write_bytes=0.0 * 2**20,
+    "cfg2_1": dict(source="kernels_patterns.hip", sha256="ed1f6d20a75b3e8c", fetch_bytes=64.3 * 2**20, write_bytes=0.1 * 2**20,
             summary="profiles/row_reduce_4096x4096_f32.md"),
-    "cfg2_2": dict(source="kernels_patterns.hip", sha256="4032b4c2ce4eaabb", fetch_bytes=1.1 * 2**20, write_bytes=256.3 * 2**20,
+    "cfg2_2": dict(source="kernels_patterns.hip", sha256="ed1f6d20a75b3e8c", fetch_bytes=1.1 * 2**20, write_bytes=256.3 * 2**20,
             summary="profiles/diagonal_8192_f32.md"),
-    "cfg2_3": dict(source="kernels_patterns.hip", sha256="4032b4c2ce4eaabb", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
+    "cfg2_3": dict(source="kernels_patterns.hip", sha256="ed1f6d20a75b3e8c", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
             summary="profiles/antidiagonal_4096x4096_f32.md"),
     "cfg5": dict(source="kernels_strided.hip", sha256="ed800e41532ec145", fetch_bytes=24.1 * 2**20, write_bytes=8.1 * 2**20,
             summary="profiles/strided_32x128x128_f32.md"),

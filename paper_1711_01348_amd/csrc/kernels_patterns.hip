@@ -47,14 +47,15 @@ __device__ __forceinline__ float wave_sum63(float v) {   // total valid in lane 
 // row reduce
 // ------------------------------------------------------------------------------------------------
 
-// block: 1024 columns x 16 rows, lane owns 4 consecutive columns
+// block: 1024 columns x RR_FTI rows, lane owns 4 consecutive columns
+constexpr int RR_FTI = 2;
 template <int BODY>
 __global__ __launch_bounds__(256) void k_rowreduce_forward(const float *__restrict__ x, float *__restrict__ f,
                                                            int I, int J) {
     const int j0 = blockIdx.x * 1024 + threadIdx.x * 4;
-    const int i0 = blockIdx.y * 16;
+    const int i0 = blockIdx.y * RR_FTI;
     if (j0 >= J) return;
-    const int rows = min(16, I - i0);
+    const int rows = min(RR_FTI, I - i0);
     float *fp = f + (size_t)i0 * J + j0;
     for (int r = 0; r < rows; ++r) {
         const float v = phi<BODY>(x[i0 + r]);
@@ -64,36 +65,39 @@ __global__ __launch_bounds__(256) void k_rowreduce_forward(const float *__restri
     }
 }
 
-// one wave per row of df; the j range of the plan is the whole row (collapsed kernel coordinate);
-// y = beta for this family (checked on the host), the feasibility rows zero the elements of a longer x
+// one block per row of df (four waves share the row; the j range of the plan is the whole row: collapsed kernel
+// coordinate); y = beta for this family (checked on the host), the feasibility rows zero the elements of a longer x.
+// Many small blocks: a 64 MiB read is too short for fewer, longer-running waves to reach the streaming rate.
 template <int BODY>
 __global__ __launch_bounds__(256) void k_rowreduce_backward(const FlatFeas feas, const float *__restrict__ x,
                                                             const float *__restrict__ df, float *__restrict__ dx,
                                                             int n_x, int J) {
-    const int lane = threadIdx.x & 63;
-    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (i >= n_x) return;
+    __shared__ float red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = blockIdx.x;
     const int32_t y[3] = {i, 0, 0};
-    if (!flat_feasible(feas, y)) {
-        if (lane == 63) dx[i] = 0.f;
+    if (!flat_feasible(feas, y)) {   // uniform over the block
+        if (tid == 0) dx[i] = 0.f;
         return;
     }
     const float *row = df + (size_t)i * J;
-    float4v acc[8];
+    float4v acc[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
-    int j = lane * 4;
-    for (; j + 7 * 256 < J; j += 8 * 256) {
-        float4v v[8];
+    for (int u = 0; u < 4; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
+    int j = tid * 4;
+    for (; j + 3 * 1024 < J; j += 4 * 1024) {
+        float4v v[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4v *>(row + j + u * 256);
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4v *>(row + j + u * 1024);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc[u] += v[u];
+        for (int u = 0; u < 4; ++u) acc[u] += v[u];
     }
-    for (; j < J; j += 256) acc[0] += *reinterpret_cast<const float4v *>(row + j);
-    const float4v t = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    for (; j < J; j += 1024) acc[0] += *reinterpret_cast<const float4v *>(row + j);
+    const float4v t = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     const float s = wave_sum63((t[0] + t[1]) + (t[2] + t[3]));
-    if (lane == 63) dx[i] = dphi<BODY>(x[i]) * s;
+    if (lane == 63) red[wave] = s;
+    __syncthreads();
+    if (tid == 0) dx[i] = dphi<BODY>(x[i]) * ((red[0] + red[1]) + (red[2] + red[3]));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -183,7 +187,8 @@ __global__ __launch_bounds__(256) void k_antidiag_backward(const FlatFeas feas, 
         hi = min(hi, zhi);
         const long long step = (long long)iz * J + jz;
         const float *p = df + ((long long)(base + iz * lo) * J + (jy * y[0] + jz * lo));
-        // four loads in flight per lane; measured faster than deeper unrolling or non-temporal loads
+        // four loads in flight per lane; measured faster than 8 or 16 (also with the surplus ones switched off), than
+        // non-temporal loads, and than 64-column blocks whose four waves split the rows
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
         int w = lo;
         for (; w + 3 <= hi; w += 4) {
@@ -200,20 +205,34 @@ __global__ __launch_bounds__(256) void k_antidiag_backward(const FlatFeas feas, 
     part[(size_t)t * n_x + m] = s;
 }
 
-// 64 outputs per block; the four waves split the tiles and are combined in fixed order
+// 64 outputs per block; sixteen waves split the tiles (a short chain of independent loads per thread) and are
+// combined in fixed order
+constexpr int AD_FIN_WAVES = 16;
 template <int BODY>
-__global__ __launch_bounds__(256) void k_antidiag_finish(const float *__restrict__ x, const float *__restrict__ part,
-                                                         int n_tiles, float *__restrict__ dx, int n_x) {
-    __shared__ double red[4][64];
+__global__ __launch_bounds__(64 * AD_FIN_WAVES) void k_antidiag_finish(const float *__restrict__ x,
+                                                                       const float *__restrict__ part, int n_tiles,
+                                                                       float *__restrict__ dx, int n_x) {
+    __shared__ double red[AD_FIN_WAVES][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = blockIdx.x * 64 + lane;
     double s = 0.0;
-    if (m < n_x)
-        for (int t = wave; t < n_tiles; t += 4) s += (double)part[(size_t)t * n_x + m];
+    if (m < n_x) {
+        int t = wave;
+        for (; t + 3 * AD_FIN_WAVES < n_tiles; t += 4 * AD_FIN_WAVES) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = part[(size_t)(t + u * AD_FIN_WAVES) * n_x + m];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s += (double)v[u];
+        }
+        for (; t < n_tiles; t += AD_FIN_WAVES) s += (double)part[(size_t)t * n_x + m];
+    }
     red[wave][lane] = s;
     __syncthreads();
     if (wave == 0 && m < n_x) {
-        s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+        s = 0.0;
+#pragma unroll
+        for (int w = 0; w < AD_FIN_WAVES; ++w) s += red[w][lane];
         dx[m] = (float)((double)dphi<BODY>(x[m]) * s);
     }
 }
@@ -238,7 +257,7 @@ int pattern_forward(const tad_plan &pl, const void *const *args, void *fo, hipSt
     switch (pl.fwd_family) {
     case TAD_FAMILY_ROW_REDUCE:
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_rowreduce_forward", (k_rowreduce_forward<B_>),
-                                                  dim3((J + 1023) / 1024, (I + 15) / 16), dim3(256), 0, s, x, f, I, J));
+                                                  dim3((J + 1023) / 1024, (I + RR_FTI - 1) / RR_FTI), dim3(256), 0, s, x, f, I, J));
         break;
     case TAD_FAMILY_DIAGONAL:
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_diagonal_forward", (k_diagonal_forward<B_>),
@@ -264,7 +283,7 @@ int pattern_backward(const tad_plan &pl, const void *const *args, const void *df
     switch (pl.ap[0].family) {
     case TAD_FAMILY_ROW_REDUCE:
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_rowreduce_backward", (k_rowreduce_backward<B_>),
-                                                  dim3((n_x + 3) / 4), dim3(256), 0, s, pl.fast.feas, x, df, dx,
+                                                  dim3(n_x), dim3(256), 0, s, pl.fast.feas, x, df, dx,
                                                   n_x, J));
         break;
     case TAD_FAMILY_DIAGONAL: {
@@ -282,7 +301,7 @@ int pattern_backward(const tad_plan &pl, const void *const *args, const void *df
                    J);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_antidiag_finish", (k_antidiag_finish<B_>),
-                                                  dim3((n_x + 63) / 64), dim3(256), 0, s, x, part, n_tiles, dx, n_x));
+                                                  dim3((n_x + 63) / 64), dim3(64 * AD_FIN_WAVES), 0, s, x, part, n_tiles, dx, n_x));
         break;
     }
     default: return TAD_EUNSUPPORTED;
