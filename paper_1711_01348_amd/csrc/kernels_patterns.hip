@@ -112,15 +112,16 @@ __global__ __launch_bounds__(256) void k_diagonal_forward(const float *__restric
 }
 
 // dense write of dx (rows x ld): zeros, except where the plan's masks pass (the diagonal inside the range)
-// block: 1024 columns x 16 rows
+// block: 1024 columns x DG_TI rows
+constexpr int DG_TI = 2;
 template <int BODY>
 __global__ __launch_bounds__(256) void k_diagonal_backward(const FlatFeas feas, const float *__restrict__ x,
                                                            const float *__restrict__ df, float *__restrict__ dx,
                                                            int rows, int ld) {
     const int c0 = blockIdx.x * 1024 + threadIdx.x * 4;
-    const int r0 = blockIdx.y * 16;
+    const int r0 = blockIdx.y * DG_TI;
     if (c0 >= ld) return;
-    const int nr = min(16, rows - r0);
+    const int nr = min(DG_TI, rows - r0);
     for (int r = 0; r < nr; ++r) {
         const int row = r0 + r;
         float4v o = {0.f, 0.f, 0.f, 0.f};
@@ -289,7 +290,7 @@ int pattern_backward(const tad_plan &pl, const void *const *args, const void *df
     case TAD_FAMILY_DIAGONAL: {
         const int rows = (int)pl.args[0].shape[0], ld = (int)pl.args[0].shape[1];
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_diagonal_backward", (k_diagonal_backward<B_>),
-                                                  dim3((ld + 1023) / 1024, (rows + 15) / 16), dim3(256), 0, s,
+                                                  dim3((ld + 1023) / 1024, (rows + DG_TI - 1) / DG_TI), dim3(256), 0, s,
                                                   pl.fast.feas, x, df, dx, rows, ld));
         break;
     }
