@@ -12,6 +12,7 @@
 #include "launch.h"
 #include "plan_dev.h"
 #include "profile.h"
+#include "worked_geom.h"
 
 namespace tad {
 
@@ -63,7 +64,7 @@ struct StridedDx {
 // Block roles in one launch.
 //  * blocks [blocks_dw, ...): one thread per gradient element (n, p, q) of x.  Masks and both ranges come from
 //    the plan (feasibility rows, rational range rows rounded exactly); the two ranges do not depend on each other.
-//  * blocks [0, blocks_dw) reduce dw over 1024 function elements each into part[block][taps].
+//  * blocks [0, blocks_dw) reduce dw over kStridedDwElems function elements each into part[block][taps].
 template <int TAPS>
 __global__ __launch_bounds__(256) void k_strided_backward(const StridedGeom g, const StridedDx D,
                                                           const float *__restrict__ x, const float *__restrict__ w,
@@ -110,8 +111,8 @@ __global__ __launch_bounds__(256) void k_strided_backward(const StridedGeom g, c
     float acc[TAPS];
 #pragma unroll
     for (int q = 0; q < TAPS; ++q) acc[q] = 0.f;
-    for (int e = 0; e < 4; ++e) {
-        const int lin = blk * 1024 + e * 256 + threadIdx.x;
+    for (int e = 0; e < kStridedDwElems / 256; ++e) {
+        const int lin = blk * kStridedDwElems + e * 256 + threadIdx.x;
         if (lin < nf) {
             const int j = lin % g.J, i = (lin / g.J) % g.I, n = lin / (g.J * g.I);
             const float fv = f[lin];
@@ -177,7 +178,7 @@ int strided_backward(const tad_plan &pl, const void *const *args, const void *f,
     const int nf = (int)pl.f_count;
     const int taps = (int)(pl.fast.U * pl.fast.V);
     const int blocks_dx = dx[0] ? (int)((pl.arg_count[0] + 255) / 256) : 0;
-    const int blocks_dw = dx[1] ? (nf + 1023) / 1024 : 0;
+    const int blocks_dw = dx[1] ? (nf + kStridedDwElems - 1) / kStridedDwElems : 0;
     if (blocks_dx + blocks_dw == 0) return TAD_OK;
     if (taps <= 4) launch_bwd<4>(pl, args, f, df, dx, ws, blocks_dx, blocks_dw, s);
     else if (taps <= 9) launch_bwd<9>(pl, args, f, df, dx, ws, blocks_dx, blocks_dw, s);

@@ -26,6 +26,8 @@ inline size_t mfma_workspace_bytes(int64_t I, int64_t J, int64_t K) {
            align256((size_t)kMfmaSplit * J * 4) + align256((size_t)I * 4);
 }
 
+constexpr int kStridedDwElems = 1024;  // function elements per dw block of the strided family (multiple of 256)
+
 constexpr int AD_BTI_ROWS = 64;   // rows per backward tile of the antidiagonal pattern
 inline size_t antidiag_workspace_bytes(int64_t I, int64_t n_x) {
     return align256((size_t)((I + AD_BTI_ROWS - 1) / AD_BTI_ROWS) * (size_t)n_x * 4);
