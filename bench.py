@@ -42,7 +42,7 @@ MEASURED_TRAFFIC = {
             summary="profiles/diagonal_8192_f32.md"),
     "cfg2_3": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
             summary="profiles/antidiagonal_4096x4096_f32.md"),
-    "cfg5": dict(source="kernels_strided.hip", sha256="ed800e41532ec145", fetch_bytes=24.1 * 2**20, write_bytes=8.1 * 2**20,
+    "cfg5": dict(source="kernels_strided.hip", sha256="09717396681524fd", fetch_bytes=24.1 * 2**20, write_bytes=8.1 * 2**20,
             summary="profiles/strided_32x128x128_f32.md"),
 }
 
