@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include "bodies.h"
+#include "gather_loop.h"
 #include "launch.h"
 #include "plan_dev.h"
 #include "profile.h"
@@ -50,66 +51,73 @@ __global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, co
     f[lin] = body_outer<BODY, T>((T)acc);
 }
 
+// Gradient element `lin` of operand p: masks, then the terms of the z loops shared by `parts` threads.
+// Returns false (and *sum = 0) when a mask zeroes the element.
 template <int BODY, typename T>
-__global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int p, const ArgPtrs A,
-                                                        const T *__restrict__ f, const T *__restrict__ df,
-                                                        T *__restrict__ dx, int n, int accumulate) {
+__device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const ArgPtrs &A, const T *__restrict__ f,
+                                               const T *__restrict__ df, int lin, int part, int parts, double *sum) {
     constexpr int NA = BodyTraits<BODY>::NA;
-    int lin = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lin >= n) return;
     int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
     {
         int t = lin;
         for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
     }
+    *sum = 0.0;
+    if (!gather_prepare(P, beta, y)) return false;
+    double acc = 0.0;
+    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t z0_hi) {
+        // innermost run: offsets advance by a constant per step
+        int64_t off[NA + 1];
+        for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
+        off[NA] = gather_offset(P, kSlotF, y, z);
+        const int32_t n = P.kappa == 0 ? 1 : z0_hi - z[0] + 1;
+        for (int32_t it = 0; it < n; ++it) {
+            T v[NA];
+            for (int q = 0; q < NA; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
+            const T fv = f[off[NA]], dfv = df[off[NA]];
+            acc += (double)(dfv * body_douter<BODY, T>(fv, v) * body_dinner<BODY, T>(p, v));
+            for (int q = 0; q < NA; ++q) off[q] += P.offZ[q][0];
+            off[NA] += P.offZ[kSlotF][0];
+        }
+    });
+    *sum = acc;
+    return true;
+}
+
+// one thread per gradient element
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int p, const ArgPtrs A,
+                                                        const T *__restrict__ f, const T *__restrict__ df,
+                                                        T *__restrict__ dx, int n, int accumulate) {
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= n) return;
     // accumulate != 0: a further occurrence of the same tensor adds to what the earlier launches stored
     // (same owner thread, launches ordered on the stream: still no atomics)
-    if (!gather_prepare(P, beta, y)) {
+    double acc;
+    if (!gather_element<BODY, T>(P, p, A, f, df, lin, 0, 1, &acc)) {
         if (!accumulate) dx[lin] = T(0);
         return;
     }
-    const T prev = accumulate ? dx[lin] : T(0);
+    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+}
 
-    double acc = 0.0;
-    auto term = [&](const int64_t *off) {
-        T v[NA];
-        for (int q = 0; q < NA; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
-        T fv = f[off[NA]], dfv = df[off[NA]];
-        acc += (double)(dfv * body_douter<BODY, T>(fv, v) * body_dinner<BODY, T>(p, v));
-    };
-    int32_t z[kMaxKernel] = {0, 0, 0, 0}, hi[kMaxKernel] = {0, 0, 0, 0};
-    int64_t off[NA + 1];
-    if (P.kappa == 0) {
-        for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
-        off[NA] = gather_offset(P, kSlotF, y, z);
-        term(off);
-        dx[lin] = prev + (T)acc;
+// one block per gradient element (few elements, long sums): the 256 threads share the z loops and their partial
+// sums are added in a fixed order
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_gather_coop(const GatherPlan P, int p, const ArgPtrs A,
+                                                             const T *__restrict__ f, const T *__restrict__ df,
+                                                             T *__restrict__ dx, int accumulate) {
+    __shared__ double red[4];
+    const int lin = blockIdx.x;
+    double acc;
+    const bool live = gather_element<BODY, T>(P, p, A, f, df, lin, threadIdx.x, 256, &acc);   // uniform over the block
+    const double total = block_sum_256(acc, red);
+    if (threadIdx.x != 0) return;
+    if (!live) {
+        if (!accumulate) dx[lin] = T(0);
         return;
     }
-    int lvl = P.kappa - 1;
-    gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
-    for (;;) {
-        if (z[lvl] > hi[lvl]) {
-            if (++lvl == P.kappa) break;
-            ++z[lvl];
-            continue;
-        }
-        if (lvl == 0) {
-            // innermost loop: offsets advance by a constant per step
-            for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
-            off[NA] = gather_offset(P, kSlotF, y, z);
-            for (int32_t z0 = z[0]; z0 <= hi[0]; ++z0) {
-                term(off);
-                for (int q = 0; q < NA; ++q) off[q] += P.offZ[q][0];
-                off[NA] += P.offZ[kSlotF][0];
-            }
-            z[0] = hi[0] + 1;
-        } else {
-            --lvl;
-            gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
-        }
-    }
-    dx[lin] = prev + (T)acc;
+    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
 }
 
 template <int BODY, typename T>
@@ -130,9 +138,14 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
         if (!dx[p] || pl.ap[q].family != TAD_FAMILY_GENERIC) continue;
         if (!pl.ap[q].derived) return TAD_EINVAL;
         int n = (int)pl.arg_count[p];
-        TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
-                   (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df), static_cast<T *>(dx[p]), n,
-                   q != p ? 1 : 0);
+        if (use_cooperative_gather(n, pl.terms_total))
+            TAD_LAUNCH("k_generic_gather_coop", (k_generic_gather_coop<BODY, T>), dim3(n), dim3(256), 0, s,
+                       pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                       static_cast<T *>(dx[p]), q != p ? 1 : 0);
+        else
+            TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s,
+                       pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                       static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

@@ -9,6 +9,7 @@
 //   gather    dx^p_beta = sum_{z in Sigma(beta)} g_alpha * (d inner / d x^p)(values at [alpha k]),  [alpha k] = I beta + K z
 #include <hip/hip_runtime.h>
 
+#include "gather_loop.h"
 #include "launch.h"
 #include "plan_dev.h"
 #include "profile.h"
@@ -116,51 +117,65 @@ __global__ __launch_bounds__(256) void k_program_forward(const ForwardPlan P, co
     out[lin] = df ? df[lin] * o : o;
 }
 
+// Gradient element `lin`: masks, then the terms of the z loops shared by `parts` threads.
+template <typename T>
+__device__ __forceinline__ bool program_element(const GatherPlan &P, const DevProg &dinner, int n_ops, const ArgPtrs &A,
+                                                const T *__restrict__ g, int lin, int part, int parts, double *sum) {
+    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
+    {
+        int t = lin;
+        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+    }
+    *sum = 0.0;
+    if (!gather_prepare(P, beta, y)) return false;
+    double acc = 0.0;
+    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t z0_hi) {
+        int64_t off[kMaxArgs + 1];
+        for (int q = 0; q < n_ops; ++q) off[q] = gather_offset(P, q, y, z);
+        off[kMaxArgs] = gather_offset(P, kSlotF, y, z);
+        const int32_t n = P.kappa == 0 ? 1 : z0_hi - z[0] + 1;
+        for (int32_t it = 0; it < n; ++it) {
+            T v[kMaxArgs];
+            for (int q = 0; q < n_ops; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
+            acc += (double)(g[off[kMaxArgs]] * prog_eval<T>(dinner, v, T(0)));
+            for (int q = 0; q < n_ops; ++q) off[q] += P.offZ[q][0];
+            off[kMaxArgs] += P.offZ[kSlotF][0];
+        }
+    });
+    *sum = acc;
+    return true;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, const DevProg dinner, int n_ops,
                                                         const ArgPtrs A, const T *__restrict__ g,
                                                         T *__restrict__ dx, int n, int accumulate) {
     const int lin = blockIdx.x * blockDim.x + threadIdx.x;
     if (lin >= n) return;
-    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
-    {
-        int t = lin;
-        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
-    }
-    if (!gather_prepare(P, beta, y)) {
+    double acc;
+    if (!program_element<T>(P, dinner, n_ops, A, g, lin, 0, 1, &acc)) {
         if (!accumulate) dx[lin] = T(0);
         return;
     }
-    const T prev = accumulate ? dx[lin] : T(0);
-    double acc = 0.0;
-    int32_t z[kMaxKernel] = {0, 0, 0, 0}, hi[kMaxKernel] = {0, 0, 0, 0};
-    auto term = [&]() {
-        T v[kMaxArgs];
-        for (int q = 0; q < n_ops; ++q) v[q] = static_cast<const T *>(A.p[q])[gather_offset(P, q, y, z)];
-        acc += (double)(g[gather_offset(P, kSlotF, y, z)] * prog_eval<T>(dinner, v, T(0)));
-    };
-    if (P.kappa == 0) {
-        term();
-        dx[lin] = prev + (T)acc;
+    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+}
+
+// one block per gradient element (few elements, long sums)
+template <typename T>
+__global__ __launch_bounds__(256) void k_program_gather_coop(const GatherPlan P, const DevProg dinner, int n_ops,
+                                                             const ArgPtrs A, const T *__restrict__ g,
+                                                             T *__restrict__ dx, int accumulate) {
+    __shared__ double red[4];
+    const int lin = blockIdx.x;
+    double acc;
+    const bool live = program_element<T>(P, dinner, n_ops, A, g, lin, threadIdx.x, 256, &acc);
+    const double total = block_sum_256(acc, red);
+    if (threadIdx.x != 0) return;
+    if (!live) {
+        if (!accumulate) dx[lin] = T(0);
         return;
     }
-    int lvl = P.kappa - 1;
-    gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
-    for (;;) {
-        if (z[lvl] > hi[lvl]) {
-            if (++lvl == P.kappa) break;
-            ++z[lvl];
-            continue;
-        }
-        if (lvl == 0) {
-            term();
-            ++z[0];
-        } else {
-            --lvl;
-            gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
-        }
-    }
-    dx[lin] = prev + (T)acc;
+    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
 }
 
 template <typename T>
@@ -191,9 +206,14 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
         if (!dx[p]) continue;
         if (!pl.ap[q].derived) return TAD_EINVAL;
         const int n = (int)pl.arg_count[p];
-        TAD_LAUNCH("k_program_gather", (k_program_gather<T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
-                   pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
-                   q != p ? 1 : 0);
+        if (use_cooperative_gather(n, pl.terms_total))
+            TAD_LAUNCH("k_program_gather_coop", (k_program_gather_coop<T>), dim3(n), dim3(256), 0, s, pl.ap[q].dev,
+                       pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]),
+                       q != p ? 1 : 0);
+        else
+            TAD_LAUNCH("k_program_gather", (k_program_gather<T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
+                       pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
+                       q != p ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

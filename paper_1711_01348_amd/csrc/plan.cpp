@@ -270,6 +270,8 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
         pl->hi[expr->n_f + s] = expr->sum_hi[s];
     }
     if (pl->f_count >= ((int64_t)1 << 31)) return TAD_EOVERFLOW;
+    pl->terms_total = (double)pl->f_count;
+    for (int s = 0; s < expr->n_sum; ++s) pl->terms_total *= (double)(expr->sum_hi[s] - expr->sum_lo[s] + 1);
 
     pl->arg_count.resize(n_args);
     pl->root.resize(n_args);

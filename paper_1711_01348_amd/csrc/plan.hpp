@@ -55,6 +55,7 @@ struct tad_plan {
     int n_ext;
     int64_t lo[TAD_MAX_EXT], hi[TAD_MAX_EXT];  // inclusive box of the extended index
     int64_t f_count;
+    double terms_total = 0;                    // extended indices in the box: f_count times the summation box
     std::vector<int64_t> arg_count;
     std::vector<int> root;                     // operand that holds the tensor of operand p (p itself unless alias)
     bool has_alias = false;

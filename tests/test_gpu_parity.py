@@ -112,6 +112,11 @@ ASSORTED = [
     lambda: wl.strided_tanh_expr(2, 5, 130, 7, 7, 8, "f32"),     # 49 taps, stride 8: general range divisors
     lambda: wl.strided_tanh_expr(2, 9, 200, 3, 3, 2, "f32"),
     lambda: wl.strided_tanh_expr(1, 6, 70, 4, 5, 1, "f32"),      # stride 1: up to 20 terms per gradient element
+    # few gradient elements with long sums: one block per element shares the z loops
+    lambda: _expr("exp", (40, 3001), [], [("x", (40,), [[1, 0]])], "f32"),                 # one range, split in pieces
+    lambda: _expr("exp", (7, 50, 61), [(0, 4)], [("x", (11,), [[1, 0, 0, 1]])], "f64"),     # three kernel coordinates
+    lambda: wl.as_program(_expr("exp", (40, 3001), [], [("x", (40,), [[1, 0]])], "f32")),
+    lambda: wl.as_program(wl.strided_tanh_expr(2, 40, 37, 3, 3, 2, "f64")),
     # a tensor that occurs twice: the gradient is the sum over both occurrences
     lambda: wl.matrix_square_expr(23, "f64"),
     lambda: wl.matrix_square_expr(67, "f32"),
