@@ -337,3 +337,30 @@ def test_program_bodies(name, make):
     plan, f, grads = run_gpu(w)
     assert plan.forward_family == "program"
     assert_parity(w, f, grads, f_ref, g_ref, name)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("K", [1, 2, 4, 6, 7, 8])
+def test_worked_family_every_short_sum_length(K):
+    """The fused kernels are instantiated per length of the summed index (1..8)."""
+    e = wl.worked_expr(261, 520, K, "f32")
+    w = wl.random_inputs(e, 30 + K, -0.8, 0.8)
+    w.inputs["c"] = np.abs(w.inputs["c"]) * np.float32(0.5)
+    f_ref, g_ref = oracle_all(w, 4)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "worked"
+    assert_parity(w, f, grads, f_ref, g_ref, "K=%d" % K)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("I,J,K", [(70, 132, 32), (129, 260, 96), (64, 64, 64)])
+def test_mfma_family_other_shapes(I, J, K):
+    """Long summed index (a multiple of 32): matrix-core kernels on ragged tiles and on exactly one tile."""
+    e = wl.worked_expr(I, J, K, "f32")
+    w = wl.random_inputs(e, 40 + K, -0.5, 0.5)
+    w.inputs["c"] = np.abs(w.inputs["c"]) * np.float32(4.0 / K)
+    w.inputs["d"] = w.inputs["d"] * np.float32(0.4)
+    f_ref, g_ref = oracle_all(w, 4)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "worked_mfma"
+    assert_parity(w, f, grads, f_ref, g_ref, "%dx%dx%d" % (I, J, K))
