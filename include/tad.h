@@ -38,6 +38,7 @@ extern "C" {
 #define TAD_MAX_RANK 4   /* rank of an argument tensor */
 #define TAD_MAX_ARGS 4
 #define TAD_MAX_KERNEL 4 /* dimension of the kernel of an index matrix */
+#define TAD_MAX_CONSTRAINTS 4 /* extra linear conditions on the extended index */
 
 typedef enum {
     TAD_OK = 0,
@@ -100,6 +101,14 @@ typedef struct {
     int32_t n_sum;                 /* number of summation indices; n_f + n_sum <= TAD_MAX_EXT */
     int64_t sum_lo[TAD_MAX_EXT];   /* inclusive constant limits of every summation index */
     int64_t sum_hi[TAD_MAX_EXT];
+    /*
+     * Extra linear conditions on the extended index [alpha k] (ranges of a sum that depend on other indices,
+     * Sec. 5.2; the form that derived expressions have, Sec. 5.3): the term at [alpha k] is part of the sum iff
+     *     sum_d constraint[j][d] * [alpha k]_d + constraint[j][n_f + n_sum] >= 0      for every j < n_constraints.
+     * An expression with such conditions runs on the plan-driven generic kernels.
+     */
+    int32_t n_constraints;         /* 0..TAD_MAX_CONSTRAINTS */
+    int64_t constraint[TAD_MAX_CONSTRAINTS][TAD_MAX_EXT + 1];
     /* TAD_BODY_PROGRAM only (ignored otherwise) */
     int32_t n_operands;            /* operands of the inner program, 1..TAD_MAX_ARGS */
     int32_t n_inner, n_outer;      /* program lengths, 1..TAD_MAX_PROGRAM */
@@ -167,8 +176,9 @@ typedef enum { TAD_ROWS_LOWER = 0, TAD_ROWS_UPPER = 1, TAD_ROWS_FEASIBILITY = 2 
  *   dt                  element type of every tensor
  *   flags               TAD_PLAN_* bits
  *   out                 receives a heap-allocated plan owned by the caller (tad_plan_free)
- * Errors: EINVAL (also: alias of a later operand or of another alias), ESHAPE (some in-range [alpha k]
- * maps outside an argument; alias with another rank or shape), EOVERFLOW, EUNSUPPORTED, ENOMEM.
+ * Errors: EINVAL (also: alias of a later operand or of another alias), ESHAPE (some [alpha k] that satisfies the
+ * ranges and the extra conditions may map outside an argument -- decided on the rational relaxation, so
+ * conservatively; alias with another rank or shape), EOVERFLOW, EUNSUPPORTED, ENOMEM.
  * An expression with aliases always runs on the plan-driven generic kernels.
  */
 int tad_plan_derive(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt,
@@ -193,9 +203,11 @@ int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out);
  *   feasibility:  coef_b . b(beta) <= 0                                  (level ignored)
  * with b(beta) = [lo - I beta ; I beta - hi] (2 (n_f+n_sum) entries, Sec. 5.1 with zero-based box lo..hi).
  * coef_b has 2*TAD_MAX_EXT entries (entry j and TAD_MAX_EXT + j for index j), coef_z TAD_MAX_KERNEL. Host memory.
+ * With extra conditions c_j . [alpha k] + c0_j >= 0 in the expression, b(beta) has one more entry per condition,
+ * -c0_j - c_j . (I beta), and coef_c (TAD_MAX_CONSTRAINTS entries, may be NULL) receives its coefficients.
  */
 int tad_plan_bound_row(const tad_plan *plan, int arg, int kind, int level, int row,
-                       int64_t *scale, int64_t *coef_b, int64_t *coef_z);
+                       int64_t *scale, int64_t *coef_b, int64_t *coef_z, int64_t *coef_c);
 
 /*
  * The extended indices the plan visits for gradient element beta (host): writes up to `cap`

@@ -32,6 +32,7 @@ class _Arg(ctypes.Structure):
 
 
 MAX_PROGRAM = 24
+MAX_COND = 4
 # postfix operation names of a program body -> the oracle's own codes (enum O_* in tad_oracle.c)
 _OPS = {"const": 0, "arg": 1, "sum": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "exp": 8, "log": 9,
         "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14}
@@ -51,7 +52,8 @@ class _Expr(ctypes.Structure):
                 ("n_args", ctypes.c_int),
                 ("args", _Arg * MAX_ARGS),
                 ("n_inner", ctypes.c_int), ("n_outer", ctypes.c_int),
-                ("inner", _Op * MAX_PROGRAM), ("outer", _Op * MAX_PROGRAM)]
+                ("inner", _Op * MAX_PROGRAM), ("outer", _Op * MAX_PROGRAM),
+                ("n_cond", ctypes.c_int), ("cond", (ctypes.c_int64 * (MAX_EXT + 1)) * MAX_COND)]
 
 
 def build(force: bool = False) -> str:
@@ -102,6 +104,14 @@ def _pack(expr) -> _Expr:
             assert len(a.A[r]) == n_ext
             for d in range(n_ext):
                 e.args[p].A[r][d] = int(a.A[r][d])
+    cond = list(getattr(expr, "constraints", []) or [])
+    assert len(cond) <= MAX_COND
+    e.n_cond = len(cond)
+    for j, (coef, const) in enumerate(cond):
+        assert len(coef) == n_ext
+        for d in range(n_ext):
+            e.cond[j][d] = int(coef[d])
+        e.cond[j][n_ext] = int(const)
     if expr.body == "program":
         for name, dst in (("inner", e.inner), ("outer", e.outer)):
             prog = list(getattr(expr, name))

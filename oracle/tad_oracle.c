@@ -42,6 +42,7 @@
 #define ORC_MAX_EXT 8   /* function indices + summation indices */
 #define ORC_MAX_RANK 4
 #define ORC_MAX_ARGS 4
+#define ORC_MAX_COND 4
 
 typedef struct {
     int rank;
@@ -68,6 +69,10 @@ typedef struct {
     orc_arg args[ORC_MAX_ARGS];
     int n_inner, n_outer;          /* body "program" only */
     orc_op inner[ORC_MAX_PROGRAM], outer[ORC_MAX_PROGRAM];
+    /* summation ranges that depend on other indices (Sec. 5.2): the term at the extended index x = [alpha k]
+       belongs to the sum iff  cond[j][0..n_ext) . x + cond[j][n_ext] >= 0  for every j < n_cond */
+    int n_cond;
+    int64_t cond[ORC_MAX_COND][ORC_MAX_EXT + 1];
 } orc_expr;
 
 enum { B_SQ, B_CUBE, B_SIN, B_EXP, B_MUL, B_WORKED, B_TANH_DOT, B_PROGRAM, B_UNKNOWN };
@@ -216,9 +221,21 @@ static int check_expr(const orc_expr *e, int *b) {
             if (e->outer[i].op == O_ARG) return -5;
     } else if (e->n_args != body_nargs(*b)) return -2;
     if (e->n_f < 0 || e->n_sum < 0 || e->n_f + e->n_sum > ORC_MAX_EXT) return -3;
+    if (e->n_cond < 0 || e->n_cond > ORC_MAX_COND) return -6;
     for (int p = 0; p < e->n_args; ++p)
         if (e->args[p].rank < 1 || e->args[p].rank > ORC_MAX_RANK) return -4;
     return 0;
+}
+
+/* does the extended index belong to the sum? */
+static int in_range(const orc_expr *e, const int64_t *ext) {
+    int n_ext = e->n_f + e->n_sum;
+    for (int j = 0; j < e->n_cond; ++j) {
+        int64_t v = e->cond[j][n_ext];
+        for (int d = 0; d < n_ext; ++d) v += e->cond[j][d] * ext[d];
+        if (v < 0) return 0;
+    }
+    return 1;
 }
 
 static int64_t f_count(const orc_expr *e) {
@@ -253,6 +270,7 @@ static int eval_s(const orc_expr *e, int b, const double *const *args, int64_t *
     if (!sums_empty(e)) {
         for (int q = 0; q < e->n_sum; ++q) ext[e->n_f + q] = e->sum_lo[q];
         do {
+            if (!in_range(e, ext)) continue;
             for (int p = 0; p < e->n_args; ++p) {
                 int64_t pos = arg_pos(&e->args[p], n_ext, ext);
                 if (pos < 0) return -10;
@@ -330,6 +348,7 @@ int orc_backward(const orc_expr *e, const double *const *args, const double *df,
                 if (sums_empty(e)) continue;
                 for (int q = 0; q < e->n_sum; ++q) ext[e->n_f + q] = e->sum_lo[q];
                 do {
+                    if (!in_range(e, ext)) continue;
                     for (int p = 0; p < e->n_args; ++p) {
                         pos[p] = arg_pos(&e->args[p], n_ext, ext);
                         v[p] = args[p][pos[p]];
@@ -386,7 +405,7 @@ int orc_gamma(const orc_expr *e, int arg, const int64_t *beta, int64_t *out, int
     int64_t ext[ORC_MAX_EXT], cnt = 0;
     if (box_first(e, ext)) {
         do {
-            int hit = 1;
+            int hit = in_range(e, ext);
             for (int r = 0; r < a->rank && hit; ++r) {
                 int64_t idx = 0;
                 for (int d = 0; d < n_ext; ++d) idx += a->A[r][d] * ext[d];
@@ -419,6 +438,7 @@ int orc_gamma_counts(const orc_expr *e, int arg, int64_t *counts) {
     int64_t ext[ORC_MAX_EXT];
     if (box_first(e, ext)) {
         do {
+            if (!in_range(e, ext)) continue;
             int64_t pos = arg_pos(a, n_ext, ext);
             if (pos < 0) return -10;
             counts[pos]++;

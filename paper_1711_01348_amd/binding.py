@@ -12,7 +12,7 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-MAX_EXT, MAX_RANK, MAX_ARGS, MAX_KERNEL = 6, 4, 4, 4
+MAX_EXT, MAX_RANK, MAX_ARGS, MAX_KERNEL, MAX_CONSTRAINTS = 6, 4, 4, 4, 4
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtad.so")
@@ -40,6 +40,7 @@ class TadExpr(ctypes.Structure):
     _fields_ = [("body", ctypes.c_int32), ("n_f", ctypes.c_int32),
                 ("f_shape", ctypes.c_int64 * MAX_EXT), ("n_sum", ctypes.c_int32),
                 ("sum_lo", ctypes.c_int64 * MAX_EXT), ("sum_hi", ctypes.c_int64 * MAX_EXT),
+                ("n_constraints", ctypes.c_int32), ("constraint", (ctypes.c_int64 * (MAX_EXT + 1)) * MAX_CONSTRAINTS),
                 ("n_operands", ctypes.c_int32), ("n_inner", ctypes.c_int32), ("n_outer", ctypes.c_int32),
                 ("inner", TadOp * MAX_PROGRAM), ("outer", TadOp * MAX_PROGRAM)]
 
@@ -84,7 +85,7 @@ def _load():
     lib.tad_plan_workspace_bytes.restype = ctypes.c_size_t
     lib.tad_plan_query.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(TadPlanInfo)]
     lib.tad_plan_bound_row.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                       i64p, i64p, i64p]
+                                       i64p, i64p, i64p, i64p]
     lib.tad_plan_enumerate.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, vp, ctypes.c_size_t,
                                        ctypes.POINTER(ctypes.c_size_t)]
     lib.tad_plan_count_all.argtypes = [vp, ctypes.c_int, vp]
@@ -119,6 +120,15 @@ def pack_expr(expr) -> TadExpr:
     e.n_sum = len(expr.sums)
     for s, (lo, hi) in enumerate(expr.sums):
         e.sum_lo[s], e.sum_hi[s] = int(lo), int(hi)
+    cons = list(getattr(expr, "constraints", []) or [])
+    if len(cons) > MAX_CONSTRAINTS:
+        raise TadError(-1, "tad_plan_derive")
+    e.n_constraints = len(cons)
+    n_ext = e.n_f + e.n_sum
+    for j, (coef, const) in enumerate(cons):     # sum_d coef[d] * [alpha k]_d + const >= 0
+        for d in range(n_ext):
+            e.constraint[j][d] = int(coef[d])
+        e.constraint[j][n_ext] = int(const)
     if expr.body == "program":
         # postfix programs as lists of tuples: ("arg", p), ("const", c), ("sum",), ("powi", n), ("add",), ...
         e.n_operands = len(expr.args)
@@ -202,13 +212,16 @@ class Plan:
             scale = ctypes.c_int64(0)
             cb = (ctypes.c_int64 * (2 * MAX_EXT))()
             cz = (ctypes.c_int64 * MAX_KERNEL)()
-            _check(lib.tad_plan_bound_row(self._h, arg, kind, level, r, ctypes.byref(scale), cb, cz),
+            cc = (ctypes.c_int64 * MAX_CONSTRAINTS)()
+            _check(lib.tad_plan_bound_row(self._h, arg, kind, level, r, ctypes.byref(scale), cb, cz, cc),
                    "tad_plan_bound_row")
             D = self.n_ext
             out.append(dict(scale=scale.value,
                             coef_b=np.array([cb[d] for d in range(D)] + [cb[MAX_EXT + d] for d in range(D)],
                                             dtype=np.int64),
-                            coef_z=np.array([cz[m] for m in range(q["kernel_dim"])], dtype=np.int64)))
+                            coef_z=np.array([cz[m] for m in range(q["kernel_dim"])], dtype=np.int64),
+                            coef_c=np.array([cc[j] for j in range(len(getattr(self.expr, "constraints", []) or []))],
+                                            dtype=np.int64)))
         return out
 
     def enumerate(self, arg: int, beta: Sequence[int], occ: int = 0) -> np.ndarray:

@@ -300,7 +300,7 @@ void select_families(tad_plan &plan) {
         plan.ws_bytes = align256((size_t)plan.f_count * (plan.dtype == TAD_F64 ? 8 : 4));
         return;
     }
-    if ((plan.flags & TAD_PLAN_GENERIC_ONLY) || plan.has_alias) return;
+    if ((plan.flags & TAD_PLAN_GENERIC_ONLY) || plan.has_alias || plan.expr.n_constraints > 0) return;
     if (match_worked(plan)) return;
     if (match_patterns(plan)) return;
     if (match_strided(plan)) return;

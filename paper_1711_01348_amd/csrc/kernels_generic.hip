@@ -34,13 +34,15 @@ __global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, co
     int32_t k[kMaxExt] = {0};
     double acc = 0.0;
     for (;;) {
-        T v[NA];
-        for (int p = 0; p < NA; ++p) {
-            int64_t o = base[p];
-            for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)k[s];
-            v[p] = static_cast<const T *>(A.p[p])[o];
+        if (forward_conditions(P, ext, k)) {   // a term outside the extra conditions is not part of the sum
+            T v[NA];
+            for (int p = 0; p < NA; ++p) {
+                int64_t o = base[p];
+                for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)k[s];
+                v[p] = static_cast<const T *>(A.p[p])[o];
+            }
+            acc += (double)body_inner<BODY, T>(v);
         }
-        acc += (double)body_inner<BODY, T>(v);
         int s = P.n_sum - 1;
         for (; s >= 0; --s) {
             if (++k[s] < P.sum_n[s]) break;

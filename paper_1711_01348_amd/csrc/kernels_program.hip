@@ -88,13 +88,15 @@ __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_op
     int32_t k[kMaxExt] = {0};
     double acc = 0.0;
     for (;;) {
-        T v[kMaxArgs];
-        for (int p = 0; p < n_ops; ++p) {
-            int64_t o = base[p];
-            for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)k[s];
-            v[p] = static_cast<const T *>(A.p[p])[o];
+        if (forward_conditions(P, ext, k)) {   // a term outside the extra conditions is not part of the sum
+            T v[kMaxArgs];
+            for (int p = 0; p < n_ops; ++p) {
+                int64_t o = base[p];
+                for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)k[s];
+                v[p] = static_cast<const T *>(A.p[p])[o];
+            }
+            acc += (double)prog_eval<T>(inner, v, T(0));
         }
-        acc += (double)prog_eval<T>(inner, v, T(0));
         int s = P.n_sum - 1;
         for (; s >= 0; --s) {
             if (++k[s] < P.sum_n[s]) break;

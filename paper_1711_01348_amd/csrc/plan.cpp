@@ -26,9 +26,10 @@ static int32_t fit32(int64_t v) {
 
 // Solve  A x = beta,  lo <= x <= hi  once for all beta with |beta_r| < extent[r]: Smith parts, constraints
 // Omega', Fourier-Motzkin rows and the folded device form (masks, transformed index, ranges).
+// Extra conditions  cons[e][0..D) . x + cons[e][D] >= 0  (n_cons of them) are further rows of the constraint system.
 static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, const int64_t *extent,
-                          ArgPlan &ap) {
-    const int D = A.cols, N = A.rows;
+                          ArgPlan &ap, int n_cons = 0, const int64_t (*cons_in)[TAD_MAX_EXT + 1] = nullptr) {
+    const int D = A.cols, N = A.rows, E = n_cons;
     bool nonzero = false;
     for (int64_t v : A.a) nonzero |= v != 0;
     if (!nonzero) return TAD_EINVAL;  // the Smith algorithm is defined for non-zero matrices only
@@ -53,14 +54,21 @@ static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, c
             else ap.K(i, j - R) = ap.smith.V(i, j);
         }
 
-    // Omega': [K ; -K] z >= b(beta),  b = [lo - I beta ; I beta - hi]  (Sec. 5.1, zero-based box)
-    IMat cons(2 * D, kappa), B = IMat::identity(2 * D);
+    // Omega': [K ; -K] z >= b(beta),  b = [lo - I beta ; I beta - hi]  (Sec. 5.1, zero-based box); an extra
+    // condition c . x + c0 >= 0 with x = I beta + K z adds the row (c K) z >= -c0 - c . (I beta)
+    IMat cons(2 * D + E, kappa), B = IMat::identity(2 * D + E);
     for (int d = 0; d < D; ++d)
         for (int m = 0; m < kappa; ++m) {
             cons(d, m) = ap.K(d, m);
             cons(D + d, m) = cneg(ap.K(d, m));
         }
-    ap.fm = fourier_motzkin(cons, 2 * D, B);
+    for (int e = 0; e < E; ++e)
+        for (int m = 0; m < kappa; ++m) {
+            int64_t v = 0;
+            for (int d = 0; d < D; ++d) v = cadd(v, cmul(cons_in[e][d], ap.K(d, m)));
+            cons(2 * D + e, m) = v;
+        }
+    ap.fm = fourier_motzkin(cons, 2 * D + E, B);
     if (!ap.fm.bounded) return TAD_EINVAL;  // a kernel direction that is bounded from one side only
 
     // ---- fold into the device form -------------------------------------------------------------
@@ -139,11 +147,17 @@ static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, c
         int64_t k0 = 0;
         for (int d = 0; d < D; ++d)
             k0 = cadd(k0, csub(cmul(cb[d], lo[d]), cmul(cb[D + d], hi[d])));
+        for (int e = 0; e < E; ++e) k0 = csub(k0, cmul(cb[2 * D + e], cons_in[e][D]));
         row.k0 = fit32(k0);
         int64_t mag = cabs(k0);
         for (int r = 0; r < R; ++r) {
             int64_t s = 0;
             for (int d = 0; d < D; ++d) s = cadd(s, cmul(csub(cb[D + d], cb[d]), ap.VR(d, r)));
+            for (int e = 0; e < E; ++e) {
+                int64_t cv = 0;
+                for (int d = 0; d < D; ++d) cv = cadd(cv, cmul(cons_in[e][d], ap.VR(d, r)));
+                s = csub(s, cmul(cb[2 * D + e], cv));
+            }
             row.ky[r] = fit32(s);
             mag = cadd(mag, cmul(cabs(s), ymax[r]));
         }
@@ -180,6 +194,45 @@ static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, c
     return TAD_OK;
 }
 
+// Range of the linear form a . x over the rational relaxation of { lo <= x <= hi, extra conditions } by
+// Fourier-Motzkin projection (variables x_0..x_{D-1} eliminated first, the form's value t last).  Returns false
+// if the set is empty (then every range is fine).  The integer range is inside [tmin, tmax].
+static bool linear_form_range(const int64_t *a, int D, const int64_t *lo, const int64_t *hi, int E,
+                              const int64_t (*cons_in)[TAD_MAX_EXT + 1], int64_t &tmin, int64_t &tmax) {
+    const int M = D + 1, rows = 2 * D + E + 2;
+    IMat A(rows, M), B(rows, 1);
+    for (int d = 0; d < D; ++d) {
+        A(d, d) = 1; B(d, 0) = lo[d];                 //  x_d >= lo_d
+        A(D + d, d) = -1; B(D + d, 0) = cneg(hi[d]);  // -x_d >= -hi_d
+    }
+    for (int e = 0; e < E; ++e) {
+        for (int d = 0; d < D; ++d) A(2 * D + e, d) = cons_in[e][d];
+        B(2 * D + e, 0) = cneg(cons_in[e][D]);
+    }
+    for (int d = 0; d < D; ++d) {
+        A(2 * D + E, d) = cneg(a[d]);                 //  t - a . x >= 0
+        A(2 * D + E + 1, d) = a[d];                   // -t + a . x >= 0
+    }
+    A(2 * D + E, D) = 1;
+    A(2 * D + E + 1, D) = -1;
+    const FMResult fm = fourier_motzkin(A, 1, B);
+    for (const auto &f : fm.feasibility)
+        if (f[0] > 0) return false;                   // F b <= 0 violated: no point at all
+    bool have_lo = false, have_hi = false;
+    for (const FMRow &r : fm.lower[D]) {
+        const int64_t v = ceil_div(r.coef_b[0], r.scale);
+        tmin = have_lo ? std::max(tmin, v) : v;
+        have_lo = true;
+    }
+    for (const FMRow &r : fm.upper[D]) {
+        const int64_t v = floor_div(r.coef_b[0], r.scale);
+        tmax = have_hi ? std::min(tmax, v) : v;
+        have_hi = true;
+    }
+    if (!have_lo || !have_hi) throw overflow_error();   // cannot happen for a bounded box
+    return tmin <= tmax;
+}
+
 // Index plan of one argument of an expression (one pass of the loop body of the derivation algorithm).
 static int derive_arg(const tad_plan &pl, int p, ArgPlan &ap) {
     const tad_arg &arg = pl.args[p];
@@ -187,7 +240,7 @@ static int derive_arg(const tad_plan &pl, int p, ArgPlan &ap) {
     IMat A(N, D);
     for (int r = 0; r < N; ++r)
         for (int d = 0; d < D; ++d) A(r, d) = arg.index[r][d];
-    int rc = derive_lattice(A, pl.lo, pl.hi, arg.shape, ap);
+    int rc = derive_lattice(A, pl.lo, pl.hi, arg.shape, ap, pl.expr.n_constraints, pl.expr.constraint);
     if (rc) return rc;
     GatherPlan &g = ap.dev;
     const int R = ap.smith.R, kappa = D - R;
@@ -236,6 +289,7 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     if (expr->body == TAD_BODY_PROGRAM && (want < 1 || want > TAD_MAX_ARGS)) return TAD_EINVAL;
     if (n_args != want) return TAD_EINVAL;
     if (expr->n_f < 1 || expr->n_sum < 0 || expr->n_f + expr->n_sum > TAD_MAX_EXT) return TAD_EINVAL;
+    if (expr->n_constraints < 0 || expr->n_constraints > TAD_MAX_CONSTRAINTS) return TAD_EINVAL;
     if (expr->n_sum > 0 &&
         (expr->body == TAD_BODY_SQ || expr->body == TAD_BODY_CUBE || expr->body == TAD_BODY_SIN))
         return TAD_EUNSUPPORTED;
@@ -293,12 +347,18 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
         for (int r = 0; r < a.rank; ++r) {
             if (a.shape[r] < 1) return TAD_ESHAPE;
             cnt = cmul(cnt, a.shape[r]);
-            // extremes of the linear map over the box: every reachable index must lie in the shape
+            // extremes of the linear map over the box (and the extra conditions): every reachable index must
+            // lie in the shape
             int64_t mn = 0, mx = 0;
-            for (int d = 0; d < D; ++d) {
-                int64_t u = cmul(a.index[r][d], pl->lo[d]), v = cmul(a.index[r][d], pl->hi[d]);
-                mn = cadd(mn, std::min(u, v));
-                mx = cadd(mx, std::max(u, v));
+            if (expr->n_constraints == 0) {
+                for (int d = 0; d < D; ++d) {
+                    int64_t u = cmul(a.index[r][d], pl->lo[d]), v = cmul(a.index[r][d], pl->hi[d]);
+                    mn = cadd(mn, std::min(u, v));
+                    mx = cadd(mx, std::max(u, v));
+                }
+            } else if (!linear_form_range(a.index[r], D, pl->lo, pl->hi, expr->n_constraints, expr->constraint, mn,
+                                          mx)) {
+                mn = mx = 0;   // no extended index satisfies the conditions: nothing is read
             }
             if (mn < 0 || mx >= a.shape[r]) return TAD_ESHAPE;
         }
@@ -323,6 +383,15 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
                 fw.off[p][d] = cadd(fw.off[p][d], cmul(stride, args[p].index[r][d]));
             stride = cmul(stride, args[p].shape[r]);
         }
+    }
+
+    fw.n_cons = expr->n_constraints;
+    for (int e = 0; e < expr->n_constraints; ++e) {
+        int64_t mag = cabs(expr->constraint[e][D]);
+        for (int d = 0; d <= D; ++d) fw.cons[e][d] = fit32(expr->constraint[e][d]);
+        for (int d = 0; d < D; ++d)
+            mag = cadd(mag, cmul(cabs(expr->constraint[e][d]), std::max(cabs(pl->lo[d]), cabs(pl->hi[d]))));
+        fit32(mag);   // the kernels evaluate the condition in int32
     }
 
     pl->ap.resize(n_args);
@@ -429,17 +498,20 @@ int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out) {
 }
 
 int tad_plan_bound_row(const tad_plan *plan, int arg, int kind, int level, int row, int64_t *scale,
-                       int64_t *coef_b, int64_t *coef_z) {
+                       int64_t *coef_b, int64_t *coef_z, int64_t *coef_c) {
     const ArgPlan *ap = get_arg(plan, arg, 0);
     if (!ap || !scale || !coef_b || !coef_z) return TAD_EINVAL;
     const int D = plan->n_ext, kappa = D - ap->smith.R;
     std::fill(coef_b, coef_b + 2 * TAD_MAX_EXT, 0);
     std::fill(coef_z, coef_z + TAD_MAX_KERNEL, 0);
+    if (coef_c) std::fill(coef_c, coef_c + TAD_MAX_CONSTRAINTS, 0);
     auto put_b = [&](const std::vector<int64_t> &cb) {
         for (int d = 0; d < D; ++d) {
             coef_b[d] = cb[d];
             coef_b[TAD_MAX_EXT + d] = cb[D + d];
         }
+        if (coef_c)
+            for (int e = 0; e < plan->expr.n_constraints; ++e) coef_c[e] = cb[2 * D + e];
     };
     if (kind == TAD_ROWS_FEASIBILITY) {
         if (row < 0 || row >= (int)ap->fm.feasibility.size()) return TAD_EINVAL;

@@ -27,6 +27,7 @@ constexpr int kMaxExt = 6;
 constexpr int kMaxRank = 4;
 constexpr int kMaxArgs = 4;
 constexpr int kMaxKernel = 4;
+constexpr int kMaxCons = 4;
 constexpr int kMaxRows = 32;   // lower + upper rows over all levels
 constexpr int kMaxFeas = 12;
 constexpr int kSlotF = kMaxArgs;        // offset slot of f / df
@@ -60,6 +61,8 @@ struct ForwardPlan {
     int32_t sum_lo[kMaxExt];
     int32_t sum_n[kMaxExt];            // number of values of each summation index
     int64_t off[kMaxArgs][kMaxExt];    // element offset of argument p = off[p] . [alpha k]
+    int32_t n_cons;                    // extra conditions: cons[j] . [alpha k] + cons[j][n_f + n_sum] >= 0
+    int32_t cons[kMaxCons][kMaxExt + 1];
 };
 
 // Scalar function in three-address form, as the kernels interpret it: operation i computes temporary i from
@@ -77,6 +80,18 @@ struct DevProg {
     int8_t k[kMaxProgOps];                                     // exponent of P_POWI
     double cst[kMaxProgConst];
 };
+
+// Extra conditions of the expression at the extended index (function part ext[0..n_f), summation counters k).
+TAD_HD bool forward_conditions(const ForwardPlan &P, const int32_t *ext, const int32_t *k) {
+    bool ok = true;
+    for (int e = 0; e < P.n_cons; ++e) {
+        int32_t v = P.cons[e][P.n_f + P.n_sum];
+        for (int d = 0; d < P.n_f; ++d) v += P.cons[e][d] * ext[d];
+        for (int s = 0; s < P.n_sum; ++s) v += P.cons[e][P.n_f + s] * (P.sum_lo[s] + k[s]);
+        ok = ok && v >= 0;
+    }
+    return ok;
+}
 
 // floor(a / b) and ceil(a / b) for b > 0, exact for negative a.  Divisors 1 and 2 (unit and stride-2
 // index maps) avoid the integer division, which costs tens of instructions on the GPU.

@@ -44,6 +44,9 @@ class ExprSpec:
     # ("log",), ("sin",), ("cos",), ("tanh",), ("sqrt",), ("powi", n)
     inner: List[tuple] = field(default_factory=list)
     outer: List[tuple] = field(default_factory=list)
+    # extra linear conditions on the extended index (summation ranges that depend on other indices, Sec. 5.2):
+    # a list of (coef, const); the term at [alpha k] is part of the sum iff sum_d coef[d] [alpha k]_d + const >= 0
+    constraints: List[tuple] = field(default_factory=list)
 
     @property
     def n_ext(self) -> int:
@@ -169,7 +172,8 @@ PROGRAM_OF_BODY = {
 def as_program(expr: ExprSpec) -> ExprSpec:
     """The same expression with its built-in body replaced by the equivalent postfix programs."""
     inner, outer = PROGRAM_OF_BODY[expr.body]
-    return ExprSpec("program", expr.f_shape, list(expr.sums), list(expr.args), expr.dtype, list(inner), list(outer))
+    return ExprSpec("program", expr.f_shape, list(expr.sums), list(expr.args), expr.dtype, list(inner), list(outer),
+                    list(expr.constraints))
 
 
 def softplus_ratio_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
@@ -180,6 +184,35 @@ def softplus_ratio_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
     return ExprSpec("program", (I, J), [(0, K - 1)],
                     [ArgSpec("x", (I, K), [[1, 0, 0], [0, 0, 1]]), ArgSpec("y", (K, J), [[0, 0, 1], [0, 1, 0]]),
                      ArgSpec("z", (I + K - 1,), [[1, 0, 1]])], dtype, inner, outer)
+
+
+# Summation ranges that depend on other indices (Sec. 5.2; the form derived expressions have, Sec. 5.3)
+
+def cumulative_sum_expr(N: int, dtype: str, body: str = "exp") -> ExprSpec:
+    """f_i = phi(sum_{k <= i} x_k), extended index (i, k) with the condition i - k >= 0."""
+    return ExprSpec(body, (N,), [(0, N - 1)], [ArgSpec("x", (N,), [[0, 1]])], dtype,
+                    constraints=[([1, -1], 0)])
+
+
+def causal_convolution_expr(N: int, K: int, dtype: str) -> ExprSpec:
+    """f_i = sum_{k <= min(i, K-1)} x_{i-k} w_k, extended index (i, k) with the condition i - k >= 0."""
+    return ExprSpec("mul", (N,), [(0, K - 1)],
+                    [ArgSpec("x", (N,), [[1, -1]]), ArgSpec("w", (K,), [[0, 1]])], dtype,
+                    constraints=[([1, -1], 0)])
+
+
+def triangular_matmul_expr(I: int, N: int, dtype: str) -> ExprSpec:
+    """f_ij = sum_{k <= j} x_ik y_kj (product with an upper triangular matrix), extended index (i, j, k)."""
+    return ExprSpec("mul", (I, N), [(0, N - 1)],
+                    [ArgSpec("x", (I, N), [[1, 0, 0], [0, 0, 1]]), ArgSpec("y", (N, N), [[0, 0, 1], [0, 1, 0]])], dtype,
+                    constraints=[([0, 1, -1], 0)])
+
+
+def band_expr(N: int, W: int, dtype: str) -> ExprSpec:
+    """f_i = tanh(sum_{i <= k <= i + W} x_k w_{k - i}): two conditions, a window that moves with i."""
+    return ExprSpec("tanh_dot", (N,), [(0, N - 1)],
+                    [ArgSpec("x", (N,), [[0, 1]]), ArgSpec("w", (W + 1,), [[-1, 1]])], dtype,
+                    constraints=[([-1, 1], 0), ([1, -1], W)])
 
 
 # A tensor that occurs more than once in an expression (Sec. 5.3: its gradient is the sum over the

@@ -33,7 +33,7 @@ static int derive_worked(int64_t I, int64_t J, int64_t K, tad_dtype dt, uint32_t
         int64_t scale, cb[2 * TAD_MAX_EXT], cz[TAD_MAX_KERNEL];
         for (int lvl = 0; lvl < info.kernel_dim; ++lvl)
             for (int r = 0; r < info.n_lower[lvl]; ++r)
-                if (tad_plan_bound_row(pl, p, TAD_ROWS_LOWER, lvl, r, &scale, cb, cz)) return -101;
+                if (tad_plan_bound_row(pl, p, TAD_ROWS_LOWER, lvl, r, &scale, cb, cz, nullptr)) return -101;
     }
     std::vector<int64_t> buf((size_t)J * K * 3 + 3);
     for (int64_t m = 0; m < I + K - 1; ++m) {

@@ -364,3 +364,29 @@ def test_mfma_family_other_shapes(I, J, K):
     plan, f, grads = run_gpu(w)
     assert plan.forward_family == "worked_mfma"
     assert_parity(w, f, grads, f_ref, g_ref, "%dx%dx%d" % (I, J, K))
+
+
+CONDITIONED = [
+    ("cumsum_f64", lambda: wl.cumulative_sum_expr(97, "f64")),
+    ("cumsum_f32", lambda: wl.cumulative_sum_expr(600, "f32")),
+    ("causal_conv_f32", lambda: wl.causal_convolution_expr(5000, 33, "f32")),
+    ("causal_conv_f64", lambda: wl.causal_convolution_expr(61, 7, "f64")),
+    ("triangular_f32", lambda: wl.triangular_matmul_expr(40, 70, "f32")),
+    ("triangular_f64", lambda: wl.triangular_matmul_expr(9, 12, "f64")),
+    ("window_f32", lambda: wl.band_expr(3000, 5, "f32")),
+    ("window_program_f64", lambda: wl.as_program(wl.band_expr(50, 4, "f64"))),
+    ("never_f64", lambda: wl.ExprSpec("exp", (4,), [(0, 3)], [wl.ArgSpec("x", (4,), [[0, 1]])], "f64",
+                                      constraints=[([-1, -1], -1)])),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,make", CONDITIONED, ids=[c[0] for c in CONDITIONED])
+def test_sums_with_index_dependent_ranges(name, make):
+    e = make()
+    lim = 0.02 if name == "cumsum_f32" else 0.9       # keep exp(sum of 600 values) in range
+    w = wl.random_inputs(e, 50, -lim, lim)
+    f_ref, g_ref = oracle_all(w, 2)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family in ("generic", "program")
+    assert_parity(w, f, grads, f_ref, g_ref, name)

@@ -377,3 +377,45 @@ def test_program_body_closed_form():
     df = np.linspace(0.5, 1.5, 6)
     assert np.allclose(oracle.forward(e, [x]), np.log1p(x * x), rtol=1e-14)
     assert np.allclose(oracle.backward(e, [x], df)[0], df * 2 * x / (1 + x * x), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- summation ranges that depend on other indices
+
+def test_cumulative_sum_closed_form():
+    """f_i = exp(sum_{k<=i} x_k): df/dx_k = sum_{i>=k} df_i f_i (reverse cumulative sum)."""
+    e = wl.cumulative_sum_expr(9, "f64")
+    rng = np.random.default_rng(1)
+    x, df = rng.uniform(-1, 1, 9), rng.uniform(-1, 1, 9)
+    f = oracle.forward(e, [x])
+    assert np.allclose(f, np.exp(np.cumsum(x)), rtol=1e-14)
+    assert np.allclose(oracle.backward(e, [x], df)[0], np.cumsum((df * f)[::-1])[::-1], rtol=1e-13)
+
+
+def test_causal_convolution_reduces_to_library_routine():
+    e = wl.causal_convolution_expr(11, 4, "f64")
+    rng = np.random.default_rng(2)
+    x, w, df = rng.uniform(-1, 1, 11), rng.uniform(-1, 1, 4), rng.uniform(-1, 1, 11)
+    assert np.allclose(oracle.forward(e, [x, w]), np.convolve(x, w)[:11], rtol=1e-13, atol=1e-14)
+    dx, dw = oracle.backward(e, [x, w], df)
+    assert np.allclose(dx, np.correlate(df, w, "full")[3:], rtol=1e-13, atol=1e-14)          # dx_m = sum_k df_{m+k} w_k
+    assert np.allclose(dw, [np.dot(df[k:], x[:11 - k]) for k in range(4)], rtol=1e-13, atol=1e-14)
+
+
+def test_triangular_matmul_closed_form():
+    e = wl.triangular_matmul_expr(4, 6, "f64")
+    rng = np.random.default_rng(3)
+    x, y, df = rng.uniform(-1, 1, (4, 6)), rng.uniform(-1, 1, (6, 6)), rng.uniform(-1, 1, (4, 6))
+    yu = np.triu(y)
+    assert np.allclose(oracle.forward(e, [x, y]), x @ yu, rtol=1e-13, atol=1e-14)
+    dx, dy = oracle.backward(e, [x, y], df)
+    assert np.allclose(dx, df @ yu.T, rtol=1e-13, atol=1e-14)
+    assert np.allclose(dy, np.triu(x.T @ df), rtol=1e-13, atol=1e-14)
+    assert np.all(np.tril(dy, -1) == 0)
+
+
+def test_moving_window_finite_differences():
+    e = wl.band_expr(8, 2, "f64")
+    w = wl.random_inputs(e, 6)
+    args = [np.asarray(a, dtype=np.float64) for a in w.arg_list()]
+    for p, g in enumerate(oracle.backward(e, args, w.df)):
+        assert np.allclose(g, _fd_grad(e, args, w.df, p), rtol=2e-7, atol=2e-8), p

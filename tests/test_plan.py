@@ -500,3 +500,50 @@ def test_program_rules():
     plan = B.Plan(wl.as_program(wl.config1().expr))
     assert plan.forward_family == "program" and plan.workspace_bytes >= 8 * 6 * 8
     assert _status(lambda: B.Plan(wl.config1().expr).program_eval(-1, np.zeros(4))) == -1   # not a program plan
+
+
+# ---- summation ranges that depend on other indices: extra linear conditions in the constraint system --------
+
+CONDITIONED = [
+    ("cumsum", lambda: wl.cumulative_sum_expr(7, "f64")),
+    ("causal_conv", lambda: wl.causal_convolution_expr(9, 4, "f64")),
+    ("triangular", lambda: wl.triangular_matmul_expr(3, 5, "f64")),
+    ("window", lambda: wl.band_expr(8, 2, "f64")),
+    ("window_program", lambda: wl.as_program(wl.band_expr(6, 3, "f64"))),
+    # a condition that couples three indices with coefficients other than one: 2 i + j - 3 k >= 1
+    ("skew", lambda: wl.ExprSpec("mul", (5, 6), [(0, 3)],
+                                 [wl.ArgSpec("x", (5, 4), [[1, 0, 0], [0, 0, 1]]), wl.ArgSpec("y", (12,), [[0, 1, 2]])],
+                                 "f64", constraints=[([2, 1, -3], -1)])),
+    # no extended index satisfies the condition at all
+    ("never", lambda: wl.ExprSpec("exp", (4,), [(0, 3)], [wl.ArgSpec("x", (4,), [[0, 1]])], "f64",
+                                  constraints=[([-1, -1], -1)])),
+]
+
+
+@pytest.mark.parametrize("name,make", CONDITIONED, ids=[c[0] for c in CONDITIONED])
+def test_conditioned_sums_match_brute_force(name, make):
+    e = make()
+    plan = B.Plan(e)
+    assert plan.forward_family in ("generic", "program")
+    for arg, a in enumerate(e.args):
+        assert (plan.count_all(arg) == oracle.gamma_counts(e, arg)).all(), (name, arg)
+        for beta in itertools.product(*[range(n) for n in a.shape]):
+            got, want = plan.enumerate(arg, beta), oracle.gamma(e, arg, beta)
+            assert got.shape == want.shape and (got == want).all(), (name, arg, beta)
+
+
+def test_condition_rules():
+    e = wl.cumulative_sum_expr(5, "f64")
+    rows = B.Plan(e).bound_rows(0, B.ROWS_LOWER) + B.Plan(e).bound_rows(0, B.ROWS_UPPER)
+    assert any(r["coef_c"].any() for r in rows)            # the condition shows up in the range rows
+    e.constraints = e.constraints * 5
+    assert _status(lambda: B.Plan(e)) == -1                 # more than TAD_MAX_CONSTRAINTS
+    # x_{i-k} without the condition k <= i leaves the tensor; with it, it does not
+    e = wl.causal_convolution_expr(6, 3, "f64")
+    B.Plan(e)
+    e.constraints = []
+    assert _status(lambda: B.Plan(e)) == -2
+    # conditions keep the specialised families off
+    e = wl.matmul_expr(8, 8, 8, "f32")
+    e.constraints = [([0, 1, -1], 0)]
+    assert B.Plan(e).forward_family == "generic"
