@@ -109,6 +109,29 @@ int main() {
         e.n_inner = TAD_MAX_PROGRAM + 1;
         if (tad_plan_derive(&e, a, 2, TAD_F64, 0, &pl) != TAD_EINVAL) return 17;
     }
+    // summation range that depends on another index: f_i = sum_{k <= i} x_{i-k} w_k
+    {
+        tad_expr e;
+        std::memset(&e, 0, sizeof e);
+        e.body = TAD_BODY_MUL; e.n_f = 1; e.f_shape[0] = 9; e.n_sum = 1; e.sum_lo[0] = 0; e.sum_hi[0] = 3;
+        e.n_constraints = 1; e.constraint[0][0] = 1; e.constraint[0][1] = -1; e.constraint[0][2] = 0;
+        tad_arg a[2];
+        std::memset(a, 0, sizeof a);
+        a[0].rank = 1; a[0].shape[0] = 9; a[0].index[0][0] = 1; a[0].index[0][1] = -1; a[0].needs_grad = 1;
+        a[1].rank = 1; a[1].shape[0] = 4; a[1].index[0][1] = 1; a[1].needs_grad = 1;
+        tad_plan *pl = nullptr;
+        if (tad_plan_derive(&e, a, 2, TAD_F64, 0, &pl)) return 18;
+        int64_t total = 0, buf[64 * 2];
+        for (int64_t m = 0; m < 9; ++m) {
+            size_t n = 0;
+            if (tad_plan_enumerate(pl, 0, 0, &m, buf, 64, &n)) return 19;
+            total += (int64_t)n;
+        }
+        if (total != 4 + 4 + 4 + 4 + 4 + 4 + 3 + 2 + 1) return 20;   // pairs (i, k) with k <= min(i, 3), grouped by i - k
+        tad_plan_free(pl);
+        e.n_constraints = 0;   // without the condition the index i - k can be negative
+        if (tad_plan_derive(&e, a, 2, TAD_F64, 0, &pl) != TAD_ESHAPE) return 21;
+    }
     // the loop-free floor division is exact on its whole domain (|a| < 2^23, 0 < s < 2^23)
     {
         const int32_t lim = (1 << 23) - 1;
