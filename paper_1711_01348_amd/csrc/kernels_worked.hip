@@ -27,12 +27,6 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
-
 // ---------------------------------------------------------------------------------------------
 // forward: block = 4 waves, 1024 columns x FWD_TI rows; lane owns 4 consecutive columns
 // ---------------------------------------------------------------------------------------------

@@ -18,7 +18,8 @@ inline size_t worked_workspace_bytes(int64_t I, int64_t J, int64_t K) {
     return align256(n_jt * I * (K + 2) * 4) + align256(n_it * (K + 1) * J * 4);
 }
 
-// long summed index (MFMA family): split of the collapsed contraction, tiles of the streaming sums pass
+// long summed index (MFMA family): number of chunks the collapsed contraction index is split in (4 leaves the
+// chip under-filled: 133 / 117 us per contraction instead of 98 / 94)
 constexpr int kMfmaSplit = 8;
 inline size_t mfma_workspace_bytes(int64_t I, int64_t J, int64_t K) {
     return align256((size_t)I * 16) + align256((size_t)J * 4) + align256((size_t)kMfmaSplit * I * K * 4) +
