@@ -159,11 +159,24 @@ def run_gpu(name, steps, warmup, rotate_bytes=0):
     ev[2].record()
     torch.cuda.synchronize()
     ms_step = (t1 - t0) * 1e3 / steps
+    extra = {}
+    if name == "cfg4":
+        # the same forward pass in the direct form on the vector ALUs, for comparison with the expanded form on MFMA
+        pd = B.Plan(w.expr, direct_form=True)
+        for _ in range(3):
+            pd.forward(args, out=f, ws=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            pd.forward(args, out=f, ws=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["ms_forward_direct_valu_form"] = e0.elapsed_time(e1) / 10
     return dict(name=name, workload=w.name, ms_per_step=ms_step, elements=elems, bytes=nbytes,
                 elements_per_s=elems / (ms_step * 1e-3), algorithmic_gbs=nbytes / (ms_step * 1e-3) / 1e9,
                 ms_forward=ev[0].elapsed_time(ev[1]), ms_backward=ev[1].elapsed_time(ev[2]),
                 dominant=dom, dominant_ms=dom_ms, dominant_launches=n.value, families=families,
-                dtype=w.expr.dtype, buffer_sets=len(sets), footprint_bytes_per_set=foot)
+                dtype=w.expr.dtype, buffer_sets=len(sets), footprint_bytes_per_set=foot, extra=extra)
 
 
 def measured_traffic(name):
@@ -267,6 +280,7 @@ def main():
                     tf = q["dominant"]["step_flops"] / (q["ms_per_step"] * 1e-3) / 1e12
                     e["step_TFLOPs"] = tf
                     e["step_frac_of_fp32_mfma_peak"] = tf / FP32_MFMA_TFLOPS
+                e.update(q["extra"])
                 e["roofline"] = roofline(q)
                 per[name] = e
             except Exception as ex:  # report, never hide

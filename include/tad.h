@@ -134,6 +134,9 @@ typedef struct {
 
 /* plan flags */
 #define TAD_PLAN_GENERIC_ONLY 1u /* never select a specialised kernel family; use the plan-driven generic kernels */
+#define TAD_PLAN_DIRECT_FORM 2u  /* worked expression with a long summed index: evaluate the forward pass in the direct
+                                    form sum_k (a_ik + b_jk)^2 on the vector ALUs instead of the expanded square on
+                                    the matrix cores (for comparing the two forms; the gradients are not affected) */
 
 typedef struct tad_plan tad_plan; /* opaque, immutable after derivation, may be shared between threads */
 

@@ -469,11 +469,72 @@ static int prep(const tad_plan &pl, const void *const *args, const MfmaWs &w, hi
     return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same forward pass in the direct form  s_ij = sum_k (a_ik + b_jk)^2  on the vector ALUs (one add and one fused
+// multiply-add per (i, j, k): 2 I J K lane operations): block tile 64 x 64, a
+// thread owns 4 x 4 results, k tile 32 through LDS.  Kept to measure the expanded form against (TAD_PLAN_DIRECT_FORM).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_worked_forward_direct(const float *__restrict__ a, const float *__restrict__ b,
+                                                               const float *__restrict__ rowv, float *__restrict__ f,
+                                                               int I, int J, int K) {
+    __shared__ __attribute__((aligned(16))) float As[32][68];   // [k][row]
+    __shared__ __attribute__((aligned(16))) float Bs[32][68];   // [k][row]: a thread reads four consecutive rows as one 16-byte load
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+    float acc[4][4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int y = 0; y < 4; ++y) acc[x][y] = 0.f;
+    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < K; k0 += 32) {
+        // 64 rows x 32 k of a and of b: 512 16-byte loads each, two per thread (K % 32 == 0)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int idx = tid + 256 * p, row = idx >> 3, kq = idx & 7;
+            const float4v va = (i0 + row < I) ? *reinterpret_cast<const float4v *>(a + (size_t)(i0 + row) * K + k0 + 4 * kq) : zero4;
+            const float4v vb = (j0 + row < J) ? *reinterpret_cast<const float4v *>(b + (size_t)(j0 + row) * K + k0 + 4 * kq) : zero4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { As[4 * kq + q][row] = va[q]; Bs[4 * kq + q][row] = vb[q]; }
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int k = 0; k < 32; ++k) {
+            const float4v av = *reinterpret_cast<const float4v *>(&As[k][4 * ty]);
+            const float4v bv = *reinterpret_cast<const float4v *>(&Bs[k][4 * tx]);
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) {
+                    const float t = av[x] + bv[y];
+                    acc[x][y] = fmaf(t, t, acc[x][y]);
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int i = i0 + 4 * ty + x, j = j0 + 4 * tx;
+        if (i < I && j < J) {   // J % 4 == 0
+            const float c = rowv[i * 4 + 1], D = rowv[i * 4 + 2];   // -log2e c_ii, -log2e D_i
+            float4v o;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) o[y] = __builtin_amdgcn_exp2f(fmaf(c, acc[x][y], D));
+            *reinterpret_cast<float4v *>(f + (size_t)i * J + j) = o;
+        }
+    }
+}
+
 int mfma_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s) {
     const int I = (int)pl.fast.I, J = (int)pl.fast.J, K = (int)pl.fast.K;
     MfmaWs w = carve_mfma(ws, I, J, K);
     int rc = prep(pl, args, w, s);
     if (rc) return rc;
+    if (pl.flags & TAD_PLAN_DIRECT_FORM) {
+        TAD_LAUNCH("k_worked_forward_direct", k_worked_forward_direct, dim3((J + 63) / 64, (I + 63) / 64), dim3(256), 0, s,
+                   (const float *)args[0], (const float *)args[1], w.rowv, (float *)f, I, J, K);
+        return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+    }
     TAD_LAUNCH("k_mfma_forward", k_mfma_forward, dim3((J + 127) / 128, (I + 127) / 128), dim3(256), 0, s,
                (const float *)args[0], (const float *)args[1], w.rowv, w.nb, (float *)f, I, J, K);
     return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;

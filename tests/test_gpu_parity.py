@@ -390,3 +390,31 @@ def test_sums_with_index_dependent_ranges(name, make):
     plan, f, grads = run_gpu(w)
     assert plan.forward_family in ("generic", "program")
     assert_parity(w, f, grads, f_ref, g_ref, name)
+
+
+@pytest.mark.gpu
+def test_direct_and_expanded_forward_forms_agree():
+    """Long summed index: the direct form on the vector ALUs and the expanded square on the matrix cores both
+    meet the fp32 tolerance against the oracle (small case element by element, full size on sampled rows)."""
+    import torch
+    from paper_1711_01348_amd import binding as B
+    w = wl.config4("small")
+    f_ref = oracle.forward(w.expr, w.arg_list())
+    args = [_to_dev(a) for a in w.arg_list()]
+    for direct in (False, True):
+        plan = B.Plan(w.expr, direct_form=direct)
+        assert plan.forward_family == "worked_mfma"
+        f = plan.forward(args).cpu().numpy()
+        assert check.within(f, f_ref, "f32"), (direct, check.errors(f, f_ref))
+    w = wl.config4()
+    args = [_to_dev(a) for a in w.arg_list()]
+    fd = B.Plan(w.expr, direct_form=True).forward(args).cpu().numpy()
+    fe = B.Plan(w.expr).forward(args).cpu().numpy()
+    a, b, c, d = [np.asarray(x, dtype=np.float64) for x in w.arg_list()]
+    for i in (0, 63, 64, 2047, 4095):
+        s = ((a[i][None, :] + b) ** 2).sum(axis=1) * c[i, i] + (d[i:i + 256] ** 3).sum()
+        e1 = wl.worked_expr(1, 4096, 256, "f32", d_len=256 + 0, c_shape=(1, 1))
+        row = oracle.forward(e1, [a[i:i + 1], b, c[i:i + 1, i:i + 1], d[i:i + 256]])[0]
+        assert np.allclose(row, np.exp(-s), rtol=1e-12)
+        assert check.within(fd[i], row, "f32"), ("direct", i, check.errors(fd[i], row))
+        assert check.within(fe[i], row, "f32"), ("expanded", i, check.errors(fe[i], row))
