@@ -30,15 +30,15 @@ ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 
 # 256 MiB copy in the same run (summaries under profiles/).  Each entry carries the SHA-256 prefix of the kernel source
 # the counters were taken with; once that file changes the entry is stale and the bench line reports traffic = null.
 MEASURED_TRAFFIC = {
-    "cfg3": dict(source="kernels_worked.hip", sha256="83d0ca98e95f19b9", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
+    "cfg3": dict(source="kernels_worked.hip", sha256="ba86f67ef4a9b366", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
             summary="profiles/worked_8192x8192x5_f32.md"),
-    "cfg4": dict(source="kernels_mfma.hip", sha256="38ef1379bb0b16f5", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
+    "cfg4": dict(source="kernels_mfma.hip", sha256="44904531fe551d9c", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
             summary="profiles/worked_mfma_4096x4096x256_f32.md"),
     "matmul": dict(source="kernels_contract.hip", sha256="766cfe452e2e41d9", fetch_bytes=512.1 * 2**20, write_bytes=64.0 * 2**20,
             summary="profiles/contraction_4096x4096x4096_f32.md"),
     "cfg2_1": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=64.3 * 2**20, write_bytes=0.1 * 2**20,
             summary="profiles/row_reduce_4096x4096_f32.md"),
-    "cfg2_2": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=1.1 * 2**20, write_bytes=256.3 * 2**20,
+    "cfg2_2": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=1.1 * 2**20, write_bytes=256.2 * 2**20,
             summary="profiles/diagonal_8192_f32.md"),
     "cfg2_3": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
             summary="profiles/antidiagonal_4096x4096_f32.md"),
