@@ -31,6 +31,22 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(B.lib, name), name
 
 
+def test_header_is_plain_c_and_struct_layouts_match(tmp_path):
+    """The boundary header compiles as C99 and as C++, and the ctypes mirrors have the C struct sizes."""
+    import ctypes
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", HEADER],
+                   check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", HEADER], check=True)
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "%s"\nint main(void){printf("%%zu %%zu %%zu %%zu\\n", sizeof(tad_expr), '
+                   'sizeof(tad_arg), sizeof(tad_plan_info), sizeof(tad_op));return 0;}\n' % HEADER)
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c99", str(src), "-o", str(exe)], check=True)
+    sizes = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert sizes == [ctypes.sizeof(B.TadExpr), ctypes.sizeof(B.TadArg), ctypes.sizeof(B.TadPlanInfo), ctypes.sizeof(B.TadOp)]
+
+
 # ---------------------------------------------------------------- Sec. 4.1: Euclid and Smith
 
 def test_extended_gcd_bezout_identity():
