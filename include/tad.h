@@ -38,7 +38,7 @@ extern "C" {
 #define TAD_MAX_RANK 4   /* rank of an argument tensor */
 #define TAD_MAX_ARGS 4
 #define TAD_MAX_KERNEL 4 /* dimension of the kernel of an index matrix */
-#define TAD_MAX_CONSTRAINTS 4 /* extra linear conditions on the extended index */
+#define TAD_MAX_CONSTRAINTS 8 /* extra linear conditions on the extended index */
 
 typedef enum {
     TAD_OK = 0,
@@ -91,7 +91,7 @@ typedef struct {
     double value;  /* CONST */
 } tad_op;
 
-#define TAD_MAX_PROGRAM 24 /* operations per program */
+#define TAD_MAX_PROGRAM 48 /* operations per program */
 
 /* Element-wise definition of f (Sec. 5.1): shape of f and the summation ranges Psi (Sec. 5.2). */
 typedef struct {
@@ -246,6 +246,34 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
 int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const void *f_dev,
                       const void *df_dev, void *const *dx_dev, void *ws_dev, size_t ws_bytes,
                       void *stream);
+
+/*
+ * The gradient of one occurrence of a tensor, written as an element-wise defined tensor of its own (Sec. 5.3:
+ * a derived expression has the form of the input expressions again, with summation ranges that depend on the
+ * other indices, so it can be evaluated, and differentiated once more, by the same machinery):
+ *
+ *     dx_beta = sum_z [conditions] df_{alpha(beta, z)} * (d inner / d x)(operand values at [alpha k](beta, z)),
+ *     [alpha k] = I beta + K z.
+ *
+ * Function indices of the new expression: beta (shape of the tensor); summation indices: the kernel coordinates
+ * z with constant limits (their extremes over the box); conditions: the box rows of the original extended index
+ * that those limits do not already imply, the original extra conditions, and the cokernel rows C beta = 0 as
+ * pairs of inequalities.  Operand 0 of the new expression is df (shape of f); the others are those operands of
+ * the original expression that the partial derivative depends on, in their original order (aliases stay
+ * aliases of one tensor).  The body is a program: inner = operand 0 times the symbolic partial derivative,
+ * outer = identity.
+ *   plan, arg, occ        as for tad_plan_query
+ *   expr_out              host, written
+ *   args_out              host, room for TAD_MAX_ARGS entries, written (needs_grad = 1 everywhere)
+ *   operand_out           host, room for TAD_MAX_ARGS ints (may be NULL): operand_out[q] = operand of the original
+ *                         expression that new operand q is, -1 for df
+ *   n_args_out            number of operands of the new expression
+ * Errors: EINVAL (as tad_plan_query); EUNSUPPORTED if the outer function is not the identity (the gradient then
+ * contains a second, nested sum), if a Smith divisor exceeds 1 (a divisibility mask is not a linear condition),
+ * or if the result exceeds the limits of an expression (indices, operands, conditions, program length).
+ */
+int tad_plan_derived_expr(const tad_plan *plan, int arg, int occ, tad_expr *expr_out, tad_arg *args_out,
+                          int *operand_out, int *n_args_out);
 
 /* Name of the device kernel family used for the forward pass (tad_family). */
 int tad_plan_forward_family(const tad_plan *plan);

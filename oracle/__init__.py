@@ -31,8 +31,8 @@ class _Arg(ctypes.Structure):
                 ("A", (ctypes.c_int64 * MAX_EXT) * MAX_RANK)]
 
 
-MAX_PROGRAM = 24
-MAX_COND = 4
+MAX_PROGRAM = 48
+MAX_COND = 8
 # postfix operation names of a program body -> the oracle's own codes (enum O_* in tad_oracle.c)
 _OPS = {"const": 0, "arg": 1, "sum": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "exp": 8, "log": 9,
         "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14}

@@ -42,7 +42,7 @@
 #define ORC_MAX_EXT 8   /* function indices + summation indices */
 #define ORC_MAX_RANK 4
 #define ORC_MAX_ARGS 4
-#define ORC_MAX_COND 4
+#define ORC_MAX_COND 8
 
 typedef struct {
     int rank;
@@ -50,7 +50,7 @@ typedef struct {
     int64_t A[ORC_MAX_RANK][ORC_MAX_EXT]; /* index matrix, columns: function then summation indices */
 } orc_arg;
 
-#define ORC_MAX_PROGRAM 24
+#define ORC_MAX_PROGRAM 48
 /* postfix operation codes of a program body */
 enum { O_CONST, O_ARG, O_SUM, O_ADD, O_SUB, O_MUL, O_DIV, O_NEG, O_EXP, O_LOG, O_SIN, O_COS, O_TANH, O_SQRT, O_POWI };
 typedef struct {

@@ -12,14 +12,14 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-MAX_EXT, MAX_RANK, MAX_ARGS, MAX_KERNEL, MAX_CONSTRAINTS = 6, 4, 4, 4, 4
+MAX_EXT, MAX_RANK, MAX_ARGS, MAX_KERNEL, MAX_CONSTRAINTS = 6, 4, 4, 4, 8
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtad.so")
 
 F32, F64 = 0, 1
 BODY = {"sq": 0, "cube": 1, "sin": 2, "exp": 3, "mul": 4, "worked": 5, "tanh_dot": 6, "program": 7}
-MAX_PROGRAM = 24
+MAX_PROGRAM = 48
 OPCODE = {"const": 0, "arg": 1, "sum": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "exp": 8, "log": 9,
           "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14}
 FAMILY = {0: "generic", 1: "row_reduce", 2: "diagonal", 3: "antidiagonal", 4: "worked",
@@ -30,7 +30,8 @@ ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
            "tad_plan_bound_row", "tad_plan_enumerate", "tad_plan_count_all", "tad_eval_forward",
-           "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval"]
+           "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval",
+           "tad_plan_derived_expr"]
 
 
 class TadOp(ctypes.Structure):
@@ -95,6 +96,9 @@ def _load():
                                       ctypes.c_size_t, vp]
     lib.tad_plan_forward_family.argtypes = [vp]
     lib.tad_plan_program_eval.argtypes = [vp, ctypes.c_int, vp, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
+    lib.tad_plan_derived_expr.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(TadExpr),
+                                          ctypes.POINTER(TadArg), ctypes.POINTER(ctypes.c_int),
+                                          ctypes.POINTER(ctypes.c_int)]
     lib.tad_strerror.argtypes = [ctypes.c_int]
     lib.tad_strerror.restype = ctypes.c_char_p
     return lib
@@ -245,6 +249,40 @@ class Plan:
         _check(lib.tad_plan_program_eval(self._h, which, None if v is None else v.ctypes.data, float(total),
                                          ctypes.byref(out)), "tad_plan_program_eval")
         return out.value
+
+    def derived_expr(self, arg: int, occ: int = 0):
+        """The gradient of occurrence `occ` of operand `arg` as an expression of its own: (expression, operands)
+        with operands[q] = index of the original operand that new operand q is, -1 for df (always operand 0).
+        The expression can be planned and evaluated like any other."""
+        from .workloads import ArgSpec, ExprSpec
+        e, a = TadExpr(), (TadArg * MAX_ARGS)()
+        src, n = (ctypes.c_int * MAX_ARGS)(), ctypes.c_int(0)
+        _check(lib.tad_plan_derived_expr(self._h, arg, occ, ctypes.byref(e), a, src, ctypes.byref(n)),
+               "tad_plan_derived_expr")
+        n_ext = e.n_f + e.n_sum
+        names = {v: k for k, v in OPCODE.items()}
+
+        def program(ops, count):
+            out = []
+            for i in range(count):
+                name = names[ops[i].op]
+                out.append((name, ops[i].iarg) if name in ("arg", "powi") else
+                           (name, ops[i].value) if name == "const" else (name,))
+            return out
+
+        operands = [src[q] for q in range(n.value)]
+        args = []
+        for q in range(n.value):
+            name = "df" if operands[q] < 0 else self.expr.args[operands[q]].name + ("" if a[q].alias == 0 else f"_{q}")
+            args.append(ArgSpec(name, tuple(a[q].shape[r] for r in range(a[q].rank)),
+                                [[a[q].index[r][d] for d in range(n_ext)] for r in range(a[q].rank)],
+                                None if a[q].alias == 0 else a[q].alias - 1))
+        spec = ExprSpec("program", tuple(e.f_shape[d] for d in range(e.n_f)),
+                        [(e.sum_lo[s], e.sum_hi[s]) for s in range(e.n_sum)], args, self.expr.dtype,
+                        inner=program(e.inner, e.n_inner), outer=program(e.outer, e.n_outer),
+                        constraints=[([e.constraint[j][d] for d in range(n_ext)], e.constraint[j][n_ext])
+                                     for j in range(e.n_constraints)])
+        return spec, operands
 
     def count_all(self, arg: int) -> np.ndarray:
         counts = np.empty(tuple(self.expr.args[arg].shape), dtype=np.int64)

@@ -219,9 +219,18 @@ static bool match_strided(tad_plan &pl) {
 
 // f_ij = sum_k P(i, k) Q(k, j): both operands are matrices indexed by one function index and the summation index,
 // their axes in either order, shapes exactly the index ranges.  Extended index (i, j, k).
+// the body is the product of its two operands, summed: built in, or a program that says the same
+static bool is_product_body(const tad_plan &pl) {
+    if (pl.expr.body == TAD_BODY_MUL) return true;
+    if (pl.expr.body != TAD_BODY_PROGRAM || pl.prog.n_operands != 2) return false;
+    const DevProg &in = pl.prog.inner, &out = pl.prog.outer;
+    return out.n == 1 && out.op[0] == P_SUM && in.n == 3 && in.result == 2 && in.op[0] == P_ARG &&
+           in.op[1] == P_ARG && in.a[0] + in.a[1] == 1 && in.op[2] == P_MUL && in.a[2] + in.b[2] == 1;
+}
+
 static bool match_contraction(tad_plan &pl) {
     const tad_expr &e = pl.expr;
-    if (e.body != TAD_BODY_MUL || pl.dtype != TAD_F32 || e.n_f != 2 || e.n_sum != 1 || e.sum_lo[0] != 0) return false;
+    if (!is_product_body(pl) || pl.dtype != TAD_F32 || e.n_f != 2 || e.n_sum != 1 || e.sum_lo[0] != 0) return false;
     if (!all_derived(pl)) return false;
     const int64_t ext[3] = {e.f_shape[0], e.f_shape[1], e.sum_hi[0] + 1};
     for (int d = 0; d < 3; ++d)
@@ -298,6 +307,11 @@ void select_families(tad_plan &plan) {
         plan.fwd_family = TAD_FAMILY_PROGRAM;
         for (auto &ap : plan.ap) ap.family = TAD_FAMILY_PROGRAM;
         plan.ws_bytes = align256((size_t)plan.f_count * (plan.dtype == TAD_F64 ? 8 : 4));
+        // a plain product of two matrices (the form the derived expressions of a matrix product have) still
+        // belongs on the matrix cores
+        if (!(plan.flags & TAD_PLAN_GENERIC_ONLY) && !plan.has_alias && plan.expr.n_constraints == 0 &&
+            match_contraction(plan))
+            plan.ws_bytes = 0;
         return;
     }
     if ((plan.flags & TAD_PLAN_GENERIC_ONLY) || plan.has_alias || plan.expr.n_constraints > 0) return;

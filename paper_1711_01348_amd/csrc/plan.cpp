@@ -138,6 +138,7 @@ static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, c
             zmax = std::max(zmax, s);
         }
         fit32(zmax);
+        ap.Vinv = Inv;
     }
 
     auto fold = [&](int64_t scale, const std::vector<int64_t> &cb, const std::vector<int64_t> *cz) {
@@ -406,6 +407,179 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     return TAD_OK;
 }
 
+// Inner function of an expression whose outer function is the identity, as a postfix program; false otherwise.
+static bool identity_outer_inner(const tad_plan &pl, std::vector<tad_op> &inner, int &n_operands) {
+    auto op = [](int code, int iarg = 0) { tad_op o{}; o.op = code; o.iarg = iarg; return o; };
+    switch (pl.expr.body) {
+    case TAD_BODY_SQ: inner = {op(TAD_OP_ARG, 0), op(TAD_OP_POWI, 2)}; n_operands = 1; return true;
+    case TAD_BODY_CUBE: inner = {op(TAD_OP_ARG, 0), op(TAD_OP_POWI, 3)}; n_operands = 1; return true;
+    case TAD_BODY_SIN: inner = {op(TAD_OP_ARG, 0), op(TAD_OP_SIN)}; n_operands = 1; return true;
+    case TAD_BODY_MUL: inner = {op(TAD_OP_ARG, 0), op(TAD_OP_ARG, 1), op(TAD_OP_MUL)}; n_operands = 2; return true;
+    case TAD_BODY_PROGRAM:
+        if (pl.prog.outer.n != 1 || pl.prog.outer.op[0] != P_SUM) return false;   // lowered form of "the sum itself"
+        inner.assign(pl.expr.inner, pl.expr.inner + pl.expr.n_inner);
+        n_operands = pl.expr.n_operands;
+        return true;
+    default: return false;
+    }
+}
+
+// The gradient of the occurrence in operand slot `slot` as an expression of its own (Sec. 5.3).  With unit Smith
+// divisors the solutions of A x = beta are x = M [beta z], M = [V_R U_R | K], for every beta with C beta = 0.
+static int derived_expr(const tad_plan &pl, int slot, const ArgPlan &ap, tad_expr *eo, tad_arg *ao, int *operand_out,
+                        int *n_out) {
+    const int D = pl.n_ext, N = pl.args[slot].rank, R = ap.smith.R, kappa = D - R, E = pl.expr.n_constraints;
+    const int nf = pl.expr.n_f, D2 = N + kappa;
+    for (int r = 0; r < R; ++r)
+        if (ap.diag[r] != 1) return TAD_EUNSUPPORTED;
+    if (D2 > TAD_MAX_EXT || nf > TAD_MAX_RANK) return TAD_EUNSUPPORTED;
+
+    // ---- scalar part: operand 0 (df) times d inner / d operand `slot` ---------------------------------------
+    std::vector<tad_op> inner;
+    int n_ops = 0;
+    if (!identity_outer_inner(pl, inner, n_ops)) return TAD_EUNSUPPORTED;
+    Graph g;
+    const int res = parse_postfix(inner.data(), (int)inner.size(), false, n_ops, g);
+    if (res < 0) return res;
+    std::vector<int> grads;
+    reverse_accumulate(g, res, n_ops, grads);
+    std::vector<tad_op> dprog;
+    bool is_one = false;
+    if (grads[slot] < 0) {
+        tad_op zero{};
+        zero.op = TAD_OP_CONST;
+        dprog.push_back(zero);
+    } else {
+        const std::vector<int> alias = simplify(g);
+        const Node &top = g.nodes[alias[grads[slot]]];
+        is_one = top.op == P_CONST && top.c == 1.0;
+        if (!is_one && !emit_postfix(g, alias, grads[slot], dprog, TAD_MAX_PROGRAM - 2)) return TAD_EUNSUPPORTED;
+    }
+    // operands the derivative depends on, in their original order; new index = 1 + position
+    int new_index[TAD_MAX_ARGS], kept[TAD_MAX_ARGS], n_kept = 0;
+    for (int q = 0; q < n_ops; ++q) {
+        new_index[q] = -1;
+        for (const tad_op &o : dprog)
+            if (o.op == TAD_OP_ARG && o.iarg == q) new_index[q] = 0;
+        if (new_index[q] == 0) {
+            if (1 + n_kept >= TAD_MAX_ARGS) return TAD_EUNSUPPORTED;
+            kept[n_kept] = q;
+            new_index[q] = 1 + n_kept++;
+        }
+    }
+    std::memset(eo, 0, sizeof *eo);
+    eo->body = TAD_BODY_PROGRAM;
+    eo->n_operands = 1 + n_kept;
+    int n = 0;
+    eo->inner[n].op = TAD_OP_ARG;
+    eo->inner[n++].iarg = 0;
+    if (!is_one) {
+        for (tad_op o : dprog) {
+            if (o.op == TAD_OP_ARG) o.iarg = new_index[o.iarg];
+            eo->inner[n++] = o;
+        }
+        eo->inner[n++].op = TAD_OP_MUL;
+    }
+    eo->n_inner = n;
+    eo->outer[0].op = TAD_OP_SUM;
+    eo->n_outer = 1;
+
+    // ---- index part ------------------------------------------------------------------------------------------
+    IMat M(D, D2);
+    for (int d = 0; d < D; ++d) {
+        for (int j = 0; j < N; ++j) {
+            int64_t v = 0;
+            for (int r = 0; r < R; ++r) v = cadd(v, cmul(ap.VR(d, r), ap.UR(r, j)));
+            M(d, j) = v;
+        }
+        for (int m = 0; m < kappa; ++m) M(d, N + m) = ap.K(d, m);
+    }
+    eo->n_f = N;
+    for (int j = 0; j < N; ++j) eo->f_shape[j] = pl.args[slot].shape[j];
+    eo->n_sum = kappa;
+    int64_t blo[TAD_MAX_EXT], bhi[TAD_MAX_EXT];   // box of the new extended index [beta z]
+    for (int j = 0; j < N; ++j) { blo[j] = 0; bhi[j] = pl.args[slot].shape[j] - 1; }
+    for (int m = 0; m < kappa; ++m) {
+        // z_m is row R + m of V^{-1} applied to the original extended index: its extremes over the original box
+        int64_t row[TAD_MAX_EXT], mn = 0, mx = 0;
+        for (int d = 0; d < D; ++d) row[d] = ap.Vinv(R + m, d);
+        if (!linear_form_range(row, D, pl.lo, pl.hi, E, pl.expr.constraint, mn, mx)) mn = mx = 0;
+        eo->sum_lo[m] = blo[N + m] = mn;
+        eo->sum_hi[m] = bhi[N + m] = mx;
+    }
+    // conditions c . [beta z] + c0 >= 0; one that holds on the whole new box, or is there already, is left out
+    auto add_condition = [&](const int64_t *c, int64_t c0) {
+        int64_t mn = c0;
+        bool any = false;
+        for (int j = 0; j < D2; ++j) {
+            mn = cadd(mn, std::min(cmul(c[j], blo[j]), cmul(c[j], bhi[j])));
+            any |= c[j] != 0;
+        }
+        if (mn >= 0) return true;
+        if (!any) return true;   // a constant condition that fails: cannot come from a valid plan; nothing to add
+        for (int e = 0; e < eo->n_constraints; ++e) {
+            bool same = eo->constraint[e][D2] == c0;
+            for (int j = 0; j < D2; ++j) same = same && eo->constraint[e][j] == c[j];
+            if (same) return true;
+        }
+        if (eo->n_constraints == TAD_MAX_CONSTRAINTS) return false;
+        int64_t *dst = eo->constraint[eo->n_constraints++];
+        for (int j = 0; j < D2; ++j) dst[j] = c[j];
+        dst[D2] = c0;
+        return true;
+    };
+    int64_t c[TAD_MAX_EXT];
+    for (int d = 0; d < D; ++d) {
+        for (int j = 0; j < D2; ++j) c[j] = M(d, j);
+        if (!add_condition(c, cneg(pl.lo[d]))) return TAD_EUNSUPPORTED;          //  x_d - lo_d >= 0
+        for (int j = 0; j < D2; ++j) c[j] = cneg(M(d, j));
+        if (!add_condition(c, pl.hi[d])) return TAD_EUNSUPPORTED;                // -x_d + hi_d >= 0
+    }
+    for (int e = 0; e < E; ++e) {
+        for (int j = 0; j < D2; ++j) {
+            int64_t v = 0;
+            for (int d = 0; d < D; ++d) v = cadd(v, cmul(pl.expr.constraint[e][d], M(d, j)));
+            c[j] = v;
+        }
+        if (!add_condition(c, pl.expr.constraint[e][D])) return TAD_EUNSUPPORTED;
+    }
+    for (int r = 0; r < N - R; ++r)
+        for (int sign = 1; sign >= -1; sign -= 2) {
+            for (int j = 0; j < D2; ++j) c[j] = j < N ? cmul(sign, ap.C(r, j)) : 0;
+            if (!add_condition(c, 0)) return TAD_EUNSUPPORTED;
+        }
+
+    // ---- operands: df through the first n_f rows of M, every kept operand through A^q M -----------------------
+    std::memset(ao, 0, sizeof(tad_arg) * TAD_MAX_ARGS);
+    ao[0].rank = nf;
+    ao[0].needs_grad = 1;
+    for (int r = 0; r < nf; ++r) {
+        ao[0].shape[r] = pl.expr.f_shape[r];
+        for (int j = 0; j < D2; ++j) ao[0].index[r][j] = M(r, j);
+    }
+    if (operand_out) operand_out[0] = -1;
+    for (int t = 0; t < n_kept; ++t) {
+        const int q = kept[t];
+        const tad_arg &src = pl.args[q];
+        tad_arg &dst = ao[1 + t];
+        dst.rank = src.rank;
+        dst.needs_grad = 1;
+        for (int r = 0; r < src.rank; ++r) {
+            dst.shape[r] = src.shape[r];
+            for (int j = 0; j < D2; ++j) {
+                int64_t v = 0;
+                for (int d = 0; d < D; ++d) v = cadd(v, cmul(src.index[r][d], M(d, j)));
+                dst.index[r][j] = v;
+            }
+        }
+        for (int u = 0; u < t; ++u)   // a later kept occurrence of the same tensor names the first kept one
+            if (pl.root[kept[u]] == pl.root[q]) { dst.alias = 1 + u + 1; break; }
+        if (operand_out) operand_out[1 + t] = q;
+    }
+    *n_out = 1 + n_kept;
+    return TAD_OK;
+}
+
 // Visit every extended index of beta through masks, ranges and the maps V_R y + K z.
 template <class Fn>
 static void visit_beta(int n_ext, const ArgPlan &ap, const int32_t *beta, Fn &&fn) {
@@ -462,13 +636,30 @@ size_t tad_plan_workspace_bytes(const tad_plan *plan) { return plan ? plan->ws_b
 int tad_plan_forward_family(const tad_plan *plan) { return plan ? plan->fwd_family : TAD_EINVAL; }
 
 // plan of occurrence `occ` of the tensor given as operand `arg` (0: the operand itself, k: its k-th alias)
-static const ArgPlan *get_arg(const tad_plan *plan, int arg, int occ) {
+static const ArgPlan *get_arg(const tad_plan *plan, int arg, int occ, int *slot_out = nullptr) {
     if (!plan || arg < 0 || arg >= (int)plan->ap.size() || occ < 0 || plan->root[arg] != arg) return nullptr;
     int slot = -1;
     for (int p = arg, k = 0; p < (int)plan->ap.size(); ++p)
         if (plan->root[p] == arg && k++ == occ) { slot = p; break; }
     if (slot < 0) return nullptr;
+    if (slot_out) *slot_out = slot;
     return plan->ap[slot].derived ? &plan->ap[slot] : nullptr;
+}
+
+int tad_plan_derived_expr(const tad_plan *plan, int arg, int occ, tad_expr *expr_out, tad_arg *args_out,
+                          int *operand_out, int *n_args_out) {
+    int slot = -1;
+    const ArgPlan *ap = get_arg(plan, arg, occ, &slot);
+    if (!ap || !expr_out || !args_out || !n_args_out) return TAD_EINVAL;
+    try {
+        return derived_expr(*plan, slot, *ap, expr_out, args_out, operand_out, n_args_out);
+    } catch (const overflow_error &) {
+        return TAD_EOVERFLOW;
+    } catch (const std::bad_alloc &) {
+        return TAD_ENOMEM;
+    } catch (...) {
+        return TAD_EINVAL;
+    }
 }
 
 int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out) {

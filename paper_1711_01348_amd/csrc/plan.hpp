@@ -16,6 +16,7 @@ struct ArgPlan {
     bool derived = false;
     Smith smith;                 // S = U A V
     IMat UR, VR, K, C;           // first R rows of U, first R columns of V, kernel, cokernel
+    IMat Vinv;                   // inverse of V: [y z] = Vinv [alpha k]
     std::vector<int64_t> diag;   // alpha_1..alpha_R
     FMResult fm;                 // rows over b(beta) in the paper's form
     GatherPlan dev;              // folded form used by kernels and by enumeration

@@ -27,7 +27,7 @@ constexpr int kMaxExt = 6;
 constexpr int kMaxRank = 4;
 constexpr int kMaxArgs = 4;
 constexpr int kMaxKernel = 4;
-constexpr int kMaxCons = 4;
+constexpr int kMaxCons = 8;
 constexpr int kMaxRows = 32;   // lower + upper rows over all levels
 constexpr int kMaxFeas = 12;
 constexpr int kSlotF = kMaxArgs;        // offset slot of f / df

@@ -123,13 +123,10 @@ inline void reverse_accumulate(Graph &g, int result, int n_inputs, std::vector<i
     }
 }
 
-// Lower the part of the graph that `result` depends on: products with the constant 1 and double negations are
-// dropped, equal constants share a slot, the nodes are renumbered densely.  False if it does not fit.
-inline bool lower(const Graph &g, int result, DevProg &out) {
-    out = DevProg{};
-    if (result < 0) { out.n = 0; out.result = -1; return true; }
+// Peephole simplification: alias[i] = an earlier node that computes the same value as node i (products with the
+// constant 1, division by 1 and double negations are dropped).
+inline std::vector<int> simplify(const Graph &g) {
     const int N = (int)g.nodes.size();
-    // peephole: alias[i] = node that computes the same value
     std::vector<int> alias(N);
     auto is_one = [&](int i) { return g.nodes[i].op == P_CONST && g.nodes[i].c == 1.0; };
     for (int i = 0; i < N; ++i) {
@@ -141,6 +138,16 @@ inline bool lower(const Graph &g, int result, DevProg &out) {
         else if (nd.op == P_DIV && is_one(b)) alias[i] = a;
         else if (nd.op == P_NEG && g.nodes[a].op == P_NEG) alias[i] = alias[g.nodes[a].a];
     }
+    return alias;
+}
+
+// Lower the part of the graph that `result` depends on: simplified as above, equal constants share a slot, the
+// nodes are renumbered densely.  False if it does not fit.
+inline bool lower(const Graph &g, int result, DevProg &out) {
+    out = DevProg{};
+    if (result < 0) { out.n = 0; out.result = -1; return true; }
+    const int N = (int)g.nodes.size();
+    const std::vector<int> alias = simplify(g);
     result = alias[result];
     std::vector<char> live(N, 0);
     live[result] = 1;
@@ -178,6 +185,25 @@ inline bool lower(const Graph &g, int result, DevProg &out) {
     out.n = n;
     out.result = slot[result];
     return true;
+}
+
+// Postfix form of the expression computing `node`, appended to `out` (a sub-expression used twice is written
+// twice); same simplifications as lower().  False once the program grows beyond `cap` operations.
+inline bool emit_postfix(const Graph &g, const std::vector<int> &alias, int node, std::vector<tad_op> &out, size_t cap) {
+    static_assert((int)P_CONST == (int)TAD_OP_CONST && (int)P_ARG == (int)TAD_OP_ARG && (int)P_SUM == (int)TAD_OP_SUM && (int)P_ADD == (int)TAD_OP_ADD &&
+                      (int)P_SUB == (int)TAD_OP_SUB && (int)P_MUL == (int)TAD_OP_MUL && (int)P_DIV == (int)TAD_OP_DIV && (int)P_NEG == (int)TAD_OP_NEG &&
+                      (int)P_EXP == (int)TAD_OP_EXP && (int)P_LOG == (int)TAD_OP_LOG && (int)P_SIN == (int)TAD_OP_SIN && (int)P_COS == (int)TAD_OP_COS &&
+                      (int)P_TANH == (int)TAD_OP_TANH && (int)P_SQRT == (int)TAD_OP_SQRT && (int)P_POWI == (int)TAD_OP_POWI,
+                  "internal and public operation codes are numbered alike");
+    const Node &nd = g.nodes[alias[node]];
+    if (nd.a >= 0 && !emit_postfix(g, alias, nd.a, out, cap)) return false;
+    if (nd.b >= 0 && !emit_postfix(g, alias, nd.b, out, cap)) return false;
+    tad_op o{};
+    o.op = nd.op;
+    o.iarg = (nd.op == P_ARG || nd.op == P_POWI) ? nd.k : 0;
+    o.value = nd.op == P_CONST ? nd.c : 0.0;
+    out.push_back(o);
+    return out.size() <= cap;
 }
 
 // Evaluation of a lowered program (the host twin of the kernels' interpreter), fp64.

@@ -1,0 +1,236 @@
+"""A gradient written out as an element-wise defined tensor of its own (Sec. 5.3: derived expressions have the
+form of the input again, so they can be evaluated and differentiated once more).  Host logic only, no GPU:
+the emitted expression is checked term by term against the brute-force scan of the original expression, and
+its values, computed by a few lines of numpy here, against the oracle's scatter gradient of the original.
+For the second level an expression that has passed this check takes the place of the original."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1711_01348_amd import binding as B
+from paper_1711_01348_amd import workloads as wl
+
+
+def _expr(body, f_shape, sums, args, dtype="f64", **kw):
+    return wl.ExprSpec(body, tuple(f_shape), list(sums), [wl.ArgSpec(n, tuple(s), A) for n, s, A in args], dtype, **kw)
+
+
+def _slots(e):
+    """(tensor operand, occurrence number, operand slot) of every occurrence."""
+    out = []
+    for p, a in enumerate(e.args):
+        root = p if a.same_as is None else a.same_as
+        out.append((root, sum(1 for r, _, _ in out if r == root), p))
+    return out
+
+
+def _ext_points(spec, beta):
+    """Extended indices [beta z] of the terms of `spec` at function index beta."""
+    for z in itertools.product(*[range(lo, hi + 1) for lo, hi in spec.sums]):
+        ext = list(beta) + list(z)
+        if all(sum(c * v for c, v in zip(coef, ext)) + const >= 0 for coef, const in spec.constraints):
+            yield ext
+
+
+def _terms_of(spec, beta):
+    """Per term: the index tuple of every operand (operand 0 is df)."""
+    out = []
+    for ext in _ext_points(spec, beta):
+        t = tuple(tuple(sum(a * v for a, v in zip(row, ext)) for row in arg.A) for arg in spec.args)
+        for idx, arg in zip(t, spec.args):
+            assert all(0 <= i < n for i, n in zip(idx, arg.shape)), (beta, ext, arg.name, idx)
+        out.append(t)
+    return sorted(out)
+
+
+def _terms_brute(e, slot, beta, operands):
+    """The same from the scan of the original box: function index and the indices of the kept operands."""
+    nf = len(e.f_shape)
+    out = []
+    for x in oracle.gamma(e, slot, beta):
+        t = [tuple(int(v) for v in x[:nf])]
+        for q in operands[1:]:
+            t.append(tuple(int(np.dot(row, x)) for row in e.args[q].A))
+        out.append(tuple(t))
+    return sorted(out)
+
+
+def _run_postfix(prog, values, total=0.0):
+    st = []
+    una = {"neg": lambda a: -a, "exp": math.exp, "log": math.log, "sin": math.sin, "cos": math.cos,
+           "tanh": math.tanh, "sqrt": math.sqrt}
+    for t in prog:
+        if t[0] == "const": st.append(float(t[1]))
+        elif t[0] == "arg": st.append(values[t[1]])
+        elif t[0] == "sum": st.append(total)
+        elif t[0] == "powi": st.append(st.pop() ** t[1])
+        elif t[0] in una: st.append(una[t[0]](st.pop()))
+        else:
+            b, a = st.pop(), st.pop()
+            st.append({"add": a + b, "sub": a - b, "mul": a * b, "div": a / b if t[0] == "div" else 0.0}[t[0]])
+    assert len(st) == 1
+    return st[0]
+
+
+def _evaluate(spec, tensors):
+    """f of a program expression by its definition."""
+    f = np.zeros(spec.f_shape)
+    for beta in itertools.product(*[range(n) for n in spec.f_shape]):
+        s = 0.0
+        for ext in _ext_points(spec, beta):
+            vals = [t[tuple(sum(a * v for a, v in zip(row, ext)) for row in arg.A)] for t, arg in zip(tensors, spec.args)]
+            s += _run_postfix(spec.inner, vals)
+        f[beta] = _run_postfix(spec.outer, [], s)
+    return f
+
+
+def _nonlinear(I, J, K):
+    """f_ij = sum_k exp(x_ik) sqrt(y_kj^2 + 1) / (2 + cos(z_{i+k})): the inner function of a body without a
+    built-in twin, summed without an outer function."""
+    e = wl.softplus_ratio_expr(I, J, K, "f64")
+    e.outer = [("sum",)]
+    return e
+
+
+def _triple(N):
+    """f_i = sum_{j <= i} x_j x_{i-j} x_i: one tensor three times, a range that depends on i."""
+    return wl.ExprSpec("program", (N,), [(0, N - 1)],
+                       [wl.ArgSpec("x", (N,), [[0, 1]]), wl.ArgSpec("x2", (N,), [[1, -1]], same_as=0),
+                        wl.ArgSpec("x3", (N,), [[1, 0]], same_as=0)], "f64",
+                       inner=[("arg", 0), ("arg", 1), ("mul",), ("arg", 2), ("mul",)], outer=[("sum",)],
+                       constraints=[([1, -1], 0)])
+
+
+def _status(fn):
+    try:
+        fn()
+    except B.TadError as e:
+        return e.status
+    return 0
+
+
+CASES = [
+    ("matmul", lambda: wl.matmul_expr(3, 4, 5, "f64")),
+    ("matmul_transposed", lambda: wl.matmul_expr(4, 3, 2, "f64", True, True, True)),
+    ("broadcast_sq", lambda: wl.broadcast_sq_expr(4, 5, "f64")),
+    ("diagonal_cube", lambda: _expr("cube", (4,), [], [("x", (4, 6), [[1], [1]])])),          # cokernel condition
+    ("antidiagonal", lambda: _expr("mul", (6, 5), [], [("x", (10,), [[1, 1]]), ("y", (6,), [[1, 0]])])),
+    ("plane", lambda: _expr("sin", (3, 3, 2), [], [("x", (12,), [[1, 2, 3]])])),               # kernel dimension 2
+    ("skew_plane", lambda: _expr("mul", (4, 3), [(0, 2)], [("x", (9, 3), [[2, 1, 0], [0, 0, 1]]),
+                                                           ("y", (6,), [[1, 0, 1]])])),
+    ("causal_conv", lambda: wl.causal_convolution_expr(9, 4, "f64")),
+    ("triangular", lambda: wl.triangular_matmul_expr(3, 5, "f64")),
+    ("skew_condition", lambda: wl.ExprSpec("mul", (5, 6), [(0, 3)],
+                                           [wl.ArgSpec("x", (5, 4), [[1, 0, 0], [0, 0, 1]]),
+                                            wl.ArgSpec("y", (12,), [[0, 1, 2]])], "f64",
+                                           constraints=[([2, 1, -3], -1)])),
+    ("matrix_square", lambda: wl.matrix_square_expr(4, "f64")),
+    ("symmetric_product", lambda: wl.symmetric_product_expr(3, 5, "f64")),
+    ("autocorrelation", lambda: wl.autocorrelation_expr(6, 3, "f64")),
+    ("nonlinear", lambda: _nonlinear(3, 4, 2)),
+    ("triple", lambda: _triple(6)),
+]
+
+
+def _check_against_original(e, depth):
+    """Every derived expression of `e` has exactly the terms of the brute-force scan, its values are the
+    oracle's gradient, and (depth > 0) the same holds for the expressions derived from it."""
+    plan = B.Plan(e)
+    w = wl.random_inputs(e, 17 + depth, -0.9, 0.9)
+    tensors = w.arg_list()
+    want = oracle.backward(e, tensors, w.df)
+    for root, occ, slot in _slots(e):
+        spec, operands = plan.derived_expr(root, occ)
+        assert operands[0] == -1 and spec.args[0].shape == tuple(e.f_shape) and spec.f_shape == tuple(e.args[slot].shape)
+        assert spec.outer == [("sum",)] and spec.inner[0] == ("arg", 0)
+        for beta in itertools.product(*[range(n) for n in spec.f_shape]):
+            assert _terms_of(spec, beta) == _terms_brute(e, slot, beta, operands), (slot, beta)
+        got = _evaluate(spec, [w.df] + [tensors[q] for q in operands[1:]])
+        np.testing.assert_allclose(got, want[slot], rtol=1e-12, atol=1e-13)
+        # occurrences of one tensor among the kept operands stay one tensor
+        for q, a in enumerate(spec.args):
+            if a.same_as is not None:
+                r0 = lambda p: p if e.args[p].same_as is None else e.args[p].same_as
+                assert r0(operands[q]) == r0(operands[a.same_as]) and spec.args[a.same_as].same_as is None
+        B.Plan(spec)    # it is a valid expression again
+        if depth > 0:
+            _check_against_original(spec, depth - 1)
+
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+def test_derived_expression_is_the_gradient(name, make):
+    _check_against_original(make(), 1 if name not in ("plane", "nonlinear") else 0)
+
+
+def test_second_level_of_a_plane_and_of_a_nonlinear_body():
+    spec, _ = B.Plan(CASES[5][1]()).derived_expr(0)
+    assert len(spec.sums) == 2 and len(spec.constraints) == 2        # x_{a+2b+3c}: two free coordinates, one clipped row
+    _check_against_original(spec, 0)
+    # with three operands in the partial derivative, the next level has room for the derivative with respect
+    # to df only: the others would need df, the first level's df and all three tensors
+    e = CASES[13][1]()
+    for p in range(3):
+        spec, _ = B.Plan(e).derived_expr(p)
+        plan = B.Plan(spec)
+        again, operands = plan.derived_expr(0)
+        assert operands == [-1, 1, 2, 3]
+        assert [_status(lambda q=q: plan.derived_expr(q)) for q in (1, 2, 3)] == [-5, -5, -5]
+
+
+def test_scalar_part_is_df_times_the_symbolic_partial_derivative():
+    e = _nonlinear(2, 2, 2)
+    plan = B.Plan(e)
+    rng = np.random.default_rng(5)
+    for p in range(3):
+        spec, operands = plan.derived_expr(p)
+        dplan = B.Plan(spec)
+        for _ in range(20):
+            vals = rng.uniform(-1, 1, 3)
+            g = rng.uniform(-1, 1)
+            got = dplan.program_eval(-1, [g] + [vals[q] for q in operands[1:]])
+            assert got == pytest.approx(g * plan.program_eval(p, vals), rel=1e-14, abs=1e-15)
+    # d (x y) / d x = y: the factor 1 from the seed of the backward sweep is not written out
+    spec, operands = B.Plan(wl.matmul_expr(2, 2, 2, "f64")).derived_expr(0)
+    assert spec.inner == [("arg", 0), ("arg", 1), ("mul",)] and operands == [-1, 1]
+    # a derivative that is the constant 1 leaves df alone: f_ij = sum_k (x_ik + y_kj)
+    e = wl.matmul_expr(2, 3, 4, "f64")
+    e = wl.ExprSpec("program", e.f_shape, e.sums, e.args, "f64", [("arg", 0), ("arg", 1), ("add",)], [("sum",)])
+    spec, operands = B.Plan(e).derived_expr(1)
+    assert spec.inner == [("arg", 0)] and operands == [-1] and len(spec.args) == 1
+
+
+def test_product_programs_run_on_the_matrix_cores():
+    """The derived expressions of a matrix product are matrix products again."""
+    plan = B.Plan(wl.matmul_expr(8, 12, 16, "f32"))
+    for p in range(2):
+        spec, _ = plan.derived_expr(p)
+        assert B.Plan(spec).forward_family == "contraction"
+        assert B.Plan(spec, generic_only=True).forward_family == "program"
+    assert B.Plan(wl.as_program(wl.matmul_expr(8, 12, 16, "f32"))).forward_family == "contraction"
+    assert B.Plan(wl.as_program(wl.matmul_expr(8, 12, 16, "f64"))).forward_family == "program"
+
+
+def test_derived_expression_rules():
+    # an outer function puts a second, nested sum into the gradient: not of the single-sum form
+    assert _status(lambda: B.Plan(wl.config1().expr).derived_expr(0)) == -5
+    assert _status(lambda: B.Plan(wl.as_program(wl.config1().expr)).derived_expr(0)) == -5
+    # a Smith divisor above 1 is a divisibility mask, not a linear condition
+    e = _expr("sq", (4,), [], [("x", (8,), [[2]])])
+    assert _status(lambda: B.Plan(e).derived_expr(0)) == -5
+    plan = B.Plan(wl.matrix_square_expr(3, "f64"))
+    assert _status(lambda: plan.derived_expr(1)) == -1           # an alias operand is reached through its tensor
+    assert _status(lambda: plan.derived_expr(0, 2)) == -1
+    assert _status(lambda: B.Plan(wl.matmul_expr(2, 2, 2, "f64"), needs_grad=[False, True]).derived_expr(0)) == -1
+    # df would be an operand of rank 5
+    e = _expr("sin", (2, 2, 2, 2, 2), [], [("x", (2, 2, 2, 4), [[1, 0, 0, 0, 0], [0, 1, 0, 0, 0], [0, 0, 1, 0, 0],
+                                                                 [0, 0, 0, 1, 1]])])
+    assert _status(lambda: B.Plan(e).derived_expr(0)) == -5
+    # rank 4 with a cokernel row and a three-dimensional kernel: 4 + 3 indices are one too many
+    e = _expr("mul", (2, 2, 2, 2), [(0, 1), (0, 1)],
+              [("x", (2, 2, 2, 2), [[1, 0, 0, 0, 0, 0], [1, 0, 0, 0, 0, 0], [0, 1, 0, 0, 0, 0], [0, 0, 1, 0, 0, 0]]),
+               ("y", (2, 2, 2), [[0, 0, 0, 1, 0, 0], [0, 0, 0, 0, 1, 0], [0, 0, 0, 0, 0, 1]])])
+    assert _status(lambda: B.Plan(e).derived_expr(0)) == -5
+    assert _status(lambda: B.Plan(e).derived_expr(1)) == 0

@@ -418,3 +418,90 @@ def test_direct_and_expanded_forward_forms_agree():
         assert np.allclose(row, np.exp(-s), rtol=1e-12)
         assert check.within(fd[i], row, "f32"), ("direct", i, check.errors(fd[i], row))
         assert check.within(fe[i], row, "f32"), ("expanded", i, check.errors(fe[i], row))
+
+
+# ---- a gradient evaluated as an expression of its own, and differentiated once more (Sec. 5.3) ---------------
+
+def _nonlinear_sum(I, J, K, dtype):
+    e = wl.softplus_ratio_expr(I, J, K, dtype)
+    e.outer = [("sum",)]
+    return e
+
+
+DERIVED = [
+    ("matmul_f64", lambda: wl.matmul_expr(23, 17, 31, "f64")),
+    ("matmul_f32", lambda: wl.matmul_expr(37, 29, 41, "f32", True, False, True)),
+    ("broadcast_sq_f32", lambda: wl.broadcast_sq_expr(70, 300, "f32")),
+    ("diagonal_cube_f64", lambda: _expr("cube", (33,), [], [("x", (33, 40), [[1], [1]])])),
+    ("causal_conv_f64", lambda: wl.causal_convolution_expr(300, 17, "f64")),
+    ("triangular_f32", lambda: wl.triangular_matmul_expr(40, 50, "f32")),
+    ("matrix_square_f64", lambda: wl.matrix_square_expr(21, "f64")),
+    ("autocorrelation_f32", lambda: wl.autocorrelation_expr(500, 33, "f32")),
+    ("nonlinear_f64", lambda: _nonlinear_sum(19, 23, 7, "f64")),
+    ("skew_plane_f64", lambda: _expr("mul", (14, 9), [(0, 5)], [("x", (40, 6), [[2, 1, 0], [0, 0, 1]]),
+                                                                ("y", (19,), [[1, 0, 1]])])),
+]
+
+
+@pytest.mark.parametrize("name,make", DERIVED, ids=[d[0] for d in DERIVED])
+def test_derived_expressions(name, make):
+    """The gradient of every occurrence, emitted as an expression and run through the forward kernels, is the
+    oracle's gradient of the original expression; its own gradients (second order) are the oracle's gradients of
+    that expression, whose terms the host tests check against the scan of the original."""
+    import torch
+    from paper_1711_01348_amd import binding as B
+    e = make()
+    w = wl.random_inputs(e, 31, -0.9, 0.9)
+    tensors = w.arg_list()
+    want = oracle.backward(e, tensors, w.df, nthreads=8)
+    plan = B.Plan(e)
+    rng = np.random.Generator(np.random.PCG64(wl.SEED_BASE + 77))
+    slots, seen = [], {}
+    for p, a in enumerate(e.args):
+        root = p if a.same_as is None else a.same_as
+        slots.append((root, seen.get(root, 0), p))
+        seen[root] = seen.get(root, 0) + 1
+    for root, occ, slot in slots:
+        spec, operands = plan.derived_expr(root, occ)
+        dplan = B.Plan(spec)
+        ins = [w.df] + [tensors[q] for q in operands[1:]]
+        dev = [_to_dev(x) for x in ins]
+        got = dplan.forward(dev)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy()
+        assert check.within(got, want[slot], e.dtype), (name, slot, check.errors(got, want[slot]))
+        assert np.all(got[want[slot] == 0] == 0), (name, slot, "mask")
+        # second order: v . dx differentiated with respect to df and the kept operands
+        v = rng.uniform(-1, 1, spec.f_shape).astype(got.dtype)
+        grads = dplan.backward(dev, _to_dev(got), _to_dev(v))
+        torch.cuda.synchronize()
+        ref = oracle.backward_by_tensor(spec, ins, v, nthreads=8)
+        for a, g, r in zip(spec.args, grads, ref):
+            if r is None:
+                continue
+            g = g.cpu().numpy()
+            assert check.within(g, r, e.dtype), (name, slot, "d" + a.name, check.errors(g, r))
+
+
+def test_second_order_matrix_product_closed_form_on_the_matrix_cores():
+    """dx = df y^T for f = x y; with a weight v on dx: d(v . dx)/d df = v y and d(v . dx)/d y = v^T df."""
+    import torch
+    from paper_1711_01348_amd import binding as B
+    I, J, K = 192, 136, 260
+    e = wl.matmul_expr(I, J, K, "f32")
+    w = wl.random_inputs(e, 5)
+    x, y = w.arg_list()
+    spec, operands = B.Plan(e).derived_expr(0)
+    assert operands == [-1, 1]
+    dplan = B.Plan(spec)
+    assert dplan.forward_family == "contraction"
+    rng = np.random.Generator(np.random.PCG64(wl.SEED_BASE + 78))
+    v = rng.uniform(-1, 1, (I, K)).astype(np.float32)
+    dev = [_to_dev(w.df), _to_dev(y)]
+    dx = dplan.forward(dev)
+    g_df, g_y = dplan.backward(dev, dx, _to_dev(v))
+    torch.cuda.synchronize()
+    df64, y64, v64 = w.df.astype(np.float64), y.astype(np.float64), v.astype(np.float64)
+    for got, ref, what in ((dx, df64 @ y64.T, "dx"), (g_df, v64 @ y64, "d df"), (g_y, v64.T @ df64, "d y")):
+        got = got.cpu().numpy()
+        assert check.within(got, ref, "f32"), (what, check.errors(got, ref))

@@ -509,7 +509,7 @@ def test_program_rules():
     assert _status(lambda: mk([("arg", 0), ("powi", 0)], ok_out)) == -1
     assert _status(lambda: mk([("const", float("inf"))], ok_out)) == -1
     assert _status(lambda: mk(ok_in, [])) == -1
-    assert _status(lambda: mk([("arg", 0)] + [("neg",)] * 24, ok_out)) == -1    # longer than TAD_MAX_PROGRAM
+    assert _status(lambda: mk([("arg", 0)] + [("neg",)] * 48, ok_out)) == -1    # longer than TAD_MAX_PROGRAM
     # a derivative too long for the device form is refused, not truncated
     long_inner = [("arg", 0)] + [("arg", 0), ("div",), ("sin",)] * 7
     assert _status(lambda: mk(long_inner, ok_out)) in (0, -5)
@@ -552,7 +552,7 @@ def test_condition_rules():
     e = wl.cumulative_sum_expr(5, "f64")
     rows = B.Plan(e).bound_rows(0, B.ROWS_LOWER) + B.Plan(e).bound_rows(0, B.ROWS_UPPER)
     assert any(r["coef_c"].any() for r in rows)            # the condition shows up in the range rows
-    e.constraints = e.constraints * 5
+    e.constraints = e.constraints * 9
     assert _status(lambda: B.Plan(e)) == -1                 # more than TAD_MAX_CONSTRAINTS
     # x_{i-k} without the condition k <= i leaves the tensor; with it, it does not
     e = wl.causal_convolution_expr(6, 3, "f64")
