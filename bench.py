@@ -236,7 +236,7 @@ def main():
                     help="also run a plain 256 MiB device copy 5 times (reference point for HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+        print("bench.py: this library runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
     import torch
