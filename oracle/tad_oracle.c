@@ -30,6 +30,10 @@
  *              derivatives are taken by forward-mode differentiation with dual numbers (value and
  *              derivative carried together through every operation), the textbook rules of Sec. 2's
  *              elementary functions -- deliberately not the reverse accumulation the GPU library uses.
+ *              The outer program may also read operands whose index does not depend on the summation
+ *              indices, at the function index (Sec. 5.2, the sum-liberated function
+ *              fhat = fbar(s(...), x^1_{A^1 alpha}, ...)): such an operand receives, per function index,
+ *              the extra gradient term df_alpha * d fbar / d x.
  */
 #include <math.h>
 #include <stdint.h>
@@ -102,12 +106,11 @@ static int body_nargs(int b) {
 typedef struct { double v, d; } dual;
 
 /*
- * Run a postfix program on dual numbers.  `args` are the operand values (inner program), `sum` the summed
- * inner value (outer program).  The input `seed` (operand index; 0 for the sum) has derivative one, every
- * other input and every constant derivative zero; seed < 0 gives the plain value.  A malformed program
- * yields NaN.
+ * Run a postfix program on dual numbers.  `args` are the operand values, `sum` the summed inner value (outer
+ * program).  One input has derivative one -- operand `seed_arg` (none if negative), or the sum if `seed_sum`
+ * is set --, every other input and every constant derivative zero.  A malformed program yields NaN.
  */
-static dual run_program(const orc_op *ops, int n, const double *args, double sum, int seed) {
+static dual run_program(const orc_op *ops, int n, const double *args, double sum, int seed_arg, int seed_sum) {
     dual st[ORC_MAX_PROGRAM + 1];
     int top = 0;
     const dual bad = {NAN, NAN};
@@ -115,8 +118,8 @@ static dual run_program(const orc_op *ops, int n, const double *args, double sum
         const orc_op *o = &ops[i];
         dual r;
         if (o->op == O_CONST) { r.v = o->value; r.d = 0.0; }
-        else if (o->op == O_ARG) { r.v = args[o->iarg]; r.d = (o->iarg == seed) ? 1.0 : 0.0; }
-        else if (o->op == O_SUM) { r.v = sum; r.d = (seed == 0) ? 1.0 : 0.0; }
+        else if (o->op == O_ARG) { r.v = args[o->iarg]; r.d = (o->iarg == seed_arg) ? 1.0 : 0.0; }
+        else if (o->op == O_SUM) { r.v = sum; r.d = seed_sum ? 1.0 : 0.0; }
         else if (o->op >= O_ADD && o->op <= O_DIV) {
             if (top < 2) return bad;
             dual y = st[--top], x = st[--top];
@@ -146,7 +149,7 @@ static dual run_program(const orc_op *ops, int n, const double *args, double sum
 
 /* summand s(v) of the inner sum */
 static double inner(const orc_expr *e, int b, const double *v) {
-    if (b == B_PROGRAM) return run_program(e->inner, e->n_inner, v, 0.0, -1).v;
+    if (b == B_PROGRAM) return run_program(e->inner, e->n_inner, v, 0.0, -1, 0).v;
     switch (b) {
     case B_MUL: case B_TANH_DOT: return v[0] * v[1];
     case B_WORKED: { double t = v[0] + v[1]; return t * t * v[2] + v[3] * v[3] * v[3]; }
@@ -156,7 +159,7 @@ static double inner(const orc_expr *e, int b, const double *v) {
 
 /* d s / d v[p] */
 static double dinner(const orc_expr *e, int b, int p, const double *v) {
-    if (b == B_PROGRAM) return run_program(e->inner, e->n_inner, v, 0.0, p).d;
+    if (b == B_PROGRAM) return run_program(e->inner, e->n_inner, v, 0.0, p, 0).d;
     switch (b) {
     case B_MUL: case B_TANH_DOT: return p == 0 ? v[1] : v[0];
     case B_WORKED:
@@ -167,8 +170,9 @@ static double dinner(const orc_expr *e, int b, int p, const double *v) {
     }
 }
 
-static double outer(const orc_expr *e, int b, double s) {
-    if (b == B_PROGRAM) return run_program(e->outer, e->n_outer, NULL, s, -1).v;
+/* fbar(s, operand values at the function index); v is only read by programs */
+static double outer(const orc_expr *e, int b, double s, const double *v) {
+    if (b == B_PROGRAM) return run_program(e->outer, e->n_outer, v, s, -1, 0).v;
     switch (b) {
     case B_SQ: return s * s;
     case B_CUBE: return s * s * s;
@@ -181,9 +185,15 @@ static double outer(const orc_expr *e, int b, double s) {
     }
 }
 
+/* d outer / d operand p (programs only; a built-in outer function takes no operands) */
+static double douter_arg(const orc_expr *e, int b, double s, const double *v, int p) {
+    if (b == B_PROGRAM) return run_program(e->outer, e->n_outer, v, s, p, 0).d;
+    return 0.0;
+}
+
 /* d outer / d s */
-static double douter(const orc_expr *e, int b, double s) {
-    if (b == B_PROGRAM) return run_program(e->outer, e->n_outer, NULL, s, 0).d;
+static double douter(const orc_expr *e, int b, double s, const double *v) {
+    if (b == B_PROGRAM) return run_program(e->outer, e->n_outer, v, s, -1, 1).d;
     switch (b) {
     case B_SQ: return 2.0 * s;
     case B_CUBE: return 3.0 * s * s;
@@ -217,8 +227,15 @@ static int check_expr(const orc_expr *e, int *b) {
         for (int i = 0; i < e->n_inner; ++i)
             if (e->inner[i].op == O_SUM || (e->inner[i].op == O_ARG && (e->inner[i].iarg < 0 || e->inner[i].iarg >= e->n_args)))
                 return -5;
+        /* the outer function may read an operand only if its index ignores the summation indices */
         for (int i = 0; i < e->n_outer; ++i)
-            if (e->outer[i].op == O_ARG) return -5;
+            if (e->outer[i].op == O_ARG) {
+                int p = e->outer[i].iarg;
+                if (p < 0 || p >= e->n_args) return -5;
+                for (int r = 0; r < e->args[p].rank && r < ORC_MAX_RANK; ++r)
+                    for (int q = 0; q < e->n_sum; ++q)
+                        if (e->args[p].A[r][e->n_f + q] != 0) return -5;
+            }
     } else if (e->n_args != body_nargs(*b)) return -2;
     if (e->n_f < 0 || e->n_sum < 0 || e->n_f + e->n_sum > ORC_MAX_EXT) return -3;
     if (e->n_cond < 0 || e->n_cond > ORC_MAX_COND) return -6;
@@ -283,6 +300,29 @@ static int eval_s(const orc_expr *e, int b, const double *const *args, int64_t *
     return 0;
 }
 
+/* is operand p read by the outer program? */
+static int in_outer(const orc_expr *e, int b, int p) {
+    if (b != B_PROGRAM) return 0;
+    for (int i = 0; i < e->n_outer; ++i)
+        if (e->outer[i].op == O_ARG && e->outer[i].iarg == p) return 1;
+    return 0;
+}
+
+/* values (and positions) of the operands the outer program reads, at the function index in ext */
+static int outer_values(const orc_expr *e, int b, const double *const *args, int64_t *ext, double *v, int64_t *pos) {
+    int n_ext = e->n_f + e->n_sum;
+    for (int q = 0; q < e->n_sum; ++q) ext[e->n_f + q] = e->sum_lo[q];   /* any value: those columns are zero */
+    for (int p = 0; p < e->n_args; ++p) {
+        v[p] = 0.0;
+        pos[p] = -1;
+        if (!in_outer(e, b, p)) continue;
+        pos[p] = arg_pos(&e->args[p], n_ext, ext);
+        if (pos[p] < 0) return -10;
+        v[p] = args[p][pos[p]];
+    }
+    return 0;
+}
+
 /* Forward: f_alpha for every alpha (Sec. 5.1, 5.2). */
 int orc_forward(const orc_expr *e, const double *const *args, double *f) {
     int b, rc = check_expr(e, &b);
@@ -292,10 +332,11 @@ int orc_forward(const orc_expr *e, const double *const *args, double *f) {
 #pragma omp parallel for schedule(static)
     for (int64_t lin = 0; lin < nf; ++lin) {
         int64_t ext[ORC_MAX_EXT];
-        double s;
+        double s, vo[ORC_MAX_ARGS];
+        int64_t po[ORC_MAX_ARGS];
         unflatten_f(e, lin, ext);
-        if (eval_s(e, b, args, ext, &s)) { err = -10; continue; }
-        f[lin] = outer(e, b, s);
+        if (eval_s(e, b, args, ext, &s) || outer_values(e, b, args, ext, vo, po)) { err = -10; continue; }
+        f[lin] = outer(e, b, s, vo);
     }
     return err;
 }
@@ -304,6 +345,7 @@ int orc_forward(const orc_expr *e, const double *const *args, double *f) {
  * Backward by brute-force scatter (Sec. 5.1 "elementary approach", with the
  * sum-extended index set of Sec. 5.2):
  *   for every alpha, every k:   dx^p[ Ahat^p [alpha k] ] += df_alpha * outer'(s_alpha) * d inner / d x^p
+ *   for every alpha, every operand the outer function reads:   dx^p[ A^p alpha ] += df_alpha * d outer / d x^p
  * dx[p] may be NULL (gradient not wanted).  dx[p] is overwritten.
  * With nthreads > 1 the function indices are split in contiguous chunks, every
  * thread scatters into private copies which are then added in thread order.
@@ -338,13 +380,15 @@ int orc_backward(const orc_expr *e, const double *const *args, const double *df,
             int64_t lo = nf * t / nthreads, hi = nf * (t + 1) / nthreads;
             double **my = priv + t * ORC_MAX_ARGS;
             int64_t ext[ORC_MAX_EXT];
-            double v[ORC_MAX_ARGS];
-            int64_t pos[ORC_MAX_ARGS];
+            double v[ORC_MAX_ARGS], vo[ORC_MAX_ARGS];
+            int64_t pos[ORC_MAX_ARGS], po[ORC_MAX_ARGS];
             for (int64_t lin = lo; lin < hi; ++lin) {
                 double s;
                 unflatten_f(e, lin, ext);
-                if (eval_s(e, b, args, ext, &s)) { err = -10; break; }
-                double w = df[lin] * douter(e, b, s);
+                if (eval_s(e, b, args, ext, &s) || outer_values(e, b, args, ext, vo, po)) { err = -10; break; }
+                double w = df[lin] * douter(e, b, s, vo);
+                for (int p = 0; p < e->n_args; ++p)
+                    if (my[p] && po[p] >= 0) my[p][po[p]] += df[lin] * douter_arg(e, b, s, vo, p);
                 if (sums_empty(e)) continue;
                 for (int q = 0; q < e->n_sum; ++q) ext[e->n_f + q] = e->sum_lo[q];
                 do {

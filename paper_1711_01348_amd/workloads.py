@@ -41,7 +41,8 @@ class ExprSpec:
     dtype: str = "f64"              # "f64" or "f32"
     # body "program": the scalar functions as postfix programs, f = outer(sum_k inner(operand values)).
     # Entries: ("arg", p), ("const", c), ("sum",), ("add",), ("sub",), ("mul",), ("div",), ("neg",), ("exp",),
-    # ("log",), ("sin",), ("cos",), ("tanh",), ("sqrt",), ("powi", n)
+    # ("log",), ("sin",), ("cos",), ("tanh",), ("sqrt",), ("powi", n).  ("sum",) belongs to the outer program;
+    # ("arg", p) to the inner one and, for operands whose index ignores the summation indices, to the outer one.
     inner: List[tuple] = field(default_factory=list)
     outer: List[tuple] = field(default_factory=list)
     # extra linear conditions on the extended index (summation ranges that depend on other indices, Sec. 5.2):
@@ -184,6 +185,26 @@ def softplus_ratio_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
     return ExprSpec("program", (I, J), [(0, K - 1)],
                     [ArgSpec("x", (I, K), [[1, 0, 0], [0, 0, 1]]), ArgSpec("y", (K, J), [[0, 0, 1], [0, 1, 0]]),
                      ArgSpec("z", (I + K - 1,), [[1, 0, 1]])], dtype, inner, outer)
+
+
+# Operands of the outer function (Sec. 5.2: fbar takes the sum and tensors indexed by the function index alone)
+
+def biased_tanh_expr(I: int, K: int, dtype: str) -> ExprSpec:
+    """f_i = tanh(b_i + sum_k x_ik w_k): the bias is read by the outer function, once per i."""
+    return ExprSpec("program", (I,), [(0, K - 1)],
+                    [ArgSpec("x", (I, K), [[1, 0], [0, 1]]), ArgSpec("w", (K,), [[0, 1]]), ArgSpec("b", (I,), [[1, 0]])],
+                    dtype, [("arg", 0), ("arg", 1), ("mul",)], [("arg", 2), ("sum",), ("add",), ("tanh",)])
+
+
+def gated_gauss_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
+    """f_ij = x_i / (1 + y_j0^2) * exp(-sum_k (x_i + y_jk)^2): x is read inside the sum and by the outer function,
+    and so is y through a second occurrence that ignores k."""
+    return ExprSpec("program", (I, J), [(0, K - 1)],
+                    [ArgSpec("x", (I,), [[1, 0, 0]]), ArgSpec("y", (J, K), [[0, 1, 0], [0, 0, 1]]),
+                     ArgSpec("y_first", (J, K), [[0, 1, 0], [0, 0, 0]], same_as=1)], dtype,
+                    [("arg", 0), ("arg", 1), ("add",), ("powi", 2)],
+                    [("arg", 0), ("const", 1.0), ("arg", 2), ("powi", 2), ("add",), ("div",),
+                     ("sum",), ("neg",), ("exp",), ("mul",)])
 
 
 # Summation ranges that depend on other indices (Sec. 5.2; the form derived expressions have, Sec. 5.3)

@@ -379,6 +379,48 @@ def test_program_body_closed_form():
     assert np.allclose(oracle.backward(e, [x], df)[0], df * 2 * x / (1 + x * x), rtol=1e-13)
 
 
+# ---------------------------------------------------------------- operands of the outer function (Sec. 5.2)
+
+def test_outer_operand_closed_form():
+    """f_i = tanh(b_i + sum_k x_ik w_k): a dense layer; textbook gradients."""
+    e = wl.biased_tanh_expr(5, 4, "f64")
+    rng = np.random.default_rng(8)
+    x, w, b, df = rng.uniform(-1, 1, (5, 4)), rng.uniform(-1, 1, 4), rng.uniform(-1, 1, 5), rng.uniform(-1, 1, 5)
+    t = np.tanh(b + x @ w)
+    assert np.allclose(oracle.forward(e, [x, w, b]), t, rtol=1e-14)
+    g = df * (1 - t * t)
+    dx, dw, db = oracle.backward(e, [x, w, b], df)
+    assert np.allclose(dx, np.outer(g, w), rtol=1e-13, atol=1e-15)
+    assert np.allclose(dw, g @ x, rtol=1e-13, atol=1e-15)
+    assert np.allclose(db, g, rtol=1e-13, atol=1e-15)
+
+
+def test_outer_operand_equals_the_factor_inside_the_sum():
+    """x_i * sum_k y_ik, with x read by the outer function, is sum_k x_i y_ik."""
+    args = [wl.ArgSpec("x", (6,), [[1, 0]]), wl.ArgSpec("y", (6, 3), [[1, 0], [0, 1]])]
+    outside = wl.ExprSpec("program", (6,), [(0, 2)], args, "f64", [("arg", 1)], [("arg", 0), ("sum",), ("mul",)])
+    inside = wl.ExprSpec("mul", (6,), [(0, 2)], args, "f64")
+    w = wl.random_inputs(inside, 9)
+    xs = w.arg_list()
+    assert np.allclose(oracle.forward(outside, xs), oracle.forward(inside, xs), rtol=1e-14)
+    for g, r in zip(oracle.backward(outside, xs, w.df), oracle.backward(inside, xs, w.df)):
+        assert np.allclose(g, r, rtol=1e-13, atol=1e-15)
+
+
+def test_outer_operand_finite_differences():
+    """A tensor read inside the sum and by the outer function, one of them through a second occurrence."""
+    e = wl.gated_gauss_expr(4, 3, 3, "f64")
+    w = wl.random_inputs(e, 10, -0.8, 0.8)
+    args = [np.asarray(a, dtype=np.float64) for a in w.arg_list()]
+    grads = oracle.backward_by_tensor(e, args, w.df)
+    for p in (0, 1):
+        assert np.allclose(grads[p], _fd_grad_tensor(e, args, w.df, p), rtol=2e-7, atol=2e-8), p
+    # an operand whose index moves with the summation index has no single value per function index
+    e.outer[0] = ("arg", 1)
+    with pytest.raises(RuntimeError):
+        oracle.forward(e, args)
+
+
 # ---------------------------------------------------------------- summation ranges that depend on other indices
 
 def test_cumulative_sum_closed_form():
