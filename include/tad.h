@@ -36,7 +36,7 @@ extern "C" {
 
 #define TAD_MAX_EXT 6    /* function indices + summation indices */
 #define TAD_MAX_RANK 4   /* rank of an argument tensor */
-#define TAD_MAX_ARGS 4
+#define TAD_MAX_ARGS 6
 #define TAD_MAX_KERNEL 4 /* dimension of the kernel of an index matrix */
 #define TAD_MAX_CONSTRAINTS 8 /* extra linear conditions on the extended index */
 
@@ -73,11 +73,14 @@ typedef enum {
 /*
  * Scalar functions given as postfix (reverse Polish) programs.  The inner program combines the operand values
  * of one extended index (TAD_OP_ARG p pushes the value of operand p), the outer program maps the summed inner
- * values to f (TAD_OP_SUM pushes that sum); each must leave exactly one value on the stack.
+ * values to f (TAD_OP_SUM pushes that sum); each must leave exactly one value on the stack.  The outer program
+ * may also read operands (Sec. 5.2: the function applied to the sum takes further tensors indexed by the
+ * function index), but only those whose index matrix has zero columns for every summation index, so that they
+ * have one value per function index; such an operand's gradient gets the additional term df * d outer / d x.
  */
 typedef enum {
     TAD_OP_CONST = 0, /* push `value` */
-    TAD_OP_ARG = 1,   /* inner program only: push the value of operand `iarg` */
+    TAD_OP_ARG = 1,   /* push the value of operand `iarg` (outer program: see above) */
     TAD_OP_SUM = 2,   /* outer program only: push the summed inner value */
     TAD_OP_ADD = 3, TAD_OP_SUB = 4, TAD_OP_MUL = 5, TAD_OP_DIV = 6,   /* pop b, pop a, push a op b */
     TAD_OP_NEG = 7, TAD_OP_EXP = 8, TAD_OP_LOG = 9, TAD_OP_SIN = 10, TAD_OP_COS = 11, TAD_OP_TANH = 12,
@@ -110,7 +113,7 @@ typedef struct {
     int32_t n_constraints;         /* 0..TAD_MAX_CONSTRAINTS */
     int64_t constraint[TAD_MAX_CONSTRAINTS][TAD_MAX_EXT + 1];
     /* TAD_BODY_PROGRAM only (ignored otherwise) */
-    int32_t n_operands;            /* operands of the inner program, 1..TAD_MAX_ARGS */
+    int32_t n_operands;            /* operands of the programs, 1..TAD_MAX_ARGS */
     int32_t n_inner, n_outer;      /* program lengths, 1..TAD_MAX_PROGRAM */
     tad_op inner[TAD_MAX_PROGRAM];
     tad_op outer[TAD_MAX_PROGRAM];
@@ -293,7 +296,8 @@ int tad_plan_forward_family(const tad_plan *plan);
  * Host evaluation of the scalar functions of a TAD_BODY_PROGRAM plan in fp64, exactly the derived programs the
  * kernels interpret (for checking the symbolic differentiation without a GPU):
  *   which = -1: inner value            which = p >= 0: d inner / d operand p     (values[n_operands], host, read)
- *   which = -2: outer(sum)             which = -3: d outer / d sum               (sum is used, values may be NULL)
+ *   which = -2: outer(sum, values)     which = -3: d outer / d sum               which = -4 - p: d outer / d operand p
+ *   (the outer forms use `sum`, and `values` only if the outer program reads operands: it may be NULL otherwise)
  * Errors: EINVAL (not a program plan, bad `which`, NULL).
  */
 int tad_plan_program_eval(const tad_plan *plan, int which, const double *values, double sum, double *out);

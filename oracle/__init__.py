@@ -22,7 +22,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tad_oracle.c")
 _LIB = os.path.join(_HERE, "libtad_oracle.so")
 
-MAX_EXT, MAX_RANK, MAX_ARGS = 8, 4, 4
+MAX_EXT, MAX_RANK, MAX_ARGS = 8, 4, 6
 
 
 class _Arg(ctypes.Structure):

@@ -45,7 +45,7 @@
 
 #define ORC_MAX_EXT 8   /* function indices + summation indices */
 #define ORC_MAX_RANK 4
-#define ORC_MAX_ARGS 4
+#define ORC_MAX_ARGS 6
 #define ORC_MAX_COND 8
 
 typedef struct {

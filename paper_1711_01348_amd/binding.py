@@ -12,7 +12,7 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-MAX_EXT, MAX_RANK, MAX_ARGS, MAX_KERNEL, MAX_CONSTRAINTS = 6, 4, 4, 4, 8
+MAX_EXT, MAX_RANK, MAX_ARGS, MAX_KERNEL, MAX_CONSTRAINTS = 6, 4, 6, 4, 8
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libtad.so")

@@ -306,7 +306,8 @@ void select_families(tad_plan &plan) {
         // interpreter kernels; the backward pass keeps g = df * outer'(sum) for every function element
         plan.fwd_family = TAD_FAMILY_PROGRAM;
         for (auto &ap : plan.ap) ap.family = TAD_FAMILY_PROGRAM;
-        plan.ws_bytes = align256((size_t)plan.f_count * (plan.dtype == TAD_F64 ? 8 : 4));
+        // ... and, if the outer function reads operands, the sums themselves for the terms df * d outer / d x
+        plan.ws_bytes = align256((size_t)plan.f_count * (plan.dtype == TAD_F64 ? 8 : 4)) * (plan.prog.outer_mask ? 2 : 1);
         // a plain product of two matrices (the form the derived expressions of a matrix product have) still
         // belongs on the matrix cores
         if (!(plan.flags & TAD_PLAN_GENERIC_ONLY) && !plan.has_alias && plan.expr.n_constraints == 0 &&

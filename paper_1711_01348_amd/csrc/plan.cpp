@@ -280,6 +280,52 @@ static int derive_arg(const tad_plan &pl, int p, ArgPlan &ap) {
     return TAD_OK;
 }
 
+// Plan of an operand the outer function reads, over the function indices alone: its index ignores the
+// summation indices and the extra conditions do not apply (the outer function is evaluated once per function
+// index whatever the sum contains).  Offsets are filled in for f and for the operands the outer function reads.
+static int derive_arg_outer(const tad_plan &pl, int p, ArgPlan &ap) {
+    const tad_arg &arg = pl.args[p];
+    const int D = pl.expr.n_f, N = arg.rank;
+    IMat A(N, D);
+    for (int r = 0; r < N; ++r)
+        for (int d = 0; d < D; ++d) A(r, d) = arg.index[r][d];
+    int rc = derive_lattice(A, pl.lo, pl.hi, arg.shape, ap);
+    if (rc) return rc;
+    GatherPlan &g = ap.dev;
+    const int R = ap.smith.R, kappa = D - R;
+    for (int s = 0; s < kSlots; ++s) {
+        int64_t lin[TAD_MAX_EXT] = {0};
+        if (s < (int)pl.args.size()) {
+            if (!((pl.prog.outer_mask >> s) & 1u)) continue;
+            const tad_arg &q = pl.args[s];
+            int64_t stride = 1;
+            for (int r = q.rank - 1; r >= 0; --r) {
+                for (int d = 0; d < D; ++d) lin[d] = cadd(lin[d], cmul(stride, q.index[r][d]));
+                stride = cmul(stride, q.shape[r]);
+            }
+        } else if (s == kSlotF) {
+            int64_t stride = 1;
+            for (int d = D - 1; d >= 0; --d) {
+                lin[d] = stride;
+                stride = cmul(stride, pl.expr.f_shape[d]);
+            }
+        } else {
+            continue;
+        }
+        for (int r = 0; r < R; ++r) {
+            int64_t v = 0;
+            for (int d = 0; d < D; ++d) v = cadd(v, cmul(lin[d], ap.VR(d, r)));
+            g.offY[s][r] = v;
+        }
+        for (int m = 0; m < kappa; ++m) {
+            int64_t v = 0;
+            for (int d = 0; d < D; ++d) v = cadd(v, cmul(lin[d], ap.K(d, m)));
+            g.offZ[s][m] = v;
+        }
+    }
+    return TAD_OK;
+}
+
 int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt, uint32_t flags,
                 tad_plan **out) {
     if (!expr || !args || !out) return TAD_EINVAL;
@@ -304,7 +350,17 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
 
     pl->expr = *expr;
     if (expr->body == TAD_BODY_PROGRAM) {
-        const int rc = build_program_body(*expr, pl->prog);
+        // the outer program may read the operands whose index ignores the summation indices
+        uint32_t constant_in_k = 0, wanted = 0;
+        for (int p = 0; p < n_args; ++p) {
+            const int root = (args[p].alias > 0 && args[p].alias <= p) ? args[p].alias - 1 : p;
+            if (args[root].needs_grad) wanted |= 1u << p;
+            bool zero = args[p].rank >= 1 && args[p].rank <= TAD_MAX_RANK;
+            for (int r = 0; zero && r < args[p].rank; ++r)
+                for (int s = 0; s < expr->n_sum; ++s) zero = zero && args[p].index[r][expr->n_f + s] == 0;
+            if (zero) constant_in_k |= 1u << p;
+        }
+        const int rc = build_program_body(*expr, pl->prog, constant_in_k, wanted);
         if (rc) return rc;
     }
     pl->args.assign(args, args + n_args);
@@ -396,10 +452,15 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     }
 
     pl->ap.resize(n_args);
+    pl->ap_outer.resize(n_args);
     for (int p = 0; p < n_args; ++p) {
         if (!pl->args[p].needs_grad) continue;
         int rc = derive_arg(*pl, p, pl->ap[p]);
         if (rc) return rc;
+        if (expr->body == TAD_BODY_PROGRAM && ((pl->prog.outer_mask >> p) & 1u)) {
+            rc = derive_arg_outer(*pl, p, pl->ap_outer[p]);
+            if (rc) return rc;
+        }
     }
     select_families(*pl);
     guard.p = nullptr;
@@ -764,9 +825,16 @@ int tad_plan_count_all(const tad_plan *plan, int arg, int64_t *counts) {
 int tad_plan_program_eval(const tad_plan *plan, int which, const double *values, double sum, double *out) {
     if (!plan || !out || plan->expr.body != TAD_BODY_PROGRAM) return TAD_EINVAL;
     const ProgramBody &pb = plan->prog;
-    if (which == -2) { *out = eval_host(pb.outer, nullptr, sum); return TAD_OK; }
-    if (which == -3) { *out = eval_host(pb.douter, nullptr, sum); return TAD_OK; }
-    if (!values || which < -1 || which >= pb.n_operands) return TAD_EINVAL;
+    if (which <= -2) {
+        if (which < -3 - pb.n_operands) return TAD_EINVAL;
+        if (which <= -4 && !plan->ap[-4 - which].derived) return TAD_EINVAL;   // derivative not planned
+        const DevProg &prog = which == -2 ? pb.outer : which == -3 ? pb.douter : pb.douter_arg[-4 - which];
+        if (!values && reads_operands(prog)) return TAD_EINVAL;
+        *out = eval_host(prog, values, sum);
+        return TAD_OK;
+    }
+    if (!values || which >= pb.n_operands) return TAD_EINVAL;
+    if (which >= 0 && !plan->ap[which].derived) return TAD_EINVAL;             // derivative not planned
     *out = eval_host(which < 0 ? pb.inner : pb.dinner[which], values, 0.0);
     return TAD_OK;
 }

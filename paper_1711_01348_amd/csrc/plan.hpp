@@ -62,6 +62,9 @@ struct tad_plan {
     bool has_alias = false;
     tad::ForwardPlan fwd;
     std::vector<tad::ArgPlan> ap;
+    // program bodies whose outer function reads operands: plan of such an operand over the function indices
+    // alone (its index ignores the summation indices), for the gradient term df * d outer / d x
+    std::vector<tad::ArgPlan> ap_outer;
     int fwd_family = TAD_FAMILY_GENERIC;
     tad::FastParams fast;
     tad::ProgramBody prog;                     // TAD_BODY_PROGRAM only

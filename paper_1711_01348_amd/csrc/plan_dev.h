@@ -25,7 +25,7 @@ namespace tad {
 
 constexpr int kMaxExt = 6;
 constexpr int kMaxRank = 4;
-constexpr int kMaxArgs = 4;
+constexpr int kMaxArgs = 6;
 constexpr int kMaxKernel = 4;
 constexpr int kMaxCons = 8;
 constexpr int kMaxRows = 32;   // lower + upper rows over all levels

@@ -30,9 +30,10 @@ struct Graph {
     int constant(double c) { return add(P_CONST, -1, -1, 0, c); }
 };
 
-// Postfix program -> graph.  `outer`: TAD_OP_SUM allowed and TAD_OP_ARG not, and vice versa.
-// Returns the result node or a negative tad_status.
-inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, Graph &g) {
+// Postfix program -> graph.  Inner program: every operand may be read, the sum may not.  Outer program: the sum
+// and those operands whose bit is set in `outer_operands` (their index ignores the summation indices, so they
+// have one value per function index).  Returns the result node or a negative tad_status.
+inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, Graph &g, uint32_t outer_operands = 0) {
     if (!ops || n < 1 || n > TAD_MAX_PROGRAM) return TAD_EINVAL;
     std::vector<int> st;
     for (int i = 0; i < n; ++i) {
@@ -44,7 +45,8 @@ inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, G
             st.push_back(g.constant(o.value));
             break;
         case TAD_OP_ARG:
-            if (outer || o.iarg < 0 || o.iarg >= n_operands) return TAD_EINVAL;
+            if (o.iarg < 0 || o.iarg >= n_operands) return TAD_EINVAL;
+            if (outer && !((outer_operands >> o.iarg) & 1u)) return TAD_EINVAL;
             st.push_back(g.add(P_ARG, -1, -1, o.iarg));
             break;
         case TAD_OP_SUM:
@@ -82,13 +84,14 @@ inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, G
 
 // Reverse accumulation from `result` back to the inputs.  The derivative expressions are appended to the same
 // graph, so they share the forward nodes (Sec. 2: the derivative graph reuses the values of the function graph).
-// input_grad[p] receives the node of d result / d input p (inputs: operands 0..n_inputs-1 for an inner program,
-// the sum as input 0 for an outer program), or -1 where the derivative is identically zero.
-inline void reverse_accumulate(Graph &g, int result, int n_inputs, std::vector<int> &input_grad) {
+// input_grad[p] receives the node of d result / d operand p for p < n_operands and input_grad[n_operands] that of
+// d result / d sum, or -1 where the derivative is identically zero.
+inline void reverse_accumulate(Graph &g, int result, int n_operands, std::vector<int> &input_grad) {
     const int n_fwd = (int)g.nodes.size();
     std::vector<int> adj(n_fwd, -1);   // node holding d result / d node, -1 = zero
     auto accumulate = [&](int node, int term) { adj[node] = adj[node] < 0 ? term : g.add(P_ADD, adj[node], term); };
-    input_grad.assign(n_inputs, -1);
+    input_grad.assign(n_operands + 1, -1);
+    const int sum_slot = n_operands;
     adj[result] = g.constant(1.0);
     for (int i = n_fwd - 1; i >= 0; --i) {
         const int d = adj[i];
@@ -97,7 +100,7 @@ inline void reverse_accumulate(Graph &g, int result, int n_inputs, std::vector<i
         switch (nd.op) {
         case P_CONST: break;
         case P_ARG: input_grad[nd.k] = input_grad[nd.k] < 0 ? d : g.add(P_ADD, input_grad[nd.k], d); break;
-        case P_SUM: input_grad[0] = input_grad[0] < 0 ? d : g.add(P_ADD, input_grad[0], d); break;
+        case P_SUM: input_grad[sum_slot] = input_grad[sum_slot] < 0 ? d : g.add(P_ADD, input_grad[sum_slot], d); break;
         case P_ADD: accumulate(nd.a, d); accumulate(nd.b, d); break;
         case P_SUB: accumulate(nd.a, d); accumulate(nd.b, g.add(P_NEG, d)); break;
         case P_MUL: accumulate(nd.a, g.add(P_MUL, d, nd.b)); accumulate(nd.b, g.add(P_MUL, d, nd.a)); break;
@@ -207,6 +210,11 @@ inline bool emit_postfix(const Graph &g, const std::vector<int> &alias, int node
 }
 
 // Evaluation of a lowered program (the host twin of the kernels' interpreter), fp64.
+inline bool reads_operands(const DevProg &P) {
+    for (int i = 0; i < P.n; ++i)
+        if (P.op[i] == P_ARG) return true;
+    return false;
+}
 inline double eval_host(const DevProg &P, const double *v, double s) {
     if (P.result < 0) return 0.0;
     double t[kMaxProgOps] = {0};
@@ -240,10 +248,14 @@ struct ProgramBody {
     DevProg inner, outer;            // values
     DevProg dinner[TAD_MAX_ARGS];    // d inner / d operand p
     DevProg douter;                  // d outer / d sum
+    DevProg douter_arg[TAD_MAX_ARGS];   // d outer / d operand p (identically zero unless the outer program reads p)
+    uint32_t outer_mask = 0;         // operands the outer program reads
 };
 
-// Parse, differentiate and lower both programs of an expression.  Returns a tad_status.
-inline int build_program_body(const tad_expr &e, ProgramBody &pb) {
+// Parse, differentiate and lower both programs of an expression.  `outer_operands`: operands the outer program
+// may read; `wanted`: operands whose gradient will be asked for (the derivatives with respect to the others are
+// not lowered, so their length does not matter).  Returns a tad_status.
+inline int build_program_body(const tad_expr &e, ProgramBody &pb, uint32_t outer_operands, uint32_t wanted) {
     if (e.n_operands < 1 || e.n_operands > TAD_MAX_ARGS) return TAD_EINVAL;
     pb.n_operands = e.n_operands;
     Graph gi;
@@ -253,13 +265,18 @@ inline int build_program_body(const tad_expr &e, ProgramBody &pb) {
     std::vector<int> grads;
     reverse_accumulate(gi, ri, e.n_operands, grads);
     for (int p = 0; p < e.n_operands; ++p)
-        if (!lower(gi, grads[p], pb.dinner[p])) return TAD_EUNSUPPORTED;
+        if (!lower(gi, ((wanted >> p) & 1u) ? grads[p] : -1, pb.dinner[p])) return TAD_EUNSUPPORTED;
     Graph go;
-    const int ro = parse_postfix(e.outer, e.n_outer, true, 0, go);
+    const int ro = parse_postfix(e.outer, e.n_outer, true, e.n_operands, go, outer_operands);
     if (ro < 0) return ro;
     if (!lower(go, ro, pb.outer)) return TAD_EUNSUPPORTED;
-    reverse_accumulate(go, ro, 1, grads);
-    if (!lower(go, grads[0], pb.douter)) return TAD_EUNSUPPORTED;
+    pb.outer_mask = 0;
+    for (int i = 0; i < e.n_outer; ++i)
+        if (e.outer[i].op == TAD_OP_ARG) pb.outer_mask |= 1u << e.outer[i].iarg;
+    reverse_accumulate(go, ro, e.n_operands, grads);
+    if (!lower(go, wanted ? grads[e.n_operands] : -1, pb.douter)) return TAD_EUNSUPPORTED;
+    for (int p = 0; p < e.n_operands; ++p)
+        if (!lower(go, ((wanted >> p) & 1u) ? grads[p] : -1, pb.douter_arg[p])) return TAD_EUNSUPPORTED;
     return TAD_OK;
 }
 

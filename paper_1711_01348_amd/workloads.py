@@ -196,6 +196,22 @@ def biased_tanh_expr(I: int, K: int, dtype: str) -> ExprSpec:
                     dtype, [("arg", 0), ("arg", 1), ("mul",)], [("arg", 2), ("sum",), ("add",), ("tanh",)])
 
 
+def dense_layer_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
+    """f_ij = tanh(b_j + sum_k x_ik w_kj): a dense layer; the gradient of the bias sums over the batch index i."""
+    return ExprSpec("program", (I, J), [(0, K - 1)],
+                    [ArgSpec("x", (I, K), [[1, 0, 0], [0, 0, 1]]), ArgSpec("w", (K, J), [[0, 0, 1], [0, 1, 0]]),
+                     ArgSpec("b", (J,), [[0, 1, 0]])], dtype,
+                    [("arg", 0), ("arg", 1), ("mul",)], [("arg", 2), ("sum",), ("add",), ("tanh",)])
+
+
+def biased_causal_conv_expr(N: int, K: int, dtype: str) -> ExprSpec:
+    """f_i = b_i * exp(-(sum_{k <= min(i, K-1)} x_{i-k} w_k)^2): a range that depends on i and an outer operand."""
+    return ExprSpec("program", (N,), [(0, K - 1)],
+                    [ArgSpec("x", (N,), [[1, -1]]), ArgSpec("w", (K,), [[0, 1]]), ArgSpec("b", (N + 2,), [[1, 0]])], dtype,
+                    [("arg", 0), ("arg", 1), ("mul",)], [("arg", 2), ("sum",), ("powi", 2), ("neg",), ("exp",), ("mul",)],
+                    constraints=[([1, -1], 0)])
+
+
 def gated_gauss_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
     """f_ij = x_i / (1 + y_j0^2) * exp(-sum_k (x_i + y_jk)^2): x is read inside the sum and by the outer function,
     and so is y through a second occurrence that ignores k."""

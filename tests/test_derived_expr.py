@@ -135,7 +135,7 @@ CASES = [
 ]
 
 
-def _check_against_original(e, depth):
+def _check_against_original(e, depth, refused=None):
     """Every derived expression of `e` has exactly the terms of the brute-force scan, its values are the
     oracle's gradient, and (depth > 0) the same holds for the expressions derived from it."""
     plan = B.Plan(e)
@@ -143,7 +143,12 @@ def _check_against_original(e, depth):
     tensors = w.arg_list()
     want = oracle.backward(e, tensors, w.df)
     for root, occ, slot in _slots(e):
-        spec, operands = plan.derived_expr(root, occ)
+        try:
+            spec, operands = plan.derived_expr(root, occ)
+        except B.TadError as err:
+            assert err.status == -5 and refused is not None
+            refused.append(slot)
+            continue
         assert operands[0] == -1 and spec.args[0].shape == tuple(e.f_shape) and spec.f_shape == tuple(e.args[slot].shape)
         assert spec.outer == [("sum",)] and spec.inner[0] == ("arg", 0)
         for beta in itertools.product(*[range(n) for n in spec.f_shape]):
@@ -155,29 +160,25 @@ def _check_against_original(e, depth):
             if a.same_as is not None:
                 r0 = lambda p: p if e.args[p].same_as is None else e.args[p].same_as
                 assert r0(operands[q]) == r0(operands[a.same_as]) and spec.args[a.same_as].same_as is None
-        B.Plan(spec)    # it is a valid expression again
+        # it is a valid expression again; if its own derivatives outgrow the device form, at least as a forward pass
+        if _status(lambda: B.Plan(spec)) != 0:
+            assert _status(lambda: B.Plan(spec)) == -5 and depth == 0
+            B.Plan(spec, needs_grad=[False] * len(spec.args))
         if depth > 0:
-            _check_against_original(spec, depth - 1)
+            below = []
+            _check_against_original(spec, depth - 1, below)
+            if refused is not None:
+                refused.append((slot, below))
 
 
 @pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
 def test_derived_expression_is_the_gradient(name, make):
-    _check_against_original(make(), 1 if name not in ("plane", "nonlinear") else 0)
-
-
-def test_second_level_of_a_plane_and_of_a_nonlinear_body():
-    spec, _ = B.Plan(CASES[5][1]()).derived_expr(0)
-    assert len(spec.sums) == 2 and len(spec.constraints) == 2        # x_{a+2b+3c}: two free coordinates, one clipped row
-    _check_against_original(spec, 0)
-    # with three operands in the partial derivative, the next level has room for the derivative with respect
-    # to df only: the others would need df, the first level's df and all three tensors
-    e = CASES[13][1]()
-    for p in range(3):
-        spec, _ = B.Plan(e).derived_expr(p)
-        plan = B.Plan(spec)
-        again, operands = plan.derived_expr(0)
-        assert operands == [-1, 1, 2, 3]
-        assert [_status(lambda q=q: plan.derived_expr(q)) for q in (1, 2, 3)] == [-5, -5, -5]
+    refused = []
+    _check_against_original(make(), 1, refused)
+    # only the body with divisions and square roots outgrows the program length, in two second derivatives
+    # (with respect to y twice and to z twice); everything else is derived at both levels
+    want = {"nonlinear": [(0, []), (1, [2]), (2, [3])]}
+    assert refused == want.get(name, [(slot, []) for _, _, slot in _slots(make())])
 
 
 def test_scalar_part_is_df_times_the_symbolic_partial_derivative():

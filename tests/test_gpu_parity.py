@@ -324,6 +324,15 @@ PROGRAM_CASES = [
     ("softplus_f64", lambda: wl.random_inputs(wl.softplus_ratio_expr(9, 13, 6, "f64"), 8)),
     ("softplus_f32", lambda: wl.random_inputs(wl.softplus_ratio_expr(33, 21, 17, "f32"), 9)),
     ("alias_f64", lambda: wl.random_inputs(_alias_program(), 10)),
+    # the outer function reads operands (Sec. 5.2): bias of a dense layer (few bias elements, long sums over the
+    # batch: cooperative gather), an operand read inside the sum and outside it, one tensor read both ways
+    # through two occurrences, a range that depends on the function index
+    ("biased_tanh_f64", lambda: wl.random_inputs(wl.biased_tanh_expr(301, 7, "f64"), 11)),
+    ("dense_layer_f32", lambda: wl.random_inputs(wl.dense_layer_expr(2500, 6, 9, "f32"), 12, -0.7, 0.7)),
+    ("dense_layer_f64", lambda: wl.random_inputs(wl.dense_layer_expr(70, 33, 5, "f64"), 13)),
+    ("gated_gauss_f64", lambda: wl.random_inputs(wl.gated_gauss_expr(37, 29, 4, "f64"), 14, -0.8, 0.8)),
+    ("gated_gauss_f32", lambda: wl.random_inputs(wl.gated_gauss_expr(130, 70, 3, "f32"), 15, -0.8, 0.8)),
+    ("biased_causal_conv_f64", lambda: wl.random_inputs(wl.biased_causal_conv_expr(400, 9, "f64"), 16)),
 ]
 
 

@@ -474,10 +474,15 @@ PROGRAMS = [
     # an operand the function does not depend on, and a constant function of the sum
     ([("arg", 0), ("const", 3.0), ("mul",)], [("const", 2.5)], 2),
     ([("arg", 1), ("powi", 1)], [("sum",), ("powi", 1)], 2),
+    # the outer function reads operands (no summation index here, so every operand has one value per f index):
+    # v2 + tanh(s) * v0 / (1 + v1^2) with s = v0 v1 + sin(v2)
+    ([("arg", 0), ("arg", 1), ("mul",), ("arg", 2), ("sin",), ("add",)],
+     [("arg", 2), ("sum",), ("tanh",), ("arg", 0), ("mul",), ("const", 1.0), ("arg", 1), ("powi", 2), ("add",),
+      ("div",), ("add",)], 3),
 ]
 
 
-@pytest.mark.parametrize("inner,outer,nop", PROGRAMS, ids=["worked", "tanh_dot", "softplus", "mixed", "unused", "powi1"])
+@pytest.mark.parametrize("inner,outer,nop", PROGRAMS, ids=["worked", "tanh_dot", "softplus", "mixed", "unused", "powi1", "outer_operands"])
 def test_symbolic_derivatives_match_forward_mode_oracle(inner, outer, nop):
     """The programs derived by reverse accumulation, evaluated on the host, against the oracle's dual numbers."""
     e = _scalar_expr(inner, outer, nop)
@@ -490,10 +495,12 @@ def test_symbolic_derivatives_match_forward_mode_oracle(inner, outer, nop):
         args = [np.array([x]) for x in v]
         total = plan.program_eval(-1, v)
         f_ref = oracle.forward(e, args)[0]
-        assert abs(plan.program_eval(-2, None, total) - f_ref) <= 1e-13 * max(1.0, abs(f_ref))
+        reads = any(t[0] == "arg" for t in outer)
+        vo = v if reads else None
+        assert abs(plan.program_eval(-2, vo, total) - f_ref) <= 1e-13 * max(1.0, abs(f_ref))
         g_ref = oracle.backward(e, args, np.array([1.0]))
         for p in range(nop):
-            got = plan.program_eval(-3, None, total) * plan.program_eval(p, v)
+            got = plan.program_eval(-3, vo, total) * plan.program_eval(p, v) + plan.program_eval(-4 - p, vo, total)
             assert abs(got - g_ref[p][0]) <= 1e-12 * max(1.0, abs(g_ref[p][0])), (p, got, g_ref[p][0])
 
 
@@ -503,7 +510,13 @@ def test_program_rules():
     mk(ok_in, ok_out)
     assert _status(lambda: mk([("arg", 1)], ok_out)) == -1                      # operand index out of range
     assert _status(lambda: mk([("sum",)], ok_out)) == -1                        # the sum is not an inner input
-    assert _status(lambda: mk(ok_in, [("arg", 0)])) == -1                       # operands are not outer inputs
+    mk(ok_in, [("arg", 0)])                                   # the outer function may read an operand that has one value per f index
+    moving = wl.ExprSpec("program", (3,), [(0, 2)], [wl.ArgSpec("x", (5,), [[1, 1]]), wl.ArgSpec("b", (3,), [[1, 0]])],
+                         "f64", [("arg", 0)], [("sum",), ("arg", 0), ("mul",)])
+    assert _status(lambda: B.Plan(moving)) == -1                                # ... not one that moves with the summation index
+    moving.outer = [("sum",), ("arg", 1), ("mul",)]
+    B.Plan(moving)
+    assert _status(lambda: mk(ok_in, [("arg", 1)])) == -1
     assert _status(lambda: mk([("arg", 0), ("add",)], ok_out)) == -1            # stack underflow
     assert _status(lambda: mk([("arg", 0), ("arg", 0)], ok_out)) == -1          # two values left
     assert _status(lambda: mk([("arg", 0), ("powi", 0)], ok_out)) == -1
@@ -516,6 +529,13 @@ def test_program_rules():
     plan = B.Plan(wl.as_program(wl.config1().expr))
     assert plan.forward_family == "program" and plan.workspace_bytes >= 8 * 6 * 8
     assert _status(lambda: B.Plan(wl.config1().expr).program_eval(-1, np.zeros(4))) == -1   # not a program plan
+    plan = B.Plan(wl.biased_tanh_expr(3, 2, "f64"), needs_grad=[True, False, True])
+    assert _status(lambda: plan.program_eval(-2, None, 0.3)) == -1             # the outer function needs the operand values
+    assert _status(lambda: plan.program_eval(1, np.zeros(3))) == -1            # derivative not planned
+    assert _status(lambda: plan.program_eval(-4 - 1, np.zeros(3), 0.3)) == -1
+    assert plan.program_eval(-4 - 2, np.zeros(3), 0.0) == 1.0                  # d tanh(b + s) / d b at 0
+    assert _status(lambda: plan.program_eval(-4 - 3, np.zeros(3), 0.3)) == -1
+    assert plan.workspace_bytes >= 2 * 3 * 8                                    # g and the sums
 
 
 # ---- summation ranges that depend on other indices: extra linear conditions in the constraint system --------
