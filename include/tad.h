@@ -157,6 +157,8 @@ typedef struct {
     int32_t n_upper[TAD_MAX_KERNEL];
     int32_t n_feasibility;
     int32_t family;                                 /* kernel family chosen for this gradient (tad_family) */
+    int32_t in_outer;                               /* 1 if the outer function reads this operand: its gradient has
+                                                       the additional term df * d outer / d x */
 } tad_plan_info;
 
 typedef enum {
@@ -251,32 +253,52 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
                       void *stream);
 
 /*
- * The gradient of one occurrence of a tensor, written as an element-wise defined tensor of its own (Sec. 5.3:
- * a derived expression has the form of the input expressions again, with summation ranges that depend on the
- * other indices, so it can be evaluated, and differentiated once more, by the same machinery):
+ * The gradient of one occurrence of a tensor, written as element-wise defined tensors again (Sec. 5.3: a
+ * derived expression has the form of the input expressions, with summation ranges that depend on the other
+ * indices, so it can be evaluated, and differentiated once more, by the same machinery).  With
+ * s_alpha = sum_k inner(...) and f_alpha = outer(s_alpha, operands at alpha) the gradient is
  *
- *     dx_beta = sum_z [conditions] df_{alpha(beta, z)} * (d inner / d x)(operand values at [alpha k](beta, z)),
- *     [alpha k] = I beta + K z.
+ *     dx_beta = sum_z [conditions] g_{alpha(beta, z)} * (d inner / d x)(operand values at [alpha k](beta, z))   (part 0)
+ *             + sum_z' [conditions] h_{alpha(beta, z')}                                                         (part 1)
+ *     g_alpha = df_alpha * (d outer / d s)(s_alpha, ...),   h_alpha = df_alpha * (d outer / d x)(s_alpha, ...),
  *
- * Function indices of the new expression: beta (shape of the tensor); summation indices: the kernel coordinates
- * z with constant limits (their extremes over the box); conditions: the box rows of the original extended index
- * that those limits do not already imply, the original extra conditions, and the cokernel rows C beta = 0 as
- * pairs of inequalities.  Operand 0 of the new expression is df (shape of f); the others are those operands of
- * the original expression that the partial derivative depends on, in their original order (aliases stay
- * aliases of one tensor).  The body is a program: inner = operand 0 times the symbolic partial derivative,
- * outer = identity.
+ * part 1 only for an operand the outer function reads.  g and h contain the sum s_alpha, a second sum nested in
+ * the first: they are expressions of their own over the function indices of the original one
+ * (tad_plan_seed_expr), and the gradient is a small graph of expressions: evaluate the seed, then hand its
+ * result to the derived expression as operand 0.  When the outer function is the identity g = df and no seed is
+ * needed; when there is neither a summation nor a condition, outer(inner(x)) is treated as one function and
+ * again no seed is needed.
+ *
+ * tad_plan_derived_expr, part 0.  Function indices of the new expression: beta (shape of the tensor); summation
+ * indices: the kernel coordinates z with constant limits (their extremes over the box); conditions: the box
+ * rows of the original extended index [alpha k] = I beta + K z that those limits do not already imply, the
+ * original extra conditions, and the cokernel rows C beta = 0 as pairs of inequalities.  Operand 0 is df or g
+ * (shape of f); the others are those operands of the original expression that the partial derivative depends
+ * on, in their original order (aliases stay aliases of one tensor).  The body is a program: inner = operand 0
+ * times the symbolic partial derivative, outer = identity.
+ * Part 1: the same construction from the operand's index map over the function indices alone; operand 0 is h,
+ * there is no other operand, inner = operand 0.
  *   plan, arg, occ        as for tad_plan_query
+ *   part                  0 or 1
  *   expr_out              host, written
  *   args_out              host, room for TAD_MAX_ARGS entries, written (needs_grad = 1 everywhere)
  *   operand_out           host, room for TAD_MAX_ARGS ints (may be NULL): operand_out[q] = operand of the original
- *                         expression that new operand q is, -1 for df
+ *                         expression that new operand q is; for operand 0: -1 = df itself, -2 = g (seed -1),
+ *                         -3 - p = h of operand p (seed p)
  *   n_args_out            number of operands of the new expression
- * Errors: EINVAL (as tad_plan_query); EUNSUPPORTED if the outer function is not the identity (the gradient then
- * contains a second, nested sum), if a Smith divisor exceeds 1 (a divisibility mask is not a linear condition),
- * or if the result exceeds the limits of an expression (indices, operands, conditions, program length).
+ * The outputs are written only on success.
+ * Errors: EINVAL (as tad_plan_query; part 1 for an operand the outer function does not read); EUNSUPPORTED if a
+ * Smith divisor exceeds 1 (a divisibility mask is not a linear condition), or if the result exceeds the limits
+ * of an expression (indices, operands, conditions, program length).
+ *
+ * tad_plan_seed_expr.  which = -1: g;  which = p: h of operand p (EINVAL unless the outer function reads p).
+ * Same function indices, summation ranges and conditions as the original expression; operand 0 is df, operand
+ * 1 + q is original operand q; inner = the original inner function, outer = operand 0 times the symbolic
+ * derivative of the outer function.  EUNSUPPORTED if the original has TAD_MAX_ARGS operands already.
  */
-int tad_plan_derived_expr(const tad_plan *plan, int arg, int occ, tad_expr *expr_out, tad_arg *args_out,
+int tad_plan_derived_expr(const tad_plan *plan, int arg, int occ, int part, tad_expr *expr_out, tad_arg *args_out,
                           int *operand_out, int *n_args_out);
+int tad_plan_seed_expr(const tad_plan *plan, int which, tad_expr *expr_out, tad_arg *args_out, int *n_args_out);
 
 /* Name of the device kernel family used for the forward pass (tad_family). */
 int tad_plan_forward_family(const tad_plan *plan);

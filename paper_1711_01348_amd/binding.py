@@ -31,7 +31,7 @@ ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
            "tad_plan_bound_row", "tad_plan_enumerate", "tad_plan_count_all", "tad_eval_forward",
            "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval",
-           "tad_plan_derived_expr"]
+           "tad_plan_derived_expr", "tad_plan_seed_expr"]
 
 
 class TadOp(ctypes.Structure):
@@ -61,7 +61,7 @@ class TadPlanInfo(ctypes.Structure):
                 ("K", (ctypes.c_int64 * MAX_KERNEL) * MAX_EXT),
                 ("C", (ctypes.c_int64 * MAX_RANK) * MAX_RANK),
                 ("n_lower", ctypes.c_int32 * MAX_KERNEL), ("n_upper", ctypes.c_int32 * MAX_KERNEL),
-                ("n_feasibility", ctypes.c_int32), ("family", ctypes.c_int32)]
+                ("n_feasibility", ctypes.c_int32), ("family", ctypes.c_int32), ("in_outer", ctypes.c_int32)]
 
 
 class TadError(RuntimeError):
@@ -96,9 +96,11 @@ def _load():
                                       ctypes.c_size_t, vp]
     lib.tad_plan_forward_family.argtypes = [vp]
     lib.tad_plan_program_eval.argtypes = [vp, ctypes.c_int, vp, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
-    lib.tad_plan_derived_expr.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(TadExpr),
+    lib.tad_plan_derived_expr.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(TadExpr),
                                           ctypes.POINTER(TadArg), ctypes.POINTER(ctypes.c_int),
                                           ctypes.POINTER(ctypes.c_int)]
+    lib.tad_plan_seed_expr.argtypes = [vp, ctypes.c_int, ctypes.POINTER(TadExpr), ctypes.POINTER(TadArg),
+                                       ctypes.POINTER(ctypes.c_int)]
     lib.tad_strerror.argtypes = [ctypes.c_int]
     lib.tad_strerror.restype = ctypes.c_char_p
     return lib
@@ -208,7 +210,7 @@ class Plan:
                     C=mat(info.C, info.n_cokernel, N),
                     n_lower=[info.n_lower[k] for k in range(kap)],
                     n_upper=[info.n_upper[k] for k in range(kap)],
-                    n_feasibility=info.n_feasibility, family=FAMILY[info.family])
+                    n_feasibility=info.n_feasibility, family=FAMILY[info.family], in_outer=bool(info.in_outer))
 
     def bound_rows(self, arg: int, kind: int, level: int = 0) -> List[dict]:
         q = self.query(arg)
@@ -250,39 +252,49 @@ class Plan:
                                          ctypes.byref(out)), "tad_plan_program_eval")
         return out.value
 
-    def derived_expr(self, arg: int, occ: int = 0):
-        """The gradient of occurrence `occ` of operand `arg` as an expression of its own: (expression, operands)
-        with operands[q] = index of the original operand that new operand q is, -1 for df (always operand 0).
-        The expression can be planned and evaluated like any other."""
+    def _unpack_expr(self, e, a, n, names):
         from .workloads import ArgSpec, ExprSpec
-        e, a = TadExpr(), (TadArg * MAX_ARGS)()
-        src, n = (ctypes.c_int * MAX_ARGS)(), ctypes.c_int(0)
-        _check(lib.tad_plan_derived_expr(self._h, arg, occ, ctypes.byref(e), a, src, ctypes.byref(n)),
-               "tad_plan_derived_expr")
         n_ext = e.n_f + e.n_sum
-        names = {v: k for k, v in OPCODE.items()}
+        opname = {v: k for k, v in OPCODE.items()}
 
         def program(ops, count):
             out = []
             for i in range(count):
-                name = names[ops[i].op]
+                name = opname[ops[i].op]
                 out.append((name, ops[i].iarg) if name in ("arg", "powi") else
                            (name, ops[i].value) if name == "const" else (name,))
             return out
 
-        operands = [src[q] for q in range(n.value)]
-        args = []
-        for q in range(n.value):
-            name = "df" if operands[q] < 0 else self.expr.args[operands[q]].name + ("" if a[q].alias == 0 else f"_{q}")
-            args.append(ArgSpec(name, tuple(a[q].shape[r] for r in range(a[q].rank)),
-                                [[a[q].index[r][d] for d in range(n_ext)] for r in range(a[q].rank)],
-                                None if a[q].alias == 0 else a[q].alias - 1))
-        spec = ExprSpec("program", tuple(e.f_shape[d] for d in range(e.n_f)),
+        args = [ArgSpec(names[q], tuple(a[q].shape[r] for r in range(a[q].rank)),
+                        [[a[q].index[r][d] for d in range(n_ext)] for r in range(a[q].rank)],
+                        None if a[q].alias == 0 else a[q].alias - 1) for q in range(n)]
+        return ExprSpec("program", tuple(e.f_shape[d] for d in range(e.n_f)),
                         [(e.sum_lo[s], e.sum_hi[s]) for s in range(e.n_sum)], args, self.expr.dtype,
                         inner=program(e.inner, e.n_inner), outer=program(e.outer, e.n_outer),
                         constraints=[([e.constraint[j][d] for d in range(n_ext)], e.constraint[j][n_ext])
                                      for j in range(e.n_constraints)])
-        return spec, operands
+
+    def derived_expr(self, arg: int, occ: int = 0, part: int = 0):
+        """The gradient of occurrence `occ` of operand `arg` as an expression of its own: (expression, operands)
+        with operands[q] = index of the original operand that new operand q is; operands[0] is -1 for df, -2 for
+        the seed g = df * d outer / d sum (``seed_expr(-1)``), -3 - p for the seed of operand p (``seed_expr(p)``).
+        part 0: the terms through the sum; part 1: the term of an operand the outer function reads.
+        The expression can be planned and evaluated like any other."""
+        e, a = TadExpr(), (TadArg * MAX_ARGS)()
+        src, n = (ctypes.c_int * MAX_ARGS)(), ctypes.c_int(0)
+        _check(lib.tad_plan_derived_expr(self._h, arg, occ, part, ctypes.byref(e), a, src, ctypes.byref(n)),
+               "tad_plan_derived_expr")
+        operands = [src[q] for q in range(n.value)]
+        names = [{-1: "df", -2: "g"}.get(operands[0], "h")]
+        names += [self.expr.args[operands[q]].name + ("" if a[q].alias == 0 else f"_{q}") for q in range(1, n.value)]
+        return self._unpack_expr(e, a, n.value, names), operands
+
+    def seed_expr(self, which: int = -1):
+        """g = df * d outer / d sum (which = -1) or h = df * d outer / d operand `which`, as an expression over the
+        function indices of this one; its operands are df followed by the operands of this expression."""
+        e, a, n = TadExpr(), (TadArg * MAX_ARGS)(), ctypes.c_int(0)
+        _check(lib.tad_plan_seed_expr(self._h, which, ctypes.byref(e), a, ctypes.byref(n)), "tad_plan_seed_expr")
+        return self._unpack_expr(e, a, n.value, ["df"] + [x.name for x in self.expr.args])
 
     def count_all(self, arg: int) -> np.ndarray:
         counts = np.empty(tuple(self.expr.args[arg].shape), dtype=np.int64)

@@ -133,22 +133,33 @@ int main() {
             tad_expr de;
             tad_arg da[TAD_MAX_ARGS];
             int src[TAD_MAX_ARGS], n = 0;
-            if (tad_plan_derived_expr(pl, p, 0, &de, da, src, &n) || n != 2 || src[0] != -1 || src[1] != 1 - p) return 22;
-            if (tad_plan_derived_expr(pl, p, 1, &de, da, src, &n) != TAD_EINVAL) return 23;
+            if (tad_plan_derived_expr(pl, p, 0, 0, &de, da, src, &n) || n != 2 || src[0] != -1 || src[1] != 1 - p) return 22;
+            if (tad_plan_derived_expr(pl, p, 1, 0, &de, da, src, &n) != TAD_EINVAL) return 23;
+            if (tad_plan_derived_expr(pl, p, 0, 1, &de, da, src, &n) != TAD_EINVAL) return 28;   // no outer operand
             tad_plan *dp = nullptr;
             if (tad_plan_derive(&de, da, n, TAD_F64, 0, &dp)) return 24;
             for (int q = 0; q < n; ++q) {
                 tad_expr de2;
                 tad_arg da2[TAD_MAX_ARGS];
                 int n2 = 0;
-                if (tad_plan_derived_expr(dp, q, 0, &de2, da2, nullptr, &n2) || n2 != 2) return 25;
+                if (tad_plan_derived_expr(dp, q, 0, 0, &de2, da2, nullptr, &n2) || n2 != 2) return 25;
                 tad_plan *dp2 = nullptr;
                 if (tad_plan_derive(&de2, da2, n2, TAD_F64, 0, &dp2)) return 26;
                 tad_plan_free(dp2);
             }
             tad_plan_free(dp);
         }
-        if (tad_plan_derived_expr(pl, 0, 0, nullptr, nullptr, nullptr, nullptr) != TAD_EINVAL) return 27;
+        if (tad_plan_derived_expr(pl, 0, 0, 0, nullptr, nullptr, nullptr, nullptr) != TAD_EINVAL) return 27;
+        {
+            tad_expr se;
+            tad_arg sa[TAD_MAX_ARGS];
+            int n = 0;
+            if (tad_plan_seed_expr(pl, -1, &se, sa, &n) || n != 3) return 29;
+            tad_plan *sp = nullptr;
+            if (tad_plan_derive(&se, sa, n, TAD_F64, 0, &sp)) return 30;
+            tad_plan_free(sp);
+            if (tad_plan_seed_expr(pl, 0, &se, sa, &n) != TAD_EINVAL) return 31;
+        }
         tad_plan_free(pl);
         e.n_constraints = 0;   // without the condition the index i - k can be negative
         if (tad_plan_derive(&e, a, 2, TAD_F64, 0, &pl) != TAD_ESHAPE) return 21;

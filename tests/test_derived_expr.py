@@ -76,14 +76,18 @@ def _run_postfix(prog, values, total=0.0):
 
 
 def _evaluate(spec, tensors):
-    """f of a program expression by its definition."""
+    """f of a program expression by its definition (the outer function may read operands at the function index)."""
     f = np.zeros(spec.f_shape)
+    nf = len(spec.f_shape)
+    reads = {t[1] for t in spec.outer if t[0] == "arg"}
     for beta in itertools.product(*[range(n) for n in spec.f_shape]):
         s = 0.0
         for ext in _ext_points(spec, beta):
             vals = [t[tuple(sum(a * v for a, v in zip(row, ext)) for row in arg.A)] for t, arg in zip(tensors, spec.args)]
             s += _run_postfix(spec.inner, vals)
-        f[beta] = _run_postfix(spec.outer, [], s)
+        at = [tensors[p][tuple(sum(a * v for a, v in zip(row[:nf], beta)) for row in arg.A)] if p in reads else None
+              for p, arg in enumerate(spec.args)]
+        f[beta] = _run_postfix(spec.outer, at, s)
     return f
 
 
@@ -132,16 +136,39 @@ CASES = [
     ("autocorrelation", lambda: wl.autocorrelation_expr(6, 3, "f64")),
     ("nonlinear", lambda: _nonlinear(3, 4, 2)),
     ("triple", lambda: _triple(6)),
+    # outer functions other than the identity: the gradient is a seed expression followed by a derived one
+    ("worked", lambda: wl.worked_expr(3, 4, 2, "f64")),
+    ("cumsum_exp", lambda: wl.cumulative_sum_expr(5, "f64")),
+    ("tanh_stencil", lambda: wl.strided_tanh_expr(1, 3, 3, 2, 2, 1, "f64")),
+    ("softplus", lambda: wl.softplus_ratio_expr(3, 2, 2, "f64")),
+    # the outer function reads operands: the gradient of such an operand has a second part
+    ("biased_tanh", lambda: wl.biased_tanh_expr(4, 3, "f64")),
+    ("gated_gauss", lambda: wl.gated_gauss_expr(3, 2, 2, "f64")),
+    ("biased_causal_conv", lambda: wl.biased_causal_conv_expr(6, 3, "f64")),
 ]
 
 
 def _check_against_original(e, depth, refused=None):
-    """Every derived expression of `e` has exactly the terms of the brute-force scan, its values are the
-    oracle's gradient, and (depth > 0) the same holds for the expressions derived from it."""
+    """Every derived expression of `e` has exactly the terms of the brute-force scan, its values (with the seed
+    expressions evaluated first where the outer function is not the identity) add up to the oracle's gradient,
+    and (depth > 0) the same holds for the expressions derived from those.  Expressions the limits refuse at the
+    lower level are recorded in `refused`."""
     plan = B.Plan(e)
     w = wl.random_inputs(e, 17 + depth, -0.9, 0.9)
     tensors = w.arg_list()
     want = oracle.backward(e, tensors, w.df)
+    fused = not e.sums and not e.constraints
+    nf = len(e.f_shape)
+    seeds = {}
+
+    def seed(which):
+        if which not in seeds:
+            sspec = plan.seed_expr(which)
+            assert [a.name for a in sspec.args] == ["df"] + [a.name for a in e.args]
+            seeds[which] = (sspec, _evaluate(sspec, [w.df] + tensors))
+        return seeds[which][1]
+
+    below = []
     for root, occ, slot in _slots(e):
         try:
             spec, operands = plan.derived_expr(root, occ)
@@ -149,36 +176,75 @@ def _check_against_original(e, depth, refused=None):
             assert err.status == -5 and refused is not None
             refused.append(slot)
             continue
-        assert operands[0] == -1 and spec.args[0].shape == tuple(e.f_shape) and spec.f_shape == tuple(e.args[slot].shape)
+        assert spec.args[0].shape == tuple(e.f_shape) and spec.f_shape == tuple(e.args[slot].shape)
         assert spec.outer == [("sum",)] and spec.inner[0] == ("arg", 0)
+        identity = e.body == "mul" or (e.body == "program" and e.outer == [("sum",)])
+        assert operands[0] == (-1 if identity or fused else -2)
         for beta in itertools.product(*[range(n) for n in spec.f_shape]):
             assert _terms_of(spec, beta) == _terms_brute(e, slot, beta, operands), (slot, beta)
-        got = _evaluate(spec, [w.df] + [tensors[q] for q in operands[1:]])
+        try:
+            first = w.df if operands[0] == -1 else seed(-1)
+            second = seed(slot) if plan.query(root, occ)["in_outer"] and not fused else None
+        except B.TadError as err:
+            assert err.status == -5 and refused is not None
+            refused.append(("no seed", slot))
+            continue
+        got = _evaluate(spec, [first] + [tensors[q] for q in operands[1:]])
+        parts = [spec]
+        if plan.query(root, occ)["in_outer"] and not fused:
+            spec1, operands1 = plan.derived_expr(root, occ, 1)
+            assert operands1 == [-3 - slot] and spec1.inner == [("arg", 0)] and spec1.outer == [("sum",)]
+            for beta in itertools.product(*[range(n) for n in spec1.f_shape]):
+                brute = sorted((alpha,) for alpha in itertools.product(*[range(n) for n in e.f_shape])
+                               if all(sum(a * v for a, v in zip(row[:nf], alpha)) == b
+                                      for row, b in zip(e.args[slot].A, beta)))
+                assert _terms_of(spec1, beta) == brute, (slot, beta)
+            got = got + _evaluate(spec1, [second])
+            parts.append(spec1)
+        else:
+            assert _status(lambda: plan.derived_expr(root, occ, 1)) == -1
         np.testing.assert_allclose(got, want[slot], rtol=1e-12, atol=1e-13)
         # occurrences of one tensor among the kept operands stay one tensor
         for q, a in enumerate(spec.args):
             if a.same_as is not None:
                 r0 = lambda p: p if e.args[p].same_as is None else e.args[p].same_as
                 assert r0(operands[q]) == r0(operands[a.same_as]) and spec.args[a.same_as].same_as is None
-        # it is a valid expression again; if its own derivatives outgrow the device form, at least as a forward pass
-        if _status(lambda: B.Plan(spec)) != 0:
-            assert _status(lambda: B.Plan(spec)) == -5 and depth == 0
-            B.Plan(spec, needs_grad=[False] * len(spec.args))
-        if depth > 0:
-            below = []
-            _check_against_original(spec, depth - 1, below)
-            if refused is not None:
-                refused.append((slot, below))
+        for part in parts:
+            # it is a valid expression again; if its own derivatives outgrow the device form, at least as a forward pass
+            if _status(lambda: B.Plan(part)) != 0:
+                assert _status(lambda: B.Plan(part)) == -5 and depth == 0
+                B.Plan(part, needs_grad=[False] * len(part.args))
+            if depth > 0:
+                inner_refused = []
+                _check_against_original(part, depth - 1, inner_refused)
+                below.append((slot, inner_refused))
+    if depth > 0:
+        for which, (sspec, _) in sorted(seeds.items()):
+            inner_refused = []
+            _check_against_original(sspec, depth - 1, inner_refused)
+            below.append(("seed", which, inner_refused))
+        if refused is not None:
+            refused.extend(below)
 
 
 @pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
 def test_derived_expression_is_the_gradient(name, make):
     refused = []
     _check_against_original(make(), 1, refused)
-    # only the body with divisions and square roots outgrows the program length, in two second derivatives
-    # (with respect to y twice and to z twice); everything else is derived at both levels
-    want = {"nonlinear": [(0, []), (1, [2]), (2, [3])]}
-    assert refused == want.get(name, [(slot, []) for _, _, slot in _slots(make())])
+    # what the limits of an expression refuse at the second level
+    want = {
+        # the body with divisions and square roots outgrows the program length in two second derivatives
+        # (with respect to y twice and to z twice)
+        "nonlinear": [(0, []), (1, [2]), (2, [3])],
+        "softplus": [(0, []), (1, [2]), (2, [3]), ("seed", -1, [])],
+        # the second derivative of the quotient in the outer function is too long as well
+        "gated_gauss": [(0, []), (0, []), (1, []), (2, []), (2, []), ("seed", -1, []), ("seed", 0, []),
+                        ("seed", 2, [("no seed", 3)])],
+    }
+    if name in want:
+        assert refused == want[name]
+    else:
+        assert all(entry[-1] == [] for entry in refused), refused
 
 
 def test_scalar_part_is_df_times_the_symbolic_partial_derivative():
@@ -215,9 +281,18 @@ def test_product_programs_run_on_the_matrix_cores():
 
 
 def test_derived_expression_rules():
-    # an outer function puts a second, nested sum into the gradient: not of the single-sum form
-    assert _status(lambda: B.Plan(wl.config1().expr).derived_expr(0)) == -5
-    assert _status(lambda: B.Plan(wl.as_program(wl.config1().expr)).derived_expr(0)) == -5
+    # an outer function puts a second, nested sum into the gradient: operand 0 is then the seed g, not df
+    assert B.Plan(wl.config1().expr).derived_expr(0)[1][0] == -2
+    assert B.Plan(wl.as_program(wl.config1().expr)).derived_expr(3)[1] == [-2, 3]
+    assert B.Plan(wl.matmul_expr(2, 2, 2, "f64")).derived_expr(0)[1][0] == -1
+    # without a summation outer(inner(x)) is one function: f_ij = x_i^2 needs no seed
+    assert B.Plan(wl.broadcast_sq_expr(3, 4, "f64")).derived_expr(0)[1] == [-1, 0]
+    plan = B.Plan(wl.biased_tanh_expr(3, 2, "f64"))
+    assert [plan.query(p)["in_outer"] for p in range(3)] == [False, False, True]
+    assert _status(lambda: plan.derived_expr(0, 0, 1)) == -1      # the outer function does not read x
+    assert _status(lambda: plan.derived_expr(2, 0, 2)) == -1
+    assert _status(lambda: plan.seed_expr(0)) == -1 and _status(lambda: plan.seed_expr(3)) == -1
+    assert plan.seed_expr(2).outer[0] == ("arg", 0)
     # a Smith divisor above 1 is a divisibility mask, not a linear condition
     e = _expr("sq", (4,), [], [("x", (8,), [[2]])])
     assert _status(lambda: B.Plan(e).derived_expr(0)) == -5

@@ -449,40 +449,69 @@ DERIVED = [
     ("nonlinear_f64", lambda: _nonlinear_sum(19, 23, 7, "f64")),
     ("skew_plane_f64", lambda: _expr("mul", (14, 9), [(0, 5)], [("x", (40, 6), [[2, 1, 0], [0, 0, 1]]),
                                                                 ("y", (19,), [[1, 0, 1]])])),
+    # outer functions: seed expression, then the derived one; operands of the outer function: a second part
+    ("worked_f64", lambda: wl.worked_expr(19, 23, 5, "f64")),
+    ("worked_f32", lambda: wl.worked_expr(40, 52, 5, "f32")),
+    ("cumsum_exp_f64", lambda: wl.cumulative_sum_expr(200, "f64")),
+    ("dense_layer_f32", lambda: wl.dense_layer_expr(300, 12, 9, "f32")),
+    ("gated_gauss_f64", lambda: wl.gated_gauss_expr(21, 17, 4, "f64")),
+    ("biased_causal_conv_f64", lambda: wl.biased_causal_conv_expr(150, 7, "f64")),
 ]
 
 
 @pytest.mark.parametrize("name,make", DERIVED, ids=[d[0] for d in DERIVED])
 def test_derived_expressions(name, make):
-    """The gradient of every occurrence, emitted as an expression and run through the forward kernels, is the
-    oracle's gradient of the original expression; its own gradients (second order) are the oracle's gradients of
-    that expression, whose terms the host tests check against the scan of the original."""
+    """The gradient of every occurrence, emitted as expressions (seed expressions first where the outer function
+    is not the identity, a second part for operands the outer function reads) and run through the forward
+    kernels, is the oracle's gradient of the original expression; the gradients of the derived expression itself
+    (second order) are the oracle's gradients of that expression, whose terms the host tests check against the
+    scan of the original."""
     import torch
     from paper_1711_01348_amd import binding as B
     e = make()
     w = wl.random_inputs(e, 31, -0.9, 0.9)
     tensors = w.arg_list()
+    npdt = tensors[0].dtype
     want = oracle.backward(e, tensors, w.df, nthreads=8)
     plan = B.Plan(e)
     rng = np.random.Generator(np.random.PCG64(wl.SEED_BASE + 77))
+    fused = not e.sums and not e.constraints
     slots, seen = [], {}
     for p, a in enumerate(e.args):
         root = p if a.same_as is None else a.same_as
         slots.append((root, seen.get(root, 0), p))
         seen[root] = seen.get(root, 0) + 1
+    seeds = {}
+
+    def seed(which):
+        """(on the device by the library, on the host by the oracle in fp64 rounded to the working precision)"""
+        if which not in seeds:
+            sspec = plan.seed_expr(which)
+            ins = [w.df] + tensors
+            on_gpu = B.Plan(sspec, needs_grad=[False] * len(ins)).forward([_to_dev(x) for x in ins])
+            ref = oracle.forward(sspec, ins)
+            torch.cuda.synchronize()
+            assert check.within(on_gpu.cpu().numpy(), ref, e.dtype), (name, "seed", which)
+            seeds[which] = (on_gpu, ref.astype(npdt))
+        return seeds[which]
+
     for root, occ, slot in slots:
         spec, operands = plan.derived_expr(root, occ)
         dplan = B.Plan(spec)
-        ins = [w.df] + [tensors[q] for q in operands[1:]]
-        dev = [_to_dev(x) for x in ins]
-        got = dplan.forward(dev)
+        kept = [tensors[q] for q in operands[1:]]
+        first_dev, first_ref = (_to_dev(w.df), w.df) if operands[0] == -1 else seed(-1)
+        got = dplan.forward([first_dev] + [_to_dev(x) for x in kept])
+        if plan.query(root, occ)["in_outer"] and not fused:
+            spec1, _ = plan.derived_expr(root, occ, 1)
+            got = got + B.Plan(spec1, needs_grad=[False]).forward([seed(slot)[0]])
         torch.cuda.synchronize()
         got = got.cpu().numpy()
         assert check.within(got, want[slot], e.dtype), (name, slot, check.errors(got, want[slot]))
-        assert np.all(got[want[slot] == 0] == 0), (name, slot, "mask")
-        # second order: v . dx differentiated with respect to df and the kept operands
-        v = rng.uniform(-1, 1, spec.f_shape).astype(got.dtype)
-        grads = dplan.backward(dev, _to_dev(got), _to_dev(v))
+        # second order: v . dx (the part through the sum) differentiated with respect to df / g and the kept operands
+        ins = [first_ref] + kept
+        dev = [_to_dev(x) for x in ins]
+        v = rng.uniform(-1, 1, spec.f_shape).astype(npdt)
+        grads = dplan.backward(dev, dplan.forward(dev), _to_dev(v))
         torch.cuda.synchronize()
         ref = oracle.backward_by_tensor(spec, ins, v, nthreads=8)
         for a, g, r in zip(spec.args, grads, ref):
