@@ -138,6 +138,7 @@ CASES = [
     ("triple", lambda: _triple(6)),
     # outer functions other than the identity: the gradient is a seed expression followed by a derived one
     ("worked", lambda: wl.worked_expr(3, 4, 2, "f64")),
+    ("worked_shared", lambda: wl.worked_shared_expr(3, 2, "f64")),
     ("cumsum_exp", lambda: wl.cumulative_sum_expr(5, "f64")),
     ("tanh_stencil", lambda: wl.strided_tanh_expr(1, 3, 3, 2, 2, 1, "f64")),
     ("softplus", lambda: wl.softplus_ratio_expr(3, 2, 2, "f64")),
