@@ -32,7 +32,7 @@ ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 
 MEASURED_TRAFFIC = {
     "cfg3": dict(source="kernels_worked.hip", sha256="ba86f67ef4a9b366", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
             summary="profiles/worked_8192x8192x5_f32.md"),
-    "cfg4": dict(source="kernels_mfma.hip", sha256="44904531fe551d9c", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
+    "cfg4": dict(source="kernels_mfma.hip", sha256="3979891315943410", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
             summary="profiles/worked_mfma_4096x4096x256_f32.md"),
     "matmul": dict(source="kernels_contract.hip", sha256="766cfe452e2e41d9", fetch_bytes=512.1 * 2**20, write_bytes=64.0 * 2**20,
             summary="profiles/contraction_4096x4096x4096_f32.md"),

@@ -220,6 +220,10 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
     float16v acc[2][2];
     zero_acc(acc);
     float4v ga[2], gb[8];
+    // what the loads of G bring in; the products and the sums on the side are formed one tile later, when the
+    // tile is staged, so that nothing waits for these loads before the matrix instructions of the current tile
+    float4v rdf[2], rf[2], rnv[2];
+    float rc[2];
     const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
     float sr[2] = {0.f, 0.f}, sq[2] = {0.f, 0.f};   // TRANS_A = false: row sums of the thread's two rows
     float4v st = zero4;                               // TRANS_A = true: column sums of the thread's four columns
@@ -227,25 +231,25 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int idx = tid + 256 * p;
+            rdf[p] = zero4; rf[p] = zero4; rnv[p] = zero4; rc[p] = 0.f;
             if (!TRANS_A) {
                 const int row = idx >> 3, q = idx & 7;            // i = m0 + row, j = c0 + 4 q
                 const int i = m0 + row, j = c0 + 4 * q;
                 if (i < I && j < ce) {
                     const size_t off = (size_t)i * J + j;
-                    ga[p] = *reinterpret_cast<const float4v *>(df + off) * *reinterpret_cast<const float4v *>(f + off);
-                    const float4v nv = *reinterpret_cast<const float4v *>(nb + j);
-                    sr[p] += (ga[p][0] + ga[p][1]) + (ga[p][2] + ga[p][3]);
-                    sq[p] += (ga[p][0] * nv[0] + ga[p][1] * nv[1]) + (ga[p][2] * nv[2] + ga[p][3] * nv[3]);
-                } else ga[p] = zero4;
+                    rdf[p] = *reinterpret_cast<const float4v *>(df + off);
+                    rf[p] = *reinterpret_cast<const float4v *>(f + off);
+                    rnv[p] = *reinterpret_cast<const float4v *>(nb + j);
+                }
             } else {
                 const int kk = idx >> 4, q = idx & 15;            // i = c0 + kk, j = m0 + 4 q
                 const int i = c0 + kk, j = m0 + 4 * q;
                 if (i < ce && j < J) {
                     const size_t off = (size_t)i * J + j;
-                    ga[p] = *reinterpret_cast<const float4v *>(df + off) * *reinterpret_cast<const float4v *>(f + off) *
-                            rowv[i * 4 + 3];
-                    st += ga[p];
-                } else ga[p] = zero4;
+                    rdf[p] = *reinterpret_cast<const float4v *>(df + off);
+                    rf[p] = *reinterpret_cast<const float4v *>(f + off);
+                    rc[p] = rowv[i * 4 + 3];
+                }
             }
         }
 #pragma unroll
@@ -255,9 +259,23 @@ __global__ __launch_bounds__(256) void k_mfma_backward(const float *__restrict__
             gb[p] = (cc < ce && n < K) ? *reinterpret_cast<const float4v *>(bmat + (size_t)cc * K + n) : zero4;
         }
     };
+    auto gprep = [&]() {   // G of the loaded tile and its plain sums (zeros where nothing was loaded)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            if (!TRANS_A) {
+                ga[p] = rdf[p] * rf[p];
+                sr[p] += (ga[p][0] + ga[p][1]) + (ga[p][2] + ga[p][3]);
+                sq[p] += (ga[p][0] * rnv[p][0] + ga[p][1] * rnv[p][1]) + (ga[p][2] * rnv[p][2] + ga[p][3] * rnv[p][3]);
+            } else {
+                ga[p] = rdf[p] * rf[p] * rc[p];
+                st += ga[p];
+            }
+        }
+    };
     gload(cs);
     const int mrow = lane & 31, kof = lane >> 5;
     for (int c0 = cs; c0 < ce; c0 += MF_KT) {
+        gprep();
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int idx = tid + 256 * p;
