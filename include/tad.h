@@ -270,9 +270,11 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
  * again no seed is needed.
  *
  * tad_plan_derived_expr, part 0.  Function indices of the new expression: beta (shape of the tensor); summation
- * indices: the kernel coordinates z with constant limits (their extremes over the box); conditions: the box
- * rows of the original extended index [alpha k] = I beta + K z that those limits do not already imply, the
- * original extra conditions, and the cokernel rows C beta = 0 as pairs of inequalities.  Operand 0 is df or g
+ * indices: the kernel coordinates z with constant limits (their extremes over the box), and one more index t per
+ * Smith divisor above 1 (the quotient (U beta)_r / alpha_r, tied to beta by the pair of conditions
+ * (U beta)_r - alpha_r t >= 0 and <= 0: the divisibility mask written as a sum of at most one term);
+ * conditions: the box rows of the original extended index [alpha k] = I beta + K z that those limits do not
+ * already imply, the original extra conditions, and the cokernel rows C beta = 0 as pairs of inequalities.  Operand 0 is df or g
  * (shape of f); the others are those operands of the original expression that the partial derivative depends
  * on, in their original order (aliases stay aliases of one tensor).  The body is a program: inner = operand 0
  * times the symbolic partial derivative, outer = identity.
@@ -287,9 +289,8 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
  *                         -3 - p = h of operand p (seed p)
  *   n_args_out            number of operands of the new expression
  * The outputs are written only on success.
- * Errors: EINVAL (as tad_plan_query; part 1 for an operand the outer function does not read); EUNSUPPORTED if a
- * Smith divisor exceeds 1 (a divisibility mask is not a linear condition), or if the result exceeds the limits
- * of an expression (indices, operands, conditions, program length).
+ * Errors: EINVAL (as tad_plan_query; part 1 for an operand the outer function does not read); EUNSUPPORTED if the
+ * result exceeds the limits of an expression (indices, operands, conditions, program length).
  *
  * tad_plan_seed_expr.  which = -1: g;  which = p: h of operand p (EINVAL unless the outer function reads p).
  * Same function indices, summation ranges and conditions as the original expression; operand 0 is df, operand

@@ -567,38 +567,48 @@ static bool postfix_of(const Graph &g, int node, std::vector<tad_op> &out, bool 
     return is_one || emit_postfix(g, alias, node, out, cap);
 }
 
-// Index part of a derived expression.  With unit Smith divisors the solutions of A x = beta are x = M [beta z],
-// M = [V_R U_R | K], for every beta with C beta = 0: the new function indices are beta, the new summation indices z
-// with the extremes of z over the old box as constant limits, and what the old box and conditions still demand
-// become the new conditions.  (D, lo, hi, E, cons): the old index space.
+// Index part of a derived expression.  The solutions of A x = beta are x = V_R y + K z with y_r = (U beta)_r / alpha_r
+// for every beta with C beta = 0 and every division exact.  Rows with alpha_r = 1 give y_r = (U beta)_r directly;
+// for a row with alpha_r > 1 the quotient becomes one more summation index t with the pair of conditions
+// (U beta)_r - alpha_r t >= 0 and <= 0, a sum of at most one term (the divisibility mask written as a sum).  So
+// x = M [beta z t]: the new function indices are beta, the new summation indices z and t with their extremes
+// over the old box as constant limits, and what the old box and conditions still demand become the new
+// conditions.  (D, lo, hi, E, cons): the old index space.
 static int derived_index(const ArgPlan &ap, int D, const tad_arg &arg, const int64_t *lo, const int64_t *hi, int E,
                          const int64_t (*cons)[TAD_MAX_EXT + 1], tad_expr *eo, IMat &M) {
-    const int N = arg.rank, R = ap.smith.R, kappa = D - R, D2 = N + kappa;
-    for (int r = 0; r < R; ++r)
-        if (ap.diag[r] != 1) return TAD_EUNSUPPORTED;
+    const int N = arg.rank, R = ap.smith.R, kappa = D - R;
+    int col_of_row[TAD_MAX_RANK], n_quot = 0;   // column of t for a row with a divisor above one, else -1
+    for (int r = 0; r < R; ++r) col_of_row[r] = ap.diag[r] != 1 ? N + kappa + n_quot++ : -1;
+    const int D2 = N + kappa + n_quot;
     if (D2 > TAD_MAX_EXT) return TAD_EUNSUPPORTED;
     M = IMat(D, D2);
     for (int d = 0; d < D; ++d) {
         for (int j = 0; j < N; ++j) {
             int64_t v = 0;
-            for (int r = 0; r < R; ++r) v = cadd(v, cmul(ap.VR(d, r), ap.UR(r, j)));
+            for (int r = 0; r < R; ++r)
+                if (col_of_row[r] < 0) v = cadd(v, cmul(ap.VR(d, r), ap.UR(r, j)));
             M(d, j) = v;
         }
         for (int m = 0; m < kappa; ++m) M(d, N + m) = ap.K(d, m);
+        for (int r = 0; r < R; ++r)
+            if (col_of_row[r] >= 0) M(d, col_of_row[r]) = ap.VR(d, r);
     }
     eo->n_f = N;
     for (int j = 0; j < N; ++j) eo->f_shape[j] = arg.shape[j];
-    eo->n_sum = kappa;
-    int64_t blo[TAD_MAX_EXT], bhi[TAD_MAX_EXT];   // box of the new extended index [beta z]
+    eo->n_sum = kappa + n_quot;
+    int64_t blo[TAD_MAX_EXT], bhi[TAD_MAX_EXT];   // box of the new extended index [beta z t]
     for (int j = 0; j < N; ++j) { blo[j] = 0; bhi[j] = arg.shape[j] - 1; }
-    for (int m = 0; m < kappa; ++m) {
-        // z_m is row R + m of V^{-1} applied to the old extended index: its extremes over the old box
+    auto limits_of = [&](int vinv_row, int col) {
+        // the coordinate is a row of V^{-1} applied to the old extended index: its extremes over the old box
         int64_t row[TAD_MAX_EXT], mn = 0, mx = 0;
-        for (int d = 0; d < D; ++d) row[d] = ap.Vinv(R + m, d);
+        for (int d = 0; d < D; ++d) row[d] = ap.Vinv(vinv_row, d);
         if (!linear_form_range(row, D, lo, hi, E, cons, mn, mx)) mn = mx = 0;
-        eo->sum_lo[m] = blo[N + m] = mn;
-        eo->sum_hi[m] = bhi[N + m] = mx;
-    }
+        eo->sum_lo[col - N] = blo[col] = mn;
+        eo->sum_hi[col - N] = bhi[col] = mx;
+    };
+    for (int m = 0; m < kappa; ++m) limits_of(R + m, N + m);
+    for (int r = 0; r < R; ++r)
+        if (col_of_row[r] >= 0) limits_of(r, col_of_row[r]);
     // conditions c . [beta z] + c0 >= 0; one that holds on the whole new box, or is there already, is left out
     eo->n_constraints = 0;
     auto add_condition = [&](const int64_t *c, int64_t c0) {
@@ -640,6 +650,14 @@ static int derived_index(const ArgPlan &ap, int D, const tad_arg &arg, const int
             for (int j = 0; j < D2; ++j) c[j] = j < N ? cmul(sign, ap.C(r, j)) : 0;
             if (!add_condition(c, 0)) return TAD_EUNSUPPORTED;
         }
+    for (int r = 0; r < R; ++r) {
+        if (col_of_row[r] < 0) continue;
+        for (int sign = 1; sign >= -1; sign -= 2) {   // (U beta)_r = alpha_r t
+            for (int j = 0; j < D2; ++j) c[j] = j < N ? cmul(sign, ap.UR(r, j)) : 0;
+            c[col_of_row[r]] = cmul(-sign, ap.diag[r]);
+            if (!add_condition(c, 0)) return TAD_EUNSUPPORTED;
+        }
+    }
     return TAD_OK;
 }
 

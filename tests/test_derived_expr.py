@@ -136,6 +136,13 @@ CASES = [
     ("autocorrelation", lambda: wl.autocorrelation_expr(6, 3, "f64")),
     ("nonlinear", lambda: _nonlinear(3, 4, 2)),
     ("triple", lambda: _triple(6)),
+    # Smith divisors above one: divisibility masks
+    ("stride2", lambda: _expr("sq", (4,), [], [("x", (9,), [[2]])])),
+    ("stride2_broadcast", lambda: _expr("cube", (4, 3), [], [("x", (8,), [[2, 0]])])),
+    ("stride_2_4", lambda: _expr("sin", (4, 3), [], [("x", (16,), [[2, 4]])])),
+    ("stride_mixed_sum", lambda: _expr("mul", (3, 4), [(0, 2)], [("x", (7, 9), [[2, 0, 1], [0, 2, 1]]),
+                                                                   ("y", (3,), [[0, 0, 1]])])),
+    ("stride_3_1", lambda: _expr("exp", (4, 3), [], [("x", (12,), [[3, 1]])])),
     # outer functions other than the identity: the gradient is a seed expression followed by a derived one
     ("worked", lambda: wl.worked_expr(3, 4, 2, "f64")),
     ("worked_shared", lambda: wl.worked_shared_expr(3, 2, "f64")),
@@ -294,9 +301,10 @@ def test_derived_expression_rules():
     assert _status(lambda: plan.derived_expr(2, 0, 2)) == -1
     assert _status(lambda: plan.seed_expr(0)) == -1 and _status(lambda: plan.seed_expr(3)) == -1
     assert plan.seed_expr(2).outer[0] == ("arg", 0)
-    # a Smith divisor above 1 is a divisibility mask, not a linear condition
+    # a Smith divisor above 1: the quotient becomes a summation index tied to beta by two conditions
     e = _expr("sq", (4,), [], [("x", (8,), [[2]])])
-    assert _status(lambda: B.Plan(e).derived_expr(0)) == -5
+    spec, _ = B.Plan(e).derived_expr(0)
+    assert spec.sums == [(0, 3)] and sorted(spec.constraints) == sorted([([1, -2], 0), ([-1, 2], 0)])
     plan = B.Plan(wl.matrix_square_expr(3, "f64"))
     assert _status(lambda: plan.derived_expr(1)) == -1           # an alias operand is reached through its tensor
     assert _status(lambda: plan.derived_expr(0, 2)) == -1

@@ -449,6 +449,10 @@ DERIVED = [
     ("nonlinear_f64", lambda: _nonlinear_sum(19, 23, 7, "f64")),
     ("skew_plane_f64", lambda: _expr("mul", (14, 9), [(0, 5)], [("x", (40, 6), [[2, 1, 0], [0, 0, 1]]),
                                                                 ("y", (19,), [[1, 0, 1]])])),
+    # Smith divisors above one (the quotient becomes a summation index of the derived expression)
+    ("stride_mixed_f64", lambda: _expr("mul", (13, 11), [(0, 4)], [("x", (29, 25), [[2, 0, 1], [0, 2, 1]]),
+                                                                   ("y", (5,), [[0, 0, 1]])])),
+    ("stride3_exp_f32", lambda: _expr("exp", (40, 3), [], [("x", (120,), [[3, 1]])], "f32")),
     # outer functions: seed expression, then the derived one; operands of the outer function: a second part
     ("worked_f64", lambda: wl.worked_expr(19, 23, 5, "f64")),
     ("worked_f32", lambda: wl.worked_expr(40, 52, 5, "f32")),
