@@ -21,5 +21,8 @@ struct ProfileScope {
     do {                                                                       \
         (void)hipGetLastError();                                               \
         tad::ProfileScope _ps(name);                                           \
-        hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, _ps.start, _ps.stop, 0, __VA_ARGS__); \
+        if (_ps.start)                                                         \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, _ps.start, _ps.stop, 0, __VA_ARGS__); \
+        else /* the plain launch: the form a stream capture records */         \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__); \
     } while (0)
