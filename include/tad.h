@@ -85,16 +85,21 @@ typedef enum {
     TAD_OP_ADD = 3, TAD_OP_SUB = 4, TAD_OP_MUL = 5, TAD_OP_DIV = 6,   /* pop b, pop a, push a op b */
     TAD_OP_NEG = 7, TAD_OP_EXP = 8, TAD_OP_LOG = 9, TAD_OP_SIN = 10, TAD_OP_COS = 11, TAD_OP_TANH = 12,
     TAD_OP_SQRT = 13, /* pop a, push op(a) */
-    TAD_OP_POWI = 14  /* pop a, push a^iarg for an integer exponent 1 <= iarg <= 16 */
+    TAD_OP_POWI = 14, /* pop a, push a^iarg for an integer exponent 1 <= iarg <= 16 */
+    TAD_OP_STORE = 15, /* copy the top of the stack into temporary `iarg` (0 <= iarg < TAD_MAX_TEMPS); the stack is unchanged */
+    TAD_OP_LOAD = 16   /* push temporary `iarg`, which an earlier operation of the same program has stored: a
+                          sub-expression that is used several times is written once (Sec. 2: a node of the
+                          expression graph may have several consumers) */
 } tad_opcode;
 
 typedef struct {
     int32_t op;    /* tad_opcode */
-    int32_t iarg;  /* operand index (ARG) or exponent (POWI) */
+    int32_t iarg;  /* operand index (ARG), exponent (POWI) or temporary (STORE, LOAD) */
     double value;  /* CONST */
 } tad_op;
 
-#define TAD_MAX_PROGRAM 48 /* operations per program */
+#define TAD_MAX_PROGRAM 64 /* operations per program */
+#define TAD_MAX_TEMPS 16   /* temporaries of TAD_OP_STORE / TAD_OP_LOAD per program */
 
 /* Element-wise definition of f (Sec. 5.1): shape of f and the summation ranges Psi (Sec. 5.2). */
 typedef struct {

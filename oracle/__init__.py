@@ -31,11 +31,11 @@ class _Arg(ctypes.Structure):
                 ("A", (ctypes.c_int64 * MAX_EXT) * MAX_RANK)]
 
 
-MAX_PROGRAM = 48
+MAX_PROGRAM = 64
 MAX_COND = 8
 # postfix operation names of a program body -> the oracle's own codes (enum O_* in tad_oracle.c)
 _OPS = {"const": 0, "arg": 1, "sum": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "exp": 8, "log": 9,
-        "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14}
+        "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14, "store": 15, "load": 16}
 
 
 class _Op(ctypes.Structure):
@@ -118,7 +118,7 @@ def _pack(expr) -> _Expr:
             assert 1 <= len(prog) <= MAX_PROGRAM
             for i, t in enumerate(prog):
                 dst[i].op = _OPS[t[0]]
-                dst[i].iarg = int(t[1]) if t[0] in ("arg", "powi") else 0
+                dst[i].iarg = int(t[1]) if t[0] in ("arg", "powi", "store", "load") else 0
                 dst[i].value = float(t[1]) if t[0] == "const" else 0.0
         e.n_inner, e.n_outer = len(expr.inner), len(expr.outer)
     return e

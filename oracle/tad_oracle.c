@@ -54,9 +54,12 @@ typedef struct {
     int64_t A[ORC_MAX_RANK][ORC_MAX_EXT]; /* index matrix, columns: function then summation indices */
 } orc_arg;
 
-#define ORC_MAX_PROGRAM 48
+#define ORC_MAX_PROGRAM 64
 /* postfix operation codes of a program body */
-enum { O_CONST, O_ARG, O_SUM, O_ADD, O_SUB, O_MUL, O_DIV, O_NEG, O_EXP, O_LOG, O_SIN, O_COS, O_TANH, O_SQRT, O_POWI };
+enum { O_CONST, O_ARG, O_SUM, O_ADD, O_SUB, O_MUL, O_DIV, O_NEG, O_EXP, O_LOG, O_SIN, O_COS, O_TANH, O_SQRT, O_POWI,
+       O_STORE, /* copy the top of the stack into temporary iarg (the stack is unchanged) */
+       O_LOAD   /* push temporary iarg */ };
+#define ORC_MAX_TEMPS 16
 typedef struct {
     int op;        /* O_* */
     int iarg;      /* operand index (O_ARG) or integer exponent (O_POWI) */
@@ -111,8 +114,8 @@ typedef struct { double v, d; } dual;
  * is set --, every other input and every constant derivative zero.  A malformed program yields NaN.
  */
 static dual run_program(const orc_op *ops, int n, const double *args, double sum, int seed_arg, int seed_sum) {
-    dual st[ORC_MAX_PROGRAM + 1];
-    int top = 0;
+    dual st[ORC_MAX_PROGRAM + 1], tmp[ORC_MAX_TEMPS];
+    int top = 0, have[ORC_MAX_TEMPS] = {0};
     const dual bad = {NAN, NAN};
     for (int i = 0; i < n; ++i) {
         const orc_op *o = &ops[i];
@@ -120,6 +123,15 @@ static dual run_program(const orc_op *ops, int n, const double *args, double sum
         if (o->op == O_CONST) { r.v = o->value; r.d = 0.0; }
         else if (o->op == O_ARG) { r.v = args[o->iarg]; r.d = (o->iarg == seed_arg) ? 1.0 : 0.0; }
         else if (o->op == O_SUM) { r.v = sum; r.d = seed_sum ? 1.0 : 0.0; }
+        else if (o->op == O_STORE) {
+            if (top < 1 || o->iarg < 0 || o->iarg >= ORC_MAX_TEMPS) return bad;
+            tmp[o->iarg] = st[top - 1];
+            have[o->iarg] = 1;
+            continue;
+        } else if (o->op == O_LOAD) {
+            if (o->iarg < 0 || o->iarg >= ORC_MAX_TEMPS || !have[o->iarg]) return bad;
+            r = tmp[o->iarg];
+        }
         else if (o->op >= O_ADD && o->op <= O_DIV) {
             if (top < 2) return bad;
             dual y = st[--top], x = st[--top];

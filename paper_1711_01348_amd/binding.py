@@ -19,9 +19,9 @@ LIB_PATH = os.path.join(_PKG, "libtad.so")
 
 F32, F64 = 0, 1
 BODY = {"sq": 0, "cube": 1, "sin": 2, "exp": 3, "mul": 4, "worked": 5, "tanh_dot": 6, "program": 7}
-MAX_PROGRAM = 48
+MAX_PROGRAM = 64
 OPCODE = {"const": 0, "arg": 1, "sum": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "exp": 8, "log": 9,
-          "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14}
+          "sin": 10, "cos": 11, "tanh": 12, "sqrt": 13, "powi": 14, "store": 15, "load": 16}
 FAMILY = {0: "generic", 1: "row_reduce", 2: "diagonal", 3: "antidiagonal", 4: "worked",
           5: "worked_mfma", 6: "strided", 7: "contraction", 8: "program"}
 PLAN_GENERIC_ONLY = 1
@@ -145,7 +145,7 @@ def pack_expr(expr) -> TadExpr:
                 raise TadError(-1, "tad_plan_derive")
             for i, t in enumerate(prog):
                 dst[i].op = OPCODE[t[0]]
-                if t[0] in ("arg", "powi"):
+                if t[0] in ("arg", "powi", "store", "load"):
                     dst[i].iarg = int(t[1])
                 elif t[0] == "const":
                     dst[i].value = float(t[1])
@@ -261,7 +261,7 @@ class Plan:
             out = []
             for i in range(count):
                 name = opname[ops[i].op]
-                out.append((name, ops[i].iarg) if name in ("arg", "powi") else
+                out.append((name, ops[i].iarg) if name in ("arg", "powi", "store", "load") else
                            (name, ops[i].value) if name == "const" else (name,))
             return out
 

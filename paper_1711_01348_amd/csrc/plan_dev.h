@@ -68,7 +68,7 @@ struct ForwardPlan {
 // Scalar function in three-address form, as the kernels interpret it: operation i computes temporary i from
 // earlier temporaries a[i], b[i] (or an operand / the sum / a constant).  Produced on the host from the user's
 // postfix program or from its symbolic derivative (program.hpp).
-constexpr int kMaxProgOps = 48;
+constexpr int kMaxProgOps = 64;
 constexpr int kMaxProgConst = 8;
 enum ProgOp : uint8_t {
     P_CONST, P_ARG, P_SUM, P_ADD, P_SUB, P_MUL, P_DIV, P_NEG, P_EXP, P_LOG, P_SIN, P_COS, P_TANH, P_SQRT, P_POWI

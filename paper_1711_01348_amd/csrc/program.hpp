@@ -36,6 +36,8 @@ struct Graph {
 inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, Graph &g, uint32_t outer_operands = 0) {
     if (!ops || n < 1 || n > TAD_MAX_PROGRAM) return TAD_EINVAL;
     std::vector<int> st;
+    int temp[TAD_MAX_TEMPS];   // node held by each temporary, -1: not stored yet
+    for (int &t : temp) t = -1;
     for (int i = 0; i < n; ++i) {
         const tad_op &o = ops[i];
         auto pop = [&]() { int v = st.back(); st.pop_back(); return v; };
@@ -75,6 +77,14 @@ inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, G
             st.push_back(g.add(P_POWI, a, -1, o.iarg));
             break;
         }
+        case TAD_OP_STORE:   // in the graph a temporary is just a second reference to the node
+            if (st.empty() || o.iarg < 0 || o.iarg >= TAD_MAX_TEMPS) return TAD_EINVAL;
+            temp[o.iarg] = st.back();
+            break;
+        case TAD_OP_LOAD:
+            if (o.iarg < 0 || o.iarg >= TAD_MAX_TEMPS || temp[o.iarg] < 0) return TAD_EINVAL;
+            st.push_back(temp[o.iarg]);
+            break;
         default: return TAD_EINVAL;
         }
     }
@@ -190,23 +200,70 @@ inline bool lower(const Graph &g, int result, DevProg &out) {
     return true;
 }
 
-// Postfix form of the expression computing `node`, appended to `out` (a sub-expression used twice is written
-// twice); same simplifications as lower().  False once the program grows beyond `cap` operations.
+// Postfix form of the expression computing `node`, appended to `out`; same simplifications as lower().  A
+// sub-expression with several consumers is written once, kept in a temporary (TAD_OP_STORE) and read back
+// (TAD_OP_LOAD) while temporaries last; after that it is written out again.  False once the program grows
+// beyond `cap` operations.
 inline bool emit_postfix(const Graph &g, const std::vector<int> &alias, int node, std::vector<tad_op> &out, size_t cap) {
     static_assert((int)P_CONST == (int)TAD_OP_CONST && (int)P_ARG == (int)TAD_OP_ARG && (int)P_SUM == (int)TAD_OP_SUM && (int)P_ADD == (int)TAD_OP_ADD &&
                       (int)P_SUB == (int)TAD_OP_SUB && (int)P_MUL == (int)TAD_OP_MUL && (int)P_DIV == (int)TAD_OP_DIV && (int)P_NEG == (int)TAD_OP_NEG &&
                       (int)P_EXP == (int)TAD_OP_EXP && (int)P_LOG == (int)TAD_OP_LOG && (int)P_SIN == (int)TAD_OP_SIN && (int)P_COS == (int)TAD_OP_COS &&
                       (int)P_TANH == (int)TAD_OP_TANH && (int)P_SQRT == (int)TAD_OP_SQRT && (int)P_POWI == (int)TAD_OP_POWI,
                   "internal and public operation codes are numbered alike");
-    const Node &nd = g.nodes[alias[node]];
-    if (nd.a >= 0 && !emit_postfix(g, alias, nd.a, out, cap)) return false;
-    if (nd.b >= 0 && !emit_postfix(g, alias, nd.b, out, cap)) return false;
-    tad_op o{};
-    o.op = nd.op;
-    o.iarg = (nd.op == P_ARG || nd.op == P_POWI) ? nd.k : 0;
-    o.value = nd.op == P_CONST ? nd.c : 0.0;
-    out.push_back(o);
-    return out.size() <= cap;
+    const int N = (int)g.nodes.size();
+    // consumers of every node inside the sub-graph of `node`
+    std::vector<int> uses(N, 0);
+    std::vector<char> seen(N, 0);
+    std::vector<int> stack{alias[node]};
+    seen[alias[node]] = 1;
+    while (!stack.empty()) {
+        const Node &nd = g.nodes[stack.back()];
+        stack.pop_back();
+        for (int in : {nd.a, nd.b}) {
+            if (in < 0) continue;
+            const int t = alias[in];
+            ++uses[t];
+            if (!seen[t]) { seen[t] = 1; stack.push_back(t); }
+        }
+    }
+    std::vector<int> slot(N, -1);
+    int next_slot = 0;
+    bool ok = true;
+    // recursion on the simplified graph
+    struct Emit {
+        const Graph &g; const std::vector<int> &alias; std::vector<int> &uses, &slot; int &next_slot;
+        std::vector<tad_op> &out; size_t cap; bool &ok;
+        void run(int n) {
+            if (!ok) return;
+            const int t = alias[n];
+            const Node &nd = g.nodes[t];
+            tad_op o{};
+            if (slot[t] >= 0) {
+                o.op = TAD_OP_LOAD;
+                o.iarg = slot[t];
+                out.push_back(o);
+                ok = out.size() <= cap;
+                return;
+            }
+            if (nd.a >= 0) run(nd.a);
+            if (nd.b >= 0) run(nd.b);
+            if (!ok) return;
+            o.op = nd.op;
+            o.iarg = (nd.op == P_ARG || nd.op == P_POWI) ? nd.k : 0;
+            o.value = nd.op == P_CONST ? nd.c : 0.0;
+            out.push_back(o);
+            const bool leaf = nd.op == P_CONST || nd.op == P_ARG || nd.op == P_SUM;
+            if (!leaf && uses[t] > 1 && next_slot < TAD_MAX_TEMPS) {
+                tad_op st{};
+                st.op = TAD_OP_STORE;
+                st.iarg = slot[t] = next_slot++;
+                out.push_back(st);
+            }
+            ok = out.size() <= cap;
+        }
+    } emit{g, alias, uses, slot, next_slot, out, cap, ok};
+    emit.run(node);
+    return ok;
 }
 
 // Evaluation of a lowered program (the host twin of the kernels' interpreter), fp64.

@@ -41,7 +41,8 @@ class ExprSpec:
     dtype: str = "f64"              # "f64" or "f32"
     # body "program": the scalar functions as postfix programs, f = outer(sum_k inner(operand values)).
     # Entries: ("arg", p), ("const", c), ("sum",), ("add",), ("sub",), ("mul",), ("div",), ("neg",), ("exp",),
-    # ("log",), ("sin",), ("cos",), ("tanh",), ("sqrt",), ("powi", n).  ("sum",) belongs to the outer program;
+    # ("log",), ("sin",), ("cos",), ("tanh",), ("sqrt",), ("powi", n), ("store", t) (keep a copy of the top of the
+    # stack in temporary t), ("load", t) (push temporary t).  ("sum",) belongs to the outer program;
     # ("arg", p) to the inner one and, for operands whose index ignores the summation indices, to the outer one.
     inner: List[tuple] = field(default_factory=list)
     outer: List[tuple] = field(default_factory=list)

@@ -59,7 +59,7 @@ def _terms_brute(e, slot, beta, operands):
 
 
 def _run_postfix(prog, values, total=0.0):
-    st = []
+    st, tmp = [], {}
     una = {"neg": lambda a: -a, "exp": math.exp, "log": math.log, "sin": math.sin, "cos": math.cos,
            "tanh": math.tanh, "sqrt": math.sqrt}
     for t in prog:
@@ -67,6 +67,8 @@ def _run_postfix(prog, values, total=0.0):
         elif t[0] == "arg": st.append(values[t[1]])
         elif t[0] == "sum": st.append(total)
         elif t[0] == "powi": st.append(st.pop() ** t[1])
+        elif t[0] == "store": tmp[t[1]] = st[-1]
+        elif t[0] == "load": st.append(tmp[t[1]])
         elif t[0] in una: st.append(una[t[0]](st.pop()))
         else:
             b, a = st.pop(), st.pop()
@@ -239,20 +241,9 @@ def _check_against_original(e, depth, refused=None):
 def test_derived_expression_is_the_gradient(name, make):
     refused = []
     _check_against_original(make(), 1, refused)
-    # what the limits of an expression refuse at the second level
-    want = {
-        # the body with divisions and square roots outgrows the program length in two second derivatives
-        # (with respect to y twice and to z twice)
-        "nonlinear": [(0, []), (1, [2]), (2, [3])],
-        "softplus": [(0, []), (1, [2]), (2, [3]), ("seed", -1, [])],
-        # the second derivative of the quotient in the outer function is too long as well
-        "gated_gauss": [(0, []), (0, []), (1, []), (2, []), (2, []), ("seed", -1, []), ("seed", 0, []),
-                        ("seed", 2, [("no seed", 3)])],
-    }
-    if name in want:
-        assert refused == want[name]
-    else:
-        assert all(entry[-1] == [] for entry in refused), refused
+    # nothing is refused at either level: shared sub-expressions are kept in temporaries, so even the second
+    # derivatives of the body with divisions and square roots fit the program length
+    assert all(entry[-1] == [] for entry in refused), refused
 
 
 def test_scalar_part_is_df_times_the_symbolic_partial_derivative():

@@ -379,6 +379,32 @@ def test_program_body_closed_form():
     assert np.allclose(oracle.backward(e, [x], df)[0], df * 2 * x / (1 + x * x), rtol=1e-13)
 
 
+def test_program_temporaries_equal_the_written_out_program():
+    """(x + y)^2 + sin(x + y) with x + y kept in a temporary, and the outer function u * exp(u) likewise, against
+    the same programs with the shared part written twice; plus the closed form of the forward value."""
+    args = [wl.ArgSpec("x", (5, 3), [[1, 0], [0, 1]]), wl.ArgSpec("y", (3,), [[0, 1]])]
+    xy = [("arg", 0), ("arg", 1), ("add",)]
+    shared = wl.ExprSpec("program", (5,), [(0, 2)], args, "f64",
+                         xy + [("store", 3), ("powi", 2), ("load", 3), ("sin",), ("add",)],
+                         [("sum",), ("const", 0.25), ("mul",), ("store", 0), ("load", 0), ("exp",), ("mul",)])
+    written = wl.ExprSpec("program", (5,), [(0, 2)], args, "f64",
+                          xy + [("powi", 2)] + xy + [("sin",), ("add",)],
+                          [("sum",), ("const", 0.25), ("mul",), ("sum",), ("const", 0.25), ("mul",), ("exp",), ("mul",)])
+    w = wl.random_inputs(written, 21)
+    xs = w.arg_list()
+    f = oracle.forward(shared, xs)
+    u = 0.25 * ((xs[0] + xs[1]) ** 2 + np.sin(xs[0] + xs[1])).sum(axis=1)
+    assert np.allclose(f, u * np.exp(u), rtol=1e-14)
+    assert np.array_equal(f, oracle.forward(written, xs))
+    for g, r in zip(oracle.backward(shared, xs, w.df), oracle.backward(written, xs, w.df)):
+        assert np.allclose(g, r, rtol=1e-14, atol=1e-16)
+    shared.inner = [("load", 3)] + shared.inner          # read before anything was stored
+    with pytest.raises(RuntimeError):
+        f = oracle.forward(shared, xs)
+        if np.isnan(f).all():
+            raise RuntimeError("malformed program")
+
+
 # ---------------------------------------------------------------- operands of the outer function (Sec. 5.2)
 
 def test_outer_operand_closed_form():

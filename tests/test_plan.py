@@ -522,7 +522,12 @@ def test_program_rules():
     assert _status(lambda: mk([("arg", 0), ("powi", 0)], ok_out)) == -1
     assert _status(lambda: mk([("const", float("inf"))], ok_out)) == -1
     assert _status(lambda: mk(ok_in, [])) == -1
-    assert _status(lambda: mk([("arg", 0)] + [("neg",)] * 48, ok_out)) == -1    # longer than TAD_MAX_PROGRAM
+    assert _status(lambda: mk([("arg", 0)] + [("neg",)] * 64, ok_out)) == -1    # longer than TAD_MAX_PROGRAM
+    mk([("arg", 0), ("store", 15), ("load", 15), ("mul",)], ok_out)             # a temporary: x * x
+    assert _status(lambda: mk([("load", 0), ("arg", 0), ("mul",)], ok_out)) == -1    # read before it is stored
+    assert _status(lambda: mk([("arg", 0), ("store", 16)], ok_out)) == -1            # beyond TAD_MAX_TEMPS
+    assert _status(lambda: mk([("store", 0), ("arg", 0)], ok_out)) == -1             # nothing on the stack to keep
+    assert _status(lambda: mk([("arg", 0), ("store", 0)], [("load", 0)])) == -1      # temporaries belong to one program
     # a derivative too long for the device form is refused, not truncated
     long_inner = [("arg", 0)] + [("arg", 0), ("div",), ("sin",)] * 7
     assert _status(lambda: mk(long_inner, ok_out)) in (0, -5)
