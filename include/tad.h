@@ -66,7 +66,7 @@ typedef enum {
     TAD_BODY_MUL = 4,      /* sum x*y                               (Sec. 5, f^2, f^4)  2 arguments */
     TAD_BODY_WORKED = 5,   /* exp(-sum((a+b)^2 c + d^3))            (Sec. 1, Sec. 6)    4 arguments a,b,c,d */
     TAD_BODY_TANH_DOT = 6, /* tanh(sum x*w)                                             2 arguments x,w */
-    TAD_BODY_PROGRAM = 7   /* inner and outer function given as postfix programs (tad_op), 1..4 operands;
+    TAD_BODY_PROGRAM = 7   /* inner and outer function given as postfix programs (tad_op), 1..TAD_MAX_ARGS operands;
                               their derivatives are derived by reverse accumulation (Sec. 2) at plan time */
 } tad_body;
 
