@@ -253,6 +253,48 @@ def band_expr(N: int, W: int, dtype: str) -> ExprSpec:
                     constraints=[([-1, 1], 0), ([1, -1], W)])
 
 
+def random_expr(seed: int, dtype: str = "f64") -> ExprSpec:
+    """A seeded random expression: 1..3 function indices, 0..2 summation indices (at most 4 together), one or two
+    operands of rank 1..3 with small non-negative index coefficients, sometimes a negative one made safe by a
+    condition, operand shapes with some slack beyond the referenced range."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 5000 + seed))
+    n_f = int(rng.integers(1, 4))
+    n_sum = int(rng.integers(0, min(2, 4 - n_f) + 1))
+    D = n_f + n_sum
+    ext = [int(rng.integers(2, 6)) for _ in range(D)]
+    sums = []
+    for q in range(n_sum):
+        lo = int(rng.integers(0, 2))
+        sums.append((lo, lo + ext[n_f + q] - 1))
+    hi = [ext[d] - 1 for d in range(n_f)] + [h for _, h in sums]
+    lo = [0] * n_f + [l for l, _ in sums]
+    n_args = 1 if n_sum == 0 and rng.random() < 0.5 else int(rng.integers(1, 3))
+    constraints = []
+    args = []
+    for p in range(n_args):
+        rank = int(rng.integers(1, 4))
+        A = [[int(rng.choice([0, 0, 0, 1, 1, 2, 3])) for _ in range(D)] for _ in range(rank)]
+        if not any(any(row) for row in A):
+            A[0][int(rng.integers(0, D))] = 1
+        if D >= 2 and not constraints and rng.random() < 0.3:
+            # x_{.. + i - k ..}: a negative coefficient, kept inside the tensor by the condition i - k >= 0
+            i, k = (int(v) for v in rng.choice(D, 2, replace=False))
+            r = int(rng.integers(0, rank))
+            A[r] = [0] * D
+            A[r][i], A[r][k] = 1, -1
+            cond = [0] * D
+            cond[i], cond[k] = 1, -1
+            constraints.append((cond, 0))
+        shape = tuple(max(1, sum(c * (hi[d] if c > 0 else lo[d]) for d, c in enumerate(row)) + 1) + int(rng.integers(0, 3))
+                      for row in A)
+        args.append(ArgSpec("xy"[p], shape, A))
+    if n_args == 2:
+        body = "mul" if rng.random() < 0.5 else "tanh_dot"
+    else:
+        body = str(rng.choice(["exp"] if n_sum else ["exp", "sq", "cube", "sin"]))
+    return ExprSpec(body, tuple(ext[:n_f]), sums, args, dtype, constraints=constraints)
+
+
 # A tensor that occurs more than once in an expression (Sec. 5.3: its gradient is the sum over the
 # occurrences): the later occurrences are alias operands.
 

@@ -136,6 +136,21 @@ def test_assorted_index_maps_fp64(make):
     assert_parity(w, f, grads, f_ref, g_ref)
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_random_expressions(seed):
+    """Seeded random expressions (index matrices, ranks, summation ranges, conditions, bodies) on the plan-driven
+    kernels, and the same expression with its body given as programs."""
+    e = wl.random_expr(seed, "f64" if seed % 2 else "f32")
+    w = wl.random_inputs(e, 100 + seed, -0.6, 0.6)
+    f_ref, g_ref = oracle_all(w, 2)
+    _, f, grads = run_gpu(w)
+    assert_parity(w, f, grads, f_ref, g_ref, "random %d" % seed)
+    wp = wl.Workload(w.name, wl.as_program(e), w.inputs, w.df)
+    plan, f, grads = run_gpu(wp)
+    assert plan.forward_family in ("program", "contraction")
+    assert_parity(wp, f, grads, f_ref, g_ref, "random %d as program" % seed)
+
+
 def test_backward_is_deterministic_and_skips_unwanted():
     import torch
     w = wl.config3("small")

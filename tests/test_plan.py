@@ -327,6 +327,13 @@ def test_assorted_index_maps_match_scan(make):
     _check_plan_against_scan(make(), sample=1000)
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_random_expressions_match_scan(seed):
+    """Seeded random index matrices (ranks 1..3, coefficients 0..3, a negative one under a condition, slack in the
+    shapes): every plan visits exactly what the scan of the box finds."""
+    _check_plan_against_scan(wl.random_expr(seed), sample=60, seed=seed)
+
+
 def test_counts_at_full_size():
     """Bit-exact counts for every gradient element at the full benchmark sizes (cfg 2, 3, 5)."""
     for w in [wl.config2(1), wl.config2(2), wl.config2(3), wl.config3(), wl.config5()]:
