@@ -246,6 +246,13 @@ def test_derived_expression_is_the_gradient(name, make):
     assert all(entry[-1] == [] for entry in refused), refused
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_expressions_have_exact_derived_expressions(seed):
+    refused = []
+    _check_against_original(wl.random_expr(seed), 0, refused)
+    assert refused == []
+
+
 def test_scalar_part_is_df_times_the_symbolic_partial_derivative():
     e = _nonlinear(2, 2, 2)
     plan = B.Plan(e)
