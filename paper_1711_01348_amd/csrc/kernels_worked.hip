@@ -97,15 +97,27 @@ __device__ __forceinline__ float dpp_add(float v) {
     return v + __int_as_float(t);
 }
 
-// sum over the 64 lanes; the total is valid in lane 63
-__device__ __forceinline__ float wave_sum_lane63(float v) {
-    v = dpp_add<0x111, 0xf>(v);   // row_shr:1
-    v = dpp_add<0x112, 0xf>(v);   // row_shr:2
-    v = dpp_add<0x114, 0xf>(v);   // row_shr:4
-    v = dpp_add<0x118, 0xf>(v);   // row_shr:8  -> lane 15 of every row of 16 holds the row total
-    v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
-    v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
-    return v;
+// One step of the sum over the 64 lanes, applied to N independent values (consecutive instructions do not depend
+// on each other, so the wait states a dependent DPP chain needs are filled with useful work).  After the six
+// steps the total is valid in lane 63; the other lanes hold partial sums nobody reads.  The broadcast steps run
+// on all rows (every step is then one fused add): row r receives lane 15 of row r - 1 and rows 2, 3 receive lane
+// 31, which gives lane 63 = (t3 + t2) + (t1 + t0), the order the masked form has.
+template <int STEP, int N>
+__device__ __forceinline__ void wave_sum_step(float (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        if (STEP == 0) v[i] = dpp_add<0x111, 0xf>(v[i]);        // row_shr:1
+        else if (STEP == 1) v[i] = dpp_add<0x112, 0xf>(v[i]);   // row_shr:2
+        else if (STEP == 2) v[i] = dpp_add<0x114, 0xf>(v[i]);   // row_shr:4
+        else if (STEP == 3) v[i] = dpp_add<0x118, 0xf>(v[i]);   // row_shr:8 -> lane 15 of every row of 16 holds the row total
+        else if (STEP == 4) v[i] = dpp_add<0x142, 0xf>(v[i]);   // row_bcast:15
+        else v[i] = dpp_add<0x143, 0xf>(v[i]);                  // row_bcast:31
+    }
+}
+template <int N>
+__device__ __forceinline__ void wave_sum_lane63(float (&v)[N]) {
+    wave_sum_step<0>(v); wave_sum_step<1>(v); wave_sum_step<2>(v);
+    wave_sum_step<3>(v); wave_sum_step<4>(v); wave_sum_step<5>(v);
 }
 
 constexpr int BWD_RB = 4;   // rows per step
@@ -168,23 +180,34 @@ __global__ __launch_bounds__(256) void k_worked_backward(const float *__restrict
     const int r0 = wave * WR;
     const int rows = max(0, min(WR, I - (i0 + r0)));
     const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+    const bool all_columns = jb + BWD_TJ <= J;   // the same for the whole block
     for (int rb = 0; rb < WR; rb += BWD_RB) {
-        float part[BWD_RB][RP];
+        float part[BWD_RB * RP];
 #pragma unroll
-        for (int r = 0; r < BWD_RB; ++r)
-#pragma unroll
-            for (int q = 0; q < RP; ++q) part[r][q] = 0.f;
+        for (int q = 0; q < BWD_RB * RP; ++q) part[q] = 0.f;
         if (rb < rows) {
             float4v fv[BWD_RB][2], dv[BWD_RB][2];
+            if (all_columns && rb + BWD_RB <= rows) {
+                // inside the tensor as a whole (the case of every step but those at the edges): plain loads
 #pragma unroll
-            for (int r = 0; r < BWD_RB; ++r)
+                for (int r = 0; r < BWD_RB; ++r)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const bool ok = live[h] && (rb + r) < rows;
-                    const size_t off = (size_t)(i0 + r0 + rb + r) * J + jc[h];
-                    fv[r][h] = ok ? *reinterpret_cast<const float4v *>(f + off) : zero4;
-                    dv[r][h] = ok ? *reinterpret_cast<const float4v *>(df + off) : zero4;
-                }
+                    for (int h = 0; h < 2; ++h) {
+                        const size_t off = (size_t)(i0 + r0 + rb + r) * J + jc[h];
+                        fv[r][h] = *reinterpret_cast<const float4v *>(f + off);
+                        dv[r][h] = *reinterpret_cast<const float4v *>(df + off);
+                    }
+            } else {
+#pragma unroll
+                for (int r = 0; r < BWD_RB; ++r)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const bool ok = live[h] && (rb + r) < rows;
+                        const size_t off = (size_t)(i0 + r0 + rb + r) * J + jc[h];
+                        fv[r][h] = ok ? *reinterpret_cast<const float4v *>(f + off) : zero4;
+                        dv[r][h] = ok ? *reinterpret_cast<const float4v *>(df + off) : zero4;
+                    }
+            }
 #pragma unroll
             for (int r = 0; r < BWD_RB; ++r) {
                 float ai[K];
@@ -196,25 +219,22 @@ __global__ __launch_bounds__(256) void k_worked_backward(const float *__restrict
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const float g = dv[r][h][v] * fv[r][h][v];
-                        part[r][0] += g;
+                        part[r * RP] += g;
 #pragma unroll
-                        for (int k = 0; k < K; ++k) part[r][1 + k] = fmaf(g, bj[h][v][k], part[r][1 + k]);
-                        part[r][K + 1] = fmaf(g, nb[h][v], part[r][K + 1]);
+                        for (int k = 0; k < K; ++k) part[r * RP + 1 + k] = fmaf(g, bj[h][v][k], part[r * RP + 1 + k]);
+                        part[r * RP + K + 1] = fmaf(g, nb[h][v], part[r * RP + K + 1]);
                         tc[h][v] = fmaf(g, ci, tc[h][v]);
 #pragma unroll
                         for (int k = 0; k < K; ++k) Tc[h][v][k] = fmaf(g, ai[k], Tc[h][v][k]);
                     }
             }
-#pragma unroll
-            for (int r = 0; r < BWD_RB; ++r)
-#pragma unroll
-                for (int q = 0; q < RP; ++q) part[r][q] = wave_sum_lane63(part[r][q]);
+            wave_sum_lane63(part);
         }
         if (lane == 63) {
 #pragma unroll
             for (int r = 0; r < BWD_RB; ++r)
 #pragma unroll
-                for (int q = 0; q < RP; ++q) rows_out[q][r0 + rb + r] = part[r][q];
+                for (int q = 0; q < RP; ++q) rows_out[q][r0 + rb + r] = part[r * RP + q];
         }
     }
 
