@@ -67,36 +67,56 @@ __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const
     *sum = 0.0;
     if (!gather_prepare(P, beta, y)) return false;
     double acc = 0.0;
-    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t z0_hi) {
+    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
         // innermost run: offsets advance by a constant per step
         int64_t off[NA + 1];
         for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
         off[NA] = gather_offset(P, kSlotF, y, z);
-        const int32_t n = P.kappa == 0 ? 1 : z0_hi - z[0] + 1;
         for (int32_t it = 0; it < n; ++it) {
             T v[NA];
             for (int q = 0; q < NA; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
             const T fv = f[off[NA]], dfv = df[off[NA]];
             acc += (double)(dfv * body_douter<BODY, T>(fv, v) * body_dinner<BODY, T>(p, v));
-            for (int q = 0; q < NA; ++q) off[q] += P.offZ[q][0];
-            off[NA] += P.offZ[kSlotF][0];
+            for (int q = 0; q < NA; ++q) off[q] += P.offZ[q][0] * step;
+            off[NA] += P.offZ[kSlotF][0] * step;
         }
     });
     *sum = acc;
     return true;
 }
 
-// one thread per gradient element
+// How many terms element `lin` sums, roughly; 0 if it is masked out.
+__device__ __forceinline__ int64_t element_estimate(const GatherPlan &P, int lin) {
+    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
+    int t = lin;
+    for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+    if (!gather_prepare(P, beta, y)) return 0;
+    return gather_estimate(P, y);
+}
+
+// one thread per gradient element; an element with many terms (the masks can leave a few elements with all the
+// work, e.g. the diagonal of a matrix that is read on its diagonal only) is summed by the whole wavefront
 template <int BODY, typename T>
 __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int p, const ArgPtrs A,
                                                         const T *__restrict__ f, const T *__restrict__ df,
                                                         T *__restrict__ dx, int n, int accumulate) {
-    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lin >= n) return;
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
+    const bool inside = lin < n;
+    const bool heavy = inside && element_estimate(P, lin) >= kHeavyTerms;
+    double acc = 0.0;
+    bool live = false;
+    if (inside && !heavy) live = gather_element<BODY, T>(P, p, A, f, df, lin, 0, 1, &acc);
+    for (unsigned long long todo = __ballot(heavy); todo; todo &= todo - 1) {   // the same in every lane
+        const int src = __ffsll((long long)todo) - 1;
+        double part_sum;
+        gather_element<BODY, T>(P, p, A, f, df, __shfl(lin, src, 64), lane, 64, &part_sum);
+        const double total = wave_sum_all(part_sum);
+        if (lane == src) { acc = total; live = true; }
+    }
+    if (!inside) return;
     // accumulate != 0: a further occurrence of the same tensor adds to what the earlier launches stored
     // (same owner thread, launches ordered on the stream: still no atomics)
-    double acc;
-    if (!gather_element<BODY, T>(P, p, A, f, df, lin, 0, 1, &acc)) {
+    if (!live) {
         if (!accumulate) dx[lin] = T(0);
         return;
     }

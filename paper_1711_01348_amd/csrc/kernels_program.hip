@@ -146,17 +146,16 @@ __device__ __forceinline__ bool outer_element(const GatherPlan &P, const DevProg
     *sum = 0.0;
     if (!gather_prepare(P, beta, y)) return false;
     double acc = 0.0;
-    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t z0_hi) {
+    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
         int64_t off[kMaxArgs + 1];
         for (int q = 0; q < n_ops; ++q) off[q] = ((outer_mask >> q) & 1u) ? gather_offset(P, q, y, z) : 0;
         off[kMaxArgs] = gather_offset(P, kSlotF, y, z);
-        const int32_t n = P.kappa == 0 ? 1 : z0_hi - z[0] + 1;
         for (int32_t it = 0; it < n; ++it) {
             T v[kMaxArgs];
             for (int q = 0; q < n_ops; ++q) v[q] = ((outer_mask >> q) & 1u) ? static_cast<const T *>(A.p[q])[off[q]] : T(0);
             acc += (double)(df[off[kMaxArgs]] * prog_eval<T>(douter_p, v, s_ws[off[kMaxArgs]]));
-            for (int q = 0; q < n_ops; ++q) off[q] += ((outer_mask >> q) & 1u) ? P.offZ[q][0] : 0;
-            off[kMaxArgs] += P.offZ[kSlotF][0];
+            for (int q = 0; q < n_ops; ++q) off[q] += ((outer_mask >> q) & 1u) ? P.offZ[q][0] * step : 0;
+            off[kMaxArgs] += P.offZ[kSlotF][0] * step;
         }
     });
     *sum = acc;
@@ -209,17 +208,16 @@ __device__ __forceinline__ bool program_element(const GatherPlan &P, const DevPr
     *sum = 0.0;
     if (!gather_prepare(P, beta, y)) return false;
     double acc = 0.0;
-    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t z0_hi) {
+    gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
         int64_t off[kMaxArgs + 1];
         for (int q = 0; q < n_ops; ++q) off[q] = gather_offset(P, q, y, z);
         off[kMaxArgs] = gather_offset(P, kSlotF, y, z);
-        const int32_t n = P.kappa == 0 ? 1 : z0_hi - z[0] + 1;
         for (int32_t it = 0; it < n; ++it) {
             T v[kMaxArgs];
             for (int q = 0; q < n_ops; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
             acc += (double)(g[off[kMaxArgs]] * prog_eval<T>(dinner, v, T(0)));
-            for (int q = 0; q < n_ops; ++q) off[q] += P.offZ[q][0];
-            off[kMaxArgs] += P.offZ[kSlotF][0];
+            for (int q = 0; q < n_ops; ++q) off[q] += P.offZ[q][0] * step;
+            off[kMaxArgs] += P.offZ[kSlotF][0] * step;
         }
     });
     *sum = acc;
@@ -230,10 +228,28 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, const DevProg dinner, int n_ops,
                                                         const ArgPtrs A, const T *__restrict__ g,
                                                         T *__restrict__ dx, int n, int accumulate) {
-    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lin >= n) return;
-    double acc;
-    if (!program_element<T>(P, dinner, n_ops, A, g, lin, 0, 1, &acc)) {
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
+    const bool inside = lin < n;
+    bool heavy = false;
+    if (inside) {
+        int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
+        int t = lin;
+        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+        heavy = gather_prepare(P, beta, y) && gather_estimate(P, y) >= kHeavyTerms;
+    }
+    double acc = 0.0;
+    bool live = false;
+    if (inside && !heavy) live = program_element<T>(P, dinner, n_ops, A, g, lin, 0, 1, &acc);
+    // an element with many terms is summed by the whole wavefront (the masks can leave few elements with all the work)
+    for (unsigned long long todo = __ballot(heavy); todo; todo &= todo - 1) {
+        const int src = __ffsll((long long)todo) - 1;
+        double part_sum;
+        program_element<T>(P, dinner, n_ops, A, g, __shfl(lin, src, 64), lane, 64, &part_sum);
+        const double total = wave_sum_all(part_sum);
+        if (lane == src) { acc = total; live = true; }
+    }
+    if (!inside) return;
+    if (!live) {
         if (!accumulate) dx[lin] = T(0);
         return;
     }
