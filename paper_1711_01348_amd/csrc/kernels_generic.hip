@@ -99,10 +99,11 @@ __device__ __forceinline__ int64_t element_estimate(const GatherPlan &P, int lin
 template <int BODY, typename T>
 __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int p, const ArgPtrs A,
                                                         const T *__restrict__ f, const T *__restrict__ df,
-                                                        T *__restrict__ dx, int n, int accumulate) {
+                                                        T *__restrict__ dx, int n, int accumulate, int classify) {
     const int lin = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
     const bool inside = lin < n;
-    const bool heavy = inside && element_estimate(P, lin) >= kHeavyTerms;
+    // classify == 0: the whole expression has fewer terms than one heavy element would
+    const bool heavy = classify && inside && element_estimate(P, lin) >= kHeavyTerms;
     double acc = 0.0;
     bool live = false;
     if (inside && !heavy) live = gather_element<BODY, T>(P, p, A, f, df, lin, 0, 1, &acc);
@@ -167,7 +168,7 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
         else
             TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s,
                        pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
-                       static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
+                       static_cast<T *>(dx[p]), n, q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

@@ -227,11 +227,11 @@ __device__ __forceinline__ bool program_element(const GatherPlan &P, const DevPr
 template <typename T>
 __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, const DevProg dinner, int n_ops,
                                                         const ArgPtrs A, const T *__restrict__ g,
-                                                        T *__restrict__ dx, int n, int accumulate) {
+                                                        T *__restrict__ dx, int n, int accumulate, int classify) {
     const int lin = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
     const bool inside = lin < n;
     bool heavy = false;
-    if (inside) {
+    if (classify && inside) {   // classify == 0: the whole expression has fewer terms than one heavy element would
         int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
         int t = lin;
         for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
@@ -319,7 +319,7 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
         else
             TAD_LAUNCH("k_program_gather", (k_program_gather<T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
                        pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
-                       q != p ? 1 : 0);
+                       q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         if (!in_outer) continue;
         if (!pl.ap_outer[q].derived) return TAD_EINVAL;
