@@ -83,6 +83,12 @@ bool y_is_beta(const GatherPlan &g);
 int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt, uint32_t flags,
                 tad_plan **out);
 int body_arg_count(int body);
+// plan of occurrence `occ` of the tensor given as operand `arg`, and the operand slot of that occurrence
+const ArgPlan *get_arg(const tad_plan *plan, int arg, int occ, int *slot_out = nullptr);
+// Range of the linear form a . x over the rational relaxation of { lo <= x <= hi, extra conditions }; false if
+// the set is empty.  The integer range is inside [tmin, tmax].
+bool linear_form_range(const int64_t *a, int D, const int64_t *lo, const int64_t *hi, int E,
+                       const int64_t (*cons_in)[TAD_MAX_EXT + 1], int64_t &tmin, int64_t &tmax);
 // Pattern recognition of the specialised kernel families (device-independent; defined in families.cpp).
 void select_families(tad_plan &plan);
 }  // namespace tad

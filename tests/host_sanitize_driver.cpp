@@ -1,5 +1,5 @@
 // Host-only driver for the address / undefined-behaviour sanitizer run of the index planner
-// (tests/test_host_sanitizers.py builds it together with plan.cpp and families.cpp; no GPU code).
+// (tests/test_host_sanitizers.py builds it together with plan.cpp, derived.cpp and families.cpp; no GPU code).
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>

@@ -11,7 +11,7 @@ def test_planner_under_asan_ubsan(tmp_path):
     exe = str(tmp_path / "plan_sanitize")
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
            "-static-libasan", "-static-libubsan",
-           os.path.join(CSRC, "plan.cpp"), os.path.join(CSRC, "families.cpp"),
+           os.path.join(CSRC, "plan.cpp"), os.path.join(CSRC, "derived.cpp"), os.path.join(CSRC, "families.cpp"),
            os.path.join(ROOT, "tests", "host_sanitize_driver.cpp"), "-o", exe]
     subprocess.run(cmd, check=True)
     env = dict(os.environ)
