@@ -13,12 +13,12 @@
 
 namespace tad {
 
+// Sum of inner(values) over the summation box of function index `lin`, fp64.  `parts` cooperating threads share it:
+// thread `part` takes the terms part, part + parts, ... of the box in row-major order (last summation index
+// fastest), so that a wavefront reads neighbouring elements together.
 template <int BODY, typename T>
-__global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, const ArgPtrs A,
-                                                         T *__restrict__ f, int nf) {
+__device__ __forceinline__ double forward_sum(const ForwardPlan &P, const ArgPtrs &A, int lin, int part, int parts) {
     constexpr int NA = BodyTraits<BODY>::NA;
-    int lin = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lin >= nf) return;
     int32_t ext[kMaxExt];
     {
         int t = lin;
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, co
     }
     int32_t k[kMaxExt] = {0};
     double acc = 0.0;
-    for (;;) {
+    auto term = [&]() {
         if (forward_conditions(P, ext, k)) {   // a term outside the extra conditions is not part of the sum
             T v[NA];
             for (int p = 0; p < NA; ++p) {
@@ -43,6 +43,19 @@ __global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, co
             }
             acc += (double)body_inner<BODY, T>(v);
         }
+    };
+    if (parts > 1) {
+        int64_t total = 1;
+        for (int s = 0; s < P.n_sum; ++s) total *= P.sum_n[s];
+        for (int64_t t = part; t < total; t += parts) {
+            int64_t r = t;
+            for (int s = P.n_sum - 1; s >= 0; --s) { k[s] = (int32_t)(r % P.sum_n[s]); r /= P.sum_n[s]; }
+            term();
+        }
+        return acc;
+    }
+    for (;;) {
+        term();
         int s = P.n_sum - 1;
         for (; s >= 0; --s) {
             if (++k[s] < P.sum_n[s]) break;
@@ -50,7 +63,23 @@ __global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, co
         }
         if (s < 0) break;
     }
-    f[lin] = body_outer<BODY, T>((T)acc);
+    return acc;
+}
+
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, const ArgPtrs A,
+                                                         T *__restrict__ f, int nf) {
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= nf) return;
+    f[lin] = body_outer<BODY, T>((T)forward_sum<BODY, T>(P, A, lin, 0, 1));
+}
+
+// one block per function index (long sums)
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_forward_coop(const ForwardPlan P, const ArgPtrs A, T *__restrict__ f) {
+    __shared__ double red[4];
+    const double total = block_sum_256(forward_sum<BODY, T>(P, A, blockIdx.x, threadIdx.x, 256), red);
+    if (threadIdx.x == 0) f[blockIdx.x] = body_outer<BODY, T>((T)total);
 }
 
 // Gradient element `lin` of operand p: masks, then the terms of the z loops shared by `parts` threads.
@@ -150,8 +179,12 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     if (fout) {
         int nf = (int)pl.f_count;
-        TAD_LAUNCH("k_generic_forward", (k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd, A,
-                   static_cast<T *>(fout), nf);
+        if (use_cooperative_gather(nf, pl.terms_total))   // every function index sums many terms
+            TAD_LAUNCH("k_generic_forward_coop", (k_generic_forward_coop<BODY, T>), dim3(nf), dim3(256), 0, s, pl.fwd, A,
+                       static_cast<T *>(fout));
+        else
+            TAD_LAUNCH("k_generic_forward", (k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
+                       A, static_cast<T *>(fout), nf);
         return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
     }
     // the gradient of a tensor is the sum over its occurrences (Sec. 5.3): the first occurrence stores,

@@ -78,9 +78,11 @@ __device__ T prog_eval(const DevProg &P, const T *v, T s) {
 // sum over the summation box of inner(values) for one function index, fp64 accumulation; base[p] receives the
 // offset of operand p at the first summation index (for an operand that ignores the summation indices: its
 // offset at this function index)
+// `parts` cooperating threads share the sum: thread `part` takes the terms part, part + parts, ... of the box
+// in row-major order (last summation index fastest), so that a wavefront reads neighbouring elements together.
 template <typename T>
 __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_ops, const ArgPtrs &A, int lin,
-                            int64_t *base) {
+                            int64_t *base, int part = 0, int parts = 1) {
     int32_t ext[kMaxExt];
     {
         int t = lin;
@@ -94,7 +96,7 @@ __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_op
     }
     int32_t k[kMaxExt] = {0};
     double acc = 0.0;
-    for (;;) {
+    auto term = [&]() {
         if (forward_conditions(P, ext, k)) {   // a term outside the extra conditions is not part of the sum
             T v[kMaxArgs];
             for (int p = 0; p < n_ops; ++p) {
@@ -104,6 +106,19 @@ __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_op
             }
             acc += (double)prog_eval<T>(inner, v, T(0));
         }
+    };
+    if (parts > 1) {
+        int64_t total = 1;
+        for (int s = 0; s < P.n_sum; ++s) total *= P.sum_n[s];
+        for (int64_t t = part; t < total; t += parts) {
+            int64_t r = t;
+            for (int s = P.n_sum - 1; s >= 0; --s) { k[s] = (int32_t)(r % P.sum_n[s]); r /= P.sum_n[s]; }
+            term();
+        }
+        return acc;
+    }
+    for (;;) {
+        term();
         int s = P.n_sum - 1;
         for (; s >= 0; --s) {
             if (++k[s] < P.sum_n[s]) break;
@@ -125,6 +140,25 @@ __global__ __launch_bounds__(256) void k_program_forward(const ForwardPlan P, co
     if (lin >= nf) return;
     int64_t base[kMaxArgs];
     const T s = (T)inner_sum<T>(P, inner, n_ops, A, lin, base);
+    T v[kMaxArgs];
+    for (int p = 0; p < n_ops; ++p) v[p] = ((outer_mask >> p) & 1u) ? static_cast<const T *>(A.p[p])[base[p]] : T(0);
+    const T o = prog_eval<T>(outer, v, s);
+    out[lin] = df ? df[lin] * o : o;
+    if (s_out) s_out[lin] = s;
+}
+
+// the same with one block per function index (long sums): the 256 threads share the sum
+template <typename T>
+__global__ __launch_bounds__(256) void k_program_forward_coop(const ForwardPlan P, const DevProg inner, const DevProg outer,
+                                                              int n_ops, uint32_t outer_mask, const ArgPtrs A,
+                                                              const T *__restrict__ df, T *__restrict__ out,
+                                                              T *__restrict__ s_out) {
+    __shared__ double red[4];
+    const int lin = blockIdx.x;
+    int64_t base[kMaxArgs];
+    const double mine = inner_sum<T>(P, inner, n_ops, A, lin, base, threadIdx.x, 256);
+    const T s = (T)block_sum_256(mine, red);
+    if (threadIdx.x != 0) return;
     T v[kMaxArgs];
     for (int p = 0; p < n_ops; ++p) v[p] = ((outer_mask >> p) & 1u) ? static_cast<const T *>(A.p[p])[base[p]] : T(0);
     const T o = prog_eval<T>(outer, v, s);
@@ -279,9 +313,14 @@ static int fwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
     ArgPtrs A{};
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     const int nf = (int)pl.f_count;
-    TAD_LAUNCH("k_program_forward", (k_program_forward<T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
-               pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
-               static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out), nf);
+    if (use_cooperative_gather(nf, pl.terms_total))   // every function index sums many terms
+        TAD_LAUNCH("k_program_forward_coop", (k_program_forward_coop<T>), dim3(nf), dim3(256), 0, s, pl.fwd,
+                   pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
+                   static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out));
+    else
+        TAD_LAUNCH("k_program_forward", (k_program_forward<T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
+                   pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
+                   static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out), nf);
     return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
 }
 

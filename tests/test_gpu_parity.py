@@ -151,6 +151,25 @@ def test_random_expressions(seed):
     assert_parity(wp, f, grads, f_ref, g_ref, "random %d as program" % seed)
 
 
+LONG_SUMS = [
+    ("matmul_f64", lambda: wl.matmul_expr(12, 9, 1500, "f64")),                       # plan-driven kernels (fp64)
+    ("matmul_program_f32", lambda: wl.as_program(wl.matmul_expr(10, 7, 1300, "f32", True, False))),
+    ("cumsum_exp_f64", lambda: wl.cumulative_sum_expr(1500, "f64")),                  # a condition on every term
+    ("two_sums_f32", lambda: _expr("exp", (5,), [(0, 39), (1, 40)], [("x", (60, 45), [[1, 1, 0], [0, 0, 1]])], "f32")),
+    ("dense_layer_f64", lambda: wl.dense_layer_expr(6, 5, 1100, "f64")),              # outer operand, long sum
+]
+
+
+@pytest.mark.parametrize("name,make", LONG_SUMS, ids=[c[0] for c in LONG_SUMS])
+def test_long_sums_per_function_index(name, make):
+    """At least 1024 terms per function index: the forward kernels give one block to every function index."""
+    e = make()
+    w = wl.random_inputs(e, 41, -0.05, 0.05) if "exp" in name or name.startswith("two") else wl.random_inputs(e, 41)
+    f_ref, g_ref = oracle_all(w, 4)
+    plan, f, grads = run_gpu(w)
+    assert_parity(w, f, grads, f_ref, g_ref, name)
+
+
 def test_backward_is_deterministic_and_skips_unwanted():
     import torch
     w = wl.config3("small")
@@ -526,6 +545,7 @@ DERIVED = [
     # outer functions: seed expression, then the derived one; operands of the outer function: a second part
     ("worked_f64", lambda: wl.worked_expr(19, 23, 5, "f64")),
     ("worked_f32", lambda: wl.worked_expr(40, 52, 5, "f32")),
+    ("worked_wide_f64", lambda: wl.worked_expr(9, 1100, 3, "f64")),      # derived expressions with long sums
     ("cumsum_exp_f64", lambda: wl.cumulative_sum_expr(200, "f64")),
     ("dense_layer_f32", lambda: wl.dense_layer_expr(300, 12, 9, "f32")),
     ("gated_gauss_f64", lambda: wl.gated_gauss_expr(21, 17, 4, "f64")),
