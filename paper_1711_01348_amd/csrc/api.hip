@@ -22,7 +22,7 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
     case TAD_FAMILY_DIAGONAL:
     case TAD_FAMILY_ANTIDIAGONAL: return pattern_forward(*plan, args_dev, f_dev, s);
     case TAD_FAMILY_STRIDED: return strided_forward(*plan, args_dev, f_dev, s);
-    case TAD_FAMILY_CONTRACTION: return contract_forward(*plan, args_dev, f_dev, s);
+    case TAD_FAMILY_CONTRACTION: return contract_forward(*plan, args_dev, f_dev, ws_dev, s);
     case TAD_FAMILY_PROGRAM: return program_forward(*plan, args_dev, f_dev, s);
     default: return TAD_EUNSUPPORTED;
     }
@@ -52,7 +52,7 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
     case TAD_FAMILY_DIAGONAL:
     case TAD_FAMILY_ANTIDIAGONAL: return pattern_backward(*plan, args_dev, df_dev, dx_dev, ws_dev, s);
     case TAD_FAMILY_STRIDED: return strided_backward(*plan, args_dev, f_dev, df_dev, dx_dev, ws_dev, s);
-    case TAD_FAMILY_CONTRACTION: return contract_backward(*plan, args_dev, df_dev, dx_dev, s);
+    case TAD_FAMILY_CONTRACTION: return contract_backward(*plan, args_dev, df_dev, dx_dev, ws_dev, s);
     case TAD_FAMILY_PROGRAM: return program_backward(*plan, args_dev, df_dev, dx_dev, ws_dev, s);
     default: return TAD_EUNSUPPORTED;
     }

@@ -293,6 +293,20 @@ static bool match_contraction(tad_plan &pl) {
     // gradient of Q in its own memory order
     if (q_kj) g[2] = GemmDesc{Kc, J, I, P, -1, Q, ldp, J, p_ik, 0};       // dQ[k][j] = sum_i P(i,k) df[i][j]
     else      g[2] = GemmDesc{J, Kc, I, -1, P, Q, J, ldp, 1, !p_ik};      // dQ[j][k] = sum_i df[i][j] P(i,k)
+    // A product with few output tiles and a long contraction index leaves most of the chip idle: cut the index
+    // into pieces for separate workgroups (partial products in the workspace, added in a fixed order afterwards).
+    size_t ws = 0;
+    for (int q = 0; q < 3; ++q) {
+        const long long tiles = (long long)((g[q].M + 127) / 128) * ((g[q].N + 127) / 128);
+        int sp = 1;
+        if (tiles < 256 && g[q].Kc >= 512) {
+            sp = (int)std::min<long long>((512 + tiles - 1) / tiles, g[q].Kc / 256);
+            sp = std::max(1, std::min(sp, 256));
+        }
+        g[q].splits = sp;
+        if (sp > 1) ws = std::max(ws, align256((size_t)sp * g[q].M * g[q].N * sizeof(float)));
+    }
+    pl.ws_bytes = ws;
     pl.fwd_family = TAD_FAMILY_CONTRACTION;
     pl.ap[0].family = pl.ap[1].family = TAD_FAMILY_CONTRACTION;
     return true;
@@ -311,8 +325,9 @@ void select_families(tad_plan &plan) {
         // a plain product of two matrices (the form the derived expressions of a matrix product have) still
         // belongs on the matrix cores
         if (!(plan.flags & TAD_PLAN_GENERIC_ONLY) && !plan.has_alias && plan.expr.n_constraints == 0 &&
-            match_contraction(plan))
-            plan.ws_bytes = 0;
+            match_contraction(plan)) {
+            // the matcher has set the family and the workspace of the products
+        }
         return;
     }
     if ((plan.flags & TAD_PLAN_GENERIC_ONLY) || plan.has_alias || plan.expr.n_constraints > 0) return;

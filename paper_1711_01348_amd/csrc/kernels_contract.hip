@@ -12,7 +12,9 @@
 //   AT = false: A(m, k) = a[m * lda + k]      AT = true: A(m, k) = a[k * lda + m]
 //   BT = false: B(k, n) = b[k * ldb + n]      BT = true: B(k, n) = b[n * ldb + k]
 // Block tile 128 x 128, four waves of 64 x 64 (2 x 2 MFMA tiles), contraction tile 32, global -> register -> LDS
-// staging with the loads of the next tile in flight during the MFMAs of the current one.
+// staging with the loads of the next tile in flight during the MFMAs of the current one.  A product with few
+// output tiles and a long contraction index is cut along that index (blockIdx.y): every piece writes its partial
+// product to the workspace and k_contract_reduce adds the pieces in a fixed order.
 //
 // MFMA operand layout (wave64): A operand lane l = A[m = l % 32][k = l / 32], B operand lane l = B[k = l / 32][n = l % 32],
 // result register r of lane l = D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32].
@@ -49,7 +51,7 @@ __device__ __forceinline__ void tile_of_block(int gm, int gn, int &tm, int &tn) 
 template <bool AT, bool BT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_contract(const float *__restrict__ a, const float *__restrict__ b, float *__restrict__ c, int M, int N, int Kc,
-                int lda, int ldb, int gm, int gn) {
+                int lda, int ldb, int gm, int gn, int chunk) {
     __shared__ __attribute__((aligned(16))) float smem[2 * CT_TILE];   // A tile, B tile; reused as the output stage in the epilogue
     float *As = smem, *Bs = smem + CT_TILE;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -57,6 +59,10 @@ void k_contract(const float *__restrict__ a, const float *__restrict__ b, float 
     int tm, tn;
     tile_of_block(gm, gn, tm, tn);
     const int m0 = tm * 128, n0 = tn * 128;
+    // this workgroup's piece of the contraction index (chunk is a multiple of the tile; one piece: chunk >= Kc)
+    const int kb = blockIdx.y * chunk;
+    Kc = min(Kc, kb + chunk);
+    c += (size_t)blockIdx.y * M * N;
     float16c acc[2][2];
 #pragma unroll
     for (int x = 0; x < 2; ++x)
@@ -122,8 +128,8 @@ void k_contract(const float *__restrict__ a, const float *__restrict__ b, float 
         const int n = wn * 64 + 32 * half + mrow;
         return BT ? Bs[n * CT_LDK + kk + kof] : Bs[(kk + kof) * CT_LDM + n];
     };
-    gload(0);
-    for (int k0 = 0; k0 < Kc; k0 += CT_KT) {
+    gload(kb);
+    for (int k0 = kb; k0 < Kc; k0 += CT_KT) {
         stage();
         __syncthreads();
         if (k0 + CT_KT < Kc) gload(k0 + CT_KT);
@@ -174,33 +180,56 @@ void k_contract(const float *__restrict__ a, const float *__restrict__ b, float 
     }
 }
 
-static int launch_gemm(const GemmDesc &g, const float *a, const float *b, float *c, hipStream_t s) {
+// c[i] = sum over the pieces of part[piece * n + i], pieces added in ascending order (n is a multiple of 4)
+__global__ __launch_bounds__(256) void k_contract_reduce(const float *__restrict__ part, float *__restrict__ c,
+                                                         long long n4, int pieces) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const float4c *src = reinterpret_cast<const float4c *>(part);
+    float4c acc = src[i];
+    for (int p = 1; p < pieces; ++p) acc += src[(long long)p * n4 + i];
+    reinterpret_cast<float4c *>(c)[i] = acc;
+}
+
+static int launch_gemm(const GemmDesc &g, const float *a, const float *b, float *c, float *ws, hipStream_t s) {
     const int gm = (g.M + 127) / 128, gn = (g.N + 127) / 128;
-    const dim3 grid(gm * gn), block(256);
+    const int pieces = (g.splits > 1 && ws) ? g.splits : 1;
+    // whole tiles per piece; the last piece may be shorter, none is empty
+    const int chunk = pieces > 1 ? ((g.Kc + pieces - 1) / pieces + CT_KT - 1) / CT_KT * CT_KT : g.Kc;
+    const int used = pieces > 1 ? (g.Kc + chunk - 1) / chunk : 1;
+    const dim3 grid(gm * gn, used), block(256);
+    float *dst = used > 1 ? ws : c;
     if (!g.at && !g.bt)
-        TAD_LAUNCH("k_contract", (k_contract<false, false>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
+        TAD_LAUNCH("k_contract", (k_contract<false, false>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
     else if (!g.at && g.bt)
-        TAD_LAUNCH("k_contract", (k_contract<false, true>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
+        TAD_LAUNCH("k_contract", (k_contract<false, true>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
     else if (g.at && !g.bt)
-        TAD_LAUNCH("k_contract", (k_contract<true, false>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
+        TAD_LAUNCH("k_contract", (k_contract<true, false>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
     else
-        TAD_LAUNCH("k_contract", (k_contract<true, true>), grid, block, 0, s, a, b, c, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn);
-    return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+        TAD_LAUNCH("k_contract", (k_contract<true, true>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
+    if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    if (used > 1) {
+        const long long n4 = (long long)g.M * g.N / 4;
+        TAD_LAUNCH("k_contract_reduce", k_contract_reduce, dim3((unsigned)((n4 + 255) / 256)), block, 0, s, ws, c, n4, used);
+        if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+    }
+    return TAD_OK;
 }
 
 // source -1 of a product is df, destination -1 is f
-int contract_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s) {
+int contract_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s) {
     const GemmDesc &g = pl.fast.gemm[0];
-    return launch_gemm(g, (const float *)args[g.a_src], (const float *)args[g.b_src], (float *)f, s);
+    return launch_gemm(g, (const float *)args[g.a_src], (const float *)args[g.b_src], (float *)f, (float *)ws, s);
 }
 
-int contract_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, hipStream_t s) {
+int contract_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
+                      hipStream_t s) {
     for (int q = 1; q <= 2; ++q) {
         const GemmDesc &g = pl.fast.gemm[q];
         if (!dx[g.out]) continue;
         const float *a = g.a_src < 0 ? (const float *)df : (const float *)args[g.a_src];
         const float *b = g.b_src < 0 ? (const float *)df : (const float *)args[g.b_src];
-        const int rc = launch_gemm(g, a, b, (float *)dx[g.out], s);
+        const int rc = launch_gemm(g, a, b, (float *)dx[g.out], (float *)ws, s);   // the products share the workspace in turn
         if (rc) return rc;
     }
     return TAD_OK;

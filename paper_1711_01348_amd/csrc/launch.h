@@ -29,8 +29,9 @@ int strided_forward(const tad_plan &pl, const void *const *args, void *f, hipStr
 int strided_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
                      void *const *dx, void *ws, hipStream_t s);
 
-int contract_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
-int contract_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, hipStream_t s);
+int contract_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s);
+int contract_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
+                      hipStream_t s);
 
 int program_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
 int program_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,

@@ -31,6 +31,7 @@ struct GemmDesc {
     int a_src = 0, b_src = 0, out = 0;
     int lda = 0, ldb = 0;
     int at = 0, bt = 0;
+    int splits = 1;   // pieces of the contraction index computed by separate workgroups (few output tiles, long sum)
 };
 
 // Parameters of the specialised kernel families (filled by pattern recognition).

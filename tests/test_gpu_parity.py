@@ -375,6 +375,31 @@ def test_contraction_family_all_memory_orders(xt, yt, sw):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("I,J,K,xt,yt", [(128, 256, 4096, False, False), (64, 68, 8192, True, False),
+                                          (132, 60, 2100, False, True), (4096, 64, 96, False, False)])
+def test_contraction_with_a_split_summation_index(I, J, K, xt, yt):
+    """Few output tiles and a long summation index (or, in the gradients, a long collapsed function index): the
+    index is cut into pieces for separate workgroups; against the fp64 matrix products."""
+    import torch
+    from paper_1711_01348_amd import binding as B
+    e = wl.matmul_expr(I, J, K, "f32", xt, yt)
+    w = wl.random_inputs(e, 23)
+    plan = B.Plan(e)
+    assert plan.forward_family == "contraction" and plan.workspace_bytes > 0
+    x, y = w.arg_list()
+    args = [_to_dev(x), _to_dev(y)]
+    f = plan.forward(args)
+    dx, dy = plan.backward(args, f, _to_dev(w.df))
+    torch.cuda.synchronize()
+    X = (x.T if xt else x).astype(np.float64)
+    Y = (y.T if yt else y).astype(np.float64)
+    D = w.df.astype(np.float64)
+    gx, gy = D @ Y.T, X.T @ D
+    for got, ref, what in ((f, X @ Y, "f"), (dx, gx.T if xt else gx, "dx"), (dy, gy.T if yt else gy, "dy")):
+        got = got.cpu().numpy()
+        assert check.within(got, ref, "f32"), (what, check.errors(got, ref))
+
+
 def test_contraction_full_size_against_sampled_rows():
     """4096^3 product: the oracle computes sampled rows of f, dx and dy one by one (fp64 dot products)."""
     w = wl.matmul_workload(4096)
