@@ -12,7 +12,9 @@
 //   AT = false: A(m, k) = a[m * lda + k]      AT = true: A(m, k) = a[k * lda + m]
 //   BT = false: B(k, n) = b[k * ldb + n]      BT = true: B(k, n) = b[n * ldb + k]
 // Block tile 128 x 128, four waves of 64 x 64 (2 x 2 MFMA tiles), contraction tile 32, global -> register -> LDS
-// staging with the loads of the next tile in flight during the MFMAs of the current one.  A product with few
+// staging.  Two sets of tiles in LDS: while the MFMAs of tile t read one set, the registers holding tile t + 1 are
+// written to the other set and the global loads of tile t + 2 go out, all of it between MFMA groups, so that one
+// barrier per tile remains and no wave stands idle while a tile is staged.  A product with few
 // output tiles and a long contraction index is cut along that index (blockIdx.y): every piece writes its partial
 // product to the workspace and k_contract_reduce adds the pieces in a fixed order.
 //
@@ -52,8 +54,7 @@ template <bool AT, bool BT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_contract(const float *__restrict__ a, const float *__restrict__ b, float *__restrict__ c, int M, int N, int Kc,
                 int lda, int ldb, int gm, int gn, int chunk) {
-    __shared__ __attribute__((aligned(16))) float smem[2 * CT_TILE];   // A tile, B tile; reused as the output stage in the epilogue
-    float *As = smem, *Bs = smem + CT_TILE;
+    __shared__ __attribute__((aligned(16))) float smem[4 * CT_TILE];   // two sets of (A tile, B tile); reused as the output stage in the epilogue
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     int tm, tn;
@@ -97,7 +98,8 @@ void k_contract(const float *__restrict__ a, const float *__restrict__ b, float 
             }
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int set) {
+        float *As = smem + set * (2 * CT_TILE), *Bs = As + CT_TILE;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int idx = tid + 256 * p;
@@ -120,30 +122,37 @@ void k_contract(const float *__restrict__ a, const float *__restrict__ b, float 
         }
     };
     const int mrow = lane & 31, kof = lane >> 5;
-    auto afrag = [&](int kk, int half) -> float {
+    auto afrag = [&](int set, int kk, int half) -> float {
+        const float *As = smem + set * (2 * CT_TILE);
         const int m = wm * 64 + 32 * half + mrow;
         return AT ? As[(kk + kof) * CT_LDM + m] : As[m * CT_LDK + kk + kof];
     };
-    auto bfrag = [&](int kk, int half) -> float {
+    auto bfrag = [&](int set, int kk, int half) -> float {
+        const float *Bs = smem + set * (2 * CT_TILE) + CT_TILE;
         const int n = wn * 64 + 32 * half + mrow;
         return BT ? Bs[n * CT_LDK + kk + kof] : Bs[(kk + kof) * CT_LDM + n];
     };
     gload(kb);
-    for (int k0 = kb; k0 < Kc; k0 += CT_KT) {
-        stage();
-        __syncthreads();
-        if (k0 + CT_KT < Kc) gload(k0 + CT_KT);
+    stage(0);
+    __syncthreads();
+    if (kb + CT_KT < Kc) gload(kb + CT_KT);
+    int set = 0;
+    for (int k0 = kb; k0 < Kc; k0 += CT_KT, set ^= 1) {
         // the operands of step ks + 1 are read from LDS before the MFMAs of step ks are issued
-        float a0 = afrag(0, 0), a1 = afrag(0, 1), b0 = bfrag(0, 0), b1 = bfrag(0, 1);
+        float a0 = afrag(set, 0, 0), a1 = afrag(set, 0, 1), b0 = bfrag(set, 0, 0), b1 = bfrag(set, 0, 1);
 #pragma unroll
         for (int ks = 0; ks < CT_KT / 2; ++ks) {
             float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
             if (ks + 1 < CT_KT / 2) {
-                na0 = afrag(2 * ks + 2, 0);
-                na1 = afrag(2 * ks + 2, 1);
-                nb0 = bfrag(2 * ks + 2, 0);
-                nb1 = bfrag(2 * ks + 2, 1);
+                na0 = afrag(set, 2 * ks + 2, 0);
+                na1 = afrag(set, 2 * ks + 2, 1);
+                nb0 = bfrag(set, 2 * ks + 2, 0);
+                nb1 = bfrag(set, 2 * ks + 2, 1);
             }
+            // between MFMA groups: tile t + 1 goes from the registers to the other set (nobody reads that set any
+            // more: the barrier at the end of tile t - 1), then the loads of tile t + 2 go out
+            if (ks == 1 && k0 + CT_KT < Kc) stage(set ^ 1);
+            if (ks == 3 && k0 + 2 * CT_KT < Kc) gload(k0 + 2 * CT_KT);
             __builtin_amdgcn_sched_barrier(0);
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
@@ -157,7 +166,7 @@ void k_contract(const float *__restrict__ a, const float *__restrict__ b, float 
     // epilogue: each wave stages 32 x 64 results at a time in its own quarter of the tile memory (32 rows of 66
     // floats) and writes them as 16-byte stores, 256 bytes per row.  The last barrier of the loop guarantees that
     // nobody still reads the tiles; a wave reads back only what it wrote itself.
-    static_assert(4 * 32 * 66 <= 2 * CT_TILE, "output stage does not fit in the tile memory");
+    static_assert(4 * 32 * 66 <= 4 * CT_TILE, "output stage does not fit in the tile memory");
     float *out = smem + wave * (32 * 66);
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
