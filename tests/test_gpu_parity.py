@@ -476,6 +476,21 @@ def test_worked_family_every_short_sum_length(K):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("I,J,K", [(256, 512, 5), (512, 1024, 3), (768, 512, 4), (512, 1536, 5), (512, 1024, 6),
+                                   (512, 1024, 2)])
+def test_worked_family_whole_tiles(I, J, K):
+    """Shapes made of whole backward tiles (256 rows x 512 columns): for some lengths of the summed index the
+    backward pass then streams df and f through LDS instead of registers; one tile, several tiles each way."""
+    e = wl.worked_expr(I, J, K, "f32")
+    w = wl.random_inputs(e, 60 + K, -0.8, 0.8)
+    w.inputs["c"] = np.abs(w.inputs["c"]) * np.float32(0.5)
+    f_ref, g_ref = oracle_all(w, 4)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "worked"
+    assert_parity(w, f, grads, f_ref, g_ref, "%dx%dx%d" % (I, J, K))
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("I,J,K", [(70, 132, 32), (129, 260, 96), (64, 64, 64)])
 def test_mfma_family_other_shapes(I, J, K):
     """Long summed index (a multiple of 32): matrix-core kernels on ragged tiles and on exactly one tile."""
