@@ -329,6 +329,15 @@ int tad_plan_forward_family(const tad_plan *plan);
  * Errors: EINVAL (not a program plan, bad `which`, NULL).
  */
 int tad_plan_program_eval(const tad_plan *plan, int which, const double *values, double sum, double *out);
+/*
+ * Number of registers of the register form of one of those programs (`which` as above): the kernels keep a
+ * program's temporaries in that many vector registers per term and interpret several terms per pass (Sec. 2:
+ * the derivative is again a computational graph; its live values decide the registers).  *registers_out = 0:
+ * more live values than the register form holds; the kernels then interpret the form with one temporary per
+ * operation in the thread's private memory.  Also 0 for a program that is identically zero.
+ * Errors: EINVAL (not a program plan, bad `which`, derivative not planned, NULL).
+ */
+int tad_plan_program_registers(const tad_plan *plan, int which, int *registers_out);
 
 int tad_extended_gcd(int64_t a, int64_t b, int64_t *g, int64_t *x, int64_t *y);
 int tad_smith_normal_form(const int64_t *A, int n, int m, int64_t *S, int64_t *U, int64_t *V, int *rank);

@@ -30,7 +30,7 @@ ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
            "tad_plan_bound_row", "tad_plan_enumerate", "tad_plan_count_all", "tad_eval_forward",
-           "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval",
+           "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval", "tad_plan_program_registers",
            "tad_plan_derived_expr", "tad_plan_seed_expr"]
 
 
@@ -96,6 +96,7 @@ def _load():
                                       ctypes.c_size_t, vp]
     lib.tad_plan_forward_family.argtypes = [vp]
     lib.tad_plan_program_eval.argtypes = [vp, ctypes.c_int, vp, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
+    lib.tad_plan_program_registers.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
     lib.tad_plan_derived_expr.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(TadExpr),
                                           ctypes.POINTER(TadArg), ctypes.POINTER(ctypes.c_int),
                                           ctypes.POINTER(ctypes.c_int)]
@@ -251,6 +252,13 @@ class Plan:
         _check(lib.tad_plan_program_eval(self._h, which, None if v is None else v.ctypes.data, float(total),
                                          ctypes.byref(out)), "tad_plan_program_eval")
         return out.value
+
+    def program_registers(self, which: int) -> int:
+        """Registers of the register form of a derived scalar program (`which` as in program_eval); 0: the
+        kernels interpret the form with one temporary per operation (or the program is identically zero)."""
+        n = ctypes.c_int(0)
+        _check(lib.tad_plan_program_registers(self._h, which, ctypes.byref(n)), "tad_plan_program_registers")
+        return n.value
 
     def _unpack_expr(self, e, a, n, names):
         from .workloads import ArgSpec, ExprSpec

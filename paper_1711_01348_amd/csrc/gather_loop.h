@@ -18,52 +18,67 @@ namespace tad {
 
 template <class Run>
 __device__ __forceinline__ void gather_loops(const GatherPlan &P, const int32_t *y, int part, int parts, Run &&run) {
+    // `run` is expanded in line: the walk below is arranged so that it is called from one place only
     int32_t z[kMaxKernel] = {0, 0, 0, 0}, hi[kMaxKernel] = {0, 0, 0, 0};
-    if (P.kappa == 0) {
-        if (part == 0) run(z, 1, 1);   // a single term: z is empty
-        return;
-    }
     const int top = P.kappa - 1;
-    gather_bounds(P, top, y, z, z[top], hi[top]);
+    bool single = false;       // exactly one run: no coordinate at all, or one coordinate shared by the threads
     bool share_runs = false;   // the same for all cooperating threads: the top range depends on the element only
-    if (parts > 1) {
-        if (top == 0) {
-            const int64_t first = (int64_t)z[0] + part;
-            if (first > hi[0]) return;
-            z[0] = (int32_t)first;
-            run(z, (int32_t)((hi[0] - first) / parts + 1), parts);
-            return;
-        } else if (((int64_t)hi[top] - z[top] + 1) * 8 >= parts) {
-            z[top] += part;
-        } else {
-            share_runs = true;
+    int32_t count = 1, step = 1;
+    int step_top = 1;
+    if (P.kappa == 0) {
+        if (part != 0) return;   // a single term: z is empty
+        single = true;
+    } else {
+        gather_bounds(P, top, y, z, z[top], hi[top]);
+        if (parts > 1) {
+            if (top == 0) {
+                const int64_t first = (int64_t)z[0] + part;
+                if (first > hi[0]) return;
+                z[0] = (int32_t)first;
+                count = (int32_t)((hi[0] - first) / parts + 1);
+                step = parts;
+                single = true;
+            } else if (((int64_t)hi[top] - z[top] + 1) * 8 >= parts) {
+                z[top] += part;
+                step_top = parts;
+            } else {
+                share_runs = true;
+            }
         }
     }
-    const int step_top = (parts > 1 && top > 0 && !share_runs) ? parts : 1;
     int turn = 0;   // whose turn it is to take a short run
     int lvl = top;
     for (;;) {
-        if (z[lvl] > hi[lvl]) {
-            if (++lvl > top) break;
-            z[lvl] += lvl == top ? step_top : 1;
-            continue;
-        }
-        if (lvl == 0) {
-            const int32_t len = hi[0] - z[0] + 1;   // >= 1 here
-            if (!share_runs) {
-                run(z, len, 1);
-            } else if (len >= parts) {
-                z[0] += part;
-                run(z, (hi[0] - z[0]) / parts + 1, parts);
-            } else {
-                if (turn == part) run(z, len, 1);
-                turn = turn + 1 == parts ? 0 : turn + 1;
+        bool mine = true;
+        if (!single) {
+            // walk to the next innermost run
+            for (;;) {
+                if (z[lvl] > hi[lvl]) {
+                    if (++lvl > top) return;
+                    z[lvl] += lvl == top ? step_top : 1;
+                } else if (lvl == 0) {
+                    break;
+                } else {
+                    --lvl;
+                    gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
+                }
             }
-            z[0] = hi[0] + 1;
-        } else {
-            --lvl;
-            gather_bounds(P, lvl, y, z, z[lvl], hi[lvl]);
+            count = hi[0] - z[0] + 1;   // >= 1 here
+            step = 1;
+            if (share_runs) {
+                if (count >= parts) {
+                    z[0] += part;
+                    count = (hi[0] - z[0]) / parts + 1;
+                    step = parts;
+                } else {
+                    mine = turn == part;
+                    turn = turn + 1 == parts ? 0 : turn + 1;
+                }
+            }
         }
+        if (mine) run(z, count, step);
+        if (single) return;
+        z[0] = hi[0] + 1;
     }
 }
 

@@ -39,10 +39,29 @@ template <> struct Fn<double> {
     static __device__ __forceinline__ double sqrt_(double x) { return sqrt(x); }
 };
 
-// One pass over the operations; temporaries live in the thread's private memory.
 template <typename T>
-__device__ T prog_eval(const DevProg &P, const T *v, T s) {
-    if (P.result < 0) return T(0);
+__device__ __forceinline__ T prog_unary(int op, T x, int k) {
+    switch (op) {
+    case P_NEG: return -x;
+    case P_EXP: return Fn<T>::exp_(x);
+    case P_LOG: return Fn<T>::log_(x);
+    case P_SIN: return Fn<T>::sin_(x);
+    case P_COS: return Fn<T>::cos_(x);
+    case P_TANH: return Fn<T>::tanh_(x);
+    case P_SQRT: return Fn<T>::sqrt_(x);
+    case P_POWI: {
+        T r = x;
+        for (int e = 1; e < k; ++e) r *= x;
+        return r;
+    }
+    default: return T(0);
+    }
+}
+
+// One pass over the operations of the form with one temporary per operation; the temporaries live in the
+// thread's private memory (programs whose live values do not fit the register form).
+template <typename T>
+__device__ __forceinline__ T prog_eval_temporaries(const DevProg &P, const T *v, T s) {
     T t[kMaxProgOps];
     for (int i = 0; i < P.n; ++i) {
         const int a = P.a[i], b = P.b[i];
@@ -55,24 +74,139 @@ __device__ T prog_eval(const DevProg &P, const T *v, T s) {
         case P_SUB: r = t[a] - t[b]; break;
         case P_MUL: r = t[a] * t[b]; break;
         case P_DIV: r = t[a] / t[b]; break;
-        case P_NEG: r = -t[a]; break;
-        case P_EXP: r = Fn<T>::exp_(t[a]); break;
-        case P_LOG: r = Fn<T>::log_(t[a]); break;
-        case P_SIN: r = Fn<T>::sin_(t[a]); break;
-        case P_COS: r = Fn<T>::cos_(t[a]); break;
-        case P_TANH: r = Fn<T>::tanh_(t[a]); break;
-        case P_SQRT: r = Fn<T>::sqrt_(t[a]); break;
-        case P_POWI: {
-            const T x = t[a];
-            r = x;
-            for (int e = 1; e < P.k[i]; ++e) r *= x;
-            break;
-        }
-        default: r = T(0);
+        default: r = prog_unary<T>(P.op[i], t[a], P.k[i]);
         }
         t[i] = r;
     }
     return t[P.result];
+}
+
+// The register form, for U terms at once: kProgRegs values per term in vector registers, addressed by the
+// wave-uniform register numbers of the operation words (every lane runs the same program, so the words are
+// scalar loads from the kernel arguments; the next word is fetched while the current operation runs).  Fetching
+// and decoding an operation costs more than carrying it out: U terms share that cost.  One array per term: an
+// array of kProgRegs values indexed by a uniform number stays in registers, a two-dimensional one does not.
+template <typename T> struct ProgWidth { static constexpr int U = sizeof(T) == 4 ? 4 : 2; };   // terms per pass
+
+// REGS chooses the form at compile time: a kernel holds one of the two, so that the kernels of the register
+// form need no private memory at all (the runtime sets private memory up per launch, and slowly once a kernel asks
+// for much of it).  The kernels below are built in three forms (template parameter FORM): 0 one temporary per
+// operation, one term per pass; 1 registers, one term per pass (elements with one or two terms: several terms per
+// pass would only cost registers, i.e. waves per SIMD); 2 registers, ProgWidth<T>::U terms per pass.
+template <typename T, int U, bool REGS>
+__device__ __forceinline__ void prog_eval_block(const DevProg &P, const T (&v)[kMaxArgs][U], const T (&s)[U], T (&out)[U]) {
+    static_assert(U >= 1 && U <= 4, "one register array per term below");
+    if (P.result < 0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) out[u] = T(0);
+        return;
+    }
+    if (!REGS) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            T col[kMaxArgs];
+#pragma unroll
+            for (int q = 0; q < kMaxArgs; ++q) col[q] = v[q][u];
+            out[u] = prog_eval_temporaries<T>(P, col, s[u]);
+        }
+        return;
+    }
+    T r0[kProgRegs], r1[kProgRegs], r2[kProgRegs], r3[kProgRegs];
+#pragma unroll
+    for (int q = 0; q < kProgRegs; ++q) r0[q] = r1[q] = r2[q] = r3[q] = T(0);
+    // EXPR sees the term's register array as `r` and its number as `u`
+#define TAD_EACH_TERM(EXPR)                                                                      \
+    {                                                                                            \
+        { T(&r)[kProgRegs] = r0; constexpr int u = 0; (void)r; (void)u; o[u] = EXPR; }           \
+        if (U > 1) { T(&r)[kProgRegs] = r1; constexpr int u = U > 1 ? 1 : 0; (void)r; (void)u; o[u] = EXPR; } \
+        if (U > 2) { T(&r)[kProgRegs] = r2; constexpr int u = U > 2 ? 2 : 0; (void)r; (void)u; o[u] = EXPR; } \
+        if (U > 3) { T(&r)[kProgRegs] = r3; constexpr int u = U > 3 ? 3 : 0; (void)r; (void)u; o[u] = EXPR; } \
+    }
+    uint32_t w = P.word[0];
+    for (int i = 0; i < P.n; ++i) {
+        const uint32_t next = P.word[(i + 1) & (kMaxProgOps - 1)];
+        const int op = (int)(w & 0xff), first = (int)((w >> 8) & 0xff), second = (int)((w >> 16) & 0xff);
+        const int dst = (int)(w >> 24) & (kProgRegs - 1);
+        const int ra = first & (kProgRegs - 1), rb = second & (kProgRegs - 1);
+        T o[U];
+        switch (op) {
+        case P_CONST: {
+            const T c = (T)P.cst[first & (kMaxProgConst - 1)];
+            TAD_EACH_TERM(c)
+            break;
+        }
+        case P_ARG:   // the operand number selects code, not an address: v stays in registers
+            static_assert(kMaxArgs == 6, "one case per operand");
+            switch (first) {
+            case 0: TAD_EACH_TERM(v[0][u]) break;
+            case 1: TAD_EACH_TERM(v[1][u]) break;
+            case 2: TAD_EACH_TERM(v[2][u]) break;
+            case 3: TAD_EACH_TERM(v[3][u]) break;
+            case 4: TAD_EACH_TERM(v[4][u]) break;
+            default: TAD_EACH_TERM(v[5][u])
+            }
+            break;
+        case P_SUM: TAD_EACH_TERM(s[u]) break;
+        case P_ADD: TAD_EACH_TERM(r[ra] + r[rb]) break;
+        case P_SUB: TAD_EACH_TERM(r[ra] - r[rb]) break;
+        case P_MUL: TAD_EACH_TERM(r[ra] * r[rb]) break;
+        case P_DIV: TAD_EACH_TERM(r[ra] / r[rb]) break;
+        default: TAD_EACH_TERM(prog_unary<T>(op, r[ra], second))
+        }
+        r0[dst] = o[0];
+        if (U > 1) r1[dst] = o[U > 1 ? 1 : 0];
+        if (U > 2) r2[dst] = o[U > 2 ? 2 : 0];
+        if (U > 3) r3[dst] = o[U > 3 ? 3 : 0];
+        w = next;
+    }
+#undef TAD_EACH_TERM
+    const int rr = P.result_reg & (kProgRegs - 1);
+    out[0] = r0[rr];
+    if (U > 1) out[U > 1 ? 1 : 0] = r1[rr];
+    if (U > 2) out[U > 2 ? 2 : 0] = r2[rr];
+    if (U > 3) out[U > 3 ? 3 : 0] = r3[rr];
+}
+
+// one term
+template <typename T, int FORM>
+__device__ __forceinline__ T prog_eval(const DevProg &P, const T *v, T s) {
+    T vv[kMaxArgs][1], ss[1] = {s}, out[1];
+#pragma unroll
+    for (int q = 0; q < kMaxArgs; ++q) vv[q][0] = v[q];
+    prog_eval_block<T, 1, (FORM > 0)>(P, vv, ss, out);
+    return out[0];
+}
+
+// A run of `n` terms whose operand q advances by stp[q] elements per term from ptr[q] (null: the program does
+// not read it), weighted by *wp (advancing by ws; null: weight 1) and with the sum operand read from *sp (same
+// stride; null: 0): ProgWidth<T>::U terms per pass of the interpreter, added in ascending order.  The terms past
+// the end of the last pass repeat the run's first term and are dropped.
+template <typename T, int FORM>
+__device__ __forceinline__ double prog_run(const DevProg &P, const T *const (&ptr0)[kMaxArgs], const int64_t (&stp)[kMaxArgs],
+                                           const T *wp, const T *sp, int64_t ws, int32_t n, double acc) {
+    constexpr int U = FORM == 2 ? ProgWidth<T>::U : 1;
+    const T *ptr[kMaxArgs];
+#pragma unroll
+    for (int q = 0; q < kMaxArgs; ++q) ptr[q] = ptr0[q];
+    for (int32_t it = 0; it < n; it += U) {
+        T v[kMaxArgs][U], sv[U], wv[U], o[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t m = it + u < n ? u : -(int64_t)it;   // in steps from the current position
+#pragma unroll
+            for (int q = 0; q < kMaxArgs; ++q) v[q][u] = ptr[q] ? ptr[q][m * stp[q]] : T(0);
+            sv[u] = sp ? sp[(it + m) * ws] : T(0);
+            wv[u] = wp ? wp[(it + m) * ws] : T(1);
+        }
+        prog_eval_block<T, U, (FORM > 0)>(P, v, sv, o);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (it + u < n) acc += (double)(wv[u] * o[u]);
+#pragma unroll
+        for (int q = 0; q < kMaxArgs; ++q)
+            if (ptr[q]) ptr[q] += (int64_t)U * stp[q];
+    }
+    return acc;
 }
 
 // sum over the summation box of inner(values) for one function index, fp64 accumulation; base[p] receives the
@@ -80,7 +214,7 @@ __device__ T prog_eval(const DevProg &P, const T *v, T s) {
 // offset at this function index)
 // `parts` cooperating threads share the sum: thread `part` takes the terms part, part + parts, ... of the box
 // in row-major order (last summation index fastest), so that a wavefront reads neighbouring elements together.
-template <typename T>
+template <typename T, int FORM>
 __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_ops, const ArgPtrs &A, int lin,
                             int64_t *base, int part = 0, int parts = 1) {
     int32_t ext[kMaxExt];
@@ -96,15 +230,51 @@ __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_op
     }
     int32_t k[kMaxExt] = {0};
     double acc = 0.0;
+    const int last = P.n_sum - 1;
+    const int32_t n_last = last >= 0 ? P.sum_n[last] : 1;
+    if (P.n_cons == 0 && last >= 0 && (parts == 1 || last == 0 || n_last >= parts)) {
+        // no extra conditions: the innermost summation index is a run of n_last terms with constant strides;
+        // cooperating threads take its terms in turn
+        const T *bp[kMaxArgs];
+        int64_t stp[kMaxArgs];
+#pragma unroll
+        for (int p = 0; p < kMaxArgs; ++p) {
+            bp[p] = p < n_ops ? static_cast<const T *>(A.p[p]) + base[p] : nullptr;
+            stp[p] = p < n_ops ? P.off[p][P.n_f + last] * parts : 0;
+        }
+        const int32_t mine = part < n_last ? (n_last - part + parts - 1) / parts : 0;
+        for (;;) {
+            const T *ptr[kMaxArgs];
+#pragma unroll
+            for (int p = 0; p < kMaxArgs; ++p) {
+                int64_t o = 0;
+                if (p < n_ops) {
+#pragma unroll
+                    for (int sidx = 0; sidx < kMaxExt; ++sidx)
+                        if (sidx < last) o += P.off[p][P.n_f + sidx] * (int64_t)k[sidx];
+                    o += P.off[p][P.n_f + last] * (int64_t)part;
+                }
+                ptr[p] = bp[p] ? bp[p] + o : nullptr;
+            }
+            acc = prog_run<T, FORM>(inner, ptr, stp, nullptr, nullptr, 0, mine, acc);
+            int sidx = last - 1;
+            for (; sidx >= 0; --sidx) {
+                if (++k[sidx] < P.sum_n[sidx]) break;
+                k[sidx] = 0;
+            }
+            if (sidx < 0) break;
+        }
+        return acc;
+    }
     auto term = [&]() {
         if (forward_conditions(P, ext, k)) {   // a term outside the extra conditions is not part of the sum
-            T v[kMaxArgs];
+            T v[kMaxArgs] = {};
             for (int p = 0; p < n_ops; ++p) {
                 int64_t o = base[p];
                 for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)k[s];
                 v[p] = static_cast<const T *>(A.p[p])[o];
             }
-            acc += (double)prog_eval<T>(inner, v, T(0));
+            acc += (double)prog_eval<T, FORM>(inner, v, T(0));
         }
     };
     if (parts > 1) {
@@ -131,7 +301,7 @@ __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_op
 
 // df == nullptr: out = outer(sum, operands) (forward);  otherwise out = df * (d outer / d sum)(sum, operands)
 // (backward preparation).  outer_mask: operands `outer` reads.  s_out (may be null): receives the sum.
-template <typename T>
+template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_forward(const ForwardPlan P, const DevProg inner, const DevProg outer,
                                                          int n_ops, uint32_t outer_mask, const ArgPtrs A,
                                                          const T *__restrict__ df, T *__restrict__ out,
@@ -139,16 +309,16 @@ __global__ __launch_bounds__(256) void k_program_forward(const ForwardPlan P, co
     const int lin = blockIdx.x * blockDim.x + threadIdx.x;
     if (lin >= nf) return;
     int64_t base[kMaxArgs];
-    const T s = (T)inner_sum<T>(P, inner, n_ops, A, lin, base);
-    T v[kMaxArgs];
+    const T s = (T)inner_sum<T, FORM>(P, inner, n_ops, A, lin, base);
+    T v[kMaxArgs] = {};
     for (int p = 0; p < n_ops; ++p) v[p] = ((outer_mask >> p) & 1u) ? static_cast<const T *>(A.p[p])[base[p]] : T(0);
-    const T o = prog_eval<T>(outer, v, s);
+    const T o = prog_eval<T, FORM>(outer, v, s);
     out[lin] = df ? df[lin] * o : o;
     if (s_out) s_out[lin] = s;
 }
 
 // the same with one block per function index (long sums): the 256 threads share the sum
-template <typename T>
+template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_forward_coop(const ForwardPlan P, const DevProg inner, const DevProg outer,
                                                               int n_ops, uint32_t outer_mask, const ArgPtrs A,
                                                               const T *__restrict__ df, T *__restrict__ out,
@@ -156,19 +326,19 @@ __global__ __launch_bounds__(256) void k_program_forward_coop(const ForwardPlan 
     __shared__ double red[4];
     const int lin = blockIdx.x;
     int64_t base[kMaxArgs];
-    const double mine = inner_sum<T>(P, inner, n_ops, A, lin, base, threadIdx.x, 256);
+    const double mine = inner_sum<T, FORM>(P, inner, n_ops, A, lin, base, threadIdx.x, 256);
     const T s = (T)block_sum_256(mine, red);
     if (threadIdx.x != 0) return;
-    T v[kMaxArgs];
+    T v[kMaxArgs] = {};
     for (int p = 0; p < n_ops; ++p) v[p] = ((outer_mask >> p) & 1u) ? static_cast<const T *>(A.p[p])[base[p]] : T(0);
-    const T o = prog_eval<T>(outer, v, s);
+    const T o = prog_eval<T, FORM>(outer, v, s);
     out[lin] = df ? df[lin] * o : o;
     if (s_out) s_out[lin] = s;
 }
 
 // Term df * d outer / d x^p of gradient element `lin` of an operand the outer function reads: masks and ranges from
 // the operand's plan over the function indices alone.
-template <typename T>
+template <typename T, int FORM>
 __device__ __forceinline__ bool outer_element(const GatherPlan &P, const DevProg &douter_p, int n_ops, uint32_t outer_mask,
                                               const ArgPtrs &A, const T *__restrict__ s_ws, const T *__restrict__ df,
                                               int lin, int part, int parts, double *sum) {
@@ -181,22 +351,22 @@ __device__ __forceinline__ bool outer_element(const GatherPlan &P, const DevProg
     if (!gather_prepare(P, beta, y)) return false;
     double acc = 0.0;
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
-        int64_t off[kMaxArgs + 1];
-        for (int q = 0; q < n_ops; ++q) off[q] = ((outer_mask >> q) & 1u) ? gather_offset(P, q, y, z) : 0;
-        off[kMaxArgs] = gather_offset(P, kSlotF, y, z);
-        for (int32_t it = 0; it < n; ++it) {
-            T v[kMaxArgs];
-            for (int q = 0; q < n_ops; ++q) v[q] = ((outer_mask >> q) & 1u) ? static_cast<const T *>(A.p[q])[off[q]] : T(0);
-            acc += (double)(df[off[kMaxArgs]] * prog_eval<T>(douter_p, v, s_ws[off[kMaxArgs]]));
-            for (int q = 0; q < n_ops; ++q) off[q] += ((outer_mask >> q) & 1u) ? P.offZ[q][0] * step : 0;
-            off[kMaxArgs] += P.offZ[kSlotF][0] * step;
+        const T *ptr[kMaxArgs];
+        int64_t stp[kMaxArgs];
+#pragma unroll
+        for (int q = 0; q < kMaxArgs; ++q) {
+            const bool on = q < n_ops && ((outer_mask >> q) & 1u);
+            ptr[q] = on ? static_cast<const T *>(A.p[q]) + gather_offset(P, q, y, z) : nullptr;
+            stp[q] = on ? P.offZ[q][0] * step : 0;
         }
+        const int64_t of = gather_offset(P, kSlotF, y, z);
+        acc = prog_run<T, FORM>(douter_p, ptr, stp, df + of, s_ws + of, P.offZ[kSlotF][0] * step, n, acc);
     });
     *sum = acc;
     return true;
 }
 
-template <typename T>
+template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_gather_outer(const GatherPlan P, const DevProg douter_p, int n_ops,
                                                               uint32_t outer_mask, const ArgPtrs A,
                                                               const T *__restrict__ s_ws, const T *__restrict__ df,
@@ -204,7 +374,7 @@ __global__ __launch_bounds__(256) void k_program_gather_outer(const GatherPlan P
     const int lin = blockIdx.x * blockDim.x + threadIdx.x;
     if (lin >= n) return;
     double acc;
-    if (!outer_element<T>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin, 0, 1, &acc)) {
+    if (!outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin, 0, 1, &acc)) {
         if (!accumulate) dx[lin] = T(0);
         return;
     }
@@ -212,7 +382,7 @@ __global__ __launch_bounds__(256) void k_program_gather_outer(const GatherPlan P
 }
 
 // one block per gradient element (few elements, many function indices each)
-template <typename T>
+template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_gather_outer_coop(const GatherPlan P, const DevProg douter_p, int n_ops,
                                                                    uint32_t outer_mask, const ArgPtrs A,
                                                                    const T *__restrict__ s_ws, const T *__restrict__ df,
@@ -220,7 +390,7 @@ __global__ __launch_bounds__(256) void k_program_gather_outer_coop(const GatherP
     __shared__ double red[4];
     const int lin = blockIdx.x;
     double acc;
-    const bool live = outer_element<T>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin, threadIdx.x, 256, &acc);
+    const bool live = outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin, threadIdx.x, 256, &acc);
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
     if (!live) {
@@ -231,7 +401,7 @@ __global__ __launch_bounds__(256) void k_program_gather_outer_coop(const GatherP
 }
 
 // Gradient element `lin`: masks, then the terms of the z loops shared by `parts` threads.
-template <typename T>
+template <typename T, int FORM>
 __device__ __forceinline__ bool program_element(const GatherPlan &P, const DevProg &dinner, int n_ops, const ArgPtrs &A,
                                                 const T *__restrict__ g, int lin, int part, int parts, double *sum) {
     int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
@@ -243,22 +413,21 @@ __device__ __forceinline__ bool program_element(const GatherPlan &P, const DevPr
     if (!gather_prepare(P, beta, y)) return false;
     double acc = 0.0;
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
-        int64_t off[kMaxArgs + 1];
-        for (int q = 0; q < n_ops; ++q) off[q] = gather_offset(P, q, y, z);
-        off[kMaxArgs] = gather_offset(P, kSlotF, y, z);
-        for (int32_t it = 0; it < n; ++it) {
-            T v[kMaxArgs];
-            for (int q = 0; q < n_ops; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
-            acc += (double)(g[off[kMaxArgs]] * prog_eval<T>(dinner, v, T(0)));
-            for (int q = 0; q < n_ops; ++q) off[q] += P.offZ[q][0] * step;
-            off[kMaxArgs] += P.offZ[kSlotF][0] * step;
+        const T *ptr[kMaxArgs];
+        int64_t stp[kMaxArgs];
+#pragma unroll
+        for (int q = 0; q < kMaxArgs; ++q) {
+            const bool on = q < n_ops;
+            ptr[q] = on ? static_cast<const T *>(A.p[q]) + gather_offset(P, q, y, z) : nullptr;
+            stp[q] = on ? P.offZ[q][0] * step : 0;
         }
+        acc = prog_run<T, FORM>(dinner, ptr, stp, g + gather_offset(P, kSlotF, y, z), nullptr, P.offZ[kSlotF][0] * step, n, acc);
     });
     *sum = acc;
     return true;
 }
 
-template <typename T>
+template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, const DevProg dinner, int n_ops,
                                                         const ArgPtrs A, const T *__restrict__ g,
                                                         T *__restrict__ dx, int n, int accumulate, int classify) {
@@ -273,12 +442,12 @@ __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, cons
     }
     double acc = 0.0;
     bool live = false;
-    if (inside && !heavy) live = program_element<T>(P, dinner, n_ops, A, g, lin, 0, 1, &acc);
+    if (inside && !heavy) live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, 0, 1, &acc);
     // an element with many terms is summed by the whole wavefront (the masks can leave few elements with all the work)
     for (unsigned long long todo = __ballot(heavy); todo; todo &= todo - 1) {
         const int src = __ffsll((long long)todo) - 1;
         double part_sum;
-        program_element<T>(P, dinner, n_ops, A, g, __shfl(lin, src, 64), lane, 64, &part_sum);
+        program_element<T, FORM>(P, dinner, n_ops, A, g, __shfl(lin, src, 64), lane, 64, &part_sum);
         const double total = wave_sum_all(part_sum);
         if (lane == src) { acc = total; live = true; }
     }
@@ -291,14 +460,14 @@ __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, cons
 }
 
 // one block per gradient element (few elements, long sums)
-template <typename T>
+template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_gather_coop(const GatherPlan P, const DevProg dinner, int n_ops,
                                                              const ArgPtrs A, const T *__restrict__ g,
                                                              T *__restrict__ dx, int accumulate) {
     __shared__ double red[4];
     const int lin = blockIdx.x;
     double acc;
-    const bool live = program_element<T>(P, dinner, n_ops, A, g, lin, threadIdx.x, 256, &acc);
+    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, threadIdx.x, 256, &acc);
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
     if (!live) {
@@ -308,19 +477,37 @@ __global__ __launch_bounds__(256) void k_program_gather_coop(const GatherPlan P,
     dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
 }
 
+// a program that is identically zero is never interpreted
+static bool has_register_form(const DevProg &P) { return P.result < 0 || P.n_regs > 0; }
+
+// Kernel form for a launch whose runs have about `run_terms` terms: several terms per pass pay from three terms on.
+static int program_form(bool registers, double run_terms) { return !registers ? 0 : run_terms >= 3.0 ? 2 : 1; }
+
+#define TAD_LAUNCH_FORM(form, name, kernel, ...)                             \
+    do {                                                                     \
+        switch (form) {                                                      \
+        case 2: TAD_LAUNCH(name, (kernel<T, 2>), __VA_ARGS__); break;        \
+        case 1: TAD_LAUNCH(name, (kernel<T, 1>), __VA_ARGS__); break;        \
+        default: TAD_LAUNCH(name, (kernel<T, 0>), __VA_ARGS__);              \
+        }                                                                    \
+    } while (0)
+
 template <typename T>
 static int fwd_t(const tad_plan &pl, const void *const *args, const void *df, void *out, void *s_out, hipStream_t s) {
     ArgPtrs A{};
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     const int nf = (int)pl.f_count;
+    const bool fwd_regs = has_register_form(pl.prog.inner) && has_register_form(df ? pl.prog.douter : pl.prog.outer);
+    // the runs of the forward sum are the values of the last summation index
+    const int form = program_form(fwd_regs, pl.fwd.n_sum > 0 ? (double)pl.fwd.sum_n[pl.fwd.n_sum - 1] : 1.0);
     if (use_cooperative_gather(nf, pl.terms_total))   // every function index sums many terms
-        TAD_LAUNCH("k_program_forward_coop", (k_program_forward_coop<T>), dim3(nf), dim3(256), 0, s, pl.fwd,
-                   pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
-                   static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out));
+        TAD_LAUNCH_FORM(form, "k_program_forward_coop", k_program_forward_coop, dim3(nf), dim3(256), 0, s, pl.fwd,
+                        pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
+                        static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out));
     else
-        TAD_LAUNCH("k_program_forward", (k_program_forward<T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
-                   pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
-                   static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out), nf);
+        TAD_LAUNCH_FORM(form, "k_program_forward", k_program_forward, dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
+                        pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
+                        static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out), nf);
     return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
 }
 
@@ -349,28 +536,30 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
         const int n = (int)pl.arg_count[p];
         const bool in_outer = (pl.prog.outer_mask >> q) & 1u;
         const bool inner_zero = pl.prog.dinner[q].result < 0;   // the inner function does not depend on this operand
+        const int form = program_form(has_register_form(pl.prog.dinner[q]), pl.terms_total / (double)(n > 0 ? n : 1));
+        const int form_outer = program_form(has_register_form(pl.prog.douter_arg[q]), (double)pl.f_count / (double)(n > 0 ? n : 1));
         if (in_outer && inner_zero) {
             // nothing to gather over the summation indices: the term of the outer function is the whole gradient
         } else if (use_cooperative_gather(n, pl.terms_total))
-            TAD_LAUNCH("k_program_gather_coop", (k_program_gather_coop<T>), dim3(n), dim3(256), 0, s, pl.ap[q].dev,
-                       pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]),
-                       q != p ? 1 : 0);
+            TAD_LAUNCH_FORM(form, "k_program_gather_coop", k_program_gather_coop, dim3(n), dim3(256), 0, s, pl.ap[q].dev,
+                        pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]),
+                        q != p ? 1 : 0);
         else
-            TAD_LAUNCH("k_program_gather", (k_program_gather<T>), dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
-                       pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
-                       q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
+            TAD_LAUNCH_FORM(form, "k_program_gather", k_program_gather, dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
+                        pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
+                        q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         if (!in_outer) continue;
         if (!pl.ap_outer[q].derived) return TAD_EINVAL;
         const int accumulate = (q != p || !inner_zero) ? 1 : 0;
         if (use_cooperative_gather(n, (double)pl.f_count))
-            TAD_LAUNCH("k_program_gather_outer_coop", (k_program_gather_outer_coop<T>), dim3(n), dim3(256), 0, s,
-                       pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
-                       static_cast<const T *>(df), static_cast<T *>(dx[p]), accumulate);
+            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer_coop", k_program_gather_outer_coop, dim3(n), dim3(256), 0, s,
+                        pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
+                        static_cast<const T *>(df), static_cast<T *>(dx[p]), accumulate);
         else
-            TAD_LAUNCH("k_program_gather_outer", (k_program_gather_outer<T>), dim3((n + 255) / 256), dim3(256), 0, s,
-                       pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
-                       static_cast<const T *>(df), static_cast<T *>(dx[p]), n, accumulate);
+            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer", k_program_gather_outer, dim3((n + 255) / 256), dim3(256), 0, s,
+                        pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
+                        static_cast<const T *>(df), static_cast<T *>(dx[p]), n, accumulate);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

@@ -653,6 +653,18 @@ int tad_plan_program_eval(const tad_plan *plan, int which, const double *values,
     return TAD_OK;
 }
 
+int tad_plan_program_registers(const tad_plan *plan, int which, int *registers_out) {
+    if (!plan || !registers_out || plan->expr.body != TAD_BODY_PROGRAM) return TAD_EINVAL;
+    const ProgramBody &pb = plan->prog;
+    if (which < -3 - pb.n_operands || which >= pb.n_operands) return TAD_EINVAL;
+    const int operand = which >= 0 ? which : which <= -4 ? -4 - which : -1;
+    if (operand >= 0 && !plan->ap[operand].derived) return TAD_EINVAL;   // derivative not planned
+    const DevProg &prog = which == -1 ? pb.inner : which >= 0 ? pb.dinner[which] : which == -2 ? pb.outer
+                          : which == -3 ? pb.douter : pb.douter_arg[operand];
+    *registers_out = prog.result < 0 ? 0 : prog.n_regs;
+    return TAD_OK;
+}
+
 int tad_extended_gcd(int64_t a, int64_t b, int64_t *g, int64_t *x, int64_t *y) {
     if (!g || !x || !y) return TAD_EINVAL;
     try {

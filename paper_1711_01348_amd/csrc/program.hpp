@@ -4,6 +4,7 @@
 // the derivatives with respect to all inputs), and lowering to the three-address form the kernels interpret.
 // Host only.
 #pragma once
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <vector>
@@ -154,6 +155,109 @@ inline std::vector<int> simplify(const Graph &g) {
     return alias;
 }
 
+inline bool prog_is_leaf(uint8_t op) { return op == P_CONST || op == P_ARG || op == P_SUM; }
+inline bool prog_is_binary(uint8_t op) { return op == P_ADD || op == P_SUB || op == P_MUL || op == P_DIV; }
+
+// One operation on values (shared by the two host evaluators below).
+inline double prog_apply(uint8_t op, double x, double y, int k) {
+    switch (op) {
+    case P_ADD: return x + y;
+    case P_SUB: return x - y;
+    case P_MUL: return x * y;
+    case P_DIV: return x / y;
+    case P_NEG: return -x;
+    case P_EXP: return std::exp(x);
+    case P_LOG: return std::log(x);
+    case P_SIN: return std::sin(x);
+    case P_COS: return std::cos(x);
+    case P_TANH: return std::tanh(x);
+    case P_SQRT: return std::sqrt(x);
+    case P_POWI: { double r = x; for (int e = 1; e < k; ++e) r *= x; return r; }
+    default: return 0.0;
+    }
+}
+
+// Evaluation of a lowered program (the host twin of the kernels' interpreter), fp64: one temporary per operation.
+inline double eval_host_temporaries(const DevProg &P, const double *v, double s) {
+    if (P.result < 0) return 0.0;
+    double t[kMaxProgOps] = {0};
+    for (int i = 0; i < P.n; ++i) {
+        switch (P.op[i]) {
+        case P_CONST: t[i] = P.cst[P.a[i]]; break;
+        case P_ARG: t[i] = v[P.a[i]]; break;
+        case P_SUM: t[i] = s; break;
+        default: t[i] = prog_apply(P.op[i], t[P.a[i]], t[P.b[i]], P.k[i]);
+        }
+    }
+    return t[P.result];
+}
+// The same from the register form.
+inline double eval_host_registers(const DevProg &P, const double *v, double s) {
+    if (P.result < 0) return 0.0;
+    double r[kProgRegs] = {0};
+    for (int i = 0; i < P.n; ++i) {
+        const uint32_t w = P.word[i];
+        const uint8_t op = (uint8_t)(w & 0xff);
+        const int first = (int)((w >> 8) & 0xff), second = (int)((w >> 16) & 0xff), dst = (int)(w >> 24);
+        double o;
+        switch (op) {
+        case P_CONST: o = P.cst[first]; break;
+        case P_ARG: o = v[first]; break;
+        case P_SUM: o = s; break;
+        case P_POWI: o = prog_apply(op, r[first], 0.0, second); break;
+        default: o = prog_apply(op, r[first], prog_is_binary(op) ? r[second] : 0.0, 0);
+        }
+        r[dst] = o;
+    }
+    return r[P.result_reg];
+}
+
+// Assign registers by live range, in program order: the inputs an operation reads for the last time are released
+// before its destination is chosen (an operation reads before it writes), the lowest free register is taken.
+// The result is checked against the form with one temporary per operation at a few points; a program that
+// needs more than kProgRegs registers, or fails the check, keeps n_regs == 0.
+inline void allocate_registers(DevProg &P) {
+    P.n_regs = 0;
+    P.result_reg = 0;
+    if (P.result < 0 || P.n <= 0) return;
+    int last[kMaxProgOps], reg[kMaxProgOps];
+    for (int i = 0; i < P.n; ++i) last[i] = -1;
+    for (int i = 0; i < P.n; ++i) {
+        if (prog_is_leaf(P.op[i])) continue;
+        last[P.a[i]] = i;
+        if (prog_is_binary(P.op[i])) last[P.b[i]] = i;
+    }
+    last[P.result] = P.n;
+    bool used[kProgRegs] = {false};
+    int high = 0;
+    for (int i = 0; i < P.n; ++i) {
+        const uint8_t op = P.op[i];
+        const bool leaf = prog_is_leaf(op), binary = prog_is_binary(op);
+        const int ra = leaf ? (int)P.a[i] : reg[P.a[i]], rb = binary ? reg[P.b[i]] : op == P_POWI ? (int)(uint8_t)P.k[i] : 0;
+        if (!leaf) {
+            if (last[P.a[i]] == i) used[reg[P.a[i]]] = false;
+            if (binary && last[P.b[i]] == i) used[reg[P.b[i]]] = false;
+        }
+        int r = 0;
+        while (r < kProgRegs && used[r]) ++r;
+        if (r == kProgRegs) return;
+        reg[i] = r;
+        if (last[i] >= 0) used[r] = true;      // a value nobody reads frees its register at once
+        high = std::max(high, r + 1);
+        P.word[i] = (uint32_t)op | (uint32_t)ra << 8 | (uint32_t)rb << 16 | (uint32_t)r << 24;
+    }
+    P.result_reg = reg[P.result];
+    // self-check at deterministic sample points (NaN results must agree as NaN)
+    for (int t = 0; t < 4; ++t) {
+        double v[TAD_MAX_ARGS];
+        for (int q = 0; q < TAD_MAX_ARGS; ++q) v[q] = 0.37 + 0.21 * q + 0.13 * t;
+        const double s = 0.45 + 0.3 * t;
+        const double x = eval_host_temporaries(P, v, s), y = eval_host_registers(P, v, s);
+        if (!(x == y || (x != x && y != y))) return;
+    }
+    P.n_regs = high;
+}
+
 // Lower the part of the graph that `result` depends on: simplified as above, equal constants share a slot, the
 // nodes are renumbered densely.  False if it does not fit.
 inline bool lower(const Graph &g, int result, DevProg &out) {
@@ -197,6 +301,7 @@ inline bool lower(const Graph &g, int result, DevProg &out) {
     }
     out.n = n;
     out.result = slot[result];
+    allocate_registers(out);
     return true;
 }
 
@@ -266,37 +371,13 @@ inline bool emit_postfix(const Graph &g, const std::vector<int> &alias, int node
     return ok;
 }
 
-// Evaluation of a lowered program (the host twin of the kernels' interpreter), fp64.
 inline bool reads_operands(const DevProg &P) {
     for (int i = 0; i < P.n; ++i)
         if (P.op[i] == P_ARG) return true;
     return false;
 }
 inline double eval_host(const DevProg &P, const double *v, double s) {
-    if (P.result < 0) return 0.0;
-    double t[kMaxProgOps] = {0};
-    for (int i = 0; i < P.n; ++i) {
-        const double x = t[P.a[i]], y = t[P.b[i]];
-        switch (P.op[i]) {
-        case P_CONST: t[i] = P.cst[P.a[i]]; break;
-        case P_ARG: t[i] = v[P.a[i]]; break;
-        case P_SUM: t[i] = s; break;
-        case P_ADD: t[i] = x + y; break;
-        case P_SUB: t[i] = x - y; break;
-        case P_MUL: t[i] = x * y; break;
-        case P_DIV: t[i] = x / y; break;
-        case P_NEG: t[i] = -x; break;
-        case P_EXP: t[i] = std::exp(x); break;
-        case P_LOG: t[i] = std::log(x); break;
-        case P_SIN: t[i] = std::sin(x); break;
-        case P_COS: t[i] = std::cos(x); break;
-        case P_TANH: t[i] = std::tanh(x); break;
-        case P_SQRT: t[i] = std::sqrt(x); break;
-        case P_POWI: { double r = x; for (int e = 1; e < P.k[i]; ++e) r *= x; t[i] = r; break; }
-        default: t[i] = 0.0;
-        }
-    }
-    return t[P.result];
+    return P.n_regs > 0 ? eval_host_registers(P, v, s) : eval_host_temporaries(P, v, s);
 }
 
 // Everything a program-body plan carries.

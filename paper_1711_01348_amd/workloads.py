@@ -188,6 +188,19 @@ def softplus_ratio_expr(I: int, J: int, K: int, dtype: str) -> ExprSpec:
                      ArgSpec("z", (I + K - 1,), [[1, 0, 1]])], dtype, inner, outer)
 
 
+def many_live_values_expr(I: int, K: int, dtype: str) -> ExprSpec:
+    """f_i = sum_k (sum of 18 different functions of x_ik and y_k), written so that all 18 values are computed
+    before the first addition: more values alive at once than the kernels' register form of a program holds."""
+    fns = [("exp",), ("sin",), ("cos",), ("tanh",), ("neg",), ("powi", 2), ("powi", 3), ("powi", 4), ("powi", 5)]
+    inner = []
+    for a in (0, 1):
+        for fn in fns:
+            inner += [("arg", a), fn]
+    inner += [("add",)] * 17
+    return ExprSpec("program", (I,), [(0, K - 1)],
+                    [ArgSpec("x", (I, K), [[1, 0], [0, 1]]), ArgSpec("y", (K,), [[0, 1]])], dtype, inner, [("sum",)])
+
+
 # Operands of the outer function (Sec. 5.2: fbar takes the sum and tensors indexed by the function index alone)
 
 def biased_tanh_expr(I: int, K: int, dtype: str) -> ExprSpec:

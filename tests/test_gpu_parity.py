@@ -447,6 +447,11 @@ PROGRAM_CASES = [
     ("gated_gauss_f64", lambda: wl.random_inputs(wl.gated_gauss_expr(37, 29, 4, "f64"), 14, -0.8, 0.8)),
     ("gated_gauss_f32", lambda: wl.random_inputs(wl.gated_gauss_expr(130, 70, 3, "f32"), 15, -0.8, 0.8)),
     ("biased_causal_conv_f64", lambda: wl.random_inputs(wl.biased_causal_conv_expr(400, 9, "f64"), 16)),
+    # more values alive at once than the interpreter's register form holds: the kernels with one temporary per
+    # operation run the forward pass, the register form the gradients
+    ("many_live_f64", lambda: wl.random_inputs(wl.many_live_values_expr(45, 7, "f64"), 17, -0.9, 0.9)),
+    ("many_live_f32", lambda: wl.random_inputs(wl.many_live_values_expr(300, 5, "f32"), 18, -0.9, 0.9)),
+    ("many_live_long_f32", lambda: wl.random_inputs(wl.many_live_values_expr(3, 2100, "f32"), 19, -0.9, 0.9)),
 ]
 
 
@@ -479,8 +484,8 @@ def test_worked_family_every_short_sum_length(K):
 @pytest.mark.parametrize("I,J,K", [(256, 512, 5), (512, 1024, 3), (768, 512, 4), (512, 1536, 5), (512, 1024, 6),
                                    (512, 1024, 2)])
 def test_worked_family_whole_tiles(I, J, K):
-    """Shapes made of whole backward tiles (256 rows x 512 columns): for some lengths of the summed index the
-    backward pass then streams df and f through LDS instead of registers; one tile, several tiles each way."""
+    """Shapes made of whole backward tiles (256 rows x 512 columns), where no load of the backward pass needs a
+    predicate: one tile, several tiles each way."""
     e = wl.worked_expr(I, J, K, "f32")
     w = wl.random_inputs(e, 60 + K, -0.8, 0.8)
     w.inputs["c"] = np.abs(w.inputs["c"]) * np.float32(0.5)

@@ -486,10 +486,12 @@ PROGRAMS = [
     ([("arg", 0), ("arg", 1), ("mul",), ("arg", 2), ("sin",), ("add",)],
      [("arg", 2), ("sum",), ("tanh",), ("arg", 0), ("mul",), ("const", 1.0), ("arg", 1), ("powi", 2), ("add",),
       ("div",), ("add",)], 3),
+    # 18 values alive at once: no register form for the inner program, one for its derivatives
+    (wl.many_live_values_expr(2, 2, "f64").inner, wl.many_live_values_expr(2, 2, "f64").outer, 2),
 ]
 
 
-@pytest.mark.parametrize("inner,outer,nop", PROGRAMS, ids=["worked", "tanh_dot", "softplus", "mixed", "unused", "powi1", "outer_operands"])
+@pytest.mark.parametrize("inner,outer,nop", PROGRAMS, ids=["worked", "tanh_dot", "softplus", "mixed", "unused", "powi1", "outer_operands", "many_live"])
 def test_symbolic_derivatives_match_forward_mode_oracle(inner, outer, nop):
     """The programs derived by reverse accumulation, evaluated on the host, against the oracle's dual numbers."""
     e = _scalar_expr(inner, outer, nop)
@@ -509,6 +511,28 @@ def test_symbolic_derivatives_match_forward_mode_oracle(inner, outer, nop):
         for p in range(nop):
             got = plan.program_eval(-3, vo, total) * plan.program_eval(p, v) + plan.program_eval(-4 - p, vo, total)
             assert abs(got - g_ref[p][0]) <= 1e-12 * max(1.0, abs(g_ref[p][0])), (p, got, g_ref[p][0])
+
+
+def test_program_register_form():
+    """Registers assigned to the temporaries of the derived programs by live range: as many as values are alive at
+    once, none (0) beyond 16 -- the kernels then fall back to one temporary per operation -- and none for a
+    program that is identically zero.  Both forms evaluate alike (the host evaluator uses the register form when
+    there is one; the oracle comparison above covers the values)."""
+    plan = B.Plan(_scalar_expr(wl.many_live_values_expr(2, 2, "f64").inner, [("sum",)], 2))
+    assert plan.program_registers(-1) == 0
+    assert 1 <= plan.program_registers(0) <= 16 and 1 <= plan.program_registers(1) <= 16
+    assert plan.program_registers(-2) == 1 and plan.program_registers(-3) == 1     # the sum itself; the constant 1
+    assert plan.program_registers(-4) == 0                                         # d outer / d operand: zero
+    # x * y: both operands are alive at the multiplication, whose result reuses a register
+    plan = B.Plan(_scalar_expr([("arg", 0), ("arg", 1), ("mul",)], [("sum",)], 2))
+    assert plan.program_registers(-1) == 2
+    assert plan.program_registers(0) == 1 and plan.program_registers(1) == 1       # d/dx = y, d/dy = x
+    # a chain of unary operations needs one register however long it is
+    plan = B.Plan(_scalar_expr([("arg", 0)] + [("sin",), ("exp",), ("tanh",)] * 5, [("sum",)], 1))
+    assert plan.program_registers(-1) == 1
+    assert _status(lambda: plan.program_registers(1)) == -1
+    assert _status(lambda: plan.program_registers(-5)) == -1
+    assert _status(lambda: B.Plan(wl.config1().expr).program_registers(-1)) == -1   # not a program plan
 
 
 def test_program_rules():
