@@ -45,7 +45,7 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
     for (size_t p = 0; p < plan->args.size(); ++p)
         if (plan->ap[p].derived && plan->ap[p].family != TAD_FAMILY_GENERIC) fam = plan->ap[p].family;
     switch (fam) {
-    case TAD_FAMILY_GENERIC: return generic_backward(*plan, args_dev, f_dev, df_dev, dx_dev, s);
+    case TAD_FAMILY_GENERIC: return generic_backward(*plan, args_dev, f_dev, df_dev, dx_dev, ws_dev, s);
     case TAD_FAMILY_WORKED: return worked_backward(*plan, args_dev, f_dev, df_dev, dx_dev, ws_dev, s);
     case TAD_FAMILY_WORKED_MFMA: return mfma_backward(*plan, args_dev, f_dev, df_dev, dx_dev, ws_dev, s);
     case TAD_FAMILY_ROW_REDUCE:

@@ -312,7 +312,7 @@ static bool match_contraction(tad_plan &pl) {
     return true;
 }
 
-void select_families(tad_plan &plan) {
+static void select_specialised(tad_plan &plan) {
     plan.fwd_family = TAD_FAMILY_GENERIC;
     for (auto &ap : plan.ap) ap.family = TAD_FAMILY_GENERIC;
     plan.ws_bytes = 0;
@@ -335,6 +335,24 @@ void select_families(tad_plan &plan) {
     if (match_patterns(plan)) return;
     if (match_strided(plan)) return;
     if (match_contraction(plan)) return;
+}
+
+void select_families(tad_plan &plan) {
+    select_specialised(plan);
+    // the fallback kernels share the elements of a gradient with few elements and long sums among several blocks:
+    // room for their partial sums behind whatever the family keeps in the workspace
+    bool fallback = true;
+    for (const auto &ap : plan.ap) fallback = fallback && (ap.family == TAD_FAMILY_GENERIC || ap.family == TAD_FAMILY_PROGRAM);
+    plan.split_ws_offset = plan.ws_bytes;
+    if (!fallback) return;
+    size_t most = 0;
+    for (size_t q = 0; q < plan.args.size(); ++q) {
+        const long long n = plan.arg_count[(size_t)plan.root[q]];
+        most = std::max(most, split_workspace_bytes(n, gather_shape(plan.ap[q].dev, n, plan.terms_total).splits));
+        if (plan.expr.body == TAD_BODY_PROGRAM && ((plan.prog.outer_mask >> q) & 1u))
+            most = std::max(most, split_workspace_bytes(n, cooperative_splits(n, (double)plan.f_count)));
+    }
+    plan.ws_bytes += most;
 }
 
 }  // namespace tad

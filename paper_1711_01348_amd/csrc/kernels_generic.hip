@@ -86,7 +86,8 @@ __global__ __launch_bounds__(256) void k_generic_forward_coop(const ForwardPlan 
 // Returns false (and *sum = 0) when a mask zeroes the element.
 template <int BODY, typename T>
 __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const ArgPtrs &A, const T *__restrict__ f,
-                                               const T *__restrict__ df, int lin, int part, int parts, double *sum) {
+                                               const T *__restrict__ df, int lin, int part, int parts, double *sum,
+                                               int group = 0, int groups = 1) {
     constexpr int NA = BodyTraits<BODY>::NA;
     int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
     {
@@ -109,7 +110,7 @@ __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const
             for (int q = 0; q < NA; ++q) off[q] += P.offZ[q][0] * step;
             off[NA] += P.offZ[kSlotF][0] * step;
         }
-    });
+    }, group, groups);
     *sum = acc;
     return true;
 }
@@ -158,13 +159,21 @@ __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int 
 template <int BODY, typename T>
 __global__ __launch_bounds__(256) void k_generic_gather_coop(const GatherPlan P, int p, const ArgPtrs A,
                                                              const T *__restrict__ f, const T *__restrict__ df,
-                                                             T *__restrict__ dx, int accumulate) {
+                                                             T *__restrict__ dx, int accumulate,
+                                                             double *__restrict__ partial, int32_t *__restrict__ live_out) {
+    // gridDim.y blocks share an element (partial != null then): block b takes the parts b * 256 ... of 256 gridDim.y
     __shared__ double red[4];
     const int lin = blockIdx.x;
     double acc;
-    const bool live = gather_element<BODY, T>(P, p, A, f, df, lin, threadIdx.x, 256, &acc);   // uniform over the block
+    const bool live = gather_element<BODY, T>(P, p, A, f, df, lin, threadIdx.x, 256, &acc,
+                                              (int)blockIdx.y, (int)gridDim.y);   // uniform over the block
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
+    if (partial) {
+        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? total : 0.0;
+        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
+        return;
+    }
     if (!live) {
         if (!accumulate) dx[lin] = T(0);
         return;
@@ -172,9 +181,32 @@ __global__ __launch_bounds__(256) void k_generic_gather_coop(const GatherPlan P,
     dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
 }
 
+// one thread per gradient element, the terms of every element shared by gridDim.y blocks (long sums read across
+// the contiguous direction of f: neighbouring threads read neighbouring f)
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_gather_lanes(const GatherPlan P, int p, const ArgPtrs A,
+                                                              const T *__restrict__ f, const T *__restrict__ df,
+                                                              T *__restrict__ dx, int n, int accumulate,
+                                                              double *__restrict__ partial, int32_t *__restrict__ live_out) {
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= n) return;
+    double acc;
+    const bool live = gather_element<BODY, T>(P, p, A, f, df, lin, 0, 1, &acc, (int)blockIdx.y, (int)gridDim.y);
+    if (partial) {
+        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? acc : 0.0;
+        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
+        return;
+    }
+    if (!live) {
+        if (!accumulate) dx[lin] = T(0);
+        return;
+    }
+    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+}
+
 template <int BODY, typename T>
 static int launch_body(const tad_plan &pl, const void *const *args, const void *f, const void *df,
-                       void *const *dx, void *fout, hipStream_t s) {
+                       void *const *dx, void *fout, void *ws, hipStream_t s) {
     ArgPtrs A{};
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     if (fout) {
@@ -194,11 +226,30 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
         if (!dx[p] || pl.ap[q].family != TAD_FAMILY_GENERIC) continue;
         if (!pl.ap[q].derived) return TAD_EINVAL;
         int n = (int)pl.arg_count[p];
-        if (use_cooperative_gather(n, pl.terms_total))
-            TAD_LAUNCH("k_generic_gather_coop", (k_generic_gather_coop<BODY, T>), dim3(n), dim3(256), 0, s,
-                       pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
-                       static_cast<T *>(dx[p]), q != p ? 1 : 0);
-        else
+        const GatherShape shape = gather_shape(pl.ap[q].dev, n, pl.terms_total);
+        if (shape.layout != kLayoutThreads) {
+            const int splits = shape.splits;
+            double *partial = nullptr;
+            int32_t *live = nullptr;
+            if (splits > 1) {
+                if (!ws) return TAD_ENOMEM;
+                partial = reinterpret_cast<double *>(static_cast<char *>(ws) + pl.split_ws_offset);
+                live = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(partial) + align256((size_t)n * splits * 8));
+            }
+            if (shape.layout == kLayoutLanes)
+                TAD_LAUNCH("k_generic_gather_lanes", (k_generic_gather_lanes<BODY, T>), dim3((n + 255) / 256, splits),
+                           dim3(256), 0, s, pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                           static_cast<T *>(dx[p]), n, q != p ? 1 : 0, partial, live);
+            else
+                TAD_LAUNCH("k_generic_gather_coop", (k_generic_gather_coop<BODY, T>), dim3(n, splits), dim3(256), 0, s,
+                           pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                           static_cast<T *>(dx[p]), q != p ? 1 : 0, partial, live);
+            if (splits > 1) {
+                if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+                TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
+                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
+            }
+        } else
             TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 255) / 256), dim3(256), 0, s,
                        pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
                        static_cast<T *>(dx[p]), n, q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
@@ -209,29 +260,29 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
 
 template <typename T>
 static int launch_dtype(const tad_plan &pl, const void *const *args, const void *f, const void *df,
-                        void *const *dx, void *fout, hipStream_t s) {
+                        void *const *dx, void *fout, void *ws, hipStream_t s) {
     switch (pl.expr.body) {
-    case TAD_BODY_SQ: return launch_body<TAD_BODY_SQ, T>(pl, args, f, df, dx, fout, s);
-    case TAD_BODY_CUBE: return launch_body<TAD_BODY_CUBE, T>(pl, args, f, df, dx, fout, s);
-    case TAD_BODY_SIN: return launch_body<TAD_BODY_SIN, T>(pl, args, f, df, dx, fout, s);
-    case TAD_BODY_EXP: return launch_body<TAD_BODY_EXP, T>(pl, args, f, df, dx, fout, s);
-    case TAD_BODY_MUL: return launch_body<TAD_BODY_MUL, T>(pl, args, f, df, dx, fout, s);
-    case TAD_BODY_WORKED: return launch_body<TAD_BODY_WORKED, T>(pl, args, f, df, dx, fout, s);
-    case TAD_BODY_TANH_DOT: return launch_body<TAD_BODY_TANH_DOT, T>(pl, args, f, df, dx, fout, s);
+    case TAD_BODY_SQ: return launch_body<TAD_BODY_SQ, T>(pl, args, f, df, dx, fout, ws, s);
+    case TAD_BODY_CUBE: return launch_body<TAD_BODY_CUBE, T>(pl, args, f, df, dx, fout, ws, s);
+    case TAD_BODY_SIN: return launch_body<TAD_BODY_SIN, T>(pl, args, f, df, dx, fout, ws, s);
+    case TAD_BODY_EXP: return launch_body<TAD_BODY_EXP, T>(pl, args, f, df, dx, fout, ws, s);
+    case TAD_BODY_MUL: return launch_body<TAD_BODY_MUL, T>(pl, args, f, df, dx, fout, ws, s);
+    case TAD_BODY_WORKED: return launch_body<TAD_BODY_WORKED, T>(pl, args, f, df, dx, fout, ws, s);
+    case TAD_BODY_TANH_DOT: return launch_body<TAD_BODY_TANH_DOT, T>(pl, args, f, df, dx, fout, ws, s);
     default: return TAD_EUNSUPPORTED;
     }
 }
 
 int generic_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s) {
-    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, nullptr, nullptr, nullptr, f, s)
-                               : launch_dtype<float>(pl, args, nullptr, nullptr, nullptr, f, s);
+    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, nullptr, nullptr, nullptr, f, nullptr, s)
+                               : launch_dtype<float>(pl, args, nullptr, nullptr, nullptr, f, nullptr, s);
 }
 
 // Launches the generic gather kernel for every wanted gradient whose family is GENERIC.
 int generic_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
-                     void *const *dx, hipStream_t s) {
-    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, f, df, dx, nullptr, s)
-                               : launch_dtype<float>(pl, args, f, df, dx, nullptr, s);
+                     void *const *dx, void *ws, hipStream_t s) {
+    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, f, df, dx, nullptr, ws, s)
+                               : launch_dtype<float>(pl, args, f, df, dx, nullptr, ws, s);
 }
 
 }  // namespace tad

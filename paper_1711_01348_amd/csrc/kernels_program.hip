@@ -341,7 +341,8 @@ __global__ __launch_bounds__(256) void k_program_forward_coop(const ForwardPlan 
 template <typename T, int FORM>
 __device__ __forceinline__ bool outer_element(const GatherPlan &P, const DevProg &douter_p, int n_ops, uint32_t outer_mask,
                                               const ArgPtrs &A, const T *__restrict__ s_ws, const T *__restrict__ df,
-                                              int lin, int part, int parts, double *sum) {
+                                              int lin, int part, int parts, double *sum, int group = 0,
+                                              int groups = 1) {
     int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
     {
         int t = lin;
@@ -361,7 +362,7 @@ __device__ __forceinline__ bool outer_element(const GatherPlan &P, const DevProg
         }
         const int64_t of = gather_offset(P, kSlotF, y, z);
         acc = prog_run<T, FORM>(douter_p, ptr, stp, df + of, s_ws + of, P.offZ[kSlotF][0] * step, n, acc);
-    });
+    }, group, groups);
     *sum = acc;
     return true;
 }
@@ -386,13 +387,20 @@ template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_gather_outer_coop(const GatherPlan P, const DevProg douter_p, int n_ops,
                                                                    uint32_t outer_mask, const ArgPtrs A,
                                                                    const T *__restrict__ s_ws, const T *__restrict__ df,
-                                                                   T *__restrict__ dx, int accumulate) {
+                                                                   T *__restrict__ dx, int accumulate,
+                                                                   double *__restrict__ partial, int32_t *__restrict__ live_out) {
     __shared__ double red[4];
     const int lin = blockIdx.x;
     double acc;
-    const bool live = outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin, threadIdx.x, 256, &acc);
+    const bool live = outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin,
+                                             threadIdx.x, 256, &acc, (int)blockIdx.y, (int)gridDim.y);
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
+    if (partial) {   // several blocks share the element
+        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? total : 0.0;
+        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
+        return;
+    }
     if (!live) {
         if (!accumulate) dx[lin] = T(0);
         return;
@@ -403,7 +411,8 @@ __global__ __launch_bounds__(256) void k_program_gather_outer_coop(const GatherP
 // Gradient element `lin`: masks, then the terms of the z loops shared by `parts` threads.
 template <typename T, int FORM>
 __device__ __forceinline__ bool program_element(const GatherPlan &P, const DevProg &dinner, int n_ops, const ArgPtrs &A,
-                                                const T *__restrict__ g, int lin, int part, int parts, double *sum) {
+                                                const T *__restrict__ g, int lin, int part, int parts, double *sum,
+                                                int group = 0, int groups = 1) {
     int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
     {
         int t = lin;
@@ -422,7 +431,7 @@ __device__ __forceinline__ bool program_element(const GatherPlan &P, const DevPr
             stp[q] = on ? P.offZ[q][0] * step : 0;
         }
         acc = prog_run<T, FORM>(dinner, ptr, stp, g + gather_offset(P, kSlotF, y, z), nullptr, P.offZ[kSlotF][0] * step, n, acc);
-    });
+    }, group, groups);
     *sum = acc;
     return true;
 }
@@ -463,18 +472,48 @@ __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, cons
 template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_gather_coop(const GatherPlan P, const DevProg dinner, int n_ops,
                                                              const ArgPtrs A, const T *__restrict__ g,
-                                                             T *__restrict__ dx, int accumulate) {
+                                                             T *__restrict__ dx, int accumulate,
+                                                             double *__restrict__ partial, int32_t *__restrict__ live_out) {
     __shared__ double red[4];
     const int lin = blockIdx.x;
     double acc;
-    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, threadIdx.x, 256, &acc);
+    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, threadIdx.x, 256, &acc,
+                                               (int)blockIdx.y, (int)gridDim.y);
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
+    if (partial) {   // several blocks share the element
+        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? total : 0.0;
+        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
+        return;
+    }
     if (!live) {
         if (!accumulate) dx[lin] = T(0);
         return;
     }
     dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
+}
+
+// one thread per gradient element, the terms of every element shared by gridDim.y blocks (long sums read across
+// the contiguous direction of g: neighbouring threads read neighbouring g)
+template <typename T, int FORM>
+__global__ __launch_bounds__(256) void k_program_gather_lanes(const GatherPlan P, const DevProg dinner, int n_ops,
+                                                              const ArgPtrs A, const T *__restrict__ g,
+                                                              T *__restrict__ dx, int n, int accumulate,
+                                                              double *__restrict__ partial, int32_t *__restrict__ live_out) {
+    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
+    if (lin >= n) return;
+    double acc;
+    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, 0, 1, &acc, (int)blockIdx.y, (int)gridDim.y);
+    if (partial) {
+        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? acc : 0.0;
+        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
+        return;
+    }
+    if (!live) {
+        if (!accumulate) dx[lin] = T(0);
+        return;
+    }
+    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
 }
 
 // a program that is identically zero is never interpreted
@@ -528,6 +567,11 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
     ArgPtrs A{};
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     const int n_ops = (int)pl.args.size();
+    // partial sums of gradient elements shared by several blocks, and behind them one flag per element
+    double *const split_partial = reinterpret_cast<double *>(static_cast<char *>(ws) + pl.split_ws_offset);
+    auto split_live = [&](int n, int splits) {
+        return reinterpret_cast<int32_t *>(reinterpret_cast<char *>(split_partial) + align256((size_t)n * splits * 8));
+    };
     // the gradient of a tensor is the sum over its occurrences: the first occurrence stores, aliases add
     for (size_t q = 0; q < pl.args.size(); ++q) {
         const size_t p = (size_t)pl.root[q];
@@ -537,14 +581,28 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
         const bool in_outer = (pl.prog.outer_mask >> q) & 1u;
         const bool inner_zero = pl.prog.dinner[q].result < 0;   // the inner function does not depend on this operand
         const int form = program_form(has_register_form(pl.prog.dinner[q]), pl.terms_total / (double)(n > 0 ? n : 1));
+        const GatherShape shape = gather_shape(pl.ap[q].dev, n, pl.terms_total);
         const int form_outer = program_form(has_register_form(pl.prog.douter_arg[q]), (double)pl.f_count / (double)(n > 0 ? n : 1));
         if (in_outer && inner_zero) {
             // nothing to gather over the summation indices: the term of the outer function is the whole gradient
-        } else if (use_cooperative_gather(n, pl.terms_total))
-            TAD_LAUNCH_FORM(form, "k_program_gather_coop", k_program_gather_coop, dim3(n), dim3(256), 0, s, pl.ap[q].dev,
-                        pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]),
-                        q != p ? 1 : 0);
-        else
+        } else if (shape.layout != kLayoutThreads) {
+            const int splits = shape.splits;
+            double *const partial = splits > 1 ? split_partial : nullptr;
+            int32_t *const live = splits > 1 ? split_live(n, splits) : nullptr;
+            if (shape.layout == kLayoutLanes)
+                TAD_LAUNCH_FORM(form, "k_program_gather_lanes", k_program_gather_lanes, dim3((n + 255) / 256, splits),
+                                dim3(256), 0, s, pl.ap[q].dev, pl.prog.dinner[q], (int)pl.args.size(), A,
+                                static_cast<const T *>(ws), static_cast<T *>(dx[p]), n, q != p ? 1 : 0, partial, live);
+            else
+                TAD_LAUNCH_FORM(form, "k_program_gather_coop", k_program_gather_coop, dim3(n, splits), dim3(256), 0, s,
+                                pl.ap[q].dev, pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws),
+                                static_cast<T *>(dx[p]), q != p ? 1 : 0, partial, live);
+            if (splits > 1) {
+                if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+                TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
+                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
+            }
+        } else
             TAD_LAUNCH_FORM(form, "k_program_gather", k_program_gather, dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
                         pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
                         q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
@@ -552,11 +610,19 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
         if (!in_outer) continue;
         if (!pl.ap_outer[q].derived) return TAD_EINVAL;
         const int accumulate = (q != p || !inner_zero) ? 1 : 0;
-        if (use_cooperative_gather(n, (double)pl.f_count))
-            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer_coop", k_program_gather_outer_coop, dim3(n), dim3(256), 0, s,
-                        pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
-                        static_cast<const T *>(df), static_cast<T *>(dx[p]), accumulate);
-        else
+        if (use_cooperative_gather(n, (double)pl.f_count)) {
+            const int splits = cooperative_splits(n, (double)pl.f_count);
+            double *const partial = splits > 1 ? split_partial : nullptr;
+            int32_t *const live = splits > 1 ? split_live(n, splits) : nullptr;
+            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer_coop", k_program_gather_outer_coop, dim3(n, splits),
+                            dim3(256), 0, s, pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
+                            static_cast<const T *>(df), static_cast<T *>(dx[p]), accumulate, partial, live);
+            if (splits > 1) {
+                if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+                TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
+                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, accumulate);
+            }
+        } else
             TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer", k_program_gather_outer, dim3((n + 255) / 256), dim3(256), 0, s,
                         pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
                         static_cast<const T *>(df), static_cast<T *>(dx[p]), n, accumulate);

@@ -12,7 +12,7 @@ struct ArgPtrs {
 
 int generic_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
 int generic_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
-                     void *const *dx, hipStream_t s);
+                     void *const *dx, void *ws, hipStream_t s);
 
 int worked_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
 int worked_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,

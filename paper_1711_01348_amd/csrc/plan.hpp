@@ -70,6 +70,7 @@ struct tad_plan {
     tad::FastParams fast;
     tad::ProgramBody prog;                     // TAD_BODY_PROGRAM only
     size_t ws_bytes = 0;
+    size_t split_ws_offset = 0;                // fallback kernels: where the partial sums of shared elements start
 };
 
 namespace tad {

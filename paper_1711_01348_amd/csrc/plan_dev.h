@@ -21,6 +21,8 @@
 #define TAD_UNROLL
 #endif
 
+#include "worked_geom.h"
+
 namespace tad {
 
 constexpr int kMaxExt = 6;
@@ -54,6 +56,44 @@ struct GatherPlan {
     int64_t offY[kSlots][kMaxRank];    // element offset of tensor slot s = offY[s] . y + offZ[s] . z
     int64_t offZ[kSlots][kMaxKernel];
 };
+
+// How the fallback gather kernels lay their threads over one gradient (decided on the host, per operand):
+//   threads  one thread per element;
+//   blocks   one block per element (long sums): the threads share the terms, taking the values of the innermost
+//            kernel coordinate in turn -- coalesced when f is contiguous along that coordinate;
+//   lanes    one thread per element again, chosen for long sums when f is contiguous along the ELEMENTS instead
+//            (a column sum: neighbouring elements read neighbouring f, successive terms lie a row apart).
+// For blocks and lanes, `splits` groups of threads can share an element (few elements or few blocks otherwise):
+// fp64 partial sums in the workspace, added in a fixed order by a finishing kernel.
+enum GatherLayout { kLayoutThreads = 0, kLayoutBlocks = 1, kLayoutLanes = 2 };
+struct GatherShape {
+    int layout;
+    int splits;
+};
+inline GatherShape gather_shape(const GatherPlan &P, long long n_elements, double terms_total) {
+    GatherShape g{kLayoutThreads, 1};
+    if (!use_cooperative_gather(n_elements, terms_total)) return g;
+    g.layout = kLayoutBlocks;
+    g.splits = cooperative_splits(n_elements, terms_total);
+    if (P.kappa < 1 || P.rank < 1) return g;
+    // offset of f between neighbouring elements (last index of beta) and between neighbouring values of z_0
+    int64_t along_elements = 0;
+    for (int r = 0; r < P.R; ++r) {
+        const int64_t num = P.offY[kSlotF][r] * (int64_t)P.U[r][P.rank - 1];
+        if (num % P.diag[r] != 0) return g;
+        along_elements += num / P.diag[r];
+    }
+    const int64_t along_z = P.offZ[kSlotF][0];
+    if ((along_elements < -1 || along_elements > 1) || (along_z > -16 && along_z < 16)) return g;
+    g.layout = kLayoutLanes;
+    const long long blocks = (n_elements + 255) / 256;
+    const long long want = (2048 + blocks - 1) / blocks;                                  // about 2048 blocks in all
+    const long long most = (long long)(terms_total / (double)n_elements / 256.0);         // at least 256 terms each
+    long long sp = want < most ? want : most;
+    if (sp > 256) sp = 256;
+    g.splits = sp < 1 ? 1 : (int)sp;
+    return g;
+}
 
 struct ForwardPlan {
     int32_t n_f, n_sum;

@@ -170,6 +170,47 @@ def test_long_sums_per_function_index(name, make):
     assert_parity(w, f, grads, f_ref, g_ref, name)
 
 
+FEW_ELEMENTS = [
+    # (name, expression, generic kernels only, value range)
+    # a 3 x 3 filter summed over 4 * 40 * 40 positions, and the worked expression with 8 rows: c has 64 elements
+    # of which the 8 on the diagonal are not masked, d has 10
+    ("filter_generic_f32", lambda: wl.strided_tanh_expr(4, 81, 81, 3, 3, 2, "f32"), True, 0.9),
+    ("worked_generic_f32", lambda: wl.worked_expr(8, 20000, 3, "f32"), True, 0.6),
+    ("worked_generic_f64", lambda: wl.worked_expr(3, 30000, 2, "f64"), True, 0.6),
+    ("filter_program_f32", lambda: wl.as_program(wl.strided_tanh_expr(4, 81, 81, 3, 3, 2, "f32")), False, 0.9),
+    # weights (54 elements) through the sum, bias (6 elements) through the outer function
+    ("dense_layer_program_f32", lambda: wl.dense_layer_expr(9000, 6, 9, "f32"), False, 0.5),
+    ("dense_layer_program_f64", lambda: wl.dense_layer_expr(7000, 3, 4, "f64"), False, 0.5),
+    # sums down the columns of f (db of the worked expression, dy of a matrix product): neighbouring elements read
+    # neighbouring f, successive terms lie a row apart -- one thread per element, the rows shared by several blocks
+    ("column_sums_generic_f32", lambda: wl.worked_expr(1100, 60, 3, "f32"), True, 0.6),
+    ("column_sums_program_f32", lambda: wl.as_program(wl.worked_expr(1100, 60, 3, "f32")), False, 0.6),
+    ("matmul_columns_generic_f64", lambda: wl.matmul_expr(1500, 40, 9, "f64"), True, 0.9),
+]
+
+
+@pytest.mark.parametrize("name,make,generic_only,span", FEW_ELEMENTS, ids=[c[0] for c in FEW_ELEMENTS])
+def test_few_elements_with_long_sums(name, make, generic_only, span):
+    """Gradients whose elements each sum a thousand terms or more and that are few (a filter, a bias, a small
+    matrix) or read f across its contiguous direction: several blocks share an element, their partial sums are
+    added in a fixed order by a finishing pass; elements that a mask zeroes stay exact zeros; two runs give
+    identical bits."""
+    from paper_1711_01348_amd import binding as B
+    e = make()
+    w = wl.random_inputs(e, 77, -span, span)
+    if "worked" in name:
+        w.inputs["c"] = np.abs(w.inputs["c"]) * 0.3
+    plan, f, grads = run_gpu(w, generic_only=generic_only)
+    assert plan.forward_family in ("generic", "program")
+    if plan.forward_family == "generic":
+        assert plan.workspace_bytes > 0          # room for the partial sums of the shared elements
+    f_ref, g_ref = oracle_all(w, 8)
+    assert_parity(w, f, grads, f_ref, g_ref, name)
+    _, _, again = run_gpu(w, generic_only=generic_only)
+    for a, b in zip(grads, again):
+        assert np.array_equal(a, b)
+
+
 def test_backward_is_deterministic_and_skips_unwanted():
     import torch
     w = wl.config3("small")
