@@ -199,7 +199,9 @@ int tad_plan_derive(const tad_expr *expr, const tad_arg *args, int n_args, tad_d
 
 void tad_plan_free(tad_plan *plan);
 
-/* Bytes of device workspace tad_eval_forward / tad_eval_backward need (two-pass reductions). */
+/* Bytes of device workspace tad_eval_forward / tad_eval_backward need: per-tile partial sums of the two-pass
+ * reductions, intermediate tensors of the program bodies, and, on the plan-driven kernels, the partial sums of
+ * gradient elements whose terms several workgroups share.  0 if the plan's kernels need none. */
 size_t tad_plan_workspace_bytes(const tad_plan *plan);
 
 /*

@@ -406,7 +406,11 @@ def test_size_limits():
 def test_workspace_sizes_are_reported():
     assert B.Plan(wl.config1().expr).workspace_bytes == 0          # generic kernels need none
     assert B.Plan(wl.config3().expr).workspace_bytes > 0
-    assert B.Plan(wl.config3().expr, generic_only=True).workspace_bytes == 0
+    # the plan-driven kernels keep partial sums only for gradients whose elements are shared by several blocks:
+    # here db (40960 elements, sums down the columns of f, 13 blocks per element: fp64 partial sums and one flag
+    # per element, each part rounded up to 256 bytes)
+    assert B.Plan(wl.config3().expr, generic_only=True).workspace_bytes == 40960 * 13 * 8 + 40960 * 4
+    assert B.Plan(wl.config3("small").expr, generic_only=True).workspace_bytes == 0
 
 
 # ---- a tensor that occurs several times (Sec. 5.3: one plan per occurrence) ---------------------
