@@ -15,7 +15,7 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
     if (plan->ws_bytes && (!ws_dev || ws_bytes < plan->ws_bytes)) return TAD_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (plan->fwd_family) {
-    case TAD_FAMILY_GENERIC: return generic_forward(*plan, args_dev, f_dev, s);
+    case TAD_FAMILY_GENERIC: return generic_forward(*plan, args_dev, f_dev, ws_dev, s);
     case TAD_FAMILY_WORKED: return worked_forward(*plan, args_dev, f_dev, s);
     case TAD_FAMILY_WORKED_MFMA: return mfma_forward(*plan, args_dev, f_dev, ws_dev, s);
     case TAD_FAMILY_ROW_REDUCE:
@@ -23,7 +23,7 @@ int tad_eval_forward(const tad_plan *plan, const void *const *args_dev, void *f_
     case TAD_FAMILY_ANTIDIAGONAL: return pattern_forward(*plan, args_dev, f_dev, s);
     case TAD_FAMILY_STRIDED: return strided_forward(*plan, args_dev, f_dev, s);
     case TAD_FAMILY_CONTRACTION: return contract_forward(*plan, args_dev, f_dev, ws_dev, s);
-    case TAD_FAMILY_PROGRAM: return program_forward(*plan, args_dev, f_dev, s);
+    case TAD_FAMILY_PROGRAM: return program_forward(*plan, args_dev, f_dev, ws_dev, s);
     default: return TAD_EUNSUPPORTED;
     }
 }

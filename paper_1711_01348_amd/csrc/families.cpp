@@ -5,7 +5,7 @@
 #include <algorithm>
 
 #include "plan.hpp"
-#include "worked_geom.h"
+#include "launch_geom.h"
 
 namespace tad {
 
@@ -345,7 +345,10 @@ void select_families(tad_plan &plan) {
     for (const auto &ap : plan.ap) fallback = fallback && (ap.family == TAD_FAMILY_GENERIC || ap.family == TAD_FAMILY_PROGRAM);
     plan.split_ws_offset = plan.ws_bytes;
     if (!fallback) return;
-    size_t most = 0;
+    // ... and those of a forward sum with few function indices
+    size_t most = cooperative_splits(plan.f_count, plan.terms_total) > 1
+                      ? align256((size_t)plan.f_count * (size_t)cooperative_splits(plan.f_count, plan.terms_total) * 8)
+                      : 0;
     for (size_t q = 0; q < plan.args.size(); ++q) {
         const long long n = plan.arg_count[(size_t)plan.root[q]];
         most = std::max(most, split_workspace_bytes(n, gather_shape(plan.ap[q].dev, n, plan.terms_total).splits));

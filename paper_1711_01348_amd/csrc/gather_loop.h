@@ -20,7 +20,7 @@
 #include <hip/hip_runtime.h>
 
 #include "plan_dev.h"
-#include "worked_geom.h"
+#include "launch_geom.h"
 
 namespace tad {
 

@@ -76,10 +76,28 @@ __global__ __launch_bounds__(256) void k_generic_forward(const ForwardPlan P, co
 
 // one block per function index (long sums)
 template <int BODY, typename T>
-__global__ __launch_bounds__(256) void k_generic_forward_coop(const ForwardPlan P, const ArgPtrs A, T *__restrict__ f) {
+__global__ __launch_bounds__(256) void k_generic_forward_coop(const ForwardPlan P, const ArgPtrs A, T *__restrict__ f,
+                                                              double *__restrict__ partial) {
+    // gridDim.y blocks share a function index (few function indices): their sums go to `partial` and
+    // k_generic_forward_finish applies the outer function
     __shared__ double red[4];
-    const double total = block_sum_256(forward_sum<BODY, T>(P, A, blockIdx.x, threadIdx.x, 256), red);
-    if (threadIdx.x == 0) f[blockIdx.x] = body_outer<BODY, T>((T)total);
+    const double total = block_sum_256(forward_sum<BODY, T>(P, A, blockIdx.x, (int)(blockIdx.y * 256 + threadIdx.x),
+                                                            (int)(256 * gridDim.y)), red);
+    if (threadIdx.x != 0) return;
+    if (partial) partial[(size_t)blockIdx.x * gridDim.y + blockIdx.y] = total;
+    else f[blockIdx.x] = body_outer<BODY, T>((T)total);
+}
+
+// one wavefront per function index: partial sums added in a fixed order, then the outer function
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_forward_finish(const double *__restrict__ partial, int splits,
+                                                                T *__restrict__ f, int nf) {
+    const int lin = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (lin >= nf) return;   // the whole wavefront leaves together
+    double mine = 0.0;
+    for (int sp = lane; sp < splits; sp += 64) mine += partial[(size_t)lin * splits + sp];
+    const double total = wave_sum_all(mine);
+    if (lane == 0) f[lin] = body_outer<BODY, T>((T)total);
 }
 
 // Gradient element `lin` of operand p: masks, then the terms of the z loops shared by `parts` threads.
@@ -211,10 +229,18 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     if (fout) {
         int nf = (int)pl.f_count;
-        if (use_cooperative_gather(nf, pl.terms_total))   // every function index sums many terms
-            TAD_LAUNCH("k_generic_forward_coop", (k_generic_forward_coop<BODY, T>), dim3(nf), dim3(256), 0, s, pl.fwd, A,
-                       static_cast<T *>(fout));
-        else
+        if (use_cooperative_gather(nf, pl.terms_total)) {   // every function index sums many terms
+            const int splits = cooperative_splits(nf, pl.terms_total);
+            if (splits > 1 && !ws) return TAD_ENOMEM;
+            double *const partial = splits > 1 ? reinterpret_cast<double *>(static_cast<char *>(ws) + pl.split_ws_offset) : nullptr;
+            TAD_LAUNCH("k_generic_forward_coop", (k_generic_forward_coop<BODY, T>), dim3(nf, splits), dim3(256), 0, s,
+                       pl.fwd, A, static_cast<T *>(fout), partial);
+            if (splits > 1) {
+                if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+                TAD_LAUNCH("k_generic_forward_finish", (k_generic_forward_finish<BODY, T>), dim3((nf + 3) / 4), dim3(256),
+                           0, s, (const double *)partial, splits, static_cast<T *>(fout), nf);
+            }
+        } else
             TAD_LAUNCH("k_generic_forward", (k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
                        A, static_cast<T *>(fout), nf);
         return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
@@ -273,9 +299,9 @@ static int launch_dtype(const tad_plan &pl, const void *const *args, const void 
     }
 }
 
-int generic_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s) {
-    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, nullptr, nullptr, nullptr, f, nullptr, s)
-                               : launch_dtype<float>(pl, args, nullptr, nullptr, nullptr, f, nullptr, s);
+int generic_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s) {
+    return pl.dtype == TAD_F64 ? launch_dtype<double>(pl, args, nullptr, nullptr, nullptr, f, ws, s)
+                               : launch_dtype<float>(pl, args, nullptr, nullptr, nullptr, f, ws, s);
 }
 
 // Launches the generic gather kernel for every wanted gradient whose family is GENERIC.

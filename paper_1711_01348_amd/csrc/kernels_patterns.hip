@@ -15,7 +15,7 @@
 #include "launch.h"
 #include "plan_dev.h"
 #include "profile.h"
-#include "worked_geom.h"
+#include "launch_geom.h"
 
 namespace tad {
 

@@ -17,7 +17,7 @@
 #include "launch.h"
 #include "plan_dev.h"
 #include "profile.h"
-#include "worked_geom.h"
+#include "launch_geom.h"
 
 namespace tad {
 
@@ -322,15 +322,55 @@ template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_forward_coop(const ForwardPlan P, const DevProg inner, const DevProg outer,
                                                               int n_ops, uint32_t outer_mask, const ArgPtrs A,
                                                               const T *__restrict__ df, T *__restrict__ out,
-                                                              T *__restrict__ s_out) {
+                                                              T *__restrict__ s_out, double *__restrict__ partial) {
+    // gridDim.y blocks share a function index (few function indices): their sums go to `partial` and
+    // k_program_forward_finish applies the outer function
     __shared__ double red[4];
     const int lin = blockIdx.x;
     int64_t base[kMaxArgs];
-    const double mine = inner_sum<T, FORM>(P, inner, n_ops, A, lin, base, threadIdx.x, 256);
-    const T s = (T)block_sum_256(mine, red);
+    const double mine = inner_sum<T, FORM>(P, inner, n_ops, A, lin, base, (int)(blockIdx.y * 256 + threadIdx.x),
+                                           (int)(256 * gridDim.y));
+    const double total = block_sum_256(mine, red);
     if (threadIdx.x != 0) return;
+    if (partial) {
+        partial[(size_t)lin * gridDim.y + blockIdx.y] = total;
+        return;
+    }
+    const T s = (T)total;
     T v[kMaxArgs] = {};
     for (int p = 0; p < n_ops; ++p) v[p] = ((outer_mask >> p) & 1u) ? static_cast<const T *>(A.p[p])[base[p]] : T(0);
+    const T o = prog_eval<T, FORM>(outer, v, s);
+    out[lin] = df ? df[lin] * o : o;
+    if (s_out) s_out[lin] = s;
+}
+
+// Second pass of a forward sum shared by several blocks per function index: one wavefront per function index adds
+// the partial sums (lane l the sums l, l + 64, ... in ascending order, then a fixed tree) and applies the outer
+// function as k_program_forward does.
+template <typename T, int FORM>
+__global__ __launch_bounds__(256) void k_program_forward_finish(const ForwardPlan P, const DevProg outer, int n_ops,
+                                                                uint32_t outer_mask, const ArgPtrs A,
+                                                                const T *__restrict__ df, T *__restrict__ out,
+                                                                T *__restrict__ s_out, const double *__restrict__ partial,
+                                                                int splits, int nf) {
+    const int lin = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (lin >= nf) return;   // the whole wavefront leaves together
+    double mine = 0.0;
+    for (int sp = lane; sp < splits; sp += 64) mine += partial[(size_t)lin * splits + sp];
+    const T s = (T)wave_sum_all(mine);
+    if (lane != 0) return;
+    int32_t ext[kMaxExt];
+    {
+        int t = lin;
+        for (int d = P.n_f - 1; d >= 0; --d) { ext[d] = t % P.f_shape[d]; t /= P.f_shape[d]; }
+    }
+    T v[kMaxArgs] = {};
+    for (int p = 0; p < n_ops; ++p) {
+        if (!((outer_mask >> p) & 1u)) continue;
+        int64_t o = 0;   // an operand of the outer function ignores the summation indices
+        for (int d = 0; d < P.n_f; ++d) o += P.off[p][d] * (int64_t)ext[d];
+        v[p] = static_cast<const T *>(A.p[p])[o];
+    }
     const T o = prog_eval<T, FORM>(outer, v, s);
     out[lin] = df ? df[lin] * o : o;
     if (s_out) s_out[lin] = s;
@@ -532,27 +572,37 @@ static int program_form(bool registers, double run_terms) { return !registers ? 
     } while (0)
 
 template <typename T>
-static int fwd_t(const tad_plan &pl, const void *const *args, const void *df, void *out, void *s_out, hipStream_t s) {
+static int fwd_t(const tad_plan &pl, const void *const *args, const void *df, void *out, void *s_out, void *ws,
+                 hipStream_t s) {
     ArgPtrs A{};
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
     const int nf = (int)pl.f_count;
     const bool fwd_regs = has_register_form(pl.prog.inner) && has_register_form(df ? pl.prog.douter : pl.prog.outer);
     // the runs of the forward sum are the values of the last summation index
     const int form = program_form(fwd_regs, pl.fwd.n_sum > 0 ? (double)pl.fwd.sum_n[pl.fwd.n_sum - 1] : 1.0);
-    if (use_cooperative_gather(nf, pl.terms_total))   // every function index sums many terms
-        TAD_LAUNCH_FORM(form, "k_program_forward_coop", k_program_forward_coop, dim3(nf), dim3(256), 0, s, pl.fwd,
+    if (use_cooperative_gather(nf, pl.terms_total)) {   // every function index sums many terms
+        const int splits = cooperative_splits(nf, pl.terms_total);
+        double *const partial = splits > 1 ? reinterpret_cast<double *>(static_cast<char *>(ws) + pl.split_ws_offset) : nullptr;
+        TAD_LAUNCH_FORM(form, "k_program_forward_coop", k_program_forward_coop, dim3(nf, splits), dim3(256), 0, s, pl.fwd,
                         pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
-                        static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out));
-    else
+                        static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out), partial);
+        if (splits > 1) {
+            if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+            TAD_LAUNCH_FORM(form, "k_program_forward_finish", k_program_forward_finish, dim3((nf + 3) / 4), dim3(256), 0,
+                            s, pl.fwd, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
+                            static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out),
+                            (const double *)partial, splits, nf);
+        }
+    } else
         TAD_LAUNCH_FORM(form, "k_program_forward", k_program_forward, dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
                         pl.prog.inner, df ? pl.prog.douter : pl.prog.outer, (int)pl.args.size(), pl.prog.outer_mask, A,
                         static_cast<const T *>(df), static_cast<T *>(out), static_cast<T *>(s_out), nf);
     return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
 }
 
-int program_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s) {
-    return pl.dtype == TAD_F64 ? fwd_t<double>(pl, args, nullptr, f, nullptr, s)
-                               : fwd_t<float>(pl, args, nullptr, f, nullptr, s);
+int program_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s) {
+    return pl.dtype == TAD_F64 ? fwd_t<double>(pl, args, nullptr, f, nullptr, ws, s)
+                               : fwd_t<float>(pl, args, nullptr, f, nullptr, ws, s);
 }
 
 template <typename T>
@@ -562,7 +612,7 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
     T *const s_ws = pl.prog.outer_mask
                         ? reinterpret_cast<T *>(static_cast<char *>(ws) + align256((size_t)pl.f_count * sizeof(T)))
                         : nullptr;
-    int rc = fwd_t<T>(pl, args, df, ws, s_ws, s);
+    int rc = fwd_t<T>(pl, args, df, ws, s_ws, ws, s);
     if (rc) return rc;
     ArgPtrs A{};
     for (size_t q = 0; q < pl.args.size(); ++q) A.p[q] = args[pl.root[q]];
@@ -602,10 +652,11 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
                 TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
                            (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
             }
-        } else
-            TAD_LAUNCH_FORM(form, "k_program_gather", k_program_gather, dim3((n + 255) / 256), dim3(256), 0, s, pl.ap[q].dev,
-                        pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws), static_cast<T *>(dx[p]), n,
-                        q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
+        } else {
+            TAD_LAUNCH_FORM(form, "k_program_gather", k_program_gather, dim3((n + 255) / 256), dim3(256), 0, s,
+                            pl.ap[q].dev, pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws),
+                            static_cast<T *>(dx[p]), n, q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
+        }
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         if (!in_outer) continue;
         if (!pl.ap_outer[q].derived) return TAD_EINVAL;
@@ -622,10 +673,11 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
                 TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
                            (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, accumulate);
             }
-        } else
-            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer", k_program_gather_outer, dim3((n + 255) / 256), dim3(256), 0, s,
-                        pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
-                        static_cast<const T *>(df), static_cast<T *>(dx[p]), n, accumulate);
+        } else {
+            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer", k_program_gather_outer, dim3((n + 255) / 256),
+                            dim3(256), 0, s, pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
+                            static_cast<const T *>(df), static_cast<T *>(dx[p]), n, accumulate);
+        }
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

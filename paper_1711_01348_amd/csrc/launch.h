@@ -10,7 +10,7 @@ struct ArgPtrs {
     const void *p[kMaxArgs];
 };
 
-int generic_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
+int generic_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s);
 int generic_backward(const tad_plan &pl, const void *const *args, const void *f, const void *df,
                      void *const *dx, void *ws, hipStream_t s);
 
@@ -33,7 +33,7 @@ int contract_forward(const tad_plan &pl, const void *const *args, void *f, void 
 int contract_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
                       hipStream_t s);
 
-int program_forward(const tad_plan &pl, const void *const *args, void *f, hipStream_t s);
+int program_forward(const tad_plan &pl, const void *const *args, void *f, void *ws, hipStream_t s);
 int program_backward(const tad_plan &pl, const void *const *args, const void *df, void *const *dx, void *ws,
                      hipStream_t s);
 

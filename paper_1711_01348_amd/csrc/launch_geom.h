@@ -1,4 +1,5 @@
-// Tile geometry and workspace layout of the worked-expression kernels (host and device).
+// Launch geometry and workspace layout shared by the host planner and the kernels: tile sizes of the specialised
+// families, sizes of their per-tile partial sums, and how the plan-driven fallback kernels share long sums.
 #pragma once
 #include <cstddef>
 #include <cstdint>

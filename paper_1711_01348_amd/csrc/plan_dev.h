@@ -21,7 +21,7 @@
 #define TAD_UNROLL
 #endif
 
-#include "worked_geom.h"
+#include "launch_geom.h"
 
 namespace tad {
 
