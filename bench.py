@@ -30,19 +30,19 @@ ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 
 # 256 MiB copy in the same run (summaries under profiles/).  Each entry carries the SHA-256 prefix of the kernel source
 # the counters were taken with; once that file changes the entry is stale and the bench line reports traffic = null.
 MEASURED_TRAFFIC = {
-    "cfg3": dict(source="kernels_worked.hip", sha256="eb3d295aa246b1f7", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
+    "cfg3": dict(source="kernels_worked.hip", sha256="526515596b424785", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
             summary="profiles/worked_8192x8192x5_f32.md"),
-    "cfg4": dict(source="kernels_mfma.hip", sha256="3979891315943410", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
+    "cfg4": dict(source="kernels_mfma.hip", sha256="a837d56d973eb5ad", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
             summary="profiles/worked_mfma_4096x4096x256_f32.md"),
     "matmul": dict(source="kernels_contract.hip", sha256="131b43a0ad9d9653", fetch_bytes=512.0 * 2**20, write_bytes=64.0 * 2**20,
             summary="profiles/contraction_4096x4096x4096_f32.md"),
-    "cfg2_1": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=64.3 * 2**20, write_bytes=0.1 * 2**20,
+    "cfg2_1": dict(source="kernels_patterns.hip", sha256="4a0de37557d44903", fetch_bytes=64.3 * 2**20, write_bytes=0.1 * 2**20,
             summary="profiles/row_reduce_4096x4096_f32.md"),
-    "cfg2_2": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=1.1 * 2**20, write_bytes=256.2 * 2**20,
+    "cfg2_2": dict(source="kernels_patterns.hip", sha256="4a0de37557d44903", fetch_bytes=1.1 * 2**20, write_bytes=256.2 * 2**20,
             summary="profiles/diagonal_8192_f32.md"),
-    "cfg2_3": dict(source="kernels_patterns.hip", sha256="277b3844cbe5120a", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
+    "cfg2_3": dict(source="kernels_patterns.hip", sha256="4a0de37557d44903", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
             summary="profiles/antidiagonal_4096x4096_f32.md"),
-    "cfg5": dict(source="kernels_strided.hip", sha256="09717396681524fd", fetch_bytes=24.1 * 2**20, write_bytes=8.1 * 2**20,
+    "cfg5": dict(source="kernels_strided.hip", sha256="c66b878b377c9ecf", fetch_bytes=24.1 * 2**20, write_bytes=8.1 * 2**20,
             summary="profiles/strided_32x128x128_f32.md"),
 }
 
