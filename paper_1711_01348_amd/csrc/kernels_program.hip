@@ -111,9 +111,8 @@ __device__ __forceinline__ void prog_eval_block(const DevProg &P, const T (&v)[k
         }
         return;
     }
+    // not cleared: the allocation on the host writes every register before it is read
     T r0[kProgRegs], r1[kProgRegs], r2[kProgRegs], r3[kProgRegs];
-#pragma unroll
-    for (int q = 0; q < kProgRegs; ++q) r0[q] = r1[q] = r2[q] = r3[q] = T(0);
     // EXPR sees the term's register array as `r` and its number as `u`
 #define TAD_EACH_TERM(EXPR)                                                                      \
     {                                                                                            \
