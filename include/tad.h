@@ -164,6 +164,12 @@ typedef struct {
     int32_t family;                                 /* kernel family chosen for this gradient (tad_family) */
     int32_t in_outer;                               /* 1 if the outer function reads this operand: its gradient has
                                                        the additional term df * d outer / d x */
+    int32_t gather_layout;                          /* plan-driven (generic / program) kernels only: how the threads
+                                                       are laid over this gradient: 0 one thread per element, 1 one
+                                                       workgroup per element (long sums), 2 one thread per element
+                                                       with the sum shared by workgroups (long sums read across the
+                                                       contiguous direction of f) */
+    int32_t gather_splits;                          /* ... and how many workgroups share one element (1: none) */
 } tad_plan_info;
 
 typedef enum {

@@ -560,6 +560,11 @@ int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out) {
     int slot = -1;
     get_arg(plan, arg, occ, &slot);
     out->in_outer = plan->expr.body == TAD_BODY_PROGRAM && ((plan->prog.outer_mask >> slot) & 1u) ? 1 : 0;
+    {
+        const GatherShape shape = gather_shape(ap->dev, plan->arg_count[(size_t)plan->root[slot]], plan->terms_total);
+        out->gather_layout = shape.layout;
+        out->gather_splits = shape.splits;
+    }
     return TAD_OK;
 }
 

@@ -517,6 +517,27 @@ def test_symbolic_derivatives_match_forward_mode_oracle(inner, outer, nop):
             assert abs(got - g_ref[p][0]) <= 1e-12 * max(1.0, abs(g_ref[p][0])), (p, got, g_ref[p][0])
 
 
+def test_gather_layouts_of_the_plan_driven_kernels():
+    """How the plan-driven kernels lay their threads over a gradient, as the query reports it: one thread per
+    element for short sums; one workgroup per element for long sums that run along the contiguous direction of
+    f; one thread per element with the sum shared by workgroups where f is contiguous along the elements instead
+    (a column sum); several workgroups per element where the elements are few."""
+    big = B.Plan(wl.config3().expr, generic_only=True)          # 8192 x 8192 x 5
+    a, b, c, d = (big.query(p) for p in range(4))
+    assert (a["gather_layout"], a["gather_splits"]) == ("blocks", 1)       # da_ik: 8192 terms along a row of f
+    assert (b["gather_layout"], b["gather_splits"]) == ("lanes", 13)       # db_jk: 8192 terms down a column of f
+    assert c["gather_layout"] == "threads"                                 # dc: 67 million elements, most of them masked
+    assert (d["gather_layout"], d["gather_splits"]) == ("blocks", 1)       # dd_m: 5 x 8192 terms, 8196 elements
+    small = B.Plan(wl.config1().expr)
+    assert all(small.query(p)["gather_layout"] == "threads" and small.query(p)["gather_splits"] == 1 for p in range(4))
+    conv = B.Plan(wl.config5().expr, generic_only=True)         # x: at most 4 terms; w: 9 elements, 524288 terms each
+    assert conv.query(0)["gather_layout"] == "threads"
+    assert (conv.query(1)["gather_layout"], conv.query(1)["gather_splits"]) == ("blocks", 114)
+    mm = B.Plan(wl.matmul_expr(1500, 40, 9, "f64"), generic_only=True)     # dy_kj = sum_i x_ik df_ij: down the columns
+    assert (mm.query(1)["gather_layout"], mm.query(1)["gather_splits"]) == ("lanes", 5)
+    assert mm.query(0)["gather_layout"] == "threads"                       # dx_ik: 40 terms
+
+
 def test_program_register_form():
     """Registers assigned to the temporaries of the derived programs by live range: as many as values are alive at
     once, none (0) beyond 16 -- the kernels then fall back to one temporary per operation -- and none for a
