@@ -652,7 +652,9 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
                            (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
             }
         } else {
-            TAD_LAUNCH_FORM(form, "k_program_gather", k_program_gather, dim3((n + 255) / 256), dim3(256), 0, s,
+            // workgroups of one wavefront, as for the generic kernels: a wavefront with a heavy element must not
+            // hold the places of its finished neighbours
+            TAD_LAUNCH_FORM(form, "k_program_gather", k_program_gather, dim3((n + 63) / 64), dim3(64), 0, s,
                             pl.ap[q].dev, pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws),
                             static_cast<T *>(dx[p]), n, q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
         }
