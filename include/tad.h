@@ -170,6 +170,11 @@ typedef struct {
                                                        with the sum shared by workgroups (long sums read across the
                                                        contiguous direction of f) */
     int32_t gather_splits;                          /* ... and how many workgroups share one element (1: none) */
+    int64_t gather_elements;                        /* ... and how many element numbers a launch runs over: all of
+                                                       the tensor, or -- for a gradient that the cokernel or the
+                                                       divisibility masks leave mostly zero -- only the box of the
+                                                       transformed index y whose images beta = U^-1 [alpha y ; 0] are
+                                                       the elements that pass those masks (Sec. 4.1) */
 } tad_plan_info;
 
 typedef enum {

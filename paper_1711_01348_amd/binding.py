@@ -62,7 +62,8 @@ class TadPlanInfo(ctypes.Structure):
                 ("C", (ctypes.c_int64 * MAX_RANK) * MAX_RANK),
                 ("n_lower", ctypes.c_int32 * MAX_KERNEL), ("n_upper", ctypes.c_int32 * MAX_KERNEL),
                 ("n_feasibility", ctypes.c_int32), ("family", ctypes.c_int32), ("in_outer", ctypes.c_int32),
-                ("gather_layout", ctypes.c_int32), ("gather_splits", ctypes.c_int32)]
+                ("gather_layout", ctypes.c_int32), ("gather_splits", ctypes.c_int32),
+                ("gather_elements", ctypes.c_int64)]
 
 
 class TadError(RuntimeError):
@@ -213,7 +214,8 @@ class Plan:
                     n_lower=[info.n_lower[k] for k in range(kap)],
                     n_upper=[info.n_upper[k] for k in range(kap)],
                     n_feasibility=info.n_feasibility, family=FAMILY[info.family], in_outer=bool(info.in_outer),
-                    gather_layout=("threads", "blocks", "lanes")[info.gather_layout], gather_splits=info.gather_splits)
+                    gather_layout=("threads", "blocks", "lanes")[info.gather_layout], gather_splits=info.gather_splits,
+                    gather_elements=info.gather_elements)
 
     def bound_rows(self, arg: int, kind: int, level: int = 0) -> List[dict]:
         q = self.query(arg)

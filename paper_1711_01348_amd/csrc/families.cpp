@@ -350,10 +350,13 @@ void select_families(tad_plan &plan) {
                       ? align256((size_t)plan.f_count * (size_t)cooperative_splits(plan.f_count, plan.terms_total) * 8)
                       : 0;
     for (size_t q = 0; q < plan.args.size(); ++q) {
-        const long long n = plan.arg_count[(size_t)plan.root[q]];
+        if (!plan.ap[q].derived) continue;   // no gradient planned for this operand
+        const long long n = gather_launch_count(plan.ap[q].dev, plan.arg_count[(size_t)plan.root[q]]);
         most = std::max(most, split_workspace_bytes(n, gather_shape(plan.ap[q].dev, n, plan.terms_total).splits));
-        if (plan.expr.body == TAD_BODY_PROGRAM && ((plan.prog.outer_mask >> q) & 1u))
-            most = std::max(most, split_workspace_bytes(n, cooperative_splits(n, (double)plan.f_count)));
+        if (plan.expr.body == TAD_BODY_PROGRAM && ((plan.prog.outer_mask >> q) & 1u)) {
+            const long long no = gather_launch_count(plan.ap_outer[q].dev, plan.arg_count[(size_t)plan.root[q]]);
+            most = std::max(most, split_workspace_bytes(no, cooperative_splits(no, (double)plan.f_count)));
+        }
     }
     plan.ws_bytes += most;
 }

@@ -143,23 +143,47 @@ __device__ __forceinline__ double block_sum_256(double v, double *red /* [4] in 
     return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// Finishing pass of a gradient whose elements were shared by several blocks: one wavefront per element, lane l
-// adds the partial sums l, l + 64, ... in ascending order and the 64 lane sums are added in a fixed tree (a
-// single thread would wait for one load after the other).
+// Result of element number idx at position lin (lin < 0: no element): masked elements are stored as zeros unless
+// the launch adds to what is there or runs over the unmasked elements only (the tensor was cleared before).
 template <typename T>
-__global__ __launch_bounds__(256) void k_split_finish(const double *__restrict__ partial, const int32_t *__restrict__ live,
-                                                      int splits, T *__restrict__ dx, int n, int accumulate) {
-    const int lin = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (lin >= n) return;   // the whole wavefront leaves together
-    double mine = 0.0;
-    for (int sp = lane; sp < splits; sp += 64) mine += partial[(size_t)lin * splits + sp];
-    const double total = wave_sum_all(mine);
-    if (lane != 0) return;
-    if (!live[lin]) {
+__device__ __forceinline__ void store_element(T *__restrict__ dx, int lin, bool live, double total, int accumulate) {
+    if (lin < 0) return;
+    if (!live) {
         if (!accumulate) dx[lin] = T(0);
         return;
     }
     dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
+}
+// The same into the partial sums of an element shared by several workgroups: flag = position, -1 masked (store a
+// zero at idx), -2 nothing to store.
+__device__ __forceinline__ void store_partial(double *__restrict__ partial, int32_t *__restrict__ flag, int idx,
+                                              int lin, bool live, double total) {
+    partial[(size_t)idx * gridDim.y + blockIdx.y] = live ? total : 0.0;
+    if (blockIdx.y == 0) flag[idx] = live ? lin : lin >= 0 ? -1 : -2;
+}
+
+// Finishing pass of a gradient whose elements were shared by several blocks: one wavefront per element, lane l
+// adds the partial sums l, l + 64, ... in ascending order and the 64 lane sums are added in a fixed tree (a
+// single thread would wait for one load after the other).  flag: see store_partial.
+template <typename T>
+__global__ __launch_bounds__(256) void k_split_finish(const double *__restrict__ partial, const int32_t *__restrict__ flag,
+                                                      int splits, T *__restrict__ dx, int n, int accumulate) {
+    const int idx = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (idx >= n) return;   // the whole wavefront leaves together
+    double mine = 0.0;
+    for (int sp = lane; sp < splits; sp += 64) mine += partial[(size_t)idx * splits + sp];
+    const double total = wave_sum_all(mine);
+    if (lane != 0) return;
+    const int32_t where = flag[idx];
+    store_element(dx, where >= 0 ? where : where == -1 ? idx : -1, where >= 0, total, accumulate);
+}
+
+// Clears a gradient before a launch that visits its unmasked elements only (a kernel rather than a memset, so
+// that the call can be recorded into a graph).
+template <typename T>
+__global__ __launch_bounds__(256) void k_clear(T *__restrict__ dx, long long n) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dx[i] = T(0);
 }
 
 }  // namespace tad

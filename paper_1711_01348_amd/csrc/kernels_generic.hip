@@ -100,20 +100,17 @@ __global__ __launch_bounds__(256) void k_generic_forward_finish(const double *__
     if (lane == 0) f[lin] = body_outer<BODY, T>((T)total);
 }
 
-// Gradient element `lin` of operand p: masks, then the terms of the z loops shared by `parts` threads.
-// Returns false (and *sum = 0) when a mask zeroes the element.
+// Element number `idx` of the launch over the gradient of operand p (gather_element_index: *lin receives its
+// position in the tensor): masks, then the terms of the z loops shared by `parts` threads.
+// Returns false (and *sum = 0) when a mask zeroes the element or the number is no element.
 template <int BODY, typename T>
 __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const ArgPtrs &A, const T *__restrict__ f,
-                                               const T *__restrict__ df, int lin, int part, int parts, double *sum,
-                                               int group = 0, int groups = 1) {
+                                               const T *__restrict__ df, int idx, int *lin, int part, int parts,
+                                               double *sum, int group = 0, int groups = 1) {
     constexpr int NA = BodyTraits<BODY>::NA;
-    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
-    {
-        int t = lin;
-        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
-    }
+    int32_t y[kMaxRank] = {0, 0, 0, 0};
     *sum = 0.0;
-    if (!gather_prepare(P, beta, y)) return false;
+    if (!gather_element_index(P, idx, lin, y)) return false;
     double acc = 0.0;
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
         // innermost run: offsets advance by a constant per step
@@ -133,12 +130,11 @@ __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const
     return true;
 }
 
-// How many terms element `lin` sums, roughly; 0 if it is masked out.
-__device__ __forceinline__ int64_t element_estimate(const GatherPlan &P, int lin) {
-    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
-    int t = lin;
-    for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
-    if (!gather_prepare(P, beta, y)) return 0;
+// How many terms element number `idx` sums, roughly; 0 if it is masked out.
+__device__ __forceinline__ int64_t element_estimate(const GatherPlan &P, int idx) {
+    int32_t y[kMaxRank] = {0, 0, 0, 0};
+    int lin;
+    if (!gather_element_index(P, idx, &lin, y)) return 0;
     return gather_estimate(P, y);
 }
 
@@ -148,28 +144,26 @@ template <int BODY, typename T>
 __global__ __launch_bounds__(256) void k_generic_gather(const GatherPlan P, int p, const ArgPtrs A,
                                                         const T *__restrict__ f, const T *__restrict__ df,
                                                         T *__restrict__ dx, int n, int accumulate, int classify) {
-    const int lin = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
-    const bool inside = lin < n;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
+    const bool inside = idx < n;
     // classify == 0: the whole expression has fewer terms than one heavy element would
-    const bool heavy = classify && inside && element_estimate(P, lin) >= kHeavyTerms;
+    const bool heavy = classify && inside && element_estimate(P, idx) >= kHeavyTerms;
     double acc = 0.0;
     bool live = false;
-    if (inside && !heavy) live = gather_element<BODY, T>(P, p, A, f, df, lin, 0, 1, &acc);
+    int lin = -1;
+    if (inside && !heavy) live = gather_element<BODY, T>(P, p, A, f, df, idx, &lin, 0, 1, &acc);
     for (unsigned long long todo = __ballot(heavy); todo; todo &= todo - 1) {   // the same in every lane
         const int src = __ffsll((long long)todo) - 1;
         double part_sum;
-        gather_element<BODY, T>(P, p, A, f, df, __shfl(lin, src, 64), lane, 64, &part_sum);
+        int lin_src;
+        gather_element<BODY, T>(P, p, A, f, df, __shfl(idx, src, 64), &lin_src, lane, 64, &part_sum);
         const double total = wave_sum_all(part_sum);
-        if (lane == src) { acc = total; live = true; }
+        if (lane == src) { acc = total; live = true; lin = lin_src; }
     }
     if (!inside) return;
     // accumulate != 0: a further occurrence of the same tensor adds to what the earlier launches stored
     // (same owner thread, launches ordered on the stream: still no atomics)
-    if (!live) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+    store_element(dx, lin, live, acc, accumulate);
 }
 
 // one block per gradient element (few elements, long sums): the 256 threads share the z loops and their partial
@@ -181,22 +175,15 @@ __global__ __launch_bounds__(256) void k_generic_gather_coop(const GatherPlan P,
                                                              double *__restrict__ partial, int32_t *__restrict__ live_out) {
     // gridDim.y blocks share an element (partial != null then): block b takes the parts b * 256 ... of 256 gridDim.y
     __shared__ double red[4];
-    const int lin = blockIdx.x;
+    const int idx = blockIdx.x;
     double acc;
-    const bool live = gather_element<BODY, T>(P, p, A, f, df, lin, threadIdx.x, 256, &acc,
+    int lin;
+    const bool live = gather_element<BODY, T>(P, p, A, f, df, idx, &lin, threadIdx.x, 256, &acc,
                                               (int)blockIdx.y, (int)gridDim.y);   // uniform over the block
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
-    if (partial) {
-        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? total : 0.0;
-        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
-        return;
-    }
-    if (!live) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
+    if (partial) store_partial(partial, live_out, idx, lin, live, total);
+    else store_element(dx, lin, live, total, accumulate);
 }
 
 // one thread per gradient element, the terms of every element shared by gridDim.y blocks (long sums read across
@@ -206,20 +193,13 @@ __global__ __launch_bounds__(256) void k_generic_gather_lanes(const GatherPlan P
                                                               const T *__restrict__ f, const T *__restrict__ df,
                                                               T *__restrict__ dx, int n, int accumulate,
                                                               double *__restrict__ partial, int32_t *__restrict__ live_out) {
-    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lin >= n) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n) return;
     double acc;
-    const bool live = gather_element<BODY, T>(P, p, A, f, df, lin, 0, 1, &acc, (int)blockIdx.y, (int)gridDim.y);
-    if (partial) {
-        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? acc : 0.0;
-        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
-        return;
-    }
-    if (!live) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+    int lin;
+    const bool live = gather_element<BODY, T>(P, p, A, f, df, idx, &lin, 0, 1, &acc, (int)blockIdx.y, (int)gridDim.y);
+    if (partial) store_partial(partial, live_out, idx, lin, live, acc);
+    else store_element(dx, lin, live, acc, accumulate);
 }
 
 template <int BODY, typename T>
@@ -251,7 +231,18 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
         const size_t p = (size_t)pl.root[q];
         if (!dx[p] || pl.ap[q].family != TAD_FAMILY_GENERIC) continue;
         if (!pl.ap[q].derived) return TAD_EINVAL;
-        int n = (int)pl.arg_count[p];
+        // a tensor one of whose occurrences is gathered over its unmasked elements only is cleared first, and
+        // all its launches add
+        bool cleared = false;
+        for (size_t o = 0; o < pl.args.size(); ++o) cleared = cleared || ((size_t)pl.root[o] == p && pl.ap[o].derived && pl.ap[o].dev.live);
+        if (cleared && q == p) {
+            const long long count = pl.arg_count[p];
+            TAD_LAUNCH("k_clear", (k_clear<T>), dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+                       static_cast<T *>(dx[p]), count);
+            if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+        }
+        const int accumulate = (q != p || cleared) ? 1 : 0;
+        const int n = (int)gather_launch_count(pl.ap[q].dev, pl.arg_count[p]);   // element numbers of the launch
         const GatherShape shape = gather_shape(pl.ap[q].dev, n, pl.terms_total);
         if (shape.layout != kLayoutThreads) {
             const int splits = shape.splits;
@@ -265,15 +256,15 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
             if (shape.layout == kLayoutLanes)
                 TAD_LAUNCH("k_generic_gather_lanes", (k_generic_gather_lanes<BODY, T>), dim3((n + 255) / 256, splits),
                            dim3(256), 0, s, pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
-                           static_cast<T *>(dx[p]), n, q != p ? 1 : 0, partial, live);
+                           static_cast<T *>(dx[p]), n, accumulate, partial, live);
             else
                 TAD_LAUNCH("k_generic_gather_coop", (k_generic_gather_coop<BODY, T>), dim3(n, splits), dim3(256), 0, s,
                            pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
-                           static_cast<T *>(dx[p]), q != p ? 1 : 0, partial, live);
+                           static_cast<T *>(dx[p]), accumulate, partial, live);
             if (splits > 1) {
                 if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
                 TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
-                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
+                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, accumulate);
             }
         } else
             // workgroups of one wavefront: a wavefront that sums a heavy element runs long after its neighbours
@@ -281,7 +272,7 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
             // worked expression at 8192 x 8192: 67 million elements, 8192 of them heavy)
             TAD_LAUNCH("k_generic_gather", (k_generic_gather<BODY, T>), dim3((n + 63) / 64), dim3(64), 0, s,
                        pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
-                       static_cast<T *>(dx[p]), n, q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
+                       static_cast<T *>(dx[p]), n, accumulate, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }
     return TAD_OK;

@@ -375,20 +375,16 @@ __global__ __launch_bounds__(256) void k_program_forward_finish(const ForwardPla
     if (s_out) s_out[lin] = s;
 }
 
-// Term df * d outer / d x^p of gradient element `lin` of an operand the outer function reads: masks and ranges from
+// Term df * d outer / d x^p of element number `idx` of an operand the outer function reads: masks and ranges from
 // the operand's plan over the function indices alone.
 template <typename T, int FORM>
 __device__ __forceinline__ bool outer_element(const GatherPlan &P, const DevProg &douter_p, int n_ops, uint32_t outer_mask,
                                               const ArgPtrs &A, const T *__restrict__ s_ws, const T *__restrict__ df,
-                                              int lin, int part, int parts, double *sum, int group = 0,
+                                              int idx, int *lin, int part, int parts, double *sum, int group = 0,
                                               int groups = 1) {
-    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
-    {
-        int t = lin;
-        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
-    }
+    int32_t y[kMaxRank] = {0, 0, 0, 0};
     *sum = 0.0;
-    if (!gather_prepare(P, beta, y)) return false;
+    if (!gather_element_index(P, idx, lin, y)) return false;
     double acc = 0.0;
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
         const T *ptr[kMaxArgs];
@@ -411,14 +407,12 @@ __global__ __launch_bounds__(256) void k_program_gather_outer(const GatherPlan P
                                                               uint32_t outer_mask, const ArgPtrs A,
                                                               const T *__restrict__ s_ws, const T *__restrict__ df,
                                                               T *__restrict__ dx, int n, int accumulate) {
-    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lin >= n) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n) return;
     double acc;
-    if (!outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin, 0, 1, &acc)) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+    int lin;
+    const bool live = outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, idx, &lin, 0, 1, &acc);
+    store_element(dx, lin, live, acc, accumulate);
 }
 
 // one block per gradient element (few elements, many function indices each)
@@ -429,36 +423,26 @@ __global__ __launch_bounds__(256) void k_program_gather_outer_coop(const GatherP
                                                                    T *__restrict__ dx, int accumulate,
                                                                    double *__restrict__ partial, int32_t *__restrict__ live_out) {
     __shared__ double red[4];
-    const int lin = blockIdx.x;
+    const int idx = blockIdx.x;
     double acc;
-    const bool live = outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, lin,
+    int lin;
+    const bool live = outer_element<T, FORM>(P, douter_p, n_ops, outer_mask, A, s_ws, df, idx, &lin,
                                              threadIdx.x, 256, &acc, (int)blockIdx.y, (int)gridDim.y);
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
-    if (partial) {   // several blocks share the element
-        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? total : 0.0;
-        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
-        return;
-    }
-    if (!live) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
+    if (partial) store_partial(partial, live_out, idx, lin, live, total);   // several blocks share the element
+    else store_element(dx, lin, live, total, accumulate);
 }
 
-// Gradient element `lin`: masks, then the terms of the z loops shared by `parts` threads.
+// Element number `idx` of the launch (gather_element_index: *lin receives its position in the tensor): masks, then
+// the terms of the z loops shared by `parts` threads.
 template <typename T, int FORM>
 __device__ __forceinline__ bool program_element(const GatherPlan &P, const DevProg &dinner, int n_ops, const ArgPtrs &A,
-                                                const T *__restrict__ g, int lin, int part, int parts, double *sum,
-                                                int group = 0, int groups = 1) {
-    int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
-    {
-        int t = lin;
-        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
-    }
+                                                const T *__restrict__ g, int idx, int *lin, int part, int parts,
+                                                double *sum, int group = 0, int groups = 1) {
+    int32_t y[kMaxRank] = {0, 0, 0, 0};
     *sum = 0.0;
-    if (!gather_prepare(P, beta, y)) return false;
+    if (!gather_element_index(P, idx, lin, y)) return false;
     double acc = 0.0;
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
         const T *ptr[kMaxArgs];
@@ -479,32 +463,28 @@ template <typename T, int FORM>
 __global__ __launch_bounds__(256) void k_program_gather(const GatherPlan P, const DevProg dinner, int n_ops,
                                                         const ArgPtrs A, const T *__restrict__ g,
                                                         T *__restrict__ dx, int n, int accumulate, int classify) {
-    const int lin = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
-    const bool inside = lin < n;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63;
+    const bool inside = idx < n;
     bool heavy = false;
+    int lin = -1;
     if (classify && inside) {   // classify == 0: the whole expression has fewer terms than one heavy element would
-        int32_t beta[kMaxRank], y[kMaxRank] = {0, 0, 0, 0};
-        int t = lin;
-        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
-        heavy = gather_prepare(P, beta, y) && gather_estimate(P, y) >= kHeavyTerms;
+        int32_t y[kMaxRank] = {0, 0, 0, 0};
+        heavy = gather_element_index(P, idx, &lin, y) && gather_estimate(P, y) >= kHeavyTerms;
     }
     double acc = 0.0;
     bool live = false;
-    if (inside && !heavy) live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, 0, 1, &acc);
+    if (inside && !heavy) live = program_element<T, FORM>(P, dinner, n_ops, A, g, idx, &lin, 0, 1, &acc);
     // an element with many terms is summed by the whole wavefront (the masks can leave few elements with all the work)
     for (unsigned long long todo = __ballot(heavy); todo; todo &= todo - 1) {
         const int src = __ffsll((long long)todo) - 1;
         double part_sum;
-        program_element<T, FORM>(P, dinner, n_ops, A, g, __shfl(lin, src, 64), lane, 64, &part_sum);
+        int lin_src;
+        program_element<T, FORM>(P, dinner, n_ops, A, g, __shfl(idx, src, 64), &lin_src, lane, 64, &part_sum);
         const double total = wave_sum_all(part_sum);
-        if (lane == src) { acc = total; live = true; }
+        if (lane == src) { acc = total; live = true; lin = lin_src; }
     }
     if (!inside) return;
-    if (!live) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+    store_element(dx, lin, live, acc, accumulate);
 }
 
 // one block per gradient element (few elements, long sums)
@@ -514,22 +494,15 @@ __global__ __launch_bounds__(256) void k_program_gather_coop(const GatherPlan P,
                                                              T *__restrict__ dx, int accumulate,
                                                              double *__restrict__ partial, int32_t *__restrict__ live_out) {
     __shared__ double red[4];
-    const int lin = blockIdx.x;
+    const int idx = blockIdx.x;
     double acc;
-    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, threadIdx.x, 256, &acc,
+    int lin;
+    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, idx, &lin, threadIdx.x, 256, &acc,
                                                (int)blockIdx.y, (int)gridDim.y);
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
-    if (partial) {   // several blocks share the element
-        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? total : 0.0;
-        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
-        return;
-    }
-    if (!live) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)total;
+    if (partial) store_partial(partial, live_out, idx, lin, live, total);   // several blocks share the element
+    else store_element(dx, lin, live, total, accumulate);
 }
 
 // one thread per gradient element, the terms of every element shared by gridDim.y blocks (long sums read across
@@ -539,20 +512,14 @@ __global__ __launch_bounds__(256) void k_program_gather_lanes(const GatherPlan P
                                                               const ArgPtrs A, const T *__restrict__ g,
                                                               T *__restrict__ dx, int n, int accumulate,
                                                               double *__restrict__ partial, int32_t *__restrict__ live_out) {
-    const int lin = blockIdx.x * blockDim.x + threadIdx.x;
-    if (lin >= n) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n) return;
     double acc;
-    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, lin, 0, 1, &acc, (int)blockIdx.y, (int)gridDim.y);
-    if (partial) {
-        partial[(size_t)lin * gridDim.y + blockIdx.y] = live ? acc : 0.0;
-        if (blockIdx.y == 0) live_out[lin] = live ? 1 : 0;
-        return;
-    }
-    if (!live) {
-        if (!accumulate) dx[lin] = T(0);
-        return;
-    }
-    dx[lin] = (accumulate ? dx[lin] : T(0)) + (T)acc;
+    int lin;
+    const bool live = program_element<T, FORM>(P, dinner, n_ops, A, g, idx, &lin, 0, 1, &acc, (int)blockIdx.y,
+                                               (int)gridDim.y);
+    if (partial) store_partial(partial, live_out, idx, lin, live, acc);
+    else store_element(dx, lin, live, acc, accumulate);
 }
 
 // a program that is identically zero is never interpreted
@@ -626,12 +593,26 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
         const size_t p = (size_t)pl.root[q];
         if (!dx[p]) continue;
         if (!pl.ap[q].derived) return TAD_EINVAL;
-        const int n = (int)pl.arg_count[p];
         const bool in_outer = (pl.prog.outer_mask >> q) & 1u;
         const bool inner_zero = pl.prog.dinner[q].result < 0;   // the inner function does not depend on this operand
+        // a tensor one of whose occurrences is gathered over its unmasked elements only is cleared first, and
+        // all its launches add
+        bool cleared = false;
+        for (size_t o = 0; o < pl.args.size(); ++o) {
+            if ((size_t)pl.root[o] != p) continue;
+            cleared = cleared || (pl.ap[o].derived && pl.ap[o].dev.live);
+            cleared = cleared || (((pl.prog.outer_mask >> o) & 1u) && pl.ap_outer[o].derived && pl.ap_outer[o].dev.live);
+        }
+        if (cleared && q == p) {
+            const long long count = pl.arg_count[p];
+            TAD_LAUNCH("k_clear", (k_clear<T>), dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+                       static_cast<T *>(dx[p]), count);
+            if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
+        }
+        const int n = (int)gather_launch_count(pl.ap[q].dev, pl.arg_count[p]);   // element numbers of the launch
         const int form = program_form(has_register_form(pl.prog.dinner[q]), pl.terms_total / (double)(n > 0 ? n : 1));
         const GatherShape shape = gather_shape(pl.ap[q].dev, n, pl.terms_total);
-        const int form_outer = program_form(has_register_form(pl.prog.douter_arg[q]), (double)pl.f_count / (double)(n > 0 ? n : 1));
+        const int add_inner = (q != p || cleared) ? 1 : 0;
         if (in_outer && inner_zero) {
             // nothing to gather over the summation indices: the term of the outer function is the whole gradient
         } else if (shape.layout != kLayoutThreads) {
@@ -641,43 +622,45 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
             if (shape.layout == kLayoutLanes)
                 TAD_LAUNCH_FORM(form, "k_program_gather_lanes", k_program_gather_lanes, dim3((n + 255) / 256, splits),
                                 dim3(256), 0, s, pl.ap[q].dev, pl.prog.dinner[q], (int)pl.args.size(), A,
-                                static_cast<const T *>(ws), static_cast<T *>(dx[p]), n, q != p ? 1 : 0, partial, live);
+                                static_cast<const T *>(ws), static_cast<T *>(dx[p]), n, add_inner, partial, live);
             else
                 TAD_LAUNCH_FORM(form, "k_program_gather_coop", k_program_gather_coop, dim3(n, splits), dim3(256), 0, s,
                                 pl.ap[q].dev, pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws),
-                                static_cast<T *>(dx[p]), q != p ? 1 : 0, partial, live);
+                                static_cast<T *>(dx[p]), add_inner, partial, live);
             if (splits > 1) {
                 if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
                 TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
-                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, q != p ? 1 : 0);
+                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, add_inner);
             }
         } else {
             // workgroups of one wavefront, as for the generic kernels: a wavefront with a heavy element must not
             // hold the places of its finished neighbours
             TAD_LAUNCH_FORM(form, "k_program_gather", k_program_gather, dim3((n + 63) / 64), dim3(64), 0, s,
                             pl.ap[q].dev, pl.prog.dinner[q], (int)pl.args.size(), A, static_cast<const T *>(ws),
-                            static_cast<T *>(dx[p]), n, q != p ? 1 : 0, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
+                            static_cast<T *>(dx[p]), n, add_inner, pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
         }
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         if (!in_outer) continue;
         if (!pl.ap_outer[q].derived) return TAD_EINVAL;
-        const int accumulate = (q != p || !inner_zero) ? 1 : 0;
-        if (use_cooperative_gather(n, (double)pl.f_count)) {
-            const int splits = cooperative_splits(n, (double)pl.f_count);
+        const int no = (int)gather_launch_count(pl.ap_outer[q].dev, pl.arg_count[p]);
+        const int form_outer = program_form(has_register_form(pl.prog.douter_arg[q]), (double)pl.f_count / (double)(no > 0 ? no : 1));
+        const int add_outer = (q != p || !inner_zero || cleared) ? 1 : 0;
+        if (use_cooperative_gather(no, (double)pl.f_count)) {
+            const int splits = cooperative_splits(no, (double)pl.f_count);
             double *const partial = splits > 1 ? split_partial : nullptr;
-            int32_t *const live = splits > 1 ? split_live(n, splits) : nullptr;
-            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer_coop", k_program_gather_outer_coop, dim3(n, splits),
+            int32_t *const live = splits > 1 ? split_live(no, splits) : nullptr;
+            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer_coop", k_program_gather_outer_coop, dim3(no, splits),
                             dim3(256), 0, s, pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
-                            static_cast<const T *>(df), static_cast<T *>(dx[p]), accumulate, partial, live);
+                            static_cast<const T *>(df), static_cast<T *>(dx[p]), add_outer, partial, live);
             if (splits > 1) {
                 if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
-                TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((n + 3) / 4), dim3(256), 0, s,
-                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), n, accumulate);
+                TAD_LAUNCH("k_split_finish", (k_split_finish<T>), dim3((no + 3) / 4), dim3(256), 0, s,
+                           (const double *)partial, (const int32_t *)live, splits, static_cast<T *>(dx[p]), no, add_outer);
             }
         } else {
-            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer", k_program_gather_outer, dim3((n + 255) / 256),
+            TAD_LAUNCH_FORM(form_outer, "k_program_gather_outer", k_program_gather_outer, dim3((no + 255) / 256),
                             dim3(256), 0, s, pl.ap_outer[q].dev, pl.prog.douter_arg[q], n_ops, pl.prog.outer_mask, A, s_ws,
-                            static_cast<const T *>(df), static_cast<T *>(dx[p]), n, accumulate);
+                            static_cast<const T *>(df), static_cast<T *>(dx[p]), no, add_outer);
         }
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     }

@@ -25,6 +25,44 @@ static int32_t fit32(int64_t v) {
 }
 
 // Solve  A x = beta,  lo <= x <= hi  once for all beta with |beta_r| < extent[r]: Smith parts, constraints
+// Inverse of a unimodular integer matrix: integer Gauss-Jordan on [M | 1] with row operations (the pivots end
+// as +-1).  False if M is not unimodular.
+static bool unimodular_inverse(const IMat &M, IMat &Inv) {
+    const int D = M.rows;
+    IMat W = M;
+    Inv = IMat::identity(D);
+    for (int c = 0; c < D; ++c) {
+        for (;;) {
+            int piv = -1;
+            int64_t best = 0;
+            for (int i = c; i < D; ++i) {
+                int64_t v = cabs(W(i, c));
+                if (v != 0 && (piv < 0 || v < best)) { best = v; piv = i; }
+            }
+            if (piv < 0) return false;
+            detail::swap_rows(W, c, piv); detail::swap_rows(Inv, c, piv);
+            bool clean = true;
+            for (int i = c + 1; i < D; ++i) {
+                if (W(i, c) == 0) continue;
+                int64_t f = W(i, c) / W(c, c);
+                detail::sub_row(W, i, c, f); detail::sub_row(Inv, i, c, f);
+                if (W(i, c) != 0) clean = false;
+            }
+            if (clean) break;
+        }
+        if (W(c, c) < 0)
+            for (int j = 0; j < D; ++j) { W(c, j) = cneg(W(c, j)); Inv(c, j) = cneg(Inv(c, j)); }
+        if (W(c, c) != 1) return false;
+    }
+    for (int c = D - 1; c >= 0; --c)   // back substitution: clear the entries above each pivot
+        for (int i = 0; i < c; ++i) {
+            int64_t f = W(i, c);
+            if (f == 0) continue;
+            detail::sub_row(W, i, c, f); detail::sub_row(Inv, i, c, f);
+        }
+    return true;
+}
+
 // Omega', Fourier-Motzkin rows and the folded device form (masks, transformed index, ranges).
 // Extra conditions  cons[e][0..D) . x + cons[e][D] >= 0  (n_cons of them) are further rows of the constraint system.
 static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, const int64_t *extent,
@@ -84,6 +122,33 @@ static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, c
     for (int c = 0; c < N - R; ++c)
         for (int d = 0; d < N; ++d) g.C[c][d] = fit32(ap.C(c, d));
 
+    // A gradient with a cokernel or a divisibility mask is zero except at beta = U^{-1} [alpha y ; 0] for integer
+    // y (Sec. 4.1: the masks say exactly that U beta has this form).  Where these elements are few, the
+    // plan-driven kernels run over the box of y instead of over all beta and never visit a masked element.
+    bool masked = N - R > 0;
+    for (int r = 0; r < R; ++r) masked = masked || ap.diag[r] != 1;
+    IMat Uinv;
+    if (masked && unimodular_inverse(ap.smith.U, Uinv)) {
+        long double box = 1, count = 1;
+        for (int d = 0; d < N; ++d) count *= (long double)extent[d];
+        for (int r = 0; r < R; ++r) {
+            int64_t mn = 0, mx = 0;
+            for (int d = 0; d < N; ++d) {
+                const int64_t v = cmul(ap.UR(r, d), csub(extent[d], 1));
+                if (v < 0) mn = cadd(mn, v); else mx = cadd(mx, v);
+            }
+            const int64_t y_lo = ceil_div(mn, ap.diag[r]), y_hi = floor_div(mx, ap.diag[r]);
+            g.y_lo[r] = fit32(y_lo);
+            g.y_n[r] = fit32(csub(y_hi, y_lo) + 1);
+            box *= (long double)g.y_n[r];
+            for (int d = 0; d < N; ++d) g.B[d][r] = fit32(cmul(Uinv(d, r), ap.diag[r]));
+        }
+        if (box * 4 <= count && box < 2147483647.0L) {
+            g.live = 1;
+            g.live_count = (int32_t)box;
+        }
+    }
+
     // Magnitude bounds of y and z over all beta, to prove that int32 arithmetic on the device cannot
     // overflow.  |y_r| <= |U beta|_r.  [y z] = V^{-1} [alpha k] with V unimodular, so |z_m| is bounded by
     // row R+m of V^{-1} applied to the box extents.
@@ -100,37 +165,8 @@ static int derive_lattice(const IMat &A, const int64_t *lo, const int64_t *hi, c
         fit32(s);
     }
     {
-        // integer Gauss-Jordan on [V | 1] with row operations (V is unimodular, pivots end as +-1)
-        IMat W = ap.smith.V, Inv = IMat::identity(D);
-        for (int c = 0; c < D; ++c) {
-            for (;;) {
-                int piv = -1;
-                int64_t best = 0;
-                for (int i = c; i < D; ++i) {
-                    int64_t v = cabs(W(i, c));
-                    if (v != 0 && (piv < 0 || v < best)) { best = v; piv = i; }
-                }
-                if (piv < 0) return TAD_EINVAL;
-                detail::swap_rows(W, c, piv); detail::swap_rows(Inv, c, piv);
-                bool clean = true;
-                for (int i = c + 1; i < D; ++i) {
-                    if (W(i, c) == 0) continue;
-                    int64_t f = W(i, c) / W(c, c);
-                    detail::sub_row(W, i, c, f); detail::sub_row(Inv, i, c, f);
-                    if (W(i, c) != 0) clean = false;
-                }
-                if (clean) break;
-            }
-            if (W(c, c) < 0)
-                for (int j = 0; j < D; ++j) { W(c, j) = cneg(W(c, j)); Inv(c, j) = cneg(Inv(c, j)); }
-            if (W(c, c) != 1) return TAD_EINVAL;
-        }
-        for (int c = D - 1; c >= 0; --c)   // back substitution: clear the entries above each pivot
-            for (int i = 0; i < c; ++i) {
-                int64_t f = W(i, c);
-                if (f == 0) continue;
-                detail::sub_row(W, i, c, f); detail::sub_row(Inv, i, c, f);
-            }
+        IMat Inv;
+        if (!unimodular_inverse(ap.smith.V, Inv)) return TAD_EINVAL;
         for (int m = 0; m < kappa; ++m) {
             int64_t s = 0;
             for (int d = 0; d < D; ++d)
@@ -468,12 +504,11 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     return TAD_OK;
 }
 
-// Visit every extended index of beta through masks, ranges and the maps V_R y + K z.
+// Visit every extended index of the element with transformed index y through the ranges and the maps V_R y + K z.
 template <class Fn>
-static void visit_beta(int n_ext, const ArgPlan &ap, const int32_t *beta, Fn &&fn) {
+static void visit_y(int n_ext, const ArgPlan &ap, const int32_t *y, Fn &&fn) {
     const GatherPlan &g = ap.dev;
-    int32_t y[kMaxRank] = {0}, z[kMaxKernel] = {0}, hi[kMaxKernel] = {0};
-    if (!gather_prepare(g, beta, y)) return;
+    int32_t z[kMaxKernel] = {0}, hi[kMaxKernel] = {0};
     auto emit = [&]() {
         int64_t ext[TAD_MAX_EXT];
         for (int d = 0; d < n_ext; ++d) {
@@ -496,6 +531,14 @@ static void visit_beta(int n_ext, const ArgPlan &ap, const int32_t *beta, Fn &&f
         if (lvl == 0) { emit(); ++z[0]; }
         else { --lvl; gather_bounds(g, lvl, y, z, z[lvl], hi[lvl]); }
     }
+}
+
+// The same for beta, through the masks.
+template <class Fn>
+static void visit_beta(int n_ext, const ArgPlan &ap, const int32_t *beta, Fn &&fn) {
+    int32_t y[kMaxRank] = {0};
+    if (!gather_prepare(ap.dev, beta, y)) return;
+    visit_y(n_ext, ap, y, fn);
 }
 
 // plan of occurrence `occ` of the tensor given as operand `arg` (0: the operand itself, k: its k-th alias)
@@ -561,9 +604,11 @@ int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out) {
     get_arg(plan, arg, occ, &slot);
     out->in_outer = plan->expr.body == TAD_BODY_PROGRAM && ((plan->prog.outer_mask >> slot) & 1u) ? 1 : 0;
     {
-        const GatherShape shape = gather_shape(ap->dev, plan->arg_count[(size_t)plan->root[slot]], plan->terms_total);
+        const GatherShape shape = gather_shape(ap->dev, gather_launch_count(ap->dev, plan->arg_count[(size_t)plan->root[slot]]),
+                                               plan->terms_total);
         out->gather_layout = shape.layout;
         out->gather_splits = shape.splits;
+        out->gather_elements = gather_launch_count(ap->dev, plan->arg_count[(size_t)plan->root[slot]]);
     }
     return TAD_OK;
 }
@@ -628,15 +673,18 @@ int tad_plan_enumerate(const tad_plan *plan, int arg, int occ, const int64_t *be
 int tad_plan_count_all(const tad_plan *plan, int arg, int64_t *counts) {
     const ArgPlan *ap = get_arg(plan, arg, 0);
     if (!ap || !counts) return TAD_EINVAL;
-    const tad_arg &a = plan->args[arg];
-    int32_t beta[kMaxRank] = {0};
+    // the way the plan-driven kernels run over the gradient: element numbers of the launch (all of the tensor, or
+    // the unmasked elements only), each mapped to its position and its transformed index
     const int64_t total = plan->arg_count[arg];
-    for (int64_t lin = 0; lin < total; ++lin) {
-        int64_t t = lin;
-        for (int r = a.rank - 1; r >= 0; --r) { beta[r] = (int32_t)(t % a.shape[r]); t /= a.shape[r]; }
+    for (int64_t lin = 0; lin < total; ++lin) counts[lin] = 0;
+    const int64_t numbers = gather_launch_count(ap->dev, total);
+    for (int64_t idx = 0; idx < numbers; ++idx) {
+        int32_t y[kMaxRank] = {0};
+        int lin = -1;
+        if (!gather_element_index(ap->dev, (int)idx, &lin, y)) continue;
         int64_t c = 0;
-        visit_beta(plan->n_ext, *ap, beta, [&](const int64_t *) { ++c; });
-        counts[lin] = c;
+        visit_y(plan->n_ext, *ap, y, [&](const int64_t *) { ++c; });
+        counts[lin] += c;
     }
     return TAD_OK;
 }

@@ -55,6 +55,11 @@ struct GatherPlan {
     GRow rows[kMaxRows];
     int64_t offY[kSlots][kMaxRank];    // element offset of tensor slot s = offY[s] . y + offZ[s] . z
     int64_t offZ[kSlots][kMaxKernel];
+    // masked gradients with few non-zero elements (live != 0): the elements that pass the masks are
+    // beta = B y for the integer y of the box y_lo <= y < y_lo + y_n (some of them outside the tensor)
+    int32_t live, live_count;          // live_count: points of the box
+    int32_t y_lo[kMaxRank], y_n[kMaxRank];
+    int32_t B[kMaxRank][kMaxRank];
 };
 
 // How the fallback gather kernels lay their threads over one gradient (decided on the host, per operand):
@@ -65,6 +70,9 @@ struct GatherPlan {
 //            (a column sum: neighbouring elements read neighbouring f, successive terms lie a row apart).
 // For blocks and lanes, `splits` groups of threads can share an element (few elements or few blocks otherwise):
 // fp64 partial sums in the workspace, added in a fixed order by a finishing kernel.
+// Elements a launch over the gradient of this plan runs over: all of the tensor, or the box of y (live plans).
+inline long long gather_launch_count(const GatherPlan &P, long long n_elements) { return P.live ? P.live_count : n_elements; }
+
 enum GatherLayout { kLayoutThreads = 0, kLayoutBlocks = 1, kLayoutLanes = 2 };
 struct GatherShape {
     int layout;
@@ -179,6 +187,36 @@ TAD_HD bool gather_prepare(const GatherPlan &P, const int32_t *beta, int32_t *y)
         for (int r = 0; r < P.R; ++r) s += P.feas[f].ky[r] * y[r];
         if (s > 0) return false;
     }
+    return true;
+}
+
+// Element number `idx` of a launch over one gradient -> position `lin` of the element in its tensor and its
+// transformed index y.  The launch runs over all beta (idx = lin) or, for a plan with live != 0, over the box of
+// y.  False: the element is zero by a mask, or (live plans) the point is no element at all: *lin < 0 then.
+TAD_HD bool gather_element_index(const GatherPlan &P, int idx, int *lin, int32_t *y) {
+    int32_t beta[kMaxRank];
+    if (!P.live) {
+        *lin = idx;
+        int t = idx;
+        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+        return gather_prepare(P, beta, y);
+    }
+    *lin = -1;
+    int t = idx;
+    for (int r = P.R - 1; r >= 0; --r) { y[r] = P.y_lo[r] + t % P.y_n[r]; t /= P.y_n[r]; }
+    int pos = 0;
+    for (int d = 0; d < P.rank; ++d) {
+        int32_t b = 0;
+        for (int r = 0; r < P.R; ++r) b += P.B[d][r] * y[r];
+        if (b < 0 || b >= P.shape[d]) return false;
+        pos = pos * P.shape[d] + b;
+    }
+    for (int f = 0; f < P.nF; ++f) {
+        int32_t s = P.feas[f].k0;
+        for (int r = 0; r < P.R; ++r) s += P.feas[f].ky[r] * y[r];
+        if (s > 0) return false;   // the element exists and is zero: the launch has cleared it
+    }
+    *lin = pos;
     return true;
 }
 

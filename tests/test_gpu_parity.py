@@ -96,6 +96,12 @@ ASSORTED = [
     lambda: _expr("exp", (3, 4), [(0, 2)], [("x", (7, 9), [[2, 0, 1], [0, 2, 1]])]),
     lambda: _expr("exp", (3, 3, 3), [], [("x", (5, 5), [[1, 1, 0], [0, 1, 1]])]),
     lambda: _expr("exp", (6,), [(0, 3), (0, 2)], [("x", (30,), [[3, 2, 4]])]),
+    # masks that leave few elements: the kernels run over the transformed index y instead of over all beta
+    # (a stride of 5; a diagonal with stride 3 in a matrix with room to spare; a sum that reaches the same element
+    # of a strided diagonal several times)
+    lambda: _expr("sq", (40,), [], [("x", (300,), [[5]])]),
+    lambda: _expr("exp", (9,), [], [("x", (31, 40), [[3], [3]])], "f32"),
+    lambda: _expr("exp", (7, 4), [(0, 2)], [("x", (50, 60), [[4, 0, 2], [4, 0, 2]])]),
     lambda: wl.worked_expr(4, 3, 5, "f64", d_len=11, c_shape=(6, 5)),
     lambda: wl.worked_expr(3, 4, 5, "f64", d_len=8),
     lambda: wl.worked_expr(70, 1301, 5, "f32"),          # row length not a multiple of 4: generic kernels

@@ -526,13 +526,22 @@ def test_gather_layouts_of_the_plan_driven_kernels():
     a, b, c, d = (big.query(p) for p in range(4))
     assert (a["gather_layout"], a["gather_splits"]) == ("blocks", 1)       # da_ik: 8192 terms along a row of f
     assert (b["gather_layout"], b["gather_splits"]) == ("lanes", 13)       # db_jk: 8192 terms down a column of f
-    assert c["gather_layout"] == "threads"                                 # dc: 67 million elements, most of them masked
+    # dc: 67 million elements, all but the diagonal masked: the launch runs over the 8192 values of y = i instead
+    assert (c["gather_layout"], c["gather_splits"], c["gather_elements"]) == ("blocks", 1, 8192)
+    assert a["gather_elements"] == 8192 * 5 and d["gather_elements"] == 8196
     assert (d["gather_layout"], d["gather_splits"]) == ("blocks", 1)       # dd_m: 5 x 8192 terms, 8196 elements
     small = B.Plan(wl.config1().expr)
     assert all(small.query(p)["gather_layout"] == "threads" and small.query(p)["gather_splits"] == 1 for p in range(4))
     conv = B.Plan(wl.config5().expr, generic_only=True)         # x: at most 4 terms; w: 9 elements, 524288 terms each
     assert conv.query(0)["gather_layout"] == "threads"
     assert (conv.query(1)["gather_layout"], conv.query(1)["gather_splits"]) == ("blocks", 114)
+    # a gradient with a divisibility mask: f_i = x_{5i}: the launch runs over y = beta / 5 (a box of at most a
+    # quarter of the elements is worth the separate clearing pass; f_i = x_{3i} runs over all beta)
+    fifth = B.Plan(_expr("sq", (40,), [], [("x", (300,), [[5]])], "f64"))
+    assert fifth.query(0)["gather_elements"] == 60            # y = 0 .. 59 (beta up to 299), 40 of them used
+    assert B.Plan(_expr("sq", (40,), [], [("x", (130,), [[3]])], "f64")).query(0)["gather_elements"] == 130
+    # no mask: all elements
+    assert B.Plan(_expr("sq", (40,), [], [("x", (40,), [[1]])], "f64")).query(0)["gather_elements"] == 40
     mm = B.Plan(wl.matmul_expr(1500, 40, 9, "f64"), generic_only=True)     # dy_kj = sum_i x_ik df_ij: down the columns
     assert (mm.query(1)["gather_layout"], mm.query(1)["gather_splits"]) == ("lanes", 5)
     assert mm.query(0)["gather_layout"] == "threads"                       # dx_ik: 40 terms
