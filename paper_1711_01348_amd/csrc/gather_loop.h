@@ -182,8 +182,24 @@ __global__ __launch_bounds__(256) void k_split_finish(const double *__restrict__
 // that the call can be recorded into a graph).
 template <typename T>
 __global__ __launch_bounds__(256) void k_clear(T *__restrict__ dx, long long n) {
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) dx[i] = T(0);
+    // 16 bytes per thread where the tensor starts on a 16-byte boundary (it does when it is an allocation of its own)
+    constexpr int V = 16 / (int)sizeof(T);
+    typedef T vec __attribute__((ext_vector_type(V)));
+    const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * V;
+    if (i >= n) return;
+    if ((reinterpret_cast<uintptr_t>(dx) & 15) == 0 && i + V <= n) {
+        vec zero;
+        for (int v = 0; v < V; ++v) zero[v] = T(0);
+        __builtin_nontemporal_store(zero, reinterpret_cast<vec *>(dx + i));
+    } else {
+        for (int v = 0; v < V && i + v < n; ++v) dx[i + v] = T(0);
+    }
+}
+// number of workgroups of k_clear for n elements
+template <typename T>
+inline unsigned clear_blocks(long long n) {
+    const long long per_block = 256 * (16 / (long long)sizeof(T));
+    return (unsigned)((n + per_block - 1) / per_block);
 }
 
 }  // namespace tad

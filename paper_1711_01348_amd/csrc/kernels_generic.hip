@@ -237,7 +237,7 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
         for (size_t o = 0; o < pl.args.size(); ++o) cleared = cleared || ((size_t)pl.root[o] == p && pl.ap[o].derived && pl.ap[o].dev.live);
         if (cleared && q == p) {
             const long long count = pl.arg_count[p];
-            TAD_LAUNCH("k_clear", (k_clear<T>), dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+            TAD_LAUNCH("k_clear", (k_clear<T>), dim3(clear_blocks<T>(count)), dim3(256), 0, s,
                        static_cast<T *>(dx[p]), count);
             if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         }

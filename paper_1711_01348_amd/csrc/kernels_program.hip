@@ -605,7 +605,7 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
         }
         if (cleared && q == p) {
             const long long count = pl.arg_count[p];
-            TAD_LAUNCH("k_clear", (k_clear<T>), dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s,
+            TAD_LAUNCH("k_clear", (k_clear<T>), dim3(clear_blocks<T>(count)), dim3(256), 0, s,
                        static_cast<T *>(dx[p]), count);
             if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         }
