@@ -33,6 +33,44 @@ __device__ __forceinline__ double forward_sum(const ForwardPlan &P, const ArgPtr
     }
     int32_t k[kMaxExt] = {0};
     double acc = 0.0;
+    const int last = P.n_sum - 1;
+    const int32_t n_last = last >= 0 ? P.sum_n[last] : 1;
+    if (P.n_cons == 0 && last >= 0 && (parts == 1 || last == 0 || n_last >= parts)) {
+        // no extra conditions: the last summation index is a run of terms a constant stride apart; cooperating
+        // threads take its terms in turn.  Four terms are loaded before the first is used (one wait for memory per
+        // four terms; added in ascending order; slots past the end of the run reload its current term and are dropped).
+        constexpr int U = 4;
+        int64_t stp[NA];
+        for (int p = 0; p < NA; ++p) stp[p] = P.off[p][P.n_f + last] * parts;
+        const int32_t mine = part < n_last ? (n_last - part + parts - 1) / parts : 0;
+        for (;;) {
+            const T *ptr[NA];
+            for (int p = 0; p < NA; ++p) {
+                int64_t o = base[p] + P.off[p][P.n_f + last] * (int64_t)part;
+                for (int sidx = 0; sidx < last; ++sidx) o += P.off[p][P.n_f + sidx] * (int64_t)k[sidx];
+                ptr[p] = static_cast<const T *>(A.p[p]) + o;
+            }
+            for (int32_t it = 0; it < mine; it += U) {
+                T v[U][NA];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t m = it + u < mine ? u : 0;
+                    for (int p = 0; p < NA; ++p) v[u][p] = ptr[p][m * stp[p]];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (it + u < mine) acc += (double)body_inner<BODY, T>(v[u]);
+                for (int p = 0; p < NA; ++p) ptr[p] += U * stp[p];
+            }
+            int sidx = last - 1;
+            for (; sidx >= 0; --sidx) {
+                if (++k[sidx] < P.sum_n[sidx]) break;
+                k[sidx] = 0;
+            }
+            if (sidx < 0) break;
+        }
+        return acc;
+    }
     auto term = [&]() {
         if (forward_conditions(P, ext, k)) {   // a term outside the extra conditions is not part of the sum
             T v[NA];
