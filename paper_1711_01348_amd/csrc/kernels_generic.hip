@@ -151,17 +151,30 @@ __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const
     if (!gather_element_index(P, idx, lin, y)) return false;
     double acc = 0.0;
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
-        // innermost run: offsets advance by a constant per step
-        int64_t off[NA + 1];
-        for (int q = 0; q < NA; ++q) off[q] = gather_offset(P, q, y, z);
+        // innermost run: offsets advance by a constant per step.  Four terms are loaded before the first is used,
+        // so that the loop waits for memory once per four terms (the terms are still added in ascending order;
+        // the slots past the end of the run reload its current term and are dropped).
+        constexpr int U = 4;
+        int64_t off[NA + 1], stp[NA + 1];
+        for (int q = 0; q < NA; ++q) {
+            off[q] = gather_offset(P, q, y, z);
+            stp[q] = P.offZ[q][0] * step;
+        }
         off[NA] = gather_offset(P, kSlotF, y, z);
-        for (int32_t it = 0; it < n; ++it) {
-            T v[NA];
-            for (int q = 0; q < NA; ++q) v[q] = static_cast<const T *>(A.p[q])[off[q]];
-            const T fv = f[off[NA]], dfv = df[off[NA]];
-            acc += (double)(dfv * body_douter<BODY, T>(fv, v) * body_dinner<BODY, T>(p, v));
-            for (int q = 0; q < NA; ++q) off[q] += P.offZ[q][0] * step;
-            off[NA] += P.offZ[kSlotF][0] * step;
+        stp[NA] = P.offZ[kSlotF][0] * step;
+        for (int32_t it = 0; it < n; it += U) {
+            T v[U][NA], fv[U], dfv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t m = it + u < n ? u : 0;
+                for (int q = 0; q < NA; ++q) v[u][q] = static_cast<const T *>(A.p[q])[off[q] + m * stp[q]];
+                fv[u] = f[off[NA] + m * stp[NA]];
+                dfv[u] = df[off[NA] + m * stp[NA]];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (it + u < n) acc += (double)(dfv[u] * body_douter<BODY, T>(fv[u], v[u]) * body_dinner<BODY, T>(p, v[u]));
+            for (int q = 0; q <= NA; ++q) off[q] += U * stp[q];
         }
     }, group, groups);
     *sum = acc;
