@@ -266,15 +266,20 @@ def band_expr(N: int, W: int, dtype: str) -> ExprSpec:
                     constraints=[([-1, 1], 0), ([1, -1], W)])
 
 
-def random_expr(seed: int, dtype: str = "f64") -> ExprSpec:
+def random_expr(seed: int, dtype: str = "f64", long_index: bool = False) -> ExprSpec:
     """A seeded random expression: 1..3 function indices, 0..2 summation indices (at most 4 together), one or two
     operands of rank 1..3 with small non-negative index coefficients, sometimes a negative one made safe by a
-    condition, operand shapes with some slack beyond the referenced range."""
-    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 5000 + seed))
+    condition, operand shapes with some slack beyond the referenced range.  Every index has 2..5 values; with
+    long_index one of them, chosen at random, has 1100..2600 (gradients or function elements with long sums)."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + (9000 if long_index else 5000) + seed))
     n_f = int(rng.integers(1, 4))
     n_sum = int(rng.integers(0, min(2, 4 - n_f) + 1))
     D = n_f + n_sum
     ext = [int(rng.integers(2, 6)) for _ in range(D)]
+    long_at = -1
+    if long_index:
+        long_at = int(rng.integers(0, D))
+        ext[long_at] = int(rng.integers(1100, 2601))
     sums = []
     for q in range(n_sum):
         lo = int(rng.integers(0, 2))
@@ -298,6 +303,11 @@ def random_expr(seed: int, dtype: str = "f64") -> ExprSpec:
             cond = [0] * D
             cond[i], cond[k] = 1, -1
             constraints.append((cond, 0))
+        if long_at >= 0:
+            # the long index in one row of an operand only, so that no tensor grows with its square
+            rows_with = [r for r in range(rank) if A[r][long_at] != 0]
+            for r in rows_with[1:]:
+                A[r][long_at] = 0          # a row of zeros is a valid index map (that axis is read at 0)
         shape = tuple(max(1, sum(c * (hi[d] if c > 0 else lo[d]) for d, c in enumerate(row)) + 1) + int(rng.integers(0, 3))
                       for row in A)
         args.append(ArgSpec("xy"[p], shape, A))

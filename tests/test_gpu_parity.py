@@ -157,6 +157,25 @@ def test_random_expressions(seed):
     assert_parity(wp, f, grads, f_ref, g_ref, "random %d as program" % seed)
 
 
+@pytest.mark.parametrize("seed", range(32))
+def test_random_expressions_with_a_long_index(seed):
+    """The same random expressions with one index of 1100..2600 values: gradients (or function elements) that sum
+    thousands of terms, so that the plan-driven kernels lay their threads out in every way they know (one workgroup
+    per element, several per element, one thread per element with shared sums, unmasked elements only).  fp32:
+    in fp64 the order in which thousands of terms are added shows at the 1e-12 level."""
+    e = wl.random_expr(seed, "f32", long_index=True)
+    terms = int(np.prod([hi - lo + 1 for lo, hi in e.sums])) if e.sums else 1
+    span = min(0.03, 2.0 / terms) if e.body == "exp" else 0.03     # exp of the sum must stay inside fp32
+    w = wl.random_inputs(e, 300 + seed, -span, span)
+    f_ref, g_ref = oracle_all(w, 8)
+    _, f, grads = run_gpu(w)
+    assert_parity(w, f, grads, f_ref, g_ref, "random %d with a long index" % seed)
+    wp = wl.Workload(w.name, wl.as_program(e), w.inputs, w.df)
+    plan, f, grads = run_gpu(wp)
+    assert plan.forward_family in ("program", "contraction")
+    assert_parity(wp, f, grads, f_ref, g_ref, "random %d with a long index, as program" % seed)
+
+
 LONG_SUMS = [
     ("matmul_f64", lambda: wl.matmul_expr(12, 9, 1500, "f64")),                       # plan-driven kernels (fp64)
     ("matmul_program_f32", lambda: wl.as_program(wl.matmul_expr(10, 7, 1300, "f32", True, False))),
