@@ -343,11 +343,12 @@ int tad_plan_forward_family(const tad_plan *plan);
  */
 int tad_plan_program_eval(const tad_plan *plan, int which, const double *values, double sum, double *out);
 /*
- * Number of registers of the register form of one of those programs (`which` as above): the kernels keep a
- * program's temporaries in that many vector registers per term and interpret several terms per pass (Sec. 2:
- * the derivative is again a computational graph; its live values decide the registers).  *registers_out = 0:
- * more live values than the register form holds; the kernels then interpret the form with one temporary per
- * operation in the thread's private memory.  Also 0 for a program that is identically zero.
+ * Number of registers of the register form of one of those programs (`which` as above): the kernels read tensor
+ * values, constants and the sum where an operation uses them, keep every other temporary in one of that many
+ * vector registers per term and interpret several terms per pass (Sec. 2: the derivative is again a computational
+ * graph; its live values decide the registers).  *registers_out = -1: more live values than the register form
+ * holds; the kernels then interpret the form with one temporary per operation in the thread's private memory.
+ * 0: the program is a single operand, a constant, or identically zero.
  * Errors: EINVAL (not a program plan, bad `which`, derivative not planned, NULL).
  */
 int tad_plan_program_registers(const tad_plan *plan, int which, int *registers_out);

@@ -258,8 +258,8 @@ class Plan:
         return out.value
 
     def program_registers(self, which: int) -> int:
-        """Registers of the register form of a derived scalar program (`which` as in program_eval); 0: the
-        kernels interpret the form with one temporary per operation (or the program is identically zero)."""
+        """Registers of the register form of a derived scalar program (`which` as in program_eval); -1: the
+        kernels interpret the form with one temporary per operation; 0: a single operand, a constant or zero."""
         n = ctypes.c_int(0)
         _check(lib.tad_plan_program_registers(self._h, which, ctypes.byref(n)), "tad_plan_program_registers")
         return n.value

@@ -113,44 +113,67 @@ __device__ __forceinline__ void prog_eval_block(const DevProg &P, const T (&v)[k
     }
     // not cleared: the allocation on the host writes every register before it is read
     T r0[kProgRegs], r1[kProgRegs], r2[kProgRegs], r3[kProgRegs];
-    // EXPR sees the term's register array as `r` and its number as `u`
-#define TAD_EACH_TERM(EXPR)                                                                      \
-    {                                                                                            \
-        { T(&r)[kProgRegs] = r0; constexpr int u = 0; (void)r; (void)u; o[u] = EXPR; }           \
-        if (U > 1) { T(&r)[kProgRegs] = r1; constexpr int u = U > 1 ? 1 : 0; (void)r; (void)u; o[u] = EXPR; } \
-        if (U > 2) { T(&r)[kProgRegs] = r2; constexpr int u = U > 2 ? 2 : 0; (void)r; (void)u; o[u] = EXPR; } \
-        if (U > 3) { T(&r)[kProgRegs] = r3; constexpr int u = U > 3 ? 3 : 0; (void)r; (void)u; o[u] = EXPR; } \
+    // DST[u] = EXPR for every term u; EXPR sees the term's register array as `r` and its number as `u`
+#define TAD_EACH_TERM(DST, EXPR)                                                                    \
+    {                                                                                               \
+        { T(&r)[kProgRegs] = r0; constexpr int u = 0; (void)r; (void)u; DST[u] = EXPR; }            \
+        if (U > 1) { T(&r)[kProgRegs] = r1; constexpr int u = U > 1 ? 1 : 0; (void)r; (void)u; DST[u] = EXPR; } \
+        if (U > 2) { T(&r)[kProgRegs] = r2; constexpr int u = U > 2 ? 2 : 0; (void)r; (void)u; DST[u] = EXPR; } \
+        if (U > 3) { T(&r)[kProgRegs] = r3; constexpr int u = U > 3 ? 3 : 0; (void)r; (void)u; DST[u] = EXPR; } \
+    }
+    // DST[u] = the operand with code CODE (wave-uniform): a register, a tensor operand, a constant or the sum.
+    // The operand number selects code, not an address: v stays in registers.
+#define TAD_FETCH(DST, CODE)                                                         \
+    {                                                                                \
+        static_assert(kMaxArgs == 6, "one case per operand");                        \
+        const int code_ = (CODE);                                                    \
+        if (code_ < kCodeArg) {                                                      \
+            const int reg_ = code_ & (kProgRegs - 1);                                \
+            TAD_EACH_TERM(DST, r[reg_])                                              \
+        } else if (code_ < kCodeConst) {                                             \
+            switch (code_ - kCodeArg) {                                              \
+            case 0: TAD_EACH_TERM(DST, v[0][u]) break;                               \
+            case 1: TAD_EACH_TERM(DST, v[1][u]) break;                               \
+            case 2: TAD_EACH_TERM(DST, v[2][u]) break;                               \
+            case 3: TAD_EACH_TERM(DST, v[3][u]) break;                               \
+            case 4: TAD_EACH_TERM(DST, v[4][u]) break;                               \
+            default: TAD_EACH_TERM(DST, v[5][u])                                     \
+            }                                                                        \
+        } else if (code_ < kCodeSum) {                                               \
+            const T cst_ = (T)P.cst[(code_ - kCodeConst) & (kMaxProgConst - 1)];     \
+            TAD_EACH_TERM(DST, cst_)                                                 \
+        } else {                                                                     \
+            TAD_EACH_TERM(DST, s[u])                                                 \
+        }                                                                            \
     }
     uint32_t w = P.word[0];
-    for (int i = 0; i < P.n; ++i) {
+    for (int i = 0; i < P.n_words; ++i) {
         const uint32_t next = P.word[(i + 1) & (kMaxProgOps - 1)];
         const int op = (int)(w & 0xff), first = (int)((w >> 8) & 0xff), second = (int)((w >> 16) & 0xff);
         const int dst = (int)(w >> 24) & (kProgRegs - 1);
-        const int ra = first & (kProgRegs - 1), rb = second & (kProgRegs - 1);
-        T o[U];
+        T x[U], y[U], o[U];
+        TAD_FETCH(x, first)
+        if (op >= P_ADD && op <= P_DIV) TAD_FETCH(y, second)
         switch (op) {
-        case P_CONST: {
-            const T c = (T)P.cst[first & (kMaxProgConst - 1)];
-            TAD_EACH_TERM(c)
+        case P_ADD:
+#pragma unroll
+            for (int u = 0; u < U; ++u) o[u] = x[u] + y[u];
             break;
-        }
-        case P_ARG:   // the operand number selects code, not an address: v stays in registers
-            static_assert(kMaxArgs == 6, "one case per operand");
-            switch (first) {
-            case 0: TAD_EACH_TERM(v[0][u]) break;
-            case 1: TAD_EACH_TERM(v[1][u]) break;
-            case 2: TAD_EACH_TERM(v[2][u]) break;
-            case 3: TAD_EACH_TERM(v[3][u]) break;
-            case 4: TAD_EACH_TERM(v[4][u]) break;
-            default: TAD_EACH_TERM(v[5][u])
-            }
+        case P_SUB:
+#pragma unroll
+            for (int u = 0; u < U; ++u) o[u] = x[u] - y[u];
             break;
-        case P_SUM: TAD_EACH_TERM(s[u]) break;
-        case P_ADD: TAD_EACH_TERM(r[ra] + r[rb]) break;
-        case P_SUB: TAD_EACH_TERM(r[ra] - r[rb]) break;
-        case P_MUL: TAD_EACH_TERM(r[ra] * r[rb]) break;
-        case P_DIV: TAD_EACH_TERM(r[ra] / r[rb]) break;
-        default: TAD_EACH_TERM(prog_unary<T>(op, r[ra], second))
+        case P_MUL:
+#pragma unroll
+            for (int u = 0; u < U; ++u) o[u] = x[u] * y[u];
+            break;
+        case P_DIV:
+#pragma unroll
+            for (int u = 0; u < U; ++u) o[u] = x[u] / y[u];
+            break;
+        default:
+#pragma unroll
+            for (int u = 0; u < U; ++u) o[u] = prog_unary<T>(op, x[u], second);
         }
         r0[dst] = o[0];
         if (U > 1) r1[dst] = o[U > 1 ? 1 : 0];
@@ -158,12 +181,9 @@ __device__ __forceinline__ void prog_eval_block(const DevProg &P, const T (&v)[k
         if (U > 3) r3[dst] = o[U > 3 ? 3 : 0];
         w = next;
     }
+    TAD_FETCH(out, P.result_code)
+#undef TAD_FETCH
 #undef TAD_EACH_TERM
-    const int rr = P.result_reg & (kProgRegs - 1);
-    out[0] = r0[rr];
-    if (U > 1) out[U > 1 ? 1 : 0] = r1[rr];
-    if (U > 2) out[U > 2 ? 2 : 0] = r2[rr];
-    if (U > 3) out[U > 3 ? 3 : 0] = r3[rr];
 }
 
 // one term
@@ -300,8 +320,9 @@ __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_op
 
 // df == nullptr: out = outer(sum, operands) (forward);  otherwise out = df * (d outer / d sum)(sum, operands)
 // (backward preparation).  outer_mask: operands `outer` reads.  s_out (may be null): receives the sum.
+// (fp32: three wavefronts per SIMD -- the register forms would otherwise end a few registers above that step)
 template <typename T, int FORM>
-__global__ __launch_bounds__(256) void k_program_forward(const ForwardPlan P, const DevProg inner, const DevProg outer,
+__global__ __launch_bounds__(256, sizeof(T) == 4 ? 3 : 1) void k_program_forward(const ForwardPlan P, const DevProg inner, const DevProg outer,
                                                          int n_ops, uint32_t outer_mask, const ArgPtrs A,
                                                          const T *__restrict__ df, T *__restrict__ out,
                                                          T *__restrict__ s_out, int nf) {
@@ -523,7 +544,7 @@ __global__ __launch_bounds__(256) void k_program_gather_lanes(const GatherPlan P
 }
 
 // a program that is identically zero is never interpreted
-static bool has_register_form(const DevProg &P) { return P.result < 0 || P.n_regs > 0; }
+static bool has_register_form(const DevProg &P) { return P.result < 0 || P.n_regs >= 0; }
 
 // Kernel form for a launch whose runs have about `run_terms` terms: several terms per pass pay from three terms on.
 static int program_form(bool registers, double run_terms) { return !registers ? 0 : run_terms >= 3.0 ? 2 : 1; }

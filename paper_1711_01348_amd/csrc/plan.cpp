@@ -714,7 +714,7 @@ int tad_plan_program_registers(const tad_plan *plan, int which, int *registers_o
     if (operand >= 0 && !plan->ap[operand].derived) return TAD_EINVAL;   // derivative not planned
     const DevProg &prog = which == -1 ? pb.inner : which >= 0 ? pb.dinner[which] : which == -2 ? pb.outer
                           : which == -3 ? pb.douter : pb.douter_arg[operand];
-    *registers_out = prog.result < 0 ? 0 : prog.n_regs;
+    *registers_out = prog.result < 0 ? 0 : prog.n_regs;   // < 0: no register form
     return TAD_OK;
 }
 

@@ -122,19 +122,27 @@ enum ProgOp : uint8_t {
     P_CONST, P_ARG, P_SUM, P_ADD, P_SUB, P_MUL, P_DIV, P_NEG, P_EXP, P_LOG, P_SIN, P_COS, P_TANH, P_SQRT, P_POWI
 };
 constexpr int kProgRegs = 16;   // registers of the register form of a program
+// operand codes of the register form: 0 .. kProgRegs-1 a register, then
+constexpr int kCodeArg = 16;     // + p: the value of tensor operand p
+constexpr int kCodeConst = 32;   // + c: constant c
+constexpr int kCodeSum = 48;     // the sum (outer programs)
 struct DevProg {
     int32_t n;        // operations
     int32_t result;   // temporary holding the result; -1: the function is identically zero
     uint8_t op[kMaxProgOps], a[kMaxProgOps], b[kMaxProgOps];   // a: first input / operand index / constant index / exponent base
     int8_t k[kMaxProgOps];                                     // exponent of P_POWI
     double cst[kMaxProgConst];
-    // Register form of the same program: every temporary is assigned one of kProgRegs registers by its live
-    // range, so that the kernels' interpreter keeps them in vector registers (indexed by a wave-uniform number)
-    // instead of the thread's private memory.  word[i] = op | first << 8 | second << 16 | destination << 24,
-    // where first is a register, an operand index or a constant index as in `a`, and second is a register or,
-    // for P_POWI, the exponent.  n_regs == 0: the program needs more registers; only the form above exists.
+    // Register form of the same program, as the kernels' interpreter runs it: operands (tensor values, the sum,
+    // constants) are read where they are used instead of being copied by operations of their own, and every other
+    // temporary is assigned one of kProgRegs registers by its live range, so that the temporaries stay in vector
+    // registers (indexed by a wave-uniform number) instead of the thread's private memory.
+    //   word[i] = op | first << 8 | second << 16 | destination << 24        (n_words of them)
+    //   first, second: an operand code (prog_code_*: register, tensor operand, constant, the sum); for P_POWI
+    //   `second` is the exponent; destination: a register.  result_code: operand code of the result.
+    // n_regs < 0: the program needs more registers than there are; only the form above exists.
     int32_t n_regs;
-    int32_t result_reg;
+    int32_t n_words;
+    int32_t result_code;
     uint32_t word[kMaxProgOps];
 };
 

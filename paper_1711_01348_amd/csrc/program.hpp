@@ -195,32 +195,30 @@ inline double eval_host_temporaries(const DevProg &P, const double *v, double s)
 inline double eval_host_registers(const DevProg &P, const double *v, double s) {
     if (P.result < 0) return 0.0;
     double r[kProgRegs] = {0};
-    for (int i = 0; i < P.n; ++i) {
+    auto fetch = [&](int code) {
+        return code < kCodeArg ? r[code] : code < kCodeConst ? v[code - kCodeArg] : code < kCodeSum ? P.cst[code - kCodeConst] : s;
+    };
+    for (int i = 0; i < P.n_words; ++i) {
         const uint32_t w = P.word[i];
         const uint8_t op = (uint8_t)(w & 0xff);
         const int first = (int)((w >> 8) & 0xff), second = (int)((w >> 16) & 0xff), dst = (int)(w >> 24);
-        double o;
-        switch (op) {
-        case P_CONST: o = P.cst[first]; break;
-        case P_ARG: o = v[first]; break;
-        case P_SUM: o = s; break;
-        case P_POWI: o = prog_apply(op, r[first], 0.0, second); break;
-        default: o = prog_apply(op, r[first], prog_is_binary(op) ? r[second] : 0.0, 0);
-        }
-        r[dst] = o;
+        r[dst] = op == P_POWI ? prog_apply(op, fetch(first), 0.0, second)
+                              : prog_apply(op, fetch(first), prog_is_binary(op) ? fetch(second) : 0.0, 0);
     }
-    return r[P.result_reg];
+    return fetch(P.result_code);
 }
 
-// Assign registers by live range, in program order: the inputs an operation reads for the last time are released
-// before its destination is chosen (an operation reads before it writes), the lowest free register is taken.
-// The result is checked against the form with one temporary per operation at a few points; a program that
-// needs more than kProgRegs registers, or fails the check, keeps n_regs == 0.
+// Register form: operands are folded into the operations that use them (no register, no operation of their
+// own); the other temporaries get registers by live range, in program order: the inputs an operation reads for the
+// last time are released before its destination is chosen (an operation reads before it writes), the lowest free
+// register is taken.  The result is checked against the form with one temporary per operation at a few points; a
+// program that needs more than kProgRegs registers, or fails the check, keeps n_regs < 0.
 inline void allocate_registers(DevProg &P) {
-    P.n_regs = 0;
-    P.result_reg = 0;
+    P.n_regs = -1;
+    P.n_words = 0;
+    P.result_code = 0;
     if (P.result < 0 || P.n <= 0) return;
-    int last[kMaxProgOps], reg[kMaxProgOps];
+    int last[kMaxProgOps], code[kMaxProgOps];
     for (int i = 0; i < P.n; ++i) last[i] = -1;
     for (int i = 0; i < P.n; ++i) {
         if (prog_is_leaf(P.op[i])) continue;
@@ -229,24 +227,27 @@ inline void allocate_registers(DevProg &P) {
     }
     last[P.result] = P.n;
     bool used[kProgRegs] = {false};
-    int high = 0;
+    int high = 0, words = 0;
     for (int i = 0; i < P.n; ++i) {
         const uint8_t op = P.op[i];
-        const bool leaf = prog_is_leaf(op), binary = prog_is_binary(op);
-        const int ra = leaf ? (int)P.a[i] : reg[P.a[i]], rb = binary ? reg[P.b[i]] : op == P_POWI ? (int)(uint8_t)P.k[i] : 0;
-        if (!leaf) {
-            if (last[P.a[i]] == i) used[reg[P.a[i]]] = false;
-            if (binary && last[P.b[i]] == i) used[reg[P.b[i]]] = false;
+        if (prog_is_leaf(op)) {
+            code[i] = op == P_ARG ? kCodeArg + P.a[i] : op == P_CONST ? kCodeConst + P.a[i] : kCodeSum;
+            continue;
         }
+        const bool binary = prog_is_binary(op);
+        const int first = code[P.a[i]], second = binary ? code[P.b[i]] : op == P_POWI ? (int)(uint8_t)P.k[i] : 0;
+        if (first < kCodeArg && last[P.a[i]] == i) used[first] = false;
+        if (binary && second < kCodeArg && last[P.b[i]] == i) used[second] = false;
         int r = 0;
         while (r < kProgRegs && used[r]) ++r;
         if (r == kProgRegs) return;
-        reg[i] = r;
+        code[i] = r;
         if (last[i] >= 0) used[r] = true;      // a value nobody reads frees its register at once
         high = std::max(high, r + 1);
-        P.word[i] = (uint32_t)op | (uint32_t)ra << 8 | (uint32_t)rb << 16 | (uint32_t)r << 24;
+        P.word[words++] = (uint32_t)op | (uint32_t)first << 8 | (uint32_t)second << 16 | (uint32_t)r << 24;
     }
-    P.result_reg = reg[P.result];
+    P.n_words = words;
+    P.result_code = code[P.result];
     // self-check at deterministic sample points (NaN results must agree as NaN)
     for (int t = 0; t < 4; ++t) {
         double v[TAD_MAX_ARGS];
@@ -377,7 +378,7 @@ inline bool reads_operands(const DevProg &P) {
     return false;
 }
 inline double eval_host(const DevProg &P, const double *v, double s) {
-    return P.n_regs > 0 ? eval_host_registers(P, v, s) : eval_host_temporaries(P, v, s);
+    return P.n_regs >= 0 ? eval_host_registers(P, v, s) : eval_host_temporaries(P, v, s);
 }
 
 // Everything a program-body plan carries.

@@ -548,24 +548,27 @@ def test_gather_layouts_of_the_plan_driven_kernels():
 
 
 def test_program_register_form():
-    """Registers assigned to the temporaries of the derived programs by live range: as many as values are alive at
-    once, none (0) beyond 16 -- the kernels then fall back to one temporary per operation -- and none for a
-    program that is identically zero.  Both forms evaluate alike (the host evaluator uses the register form when
-    there is one; the oracle comparison above covers the values)."""
+    """Registers assigned to the temporaries of the derived programs by live range: operands, constants and the sum
+    take none (they are read where they are used); as many as values are alive at once; -1 beyond 16 -- the
+    kernels then fall back to one temporary per operation.  Both forms evaluate alike (the host evaluator uses the
+    register form when there is one; the oracle comparison above covers the values)."""
     plan = B.Plan(_scalar_expr(wl.many_live_values_expr(2, 2, "f64").inner, [("sum",)], 2))
-    assert plan.program_registers(-1) == 0
+    assert plan.program_registers(-1) == -1                                        # 18 function values alive at once
     assert 1 <= plan.program_registers(0) <= 16 and 1 <= plan.program_registers(1) <= 16
-    assert plan.program_registers(-2) == 1 and plan.program_registers(-3) == 1     # the sum itself; the constant 1
+    assert plan.program_registers(-2) == 0 and plan.program_registers(-3) == 0     # the sum itself; the constant 1
     assert plan.program_registers(-4) == 0                                         # d outer / d operand: zero
-    # x * y: both operands are alive at the multiplication, whose result reuses a register
+    # x * y: one operation on two operands
     plan = B.Plan(_scalar_expr([("arg", 0), ("arg", 1), ("mul",)], [("sum",)], 2))
-    assert plan.program_registers(-1) == 2
-    assert plan.program_registers(0) == 1 and plan.program_registers(1) == 1       # d/dx = y, d/dy = x
+    assert plan.program_registers(-1) == 1
+    assert plan.program_registers(0) == 0 and plan.program_registers(1) == 0       # d/dx = y, d/dy = x: operands
     # a chain of unary operations needs one register however long it is
     plan = B.Plan(_scalar_expr([("arg", 0)] + [("sin",), ("exp",), ("tanh",)] * 5, [("sum",)], 1))
     assert plan.program_registers(-1) == 1
-    assert _status(lambda: plan.program_registers(1)) == -1
-    assert _status(lambda: plan.program_registers(-5)) == -1
+    # (x + y) * (x - y): two values alive before the product
+    plan = B.Plan(_scalar_expr([("arg", 0), ("arg", 1), ("add",), ("arg", 0), ("arg", 1), ("sub",), ("mul",)], [("sum",)], 2))
+    assert plan.program_registers(-1) == 2
+    assert _status(lambda: plan.program_registers(2)) == -1
+    assert _status(lambda: plan.program_registers(-6)) == -1
     assert _status(lambda: B.Plan(wl.config1().expr).program_registers(-1)) == -1   # not a program plan
 
 
