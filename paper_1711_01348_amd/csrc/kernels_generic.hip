@@ -253,6 +253,31 @@ __global__ __launch_bounds__(256) void k_generic_gather_lanes(const GatherPlan P
     else store_element(dx, lin, live, acc, accumulate);
 }
 
+// Several gradients of a small expression in one launch: every kernel launch starts with cold instruction caches,
+// and a wavefront that walks this code once spends most of its time fetching it (8 to 25 us per launch for a few
+// dozen terms); in one launch the gradients pay that together instead of one after the other.  Workgroups of one
+// wavefront; workgroup b works on gradient g with first[g] <= b < first[g + 1].
+struct MultiGather {
+    int32_t count;
+    int32_t first[kMaxArgs + 1];
+    int32_t n[kMaxArgs];         // elements of gradient g
+    int32_t operand[kMaxArgs];   // operand whose plan and partial derivative gradient g uses
+    void *dx[kMaxArgs];
+    GatherPlan plan[kMaxArgs];
+};
+template <int BODY, typename T>
+__global__ __launch_bounds__(64) void k_generic_gather_multi(const MultiGather M, const ArgPtrs A,
+                                                             const T *__restrict__ f, const T *__restrict__ df) {
+    int g = 0;
+    while (g + 1 < M.count && (int)blockIdx.x >= M.first[g + 1]) ++g;   // the same for the whole workgroup
+    const int idx = ((int)blockIdx.x - M.first[g]) * 64 + (int)threadIdx.x;
+    if (idx >= M.n[g]) return;
+    double acc;
+    int lin;
+    const bool live = gather_element<BODY, T>(M.plan[g], M.operand[g], A, f, df, idx, &lin, 0, 1, &acc);
+    store_element(static_cast<T *>(M.dx[g]), lin, live, acc, 0);
+}
+
 template <int BODY, typename T>
 static int launch_body(const tad_plan &pl, const void *const *args, const void *f, const void *df,
                        void *const *dx, void *fout, void *ws, hipStream_t s) {
@@ -275,6 +300,33 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
             TAD_LAUNCH("k_generic_forward", (k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
                        A, static_cast<T *>(fout), nf);
         return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+    }
+    // a small expression without aliases: all gradients in one launch
+    if (!pl.has_alias && pl.terms_total < (double)kHeavyTerms) {
+        MultiGather M{};
+        bool fits = true;
+        long long blocks = 0;
+        for (size_t q = 0; q < pl.args.size() && fits; ++q) {
+            if (!dx[q]) continue;
+            const long long n = pl.arg_count[q];
+            fits = pl.ap[q].family == TAD_FAMILY_GENERIC && pl.ap[q].derived && n <= (1 << 16) &&
+                   gather_shape(pl.ap[q].dev, n, pl.terms_total).layout == kLayoutThreads;
+            if (!fits) break;
+            const int g = M.count++;
+            M.first[g] = (int32_t)blocks;
+            M.n[g] = (int32_t)n;
+            M.operand[g] = (int32_t)q;
+            M.dx[g] = dx[q];
+            M.plan[g] = pl.ap[q].dev;
+            M.plan[g].live = 0;   // all elements of the small tensor are visited; masked ones are stored as zeros
+            blocks += (n + 63) / 64;
+        }
+        if (fits && M.count >= 2) {
+            M.first[M.count] = (int32_t)blocks;
+            TAD_LAUNCH("k_generic_gather_multi", (k_generic_gather_multi<BODY, T>), dim3((unsigned)blocks), dim3(64), 0, s,
+                       M, A, static_cast<const T *>(f), static_cast<const T *>(df));
+            return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+        }
     }
     // the gradient of a tensor is the sum over its occurrences (Sec. 5.3): the first occurrence stores,
     // every alias operand adds in a launch of its own
