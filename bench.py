@@ -22,7 +22,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VALU_TFLOPS = 157.3       # published vector fp32 peak (packed); 256 CUs x 2.4 GHz x 256 flop/clk
 FP32_MFMA_TFLOPS = 157.3
-PROFILE_EVERY = 7               # every 7th launch of the dominant kernel carries timing events (a timed launch delays its successor)
+PROFILE_EVERY = 25              # every 25th launch of the dominant kernel carries timing events (a timed launch delays its
+                                # successor: every 7th cost the 25 us workload 3 us per step, every 25th nothing measurable)
 ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 2x the 256 MB last-level cache)
 
 
