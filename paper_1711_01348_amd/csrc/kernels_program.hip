@@ -543,6 +543,30 @@ __global__ __launch_bounds__(256) void k_program_gather_lanes(const GatherPlan P
     else store_element(dx, lin, live, acc, accumulate);
 }
 
+// Several gradients of a small expression in one launch (every launch starts with cold instruction caches, which a
+// wavefront that walks this code once pays dearly: together instead of one after the other).  Workgroups of one
+// wavefront; workgroup b works on gradient g with first[g] <= b < first[g + 1].
+struct MultiProgramGather {
+    int32_t count;
+    int32_t first[kMaxArgs + 1];
+    int32_t n[kMaxArgs];         // elements of gradient g
+    void *dx[kMaxArgs];
+    GatherPlan plan[kMaxArgs];
+    DevProg dinner[kMaxArgs];    // d inner / d operand of gradient g
+};
+template <typename T, int FORM>
+__global__ __launch_bounds__(64) void k_program_gather_multi(const MultiProgramGather M, int n_ops, const ArgPtrs A,
+                                                             const T *__restrict__ g) {
+    int w = 0;
+    while (w + 1 < M.count && (int)blockIdx.x >= M.first[w + 1]) ++w;   // the same for the whole workgroup
+    const int idx = ((int)blockIdx.x - M.first[w]) * 64 + (int)threadIdx.x;
+    if (idx >= M.n[w]) return;
+    double acc;
+    int lin;
+    const bool live = program_element<T, FORM>(M.plan[w], M.dinner[w], n_ops, A, g, idx, &lin, 0, 1, &acc);
+    store_element(static_cast<T *>(M.dx[w]), lin, live, acc, 0);
+}
+
 // a program that is identically zero is never interpreted
 static bool has_register_form(const DevProg &P) { return P.result < 0 || P.n_regs >= 0; }
 
@@ -609,6 +633,34 @@ static int bwd_t(const tad_plan &pl, const void *const *args, const void *df, vo
     auto split_live = [&](int n, int splits) {
         return reinterpret_cast<int32_t *>(reinterpret_cast<char *>(split_partial) + align256((size_t)n * splits * 8));
     };
+    // a small expression without aliases whose outer function reads no operand: all gradients in one launch
+    if (!pl.has_alias && !pl.prog.outer_mask && pl.terms_total < (double)kHeavyTerms) {
+        MultiProgramGather M{};
+        bool fits = true, registers = true;
+        long long blocks = 0;
+        for (size_t q = 0; q < pl.args.size() && fits; ++q) {
+            if (!dx[q]) continue;
+            const long long n = pl.arg_count[q];
+            fits = pl.ap[q].derived && n <= (1 << 16) &&
+                   gather_shape(pl.ap[q].dev, n, pl.terms_total).layout == kLayoutThreads;
+            if (!fits) break;
+            const int w = M.count++;
+            M.first[w] = (int32_t)blocks;
+            M.n[w] = (int32_t)n;
+            M.dx[w] = dx[q];
+            M.plan[w] = pl.ap[q].dev;
+            M.plan[w].live = 0;   // all elements of the small tensor are visited; masked ones are stored as zeros
+            M.dinner[w] = pl.prog.dinner[q];
+            registers = registers && has_register_form(pl.prog.dinner[q]);
+            blocks += (n + 63) / 64;
+        }
+        if (fits && M.count >= 2) {
+            M.first[M.count] = (int32_t)blocks;
+            TAD_LAUNCH_FORM(registers ? 1 : 0, "k_program_gather_multi", k_program_gather_multi, dim3((unsigned)blocks),
+                            dim3(64), 0, s, M, n_ops, A, static_cast<const T *>(ws));
+            return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+        }
+    }
     // the gradient of a tensor is the sum over its occurrences: the first occurrence stores, aliases add
     for (size_t q = 0; q < pl.args.size(); ++q) {
         const size_t p = (size_t)pl.root[q];
