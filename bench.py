@@ -43,7 +43,7 @@ MEASURED_TRAFFIC = {
             summary="profiles/diagonal_8192_f32.md"),
     "cfg2_3": dict(source="kernels_patterns.hip", sha256="4a0de37557d44903", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
             summary="profiles/antidiagonal_4096x4096_f32.md"),
-    "cfg5": dict(source="kernels_strided.hip", sha256="c66b878b377c9ecf", fetch_bytes=24.1 * 2**20, write_bytes=8.1 * 2**20,
+    "cfg5": dict(source="kernels_strided.hip", sha256="45eafb292ba47827", fetch_bytes=24.2 * 2**20, write_bytes=8.1 * 2**20,
             summary="profiles/strided_32x128x128_f32.md"),
 }
 

@@ -77,25 +77,53 @@ __global__ __launch_bounds__(256) void k_strided_backward(const StridedGeom g, c
     const int taps = g.U * g.V;
     // the few long-running dw blocks come first in launch order so that they overlap the dx stream
     if ((int)blockIdx.x >= blocks_dw) {
-        if (threadIdx.x < taps) ws[threadIdx.x] = w[threadIdx.x];
-        __syncthreads();
         const int lin = ((int)blockIdx.x - blocks_dw) * 256 + threadIdx.x;
-        if (lin >= n_x) return;
+        const bool inside = lin < n_x;
         const int q = lin % g.Q, t = lin / g.Q;
         const int32_t y[3] = {t / g.P, t % g.P, q};
-        float acc = 0.f;
-        if (flat_feasible(D.feas, y)) {
-            int32_t lo1, hi1, lo0, hi0;
+        int32_t lo1 = 0, hi1 = -1, lo0 = 0, hi0 = -1;
+        if (inside && flat_feasible(D.feas, y)) {
             flat_bounds(D.lvl[1], y, lo1, hi1);
             flat_bounds(D.lvl[0], y, lo0, hi0);
-            const int base_f = D.fY[0] * y[0] + D.fY[1] * y[1] + D.fY[2] * y[2];
-            const int base_w = D.wY[0] * y[0] + D.wY[1] * y[1] + D.wY[2] * y[2];
+        }
+        const int base_f = D.fY[0] * y[0] + D.fY[1] * y[1] + D.fY[2] * y[2];
+        const int base_w = D.wY[0] * y[0] + D.wY[1] * y[1] + D.wY[2] * y[2];
+        const int n1 = hi1 - lo1 + 1, n0 = hi0 - lo0 + 1;
+        // Up to two values per coordinate (a stride of two or more under a 3 x 3 filter, ...): the loads of all
+        // terms are issued together, before the filter taps are staged, so that the wavefront waits for memory
+        // once instead of once per term.  Terms are added in the order of the loops below.
+        const bool few = n1 <= 2 && n0 <= 2;
+        float fv[2][2], dv[2][2];
+        if (few) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    const bool on = a < n1 && b < n0;
+                    const int of = base_f + D.fZ[1] * (lo1 + a) + D.fZ[0] * (lo0 + b);
+                    fv[a][b] = on ? f[of] : 0.f;
+                    dv[a][b] = on ? df[of] : 0.f;
+                }
+        }
+        if (threadIdx.x < taps) ws[threadIdx.x] = w[threadIdx.x];
+        __syncthreads();
+        if (!inside) return;
+        float acc = 0.f;
+        if (few) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    if (a < n1 && b < n0)
+                        acc = fmaf(dv[a][b] * (1.f - fv[a][b] * fv[a][b]),
+                                   ws[base_w + D.wZ[1] * (lo1 + a) + D.wZ[0] * (lo0 + b)], acc);
+        } else {
             for (int32_t z1 = lo1; z1 <= hi1; ++z1) {
                 int of = base_f + D.fZ[1] * z1 + D.fZ[0] * lo0;
                 int ow = base_w + D.wZ[1] * z1 + D.wZ[0] * lo0;
                 for (int32_t z0 = lo0; z0 <= hi0; ++z0) {
-                    const float fv = f[of];
-                    acc = fmaf(df[of] * (1.f - fv * fv), ws[ow], acc);
+                    const float fval = f[of];
+                    acc = fmaf(df[of] * (1.f - fval * fval), ws[ow], acc);
                     of += D.fZ[0];
                     ow += D.wZ[0];
                 }
@@ -111,6 +139,7 @@ __global__ __launch_bounds__(256) void k_strided_backward(const StridedGeom g, c
     float acc[TAPS];
 #pragma unroll
     for (int q = 0; q < TAPS; ++q) acc[q] = 0.f;
+#pragma unroll
     for (int e = 0; e < kStridedDwElems / 256; ++e) {
         const int lin = blk * kStridedDwElems + e * 256 + threadIdx.x;
         if (lin < nf) {
