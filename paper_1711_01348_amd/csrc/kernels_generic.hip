@@ -253,7 +253,7 @@ __global__ __launch_bounds__(256) void k_generic_gather_lanes(const GatherPlan P
     else store_element(dx, lin, live, acc, accumulate);
 }
 
-// Several gradients of a small expression in one launch: every kernel launch starts with cold instruction caches,
+// Several gradients of small tensors in one launch: every kernel launch starts with cold instruction caches,
 // and a wavefront that walks this code once spends most of its time fetching it (8 to 25 us per launch for a few
 // dozen terms); in one launch the gradients pay that together instead of one after the other.  Workgroups of one
 // wavefront; workgroup b works on gradient g with first[g] <= b < first[g + 1].
@@ -267,14 +267,29 @@ struct MultiGather {
 };
 template <int BODY, typename T>
 __global__ __launch_bounds__(64) void k_generic_gather_multi(const MultiGather M, const ArgPtrs A,
-                                                             const T *__restrict__ f, const T *__restrict__ df) {
+                                                             const T *__restrict__ f, const T *__restrict__ df,
+                                                             int classify) {
     int g = 0;
     while (g + 1 < M.count && (int)blockIdx.x >= M.first[g + 1]) ++g;   // the same for the whole workgroup
-    const int idx = ((int)blockIdx.x - M.first[g]) * 64 + (int)threadIdx.x;
-    if (idx >= M.n[g]) return;
-    double acc;
-    int lin;
-    const bool live = gather_element<BODY, T>(M.plan[g], M.operand[g], A, f, df, idx, &lin, 0, 1, &acc);
+    const GatherPlan &P = M.plan[g];
+    const int p = M.operand[g];
+    const int idx = ((int)blockIdx.x - M.first[g]) * 64 + (int)threadIdx.x, lane = threadIdx.x;
+    const bool inside = idx < M.n[g];
+    // as in k_generic_gather: an element with many terms is summed by the whole wavefront
+    const bool heavy = classify && inside && element_estimate(P, idx) >= kHeavyTerms;
+    double acc = 0.0;
+    bool live = false;
+    int lin = -1;
+    if (inside && !heavy) live = gather_element<BODY, T>(P, p, A, f, df, idx, &lin, 0, 1, &acc);
+    for (unsigned long long todo = __ballot(heavy); todo; todo &= todo - 1) {   // the same in every lane
+        const int src = __ffsll((long long)todo) - 1;
+        double part_sum;
+        int lin_src;
+        gather_element<BODY, T>(P, p, A, f, df, __shfl(idx, src, 64), &lin_src, lane, 64, &part_sum);
+        const double total = wave_sum_all(part_sum);
+        if (lane == src) { acc = total; live = true; lin = lin_src; }
+    }
+    if (!inside) return;
     store_element(static_cast<T *>(M.dx[g]), lin, live, acc, 0);
 }
 
@@ -301,8 +316,8 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
                        A, static_cast<T *>(fout), nf);
         return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
     }
-    // a small expression without aliases: all gradients in one launch
-    if (!pl.has_alias && pl.terms_total < (double)kHeavyTerms) {
+    // an expression without aliases whose gradients are all small tensors with short sums: one launch for all
+    if (!pl.has_alias) {
         MultiGather M{};
         bool fits = true;
         long long blocks = 0;
@@ -324,7 +339,8 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
         if (fits && M.count >= 2) {
             M.first[M.count] = (int32_t)blocks;
             TAD_LAUNCH("k_generic_gather_multi", (k_generic_gather_multi<BODY, T>), dim3((unsigned)blocks), dim3(64), 0, s,
-                       M, A, static_cast<const T *>(f), static_cast<const T *>(df));
+                       M, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                       pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
             return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
         }
     }
