@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
+import rounding_bound
 from paper_1711_01348_amd import check
 from paper_1711_01348_amd import workloads as wl
 
@@ -41,6 +42,21 @@ def assert_parity(w, f, grads, f_ref, g_ref, tag=""):
         assert check.within(g, r, dt), (w.name, tag, "d" + a.name, e)
         # structural zeros (cokernel mask, unreferenced elements) must be exact zeros
         assert np.all(g[r == 0] == 0), (w.name, tag, "d" + a.name, "mask")
+
+
+def assert_within_rounding_bounds(w, f, grads, f_ref, g_ref, bound_f, bound_g, tag=""):
+    """Long sums: the element-wise difference stays below the bound that follows from the number of terms and the
+    sum of their magnitudes (rounding_bound.py); returns the largest floored relative error seen, for the record."""
+    worst = 0.0
+    for what, got, ref, bound in [("f", f, f_ref, bound_f)] + [("d" + a.name, g, r, b) for a, g, r, b in
+                                                                zip(w.expr.args, grads, g_ref, bound_g) if g is not None]:
+        diff = np.abs(np.asarray(got, dtype=np.float64) - ref)
+        over = diff > bound
+        assert not over.any(), (w.name, tag, what, "difference", float(diff[over].max()), "bound", float(bound[over].min()),
+                                check.errors(got, ref))
+        assert np.all(np.asarray(got)[ref == 0] == 0), (w.name, tag, what, "mask")
+        worst = max(worst, check.errors(got, ref)["floored"])
+    return worst
 
 
 def oracle_all(w, nthreads=8):
@@ -161,8 +177,8 @@ def test_random_expressions(seed):
 def test_random_expressions_with_a_long_index(seed):
     """The same random expressions with one index of 1100..2600 values: gradients (or function elements) that sum
     thousands of terms, so that the plan-driven kernels lay their threads out in every way they know (one workgroup
-    per element, several per element, one thread per element with shared sums, unmasked elements only).  fp32:
-    in fp64 the order in which thousands of terms are added shows at the 1e-12 level."""
+    per element, several per element, one thread per element with shared sums, unmasked elements only).  fp32,
+    values small enough that exp of the sum stays inside fp32."""
     e = wl.random_expr(seed, "f32", long_index=True)
     terms = int(np.prod([hi - lo + 1 for lo, hi in e.sums])) if e.sums else 1
     span = min(0.03, 2.0 / terms) if e.body == "exp" else 0.03     # exp of the sum must stay inside fp32
@@ -174,6 +190,25 @@ def test_random_expressions_with_a_long_index(seed):
     plan, f, grads = run_gpu(wp)
     assert plan.forward_family in ("program", "contraction")
     assert_parity(wp, f, grads, f_ref, g_ref, "random %d with a long index, as program" % seed)
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_expressions_with_a_long_index_fp64(seed):
+    """The long-index expressions in fp64 on values of order one (the range of the short random expressions, not
+    shrunk).  The kernels add thousands of terms in another order than the oracle, which shows beyond 1e-12 on
+    some elements; what must hold is the bound that grows with the number of terms, 2 (n + 1) 2^-53 sum |term|
+    carried through the outer function and the gradient sums, element by element."""
+    e = wl.random_expr(seed, "f64", long_index=True)
+    w = wl.random_inputs(e, 300 + seed, -0.6, 0.6)
+    f_ref, g_ref = oracle_all(w, 8)
+    bound_f, bound_g = rounding_bound.bounds(e, w.arg_list(), w.df)
+    _, f, grads = run_gpu(w)
+    worst = assert_within_rounding_bounds(w, f, grads, f_ref, g_ref, bound_f, bound_g, "long index %d, fp64" % seed)
+    wp = wl.Workload(w.name, wl.as_program(e), w.inputs, w.df)
+    plan, f, grads = run_gpu(wp)
+    assert plan.forward_family in ("program", "contraction")
+    worst = max(worst, assert_within_rounding_bounds(wp, f, grads, f_ref, g_ref, bound_f, bound_g, "as program"))
+    print("long index %d fp64: largest floored relative error %.2e" % (seed, worst))
 
 
 LONG_SUMS = [
@@ -192,15 +227,24 @@ LONG_SUMS = [
 
 @pytest.mark.parametrize("name,make", LONG_SUMS, ids=[c[0] for c in LONG_SUMS])
 def test_long_sums_per_function_index(name, make):
-    """At least 1024 terms per function index: the forward kernels give one block to every function index."""
+    """At least 1024 terms per function index: the forward kernels give one block to every function index.
+    Inputs are uniform in [-1, 1] throughout (only the fp32 exp of 1600 terms draws from [-0.5, 0.5] to stay inside
+    the format); the results are held to the element-wise bound that follows from the number of terms and the sum
+    of their magnitudes, and the fp32 ones to the normwise limit as well."""
     e = make()
-    # small values where the sum feeds exp or tanh: thousands of terms of order one would make the result depend
-    # on the order of the additions beyond the tolerance
-    small = "exp" in name or name.startswith("two") or name.startswith("dense_layer_few")
-    w = wl.random_inputs(e, 41, -0.05, 0.05) if small else wl.random_inputs(e, 41)
+    w = wl.random_inputs(e, 41, -0.5, 0.5) if name == "two_sums_f32" else wl.random_inputs(e, 41)
     f_ref, g_ref = oracle_all(w, 4)
+    if name.startswith("dense_layer"):
+        bound_f, bound_g = rounding_bound.dense_layer_bounds(e.dtype, *w.arg_list(), w.df)
+    else:
+        plain = e if e.body != "program" else wl.matmul_expr(*e.f_shape, e.sums[0][1] + 1, e.dtype, True, False)
+        bound_f, bound_g = rounding_bound.bounds(plain, w.arg_list(), w.df)
     plan, f, grads = run_gpu(w)
-    assert_parity(w, f, grads, f_ref, g_ref, name)
+    worst = assert_within_rounding_bounds(w, f, grads, f_ref, g_ref, bound_f, bound_g, name)
+    if e.dtype == "f32":
+        for got, ref in [(f, f_ref)] + list(zip(grads, g_ref)):
+            assert check.errors(got, ref)["normwise"] <= check.LIMITS["f32"][1], (name, check.errors(got, ref))
+    print("%s: largest floored relative error %.2e" % (name, worst))
 
 
 FEW_ELEMENTS = [
@@ -276,42 +320,24 @@ def test_full_size_config3():
     _full(wl.config3())
 
 
-def test_full_size_config4_sampled_blocks():
-    """4096 x 4096 x 256 in the benchmark's launch configuration.  The oracle evaluates a contiguous block of
-    rows i (which fixes f, da, dc on that block exactly) and a contiguous block of columns j (which fixes db
-    on that block); dd is checked on the elements whose whole window lies inside the row block."""
+def test_full_size_config4():
+    """4096 x 4096 x 256 in the benchmark's launch configuration (matrix-core family, the collapsed indices split
+    over 8 chunks of workgroups): every element of f, da, db, dc and dd against the oracle, which visits all
+    4.3e9 extended indices.  dd is looked at once more on its own: the elements whose window
+    max(0, m - (I-1)) .. min(K-1, m) of Sec. 6 is complete (K-1 <= m <= I-1) and the clipped ones at both ends."""
     w = wl.config4()
     I, J = w.expr.f_shape
     K = w.expr.sums[0][1] + 1
-    a, b, c, d = w.arg_list()
-    _, f, (da, db, dc, dd) = run_gpu(w)
-    dt = "f32"
-    # rows i0 .. i0+n-1
-    i0, n = 1000, 24
-    sub = wl.worked_expr(n, J, K, dt)
-    sa, sc, sd, sdf = a[i0:i0 + n], np.ascontiguousarray(c[i0:i0 + n, i0:i0 + n]), d[i0:i0 + n + K - 1], w.df[i0:i0 + n]
-    f_ref = oracle.forward(sub, [sa, b, sc, sd])
-    g_ref = oracle.backward(sub, [sa, b, sc, sd], sdf, wanted=[True, False, True, True], nthreads=16)
-    assert check.within(f[i0:i0 + n], f_ref, dt), check.errors(f[i0:i0 + n], f_ref)
-    assert check.within(da[i0:i0 + n], g_ref[0], dt), check.errors(da[i0:i0 + n], g_ref[0])
-    assert check.within(np.diag(dc)[i0:i0 + n], np.diag(g_ref[2]), dt)
-    # columns j0 .. j0+m-1
-    j0, m = 3000, 8
-    sub = wl.worked_expr(I, m, K, dt)
-    sb, sdf = b[j0:j0 + m], np.ascontiguousarray(w.df[:, j0:j0 + m])
-    g_ref = oracle.backward(sub, [a, sb, c, d], sdf, wanted=[False, True, False, False], nthreads=16)
-    assert check.within(db[j0:j0 + m], g_ref[1], dt), check.errors(db[j0:j0 + m], g_ref[1])
-    # structure of dc and the ends of dd
+    f_ref, g_ref = oracle_all(w, 16)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "worked_mfma"
+    assert_parity(w, f, grads, f_ref, g_ref, "full")
+    dd, dd_ref = grads[3], g_ref[3]
+    assert dd.shape == (I + K - 1,)
+    for lo, hi, what in ((0, K - 1, "clipped below"), (K - 1, I, "complete window"), (I, I + K - 1, "clipped above")):
+        assert check.within(dd[lo:hi], dd_ref[lo:hi], "f32"), (what, check.errors(dd[lo:hi], dd_ref[lo:hi]))
+    dc = grads[2]
     assert np.count_nonzero(dc) <= I and np.count_nonzero(dc - np.diag(np.diag(dc))) == 0
-    # dd over a window-complete range needs all rows: use the identity dd_m = -3 d_m^2 sum_{i in window} r_i with
-    # r_i = -da_i. a_i ... not available in closed form; instead compare a short slice against the oracle on the
-    # first rows only, where the window is cut by the border i >= 0
-    n2 = 16
-    sub = wl.worked_expr(n2, J, K, dt)
-    g_ref = oracle.backward(sub, [a[:n2], b, np.ascontiguousarray(c[:n2, :n2]), d[:n2 + K - 1]], w.df[:n2],
-                            wanted=[False, False, False, True], nthreads=16)
-    # elements m < n2 receive contributions from rows i <= m only, all inside the block
-    assert check.within(dd[:n2], g_ref[3][:n2], dt), check.errors(dd[:n2], g_ref[3][:n2])
 
 
 def test_determinism_full_config3():
@@ -335,7 +361,7 @@ def test_device_entry_points_reject_misuse():
     ptrs = (ctypes.c_void_p * 4)(*[t.data_ptr() for t in args])
     assert plan.workspace_bytes > 0
     # workspace missing / too small
-    assert B.lib.tad_eval_forward(plan._h, ptrs, f.data_ptr(), None, 0, None) in (0, -7)
+    assert B.lib.tad_eval_forward(plan._h, ptrs, f.data_ptr(), None, 0, None) == -7
     small = torch.empty(16, dtype=torch.uint8, device="cuda")
     dptr = (ctypes.c_void_p * 4)(*[t.data_ptr() for t in args])
     assert B.lib.tad_eval_backward(plan._h, ptrs, f.data_ptr(), f.data_ptr(), dptr, small.data_ptr(), 16, None) == -7

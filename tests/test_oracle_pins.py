@@ -379,6 +379,28 @@ def test_program_body_closed_form():
     assert np.allclose(oracle.backward(e, [x], df)[0], df * 2 * x / (1 + x * x), rtol=1e-13)
 
 
+def test_program_subtraction_closed_forms():
+    """The subtraction rule of the interpreter, as the second operand of the inner function and in the outer one:
+    f_i = sum_k (x_ik - y_k)^2 has d/dx = 2 (x - y) df_i and d/dy = -2 sum_i (x - y) df_i (the sign and the order of
+    the operands both show); f_i = 3 - s_i with s_i = sum_k (x_ik - y_k) has d/dx = -df_i, d/dy = +sum_i df_i."""
+    args = [wl.ArgSpec("x", (5, 4), [[1, 0], [0, 1]]), wl.ArgSpec("y", (4,), [[0, 1]])]
+    rng = np.random.default_rng(31)
+    x, y, df = rng.uniform(-1, 1, (5, 4)), rng.uniform(-1, 1, 4), rng.uniform(-1, 1, 5)
+    sq = wl.ExprSpec("program", (5,), [(0, 3)], args, "f64",
+                     [("arg", 0), ("arg", 1), ("sub",), ("powi", 2)], [("sum",)])
+    diff = x - y[None, :]
+    assert np.allclose(oracle.forward(sq, [x, y]), (diff ** 2).sum(axis=1), rtol=1e-14)
+    dx, dy = oracle.backward(sq, [x, y], df)
+    assert np.allclose(dx, 2 * diff * df[:, None], rtol=1e-13, atol=1e-15)
+    assert np.allclose(dy, -2 * (diff * df[:, None]).sum(axis=0), rtol=1e-13, atol=1e-15)
+    lin = wl.ExprSpec("program", (5,), [(0, 3)], args, "f64",
+                      [("arg", 0), ("arg", 1), ("sub",)], [("const", 3.0), ("sum",), ("sub",)])
+    assert np.allclose(oracle.forward(lin, [x, y]), 3.0 - diff.sum(axis=1), rtol=1e-14)
+    dx, dy = oracle.backward(lin, [x, y], df)
+    assert np.allclose(dx, -np.broadcast_to(df[:, None], (5, 4)), rtol=1e-14)
+    assert np.allclose(dy, np.full(4, df.sum()), rtol=1e-13)
+
+
 def test_program_temporaries_equal_the_written_out_program():
     """(x + y)^2 + sin(x + y) with x + y kept in a temporary, and the outer function u * exp(u) likewise, against
     the same programs with the shared part written twice; plus the closed form of the forward value."""
@@ -487,3 +509,46 @@ def test_moving_window_finite_differences():
     args = [np.asarray(a, dtype=np.float64) for a in w.arg_list()]
     for p, g in enumerate(oracle.backward(e, args, w.df)):
         assert np.allclose(g, _fd_grad(e, args, w.df, p), rtol=2e-7, atol=2e-8), p
+
+
+# ---------------------------------------------------------------- the rounding bound used for long sums
+
+def test_rounding_bound_covers_another_summation_order_and_stays_small():
+    """The element-wise bound for long sums (rounding_bound.py) against a second evaluation that adds in another
+    order (numpy's pairwise / blocked sums): every difference lies below the bound, the bound itself stays a
+    modest multiple of n * 2^-53 * sum|term|, and it grows with the number of terms."""
+    import rounding_bound
+    worst = []
+    for K in (300, 2400):
+        e = wl.matmul_expr(7, 5, K, "f64")
+        w = wl.random_inputs(e, 61)
+        x, y = w.arg_list()
+        bound_f, (bound_x, bound_y) = rounding_bound.bounds(e, [x, y], w.df)
+        f = oracle.forward(e, [x, y])
+        dx, dy = oracle.backward(e, [x, y], w.df)
+        assert np.all(np.abs(f - x @ y) <= bound_f)
+        assert np.all(np.abs(dx - w.df @ y.T) <= bound_x) and np.all(np.abs(dy - x.T @ w.df) <= bound_y)
+        mags = np.abs(x) @ np.abs(y)
+        assert np.all(bound_f <= 2.1 * (K + 2) * 2.0 ** -53 * mags)
+        worst.append(float(bound_f.max()))
+    assert worst[1] > 10 * worst[0]
+    # exp of a cumulative sum: the bound follows the magnification by the outer function
+    e = wl.cumulative_sum_expr(900, "f64")
+    w = wl.random_inputs(e, 62)
+    (x,) = w.arg_list()
+    bound_f, (bound_x,) = rounding_bound.bounds(e, [x], w.df)
+    f = oracle.forward(e, [x])
+    ref = np.exp(np.cumsum(x))
+    assert np.all(np.abs(f - ref) <= bound_f) and np.all(bound_f <= 1e-10 * ref)
+    dx = oracle.backward(e, [x], w.df)[0]
+    assert np.all(np.abs(dx - np.cumsum((w.df * ref)[::-1])[::-1]) <= bound_x)
+    # dense layer, matrix form of the same bound
+    e = wl.dense_layer_expr(6, 5, 700, "f64")
+    w = wl.random_inputs(e, 63)
+    x, wt, b = w.arg_list()
+    bound_f, bound_g = rounding_bound.dense_layer_bounds("f64", x, wt, b, w.df)
+    t = np.tanh(b + x @ wt)
+    g = w.df * (1 - t * t)
+    assert np.all(np.abs(oracle.forward(e, [x, wt, b]) - t) <= bound_f)
+    for got, ref, bd in zip(oracle.backward(e, [x, wt, b], w.df), (g @ wt.T, x.T @ g, g.sum(axis=0)), bound_g):
+        assert np.all(np.abs(got - ref) <= bd)
