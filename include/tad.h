@@ -271,6 +271,25 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
                       void *stream);
 
 /*
+ * tad_eval_backward for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as tad_eval_backward
+ * (bit-identical: the same kernels run), but the per-tile partial sums live in an array of
+ * TAD_STATIC_SCRATCH_BYTES that is part of the library's device code: every GPU the library runs on holds one copy
+ * until the process ends.  The call allocates nothing and frees nothing.
+ *   - a plan with tad_plan_workspace_bytes above TAD_STATIC_SCRATCH_BYTES is refused with TAD_ENOMEM before
+ *     anything is launched (the matrix-core family at 4096 x 4096 x 256 needs 64 MiB; the 8192 x 8192 x 5 worked
+ *     expression 9.5 MiB);
+ *   - the first call on a device looks up the array's address (no allocation); make it outside a stream capture;
+ *   - all calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *     threads) race on it and give wrong gradients; calls on one stream are ordered and safe.  The array keeps
+ *     the last call's contents; the kernels overwrite every entry before reading it.
+ * Errors: as tad_eval_backward; TAD_EDEVICE if the array's address cannot be obtained.
+ */
+#define TAD_STATIC_SCRATCH_BYTES (16u << 20)
+int tad_eval_backward_static(const tad_plan *plan, const void *const *args_dev, const void *f_dev,
+                             const void *df_dev, void *const *dx_dev, void *stream);
+
+/*
  * The gradient of one occurrence of a tensor, written as element-wise defined tensors again (Sec. 5.3: a
  * derived expression has the form of the input expressions, with summation ranges that depend on the other
  * indices, so it can be evaluated, and differentiated once more, by the same machinery).  With

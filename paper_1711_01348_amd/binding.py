@@ -31,7 +31,8 @@ ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
            "tad_plan_bound_row", "tad_plan_enumerate", "tad_plan_count_all", "tad_eval_forward",
            "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval", "tad_plan_program_registers",
-           "tad_plan_derived_expr", "tad_plan_seed_expr"]
+           "tad_plan_derived_expr", "tad_plan_seed_expr", "tad_eval_backward_static"]
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class TadOp(ctypes.Structure):
@@ -96,6 +97,7 @@ def _load():
     lib.tad_eval_forward.argtypes = [vp, ctypes.POINTER(vp), vp, vp, ctypes.c_size_t, vp]
     lib.tad_eval_backward.argtypes = [vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp,
                                       ctypes.c_size_t, vp]
+    lib.tad_eval_backward_static.argtypes = [vp, ctypes.POINTER(vp), vp, vp, ctypes.POINTER(vp), vp]
     lib.tad_plan_forward_family.argtypes = [vp]
     lib.tad_plan_program_eval.argtypes = [vp, ctypes.c_int, vp, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
     lib.tad_plan_program_registers.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
@@ -355,7 +357,8 @@ class Plan:
                                     ctypes.c_void_p(stream)), "tad_eval_forward")
         return out
 
-    def backward(self, args, f, df, wanted: Optional[Sequence[bool]] = None, out=None, ws=None):
+    def backward(self, args, f, df, wanted: Optional[Sequence[bool]] = None, out=None, ws=None, static=False):
+        """static=True: tad_eval_backward_static (the library's own fixed scratch array instead of a workspace)."""
         import torch
         ptrs = self._arg_ptrs(args)
         self._check_tensor(f, self.expr.f_shape, "f")
@@ -368,8 +371,12 @@ class Plan:
             if t is not None:
                 self._check_tensor(t, a.shape, "d" + a.name)
         dptr = (ctypes.c_void_p * len(args))(*[None if t is None else t.data_ptr() for t in out])
-        ws = self.workspace(args[0].device) if ws is None else ws
         stream = torch.cuda.current_stream().cuda_stream
+        if static:
+            _check(lib.tad_eval_backward_static(self._h, ptrs, f.data_ptr(), df.data_ptr(), dptr,
+                                                ctypes.c_void_p(stream)), "tad_eval_backward_static")
+            return out
+        ws = self.workspace(args[0].device) if ws is None else ws
         _check(lib.tad_eval_backward(self._h, ptrs, f.data_ptr(), df.data_ptr(), dptr, ws.data_ptr(),
                                      ws.numel(), ctypes.c_void_p(stream)), "tad_eval_backward")
         return out

@@ -1,9 +1,35 @@
 // Device entry points of the C ABI: dispatch on the kernel family chosen at plan time.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "launch.h"
 
 using namespace tad;
+
+// Scratch memory of tad_eval_backward_static: one array per GPU, part of the loaded code object, held until the
+// process ends.  In host code the array's name only stands for the symbol; its device address is looked up once per
+// device with hipGetSymbolAddress and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[TAD_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TAD_EDEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TAD_EDEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TAD_OK;
+}
+}  // namespace
 
 extern "C" {
 
@@ -56,6 +82,18 @@ int tad_eval_backward(const tad_plan *plan, const void *const *args_dev, const v
     case TAD_FAMILY_PROGRAM: return program_backward(*plan, args_dev, df_dev, dx_dev, ws_dev, s);
     default: return TAD_EUNSUPPORTED;
     }
+}
+
+int tad_eval_backward_static(const tad_plan *plan, const void *const *args_dev, const void *f_dev,
+                             const void *df_dev, void *const *dx_dev, void *stream) {
+    if (!plan) return TAD_EINVAL;
+    if (plan->ws_bytes > (size_t)TAD_STATIC_SCRATCH_BYTES) return TAD_ENOMEM;
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc != TAD_OK) return rc;
+    // the kernels write every workspace entry before they read it, so the contents the previous call left behind
+    // need no clearing
+    return tad_eval_backward(plan, args_dev, f_dev, df_dev, dx_dev, ws, TAD_STATIC_SCRATCH_BYTES, stream);
 }
 
 }  // extern "C"
