@@ -22,9 +22,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VALU_TFLOPS = 157.3       # published vector fp32 peak (packed); 256 CUs x 2.4 GHz x 256 flop/clk
 FP32_MFMA_TFLOPS = 157.3
-PROFILE_EVERY = 25              # every 25th launch of the dominant kernel carries timing events (a timed launch delays its
-                                # successor: every 7th cost the 25 us workload 3 us per step, every 25th nothing measurable)
+PROFILE_EVERY = 25              # at most every 25th launch of the dominant kernel carries timing events (a timed launch delays
+                                # its successor: every 7th cost the 25 us workload 3 us per step, every 25th nothing measurable);
+                                # short runs time every (steps // 4)-th launch instead, so that several launches are averaged
 ROTATE_BYTES = 640 << 20      # cycle over buffer sets beyond this footprint (> 2x the 256 MB last-level cache)
+WARM_PASSES = 3                 # every buffer set is run this often before anything is timed, whatever --warmup says
+MIN_WINDOW_MS = 20.0            # the workloads beside the headline are timed for at least this long (own step count)
 
 
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a plain
@@ -107,10 +110,11 @@ def accounting(name, w):
     return elems, elems * es, dom
 
 
-def run_gpu(name, steps, warmup, rotate_bytes=0):
+def run_gpu(name, steps, warmup, rotate_bytes=0, min_window_ms=0.0):
     """Time `steps` forward+backward passes.  With rotate_bytes > 0 the step cycles over enough independent
     buffer sets to exceed that footprint, so that a workload smaller than the last-level cache still streams
-    from HBM."""
+    from HBM.  With min_window_ms > 0 the step count is raised until the timed region lasts that long (a 1.5 ms
+    window of 20 short steps measures the start of the run, not the steady state)."""
     import ctypes
     import torch
     from paper_1711_01348_amd import binding as B
@@ -139,12 +143,22 @@ def run_gpu(name, steps, warmup, rotate_bytes=0):
         plan.forward(args, out=f, ws=ws)
         plan.backward(args, f, df, out=grads, ws=ws)
 
-    for i in range(warmup):
+    warm = max(warmup, WARM_PASSES * len(sets))      # first touches of a buffer set are never part of the timed region
+    for i in range(warm):
         step(i)
     torch.cuda.synchronize()
+    if min_window_ms:
+        pilot = max(steps, len(sets))
+        t0 = time.perf_counter()
+        for i in range(pilot):
+            step(i)
+        torch.cuda.synchronize()
+        per_step_ms = (time.perf_counter() - t0) * 1e3 / pilot
+        steps = max(steps, int(min_window_ms / per_step_ms) + 1)
+    every = max(1, min(PROFILE_EVERY, steps // 4))
     families = {"forward": plan.forward_family, "backward": [plan.query(p)["family"] for p in range(len(w.expr.args))]}
     if dom["per_launch"]:   # a workload without a roofline figure (cfg1: all latency) runs without timed launches
-        B._check(B.lib.tad_profile_begin(dom["kernel"].encode(), PROFILE_EVERY), "tad_profile_begin")
+        B._check(B.lib.tad_profile_begin(dom["kernel"].encode(), every), "tad_profile_begin")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
@@ -180,7 +194,8 @@ def run_gpu(name, steps, warmup, rotate_bytes=0):
     return dict(name=name, workload=w.name, ms_per_step=ms_step, elements=elems, bytes=nbytes,
                 elements_per_s=elems / (ms_step * 1e-3), algorithmic_gbs=nbytes / (ms_step * 1e-3) / 1e9,
                 ms_forward=ev[0].elapsed_time(ev[1]), ms_backward=ev[1].elapsed_time(ev[2]),
-                dominant=dom, dominant_ms=dom_ms, dominant_launches=n.value, families=families,
+                dominant=dom, dominant_ms=dom_ms, dominant_launches=n.value, timed_every=every, steps=steps,
+                warm_steps=warm, families=families,
                 dtype=w.expr.dtype, buffer_sets=len(sets), footprint_bytes_per_set=foot, extra=extra)
 
 
@@ -211,22 +226,48 @@ def roofline(r):
     else:
         achieved, peak, unit = dom["per_launch"] / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
     return {"bound": dom["bound"], "kernel": dom["kernel"], "achieved": achieved, "peak": peak, "unit": unit,
-            "frac": achieved / peak, "traffic": measured_traffic(r["name"]), "avg_kernel_ms": ms, "launches": r["dominant_launches"], "timed_every": PROFILE_EVERY,
+            "frac": achieved / peak, "traffic": measured_traffic(r["name"]), "avg_kernel_ms": ms, "launches": r["dominant_launches"], "timed_every": r["timed_every"],
             "algorithmic_per_launch": dom["per_launch"]}
 
 
 def run_cpu_oracle(name):
-    """The fp64 oracle as it stands, on the host cores, on the same workload (whole cfg3 fits in ~10-30 s)."""
+    """The fp64 oracle as it stands, on the host cores, on the same workload: the whole workload with the function
+    indices split over the cores (cfg3 takes a few seconds), and one thread on a contiguous block of rows of it."""
+    import ctypes
     import oracle
     w = workload(name)
-    nthreads = min(oracle.max_threads(), 16)
+    nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    nthreads = min(oracle.max_threads(), 16, nproc)      # the share of the host that belongs to one GPU
     t0 = time.perf_counter()
     oracle.forward(w.expr, w.arg_list())
     oracle.backward(w.expr, w.arg_list(), w.df, nthreads=nthreads)
     t = time.perf_counter() - t0
     elems, _, _ = accounting(name, w)
-    return dict(value=elems / t, unit="elements/s", cores=nthreads, kind="oracle",
-                sample=f"whole workload {w.name}: forward + brute-force scatter backward, fp64, {t:.1f} s")
+    out = dict(value=elems / t, unit="elements/s", cores=nthreads, nproc=nproc, kind="oracle",
+               sample=f"whole workload {w.name}: forward + brute-force scatter backward, fp64, {t:.1f} s on {nthreads} threads")
+    if name in ("cfg3", "cfg4") and w.expr.f_shape[0] >= 1024:
+        # one thread: rows 0 .. n-1 of the same tensors (an n x J x K worked expression: a, c, d and df cut to those rows)
+        from paper_1711_01348_amd import workloads as wl
+        I, J = w.expr.f_shape
+        K = w.expr.sums[0][1] + 1
+        n = I // 16 if name == "cfg3" else I // 128
+        a_, b_, c_, d_ = w.arg_list()
+        sub = wl.worked_expr(n, J, K, w.expr.dtype)
+        xs = [a_[:n], b_, c_[:n, :n].copy(), d_[:n + K - 1]]
+        try:
+            omp = ctypes.CDLL("libgomp.so.1")
+        except OSError:
+            return out
+        before = oracle.max_threads()
+        omp.omp_set_num_threads(1)               # the forward pass takes its thread count from the OpenMP runtime
+        t0 = time.perf_counter()
+        oracle.forward(sub, xs)
+        oracle.backward(sub, xs, w.df[:n], nthreads=1)
+        t1 = time.perf_counter() - t0
+        omp.omp_set_num_threads(before)
+        out["single_thread_value"] = elems * (n / I) / t1
+        out["single_thread_sample"] = f"rows 0..{n - 1} of {I} of the same workload, one thread, {t1:.1f} s"
+    return out
 
 
 def main():
@@ -277,8 +318,8 @@ def main():
             if name == a.workload:
                 continue
             try:
-                q = run_gpu(name, a.steps, a.warmup, rotate_bytes=ROTATE_BYTES)
-                e = {k: q[k] for k in ("workload", "ms_per_step", "ms_forward", "ms_backward", "elements_per_s",
+                q = run_gpu(name, a.steps, a.warmup, rotate_bytes=ROTATE_BYTES, min_window_ms=MIN_WINDOW_MS)
+                e = {k: q[k] for k in ("workload", "steps", "warm_steps", "ms_per_step", "ms_forward", "ms_backward", "elements_per_s",
                                        "algorithmic_gbs", "families", "buffer_sets")}
                 e["frac_of_hbm_peak"] = q["algorithmic_gbs"] / HBM_PEAK_GBS
                 if q["dominant"]["bound"] == "mfma":

@@ -51,6 +51,7 @@ def assert_within_rounding_bounds(w, f, grads, f_ref, g_ref, bound_f, bound_g, t
     for what, got, ref, bound in [("f", f, f_ref, bound_f)] + [("d" + a.name, g, r, b) for a, g, r, b in
                                                                 zip(w.expr.args, grads, g_ref, bound_g) if g is not None]:
         diff = np.abs(np.asarray(got, dtype=np.float64) - ref)
+        assert np.all(np.isfinite(diff)), (w.name, tag, what, "not finite")
         over = diff > bound
         assert not over.any(), (w.name, tag, what, "difference", float(diff[over].max()), "bound", float(bound[over].min()),
                                 check.errors(got, ref))
@@ -199,8 +200,11 @@ def test_random_expressions_with_a_long_index_fp64(seed):
     some elements; what must hold is the bound that grows with the number of terms, 2 (n + 1) 2^-53 sum |term|
     carried through the outer function and the gradient sums, element by element."""
     e = wl.random_expr(seed, "f64", long_index=True)
-    w = wl.random_inputs(e, 300 + seed, -0.6, 0.6)
+    terms = int(np.prod([hi - lo + 1 for lo, hi in e.sums])) if e.sums else 1
+    span = min(0.6, 600.0 / terms) if e.body == "exp" else 0.6     # exp of the sum must stay finite in fp64
+    w = wl.random_inputs(e, 300 + seed, -span, span)
     f_ref, g_ref = oracle_all(w, 8)
+    assert np.all(np.isfinite(f_ref)) and all(np.all(np.isfinite(g)) for g in g_ref if g is not None)
     bound_f, bound_g = rounding_bound.bounds(e, w.arg_list(), w.df)
     _, f, grads = run_gpu(w)
     worst = assert_within_rounding_bounds(w, f, grads, f_ref, g_ref, bound_f, bound_g, "long index %d, fp64" % seed)
