@@ -177,7 +177,7 @@ static bool match_patterns(tad_plan &pl) {
             return false;
         pl.fast.dd_iy = (int)px.VR(0, 0); pl.fast.dd_iz = (int)px.K(0, 0);
         pl.fast.jy = (int)px.VR(1, 0); pl.fast.jz = (int)px.K(1, 0);
-        pl.ws_bytes = antidiag_workspace_bytes(e.f_shape[0], x.shape[0]);
+        pl.ws_bytes = antidiag_workspace_bytes(e.f_shape[0], e.f_shape[1]);
         fam = TAD_FAMILY_ANTIDIAGONAL;
     } else {
         return false;

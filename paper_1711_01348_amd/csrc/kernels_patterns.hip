@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void k_rowreduce_backward(const FlatFeas feas,
     for (; j + 3 * 1024 < J; j += 4 * 1024) {
         float4v v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4v *>(row + j + u * 1024);
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const float4v *>(row + j + u * 1024));
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc[u] += v[u];
     }
@@ -141,8 +141,7 @@ __global__ __launch_bounds__(256) void k_diagonal_backward(const FlatFeas feas, 
 // ------------------------------------------------------------------------------------------------
 // antidiagonal
 // ------------------------------------------------------------------------------------------------
-constexpr int AD_FTI = 32;    // rows per forward block
-constexpr int AD_BTI = AD_BTI_ROWS;    // rows per backward tile
+constexpr int AD_FTI = 2;     // rows per forward block (small tiles for a pure write stream: 11.2 us against 11.8 with 32 rows)
 
 // block: 1024 columns x AD_FTI rows; the lane's window of phi(x) slides by one element per row
 template <int BODY>
@@ -165,76 +164,122 @@ __global__ __launch_bounds__(256) void k_antidiag_forward(const float *__restric
     }
 }
 
-// partial[tile][m] = sum over the rows i of the tile that lie in window(m) of df[i][m - i].
-// Thread owns m: for a fixed row consecutive m are consecutive addresses.  z is the plan's kernel coordinate,
-// i = iy*y + iz*z (iz = +-1), j = jy*y + jz*z.
-__global__ __launch_bounds__(256) void k_antidiag_backward(const FlatFeas feas, const FlatLevel win, int iy, int iz,
-                                                           int jy, int jz, const float *__restrict__ df,
-                                                           float *__restrict__ part, int n_x, int J) {
-    const int m = blockIdx.x * 256 + threadIdx.x;
-    if (m >= n_x) return;
-    const int t = blockIdx.y;
-    const int32_t y[3] = {m, 0, 0};   // the transformed index is the gradient index (checked on the host)
-    float s = 0.f;
-    if (flat_feasible(feas, y)) {
-        int32_t lo, hi;
-        flat_bounds(win, y, lo, hi);
-        // rows of this tile: i0 <= iy*y + iz*z < i0 + AD_BTI
-        const int base = iy * y[0], i0 = t * AD_BTI;
-        int zlo, zhi;
-        if (iz > 0) { zlo = i0 - base; zhi = i0 + AD_BTI - 1 - base; }
-        else { zlo = base - (i0 + AD_BTI - 1); zhi = base - i0; }
-        lo = max(lo, zlo);
-        hi = min(hi, zhi);
-        const long long step = (long long)iz * J + jz;
-        const float *p = df + ((long long)(base + iz * lo) * J + (jy * y[0] + jz * lo));
-        // four loads in flight per lane; measured faster than 8 or 16 (also with the surplus ones switched off), than
-        // non-temporal loads, and than 64-column blocks whose four waves split the rows
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        int w = lo;
-        for (; w + 3 <= hi; w += 4) {
-            float v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = p[u * step];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc[u] += v[u];
-            p += 4 * step;
-        }
-        for (; w <= hi; ++w) { acc[0] += *p; p += step; }
-        s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-    }
-    part[(size_t)t * n_x + m] = s;
+// Backward, first pass.  A block takes one aligned tile of df (AD_TR rows x AD_TC columns, 16-byte loads along the
+// rows) and sums it along its antidiagonals: element (r, c) of the tile belongs to the sum with offset r + c.  Each of
+// its four waves takes 64 rows.  A lane loads four consecutive columns, so over four rows it meets the offsets
+// 4 lane .. 4 lane + 6: its own group of four sums and three sums of the next group.  The groups sit in a ring over
+// the lanes that moves down by one lane every four rows (wave_shl:1), so the group a lane holds stays the one its
+// next four rows start at; the carry for the next group is added while it moves in.  The group that leaves lane 0 is
+// finished.  The waves' sums are combined in LDS in a fixed order and the block writes 4 (64 + AD_TR / 4) sums per
+// tile; nothing here needs the plan: the window of Sec. 1's dx_k = sum_i df_{i,k-i} restricted to a tile is the tile's
+// whole antidiagonal, and the finishing pass takes the tiles that the plan's window meets.
+constexpr int AD_TR = AD_TILE_ROWS, AD_TC = AD_TILE_COLS, AD_WAVES = 4;
+constexpr int AD_WR = AD_TR / AD_WAVES;          // rows per wave
+constexpr int AD_G = AD_WR / 4;                  // groups of four rows per wave
+constexpr int AD_NB = 64 + AD_G;                 // groups of four sums per wave
+constexpr int AD_OUTB = 64 + AD_G * AD_WAVES;    // ... per tile
+static_assert(AD_TC == 256 && AD_G % 2 == 0 && AD_OUTB * 4 == AD_TILE_SUMS, "tile geometry");
+
+__device__ __forceinline__ float lane_above(float v) {   // value of lane + 1; 0 in lane 63
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
 }
 
-// 64 outputs per block; sixteen waves split the tiles (a short chain of independent loads per thread) and are
-// combined in fixed order
-constexpr int AD_FIN_WAVES = 16;
-template <int BODY>
-__global__ __launch_bounds__(64 * AD_FIN_WAVES) void k_antidiag_finish(const float *__restrict__ x,
-                                                                       const float *__restrict__ part, int n_tiles,
-                                                                       float *__restrict__ dx, int n_x) {
-    __shared__ double red[AD_FIN_WAVES][64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int m = blockIdx.x * 64 + lane;
-    double s = 0.0;
-    if (m < n_x) {
-        int t = wave;
-        for (; t + 3 * AD_FIN_WAVES < n_tiles; t += 4 * AD_FIN_WAVES) {
-            float v[4];
+template <bool FULL>
+__device__ __forceinline__ void antidiag_tile(const float *__restrict__ df, float4v (*outb)[AD_NB], int I, int J, int i0,
+                                              int col, int lane, int wave) {
+    const float *p = df + (size_t)i0 * J + col;
+    float4v A = {0.f, 0.f, 0.f, 0.f};
+    const bool col_ok = FULL || col < J;
+    for (int g = 0; g < AD_G; g += 2) {
+        float4v v[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = part[(size_t)(t + u * AD_FIN_WAVES) * n_x + m];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) s += (double)v[u];
+        for (int r = 0; r < 8; ++r) {
+            if (FULL || (col_ok && i0 + g * 4 + r < I))   // read once: non-temporal (12.0 us against 12.7 alone)
+                v[r] = __builtin_nontemporal_load(reinterpret_cast<const float4v *>(p + (size_t)r * J));
+            else v[r] = float4v{0.f, 0.f, 0.f, 0.f};
         }
-        for (; t < n_tiles; t += AD_FIN_WAVES) s += (double)part[(size_t)t * n_x + m];
+        p += (size_t)8 * J;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float4v v0 = v[4 * h], v1 = v[4 * h + 1], v2 = v[4 * h + 2], v3 = v[4 * h + 3];
+            A[0] += v0[0];
+            A[1] += v0[1] + v1[0];
+            A[2] += (v0[2] + v1[1]) + v2[0];
+            A[3] += (v0[3] + v1[2]) + (v2[1] + v3[0]);
+            const float c0 = (v1[3] + v2[2]) + v3[1], c1 = v2[3] + v3[2], c2 = v3[3];
+            if (lane == 0) outb[wave][g + h] = A;
+            A[0] = lane_above(A[0]) + c0;
+            A[1] = lane_above(A[1]) + c1;
+            A[2] = lane_above(A[2]) + c2;
+            A[3] = lane_above(A[3]);
+        }
     }
-    red[wave][lane] = s;
+    outb[wave][AD_G + lane] = A;
+}
+
+__global__ __launch_bounds__(64 * AD_WAVES) void k_antidiag_backward(const float *__restrict__ df, float *__restrict__ part,
+                                                                     int I, int J, int n_ct) {
+    __shared__ float4v outb[AD_WAVES][AD_NB];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = blockIdx.x, t = blockIdx.y;
+    const int i0 = t * AD_TR + wave * AD_WR, col = c * AD_TC + lane * 4;
+    if ((t + 1) * AD_TR <= I && (c + 1) * AD_TC <= J) antidiag_tile<true>(df, outb, I, J, i0, col, lane, wave);
+    else antidiag_tile<false>(df, outb, I, J, i0, col, lane, wave);
     __syncthreads();
-    if (wave == 0 && m < n_x) {
+    float4v *out = reinterpret_cast<float4v *>(part + (size_t)(t * n_ct + c) * AD_TILE_SUMS);
+    for (int b = threadIdx.x; b < AD_OUTB; b += 64 * AD_WAVES) {
+        float4v s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < AD_WAVES; ++w) {
+            const int q = b - AD_G * w;      // wave w starts AD_WR rows, i.e. AD_G groups, further down
+            if (q >= 0 && q < AD_NB) s += outb[w][q];
+        }
+        out[b] = s;
+    }
+}
+
+// Second pass: dx_m = phi'(x_m) * sum over the tiles that the plan's window of m meets.  The window (Sec. 5.1 range
+// rows, kernel coordinate z with i = iy*y + iz*z, iz = +-1) gives the rows of df that carry terms of m; a tile row t
+// holds the sum with offset m - AD_TR t of two neighbouring tile columns.  A block finishes 16 elements: thread
+// (e, q) takes element e and the tile rows q, q + 16, ... of its window, so that every thread has one short round of
+// independent loads; the 16 partial sums of an element are added in fp64 in a fixed order.
+constexpr int AD_FIN_M = 16, AD_FIN_Q = 16;
+template <int BODY>
+__global__ __launch_bounds__(AD_FIN_M * AD_FIN_Q) void k_antidiag_finish(const FlatFeas feas, const FlatLevel win, int iy, int iz,
+                                                                         const float *__restrict__ x,
+                                                                         const float *__restrict__ part, int n_ct,
+                                                                         float *__restrict__ dx, int n_x) {
+    __shared__ double red[AD_FIN_Q][AD_FIN_M];
+    const int e = threadIdx.x % AD_FIN_M, q = threadIdx.x / AD_FIN_M;
+    const int m = blockIdx.x * AD_FIN_M + e;
+    double s = 0.0;
+    float xm = 0.f;
+    if (q == 0 && m < n_x) xm = x[m];   // issued with the loads of the partial sums, not after the barrier
+    if (m < n_x) {
+        const int32_t y[3] = {m, 0, 0};   // the transformed index is the gradient index (checked on the host)
+        int32_t lo = 0, hi = -1;
+        if (flat_feasible(feas, y)) flat_bounds(win, y, lo, hi);
+        if (lo <= hi) {
+            const int ia = iy * m + iz * lo, ib = iy * m + iz * hi;
+            const int t_lo = min(ia, ib) / AD_TR, t_hi = max(ia, ib) / AD_TR;
+            for (int t = t_lo + q; t <= t_hi; t += AD_FIN_Q) {
+                const int off = m - t * AD_TR;                 // >= 0: the window's rows do not exceed m
+                if (off < 0) continue;
+                const int c1 = off / AD_TC, o = off % AD_TC;
+                float a = 0.f, b = 0.f;
+                if (c1 < n_ct) a = part[(size_t)(t * n_ct + c1) * AD_TILE_SUMS + o];
+                if (c1 >= 1 && c1 - 1 < n_ct && o + AD_TC < AD_TILE_SUMS) b = part[(size_t)(t * n_ct + c1 - 1) * AD_TILE_SUMS + o + AD_TC];
+                s += (double)a + (double)b;
+            }
+        }
+    }
+    red[q][e] = s;
+    __syncthreads();
+    if (q == 0 && m < n_x) {
         s = 0.0;
 #pragma unroll
-        for (int w = 0; w < AD_FIN_WAVES; ++w) s += red[w][lane];
-        dx[m] = (float)((double)dphi<BODY>(x[m]) * s);
+        for (int w = 0; w < AD_FIN_Q; ++w) s += red[w][e];
+        dx[m] = (float)((double)dphi<BODY>(xm) * s);
     }
 }
 
@@ -295,14 +340,16 @@ int pattern_backward(const tad_plan &pl, const void *const *args, const void *df
         break;
     }
     case TAD_FAMILY_ANTIDIAGONAL: {
-        const int n_tiles = (I + AD_BTI - 1) / AD_BTI;
+        const int n_rt = (I + AD_TR - 1) / AD_TR, n_ct = (J + AD_TC - 1) / AD_TC;
         float *part = (float *)ws;
-        TAD_LAUNCH("k_antidiag_backward", k_antidiag_backward, dim3((n_x + 255) / 256, n_tiles), dim3(256), 0, s,
-                   pl.fast.feas, pl.fast.flat[0], pl.fast.dd_iy, pl.fast.dd_iz, pl.fast.jy, pl.fast.jz, df, part, n_x,
-                   J);
+        // the kernels address f as i * J + j with j = m - i: only the plain sum of the two function indices
+        if (pl.fast.dd_iy + pl.fast.jy != 1 || pl.fast.dd_iz + pl.fast.jz != 0) return TAD_EUNSUPPORTED;
+        TAD_LAUNCH("k_antidiag_backward", k_antidiag_backward, dim3(n_ct, n_rt), dim3(64 * AD_WAVES), 0, s, df, part, I, J,
+                   n_ct);
         if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
         TAD_UNARY_SWITCH(pl.expr.body, TAD_LAUNCH("k_antidiag_finish", (k_antidiag_finish<B_>),
-                                                  dim3((n_x + 63) / 64), dim3(64 * AD_FIN_WAVES), 0, s, x, part, n_tiles, dx, n_x));
+                                                  dim3((n_x + AD_FIN_M - 1) / AD_FIN_M), dim3(AD_FIN_M * AD_FIN_Q), 0, s, pl.fast.feas,
+                                                  pl.fast.flat[0], pl.fast.dd_iy, pl.fast.dd_iz, x, part, n_ct, dx, n_x));
         break;
     }
     default: return TAD_EUNSUPPORTED;

@@ -194,8 +194,8 @@ __global__ __launch_bounds__(256) void k_worked_backward(const float *__restrict
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const size_t off = (size_t)(i0 + r0 + rb + r) * J + jc[h];
-                        fv[r][h] = *reinterpret_cast<const float4v *>(f + off);
-                        dv[r][h] = *reinterpret_cast<const float4v *>(df + off);
+                        fv[r][h] = __builtin_nontemporal_load(reinterpret_cast<const float4v *>(f + off));
+                        dv[r][h] = __builtin_nontemporal_load(reinterpret_cast<const float4v *>(df + off));
                     }
             } else {
 #pragma unroll

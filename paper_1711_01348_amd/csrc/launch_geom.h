@@ -53,9 +53,11 @@ inline size_t split_workspace_bytes(long long n_elements, int splits) {
 
 constexpr int kStridedDwElems = 1024;  // function elements per dw block of the strided family (multiple of 256)
 
-constexpr int AD_BTI_ROWS = 64;   // rows per backward tile of the antidiagonal pattern
-inline size_t antidiag_workspace_bytes(int64_t I, int64_t n_x) {
-    return align256((size_t)((I + AD_BTI_ROWS - 1) / AD_BTI_ROWS) * (size_t)n_x * 4);
+// antidiagonal pattern, backward: aligned tiles of df; a tile yields AD_TILE_ROWS + AD_TILE_COLS antidiagonal sums
+constexpr int AD_TILE_ROWS = 256, AD_TILE_COLS = 256, AD_TILE_SUMS = AD_TILE_ROWS + AD_TILE_COLS;
+inline size_t antidiag_workspace_bytes(int64_t I, int64_t J) {
+    return align256((size_t)((I + AD_TILE_ROWS - 1) / AD_TILE_ROWS) * (size_t)((J + AD_TILE_COLS - 1) / AD_TILE_COLS) *
+                    AD_TILE_SUMS * 4);
 }
 
 }  // namespace tad
