@@ -213,7 +213,7 @@ static bool match_strided(tad_plan &pl) {
     pl.fast.P = x.shape[1]; pl.fast.Q = x.shape[2];
     pl.fwd_family = TAD_FAMILY_STRIDED;
     pl.ap[0].family = pl.ap[1].family = TAD_FAMILY_STRIDED;
-    pl.ws_bytes = align256((size_t)((pl.f_count + kStridedDwElems - 1) / kStridedDwElems) * (size_t)(U * V) * 4);
+    pl.ws_bytes = strided_workspace_bytes(e.f_shape[0], e.f_shape[1], e.f_shape[2], U, V, s, x.shape[1], x.shape[2]);
     return true;
 }
 

@@ -51,7 +51,47 @@ inline size_t split_workspace_bytes(long long n_elements, int splits) {
     return splits > 1 ? align256((size_t)n_elements * (size_t)splits * 8) + align256((size_t)n_elements * 4) : 0;
 }
 
-constexpr int kStridedDwElems = 1024;  // function elements per dw block of the strided family (multiple of 256)
+constexpr int kStridedDwElems = 1024;  // function elements per dw block of the strided family, direct form (multiple of 256)
+
+// Strided family: the tiled kernels stage contiguous slices of x (forward, dw) and of df (1 - f^2) (dx) in LDS.
+//   ti  rows i of f per forward / dw block (0: the slice of x does not fit, direct kernels)
+//   tp  rows p of x per dx wavefront       (0: the slice of f does not fit, direct kernel)
+struct StridedTiling {
+    int ti, tp;
+    int x_slice;    // floats of LDS for the slice of x (with room for the alignment shift)
+    int t_slice;    // floats of LDS for the slice of df (1 - f^2), per wavefront
+};
+constexpr int kStridedLdsFloats = 10240;   // 40 KiB per block: four blocks per compute unit
+constexpr int kStridedMaxPerThread = 4;    // function elements per thread of a dw block
+constexpr int kStridedWaveFloats = 1280;   // LDS of one wavefront of a dx block: its slice of df (1 - f^2)
+inline StridedTiling strided_tiling(int64_t N, int64_t I, int64_t J, int64_t U, int64_t s, int64_t P, int64_t Q) {
+    StridedTiling t{0, 0, 0, 0};
+    // forward / dw: rows s*i0 .. s*(i0+ti-1)+U-1 of x, whole rows; prefer at least 1024 blocks
+    for (int ti = 8; ti >= 1; --ti) {
+        const int64_t slice = (s * (ti - 1) + U) * Q + 8;   // + alignment shift and the ragged last vector
+        if (ti * J > 256 * kStridedMaxPerThread || slice > kStridedLdsFloats) continue;
+        if (t.ti == 0) { t.ti = ti; t.x_slice = (int)slice; }
+        if (N * ((I + ti - 1) / ti) >= 1024) { t.ti = ti; t.x_slice = (int)slice; break; }
+    }
+    // dx: a wavefront takes tp rows p and 64 columns q; the rows ceil((p0-U+1)/s) .. floor((p0+tp-1)/s) of f carry its
+    // terms.  Whole rows of f between the first and the last term: (rows - 1) J + about 64 / s + U columns.
+    for (int tp = 16; tp >= 1; --tp) {
+        const int64_t rows = (tp - 1 + U - 1) / s + 2;
+        const int64_t piece = (rows - 1) * J + 64 / s + U + 2 + 8;
+        if (piece > kStridedWaveFloats) continue;
+        t.tp = tp;
+        t.t_slice = (int)kStridedWaveFloats;
+        break;
+    }
+    (void)P;
+    return t;
+}
+inline size_t strided_workspace_bytes(int64_t N, int64_t I, int64_t J, int64_t U, int64_t V, int64_t s, int64_t P, int64_t Q) {
+    const StridedTiling t = strided_tiling(N, I, J, U, s, P, Q);
+    const int64_t direct = (N * I * J + kStridedDwElems - 1) / kStridedDwElems;
+    const int64_t tiled = t.ti ? N * ((I + t.ti - 1) / t.ti) : 0;
+    return align256((size_t)(direct > tiled ? direct : tiled) * (size_t)(U * V) * 4);
+}
 
 // antidiagonal pattern, backward: aligned tiles of df; a tile yields AD_TILE_ROWS + AD_TILE_COLS antidiagonal sums
 constexpr int AD_TILE_ROWS = 256, AD_TILE_COLS = 256, AD_TILE_SUMS = AD_TILE_ROWS + AD_TILE_COLS;

@@ -16,9 +16,11 @@
 #if defined(__HIPCC__)
 #define TAD_HD __host__ __device__ __forceinline__
 #define TAD_UNROLL _Pragma("unroll")
+#define TAD_NOUNROLL _Pragma("unroll 1")
 #else
 #define TAD_HD inline
 #define TAD_UNROLL
+#define TAD_NOUNROLL
 #endif
 
 #include "launch_geom.h"
@@ -283,15 +285,20 @@ TAD_HD int32_t mul24(int32_t a, int32_t b) {
 // floor(a / s) for s > 0 and |a| < 2^23 (guaranteed by flatten_level) without an integer division:
 // a converts exactly, the float quotient a * (1 / s) is within 1/2 of a / s, so its floor is off by at most one
 // and one correction in each direction makes it exact.
-TAD_HD int32_t floor_div_flat(int32_t a, int32_t s, float rs) {
-    // unit and stride-2 index maps: the branch is uniform over the wave and far cheaper than the arithmetic below
-    if (s == 1) return a;
-    if (s == 2) return a >> 1;
+// The division itself, without the shortcuts for the divisors 1 and 2: straight-line code for kernels whose
+// instruction footprint matters more than a few arithmetic instructions.
+TAD_HD int32_t floor_div_float(int32_t a, int32_t s, float rs) {
     int32_t q = (int32_t)floorf((float)a * rs);
     const int32_t r = a - mul24(q, s);
     q += (r >= s) ? 1 : 0;
     q -= (r < 0) ? 1 : 0;
     return q;
+}
+TAD_HD int32_t floor_div_flat(int32_t a, int32_t s, float rs) {
+    // a power of two (unit index maps, strides 2, 4, ...): an arithmetic shift is the exact floor, and the test is a
+    // scalar one, uniform over the wave and far cheaper than the arithmetic below
+    if ((s & (s - 1)) == 0) return a >> __builtin_ctz((unsigned)s);
+    return floor_div_float(a, s, rs);
 }
 
 TAD_HD void flat_bounds(const FlatLevel &L, const int32_t *y, int32_t &lo, int32_t &hi) {

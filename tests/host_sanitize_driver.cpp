@@ -172,8 +172,10 @@ int main() {
         auto exact = [](int64_t a, int64_t s) { int64_t q = a / s; if (a % s != 0 && a < 0) --q; return (int32_t)q; };
         for (int32_t s = 1; s <= 64; ++s) {
             const float rs = 1.f / (float)s;
-            for (int32_t a = -lim; a <= lim; a += (s <= 8 ? 1 : 97))
+            for (int32_t a = -lim; a <= lim; a += (s <= 8 ? 1 : 97)) {
                 if (tad::floor_div_flat(a, s, rs) != exact(a, s)) return 9;
+                if (tad::floor_div_float(a, s, rs) != exact(a, s)) return 13;   // also exact for the divisors 1 and 2
+            }
             for (int32_t a : {-lim, -lim + 1, -s, -s - 1, -s + 1, -1, 0, 1, s - 1, s, s + 1, lim - 1, lim})
                 if (tad::floor_div_flat(a, s, rs) != exact(a, s)) return 10;
         }
