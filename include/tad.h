@@ -48,8 +48,7 @@ typedef enum {
     TAD_EOVERFLOW = -4,    /* integer overflow in Smith / Fourier-Motzkin, or index range beyond int32 */
     TAD_EUNSUPPORTED = -5, /* body / pattern without a kernel, plan beyond the fixed device limits */
     TAD_EDEVICE = -6,      /* kernel launch failed */
-    TAD_ENOMEM = -7,       /* host allocation failed, or workspace too small */
-    TAD_ENOGPU = -8        /* library built without / cannot reach a HIP device */
+    TAD_ENOMEM = -7        /* host allocation failed, or workspace too small */
 } tad_status;
 
 typedef enum { TAD_F32 = 0, TAD_F64 = 1 } tad_dtype;
@@ -212,7 +211,11 @@ void tad_plan_free(tad_plan *plan);
 
 /* Bytes of device workspace tad_eval_forward / tad_eval_backward need: per-tile partial sums of the two-pass
  * reductions, intermediate tensors of the program bodies, and, on the plan-driven kernels, the partial sums of
- * gradient elements whose terms several workgroups share.  0 if the plan's kernels need none. */
+ * gradient elements whose terms several workgroups share.  0 if the plan's kernels need none.
+ * The paper's sketch of the gather form (Sec. 5.1, last paragraphs; Sec. 7) needs no temporary memory: one thread
+ * sums all terms of one gradient element.  This library departs from that where a range collapses a whole
+ * dimension: the terms of an element are split over a wavefront, a tile or several workgroups, and the partial
+ * sums of the tiles wait here for a finishing pass that adds them in a fixed order. */
 size_t tad_plan_workspace_bytes(const tad_plan *plan);
 
 /*
@@ -236,15 +239,17 @@ int tad_plan_bound_row(const tad_plan *plan, int arg, int kind, int level, int r
                        int64_t *scale, int64_t *coef_b, int64_t *coef_z, int64_t *coef_c);
 
 /*
- * The extended indices the plan visits for gradient element beta (host): writes up to `cap`
- * points ((n_f+n_sum) int64 each) in lexicographic order to alpha_out and the total count to *n.
- * Uses exactly the masks, bound rows and index maps the kernels use.
+ * The set Gamma-hat(beta) of Sec. 5.2 -- all extended indices [alpha k] inside the ranges that the index map sends
+ * to gradient element beta -- as the plan enumerates it (host): writes up to `cap` points ((n_f+n_sum) int64 each)
+ * in lexicographic order to alpha_out and the total count to *n.  Uses exactly the masks (Sec. 4.1: cokernel,
+ * divisibility), bound rows (Sec. 4.2) and index maps the kernels use, so comparing it with a scan of the whole
+ * index box checks what the kernels sum over.
  */
 int tad_plan_enumerate(const tad_plan *plan, int arg, int occ, const int64_t *beta,
                        int64_t *alpha_out, size_t cap, size_t *n);
 
-/* Number of visited extended indices for every beta of operand `arg`, first occurrence only (host; counts has
- * one int64 per element). */
+/* |Gamma-hat(beta)| (Sec. 5.2) for every beta of operand `arg`, first occurrence only: the number of terms the
+ * gather sum of that element has (host; counts has one int64 per element). */
 int tad_plan_count_all(const tad_plan *plan, int arg, int64_t *counts);
 
 /*
@@ -338,6 +343,34 @@ int tad_plan_derived_expr(const tad_plan *plan, int arg, int occ, int part, tad_
                           int *operand_out, int *n_args_out);
 int tad_plan_seed_expr(const tad_plan *plan, int which, tad_expr *expr_out, tad_arg *args_out, int *n_args_out);
 
+/*
+ * A gradient evaluated through its derived expressions (Sec. 5.3), end to end: the small graph described above --
+ * seed expressions for g and h where the outer function is not the identity, part 0 of every occurrence of the
+ * tensor, part 1 of the occurrences the outer function reads -- with a plan for each expression, evaluated by the
+ * forward kernels, the parts added by the library in a fixed order.  The result equals what tad_eval_backward gives
+ * for the same tensor (up to the order of the additions); nothing of the method is left to the caller.
+ *
+ * tad_derived_create   host only.  arg: an operand that is a tensor of its own (not an alias) and has a gradient
+ *                      plan; all its occurrences are included.  The object is owned by the caller
+ *                      (tad_derived_free), immutable, and independent of `plan` afterwards.
+ *                      Errors: EINVAL, EUNSUPPORTED (an emitted expression exceeds the limits of tad_expr), EOVERFLOW, ENOMEM.
+ * tad_derived_count    number of seed expressions and of parts in the graph (either pointer may be NULL).
+ * tad_eval_derived     enqueues on `stream`, never synchronises, never allocates.
+ *   args_dev[n_args]   device, read: the operands of the original expression (alias entries ignored)
+ *   df_dev             device, read: dl/df
+ *   dx_dev             device, overwritten with the gradient of tensor `arg`
+ *   ws_dev, ws_bytes   device scratch of at least tad_derived_workspace_bytes: the seed tensors (shape of f), a second
+ *                      tensor of the gradient's size when there are several parts, and the workspace of the
+ *                      expressions' own kernels
+ */
+typedef struct tad_derived tad_derived;
+int tad_derived_create(const tad_plan *plan, int arg, tad_derived **out);
+void tad_derived_free(tad_derived *d);
+size_t tad_derived_workspace_bytes(const tad_derived *d);
+int tad_derived_count(const tad_derived *d, int *n_seeds, int *n_parts);
+int tad_eval_derived(const tad_derived *d, const void *const *args_dev, const void *df_dev, void *dx_dev,
+                     void *ws_dev, size_t ws_bytes, void *stream);
+
 /* Name of the device kernel family used for the forward pass (tad_family). */
 int tad_plan_forward_family(const tad_plan *plan);
 
@@ -378,7 +411,7 @@ int tad_lattice_enumerate(const int64_t *A, int n, int m, const int64_t *lo, con
                           const int64_t *beta, int64_t *x_out, size_t cap, size_t *count);
 
 /*
- * Instrumentation: time one kernel of the library with HIP events.  After tad_profile_begin(name, every)
+ * Instrumentation for benchmarks, not part of the evaluation path: time one kernel of the library with HIP events.  After tad_profile_begin(name, every)
  * each `every`-th launch of the kernel called `name` (the first one included, up to 4096 timed launches)
  * carries a start and a stop event attached to its own dispatch on the stream it is launched on, so the
  * pair reads that kernel's begin and end timestamps.  A timed launch delays the launch that follows it by

@@ -31,7 +31,8 @@ ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
            "tad_plan_bound_row", "tad_plan_enumerate", "tad_plan_count_all", "tad_eval_forward",
            "tad_eval_backward", "tad_plan_forward_family", "tad_strerror", "tad_plan_program_eval", "tad_plan_program_registers",
-           "tad_plan_derived_expr", "tad_plan_seed_expr", "tad_eval_backward_static"]
+           "tad_plan_derived_expr", "tad_plan_seed_expr", "tad_eval_backward_static", "tad_derived_create",
+           "tad_derived_free", "tad_derived_workspace_bytes", "tad_derived_count", "tad_eval_derived"]
 STATIC_SCRATCH_BYTES = 16 << 20
 
 
@@ -106,6 +107,13 @@ def _load():
                                           ctypes.POINTER(ctypes.c_int)]
     lib.tad_plan_seed_expr.argtypes = [vp, ctypes.c_int, ctypes.POINTER(TadExpr), ctypes.POINTER(TadArg),
                                        ctypes.POINTER(ctypes.c_int)]
+    lib.tad_derived_create.argtypes = [vp, ctypes.c_int, ctypes.POINTER(vp)]
+    lib.tad_derived_free.argtypes = [vp]
+    lib.tad_derived_free.restype = None
+    lib.tad_derived_workspace_bytes.argtypes = [vp]
+    lib.tad_derived_workspace_bytes.restype = ctypes.c_size_t
+    lib.tad_derived_count.argtypes = [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    lib.tad_eval_derived.argtypes = [vp, ctypes.POINTER(vp), vp, vp, vp, ctypes.c_size_t, vp]
     lib.tad_strerror.argtypes = [ctypes.c_int]
     lib.tad_strerror.restype = ctypes.c_char_p
     return lib
@@ -379,6 +387,44 @@ class Plan:
         ws = self.workspace(args[0].device) if ws is None else ws
         _check(lib.tad_eval_backward(self._h, ptrs, f.data_ptr(), df.data_ptr(), dptr, ws.data_ptr(),
                                      ws.numel(), ctypes.c_void_p(stream)), "tad_eval_backward")
+        return out
+
+
+class DerivedGradient:
+    """Owner of one ``tad_derived``: the gradient of tensor `arg` of a plan's expression, evaluated through its
+    derived expressions (seed expressions, one part per occurrence, a second part for operands of the outer
+    function); ``counts`` = (seed expressions, parts)."""
+
+    def __init__(self, plan: Plan, arg: int):
+        self.plan, self.arg = plan, arg
+        self._h = ctypes.c_void_p(None)
+        _check(lib.tad_derived_create(plan._h, arg, ctypes.byref(self._h)), "tad_derived_create")
+        a, b = ctypes.c_int(0), ctypes.c_int(0)
+        _check(lib.tad_derived_count(self._h, ctypes.byref(a), ctypes.byref(b)), "tad_derived_count")
+        self.counts = (a.value, b.value)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and lib is not None:
+            lib.tad_derived_free(h)
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib.tad_derived_workspace_bytes(self._h))
+
+    def evaluate(self, args, df, out=None, ws=None):
+        import torch
+        plan = self.plan
+        ptrs = plan._arg_ptrs(args)
+        plan._check_tensor(df, plan.expr.f_shape, "df")
+        if out is None:
+            out = torch.empty_like(args[self.arg])
+        plan._check_tensor(out, plan.expr.args[self.arg].shape, "d" + plan.expr.args[self.arg].name)
+        if ws is None:
+            ws = torch.empty(max(self.workspace_bytes, 1), dtype=torch.uint8, device=df.device)
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.tad_eval_derived(self._h, ptrs, df.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(),
+                                    ctypes.c_void_p(stream)), "tad_eval_derived")
         return out
 
 

@@ -4,6 +4,8 @@
 #include <algorithm>
 #include <cstring>
 
+#include "derived.hpp"
+#include "launch_geom.h"
 #include "plan.hpp"
 
 namespace tad {
@@ -363,11 +365,117 @@ static int seed_expr(const tad_plan &pl, int which, tad_expr *eo, tad_arg *ao, i
     return TAD_OK;
 }
 
+// Plan of one expression of the graph: forward evaluation only, so no gradient plans are derived for it.
+static int node_plan(tad_expr &e, tad_arg *a, int n, tad_dtype dt, tad_derived::Node &node) {
+    for (int q = 0; q < n; ++q) a[q].needs_grad = 0;
+    return tad_plan_derive(&e, a, n, dt, 0, &node.plan);
+}
+
+static int build_graph(const tad_plan &pl, int arg, tad_derived &d) {
+    ScalarForm sf;
+    int rc = scalar_form(pl, sf);
+    if (rc) return rc;
+    d.dtype = pl.dtype;
+    d.arg = arg;
+    d.n_original = (int)pl.args.size();
+    d.root = pl.root;
+    d.count = pl.arg_count[(size_t)arg];
+    const size_t es = pl.dtype == TAD_F64 ? 8 : 4;
+    size_t ws = 0, sub = 0;
+    auto seed_for = [&](int which) -> int {        // which: kSrcSeedG or -3 - p
+        for (const auto &s : d.seeds)
+            if (s.seed == which) return TAD_OK;
+        tad_expr e;
+        tad_arg a[TAD_MAX_ARGS];
+        int n = 0;
+        int r = seed_expr(pl, which == kSrcSeedG ? -1 : -3 - which, &e, a, &n);
+        if (r) return r;
+        tad_derived::Node node;
+        r = node_plan(e, a, n, pl.dtype, node);
+        if (r) return r;
+        node.seed = which;
+        node.src.push_back(kSrcDf);
+        for (int q = 0; q < n - 1; ++q) node.src.push_back(q);
+        node.out_offset = ws;
+        ws += align256((size_t)pl.f_count * es);
+        sub = std::max(sub, node.plan->ws_bytes);
+        d.seeds.push_back(std::move(node));
+        node.plan = nullptr;
+        return TAD_OK;
+    };
+    for (int occ = 0;; ++occ) {
+        int slot = -1;
+        const ArgPlan *ap = get_arg(&pl, arg, occ, &slot);
+        if (!ap) {
+            if (occ == 0) return TAD_EINVAL;
+            if (slot < 0) break;                 // no further occurrence
+            return TAD_EINVAL;                   // an occurrence without a plan
+        }
+        const bool second = !sf.fused && ((sf.outer_mask >> slot) & 1u);
+        for (int part = 0; part < (second ? 2 : 1); ++part) {
+            tad_expr e;
+            tad_arg a[TAD_MAX_ARGS];
+            int src[TAD_MAX_ARGS] = {0}, n = 0;
+            rc = derived_expr(pl, slot, part, &e, a, src, &n);
+            if (rc) return rc;
+            if (src[0] != kSrcDf) {
+                rc = seed_for(src[0]);
+                if (rc) return rc;
+            }
+            tad_derived::Node node;
+            rc = node_plan(e, a, n, pl.dtype, node);
+            if (rc) return rc;
+            node.src.assign(src, src + n);
+            sub = std::max(sub, node.plan->ws_bytes);
+            d.parts.push_back(std::move(node));
+            node.plan = nullptr;
+        }
+    }
+    d.tmp_offset = ws;
+    if (d.parts.size() > 1) ws += align256((size_t)d.count * es);
+    d.sub_offset = ws;
+    d.ws_bytes = ws + sub;
+    return TAD_OK;
+}
+
 }  // namespace tad
 
 using namespace tad;
 
 extern "C" {
+
+int tad_derived_create(const tad_plan *plan, int arg, tad_derived **out) {
+    if (!plan || !out || arg < 0 || arg >= (int)plan->args.size() || plan->root[(size_t)arg] != arg) return TAD_EINVAL;
+    *out = nullptr;
+    tad_derived *d = nullptr;
+    try {
+        d = new tad_derived();
+        const int rc = build_graph(*plan, arg, *d);
+        if (rc) { delete d; return rc; }
+        *out = d;
+        return TAD_OK;
+    } catch (const overflow_error &) {
+        delete d;
+        return TAD_EOVERFLOW;
+    } catch (const std::bad_alloc &) {
+        delete d;
+        return TAD_ENOMEM;
+    } catch (...) {
+        delete d;
+        return TAD_EINVAL;
+    }
+}
+
+void tad_derived_free(tad_derived *d) { delete d; }
+
+size_t tad_derived_workspace_bytes(const tad_derived *d) { return d ? d->ws_bytes : 0; }
+
+int tad_derived_count(const tad_derived *d, int *n_seeds, int *n_parts) {
+    if (!d) return TAD_EINVAL;
+    if (n_seeds) *n_seeds = (int)d->seeds.size();
+    if (n_parts) *n_parts = (int)d->parts.size();
+    return TAD_OK;
+}
 
 int tad_plan_derived_expr(const tad_plan *plan, int arg, int occ, int part, tad_expr *expr_out, tad_arg *args_out,
                           int *operand_out, int *n_args_out) {

@@ -797,7 +797,6 @@ const char *tad_strerror(int status) {
     case TAD_EUNSUPPORTED: return "unsupported body or index pattern";
     case TAD_EDEVICE: return "device error";
     case TAD_ENOMEM: return "out of memory or workspace too small";
-    case TAD_ENOGPU: return "no HIP device";
     default: return "unknown status";
     }
 }

@@ -317,3 +317,35 @@ def test_derived_expression_rules():
                ("y", (2, 2, 2), [[0, 0, 0, 1, 0, 0], [0, 0, 0, 0, 1, 0], [0, 0, 0, 0, 0, 1]])])
     assert _status(lambda: B.Plan(e).derived_expr(0)) == -5
     assert _status(lambda: B.Plan(e).derived_expr(1)) == 0
+
+
+def test_gradient_graph_counts_and_misuse():
+    """tad_derived_create on the host: how many seed expressions and parts the gradient of a tensor consists of."""
+    from paper_1711_01348_amd import binding as B
+    from paper_1711_01348_amd import workloads as wl
+    cases = [
+        # (expression, tensor, seeds, parts)
+        (wl.matmul_expr(5, 4, 3, "f64"), 0, 0, 1),                       # outer function = the sum: no seed
+        (wl.worked_expr(4, 5, 3, "f64"), 2, 1, 1),                        # exp(-s): g is a seed
+        (wl.matrix_square_expr(6, "f64"), 0, 0, 2),                       # two occurrences, one part each
+        (wl.dense_layer_expr(5, 4, 3, "f64"), 2, 1, 1),                   # bias: only read by the outer function ...
+        (wl.gated_gauss_expr(4, 3, 2, "f64"), 0, 2, 2),                   # x inside the sum and outside: g and h, two parts
+        (wl.broadcast_sq_expr(5, 6, "f64"), 0, 0, 1),                     # no sum, no condition: one fused function
+    ]
+    for e, arg, n_seeds, n_parts in cases:
+        plan = B.Plan(e)
+        dg = B.DerivedGradient(plan, arg)
+        if e is cases[3][0]:
+            # the bias does not occur inside the sum: part 0 sums an inner derivative that is identically zero
+            assert dg.counts[1] in (1, 2)
+        else:
+            assert dg.counts == (n_seeds, n_parts), (e.body, arg, dg.counts)
+        assert dg.workspace_bytes >= 0
+    e = wl.matrix_square_expr(6, "f64")
+    plan = B.Plan(e)
+    with pytest.raises(B.TadError):
+        B.DerivedGradient(plan, 1)          # an alias has no gradient of its own
+    with pytest.raises(B.TadError):
+        B.DerivedGradient(plan, 7)
+    assert B.lib.tad_derived_workspace_bytes(None) == 0
+    assert B.lib.tad_eval_derived(None, None, None, None, None, 0, None) == -1

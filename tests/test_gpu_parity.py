@@ -704,64 +704,69 @@ DERIVED = [
 
 @pytest.mark.parametrize("name,make", DERIVED, ids=[d[0] for d in DERIVED])
 def test_derived_expressions(name, make):
-    """The gradient of every occurrence, emitted as expressions (seed expressions first where the outer function
-    is not the identity, a second part for operands the outer function reads) and run through the forward
-    kernels, is the oracle's gradient of the original expression; the gradients of the derived expression itself
-    (second order) are the oracle's gradients of that expression, whose terms the host tests check against the
-    scan of the original."""
+    """tad_eval_derived: the gradient of every tensor, evaluated by the library through its derived expressions
+    (seed expressions first where the outer function is not the identity, one part per occurrence, a second part for
+    operands the outer function reads, the parts added by the library), is the oracle's gradient of the original
+    expression.  Then the derived expression of every occurrence is differentiated once more: its gradients (second
+    order) are the oracle's gradients of that expression, whose terms the host tests check against the scan of the
+    original."""
     import torch
     from paper_1711_01348_amd import binding as B
     e = make()
     w = wl.random_inputs(e, 31, -0.9, 0.9)
     tensors = w.arg_list()
     npdt = tensors[0].dtype
-    want = oracle.backward(e, tensors, w.df, nthreads=8)
+    want = oracle.backward_by_tensor(e, tensors, w.df, nthreads=8)
     plan = B.Plan(e)
-    rng = np.random.Generator(np.random.PCG64(wl.SEED_BASE + 77))
+    dev_args = [_to_dev(x) for x in tensors]
+    dev_df = _to_dev(w.df)
     fused = not e.sums and not e.constraints
-    slots, seen = [], {}
+    occurrences = {}
     for p, a in enumerate(e.args):
-        root = p if a.same_as is None else a.same_as
-        slots.append((root, seen.get(root, 0), p))
-        seen[root] = seen.get(root, 0) + 1
+        occurrences.setdefault(p if a.same_as is None else a.same_as, []).append(p)
+    for root, slots in occurrences.items():
+        dg = B.DerivedGradient(plan, root)
+        n_second = sum(1 for sl in slots if plan.query(root, slots.index(sl))["in_outer"] and not fused)
+        assert dg.counts[1] == len(slots) + n_second, (name, root, dg.counts)
+        got = dg.evaluate(dev_args, dev_df)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy()
+        assert check.within(got, want[root], e.dtype), (name, root, check.errors(got, want[root]))
+        again = dg.evaluate(dev_args, dev_df).cpu().numpy()
+        assert np.array_equal(got, again), (name, root, "not deterministic")
+
+    # second order: v . dx (the part through the sum) differentiated with respect to df / g and the kept operands
+    rng = np.random.Generator(np.random.PCG64(wl.SEED_BASE + 77))
     seeds = {}
 
-    def seed(which):
-        """(on the device by the library, on the host by the oracle in fp64 rounded to the working precision)"""
-        if which not in seeds:
-            sspec = plan.seed_expr(which)
+    def seed():
+        """g = df * d outer / d sum on the device (by the library) and on the host (by the oracle, rounded)"""
+        if not seeds:
+            sspec = plan.seed_expr(-1)
             ins = [w.df] + tensors
             on_gpu = B.Plan(sspec, needs_grad=[False] * len(ins)).forward([_to_dev(x) for x in ins])
             ref = oracle.forward(sspec, ins)
             torch.cuda.synchronize()
-            assert check.within(on_gpu.cpu().numpy(), ref, e.dtype), (name, "seed", which)
-            seeds[which] = (on_gpu, ref.astype(npdt))
-        return seeds[which]
+            assert check.within(on_gpu.cpu().numpy(), ref, e.dtype), (name, "seed")
+            seeds[-1] = ref.astype(npdt)
+        return seeds[-1]
 
-    for root, occ, slot in slots:
-        spec, operands = plan.derived_expr(root, occ)
-        dplan = B.Plan(spec)
-        kept = [tensors[q] for q in operands[1:]]
-        first_dev, first_ref = (_to_dev(w.df), w.df) if operands[0] == -1 else seed(-1)
-        got = dplan.forward([first_dev] + [_to_dev(x) for x in kept])
-        if plan.query(root, occ)["in_outer"] and not fused:
-            spec1, _ = plan.derived_expr(root, occ, 1)
-            got = got + B.Plan(spec1, needs_grad=[False]).forward([seed(slot)[0]])
-        torch.cuda.synchronize()
-        got = got.cpu().numpy()
-        assert check.within(got, want[slot], e.dtype), (name, slot, check.errors(got, want[slot]))
-        # second order: v . dx (the part through the sum) differentiated with respect to df / g and the kept operands
-        ins = [first_ref] + kept
-        dev = [_to_dev(x) for x in ins]
-        v = rng.uniform(-1, 1, spec.f_shape).astype(npdt)
-        grads = dplan.backward(dev, dplan.forward(dev), _to_dev(v))
-        torch.cuda.synchronize()
-        ref = oracle.backward_by_tensor(spec, ins, v, nthreads=8)
-        for a, g, r in zip(spec.args, grads, ref):
-            if r is None:
-                continue
-            g = g.cpu().numpy()
-            assert check.within(g, r, e.dtype), (name, slot, "d" + a.name, check.errors(g, r))
+    for root, slots in occurrences.items():
+        for occ in range(len(slots)):
+            spec, operands = plan.derived_expr(root, occ)
+            dplan = B.Plan(spec)
+            kept = [tensors[q] for q in operands[1:]]
+            ins = [w.df if operands[0] == -1 else seed()] + kept
+            dev = [_to_dev(x) for x in ins]
+            v = rng.uniform(-1, 1, spec.f_shape).astype(npdt)
+            grads = dplan.backward(dev, dplan.forward(dev), _to_dev(v))
+            torch.cuda.synchronize()
+            ref = oracle.backward_by_tensor(spec, ins, v, nthreads=8)
+            for a, g, r in zip(spec.args, grads, ref):
+                if r is None:
+                    continue
+                g = g.cpu().numpy()
+                assert check.within(g, r, e.dtype), (name, root, occ, "d" + a.name, check.errors(g, r))
 
 
 def test_second_order_matrix_product_closed_form_on_the_matrix_cores():
