@@ -145,6 +145,10 @@ typedef struct {
                                     form sum_k (a_ik + b_jk)^2 on the vector ALUs instead of the expanded square on
                                     the matrix cores (for comparing the two forms; the gradients are not affected) */
 
+#define TAD_PLAN_KEEP_PROGRAM 4u /* a program body that spells out one of the built-in bodies (same operations on the
+                                    same operands; sums and products in either order, x * x for x^2) is normally planned
+                                    as that body; with this flag it stays a program and runs on the interpreter kernels */
+
 typedef struct tad_plan tad_plan; /* opaque, immutable after derivation, may be shared between threads */
 
 /* What the derivation found for one argument (Sec. 4.1 quantities, host memory, row-major). */

@@ -26,6 +26,7 @@ FAMILY = {0: "generic", 1: "row_reduce", 2: "diagonal", 3: "antidiagonal", 4: "w
           5: "worked_mfma", 6: "strided", 7: "contraction", 8: "program"}
 PLAN_GENERIC_ONLY = 1
 PLAN_DIRECT_FORM = 2
+PLAN_KEEP_PROGRAM = 4
 ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
@@ -185,7 +186,7 @@ class Plan:
     """Owner of one ``tad_plan``."""
 
     def __init__(self, expr, needs_grad: Optional[Sequence[bool]] = None, generic_only: bool = False,
-                 direct_form: bool = False):
+                 direct_form: bool = False, keep_program: bool = False):
         self.expr = expr
         self.n_ext = len(expr.f_shape) + len(expr.sums)
         if self.n_ext > MAX_EXT or len(expr.args) > MAX_ARGS:
@@ -195,7 +196,8 @@ class Plan:
         self.dtype = {"f32": F32, "f64": F64}[expr.dtype]
         self._h = ctypes.c_void_p(None)
         e, a = pack_expr(expr), pack_args(expr, needs_grad)
-        flags = (PLAN_GENERIC_ONLY if generic_only else 0) | (PLAN_DIRECT_FORM if direct_form else 0)
+        flags = (PLAN_GENERIC_ONLY if generic_only else 0) | (PLAN_DIRECT_FORM if direct_form else 0) | \
+            (PLAN_KEEP_PROGRAM if keep_program else 0)
         _check(lib.tad_plan_derive(ctypes.byref(e), a, len(expr.args), self.dtype, flags,
                                    ctypes.byref(self._h)), "tad_plan_derive")
 

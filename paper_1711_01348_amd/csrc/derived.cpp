@@ -12,28 +12,14 @@ namespace tad {
 
 // Inner and outer function of any body as postfix programs.
 static bool body_programs(const tad_plan &pl, std::vector<tad_op> &inner, std::vector<tad_op> &outer, int &n_operands) {
-    auto op = [](int code, int iarg = 0) { tad_op o{}; o.op = code; o.iarg = iarg; return o; };
-    const tad_op A0 = op(TAD_OP_ARG, 0), A1 = op(TAD_OP_ARG, 1), SUM = op(TAD_OP_SUM);
-    n_operands = body_arg_count(pl.expr.body);
-    switch (pl.expr.body) {
-    case TAD_BODY_SQ: inner = {A0}; outer = {SUM, op(TAD_OP_POWI, 2)}; return true;
-    case TAD_BODY_CUBE: inner = {A0}; outer = {SUM, op(TAD_OP_POWI, 3)}; return true;
-    case TAD_BODY_SIN: inner = {A0}; outer = {SUM, op(TAD_OP_SIN)}; return true;
-    case TAD_BODY_EXP: inner = {A0}; outer = {SUM, op(TAD_OP_EXP)}; return true;
-    case TAD_BODY_MUL: inner = {A0, A1, op(TAD_OP_MUL)}; outer = {SUM}; return true;
-    case TAD_BODY_TANH_DOT: inner = {A0, A1, op(TAD_OP_MUL)}; outer = {SUM, op(TAD_OP_TANH)}; return true;
-    case TAD_BODY_WORKED:   // exp(-sum((a + b)^2 c + d^3))
-        inner = {A0, A1, op(TAD_OP_ADD), op(TAD_OP_POWI, 2), op(TAD_OP_ARG, 2), op(TAD_OP_MUL),
-                 op(TAD_OP_ARG, 3), op(TAD_OP_POWI, 3), op(TAD_OP_ADD)};
-        outer = {SUM, op(TAD_OP_NEG), op(TAD_OP_EXP)};
-        return true;
-    case TAD_BODY_PROGRAM:
+    if (pl.expr.body == TAD_BODY_PROGRAM) {
         inner.assign(pl.expr.inner, pl.expr.inner + pl.expr.n_inner);
         outer.assign(pl.expr.outer, pl.expr.outer + pl.expr.n_outer);
         n_operands = pl.expr.n_operands;
         return true;
-    default: return false;
     }
+    n_operands = body_arg_count(pl.expr.body);
+    return builtin_body_programs(pl.expr.body, inner, outer);
 }
 
 // How the scalar part of the gradients is organised.

@@ -367,6 +367,18 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
     if (!expr || !args || !out) return TAD_EINVAL;
     *out = nullptr;
     if (dt != TAD_F32 && dt != TAD_F64) return TAD_EINVAL;
+    // a program body that spells out one of the built-in bodies is planned as that body: the expression then reaches
+    // the kernels written for it (and their hand-written partial derivatives, the same functions)
+    tad_expr as_builtin;
+    if (expr->body == TAD_BODY_PROGRAM && !(flags & TAD_PLAN_KEEP_PROGRAM) && expr->n_operands >= 1 &&
+        expr->n_operands <= TAD_MAX_ARGS && expr->n_sum >= 0) {
+        const int id = matching_builtin_body(*expr);
+        if (id >= 0) {
+            as_builtin = *expr;
+            as_builtin.body = id;
+            expr = &as_builtin;
+        }
+    }
     const int want = expr->body == TAD_BODY_PROGRAM ? expr->n_operands : body_arg_count(expr->body);
     if (want < 0) return TAD_EUNSUPPORTED;
     if (expr->body == TAD_BODY_PROGRAM && (want < 1 || want > TAD_MAX_ARGS)) return TAD_EINVAL;

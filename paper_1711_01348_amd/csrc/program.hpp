@@ -93,6 +93,74 @@ inline int parse_postfix(const tad_op *ops, int n, bool outer, int n_operands, G
     return st[0];
 }
 
+// The built-in bodies written as the postfix programs they stand for; false for a body that has none.
+inline bool builtin_body_programs(int body, std::vector<tad_op> &inner, std::vector<tad_op> &outer) {
+    auto op = [](int code, int iarg = 0) { tad_op o{}; o.op = code; o.iarg = iarg; return o; };
+    const tad_op A0 = op(TAD_OP_ARG, 0), A1 = op(TAD_OP_ARG, 1), SUM = op(TAD_OP_SUM);
+    switch (body) {
+    case TAD_BODY_SQ: inner = {A0}; outer = {SUM, op(TAD_OP_POWI, 2)}; return true;
+    case TAD_BODY_CUBE: inner = {A0}; outer = {SUM, op(TAD_OP_POWI, 3)}; return true;
+    case TAD_BODY_SIN: inner = {A0}; outer = {SUM, op(TAD_OP_SIN)}; return true;
+    case TAD_BODY_EXP: inner = {A0}; outer = {SUM, op(TAD_OP_EXP)}; return true;
+    case TAD_BODY_MUL: inner = {A0, A1, op(TAD_OP_MUL)}; outer = {SUM}; return true;
+    case TAD_BODY_TANH_DOT: inner = {A0, A1, op(TAD_OP_MUL)}; outer = {SUM, op(TAD_OP_TANH)}; return true;
+    case TAD_BODY_WORKED:   // exp(-sum((a + b)^2 c + d^3))
+        inner = {A0, A1, op(TAD_OP_ADD), op(TAD_OP_POWI, 2), op(TAD_OP_ARG, 2), op(TAD_OP_MUL),
+                 op(TAD_OP_ARG, 3), op(TAD_OP_POWI, 3), op(TAD_OP_ADD)};
+        outer = {SUM, op(TAD_OP_NEG), op(TAD_OP_EXP)};
+        return true;
+    default: return false;
+    }
+}
+
+// Do two expression graphs compute the same function by the same operations?  Structural comparison from the result
+// nodes down; sums and products match with their inputs in either order, x * x matches x^2.
+inline bool same_expression(const Graph &ga, int a, const Graph &gb, int b) {
+    const Node &x = ga.nodes[(size_t)a], &y = gb.nodes[(size_t)b];
+    if (x.op != y.op) {
+        // x * x against x^2
+        const Node *m = x.op == P_MUL ? &x : y.op == P_MUL ? &y : nullptr, *p = x.op == P_POWI ? &x : y.op == P_POWI ? &y : nullptr;
+        if (!m || !p || p->k != 2) return false;
+        const Graph &gm = m == &x ? ga : gb, &gp = p == &x ? ga : gb;
+        return same_expression(gm, m->a, gm, m->b) && same_expression(gm, m->a, gp, p->a);
+    }
+    switch (x.op) {
+    case P_CONST: return x.c == y.c;
+    case P_ARG: return x.k == y.k;
+    case P_SUM: return true;
+    case P_ADD: case P_MUL:
+        return (same_expression(ga, x.a, gb, y.a) && same_expression(ga, x.b, gb, y.b)) ||
+               (same_expression(ga, x.a, gb, y.b) && same_expression(ga, x.b, gb, y.a));
+    case P_SUB: case P_DIV: return same_expression(ga, x.a, gb, y.a) && same_expression(ga, x.b, gb, y.b);
+    case P_POWI: return x.k == y.k && same_expression(ga, x.a, gb, y.a);
+    default: return same_expression(ga, x.a, gb, y.a);   // one-input functions
+    }
+}
+
+// The built-in body whose inner and outer function a program body spells out (same operands in the same order), or -1.
+// Such an expression is planned as that body, so that it reaches the kernels written for it.
+inline int matching_builtin_body(const tad_expr &e) {
+    if (e.body != TAD_BODY_PROGRAM) return -1;
+    Graph gi, go;
+    const uint32_t none = 0;
+    const int ri = parse_postfix(e.inner, e.n_inner, false, e.n_operands, gi);
+    const int ro = parse_postfix(e.outer, e.n_outer, true, e.n_operands, go, none);   // an outer function that reads operands fails here
+    if (ri < 0 || ro < 0) return -1;
+    static const int bodies[] = {TAD_BODY_SQ, TAD_BODY_CUBE, TAD_BODY_SIN, TAD_BODY_EXP, TAD_BODY_MUL, TAD_BODY_WORKED, TAD_BODY_TANH_DOT};
+    static const int operands[] = {1, 1, 1, 1, 2, 4, 2};
+    for (size_t t = 0; t < sizeof bodies / sizeof bodies[0]; ++t) {
+        if (operands[t] != e.n_operands) continue;
+        if (e.n_sum > 0 && (bodies[t] == TAD_BODY_SQ || bodies[t] == TAD_BODY_CUBE || bodies[t] == TAD_BODY_SIN)) continue;
+        std::vector<tad_op> bi, bo;
+        builtin_body_programs(bodies[t], bi, bo);
+        Graph hi, ho;
+        const int si = parse_postfix(bi.data(), (int)bi.size(), false, operands[t], hi);
+        const int so = parse_postfix(bo.data(), (int)bo.size(), true, operands[t], ho, none);
+        if (si >= 0 && so >= 0 && same_expression(gi, ri, hi, si) && same_expression(go, ro, ho, so)) return bodies[t];
+    }
+    return -1;
+}
+
 // Reverse accumulation from `result` back to the inputs.  The derivative expressions are appended to the same
 // graph, so they share the forward nodes (Sec. 2: the derivative graph reuses the values of the function graph).
 // input_grad[p] receives the node of d result / d operand p for p < n_operands and input_grad[n_operands] that of

@@ -281,15 +281,17 @@ def test_product_programs_run_on_the_matrix_cores():
     for p in range(2):
         spec, _ = plan.derived_expr(p)
         assert B.Plan(spec).forward_family == "contraction"
-        assert B.Plan(spec, generic_only=True).forward_family == "program"
+        assert B.Plan(spec, generic_only=True, keep_program=True).forward_family == "program"
+        assert B.Plan(spec, generic_only=True).forward_family == "generic"      # recognised as the product body
     assert B.Plan(wl.as_program(wl.matmul_expr(8, 12, 16, "f32"))).forward_family == "contraction"
-    assert B.Plan(wl.as_program(wl.matmul_expr(8, 12, 16, "f64"))).forward_family == "program"
+    assert B.Plan(wl.as_program(wl.matmul_expr(8, 12, 16, "f64")), keep_program=True).forward_family == "program"
+    assert B.Plan(wl.as_program(wl.matmul_expr(8, 12, 16, "f64"))).forward_family == "generic"   # recognised as the product body
 
 
 def test_derived_expression_rules():
     # an outer function puts a second, nested sum into the gradient: operand 0 is then the seed g, not df
     assert B.Plan(wl.config1().expr).derived_expr(0)[1][0] == -2
-    assert B.Plan(wl.as_program(wl.config1().expr)).derived_expr(3)[1] == [-2, 3]
+    assert B.Plan(wl.as_program(wl.config1().expr), keep_program=True).derived_expr(3)[1] == [-2, 3]
     assert B.Plan(wl.matmul_expr(2, 2, 2, "f64")).derived_expr(0)[1][0] == -1
     # without a summation outer(inner(x)) is one function: f_ij = x_i^2 needs no seed
     assert B.Plan(wl.broadcast_sq_expr(3, 4, "f64")).derived_expr(0)[1] == [-1, 0]

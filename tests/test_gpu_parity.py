@@ -20,10 +20,12 @@ def _to_dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-def run_gpu(w, generic_only=False, wanted=None):
+def run_gpu(w, generic_only=False, wanted=None, keep_program=True):
+    """keep_program: a body given as programs stays on the interpreter kernels even where it spells out a built-in
+    body (most tests here give built-in bodies as programs precisely to exercise those kernels)."""
     import torch
     from paper_1711_01348_amd import binding as B
-    plan = B.Plan(w.expr, generic_only=generic_only)
+    plan = B.Plan(w.expr, generic_only=generic_only, keep_program=keep_program)
     args = [_to_dev(a) for a in w.arg_list()]
     f = plan.forward(args)
     grads = plan.backward(args, f, _to_dev(w.df), wanted=wanted)
@@ -569,6 +571,39 @@ def test_program_bodies(name, make):
     plan, f, grads = run_gpu(w)
     assert plan.forward_family == "program"
     assert_parity(w, f, grads, f_ref, g_ref, name)
+
+
+RECOGNISED = [
+    ("worked", lambda: wl.config3("small"), "worked"),
+    ("worked_mfma", lambda: wl.config4("small"), "worked_mfma"),
+    ("strided", lambda: wl.config5("small"), "strided"),
+    ("antidiagonal", lambda: wl.config2(3, "small"), "antidiagonal"),
+    ("row_reduce", lambda: wl.config2(1, "small"), "row_reduce"),
+    ("product", lambda: wl.random_inputs(wl.matmul_expr(132, 260, 72, "f32"), 21), "contraction"),
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,make,family", RECOGNISED, ids=[c[0] for c in RECOGNISED])
+def test_program_that_spells_out_a_builtin_body_reaches_its_kernels(name, make, family):
+    """A body given as postfix programs that are the built-in body's own functions (here also with the operands of
+    its sums and products swapped) is planned as that body: same kernel family, same bits as the built-in form."""
+    from paper_1711_01348_amd import binding as B
+    w = make()
+    ep = wl.as_program(w.expr)
+    if name.startswith("worked"):       # (b + a)^2, c on the left of the product, d^3 first
+        ep.inner = [("arg", 3), ("powi", 3), ("arg", 2), ("arg", 1), ("arg", 0), ("add",), ("powi", 2), ("mul",), ("add",)]
+    wp = wl.Workload(w.name, ep, w.inputs, w.df)
+    plan, f, grads = run_gpu(wp, keep_program=False)
+    assert plan.forward_family == family
+    _, f_ref, g_ref = run_gpu(w)
+    assert np.array_equal(f, f_ref)
+    for g, r in zip(grads, g_ref):
+        assert np.array_equal(g, r)
+    # a different function must not match: (a + b)^2 c + d^2
+    if name == "worked":
+        ep.inner[1] = ("powi", 2)
+        assert B.Plan(ep).forward_family == "program"
 
 
 @pytest.mark.gpu

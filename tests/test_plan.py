@@ -499,7 +499,7 @@ PROGRAMS = [
 def test_symbolic_derivatives_match_forward_mode_oracle(inner, outer, nop):
     """The programs derived by reverse accumulation, evaluated on the host, against the oracle's dual numbers."""
     e = _scalar_expr(inner, outer, nop)
-    plan = B.Plan(e)
+    plan = B.Plan(e, keep_program=True)
     rng = np.random.default_rng(8)
     for _ in range(20):
         v = rng.uniform(0.2, 1.4, size=nop)      # positive: sqrt and log stay real, y - x may be either sign
@@ -558,7 +558,7 @@ def test_program_register_form():
     assert plan.program_registers(-2) == 0 and plan.program_registers(-3) == 0     # the sum itself; the constant 1
     assert plan.program_registers(-4) == 0                                         # d outer / d operand: zero
     # x * y: one operation on two operands
-    plan = B.Plan(_scalar_expr([("arg", 0), ("arg", 1), ("mul",)], [("sum",)], 2))
+    plan = B.Plan(_scalar_expr([("arg", 0), ("arg", 1), ("mul",)], [("sum",)], 2), keep_program=True)
     assert plan.program_registers(-1) == 1
     assert plan.program_registers(0) == 0 and plan.program_registers(1) == 0       # d/dx = y, d/dy = x: operands
     # a chain of unary operations needs one register however long it is
@@ -599,8 +599,11 @@ def test_program_rules():
     # a derivative too long for the device form is refused, not truncated
     long_inner = [("arg", 0)] + [("arg", 0), ("div",), ("sin",)] * 7
     assert _status(lambda: mk(long_inner, ok_out)) in (0, -5)
-    plan = B.Plan(wl.as_program(wl.config1().expr))
+    plan = B.Plan(wl.as_program(wl.config1().expr), keep_program=True)
     assert plan.forward_family == "program" and plan.workspace_bytes >= 8 * 6 * 8
+    # without the flag a program that spells out a built-in body is planned as that body
+    assert B.Plan(wl.as_program(wl.config1().expr)).forward_family == "generic"
+    assert B.Plan(wl.as_program(wl.config3("small").expr)).forward_family == "worked"
     assert _status(lambda: B.Plan(wl.config1().expr).program_eval(-1, np.zeros(4))) == -1   # not a program plan
     plan = B.Plan(wl.biased_tanh_expr(3, 2, "f64"), needs_grad=[True, False, True])
     assert _status(lambda: plan.program_eval(-2, None, 0.3)) == -1             # the outer function needs the operand values
