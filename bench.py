@@ -34,19 +34,19 @@ MIN_WINDOW_MS = 20.0            # the workloads beside the headline are timed fo
 # 256 MiB copy in the same run (summaries under profiles/).  Each entry carries the SHA-256 prefix of the kernel source
 # the counters were taken with; once that file changes the entry is stale and the bench line reports traffic = null.
 MEASURED_TRAFFIC = {
-    "cfg3": dict(source="kernels_worked.hip", sha256="526515596b424785", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
+    "cfg3": dict(source="kernels_worked.hip", sha256="c4542a3a73030316", fetch_bytes=521.5 * 2**20, write_bytes=9.5 * 2**20,
             summary="profiles/worked_8192x8192x5_f32.md"),
     "cfg4": dict(source="kernels_mfma.hip", sha256="a837d56d973eb5ad", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
             summary="profiles/worked_mfma_4096x4096x256_f32.md"),
     "matmul": dict(source="kernels_contract.hip", sha256="131b43a0ad9d9653", fetch_bytes=512.0 * 2**20, write_bytes=64.0 * 2**20,
             summary="profiles/contraction_4096x4096x4096_f32.md"),
-    "cfg2_1": dict(source="kernels_patterns.hip", sha256="4a0de37557d44903", fetch_bytes=64.3 * 2**20, write_bytes=0.1 * 2**20,
+    "cfg2_1": dict(source="kernels_patterns.hip", sha256="82a47a45178e317d", fetch_bytes=64.3 * 2**20, write_bytes=0.1 * 2**20,
             summary="profiles/row_reduce_4096x4096_f32.md"),
-    "cfg2_2": dict(source="kernels_patterns.hip", sha256="4a0de37557d44903", fetch_bytes=1.1 * 2**20, write_bytes=256.2 * 2**20,
+    "cfg2_2": dict(source="kernels_patterns.hip", sha256="82a47a45178e317d", fetch_bytes=1.1 * 2**20, write_bytes=256.2 * 2**20,
             summary="profiles/diagonal_8192_f32.md"),
-    "cfg2_3": dict(source="kernels_patterns.hip", sha256="4a0de37557d44903", fetch_bytes=72.0 * 2**20, write_bytes=2.1 * 2**20,
+    "cfg2_3": dict(source="kernels_patterns.hip", sha256="82a47a45178e317d", fetch_bytes=64.1 * 2**20, write_bytes=0.5 * 2**20,
             summary="profiles/antidiagonal_4096x4096_f32.md"),
-    "cfg5": dict(source="kernels_strided.hip", sha256="45eafb292ba47827", fetch_bytes=24.2 * 2**20, write_bytes=8.1 * 2**20,
+    "cfg5": dict(source="kernels_strided.hip", sha256="748ea7db15a78ccd", fetch_bytes=20.6 * 2**20, write_bytes=8.5 * 2**20,
             summary="profiles/strided_32x128x128_f32.md"),
 }
 
@@ -110,7 +110,7 @@ def accounting(name, w):
     return elems, elems * es, dom
 
 
-def run_gpu(name, steps, warmup, rotate_bytes=0, min_window_ms=0.0):
+def run_gpu(name, steps, warmup, rotate_bytes=0, min_window_ms=0.0, grads=None):
     """Time `steps` forward+backward passes.  With rotate_bytes > 0 the step cycles over enough independent
     buffer sets to exceed that footprint, so that a workload smaller than the last-level cache still streams
     from HBM.  With min_window_ms > 0 the step count is raised until the timed region lasts that long (a 1.5 ms
@@ -130,18 +130,18 @@ def run_gpu(name, steps, warmup, rotate_bytes=0, min_window_ms=0.0):
         args = [torch.from_numpy(a).to(dev) for a in w.arg_list()]
         df = torch.from_numpy(w.df).to(dev)
         f = torch.empty(tuple(w.expr.f_shape), dtype=df.dtype, device=dev)
-        grads = [torch.empty_like(a) for a in args]
-        return args, df, f, grads, plan.workspace(dev)
+        out = [torch.empty_like(a) if (grads is None or p in grads) else None for p, a in enumerate(args)]
+        return args, df, f, out, plan.workspace(dev)
 
     sets = [make_set()]
-    foot = sum(t.numel() * t.element_size() for t in sets[0][0] + [sets[0][1], sets[0][2]] + sets[0][3])
+    foot = sum(t.numel() * t.element_size() for t in sets[0][0] + [sets[0][1], sets[0][2]] + [o for o in sets[0][3] if o is not None])
     while rotate_bytes and foot * len(sets) < rotate_bytes and len(sets) < 64:
         sets.append(make_set())
 
     def step(i):
-        args, df, f, grads, ws = sets[i % len(sets)]
+        args, df, f, out, ws = sets[i % len(sets)]
         plan.forward(args, out=f, ws=ws)
-        plan.backward(args, f, df, out=grads, ws=ws)
+        plan.backward(args, f, df, wanted=[o is not None for o in out], out=out, ws=ws)
 
     warm = max(warmup, WARM_PASSES * len(sets))      # first touches of a buffer set are never part of the timed region
     for i in range(warm):
@@ -170,11 +170,11 @@ def run_gpu(name, steps, warmup, rotate_bytes=0, min_window_ms=0.0):
     dom_ms = ms.value / n.value if n.value else None
     # forward / backward split (outside the timed region) with events on the stream the kernels run on
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    args, df, f, grads, ws = sets[0]
+    args, df, f, out, ws = sets[0]
     ev[0].record()
     plan.forward(args, out=f, ws=ws)
     ev[1].record()
-    plan.backward(args, f, df, out=grads, ws=ws)
+    plan.backward(args, f, df, wanted=[o is not None for o in out], out=out, ws=ws)
     ev[2].record()
     torch.cuda.synchronize()
     ms_step = (t1 - t0) * 1e3 / steps
@@ -278,6 +278,9 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-others", action="store_true", help="skip the other configurations (extra keys)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--grads", default=None,
+                    help="operand numbers whose gradients the backward call computes (e.g. 0 or 0,2); default: all. "
+                         "For looking at one gradient's kernels alone; the accounting of elements stays that of the whole step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (reference point for HBM byte counters)")
     a = ap.parse_args()
@@ -298,7 +301,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     rot = 0 if a.workload == "cfg3" else ROTATE_BYTES
-    r = run_gpu(a.workload, a.steps, a.warmup, rotate_bytes=rot)
+    only = None if a.grads is None else [int(t) for t in a.grads.split(",")]
+    r = run_gpu(a.workload, a.steps, a.warmup, rotate_bytes=rot, grads=only)
     out = {
         "metric": "fwd+bwd tensor elements/s; achieved HBM GB/s or FLOP/s vs MI355X peak",
         "value": r["elements_per_s"], "unit": "elements/s", "n_gpus": 1, "steps": a.steps,
@@ -309,7 +313,7 @@ def main():
                    "ms_forward": r["ms_forward"], "ms_backward": r["ms_backward"],
                    "step_algorithmic_GBs": r["algorithmic_gbs"],
                    "step_frac_of_hbm_peak": r["algorithmic_gbs"] / HBM_PEAK_GBS,
-                   "buffer_sets": r["buffer_sets"]},
+                   "buffer_sets": r["buffer_sets"], "gradients": "all" if only is None else only},
         "roofline": roofline(r),
     }
     if not a.no_others:
