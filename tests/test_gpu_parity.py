@@ -102,6 +102,14 @@ def test_config1_fp64_tight():
     assert np.count_nonzero(dc - np.diag(np.diag(dc))) == 0
 
 
+def _padded_strided(N, I, J, U, V, stride, more_rows, more_cols):
+    """The strided map with an x that is larger than the range the map reaches: the gradient there is exactly zero."""
+    e = wl.strided_tanh_expr(N, I, J, U, V, stride, "f32")
+    x = e.args[0]
+    e.args[0] = wl.ArgSpec(x.name, (x.shape[0], x.shape[1] + more_rows, x.shape[2] + more_cols), x.A)
+    return e
+
+
 ASSORTED = [
     lambda: _expr("sin", (13,), [], [("x", (13,), [[1]])]),
     lambda: _expr("cube", (5,), [], [("x", (5, 5), [[1], [1]])]),
@@ -137,6 +145,10 @@ ASSORTED = [
     lambda: wl.strided_tanh_expr(2, 5, 130, 7, 7, 8, "f32"),     # 49 taps, stride 8: general range divisors
     lambda: wl.strided_tanh_expr(2, 9, 200, 3, 3, 2, "f32"),
     lambda: wl.strided_tanh_expr(1, 6, 70, 4, 5, 1, "f32"),      # stride 1: up to 20 terms per gradient element
+    lambda: wl.strided_tanh_expr(1, 3, 4, 3, 3, 2, "f32"),       # one wavefront's worth of columns, one n
+    lambda: wl.strided_tanh_expr(5, 40, 132, 3, 3, 1, "f32"),    # stride 1 under a 3 x 3 filter: three values per range
+    lambda: wl.strided_tanh_expr(2, 70, 96, 2, 2, 3, "f32"),     # stride 3 under a 2 x 2 filter: rows and columns of x nobody reads
+    lambda: _padded_strided(3, 33, 60, 3, 3, 2, 4, 7),           # x with rows and columns beyond the referenced range
     # few gradient elements with long sums: one block per element shares the z loops
     lambda: _expr("exp", (40, 3001), [], [("x", (40,), [[1, 0]])], "f32"),                 # one range, split in pieces
     lambda: _expr("exp", (7, 50, 61), [(0, 4)], [("x", (11,), [[1, 0, 0, 1]])], "f64"),     # three kernel coordinates
