@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void k_generic_forward_finish(const double *__
 // Element number `idx` of the launch over the gradient of operand p (gather_element_index: *lin receives its
 // position in the tensor): masks, then the terms of the z loops shared by `parts` threads.
 // Returns false (and *sum = 0) when a mask zeroes the element or the number is no element.
-template <int BODY, typename T>
+template <int BODY, typename T, int U = 4>
 __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const ArgPtrs &A, const T *__restrict__ f,
                                                const T *__restrict__ df, int idx, int *lin, int part, int parts,
                                                double *sum, int group = 0, int groups = 1) {
@@ -153,8 +153,7 @@ __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
         // innermost run: offsets advance by a constant per step.  Four terms are loaded before the first is used,
         // so that the loop waits for memory once per four terms (the terms are still added in ascending order;
-        // the slots past the end of the run reload its current term and are dropped).
-        constexpr int U = 4;
+        // the slots past the end of the run reload its current term and are dropped).  U = 1: the plain loop.
         int64_t off[NA + 1], stp[NA + 1];
         for (int q = 0; q < NA; ++q) {
             off[q] = gather_offset(P, q, y, z);
@@ -257,6 +256,7 @@ __global__ __launch_bounds__(256) void k_generic_gather_lanes(const GatherPlan P
 // and a wavefront that walks this code once spends most of its time fetching it (8 to 25 us per launch for a few
 // dozen terms); in one launch the gradients pay that together instead of one after the other.  Workgroups of one
 // wavefront; workgroup b works on gradient g with first[g] <= b < first[g + 1].
+constexpr long long kSpreadElements = 1024;   // up to this many gradient elements in all: a wavefront each
 struct MultiGather {
     int32_t count;
     int32_t first[kMaxArgs + 1];
@@ -265,14 +265,29 @@ struct MultiGather {
     void *dx[kMaxArgs];
     GatherPlan plan[kMaxArgs];
 };
-template <int BODY, typename T>
+// SPREAD: for expressions with few gradient elements in all (the host checks): one workgroup, a single wavefront,
+// per element; the lanes share its terms and add their sums in a fixed order, and none of the code for elements of
+// very different weight is compiled in (700 instead of 5100 instructions for the worked expression in fp64).
+// Such a launch waits for its instructions, not for its data: on the 8 x 6 x 5 worked expression a wavefront
+// spends two thirds of its cycles waiting, 1.5 % of them for memory instructions (24.7 -> 22.2 us).
+template <int BODY, typename T, bool SPREAD>
 __global__ __launch_bounds__(64) void k_generic_gather_multi(const MultiGather M, const ArgPtrs A,
                                                              const T *__restrict__ f, const T *__restrict__ df,
                                                              int classify) {
     int g = 0;
     while (g + 1 < M.count && (int)blockIdx.x >= M.first[g + 1]) ++g;   // the same for the whole workgroup
-    const GatherPlan &P = M.plan[g];
     const int p = M.operand[g];
+    if constexpr (SPREAD) {
+        const GatherPlan &P = M.plan[g];
+        double part_sum;
+        int lin;
+        const bool live = gather_element<BODY, T, 1>(P, p, A, f, df, (int)blockIdx.x - M.first[g], &lin, (int)threadIdx.x,
+                                                     64, &part_sum);   // the same for all lanes
+        const double total = wave_sum_all(part_sum);
+        if (threadIdx.x == 0) store_element(static_cast<T *>(M.dx[g]), lin, live, total, 0);
+        return;
+    }
+    const GatherPlan &P = M.plan[g];
     const int idx = ((int)blockIdx.x - M.first[g]) * 64 + (int)threadIdx.x, lane = threadIdx.x;
     const bool inside = idx < M.n[g];
     // as in k_generic_gather: an element with many terms is summed by the whole wavefront
@@ -320,7 +335,7 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
     if (!pl.has_alias) {
         MultiGather M{};
         bool fits = true;
-        long long blocks = 0;
+        long long blocks = 0, elements = 0;
         for (size_t q = 0; q < pl.args.size() && fits; ++q) {
             if (!dx[q]) continue;
             const long long n = pl.arg_count[q];
@@ -335,12 +350,24 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
             M.plan[g] = pl.ap[q].dev;
             M.plan[g].live = 0;   // all elements of the small tensor are visited; masked ones are stored as zeros
             blocks += (n + 63) / 64;
+            elements += n;
         }
         if (fits && M.count >= 2) {
             M.first[M.count] = (int32_t)blocks;
-            TAD_LAUNCH("k_generic_gather_multi", (k_generic_gather_multi<BODY, T>), dim3((unsigned)blocks), dim3(64), 0, s,
-                       M, A, static_cast<const T *>(f), static_cast<const T *>(df),
-                       pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
+            if (elements <= kSpreadElements) {
+                // one wavefront per element: the first workgroup of gradient g is the sum of the earlier gradients' elements
+                long long first = 0;
+                for (int g = 0; g < M.count; ++g) {
+                    M.first[g] = (int32_t)first;
+                    first += M.n[g];
+                }
+                M.first[M.count] = (int32_t)first;
+                TAD_LAUNCH("k_generic_gather_multi", (k_generic_gather_multi<BODY, T, true>), dim3((unsigned)first), dim3(64),
+                           0, s, M, A, static_cast<const T *>(f), static_cast<const T *>(df), 0);
+            } else
+                TAD_LAUNCH("k_generic_gather_multi", (k_generic_gather_multi<BODY, T, false>), dim3((unsigned)blocks), dim3(64),
+                           0, s, M, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                           pl.terms_total >= (double)kHeavyTerms ? 1 : 0);
             return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
         }
     }
