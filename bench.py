@@ -38,7 +38,7 @@ MEASURED_TRAFFIC = {
             summary="profiles/worked_8192x8192x5_f32.md"),
     "cfg4": dict(source="kernels_mfma.hip", sha256="a837d56d973eb5ad", fetch_bytes=160.5 * 2**20, write_bytes=32.2 * 2**20,
             summary="profiles/worked_mfma_4096x4096x256_f32.md"),
-    "matmul": dict(source="kernels_contract.hip", sha256="131b43a0ad9d9653", fetch_bytes=512.0 * 2**20, write_bytes=64.0 * 2**20,
+    "matmul": dict(source="kernels_contract.hip", sha256="44643592ea5bb39b", fetch_bytes=626.4 * 2**20, write_bytes=64.0 * 2**20,
             summary="profiles/contraction_4096x4096x4096_f32.md"),
     "cfg2_1": dict(source="kernels_patterns.hip", sha256="82a47a45178e317d", fetch_bytes=64.3 * 2**20, write_bytes=0.1 * 2**20,
             summary="profiles/row_reduce_4096x4096_f32.md"),

@@ -14,13 +14,21 @@
 // Block tile 128 x 128, four waves of 64 x 64 (2 x 2 MFMA tiles), contraction tile 32, global -> register -> LDS
 // staging.  Two sets of tiles in LDS: while the MFMAs of tile t read one set, the registers holding tile t + 1 are
 // written to the other set and the global loads of tile t + 2 go out, all of it between MFMA groups, so that one
-// barrier per tile remains and no wave stands idle while a tile is staged.  A product with few
+// barrier per tile remains and no wave stands idle while a tile is staged.  Every vector-ALU instruction issued on
+// a SIMD takes about four cycles from its matrix core (measured: 4 / 8 / 16 extra v_add per group of four MFMAs
+// lengthen the group by 14 / 26 / 61 cycles; LDS and scalar instructions cost nothing), so a workgroup whose tiles lie
+// wholly inside the operands runs a loop with next to no vector-ALU work: two tiles per pass, so that the LDS set is
+// a constant and every LDS address is one per-lane base plus an immediate; global addresses are a uniform base,
+// advanced on the scalar unit, plus a constant 32-bit offset per thread; no bounds checks, no zero fill (about 20
+// instead of 85 vector-ALU instructions per 64 MFMAs).  Workgroups on a ragged edge take the checked loop.  A product with few
 // output tiles and a long contraction index is cut along that index (blockIdx.y): every piece writes its partial
 // product to the workspace and k_contract_reduce adds the pieces in a fixed order.
 //
 // MFMA operand layout (wave64): A operand lane l = A[m = l % 32][k = l / 32], B operand lane l = B[k = l / 32][n = l % 32],
 // result register r of lane l = D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32].
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "launch.h"
 #include "profile.h"
@@ -53,7 +61,7 @@ __device__ __forceinline__ void tile_of_block(int gm, int gn, int &tm, int &tn) 
 template <bool AT, bool BT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_contract(const float *__restrict__ a, const float *__restrict__ b, float *__restrict__ c, int M, int N, int Kc,
-                int lda, int ldb, int gm, int gn, int chunk) {
+                int lda, int ldb, int gm, int gn, int chunk, int lean_ok) {
     __shared__ __attribute__((aligned(16))) float smem[4 * CT_TILE];   // two sets of (A tile, B tile); reused as the output stage in the epilogue
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -72,96 +80,174 @@ void k_contract(const float *__restrict__ a, const float *__restrict__ b, float 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
     float4c ra[4], rb[4];
-    const float4c zero4 = {0.f, 0.f, 0.f, 0.f};
-    // every dimension is a multiple of 4 (checked on the host): a 16-byte load is inside or outside as a whole
-    auto gload = [&](int k0) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int idx = tid + 256 * p;
-            if (!AT) {
-                const int row = idx >> 3, kq = idx & 7;
-                const int m = m0 + row, k = k0 + 4 * kq;
-                ra[p] = (m < M && k < Kc) ? *reinterpret_cast<const float4c *>(a + (size_t)m * lda + k) : zero4;
-            } else {
-                const int kk = idx >> 5, mq = idx & 31;
-                const int m = m0 + 4 * mq, k = k0 + kk;
-                ra[p] = (m < M && k < Kc) ? *reinterpret_cast<const float4c *>(a + (size_t)k * lda + m) : zero4;
-            }
-            if (BT) {
-                const int row = idx >> 3, kq = idx & 7;
-                const int n = n0 + row, k = k0 + 4 * kq;
-                rb[p] = (n < N && k < Kc) ? *reinterpret_cast<const float4c *>(b + (size_t)n * ldb + k) : zero4;
-            } else {
-                const int kk = idx >> 5, nq = idx & 31;
-                const int n = n0 + 4 * nq, k = k0 + kk;
-                rb[p] = (n < N && k < Kc) ? *reinterpret_cast<const float4c *>(b + (size_t)k * ldb + n) : zero4;
-            }
-        }
-    };
-    auto stage = [&](int set) {
-        float *As = smem + set * (2 * CT_TILE), *Bs = As + CT_TILE;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int idx = tid + 256 * p;
-            if (!AT) {
-                const int row = idx >> 3, kq = idx & 7;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) As[row * CT_LDK + 4 * kq + q] = ra[p][q];
-            } else {
-                const int kk = idx >> 5, mq = idx & 31;
-                *reinterpret_cast<float4c *>(&As[kk * CT_LDM + 4 * mq]) = ra[p];
-            }
-            if (BT) {
-                const int row = idx >> 3, kq = idx & 7;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) Bs[row * CT_LDK + 4 * kq + q] = rb[p][q];
-            } else {
-                const int kk = idx >> 5, nq = idx & 31;
-                *reinterpret_cast<float4c *>(&Bs[kk * CT_LDM + 4 * nq]) = rb[p];
-            }
-        }
-    };
     const int mrow = lane & 31, kof = lane >> 5;
-    auto afrag = [&](int set, int kk, int half) -> float {
-        const float *As = smem + set * (2 * CT_TILE);
-        const int m = wm * 64 + 32 * half + mrow;
-        return AT ? As[(kk + kof) * CT_LDM + m] : As[m * CT_LDK + kk + kof];
-    };
-    auto bfrag = [&](int set, int kk, int half) -> float {
-        const float *Bs = smem + set * (2 * CT_TILE) + CT_TILE;
-        const int n = wn * 64 + 32 * half + mrow;
-        return BT ? Bs[n * CT_LDK + kk + kof] : Bs[(kk + kof) * CT_LDM + n];
-    };
-    gload(kb);
-    stage(0);
-    __syncthreads();
-    if (kb + CT_KT < Kc) gload(kb + CT_KT);
-    int set = 0;
-    for (int k0 = kb; k0 < Kc; k0 += CT_KT, set ^= 1) {
-        // the operands of step ks + 1 are read from LDS before the MFMAs of step ks are issued
-        float a0 = afrag(set, 0, 0), a1 = afrag(set, 0, 1), b0 = bfrag(set, 0, 0), b1 = bfrag(set, 0, 1);
+    // lean_ok (host): the 32-bit byte offsets below cannot overflow
+    if (lean_ok && m0 + 128 <= M && n0 + 128 <= N && (Kc - kb) % CT_KT == 0) {   // the same for the whole workgroup
+        // global: thread -> (row, 4 consecutive k) or (k, 4 consecutive rows); part p adds 32 rows / 8 values of k
+        const unsigned ga = !AT ? (unsigned)(((tid >> 3) * lda + 4 * (tid & 7)) * 4) : (unsigned)(((tid >> 5) * lda + 4 * (tid & 31)) * 4);
+        const unsigned gb = BT ? (unsigned)(((tid >> 3) * ldb + 4 * (tid & 7)) * 4) : (unsigned)(((tid >> 5) * ldb + 4 * (tid & 31)) * 4);
+        const unsigned gpa = (!AT ? 32u : 8u) * (unsigned)lda * 4u, gpb = (BT ? 32u : 8u) * (unsigned)ldb * 4u;
+        const char *pa = reinterpret_cast<const char *>(!AT ? a + (size_t)m0 * lda + kb : a + (size_t)kb * lda + m0);
+        const char *pb = reinterpret_cast<const char *>(BT ? b + (size_t)n0 * ldb + kb : b + (size_t)kb * ldb + n0);
+        const size_t stepa = (!AT ? (size_t)CT_KT : (size_t)CT_KT * lda) * 4, stepb = (BT ? (size_t)CT_KT : (size_t)CT_KT * ldb) * 4;
+        auto gload = [&]() {   // the tile at pa, pb; then on to the next one
 #pragma unroll
-        for (int ks = 0; ks < CT_KT / 2; ++ks) {
-            float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
-            if (ks + 1 < CT_KT / 2) {
-                na0 = afrag(set, 2 * ks + 2, 0);
-                na1 = afrag(set, 2 * ks + 2, 1);
-                nb0 = bfrag(set, 2 * ks + 2, 0);
-                nb1 = bfrag(set, 2 * ks + 2, 1);
+            for (int p = 0; p < 4; ++p) {
+                ra[p] = *reinterpret_cast<const float4c *>(pa + (ga + p * gpa));
+                rb[p] = *reinterpret_cast<const float4c *>(pb + (gb + p * gpb));
             }
-            // between MFMA groups: tile t + 1 goes from the registers to the other set (nobody reads that set any
-            // more: the barrier at the end of tile t - 1), then the loads of tile t + 2 go out
-            if (ks == 1 && k0 + CT_KT < Kc) stage(set ^ 1);
-            if (ks == 3 && k0 + 2 * CT_KT < Kc) gload(k0 + 2 * CT_KT);
-            __builtin_amdgcn_sched_barrier(0);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
-        }
+            pa += stepa;
+            pb += stepb;
+        };
+        // LDS: one base per lane for the writes of each operand and one for its reads
+        const int wa = !AT ? (tid >> 3) * CT_LDK + 4 * (tid & 7) : (tid >> 5) * CT_LDM + 4 * (tid & 31);
+        const int wb = CT_TILE + (BT ? (tid >> 3) * CT_LDK + 4 * (tid & 7) : (tid >> 5) * CT_LDM + 4 * (tid & 31));
+        const int rda = !AT ? (wm * 64 + mrow) * CT_LDK + kof : kof * CT_LDM + wm * 64 + mrow;
+        const int rdb = CT_TILE + (BT ? (wn * 64 + mrow) * CT_LDK + kof : kof * CT_LDM + wn * 64 + mrow);
+        auto stage = [&](auto SET) {
+            constexpr int so = decltype(SET)::value * 2 * CT_TILE;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                if (!AT) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) smem[wa + so + p * 32 * CT_LDK + q] = ra[p][q];
+                } else {
+                    *reinterpret_cast<float4c *>(&smem[wa + so + p * 8 * CT_LDM]) = ra[p];
+                }
+                if (BT) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) smem[wb + so + p * 32 * CT_LDK + q] = rb[p][q];
+                } else {
+                    *reinterpret_cast<float4c *>(&smem[wb + so + p * 8 * CT_LDM]) = rb[p];
+                }
+            }
+        };
+        auto tile = [&](auto SET, bool more1, bool more2) {
+            constexpr int set = decltype(SET)::value, so = set * 2 * CT_TILE;
+            auto afrag = [&](int kk, int half) -> float { return smem[rda + so + (!AT ? 32 * half * CT_LDK + kk : kk * CT_LDM + 32 * half)]; };
+            auto bfrag = [&](int kk, int half) -> float { return smem[rdb + so + (BT ? 32 * half * CT_LDK + kk : kk * CT_LDM + 32 * half)]; };
+            float a0 = afrag(0, 0), a1 = afrag(0, 1), b0 = bfrag(0, 0), b1 = bfrag(0, 1);
+#pragma unroll
+            for (int ks = 0; ks < CT_KT / 2; ++ks) {
+                float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+                if (ks + 1 < CT_KT / 2) {
+                    na0 = afrag(2 * ks + 2, 0);
+                    na1 = afrag(2 * ks + 2, 1);
+                    nb0 = bfrag(2 * ks + 2, 0);
+                    nb1 = bfrag(2 * ks + 2, 1);
+                }
+                if (ks == 1 && more1) stage(std::integral_constant<int, set ^ 1>{});
+                if (ks == 3 && more2) gload();
+                __builtin_amdgcn_sched_barrier(0);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+            }
+            __syncthreads();
+        };
+        const int nt = (Kc - kb) / CT_KT;   // >= 1: no piece is empty
+        gload();
+        stage(std::integral_constant<int, 0>{});
         __syncthreads();
+        if (nt > 1) gload();
+        for (int t = 0; t < nt; t += 2) {
+            tile(std::integral_constant<int, 0>{}, t + 1 < nt, t + 2 < nt);
+            if (t + 1 < nt) tile(std::integral_constant<int, 1>{}, t + 2 < nt, t + 3 < nt);
+        }
+    } else {
+        const float4c zero4 = {0.f, 0.f, 0.f, 0.f};
+        // every dimension is a multiple of 4 (checked on the host): a 16-byte load is inside or outside as a whole
+        auto gload = [&](int k0) {
+    #pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int idx = tid + 256 * p;
+                if (!AT) {
+                    const int row = idx >> 3, kq = idx & 7;
+                    const int m = m0 + row, k = k0 + 4 * kq;
+                    ra[p] = (m < M && k < Kc) ? *reinterpret_cast<const float4c *>(a + (size_t)m * lda + k) : zero4;
+                } else {
+                    const int kk = idx >> 5, mq = idx & 31;
+                    const int m = m0 + 4 * mq, k = k0 + kk;
+                    ra[p] = (m < M && k < Kc) ? *reinterpret_cast<const float4c *>(a + (size_t)k * lda + m) : zero4;
+                }
+                if (BT) {
+                    const int row = idx >> 3, kq = idx & 7;
+                    const int n = n0 + row, k = k0 + 4 * kq;
+                    rb[p] = (n < N && k < Kc) ? *reinterpret_cast<const float4c *>(b + (size_t)n * ldb + k) : zero4;
+                } else {
+                    const int kk = idx >> 5, nq = idx & 31;
+                    const int n = n0 + 4 * nq, k = k0 + kk;
+                    rb[p] = (n < N && k < Kc) ? *reinterpret_cast<const float4c *>(b + (size_t)k * ldb + n) : zero4;
+                }
+            }
+        };
+        auto stage = [&](int set) {
+            float *As = smem + set * (2 * CT_TILE), *Bs = As + CT_TILE;
+    #pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int idx = tid + 256 * p;
+                if (!AT) {
+                    const int row = idx >> 3, kq = idx & 7;
+    #pragma unroll
+                    for (int q = 0; q < 4; ++q) As[row * CT_LDK + 4 * kq + q] = ra[p][q];
+                } else {
+                    const int kk = idx >> 5, mq = idx & 31;
+                    *reinterpret_cast<float4c *>(&As[kk * CT_LDM + 4 * mq]) = ra[p];
+                }
+                if (BT) {
+                    const int row = idx >> 3, kq = idx & 7;
+    #pragma unroll
+                    for (int q = 0; q < 4; ++q) Bs[row * CT_LDK + 4 * kq + q] = rb[p][q];
+                } else {
+                    const int kk = idx >> 5, nq = idx & 31;
+                    *reinterpret_cast<float4c *>(&Bs[kk * CT_LDM + 4 * nq]) = rb[p];
+                }
+            }
+        };
+        auto afrag = [&](int set, int kk, int half) -> float {
+            const float *As = smem + set * (2 * CT_TILE);
+            const int m = wm * 64 + 32 * half + mrow;
+            return AT ? As[(kk + kof) * CT_LDM + m] : As[m * CT_LDK + kk + kof];
+        };
+        auto bfrag = [&](int set, int kk, int half) -> float {
+            const float *Bs = smem + set * (2 * CT_TILE) + CT_TILE;
+            const int n = wn * 64 + 32 * half + mrow;
+            return BT ? Bs[n * CT_LDK + kk + kof] : Bs[(kk + kof) * CT_LDM + n];
+        };
+        gload(kb);
+        stage(0);
+        __syncthreads();
+        if (kb + CT_KT < Kc) gload(kb + CT_KT);
+        int set = 0;
+        for (int k0 = kb; k0 < Kc; k0 += CT_KT, set ^= 1) {
+            // the operands of step ks + 1 are read from LDS before the MFMAs of step ks are issued
+            float a0 = afrag(set, 0, 0), a1 = afrag(set, 0, 1), b0 = bfrag(set, 0, 0), b1 = bfrag(set, 0, 1);
+    #pragma unroll
+            for (int ks = 0; ks < CT_KT / 2; ++ks) {
+                float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+                if (ks + 1 < CT_KT / 2) {
+                    na0 = afrag(set, 2 * ks + 2, 0);
+                    na1 = afrag(set, 2 * ks + 2, 1);
+                    nb0 = bfrag(set, 2 * ks + 2, 0);
+                    nb1 = bfrag(set, 2 * ks + 2, 1);
+                }
+                // between MFMA groups: tile t + 1 goes from the registers to the other set (nobody reads that set any
+                // more: the barrier at the end of tile t - 1), then the loads of tile t + 2 go out
+                if (ks == 1 && k0 + CT_KT < Kc) stage(set ^ 1);
+                if (ks == 3 && k0 + 2 * CT_KT < Kc) gload(k0 + 2 * CT_KT);
+                __builtin_amdgcn_sched_barrier(0);
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                a0 = na0; a1 = na1; b0 = nb0; b1 = nb1;
+            }
+            __syncthreads();
+        }
     }
     // epilogue: each wave stages 32 x 64 results at a time in its own quarter of the tile memory (32 rows of 66
     // floats) and writes them as 16-byte stores, 256 bytes per row.  The last barrier of the loop guarantees that
@@ -207,15 +293,17 @@ static int launch_gemm(const GemmDesc &g, const float *a, const float *b, float 
     const int chunk = pieces > 1 ? ((g.Kc + pieces - 1) / pieces + CT_KT - 1) / CT_KT * CT_KT : g.Kc;
     const int used = pieces > 1 ? (g.Kc + chunk - 1) / chunk : 1;
     const dim3 grid(gm * gn, used), block(256);
+    // the lean loop addresses a tile's rows with 32-bit byte offsets
+    const int lean_ok = (long long)g.lda * 128 * 4 < (1ll << 31) && (long long)g.ldb * 128 * 4 < (1ll << 31) ? 1 : 0;
     float *dst = used > 1 ? ws : c;
     if (!g.at && !g.bt)
-        TAD_LAUNCH("k_contract", (k_contract<false, false>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
+        TAD_LAUNCH("k_contract", (k_contract<false, false>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk, lean_ok);
     else if (!g.at && g.bt)
-        TAD_LAUNCH("k_contract", (k_contract<false, true>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
+        TAD_LAUNCH("k_contract", (k_contract<false, true>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk, lean_ok);
     else if (g.at && !g.bt)
-        TAD_LAUNCH("k_contract", (k_contract<true, false>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
+        TAD_LAUNCH("k_contract", (k_contract<true, false>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk, lean_ok);
     else
-        TAD_LAUNCH("k_contract", (k_contract<true, true>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk);
+        TAD_LAUNCH("k_contract", (k_contract<true, true>), grid, block, 0, s, a, b, dst, g.M, g.N, g.Kc, g.lda, g.ldb, gm, gn, chunk, lean_ok);
     if (hipGetLastError() != hipSuccess) return TAD_EDEVICE;
     if (used > 1) {
         const long long n4 = (long long)g.M * g.N / 4;

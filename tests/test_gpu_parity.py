@@ -493,6 +493,21 @@ def test_contraction_family_all_memory_orders(xt, yt, sw):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("xt,yt,sw", CONTRACTIONS)
+@pytest.mark.parametrize("I,J,K", [(260, 384, 160), (288, 260, 256)])
+def test_contraction_whole_tiles_beside_ragged_ones(I, J, K, xt, yt, sw):
+    """Shapes where some workgroups own tiles wholly inside the operands (they run the loop without bounds checks, an
+    odd and an even number of contraction tiles) and others a ragged edge, in the product and in one derived
+    product each, every storage order."""
+    e = wl.matmul_expr(I, J, K, "f32", xt, yt, sw)
+    w = wl.random_inputs(e, 29)
+    f_ref, g_ref = oracle_all(w, 8)
+    plan, f, grads = run_gpu(w)
+    assert plan.forward_family == "contraction"
+    assert_parity(w, f, grads, f_ref, g_ref)
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("I,J,K,xt,yt", [(128, 256, 4096, False, False), (64, 68, 8192, True, False),
                                           (132, 60, 2100, False, True), (4096, 64, 96, False, False)])
 def test_contraction_with_a_split_summation_index(I, J, K, xt, yt):
