@@ -270,6 +270,27 @@ def run_cpu_oracle(name):
     return out
 
 
+def vendor_product(torch):
+    """torch.mm in fp32 on random normal operands, HIP events around 50 calls after 10 warm-up calls."""
+    torch.backends.cuda.matmul.allow_tf32 = False
+    for m, n, k in ((4096, 4096, 4096), (4096, 4096, 256), (4096, 256, 4096)):
+        x = torch.randn(m, k, device="cuda:0")
+        y = torch.randn(k, n, device="cuda:0")
+        out = torch.empty(m, n, device="cuda:0")
+        for _ in range(10):
+            torch.mm(x, y, out=out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(50):
+            torch.mm(x, y, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 50 * 1e3
+        print(json.dumps({"vendor_product": "torch.mm fp32", "shape_mnk": [m, n, k], "us": us,
+                          "tflops": 2.0 * m * n * k / us / 1e6, "frac_of_mfma_peak": 2.0 * m * n * k / us / 1e6 / FP32_MFMA_TFLOPS}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -283,6 +304,9 @@ def main():
                          "For looking at one gradient's kernels alone; the accounting of elements stays that of the whole step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (reference point for HBM byte counters)")
+    ap.add_argument("--vendor-product", action="store_true",
+                    help="instead of a workload, time torch.mm (the vendor's fp32 product) at the shapes of the matmul "
+                         "workload and of cfg4's three contractions: a yardstick for the matrix-core kernels, one line each")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this library runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -293,6 +317,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
 
+    if a.vendor_product:
+        vendor_product(torch)
+        return
     if a.calibrate_copy:
         src = torch.empty(64 << 20, dtype=torch.float32, device="cuda:0").normal_()
         dst = torch.empty_like(src)
