@@ -151,9 +151,12 @@ __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const
     if (!gather_element_index(P, idx, lin, y)) return false;
     double acc = 0.0;
     gather_loops(P, y, part, parts, [&](const int32_t *z, int32_t n, int32_t step) {
-        // innermost run: offsets advance by a constant per step.  Four terms are loaded before the first is used,
-        // so that the loop waits for memory once per four terms (the terms are still added in ascending order;
-        // the slots past the end of the run reload its current term and are dropped).  U = 1: the plain loop.
+        // innermost run: offsets advance by a constant per term.  Whole batches of U terms are loaded before the
+        // first of them is used, so that the loop waits for memory once per batch (U = 8 for the long runs of the
+        // cooperative layouts: 4 and 16 measured slower); their offsets come from running 64-bit additions, no
+        // multiplications and no predicates; what is left of the run goes one term at a time.  The terms are added
+        // in ascending order.  An operand whose index does not move along the run (a_ik summed over j, ...) is
+        // loaded once per run.
         int64_t off[NA + 1], stp[NA + 1];
         for (int q = 0; q < NA; ++q) {
             off[q] = gather_offset(P, q, y, z);
@@ -161,19 +164,48 @@ __device__ __forceinline__ bool gather_element(const GatherPlan &P, int p, const
         }
         off[NA] = gather_offset(P, kSlotF, y, z);
         stp[NA] = P.offZ[kSlotF][0] * step;
-        for (int32_t it = 0; it < n; it += U) {
+        T still[NA];
+        for (int q = 0; q < NA; ++q) still[q] = stp[q] == 0 && n > 0 ? static_cast<const T *>(A.p[q])[off[q]] : T(0);
+        int32_t it = 0;
+        for (; it + U <= n; it += U) {
             T v[U][NA], fv[U], dfv[U];
+            for (int q = 0; q < NA; ++q) {
+                if (stp[q] == 0) {   // the same for the whole wavefront
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t m = it + u < n ? u : 0;
-                for (int q = 0; q < NA; ++q) v[u][q] = static_cast<const T *>(A.p[q])[off[q] + m * stp[q]];
-                fv[u] = f[off[NA] + m * stp[NA]];
-                dfv[u] = df[off[NA] + m * stp[NA]];
+                    for (int u = 0; u < U; ++u) v[u][q] = still[q];
+                } else {
+                    int64_t o = off[q];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        v[u][q] = static_cast<const T *>(A.p[q])[o];
+                        o += stp[q];
+                    }
+                    off[q] = o;
+                }
+            }
+            {
+                int64_t o = off[NA];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    fv[u] = f[o];
+                    dfv[u] = df[o];
+                    o += stp[NA];
+                }
+                off[NA] = o;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (it + u < n) acc += (double)(dfv[u] * body_douter<BODY, T>(fv[u], v[u]) * body_dinner<BODY, T>(p, v[u]));
-            for (int q = 0; q <= NA; ++q) off[q] += U * stp[q];
+                acc += (double)(dfv[u] * body_douter<BODY, T>(fv[u], v[u]) * body_dinner<BODY, T>(p, v[u]));
+        }
+        for (; it < n; ++it) {
+            T v[NA];
+            for (int q = 0; q < NA; ++q) {
+                v[q] = stp[q] == 0 ? still[q] : static_cast<const T *>(A.p[q])[off[q]];
+                off[q] += stp[q];
+            }
+            const T fv = f[off[NA]], dfv = df[off[NA]];
+            off[NA] += stp[NA];
+            acc += (double)(dfv * body_douter<BODY, T>(fv, v) * body_dinner<BODY, T>(p, v));
         }
     }, group, groups);
     *sum = acc;
@@ -225,10 +257,18 @@ __global__ __launch_bounds__(256) void k_generic_gather_coop(const GatherPlan P,
                                                              double *__restrict__ partial, int32_t *__restrict__ live_out) {
     // gridDim.y blocks share an element (partial != null then): block b takes the parts b * 256 ... of 256 gridDim.y
     __shared__ double red[4];
-    const int idx = blockIdx.x;
+    // The accelerator dies take workgroups in turn, each with an L2 of its own.  Neighbouring elements often sum
+    // over the same part of f (da_ik for k = 0 .. K-1: the same row; dd_m, dd_m+1: K-1 rows in common), so every
+    // die gets a contiguous range of elements and neighbours run side by side on one die instead of fetching
+    // that part once per die.
+    int idx = blockIdx.x;
+    if (gridDim.y == 1) {
+        const int per_die = gridDim.x >> 3;
+        if (idx < (per_die << 3)) idx = (idx & 7) * per_die + (idx >> 3);
+    }
     double acc;
     int lin;
-    const bool live = gather_element<BODY, T>(P, p, A, f, df, idx, &lin, threadIdx.x, 256, &acc,
+    const bool live = gather_element<BODY, T, 8>(P, p, A, f, df, idx, &lin, threadIdx.x, 256, &acc,
                                               (int)blockIdx.y, (int)gridDim.y);   // uniform over the block
     const double total = block_sum_256(acc, red);
     if (threadIdx.x != 0) return;
@@ -247,7 +287,7 @@ __global__ __launch_bounds__(256) void k_generic_gather_lanes(const GatherPlan P
     if (idx >= n) return;
     double acc;
     int lin;
-    const bool live = gather_element<BODY, T>(P, p, A, f, df, idx, &lin, 0, 1, &acc, (int)blockIdx.y, (int)gridDim.y);
+    const bool live = gather_element<BODY, T, 8>(P, p, A, f, df, idx, &lin, 0, 1, &acc, (int)blockIdx.y, (int)gridDim.y);
     if (partial) store_partial(partial, live_out, idx, lin, live, acc);
     else store_element(dx, lin, live, acc, accumulate);
 }
