@@ -37,30 +37,49 @@ __device__ __forceinline__ double forward_sum(const ForwardPlan &P, const ArgPtr
     const int32_t n_last = last >= 0 ? P.sum_n[last] : 1;
     if (P.n_cons == 0 && last >= 0 && (parts == 1 || last == 0 || n_last >= parts)) {
         // no extra conditions: the last summation index is a run of terms a constant stride apart; cooperating
-        // threads take its terms in turn.  Four terms are loaded before the first is used (one wait for memory per
-        // four terms; added in ascending order; slots past the end of the run reload its current term and are dropped).
+        // threads take its terms in turn.  Whole batches of four terms are loaded before the first is used (one wait
+        // for memory per batch, pointers advanced by additions, no predicates), the rest of the run goes one term at
+        // a time; added in ascending order.  An operand that does not move along the run is loaded once per run.
         constexpr int U = 4;
         int64_t stp[NA];
         for (int p = 0; p < NA; ++p) stp[p] = P.off[p][P.n_f + last] * parts;
         const int32_t mine = part < n_last ? (n_last - part + parts - 1) / parts : 0;
         for (;;) {
             const T *ptr[NA];
+            T still[NA];
             for (int p = 0; p < NA; ++p) {
                 int64_t o = base[p] + P.off[p][P.n_f + last] * (int64_t)part;
                 for (int sidx = 0; sidx < last; ++sidx) o += P.off[p][P.n_f + sidx] * (int64_t)k[sidx];
                 ptr[p] = static_cast<const T *>(A.p[p]) + o;
+                still[p] = stp[p] == 0 && mine > 0 ? *ptr[p] : T(0);
             }
-            for (int32_t it = 0; it < mine; it += U) {
+            int32_t it = 0;
+            for (; it + U <= mine; it += U) {
                 T v[U][NA];
+                for (int p = 0; p < NA; ++p) {
+                    if (stp[p] == 0) {   // the same for the whole wavefront
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t m = it + u < mine ? u : 0;
-                    for (int p = 0; p < NA; ++p) v[u][p] = ptr[p][m * stp[p]];
+                        for (int u = 0; u < U; ++u) v[u][p] = still[p];
+                    } else {
+                        const T *q = ptr[p];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            v[u][p] = *q;
+                            q += stp[p];
+                        }
+                        ptr[p] = q;
+                    }
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (it + u < mine) acc += (double)body_inner<BODY, T>(v[u]);
-                for (int p = 0; p < NA; ++p) ptr[p] += U * stp[p];
+                for (int u = 0; u < U; ++u) acc += (double)body_inner<BODY, T>(v[u]);
+            }
+            for (; it < mine; ++it) {
+                T v[NA];
+                for (int p = 0; p < NA; ++p) {
+                    v[p] = stp[p] == 0 ? still[p] : *ptr[p];
+                    ptr[p] += stp[p];
+                }
+                acc += (double)body_inner<BODY, T>(v);
             }
             int sidx = last - 1;
             for (; sidx >= 0; --sidx) {
