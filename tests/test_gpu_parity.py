@@ -338,6 +338,18 @@ def test_full_size_config3():
     _full(wl.config3())
 
 
+@pytest.mark.parametrize("make", [lambda: wl.config2(1), lambda: wl.config2(3), lambda: wl.config5(), lambda: wl.config3()],
+                         ids=["cfg2_1", "cfg2_3", "cfg5", "cfg3"])
+def test_full_size_on_the_plan_driven_kernels(make):
+    """The same workloads with the specialised families switched off: the cooperative layouts (every die a range of
+    elements of its own, batches of terms, operands that stand still along a run) at the sizes they are meant for."""
+    w = make()
+    f_ref, g_ref = oracle_all(w, 16)
+    plan, f, grads = run_gpu(w, generic_only=True)
+    assert plan.forward_family == "generic"
+    assert_parity(w, f, grads, f_ref, g_ref, "full, generic")
+
+
 def test_full_size_config4():
     """4096 x 4096 x 256 in the benchmark's launch configuration (matrix-core family, the collapsed indices split
     over 8 chunks of workgroups): every element of f, da, db, dc and dd against the oracle, which visits all
