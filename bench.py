@@ -19,6 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+GRAPH_WORKLOADS = ("cfg1", "cfg5")   # steps of a few short launches: also timed as replays of a captured graph
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VALU_TFLOPS = 157.3       # published vector fp32 peak (packed); 256 CUs x 2.4 GHz x 256 flop/clk
 FP32_MFMA_TFLOPS = 157.3
@@ -179,6 +180,29 @@ def run_gpu(name, steps, warmup, rotate_bytes=0, min_window_ms=0.0, grads=None):
     torch.cuda.synchronize()
     ms_step = (t1 - t0) * 1e3 / steps
     extra = {}
+    if name in GRAPH_WORKLOADS:
+        # launch-bound workloads: the same steps captured once per buffer set into a HIP graph and replayed (both
+        # evaluation calls only enqueue kernels), which is how a caller with steps this short would issue them
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graphs = []
+        for i in range(len(sets)):
+            with torch.cuda.stream(side):
+                step(i)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                step(i)
+            graphs.append(g)
+        for k in range(WARM_PASSES * len(graphs)):
+            graphs[k % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for k in range(steps):
+            graphs[k % len(graphs)].replay()
+        torch.cuda.synchronize()
+        extra["ms_per_step_graph_replay"] = (time.perf_counter() - t2) * 1e3 / steps
+        del graphs
     if name == "cfg4":
         # the same forward pass in the direct form on the vector ALUs, for comparison with the expanded form on MFMA
         pd = B.Plan(w.expr, direct_form=True)
@@ -343,6 +367,7 @@ def main():
                    "buffer_sets": r["buffer_sets"], "gradients": "all" if only is None else only},
         "roofline": roofline(r),
     }
+    out["config"].update(r["extra"])
     if not a.no_others:
         per = {}
         for name in ("cfg1", "cfg2_1", "cfg2_2", "cfg2_3", "cfg4", "cfg5", "matmul"):

@@ -149,6 +149,12 @@ typedef struct {
                                     same operands; sums and products in either order, x * x for x^2) is normally planned
                                     as that body; with this flag it stays a program and runs on the interpreter kernels */
 
+#define TAD_PLAN_NO_TERM_LISTS 8u /* a small expression (at most 1024 gradient elements and 1024 extended indices per
+                                     gradient set in all, built-in body, plan-driven kernels) normally has the sets
+                                     Gamma-hat(beta) of Sec. 5.1 that its ranges enumerate written out at plan time, and
+                                     the device sums the listed terms; with this flag the device walks the ranges itself,
+                                     as it does for every larger expression */
+
 typedef struct tad_plan tad_plan; /* opaque, immutable after derivation, may be shared between threads */
 
 /* What the derivation found for one argument (Sec. 4.1 quantities, host memory, row-major). */
@@ -178,6 +184,8 @@ typedef struct {
                                                        divisibility masks leave mostly zero -- only the box of the
                                                        transformed index y whose images beta = U^-1 [alpha y ; 0] are
                                                        the elements that pass those masks (Sec. 4.1) */
+    int32_t listed;                                 /* 1: the terms of every element were listed at plan time (small
+                                                       expression, see TAD_PLAN_NO_TERM_LISTS) */
 } tad_plan_info;
 
 typedef enum {

@@ -27,6 +27,7 @@ FAMILY = {0: "generic", 1: "row_reduce", 2: "diagonal", 3: "antidiagonal", 4: "w
 PLAN_GENERIC_ONLY = 1
 PLAN_DIRECT_FORM = 2
 PLAN_KEEP_PROGRAM = 4
+PLAN_NO_TERM_LISTS = 8
 ROWS_LOWER, ROWS_UPPER, ROWS_FEASIBILITY = 0, 1, 2
 
 EXPORTS = ["tad_plan_derive", "tad_plan_free", "tad_plan_workspace_bytes", "tad_plan_query",
@@ -66,7 +67,7 @@ class TadPlanInfo(ctypes.Structure):
                 ("n_lower", ctypes.c_int32 * MAX_KERNEL), ("n_upper", ctypes.c_int32 * MAX_KERNEL),
                 ("n_feasibility", ctypes.c_int32), ("family", ctypes.c_int32), ("in_outer", ctypes.c_int32),
                 ("gather_layout", ctypes.c_int32), ("gather_splits", ctypes.c_int32),
-                ("gather_elements", ctypes.c_int64)]
+                ("gather_elements", ctypes.c_int64), ("listed", ctypes.c_int32)]
 
 
 class TadError(RuntimeError):
@@ -186,7 +187,7 @@ class Plan:
     """Owner of one ``tad_plan``."""
 
     def __init__(self, expr, needs_grad: Optional[Sequence[bool]] = None, generic_only: bool = False,
-                 direct_form: bool = False, keep_program: bool = False):
+                 direct_form: bool = False, keep_program: bool = False, term_lists: bool = True):
         self.expr = expr
         self.n_ext = len(expr.f_shape) + len(expr.sums)
         if self.n_ext > MAX_EXT or len(expr.args) > MAX_ARGS:
@@ -197,7 +198,7 @@ class Plan:
         self._h = ctypes.c_void_p(None)
         e, a = pack_expr(expr), pack_args(expr, needs_grad)
         flags = (PLAN_GENERIC_ONLY if generic_only else 0) | (PLAN_DIRECT_FORM if direct_form else 0) | \
-            (PLAN_KEEP_PROGRAM if keep_program else 0)
+            (PLAN_KEEP_PROGRAM if keep_program else 0) | (0 if term_lists else PLAN_NO_TERM_LISTS)
         _check(lib.tad_plan_derive(ctypes.byref(e), a, len(expr.args), self.dtype, flags,
                                    ctypes.byref(self._h)), "tad_plan_derive")
 
@@ -227,7 +228,7 @@ class Plan:
                     n_upper=[info.n_upper[k] for k in range(kap)],
                     n_feasibility=info.n_feasibility, family=FAMILY[info.family], in_outer=bool(info.in_outer),
                     gather_layout=("threads", "blocks", "lanes")[info.gather_layout], gather_splits=info.gather_splits,
-                    gather_elements=info.gather_elements)
+                    gather_elements=info.gather_elements, listed=bool(info.listed))
 
     def bound_rows(self, arg: int, kind: int, level: int = 0) -> List[dict]:
         q = self.query(arg)

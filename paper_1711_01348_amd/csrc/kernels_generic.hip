@@ -367,6 +367,33 @@ __global__ __launch_bounds__(64) void k_generic_gather_multi(const MultiGather M
     store_element(static_cast<T *>(M.dx[g]), lin, live, acc, 0);
 }
 
+// Small expressions whose terms were listed at plan time: one workgroup, a single wavefront, per gradient element;
+// lane l adds the terms l, l + 64, ... of the element's list and the lane sums are added in a fixed order.  An
+// element without terms (masked out, or never referenced) is stored as zero.
+struct ListedOut {
+    void *dx[kMaxArgs];   // per gradient of the list; null: not wanted
+};
+template <int BODY, typename T>
+__global__ __launch_bounds__(64) void k_generic_gather_listed(const TermList L, const ListedOut O, const ArgPtrs A,
+                                                              const T *__restrict__ f, const T *__restrict__ df) {
+    constexpr int NA = BodyTraits<BODY>::NA;
+    const int e = blockIdx.x;
+    int g = 0;
+    while (g + 1 < L.n_grad && e >= L.first_element[g + 1]) ++g;   // the same for the whole workgroup
+    T *const dx = static_cast<T *>(O.dx[g]);
+    if (!dx) return;
+    const int p = L.operand[g];
+    double acc = 0.0;
+    for (int t = L.first_term[e] + (int)threadIdx.x; t < (int)L.first_term[e + 1]; t += 64) {
+        T v[NA];
+        for (int q = 0; q < NA; ++q) v[q] = static_cast<const T *>(A.p[q])[L.off[t][q]];
+        const int of = L.off[t][kListSlots - 1];
+        acc += (double)(df[of] * body_douter<BODY, T>(f[of], v) * body_dinner<BODY, T>(p, v));
+    }
+    const double total = wave_sum_all(acc);
+    if (threadIdx.x == 0) dx[e - L.first_element[g]] = (T)total;
+}
+
 template <int BODY, typename T>
 static int launch_body(const tad_plan &pl, const void *const *args, const void *f, const void *df,
                        void *const *dx, void *fout, void *ws, hipStream_t s) {
@@ -388,6 +415,22 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
         } else
             TAD_LAUNCH("k_generic_forward", (k_generic_forward<BODY, T>), dim3((nf + 255) / 256), dim3(256), 0, s, pl.fwd,
                        A, static_cast<T *>(fout), nf);
+        return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
+    }
+    // a small expression with its terms listed at plan time: one launch for all its gradients
+    if (!pl.term_list.empty()) {
+        const TermList &L = pl.term_list[0];
+        ListedOut O{};
+        for (size_t q = 0; q < pl.args.size(); ++q)
+            if (dx[q] && !pl.ap[q].derived) return TAD_EINVAL;
+        bool any = false;
+        for (int g = 0; g < L.n_grad; ++g) {
+            O.dx[g] = dx[L.operand[g]];
+            any = any || O.dx[g];
+        }
+        if (!any) return TAD_OK;
+        TAD_LAUNCH("k_generic_gather_listed", (k_generic_gather_listed<BODY, T>), dim3((unsigned)L.first_element[L.n_grad]),
+                   dim3(64), 0, s, L, O, A, static_cast<const T *>(f), static_cast<const T *>(df));
         return hipGetLastError() == hipSuccess ? TAD_OK : TAD_EDEVICE;
     }
     // an expression without aliases whose gradients are all small tensors with short sums: one launch for all

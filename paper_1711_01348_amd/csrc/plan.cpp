@@ -362,6 +362,8 @@ static int derive_arg_outer(const tad_plan &pl, int p, ArgPlan &ap) {
     return TAD_OK;
 }
 
+static void list_terms(tad_plan &pl);
+
 int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype dt, uint32_t flags,
                 tad_plan **out) {
     if (!expr || !args || !out) return TAD_EINVAL;
@@ -511,10 +513,14 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
         }
     }
     select_families(*pl);
+    list_terms(*pl);
     guard.p = nullptr;
     *out = pl;
     return TAD_OK;
 }
+
+template <class Fn>
+static void visit_beta(int n_ext, const ArgPlan &ap, const int32_t *beta, Fn &&fn);
 
 // Visit every extended index of the element with transformed index y through the ranges and the maps V_R y + K z.
 template <class Fn>
@@ -551,6 +557,57 @@ static void visit_beta(int n_ext, const ArgPlan &ap, const int32_t *beta, Fn &&f
     int32_t y[kMaxRank] = {0};
     if (!gather_prepare(ap.dev, beta, y)) return;
     visit_y(n_ext, ap, y, fn);
+}
+
+// Small expressions on the plan-driven kernels: write out, per gradient element, the extended indices that the
+// plan's masks and ranges enumerate (exactly what the device would walk), as offsets into the tensors.
+static void list_terms(tad_plan &pl) {
+    if ((pl.flags & TAD_PLAN_NO_TERM_LISTS) || pl.expr.body == TAD_BODY_PROGRAM || pl.has_alias) return;
+    const int n_args = (int)pl.args.size();
+    if (n_args > kListSlots - 1) return;
+    long long elements = 0;
+    int n_grad = 0;
+    for (int q = 0; q < n_args; ++q) {
+        if (!pl.ap[q].derived) continue;
+        if (pl.ap[q].family != TAD_FAMILY_GENERIC) return;
+        elements += pl.arg_count[q];
+        ++n_grad;
+    }
+    if (n_grad == 0 || elements > kListElements || pl.terms_total * n_grad > (double)kListTerms) return;
+    TermList L{};
+    int e = 0, t = 0;
+    bool fits = true;
+    for (int q = 0; q < n_args && fits; ++q) {
+        if (!pl.ap[q].derived) continue;
+        const int g = L.n_grad++;
+        L.first_element[g] = e;
+        L.operand[g] = q;
+        const tad_arg &a = pl.args[q];
+        for (int64_t lin = 0; lin < pl.arg_count[q] && fits; ++lin, ++e) {
+            int32_t beta[kMaxRank] = {0};
+            int64_t r = lin;
+            for (int d = a.rank - 1; d >= 0; --d) { beta[d] = (int32_t)(r % a.shape[d]); r /= a.shape[d]; }
+            L.first_term[e] = (uint16_t)t;
+            visit_beta(pl.n_ext, pl.ap[q], beta, [&](const int64_t *ext) {
+                if (t >= kListTerms) { fits = false; return; }
+                for (int s = 0; s < n_args; ++s) {
+                    int64_t o = 0;
+                    for (int d = 0; d < pl.n_ext; ++d) o += pl.fwd.off[s][d] * ext[d];
+                    if (o < 0 || o > INT32_MAX) fits = false;
+                    L.off[t][s] = (int32_t)o;
+                }
+                int64_t of = 0;
+                for (int d = 0; d < pl.expr.n_f; ++d) of = of * pl.expr.f_shape[d] + ext[d];
+                if (of < 0 || of > INT32_MAX) fits = false;
+                L.off[t][kListSlots - 1] = (int32_t)of;
+                ++t;
+            });
+        }
+    }
+    if (!fits) return;
+    for (int g = L.n_grad; g <= kMaxArgs; ++g) L.first_element[g] = e;
+    for (int x = e; x <= kListElements; ++x) L.first_term[x] = (uint16_t)t;
+    pl.term_list.push_back(L);
 }
 
 // plan of occurrence `occ` of the tensor given as operand `arg` (0: the operand itself, k: its k-th alias)
@@ -622,6 +679,7 @@ int tad_plan_query(const tad_plan *plan, int arg, int occ, tad_plan_info *out) {
         out->gather_splits = shape.splits;
         out->gather_elements = gather_launch_count(ap->dev, plan->arg_count[(size_t)plan->root[slot]]);
     }
+    out->listed = plan->term_list.empty() ? 0 : 1;
     return TAD_OK;
 }
 

@@ -69,6 +69,7 @@ struct tad_plan {
     int fwd_family = TAD_FAMILY_GENERIC;
     tad::FastParams fast;
     tad::ProgramBody prog;                     // TAD_BODY_PROGRAM only
+    std::vector<tad::TermList> term_list;      // one entry if the terms of every gradient element are listed (small expressions)
     size_t ws_bytes = 0;
     size_t split_ws_offset = 0;                // fallback kernels: where the partial sums of shared elements start
 };

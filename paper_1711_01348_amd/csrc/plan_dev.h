@@ -105,6 +105,21 @@ inline GatherShape gather_shape(const GatherPlan &P, long long n_elements, doubl
     return g;
 }
 
+// Small expressions: the extended indices of every gradient element, which the ranges of the plan enumerate
+// (the sets Gamma-hat(beta) of Sec. 5.1), written out on the host as element offsets into the tensors.  A launch
+// over a few dozen elements with a handful of terms each is as long as the code it walks through, not as its
+// arithmetic: with the terms listed that path is a few dozen instructions.
+constexpr int kListElements = 1024;   // gradient elements of all operands together
+constexpr int kListTerms = 1024;      // terms of all of them together
+constexpr int kListSlots = 5;         // offsets per term: up to four operands, then f (and df)
+struct TermList {
+    int32_t n_grad;
+    int32_t first_element[kMaxArgs + 1];   // gradient g owns the element numbers first_element[g] .. first_element[g + 1] - 1
+    int32_t operand[kMaxArgs];             // whose gradient g is
+    uint16_t first_term[kListElements + 1];   // element e sums the terms first_term[e] .. first_term[e + 1] - 1
+    int32_t off[kListTerms][kListSlots];
+};
+
 struct ForwardPlan {
     int32_t n_f, n_sum;
     int32_t f_shape[kMaxExt];

@@ -20,12 +20,13 @@ def _to_dev(x):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-def run_gpu(w, generic_only=False, wanted=None, keep_program=True):
+def run_gpu(w, generic_only=False, wanted=None, keep_program=True, term_lists=True):
     """keep_program: a body given as programs stays on the interpreter kernels even where it spells out a built-in
-    body (most tests here give built-in bodies as programs precisely to exercise those kernels)."""
+    body (most tests here give built-in bodies as programs precisely to exercise those kernels).
+    term_lists=False: a small expression is not expanded into term lists at plan time; the device walks its ranges."""
     import torch
     from paper_1711_01348_amd import binding as B
-    plan = B.Plan(w.expr, generic_only=generic_only, keep_program=keep_program)
+    plan = B.Plan(w.expr, generic_only=generic_only, keep_program=keep_program, term_lists=term_lists)
     args = [_to_dev(a) for a in w.arg_list()]
     f = plan.forward(args)
     grads = plan.backward(args, f, _to_dev(w.df), wanted=wanted)
@@ -73,6 +74,10 @@ def test_configs_small(w, generic_only):
     f_ref, g_ref = oracle_all(w)
     plan, f, grads = run_gpu(w, generic_only)
     assert_parity(w, f, grads, f_ref, g_ref, "generic" if generic_only else "selected")
+    if plan.query(0)["listed"]:   # small enough for term lists: also with the ranges walked on the device
+        plan, f, grads = run_gpu(w, generic_only, term_lists=False)
+        assert not plan.query(0)["listed"]
+        assert_parity(w, f, grads, f_ref, g_ref, "ranges walked on the device")
 
 
 EXPECTED_FAMILY = {"cfg1": "generic", "cfg2_1": "row_reduce", "cfg2_2": "diagonal", "cfg2_3": "antidiagonal",
@@ -92,12 +97,15 @@ def test_selected_kernel_family(w):
     assert B.Plan(w.expr, generic_only=True).forward_family == "generic"
 
 
-def test_config1_fp64_tight():
+@pytest.mark.parametrize("term_lists", [True, False], ids=["terms listed", "ranges walked"])
+def test_config1_fp64_tight(term_lists):
     w = wl.config1()
     f_ref, g_ref = oracle_all(w, 1)
-    _, f, grads = run_gpu(w)
+    plan, f, grads = run_gpu(w, term_lists=term_lists)
+    assert [plan.query(p)["listed"] for p in range(4)] == [term_lists] * 4
     for got, ref in [(f, f_ref)] + list(zip(grads, g_ref)):
-        assert check.errors(got, ref)["floored"] <= 1e-12
+        e = check.errors(got, ref)
+        assert e["floored"] <= 1e-12 and e["raw"] <= 1e-12, e   # the plain element-wise relative error holds here too
     dc = grads[2]
     assert np.count_nonzero(dc - np.diag(np.diag(dc))) == 0
 
@@ -169,8 +177,11 @@ def test_assorted_index_maps_fp64(make):
     e = make()
     w = wl.random_inputs(e, 11, -0.9, 0.9)
     f_ref, g_ref = oracle_all(w, 1)
-    _, f, grads = run_gpu(w)
+    plan, f, grads = run_gpu(w)
     assert_parity(w, f, grads, f_ref, g_ref)
+    if plan.query(0)["listed"]:
+        _, f, grads = run_gpu(w, term_lists=False)
+        assert_parity(w, f, grads, f_ref, g_ref, "ranges walked on the device")
 
 
 @pytest.mark.parametrize("seed", range(40))
@@ -180,8 +191,11 @@ def test_random_expressions(seed):
     e = wl.random_expr(seed, "f64" if seed % 2 else "f32")
     w = wl.random_inputs(e, 100 + seed, -0.6, 0.6)
     f_ref, g_ref = oracle_all(w, 2)
-    _, f, grads = run_gpu(w)
+    plan, f, grads = run_gpu(w)
     assert_parity(w, f, grads, f_ref, g_ref, "random %d" % seed)
+    if plan.query(0)["listed"]:
+        _, f, grads = run_gpu(w, term_lists=False)
+        assert_parity(w, f, grads, f_ref, g_ref, "random %d, ranges walked on the device" % seed)
     wp = wl.Workload(w.name, wl.as_program(e), w.inputs, w.df)
     plan, f, grads = run_gpu(wp)
     assert plan.forward_family in ("program", "contraction")

@@ -659,3 +659,17 @@ def test_condition_rules():
     e = wl.matmul_expr(8, 8, 8, "f32")
     e.constraints = [([0, 1, -1], 0)]
     assert B.Plan(e).forward_family == "generic"
+
+
+def test_small_expressions_get_term_lists():
+    """Sec. 5.1: a small expression on the plan-driven kernels has its sets Gamma-hat(beta) written out at plan time
+    (tad_plan_query reports it); larger ones, program bodies and expressions with aliases keep the ranges."""
+    from paper_1711_01348_amd import binding as B
+    w = wl.config1()
+    assert all(B.Plan(w.expr).query(p)["listed"] for p in range(4))
+    assert not any(B.Plan(w.expr, term_lists=False).query(p)["listed"] for p in range(4))
+    assert not B.Plan(wl.config3("small").expr, generic_only=True).query(0)["listed"]      # too many terms
+    assert not B.Plan(wl.as_program(w.expr), keep_program=True).query(0)["listed"]          # program body
+    assert not B.Plan(wl.matrix_square_expr(5, "f64")).query(0)["listed"]                   # alias operand
+    small = B.Plan(wl.config3("small").expr)                                                # specialised family: no list
+    assert small.query(0)["family"] == "worked" and not small.query(0)["listed"]
