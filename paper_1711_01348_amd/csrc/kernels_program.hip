@@ -236,16 +236,31 @@ __device__ __forceinline__ double prog_run(const DevProg &P, const T *const (&pt
 template <typename T, int FORM>
 __device__ double inner_sum(const ForwardPlan &P, const DevProg &inner, int n_ops, const ArgPtrs &A, int lin,
                             int64_t *base, int part = 0, int parts = 1) {
+    // unrolled to the largest rank and cut short by tests of the uniform rank: every field of the plan comes from a
+    // fixed place in the kernel arguments (see forward_sum of the built-in bodies)
     int32_t ext[kMaxExt];
     {
         int t = lin;
-        for (int d = P.n_f - 1; d >= 0; --d) { ext[d] = t % P.f_shape[d]; t /= P.f_shape[d]; }
+#pragma unroll
+        for (int d = kMaxExt - 1; d >= 1; --d) {
+            ext[d] = 0;
+            if (d < P.n_f) {
+                const int s = P.f_shape[d], q = t / s;
+                ext[d] = t - q * s;
+                t = q;
+            }
+        }
+        ext[0] = t;   // lin is below the number of function elements: no division for the first index
     }
-    for (int p = 0; p < n_ops; ++p) {
-        int64_t o = 0;
-        for (int d = 0; d < P.n_f; ++d) o += P.off[p][d] * (int64_t)ext[d];
-        for (int s = 0; s < P.n_sum; ++s) o += P.off[p][P.n_f + s] * (int64_t)P.sum_lo[s];
-        base[p] = o;
+#pragma unroll
+    for (int p = 0; p < kMaxArgs; ++p) {
+        if (p < n_ops) {
+            int64_t o = P.base0[p];
+#pragma unroll
+            for (int d = 0; d < kMaxExt; ++d)
+                if (d < P.n_f) o += P.off[p][d] * (int64_t)ext[d];
+            base[p] = o;
+        }
     }
     int32_t k[kMaxExt] = {0};
     double acc = 0.0;

@@ -492,6 +492,12 @@ int derive_plan(const tad_expr *expr, const tad_arg *args, int n_args, tad_dtype
         }
     }
 
+    for (int p = 0; p < n_args; ++p) {
+        for (int s = 0; s < expr->n_sum; ++s)
+            fw.base0[p] = cadd(fw.base0[p], cmul(fw.off[p][expr->n_f + s], expr->sum_lo[s]));
+        fw.last_stride[p] = expr->n_sum > 0 ? fw.off[p][expr->n_f + expr->n_sum - 1] : 0;
+    }
+
     fw.n_cons = expr->n_constraints;
     for (int e = 0; e < expr->n_constraints; ++e) {
         int64_t mag = cabs(expr->constraint[e][D]);

@@ -126,6 +126,8 @@ struct ForwardPlan {
     int32_t sum_lo[kMaxExt];
     int32_t sum_n[kMaxExt];            // number of values of each summation index
     int64_t off[kMaxArgs][kMaxExt];    // element offset of argument p = off[p] . [alpha k]
+    int64_t base0[kMaxArgs];           // its part from the lower summation limits: sum_s off[p][n_f + s] * sum_lo[s]
+    int64_t last_stride[kMaxArgs];     // off[p][n_f + n_sum - 1]: advance along the last summation index (0 without sums)
     int32_t n_cons;                    // extra conditions: cons[j] . [alpha k] + cons[j][n_f + n_sum] >= 0
     int32_t cons[kMaxCons][kMaxExt + 1];
 };
