@@ -225,7 +225,8 @@ TAD_HD bool gather_element_index(const GatherPlan &P, int idx, int *lin, int32_t
     if (!P.live) {
         *lin = idx;
         int t = idx;
-        for (int r = P.rank - 1; r >= 0; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+        for (int r = P.rank - 1; r >= 1; --r) { beta[r] = t % P.shape[r]; t /= P.shape[r]; }
+        beta[0] = t;   // idx is below the number of elements: no division for the first index
         return gather_prepare(P, beta, y);
     }
     *lin = -1;
