@@ -310,6 +310,27 @@ __global__ __launch_bounds__(256) void k_generic_gather_coop(const GatherPlan P,
     else store_element(dx, lin, live, total, accumulate);
 }
 
+// One wavefront per gradient element, four elements per workgroup: the form of the cooperative layout for gradients
+// with many elements (thousands of long sums, e.g. da_ik, i < 8192: 8192 terms each).  With a whole workgroup per
+// element a thread has only a few dozen terms, and walking the plan and adding up the workgroup cost as much as
+// the terms; a wavefront has four times as many terms per lane and adds up with lane exchanges alone.
+template <int BODY, typename T>
+__global__ __launch_bounds__(256) void k_generic_gather_wave(const GatherPlan P, int p, const ArgPtrs A,
+                                                             const T *__restrict__ f, const T *__restrict__ df,
+                                                             T *__restrict__ dx, int n, int accumulate) {
+    // every die a contiguous range of workgroups (see k_generic_gather_coop)
+    int blk = blockIdx.x;
+    const int per_die = gridDim.x >> 3;
+    if (blk < (per_die << 3)) blk = (blk & 7) * per_die + (blk >> 3);
+    const int idx = blk * 4 + (int)(threadIdx.x >> 6);
+    if (idx >= n) return;   // the whole wavefront leaves together
+    double acc;
+    int lin;
+    const bool live = gather_element<BODY, T, 8>(P, p, A, f, df, idx, &lin, (int)(threadIdx.x & 63), 64, &acc);
+    const double total = wave_sum_all(acc);
+    if ((threadIdx.x & 63) == 0) store_element(dx, lin, live, total, accumulate);
+}
+
 // one thread per gradient element, the terms of every element shared by gridDim.y blocks (long sums read across
 // the contiguous direction of f: neighbouring threads read neighbouring f)
 template <int BODY, typename T>
@@ -330,6 +351,7 @@ __global__ __launch_bounds__(256) void k_generic_gather_lanes(const GatherPlan P
 // and a wavefront that walks this code once spends most of its time fetching it (8 to 25 us per launch for a few
 // dozen terms); in one launch the gradients pay that together instead of one after the other.  Workgroups of one
 // wavefront; workgroup b works on gradient g with first[g] <= b < first[g + 1].
+constexpr int kWaveElements = 4096;           // cooperative layout with at least this many elements: a wavefront each
 constexpr long long kSpreadElements = 1024;   // up to this many gradient elements in all: a wavefront each
 struct MultiGather {
     int32_t count;
@@ -520,6 +542,10 @@ static int launch_body(const tad_plan &pl, const void *const *args, const void *
                 TAD_LAUNCH("k_generic_gather_lanes", (k_generic_gather_lanes<BODY, T>), dim3((n + 255) / 256, splits),
                            dim3(256), 0, s, pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
                            static_cast<T *>(dx[p]), n, accumulate, partial, live);
+            else if (splits == 1 && n >= kWaveElements)
+                TAD_LAUNCH("k_generic_gather_wave", (k_generic_gather_wave<BODY, T>), dim3((n + 3) / 4), dim3(256), 0, s,
+                           pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
+                           static_cast<T *>(dx[p]), n, accumulate);
             else
                 TAD_LAUNCH("k_generic_gather_coop", (k_generic_gather_coop<BODY, T>), dim3(n, splits), dim3(256), 0, s,
                            pl.ap[q].dev, (int)q, A, static_cast<const T *>(f), static_cast<const T *>(df),
