@@ -86,7 +86,7 @@ def accounting(name, w):
         elif name == "cfg3":
             dom = dict(kernel="k_worked_backward", bound="hbm", per_launch=2 * nf * es, launches=1)
         else:
-            dom = dict(kernel="k_generic_gather_multi", bound="hbm", per_launch=0, launches=1)   # four gradients, one launch
+            dom = dict(kernel="k_generic_gather_listed", bound="hbm", per_launch=0, launches=1)   # four gradients, one launch
     elif name == "cfg2_1":
         elems = nf + nf + 2 * small                   # write f; read df; x read, dx written
         dom = dict(kernel="k_rowreduce_backward", bound="hbm", per_launch=nf * es, launches=1)
