@@ -320,6 +320,24 @@ def test_few_elements_with_long_sums(name, make, generic_only, span):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("rows,dtype", [(4097, "f32"), (4095, "f32"), (4400, "f64")])
+def test_many_elements_with_long_sums(rows, dtype):
+    """A gradient with thousands of elements that each sum more than a thousand terms (dx_ik = sum_j df_ij y_kj with
+    one k): from 4096 elements on the cooperative layout gives every element a wavefront (four to a workgroup, the
+    last workgroup not full), below that a workgroup; against the oracle, twice with identical bits."""
+    from paper_1711_01348_amd import binding as B
+    e = wl.matmul_expr(rows, 1500, 1, dtype)
+    w = wl.random_inputs(e, 83, -0.9, 0.9)
+    plan, f, grads = run_gpu(w, generic_only=True)
+    q = plan.query(0)
+    assert q["family"] == "generic" and q["gather_layout"] == "blocks" and q["gather_elements"] == rows
+    f_ref, g_ref = oracle_all(w, 8)
+    assert_parity(w, f, grads, f_ref, g_ref, "rows %d" % rows)
+    _, _, again = run_gpu(w, generic_only=True)
+    for x, y in zip(grads, again):
+        assert np.array_equal(x, y)
+
+
 def test_backward_is_deterministic_and_skips_unwanted():
     import torch
     w = wl.config3("small")
